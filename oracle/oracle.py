@@ -1,0 +1,202 @@
+"""ctypes loader and numpy marshalling for the C oracle (``qnn_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
+cpu_baseline leg may import this module; the product path must not.
+
+Every function here only converts arrays and calls the C routine of the same
+name; the arithmetic, with its citations of the paper, is in the C file.
+"""
+import ctypes
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qnn_oracle.c")
+_LIB = os.path.join(_HERE, "libqnn_oracle.so")
+
+__all__ = [
+    "build", "threads", "encode", "decode", "pack_planes", "gemm", "gemm_wt", "conv3x3",
+    "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
+]
+
+
+def build(force=True):
+    """Compile the oracle with gcc (-O2, no fast-math, no FMA contraction)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    tmp = _LIB + ".tmp%d" % os.getpid()
+    cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+           "-shared", "-fPIC", "-Wall", "-o", tmp, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        lib = ctypes.CDLL(_LIB)
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.qnn_oracle_encode.argtypes = [i64, i32, vp]
+        lib.qnn_oracle_encode.restype = i32
+        lib.qnn_oracle_decode.argtypes = [vp, i32]
+        lib.qnn_oracle_decode.restype = i64
+        lib.qnn_oracle_pack_planes.argtypes = [vp, i64, i64, i32, vp]
+        lib.qnn_oracle_pack_planes.restype = i64
+        lib.qnn_oracle_gemm.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.qnn_oracle_gemm.restype = None
+        lib.qnn_oracle_gemm_wt.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.qnn_oracle_gemm_wt.restype = None
+        lib.qnn_oracle_conv3x3.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp]
+        lib.qnn_oracle_conv3x3.restype = None
+        lib.qnn_oracle_branch_dot.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+        lib.qnn_oracle_branch_dot.restype = i64
+        lib.qnn_oracle_scale_f64.argtypes = [vp, i64, i64, vp, vp]
+        lib.qnn_oracle_scale_f64.restype = None
+        lib.qnn_oracle_scale_f32.argtypes = [vp, i64, i64, vp, vp]
+        lib.qnn_oracle_scale_f32.restype = None
+        lib.qnn_oracle_maxpool2x2.argtypes = [vp, i64, i64, i64, i64, vp]
+        lib.qnn_oracle_maxpool2x2.restype = None
+        lib.qnn_oracle_round_odd.argtypes = [ctypes.c_float, i32]
+        lib.qnn_oracle_round_odd.restype = ctypes.c_int16
+        lib.qnn_oracle_requant.argtypes = [vp, i64, i32, vp]
+        lib.qnn_oracle_requant.restype = None
+        _lib = lib
+    return _lib
+
+
+def threads():
+    """Number of OpenMP threads the oracle's parallel loops use."""
+    n = os.environ.get("OMP_NUM_THREADS")
+    if n:
+        return int(n.split(",")[0])
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _codes(a):
+    return np.ascontiguousarray(a, dtype=np.int16)
+
+
+def encode(v, bits):
+    """Elements [c_1..c_bits] in {-1,+1} of one odd code; ValueError if not a code."""
+    c = np.zeros(8, dtype=np.int8)
+    if _L().qnn_oracle_encode(int(v), int(bits), _p(c)) != 0:
+        raise ValueError("%r is not a %d-bit {-1,+1} code" % (v, bits))
+    return c[:bits].copy()
+
+
+def decode(c):
+    c = np.ascontiguousarray(c, dtype=np.int8)
+    return int(_L().qnn_oracle_decode(_p(c), int(c.size)))
+
+
+def pack_planes(codes, bits):
+    """codes[rows][K] -> (planes uint32 [rows][bits][ceil(K/32)], bad_count)."""
+    a = _codes(codes)
+    rows, K = a.shape
+    out = np.zeros((rows, bits, (K + 31) // 32), dtype=np.uint32)
+    bad = _L().qnn_oracle_pack_planes(_p(a), rows, K, int(bits), _p(out))
+    return out, int(bad)
+
+
+def gemm(A, W):
+    """A[M][K] . W[K][N] -> int64 [M][N]."""
+    A, W = _codes(A), _codes(W)
+    M, K = A.shape
+    K2, N = W.shape
+    assert K == K2
+    C = np.zeros((M, N), dtype=np.int64)
+    _L().qnn_oracle_gemm(_p(A), _p(W), M, N, K, _p(C))
+    return C
+
+
+def gemm_wt(A, Wt):
+    """A[M][K] . Wt[N][K]^T -> int64 [M][N]."""
+    A, Wt = _codes(A), _codes(Wt)
+    M, K = A.shape
+    N, K2 = Wt.shape
+    assert K == K2
+    C = np.zeros((M, N), dtype=np.int64)
+    _L().qnn_oracle_gemm_wt(_p(A), _p(Wt), M, N, K, _p(C))
+    return C
+
+
+def conv3x3(X, Wt):
+    """X NHWC [Nb][H][W][C], Wt [Cout][3][3][C] -> int64 NHWC [Nb][H][W][Cout]."""
+    X, Wt = _codes(X), _codes(Wt)
+    Nb, H, W, C = X.shape
+    Cout, kh, kw, C2 = Wt.shape
+    assert (kh, kw, C2) == (3, 3, C)
+    O = np.zeros((Nb, H, W, Cout), dtype=np.int64)
+    _L().qnn_oracle_conv3x3(_p(X), _p(Wt), Nb, H, W, C, Cout, _p(O))
+    return O
+
+
+def branch_dot(x, w, xb, wb):
+    """x.w through the literal multi-branch sum of +-1 vectors."""
+    x, w = _codes(x).ravel(), _codes(w).ravel()
+    assert x.size == w.size
+    n = x.size
+    cm = np.zeros(max(n, 1), dtype=np.int8)
+    dk = np.zeros(max(n, 1), dtype=np.int8)
+    r = _L().qnn_oracle_branch_dot(_p(x), _p(w), n, int(xb), int(wb), _p(cm), _p(dk))
+    if r == -(1 << 63):
+        raise ValueError("input holds a value that is not a code")
+    return int(r)
+
+
+def _acc2d(acc):
+    acc = np.ascontiguousarray(acc, dtype=np.int64)
+    cols = acc.shape[-1]
+    return acc, acc.size // cols if cols else 0, cols
+
+
+def scale_f64(acc, s):
+    acc, rows, cols = _acc2d(acc)
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert s.size == cols
+    y = np.zeros(acc.shape, dtype=np.float64)
+    _L().qnn_oracle_scale_f64(_p(acc), rows, cols, _p(s), _p(y))
+    return y
+
+
+def scale_f32(acc, s):
+    acc, rows, cols = _acc2d(acc)
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert s.size == cols
+    y = np.zeros(acc.shape, dtype=np.float32)
+    _L().qnn_oracle_scale_f32(_p(acc), rows, cols, _p(s), _p(y))
+    return y
+
+
+def maxpool2x2(y):
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    Nb, H, W, C = y.shape
+    assert H % 2 == 0 and W % 2 == 0
+    o = np.zeros((Nb, H // 2, W // 2, C), dtype=np.float32)
+    _L().qnn_oracle_maxpool2x2(_p(y), Nb, H, W, C, _p(o))
+    return o
+
+
+def round_odd(y, bits):
+    return int(_L().qnn_oracle_round_odd(float(np.float32(y)), int(bits)))
+
+
+def requant(y, bits):
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    codes = np.zeros(y.shape, dtype=np.int16)
+    _L().qnn_oracle_requant(_p(y), y.size, int(bits), _p(codes))
+    return codes

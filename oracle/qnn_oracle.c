@@ -1,0 +1,230 @@
+/*
+ * CPU oracle for the {-1,+1} encoding decomposition of quantized layers.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It is never part of the product path: only
+ * the tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code, header, table or helper with the HIP sources.
+ *
+ * The decomposition is an exact identity on odd-integer codes (Sec. 3.1,
+ * Eq. (8) equals Eq. (1)), so the reference result of a layer is the ordinary
+ * integer product of the decoded codes, accumulated in int64.  The encoding
+ * itself (Eq. (7)), the literal multi-branch sum (Eq. (8)) and the bit-plane
+ * store are written out as well, so that each can be pinned against the values
+ * and identities the paper fixes.
+ *
+ * Conventions (readings of the paper where it is silent are listed in the
+ * design notes of the repository):
+ *   - codes are odd integers v with |v| <= 2^bits - 1, held as int16;
+ *   - element c_m (m = 1..bits) has weight 2^(m-1); c_1 is the low element
+ *     (Sec. 3.2: x = x_1 + 2 x_2 with x_2 the high bit);
+ *   - in a stored bit-plane a set bit means +1, a clear bit means -1.
+ *
+ * Parallelism: an OpenMP "parallel for" over the outermost loop only.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <math.h>
+
+/* ---- Eq. (7): x = sum_{m=1..M} 2^(m-1) c_m, c_m in {-1,+1} ------------- */
+
+/* Writes c[0..bits-1] = c_1..c_M.  Returns 0, or -1 if v is not a code.
+ * Greedy from the high element down: the remaining elements can represent
+ * magnitudes up to 2^(m-1)-1 only, so the sign of the residual fixes c_m. */
+int qnn_oracle_encode(int64_t v, int bits, int8_t *c)
+{
+    if (bits < 1 || bits > 8) return -1;
+    int64_t vmax = ((int64_t)1 << bits) - 1;
+    if (v < -vmax || v > vmax || ((v & 1) == 0)) return -1;
+    int64_t r = v;
+    for (int m = bits; m >= 1; --m) {
+        int8_t s = (r > 0) ? 1 : -1;
+        c[m - 1] = s;
+        r -= (int64_t)s * ((int64_t)1 << (m - 1));
+    }
+    return (r == 0) ? 0 : -1;
+}
+
+int64_t qnn_oracle_decode(const int8_t *c, int bits)
+{
+    int64_t v = 0;
+    for (int m = 1; m <= bits; ++m) v += ((int64_t)1 << (m - 1)) * (int64_t)c[m - 1];
+    return v;
+}
+
+/* ---- bit-plane store (Sec. 3.1 bit-plane rows; Sec. 5.4 "store by bits") - */
+
+/* codes[rows][K] -> planes[rows][bits][Kw], Kw = ceil(K/32).
+ * Plane p (0-based) holds element c_{p+1}; element k of a row is bit (k mod 32)
+ * of word k/32; bit set <=> +1.  Bits past K are zero.
+ * Returns the number of entries that are not valid codes (they pack as zeros). */
+int64_t qnn_oracle_pack_planes(const int16_t *codes, int64_t rows, int64_t K, int bits,
+                               uint32_t *planes)
+{
+    int64_t Kw = (K + 31) / 32;
+    int64_t bad = 0;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int p = 0; p < bits; ++p)
+            for (int64_t w = 0; w < Kw; ++w) planes[(r * bits + p) * Kw + w] = 0u;
+        for (int64_t k = 0; k < K; ++k) {
+            int8_t c[8];
+            if (qnn_oracle_encode(codes[r * K + k], bits, c) != 0) { ++bad; continue; }
+            for (int p = 0; p < bits; ++p)
+                if (c[p] == 1) planes[(r * bits + p) * Kw + k / 32] |= (uint32_t)1 << (k % 32);
+        }
+    }
+    return bad;
+}
+
+/* ---- Eq. (1): plain integer product ------------------------------------ */
+
+/* C[M][N] = A[M][K] * W[K][N], int64 accumulate. */
+void qnn_oracle_gemm(const int16_t *A, const int16_t *W, int64_t M, int64_t N, int64_t K,
+                     int64_t *C)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k) s += (int64_t)A[i * K + k] * (int64_t)W[k * N + j];
+            C[i * N + j] = s;
+        }
+}
+
+/* Same product with the second operand given transposed: Wt[N][K]. */
+void qnn_oracle_gemm_wt(const int16_t *A, const int16_t *Wt, int64_t M, int64_t N, int64_t K,
+                        int64_t *C)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k) s += (int64_t)A[i * K + k] * (int64_t)Wt[j * K + k];
+            C[i * N + j] = s;
+        }
+}
+
+/* ---- direct 3x3 convolution (Sec. 3.2: Op may be a convolution) --------- */
+
+/* O[n][oh][ow][f] = sum_{kh,kw,c} X[n][oh+kh-1][ow+kw-1][c] * Wt[f][kh][kw][c]
+ * NHWC, stride 1, pad 1, cross-correlation, X taken as 0 outside the image. */
+void qnn_oracle_conv3x3(const int16_t *X, const int16_t *Wt, int64_t Nb, int64_t H, int64_t W,
+                        int64_t C, int64_t Cout, int64_t *O)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t nh = 0; nh < Nb * H; ++nh) {
+        int64_t n = nh / H, oh = nh % H;
+        for (int64_t ow = 0; ow < W; ++ow)
+            for (int64_t f = 0; f < Cout; ++f) {
+                int64_t s = 0;
+                for (int kh = 0; kh < 3; ++kh) {
+                    int64_t ih = oh + kh - 1;
+                    if (ih < 0 || ih >= H) continue;
+                    for (int kw = 0; kw < 3; ++kw) {
+                        int64_t iw = ow + kw - 1;
+                        if (iw < 0 || iw >= W) continue;
+                        const int16_t *x = X + ((n * H + ih) * W + iw) * C;
+                        const int16_t *w = Wt + ((f * 3 + kh) * 3 + kw) * C;
+                        for (int64_t c = 0; c < C; ++c) s += (int64_t)x[c] * (int64_t)w[c];
+                    }
+                }
+                O[((n * H + oh) * W + ow) * Cout + f] = s;
+            }
+    }
+}
+
+/* ---- Eq. (8): the multi-branch sum, written out literally --------------- */
+
+/* XnorPopcount of two {-1,+1} vectors: the number of positions where they
+ * agree minus the number where they differ (= their dot product). */
+static int64_t xnor_popcount_pm1(const int8_t *c, const int8_t *d, int64_t n)
+{
+    int64_t agree = 0;
+    for (int64_t i = 0; i < n; ++i) agree += (c[i] == d[i]) ? 1 : 0;
+    return 2 * agree - n;
+}
+
+/* x^T w via Eq. (8): encode both vectors element by element with Eq. (7),
+ * form the xb*wb branch results and add them with weights 2^(m-1) 2^(k-1).
+ * cm / dk are caller scratch of n int8 each.  Returns INT64_MIN on a bad code. */
+int64_t qnn_oracle_branch_dot(const int16_t *x, const int16_t *w, int64_t n, int xb, int wb,
+                              int8_t *cm, int8_t *dk)
+{
+    int64_t total = 0;
+    int8_t e[8];
+    for (int m = 1; m <= xb; ++m)
+        for (int k = 1; k <= wb; ++k) {
+            for (int64_t i = 0; i < n; ++i) {
+                if (qnn_oracle_encode(x[i], xb, e) != 0) return INT64_MIN;
+                cm[i] = e[m - 1];
+                if (qnn_oracle_encode(w[i], wb, e) != 0) return INT64_MIN;
+                dk[i] = e[k - 1];
+            }
+            total += ((int64_t)1 << (m - 1)) * ((int64_t)1 << (k - 1)) * xnor_popcount_pm1(cm, dk, n);
+        }
+    return total;
+}
+
+/* ---- Eq. (9): scale --------------------------------------------------- */
+
+/* y[i][j] = acc[i][j] * s[j] in double precision (the reference value). */
+void qnn_oracle_scale_f64(const int64_t *acc, int64_t rows, int64_t cols, const float *s, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) y[i * cols + j] = (double)acc[i * cols + j] * (double)s[j];
+}
+
+/* The same scale as one IEEE binary32 multiply of (float)acc by s[j].  Used
+ * where a later integer decision (requantisation) depends on the rounded
+ * value, so that both sides decide in binary32.  Build with -ffp-contract=off. */
+void qnn_oracle_scale_f32(const int64_t *acc, int64_t rows, int64_t cols, const float *s, float *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            volatile float a = (float)acc[i * cols + j];
+            y[i * cols + j] = a * s[j];
+        }
+}
+
+/* ---- layer chain: pooling and re-encoding (Alg. 1 forward, Table 2) ------ */
+
+/* 2x2 max pool, stride 2, NHWC float; H and W even. */
+void qnn_oracle_maxpool2x2(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, float *o)
+{
+    int64_t Ho = H / 2, Wo = W / 2;
+#pragma omp parallel for schedule(static)
+    for (int64_t nh = 0; nh < Nb * Ho; ++nh) {
+        int64_t n = nh / Ho, oh = nh % Ho;
+        for (int64_t ow = 0; ow < Wo; ++ow)
+            for (int64_t c = 0; c < C; ++c) {
+                float m = y[((n * H + 2 * oh) * W + 2 * ow) * C + c];
+                for (int dh = 0; dh < 2; ++dh)
+                    for (int dw = 0; dw < 2; ++dw) {
+                        float v = y[((n * H + 2 * oh + dh) * W + 2 * ow + dw) * C + c];
+                        if (v > m) m = v;
+                    }
+                o[((n * Ho + oh) * Wo + ow) * C + c] = m;
+            }
+    }
+}
+
+/* Real value (in code units) -> nearest-below-in-magnitude odd code, following
+ * the interval closures of Table 2 scaled by 2^bits-1:
+ *   magnitude a = |y| falls in [2j, 2j+2) -> 2j+1, clamped to 2^bits-1;
+ *   y > 0 -> +, otherwise (including 0) -> -.                                  */
+int16_t qnn_oracle_round_odd(float y, int bits)
+{
+    double a = fabs((double)y);
+    double cmax = (double)(((int64_t)1 << bits) - 1);
+    double c = 2.0 * floor(a / 2.0) + 1.0;
+    if (!(c <= cmax)) c = cmax;            /* also catches inf/nan -> clamp */
+    return (int16_t)((y > 0.0f) ? c : -c);
+}
+
+void qnn_oracle_requant(const float *y, int64_t n, int bits, int16_t *codes)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) codes[i] = qnn_oracle_round_odd(y[i], bits);
+}

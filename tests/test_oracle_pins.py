@@ -1,0 +1,382 @@
+"""Pins of the CPU oracle against what the paper and plain mathematics fix.
+
+None of these tests touches the GPU library.  Each names the passage it checks.
+Python integers / Fractions, numpy float64 matmul and torch's CPU conv2d are
+the independent references; no expected value comes from the HIP path.
+"""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def all_codes(bits):
+    m = (1 << bits) - 1
+    return list(range(-m, m + 1, 2))
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def rand_codes(r, shape, bits):
+    m = (1 << bits) - 1
+    return (2 * r.integers(0, 1 << bits, size=shape) - m).astype(np.int16)
+
+
+# ------------------------------------------------------------------ Eq. (7)
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_encoding_round_trip_and_state_count(oracle, bits):
+    """Eq. (7): every odd code in [-(2^M-1), 2^M-1] has exactly one +-1 expansion."""
+    seen = set()
+    for v in all_codes(bits):
+        c = oracle.encode(v, bits)
+        assert set(np.unique(c)).issubset({-1, 1})
+        assert sum((1 << m) * int(c[m]) for m in range(bits)) == v   # Eq. (7) in Python ints
+        assert oracle.decode(c) == v
+        seen.add(tuple(c))
+    assert len(seen) == 1 << bits                                    # 2^M states
+    # every +-1 vector decodes to a code of the space (bijection)
+    for c in itertools.product((-1, 1), repeat=bits):
+        assert oracle.decode(c) in all_codes(bits)
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_non_codes_are_rejected(oracle, bits):
+    m = (1 << bits) - 1
+    for v in (0, 2, -2, m + 1, m + 2, -m - 2):
+        with pytest.raises(ValueError):
+            oracle.encode(v, bits)
+
+
+def _table2():
+    rows = []
+    with open(os.path.join(GOLDEN, "table2_states.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            lo, loc, hi, hic, q, a, b = line.split()
+            rows.append((Fraction(lo), int(loc), Fraction(hi), int(hic), Fraction(q), int(a), int(b)))
+    return rows
+
+
+def test_table2_states(oracle):
+    """Table 2: the four printed 2-bit states, printed as {high, low}; alpha = 3."""
+    rows = _table2()
+    assert len(rows) == 4
+    for _, _, _, _, q, high, low in rows:
+        v = q * 3
+        assert v.denominator == 1
+        c = oracle.encode(int(v), 2)
+        assert (int(c[1]), int(c[0])) == (high, low)
+        assert low + 2 * high == int(v)            # Sec. 3.2: x = x_1 + 2 x_2
+
+
+@pytest.mark.parametrize("bits", range(1, 7))
+def test_trigonometric_encoder_agrees(oracle, bits):
+    """Eq. (10)/(11): sign(+-sin((2^M-1)/2^m pi x)) at the quantized points x = v/(2^M-1)."""
+    M = bits
+    for v in all_codes(M):
+        x = v / ((1 << M) - 1)
+        c = oracle.encode(v, M)
+        for m in range(1, M + 1):
+            s = math.sin(((1 << M) - 1) / (1 << m) * math.pi * x)
+            if m != M:
+                s = -s
+            assert abs(s) > 1e-9
+            assert (1 if s > 0 else -1) == int(c[m - 1]), (M, m, v)
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_zero_one_index_identity_and_bit_convention(oracle, bits):
+    """Eq. (17): x^q = 2u/(2^M-1) - 1 with u the {0,1} fixed-point integer, so the
+    code is v = 2u-(2^M-1) and stored plane p must be binary digit p of u."""
+    codes = np.array([all_codes(bits)], dtype=np.int16)       # one row, K = 2^bits
+    planes, bad = oracle.pack_planes(codes, bits)
+    assert bad == 0
+    K = codes.shape[1]
+    for k in range(K):
+        v = int(codes[0, k])
+        u = (v + (1 << bits) - 1) // 2
+        assert Fraction(2 * u, (1 << bits) - 1) - 1 == Fraction(v, (1 << bits) - 1)
+        for p in range(bits):
+            bit = (int(planes[0, p, k // 32]) >> (k % 32)) & 1
+            assert bit == (u >> p) & 1
+
+
+# ---------------------------------------------------------- bit-plane store
+def test_pack_layout_tail_and_position(oracle):
+    """Element k lands in bit k%32 of word k//32 of every plane; tail bits are zero."""
+    for bits in (1, 2, 3, 8):
+        m = (1 << bits) - 1
+        for K in (1, 27, 31, 32, 33, 64, 65, 100):
+            for k in (0, K // 2, K - 1):
+                codes = np.full((3, K), -m, dtype=np.int16)
+                codes[1, k] = m
+                planes, bad = oracle.pack_planes(codes, bits)
+                assert bad == 0 and planes.shape == (3, bits, (K + 31) // 32)
+                assert not planes[0].any() and not planes[2].any()
+                want = np.zeros((bits, (K + 31) // 32), dtype=np.uint32)
+                want[:, k // 32] = np.uint32(1) << np.uint32(k % 32)
+                assert (planes[1] == want).all()
+            allp = np.full((1, K), m, dtype=np.int16)
+            planes, _ = oracle.pack_planes(allp, bits)
+            total = sum(bin(int(x)).count("1") for x in planes.ravel())
+            assert total == bits * K                           # nothing set past K
+
+
+def test_pack_counts_invalid_codes(oracle):
+    codes = np.array([[1, 0, 3, 5, -3, 2]], dtype=np.int16)
+    planes, bad = oracle.pack_planes(codes, 2)
+    assert bad == 3                                            # 0, 5, 2
+    good, _ = oracle.pack_planes(np.array([[1, -3, 3, -3, -3, -3]], dtype=np.int16), 2)
+    assert (planes == good).all()                              # invalid entries pack as zeros
+
+
+# ----------------------------------------------------- XnorPopcount, Eq. (8)
+def test_xnor_popcount_identity_brute_force(oracle):
+    """1-bit x 1-bit: c.d = 2*popcount(xnor) - L = L - 2*popcount(xor), all vectors L<=6."""
+    for L in range(1, 7):
+        vecs = list(itertools.product((-1, 1), repeat=L))
+        for c in vecs:
+            pc = sum(1 << i for i in range(L) if c[i] == 1)
+            for d in vecs:
+                pd = sum(1 << i for i in range(L) if d[i] == 1)
+                dot = sum(a * b for a, b in zip(c, d))
+                assert oracle.branch_dot(c, d, 1, 1) == dot
+                xnor = ~(pc ^ pd) & ((1 << L) - 1)
+                assert 2 * bin(xnor).count("1") - L == dot
+                assert L - 2 * bin(pc ^ pd).count("1") == dot
+
+
+@pytest.mark.parametrize("L", [1, 27, 31, 32, 33, 63, 64, 65, 576])
+def test_xor_popcount_on_packed_planes(oracle, L):
+    """The stored planes reproduce every branch dot product as L - 2 popcount(xor),
+    with the zero tail bits contributing nothing."""
+    r = rng(100 + L)
+    for xb, wb in ((1, 1), (2, 2), (4, 3), (8, 2)):
+        x = rand_codes(r, (1, L), xb)
+        w = rand_codes(r, (1, L), wb)
+        px, _ = oracle.pack_planes(x, xb)
+        pw, _ = oracle.pack_planes(w, wb)
+        total = 0
+        for m in range(xb):
+            for k in range(wb):
+                pop = sum(bin(int(a) ^ int(b)).count("1") for a, b in zip(px[0, m], pw[0, k]))
+                total += (1 << (m + k)) * (L - 2 * pop)
+        assert total == int(np.dot(x[0].astype(np.int64), w[0].astype(np.int64)))
+
+
+@pytest.mark.parametrize("xb", range(1, 9))
+@pytest.mark.parametrize("wb", range(1, 9))
+def test_branch_sum_equals_integer_dot(oracle, xb, wb):
+    """Eq. (8) = Eq. (1) for every bit-width pair (M x K branches)."""
+    r = rng(1000 + 8 * xb + wb)
+    for n in (1, 2, 7, 40):
+        x = rand_codes(r, (n,), xb)
+        w = rand_codes(r, (n,), wb)
+        want = sum(int(a) * int(b) for a, b in zip(x, w))
+        assert oracle.branch_dot(x, w, xb, wb) == want
+        assert int(oracle.gemm(x[None, :], w[:, None])[0, 0]) == want
+
+
+def test_two_bit_fc_example(oracle):
+    """Sec. 3.2 / Fig. 1: x = x1 + 2 x2, w = w1 + 2 w2, four branch products with
+    weights 1, 2, 2, 4 and the final factor 1/9 on values in {-1,-1/3,1/3,1}."""
+    consts = {}
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            if not line.startswith("#") and line.strip():
+                k, v = line.split()
+                consts[k] = v
+    scale = Fraction(consts["fc_2bit_scale"])
+    assert scale == Fraction(1, (2 ** 2 - 1) * (2 ** 2 - 1))          # Eq. (9), r = 1
+    r = rng(7)
+    n = 12
+    x = rand_codes(r, (n,), 2)
+    w = rand_codes(r, (n,), 2)
+    x1 = [int(oracle.encode(v, 2)[0]) for v in x]
+    x2 = [int(oracle.encode(v, 2)[1]) for v in x]
+    w1 = [int(oracle.encode(v, 2)[0]) for v in w]
+    w2 = [int(oracle.encode(v, 2)[1]) for v in w]
+    dot = lambda a, b: sum(p * q for p, q in zip(a, b))
+    y = [dot(x1, w1), dot(x2, w1), dot(x1, w2), dot(x2, w2)]
+    assert len(y) == int(consts["fc_2bit_branches"])
+    enc = y[0] + 2 * y[1] + 2 * y[2] + 4 * y[3]
+    assert enc == oracle.branch_dot(x, w, 2, 2) == int(oracle.gemm(x[None], w[:, None])[0, 0])
+    real = sum(Fraction(int(a), 3) * Fraction(int(b), 3) for a, b in zip(x, w))   # Eq. (19)
+    assert real == scale * enc
+    y64 = oracle.scale_f64(np.array([[enc]]), np.array([1.0 / 9.0], dtype=np.float32))
+    assert abs(y64[0, 0] - float(real)) <= 1e-6 * max(1.0, abs(float(real)))
+
+
+# ------------------------------------------------------------- Eq. (1) GEMM
+@pytest.mark.parametrize("ab,wb", [(1, 1), (2, 2), (4, 3), (8, 2), (8, 8)])
+def test_gemm_against_float64_matmul(oracle, ab, wb):
+    r = rng(ab * 10 + wb)
+    M, N, K = 13, 9, 77
+    A = rand_codes(r, (M, K), ab)
+    W = rand_codes(r, (K, N), wb)
+    want = np.matmul(A.astype(np.float64), W.astype(np.float64))     # exact: |values| << 2^53
+    got = oracle.gemm(A, W)
+    assert got.dtype == np.int64 and (got == want.astype(np.int64)).all()
+    assert (oracle.gemm_wt(A, np.ascontiguousarray(W.T)) == got).all()
+    # a transposed operand would change the result
+    A2 = rand_codes(r, (K, K), ab)
+    W2 = rand_codes(r, (K, K), wb)
+    assert not (oracle.gemm(A2, W2) == oracle.gemm(A2, np.ascontiguousarray(W2.T))).all()
+
+
+def test_gemm_closed_forms(oracle):
+    for ab, wb, K in ((2, 2, 256), (4, 3, 2304), (8, 8, 33), (1, 1, 5)):
+        ma, mw = (1 << ab) - 1, (1 << wb) - 1
+        A = np.full((2, K), ma, dtype=np.int16)
+        W = np.full((K, 3), mw, dtype=np.int16)
+        assert (oracle.gemm(A, W) == K * ma * mw).all()              # all agree: S = 0
+        assert (oracle.gemm(-A, W) == -K * ma * mw).all()
+        r = rng(K)
+        A = rand_codes(r, (5, K), ab)
+        W = rand_codes(r, (K, 4), wb)
+        C = oracle.gemm(A, W)
+        assert (oracle.gemm(-A, W) == -C).all()
+        assert ((C - K) % 2 == 0).all()                              # odd*odd summed K times
+        assert (np.abs(C) <= K * ma * mw).all()
+    alt = np.array([[1, -1] * 8], dtype=np.int16)
+    assert oracle.gemm(alt, np.ones((16, 1), dtype=np.int16))[0, 0] == 0
+
+
+def test_one_bit_case_is_binary_network(oracle):
+    """M = K = 1 reduces to a +-1 (binary network) product."""
+    r = rng(3)
+    A = rand_codes(r, (6, 50), 1)
+    W = rand_codes(r, (50, 7), 1)
+    assert set(np.unique(A)) <= {-1, 1}
+    agree = (A[:, :, None] == W[None, :, :]).sum(axis=1)
+    assert (oracle.gemm(A, W) == 2 * agree - 50).all()
+
+
+# --------------------------------------------------------------- convolution
+@pytest.mark.parametrize("shape", [(2, 1, 1, 3, 2), (1, 2, 2, 5, 3), (2, 3, 4, 7, 5), (1, 6, 5, 33, 4)])
+def test_conv_against_torch(oracle, shape):
+    import torch
+    Nb, H, W, C, Cout = shape
+    r = rng(sum(shape))
+    X = rand_codes(r, (Nb, H, W, C), 4)
+    Wt = rand_codes(r, (Cout, 3, 3, C), 3)
+    got = oracle.conv3x3(X, Wt)
+    x = torch.from_numpy(X.astype(np.float64)).permute(0, 3, 1, 2)
+    w = torch.from_numpy(Wt.astype(np.float64)).permute(0, 3, 1, 2)
+    want = torch.nn.functional.conv2d(x, w, stride=1, padding=1).permute(0, 2, 3, 1).numpy()
+    assert (got == want.astype(np.int64)).all()
+
+
+def test_conv_equals_explicit_im2col_gemm(oracle):
+    """3x3/pad 1 conv = GEMM on the explicit patch matrix with K ordered (kh, kw, c)."""
+    r = rng(11)
+    Nb, H, W, C, Cout = 2, 4, 5, 6, 3
+    X = rand_codes(r, (Nb, H, W, C), 2)
+    Wt = rand_codes(r, (Cout, 3, 3, C), 2)
+    Xp = np.zeros((Nb, H + 2, W + 2, C), dtype=np.int16)
+    Xp[:, 1:-1, 1:-1] = X
+    rows = []
+    for n in range(Nb):
+        for oh in range(H):
+            for ow in range(W):
+                rows.append(Xp[n, oh:oh + 3, ow:ow + 3, :].reshape(-1))
+    patches = np.stack(rows)
+    # zero padding is not a code, so use float64 matmul rather than the code GEMM
+    want = patches.astype(np.float64) @ Wt.reshape(Cout, -1).T.astype(np.float64)
+    assert (oracle.conv3x3(X, Wt).reshape(-1, Cout) == want.astype(np.int64)).all()
+
+
+def test_conv_special_cases(oracle):
+    r = rng(5)
+    Nb, H, W, C = 1, 5, 6, 4
+    X = rand_codes(r, (Nb, H, W, C), 3)
+    # all-ones image and kernel: counts the valid taps (4 / 6 / 9) times C
+    ones = np.ones((Nb, H, W, C), dtype=np.int16)
+    k1 = np.ones((1, 3, 3, C), dtype=np.int16)
+    O = oracle.conv3x3(ones, k1)[0, :, :, 0]
+    taps = np.array([[(3 - (oh == 0) - (oh == H - 1)) * (3 - (ow == 0) - (ow == W - 1))
+                      for ow in range(W)] for oh in range(H)])
+    assert (O == taps * C).all()
+    # parity: sum of (valid taps * C) odd products
+    Wt = rand_codes(r, (2, 3, 3, C), 2)
+    O = oracle.conv3x3(X, Wt)
+    assert (((O[0] - (taps * C)[:, :, None]) % 2) == 0).all()
+    # no kernel flip: a kernel with a single +1-vs-(-1) asymmetry at (kh=0,kw=0) looks up-left
+    Xs = np.ones((1, 3, 3, 1), dtype=np.int16)
+    Xs[0, 0, 0, 0] = 3
+    K = np.ones((1, 3, 3, 1), dtype=np.int16)
+    K[0, 0, 0, 0] = 3
+    O = oracle.conv3x3(Xs, K)
+    assert O[0, 1, 1, 0] == 8 + 9                                   # x[0,0]*k[0,0] aligned
+    K2 = np.ones((1, 3, 3, 1), dtype=np.int16)
+    K2[0, 2, 2, 0] = 3
+    assert oracle.conv3x3(Xs, K2)[0, 1, 1, 0] == 3 + 7 + 3           # x[0,0]*1 + 7 + x[2,2]*3
+
+
+# ------------------------------------------------------------ Eq. (9) scale
+def test_scale_epilogue(oracle):
+    r = rng(9)
+    acc = r.integers(-(1 << 23), 1 << 23, size=(50, 17)).astype(np.int64)
+    s = r.uniform(0.0005, 0.005, size=17).astype(np.float32)
+    y64 = oracle.scale_f64(acc, s)
+    assert (y64 == acc.astype(np.float64) * s.astype(np.float64)[None, :]).all()
+    y32 = oracle.scale_f32(acc, s)
+    assert y32.dtype == np.float32
+    assert (y32 == (acc.astype(np.float32) * s[None, :])).all()       # one binary32 multiply
+    rel = np.abs(y32.astype(np.float64) - y64) / np.maximum(np.abs(y64), 1e-30)
+    assert rel.max() <= 2.0 ** -24 * 1.0001
+    # column j uses s[j], not s[i]
+    acc1 = np.ones((3, 17), dtype=np.int64)
+    assert (oracle.scale_f64(acc1, s)[2] == s.astype(np.float64)).all()
+
+
+# ------------------------------------------------- re-encoding between layers
+def test_round_odd_reproduces_table2_intervals(oracle):
+    """Table 2 scaled by alpha = 3: closures of the four intervals, endpoints included."""
+    for lo, loc, hi, hic, q, _, _ in _table2():
+        code = int(q * 3)
+        lo3, hi3 = float(lo * 3), float(hi * 3)
+        pts = [lo3 + (hi3 - lo3) * t for t in (0.001, 0.25, 0.5, 0.75, 0.999)]
+        if loc:
+            pts.append(lo3)
+        if hic:
+            pts.append(hi3)
+        for y in pts:
+            assert oracle.round_odd(y, 2) == code, (y, code)
+        if not loc:
+            assert oracle.round_odd(lo3, 2) != code
+        if not hic:
+            assert oracle.round_odd(hi3, 2) != code
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+def test_round_odd_properties(oracle, bits):
+    m = (1 << bits) - 1
+    ys = np.linspace(-m - 3.0, m + 3.0, 2001).astype(np.float32)
+    codes = oracle.requant(ys, bits)
+    assert (np.diff(codes.astype(np.int64)) >= 0).all()               # monotone
+    assert set(np.unique(codes)) == set(all_codes(bits))              # onto the code space
+    assert (np.abs(codes) <= m).all()
+    for v in all_codes(bits):                                         # codes are fixed points
+        assert oracle.round_odd(float(v), bits) == v
+    assert oracle.round_odd(0.0, bits) == -1 and oracle.round_odd(-0.0, bits) == -1
+    assert oracle.round_odd(1e30, bits) == m and oracle.round_odd(-1e30, bits) == -m
+
+
+def test_maxpool_and_requant_commute(oracle):
+    r = rng(21)
+    y = r.normal(0, 6, size=(2, 4, 6, 5)).astype(np.float32)
+    p = oracle.maxpool2x2(y)
+    want = y.reshape(2, 2, 2, 3, 2, 5).max(axis=(2, 4))
+    assert (p == want).all()
+    a = oracle.requant(p, 4)
+    b = oracle.maxpool2x2(oracle.requant(y, 4).astype(np.float32)).astype(np.int16)
+    assert (a == b).all()
