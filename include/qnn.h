@@ -1,0 +1,142 @@
+/*
+ * libqnn — C ABI of the {-1,+1} multi-branch binary matrix product on MI355X (gfx950).
+ *
+ * The method (paper Sec. 3.1, Eq. (7)-(8)): an odd integer code v, |v| <= 2^b - 1, is
+ * written v = sum_{m=1..b} 2^(m-1) c_m with c_m in {-1,+1}.  A product of a b_a-bit
+ * activation matrix with a b_w-bit weight matrix then splits into b_a*b_w binary
+ * branch products; each is evaluated on bit-packed words as  L - 2*popcount(a xor w)
+ * (= 2*popcount(xnor) - L) and the branches are summed with weights 2^(p+q).
+ *
+ * Conventions shared by every entry point
+ *   - All pointers are DEVICE pointers (HBM) unless the parameter name starts with h_.
+ *   - The caller owns every buffer.  Except where a function says otherwise the library
+ *     allocates nothing, frees nothing and never synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
+ *     function returns at once.
+ *   - Outputs are fully overwritten; inputs and outputs must not overlap.
+ *   - Argument errors are detected on the host before anything is launched and are
+ *     reported by the return code only (no exceptions, no aborts, no global state).
+ *     Asynchronous device faults surface at the caller's next synchronisation.
+ *   - Bit-plane layout ("planes"): uint32 [rows][bits][Kw], Kw = ceil(K/32).  Plane p
+ *     (p = 0 low ... bits-1 high) holds element c_{p+1} of every code of the row;
+ *     element k of the row is bit (k mod 32) of word k/32; bit 1 <=> +1, bit 0 <=> -1;
+ *     bits at positions >= K are 0.  Plane buffers must be 16-byte aligned.
+ */
+#ifndef QNN_H
+#define QNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QNN_OK = 0,
+    QNN_EINVAL = 1,        /* null pointer, bits outside 1..8, negative size, bad flag/enum   */
+    QNN_EALIGN = 2,        /* a buffer is not aligned as documented                          */
+    QNN_EUNSUPPORTED = 3,  /* a size beyond the documented limits                            */
+    QNN_EWORKSPACE = 4,    /* workspace smaller than the matching *_workspace_bytes()         */
+    QNN_EHIP = 5           /* the HIP runtime refused a launch (see qnn_last_hip_error)       */
+} qnn_status;
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *qnn_status_string(int status);
+
+/* hipError_t (as int) of the most recent failed launch on the calling thread, 0 if none. */
+int qnn_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int qnn_version(void);
+
+/*
+ * Performance knobs (process-wide; results never depend on them).  value 0 restores the
+ * automatic choice.  Returns QNN_OK or QNN_EINVAL.  Not thread-safe against running calls.
+ */
+#define QNN_TUNE_WAVES_PER_SIMD 1 /* resident wavefronts per SIMD the launch sizing aims for */
+#define QNN_TUNE_ROWS_PER_WAVE 2  /* rows (GEMM rows / output pixels) per wavefront        */
+int qnn_tune(int key, int value);
+
+/* flags of qnn_encode_pack */
+#define QNN_PACK_VALIDATE 1u /* count entries that are not codes into *bad_count */
+
+/*
+ * Encode + pack (Eq. (7); the "store those numbers by bits" step of Sec. 5.4).
+ *   codes      [rows][K] row-major integer codes; element size code_bytes = 1 (int8,
+ *              bits <= 7) or 2 (int16, any bits).  A valid code is odd with
+ *              |v| <= 2^bits - 1.
+ *   planes     out, uint32 [rows][bits][Kw] in the bit-plane layout above.
+ *   bad_count  optional device int32.  With QNN_PACK_VALIDATE the number of entries that
+ *              are not valid codes is ADDED to it (caller zeroes it); such entries pack
+ *              as the lowest code (all plane bits 0).  Without the flag, or if NULL, no
+ *              check is made and an invalid entry packs as the low `bits` binary digits
+ *              of (v + 2^bits - 1) >> 1.
+ *   rows == 0 or K == 0 is valid and launches nothing.
+ * Limits: rows * bits * Kw < 2^40, K < 2^31.
+ */
+qnn_status qnn_encode_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
+                           uint32_t *planes, int32_t *bad_count, unsigned flags, void *stream);
+
+/*
+ * Multi-branch binary GEMM with fused weighted accumulation (Eq. (8); Alg. 1 forward).
+ *   A    activation planes [M][ab][Kw];  Wt  weight planes [N][wb][Kw] (the weight matrix
+ *        transposed: row n holds output column n);  K = true inner length.
+ *   acc  out int32 [M][N] row-major:
+ *          acc[i][j] = sum_{p<ab} sum_{q<wb} 2^(p+q) * (K - 2*popcount(A[i][p] xor Wt[j][q]))
+ *        which equals the integer product of the decoded codes.  May be NULL if out_f32
+ *        is given.
+ *   scale, out_f32   optional fused scale (Eq. (9)): if both non-NULL,
+ *        out_f32[i][j] = (float)acc[i][j] * scale[j]  (one IEEE binary32 multiply).
+ *        scale is fp32 [N]; out_f32 is fp32 [M][N].  Both NULL = no epilogue.
+ *   M == 0 or N == 0 launches nothing.  K == 0 gives all zeros.
+ * Limits: K*(2^ab-1)*(2^wb-1) < 2^31 (else QNN_EUNSUPPORTED), M, N < 2^31.
+ */
+qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M,
+                           int64_t N, int64_t K, int32_t *acc, const float *scale,
+                           float *out_f32, void *stream);
+
+/*
+ * 3x3 convolution, stride 1, zero padding 1, NHWC, as an implicit-im2col multi-branch
+ * GEMM (Sec. 3.2: Op may be a convolution).  K order is (kh, kw, c), cross-correlation.
+ *   x_codes   [Nb][H][W][C] codes (code_bytes as in qnn_encode_pack), ab bits.
+ *   Wt        weight planes of the codes viewed as [Cout*9][C] rows, i.e. the output of
+ *             qnn_encode_pack(codes = Wt[Cout][3][3][C], rows = Cout*9, K = C, bits = wb):
+ *             uint32 [Cout][9][wb][Cw], Cw = ceil(C/32).
+ *   acc       out int32 NHWC [Nb][H][W][Cout] (may be NULL if out_f32 is given);
+ *             taps that fall outside the image contribute exactly 0.
+ *   scale, out_f32  optional fused per-output-channel scale as in qnn_branch_gemm.
+ *   workspace device scratch of at least qnn_conv2d_im2col_workspace_bytes() bytes,
+ *             16-byte aligned; holds the per-pixel activation planes
+ *             uint32 [Nb*H*W][ab][Cw] between the two kernels of this call.
+ * Limits: 9*C*(2^ab-1)*(2^wb-1) < 2^31, Nb*H*W < 2^31, Cout < 2^31.
+ */
+size_t qnn_conv2d_im2col_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int ab);
+
+qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt,
+                             int wb, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                             int32_t *acc, const float *scale, float *out_f32, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
+ * The same convolution from activations that are already packed per pixel
+ * (x_planes = qnn_encode_pack(codes viewed as [Nb*H*W][C], bits = ab), uint32
+ * [Nb*H*W][ab][Cw]).  This is the second kernel of qnn_conv2d_im2col on its own; it is
+ * what a layer chain calls when the previous layer already emitted packed planes.
+ */
+qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb,
+                             int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                             int32_t *acc, const float *scale, float *out_f32, void *stream);
+
+/*
+ * Stand-alone scale epilogue (Eq. (9); Eq. (19)): out_f32[i][j] = (float)acc[i][j] * scale[j],
+ * acc int32 [M][N], scale fp32 [N], out fp32 [M][N].  One IEEE binary32 multiply per
+ * element, no fused multiply-add.  M == 0 or N == 0 launches nothing.
+ */
+qnn_status qnn_scale_epilogue(const int32_t *acc, int64_t M, int64_t N, const float *scale,
+                              float *out_f32, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QNN_H */

@@ -1,0 +1,186 @@
+"""Thin Python binding of libqnn (see include/qnn.h): argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their device
+pointers to the C entry point of the same name on torch's current stream, and returns the
+output tensors it allocated.  No step of the method runs in Python or in torch ops.  If the
+HIP library has not been built the import of :func:`lib` raises; there is no fallback.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqnn.so")
+
+QNN_OK, QNN_EINVAL, QNN_EALIGN, QNN_EUNSUPPORTED, QNN_EWORKSPACE, QNN_EHIP = range(6)
+QNN_PACK_VALIDATE = 1
+QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE = 1, 2
+
+EXPORTS = (
+    "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_encode_pack",
+    "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col",
+    "qnn_conv2d_packed", "qnn_scale_epilogue",
+)
+
+
+class QnnError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        msg = lib().qnn_status_string(status).decode()
+        if status == QNN_EHIP:
+            msg += " (hipError %d)" % lib().qnn_last_hip_error()
+        super().__init__("%s: %s" % (what, msg))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library with argument types set.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libqnn.so is not built (%s); run `python -m paper_2106_09886_amd.build`" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp, u32, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_uint, ctypes.c_size_t
+    L.qnn_status_string.argtypes = [i32]
+    L.qnn_status_string.restype = ctypes.c_char_p
+    L.qnn_last_hip_error.argtypes = []
+    L.qnn_last_hip_error.restype = i32
+    L.qnn_version.argtypes = []
+    L.qnn_version.restype = i32
+    L.qnn_tune.argtypes = [i32, i32]
+    L.qnn_tune.restype = i32
+    L.qnn_encode_pack.argtypes = [vp, i32, i64, i64, i32, vp, vp, u32, vp]
+    L.qnn_encode_pack.restype = i32
+    L.qnn_branch_gemm.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, vp]
+    L.qnn_branch_gemm.restype = i32
+    L.qnn_conv2d_im2col_workspace_bytes.argtypes = [i64, i64, i64, i64, i32]
+    L.qnn_conv2d_im2col_workspace_bytes.restype = sz
+    L.qnn_conv2d_im2col.argtypes = [vp, i32, i32, vp, i32, i64, i64, i64, i64, i64, vp, vp, vp, vp, sz, vp]
+    L.qnn_conv2d_im2col.restype = i32
+    L.qnn_conv2d_packed.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, i64, vp, vp, vp, vp]
+    L.qnn_conv2d_packed.restype = i32
+    L.qnn_scale_epilogue.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.qnn_scale_epilogue.restype = i32
+    _lib = L
+    return L
+
+
+def _check(status, what):
+    if status != QNN_OK:
+        raise QnnError(status, what)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if t.dtype != dtype:
+        raise ValueError("%s must have dtype %s" % (name, dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t
+
+
+def tune(waves_per_simd=None, rows_per_wave=None):
+    if waves_per_simd is not None:
+        _check(lib().qnn_tune(QNN_TUNE_WAVES_PER_SIMD, int(waves_per_simd)), "qnn_tune")
+    if rows_per_wave is not None:
+        _check(lib().qnn_tune(QNN_TUNE_ROWS_PER_WAVE, int(rows_per_wave)), "qnn_tune")
+
+
+def encode_pack(codes, bits, validate=False, out=None):
+    """codes: int8/int16 GPU tensor [rows][K] -> uint32-as-int32 planes [rows][bits][Kw].
+
+    With validate=True also returns the device int32 counter of invalid entries."""
+    if codes.dtype not in (torch.int8, torch.int16):
+        raise ValueError("codes must be int8 or int16")
+    _dev(codes, codes.dtype, "codes")
+    rows, K = codes.shape
+    Kw = (K + 31) // 32
+    planes = out if out is not None else torch.empty((rows, bits, Kw), dtype=torch.int32, device=codes.device)
+    bad = torch.zeros(1, dtype=torch.int32, device=codes.device) if validate else None
+    st = lib().qnn_encode_pack(_ptr(codes), codes.element_size(), rows, K, bits, _ptr(planes), _ptr(bad),
+                               QNN_PACK_VALIDATE if validate else 0, _stream())
+    _check(st, "qnn_encode_pack")
+    return (planes, bad) if validate else planes
+
+
+def _outputs(rows_shape, N, device, scale, want_acc):
+    acc = torch.empty(tuple(rows_shape) + (N,), dtype=torch.int32, device=device) if want_acc else None
+    out = torch.empty(tuple(rows_shape) + (N,), dtype=torch.float32, device=device) if scale is not None else None
+    return acc, out
+
+
+def branch_gemm(A, ab, Wt, wb, K, scale=None, want_acc=True):
+    """A planes [M][ab][Kw], Wt planes [N][wb][Kw] -> (acc int32 [M][N] | None, out fp32 | None)."""
+    _dev(A, torch.int32, "A")
+    _dev(Wt, torch.int32, "Wt")
+    M, N = A.shape[0], Wt.shape[0]
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    acc, out = _outputs((M,), N, A.device, scale, want_acc)
+    st = lib().qnn_branch_gemm(_ptr(A), ab, _ptr(Wt), wb, M, N, K, _ptr(acc), _ptr(scale), _ptr(out), _stream())
+    _check(st, "qnn_branch_gemm")
+    return acc, out
+
+
+def conv2d_im2col_workspace_bytes(Nb, H, W, C, ab):
+    return int(lib().qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab))
+
+
+def conv2d_im2col(x_codes, ab, Wt, wb, Cout, scale=None, want_acc=True, workspace=None, out=None):
+    """x_codes NHWC int8/int16, Wt planes [Cout][9][wb][Cw] -> (acc int32 NHWC | None, out fp32 | None)."""
+    _dev(x_codes, x_codes.dtype, "x_codes")
+    _dev(Wt, torch.int32, "Wt")
+    Nb, H, W, C = x_codes.shape
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    if out is None:
+        acc, o32 = _outputs((Nb, H, W), Cout, x_codes.device, scale, want_acc)
+    else:
+        acc, o32 = out
+    need = conv2d_im2col_workspace_bytes(Nb, H, W, C, ab)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x_codes.device)
+    st = lib().qnn_conv2d_im2col(_ptr(x_codes), x_codes.element_size(), ab, _ptr(Wt), wb, Nb, H, W, C, Cout,
+                                 _ptr(acc), _ptr(scale), _ptr(o32), _ptr(workspace), workspace.numel(),
+                                 _stream())
+    _check(st, "qnn_conv2d_im2col")
+    return acc, o32
+
+
+def conv2d_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, scale=None, want_acc=True, out=None):
+    _dev(x_planes, torch.int32, "x_planes")
+    _dev(Wt, torch.int32, "Wt")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    if out is None:
+        acc, o32 = _outputs((Nb, H, W), Cout, x_planes.device, scale, want_acc)
+    else:
+        acc, o32 = out
+    st = lib().qnn_conv2d_packed(_ptr(x_planes), ab, _ptr(Wt), wb, Nb, H, W, C, Cout, _ptr(acc), _ptr(scale),
+                                 _ptr(o32), _stream())
+    _check(st, "qnn_conv2d_packed")
+    return acc, o32
+
+
+def scale_epilogue(acc, scale):
+    _dev(acc, torch.int32, "acc")
+    _dev(scale, torch.float32, "scale")
+    N = acc.shape[-1]
+    M = acc.numel() // N if N else 0
+    out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    _check(lib().qnn_scale_epilogue(_ptr(acc), M, N, _ptr(scale), _ptr(out), _stream()), "qnn_scale_epilogue")
+    return out

@@ -1,0 +1,213 @@
+// C ABI of libqnn: argument checks on the host, then launches.  See include/qnn.h.
+#include <atomic>
+#include "qnn_internal.h"
+
+namespace qnn {
+
+Tuning &tuning() {
+    static Tuning t = {4, 0};
+    return t;
+}
+
+int device_simd_count() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1024;
+    int v = cached[dev].load(std::memory_order_relaxed);
+    if (v == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        v = 4 * cus;
+        cached[dev].store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+qnn_status from_hip(hipError_t e) {
+    if (e == hipSuccess) return QNN_OK;
+    g_last_hip_error = (int)e;
+    return QNN_EHIP;
+}
+
+bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+bool aligned4(const void *p) { return (((uintptr_t)p) & 3u) == 0; }
+bool bits_ok(int b) { return b >= 1 && b <= 8; }
+
+const branch_launch_fn k_gemm[8] = {launch_gemm_ab1, launch_gemm_ab2, launch_gemm_ab3, launch_gemm_ab4,
+                                    launch_gemm_ab5, launch_gemm_ab6, launch_gemm_ab7, launch_gemm_ab8};
+const branch_launch_fn k_conv[8] = {launch_conv_ab1, launch_conv_ab2, launch_conv_ab3, launch_conv_ab4,
+                                    launch_conv_ab5, launch_conv_ab6, launch_conv_ab7, launch_conv_ab8};
+
+const int64_t kInt31 = ((int64_t)1 << 31) - 1;
+
+// Rows handled by one wavefront: enough wavefronts to give every SIMD of the chip
+// `waves_per_simd` of them, but never fewer than `min_rows` rows each (the weight chunk a
+// wavefront loads is reused for all of its rows).
+int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows) {
+    const Tuning &t = tuning();
+    if (t.rows_per_wave > 0) return t.rows_per_wave;
+    const int64_t target_waves = (int64_t)device_simd_count() * (t.waves_per_simd > 0 ? t.waves_per_simd : 4);
+    int64_t row_blocks = target_waves / col_tiles;
+    if (row_blocks < 1) row_blocks = 1;
+    int64_t rpw = (rows + row_blocks - 1) / row_blocks;
+    if (rpw < min_rows) rpw = min_rows;
+    if (rpw > rows) rpw = rows;
+    if (rpw < 1) rpw = 1;
+    return (int)rpw;
+}
+
+// Checks shared by the GEMM and convolution entry points.  k_tap = true inner length of one
+// tap (K for GEMM, C for conv), taps = 1 or 9.
+qnn_status check_branch(const void *A, int ab, const void *Wt, int wb, int64_t rows, int64_t N,
+                        int64_t k_tap, int taps, const void *acc, const void *scale, const void *out) {
+    if (!bits_ok(ab) || !bits_ok(wb)) return QNN_EINVAL;
+    if (rows < 0 || N < 0 || k_tap < 0) return QNN_EINVAL;
+    if ((scale == nullptr) != (out == nullptr)) return QNN_EINVAL;
+    if (rows == 0 || N == 0) return QNN_OK;            // empty output: nothing is dereferenced
+    if (acc == nullptr && out == nullptr) return QNN_EINVAL;
+    if ((A == nullptr || Wt == nullptr) && k_tap > 0) return QNN_EINVAL;
+    if (!aligned16(A) || !aligned16(Wt)) return QNN_EALIGN;
+    if (!aligned4(acc) || !aligned4(scale) || !aligned4(out)) return QNN_EALIGN;
+    const int64_t fa = ((int64_t)1 << ab) - 1, fw = ((int64_t)1 << wb) - 1;
+    if (k_tap > kInt31 / (fa * fw * taps)) return QNN_EUNSUPPORTED;       // int32 result range
+    const int64_t cw = (k_tap + 31) / 32;
+    if (rows > kInt31 || N > kInt31) return QNN_EUNSUPPORTED;
+    if (cw > 0 && (rows > kInt31 / (ab * cw) || N > kInt31 / (wb * cw * taps))) return QNN_EUNSUPPORTED;
+    return QNN_OK;
+}
+
+}  // namespace
+}  // namespace qnn
+
+using namespace qnn;
+
+extern "C" {
+
+const char *qnn_status_string(int status) {
+    switch (status) {
+        case QNN_OK: return "ok";
+        case QNN_EINVAL: return "invalid argument";
+        case QNN_EALIGN: return "buffer not aligned as documented";
+        case QNN_EUNSUPPORTED: return "size beyond the documented limits";
+        case QNN_EWORKSPACE: return "workspace too small";
+        case QNN_EHIP: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+int qnn_last_hip_error(void) { return g_last_hip_error; }
+
+int qnn_version(void) { return 100; }
+
+int qnn_tune(int key, int value) {
+    if (value < 0) return QNN_EINVAL;
+    switch (key) {
+        case QNN_TUNE_WAVES_PER_SIMD: tuning().waves_per_simd = value; return QNN_OK;
+        case QNN_TUNE_ROWS_PER_WAVE: tuning().rows_per_wave = value; return QNN_OK;
+    }
+    return QNN_EINVAL;
+}
+
+qnn_status qnn_encode_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
+                           uint32_t *planes, int32_t *bad_count, unsigned flags, void *stream) {
+    if (!bits_ok(bits) || rows < 0 || K < 0) return QNN_EINVAL;
+    if (code_bytes != 1 && code_bytes != 2) return QNN_EINVAL;
+    if (code_bytes == 1 && bits == 8) return QNN_EINVAL;          // 8-bit codes need int16
+    if (flags & ~QNN_PACK_VALIDATE) return QNN_EINVAL;
+    if (rows == 0 || K == 0) return QNN_OK;
+    if (codes == nullptr || planes == nullptr) return QNN_EINVAL;
+    if (!aligned16(planes)) return QNN_EALIGN;
+    if (code_bytes == 2 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
+    if (!aligned4(bad_count)) return QNN_EALIGN;
+    if (K > kInt31) return QNN_EUNSUPPORTED;
+    const int64_t Kw = (K + 31) / 32;
+    if (rows > (((int64_t)1 << 40) - 1) / (bits * Kw)) return QNN_EUNSUPPORTED;
+    const bool validate = (flags & QNN_PACK_VALIDATE) && bad_count != nullptr;
+    return from_hip(launch_pack(codes, code_bytes, rows, K, bits, planes, bad_count, validate,
+                                (hipStream_t)stream));
+}
+
+qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M, int64_t N,
+                           int64_t K, int32_t *acc, const float *scale, float *out_f32, void *stream) {
+    qnn_status st = check_branch(A, ab, Wt, wb, M, N, K, 1, acc, scale, out_f32);
+    if (st != QNN_OK || M == 0 || N == 0) return st;
+    BranchArgs g;
+    g.A = A; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+    g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
+    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1;
+    g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+    g.col_tiles = (int)((N + 63) / 64);
+    g.rows_per_wave = pick_rows_per_wave(M, g.col_tiles, 4);
+    return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
+}
+
+size_t qnn_conv2d_im2col_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int ab) {
+    if (Nb <= 0 || H <= 0 || W <= 0 || C <= 0 || !bits_ok(ab)) return 0;
+    const int64_t cw = (C + 31) / 32;
+    return (size_t)(Nb * H * W * ab * cw * 4);
+}
+
+qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
+                             int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc,
+                             const float *scale, float *out_f32, void *stream) {
+    if (Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
+    if (H > kInt31 || W > kInt31 || Nb > kInt31) return QNN_EUNSUPPORTED;
+    if (H > 0 && W > 0 && Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
+    const int64_t rows = Nb * H * W;
+    qnn_status st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32);
+    if (st != QNN_OK || rows == 0 || Cout == 0) return st;
+    BranchArgs g;
+    g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+    g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
+    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W;
+    g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+    g.col_tiles = (int)((Cout + 63) / 64);
+    g.rows_per_wave = pick_rows_per_wave(rows, g.col_tiles, 4);
+    return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
+}
+
+qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt, int wb,
+                             int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc,
+                             const float *scale, float *out_f32, void *workspace,
+                             size_t workspace_bytes, void *stream) {
+    if (Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
+    if (code_bytes != 1 && code_bytes != 2) return QNN_EINVAL;
+    if (code_bytes == 1 && ab == 8) return QNN_EINVAL;
+    if (H > kInt31 || W > kInt31 || Nb > kInt31) return QNN_EUNSUPPORTED;
+    if (H > 0 && W > 0 && Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
+    const int64_t rows = Nb * H * W;
+    uint32_t *planes = static_cast<uint32_t *>(workspace);
+    // validate everything before the first launch, so that an error launches nothing
+    const bool have_k = C > 0;
+    if (have_k && rows > 0 && Cout > 0) {
+        if (x_codes == nullptr || workspace == nullptr) return QNN_EINVAL;
+        if (!aligned16(workspace)) return QNN_EALIGN;
+        if (code_bytes == 2 && (((uintptr_t)x_codes) & 1u)) return QNN_EALIGN;
+    }
+    qnn_status st = check_branch(planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32);
+    if (st != QNN_OK) return st;
+    if (rows == 0 || Cout == 0) return QNN_OK;
+    if (have_k) {
+        if (workspace_bytes < qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab)) return QNN_EWORKSPACE;
+        st = qnn_encode_pack(x_codes, code_bytes, rows, C, ab, planes, nullptr, 0, stream);
+        if (st != QNN_OK) return st;
+    }
+    return qnn_conv2d_packed(planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, stream);
+}
+
+qnn_status qnn_scale_epilogue(const int32_t *acc, int64_t M, int64_t N, const float *scale,
+                              float *out_f32, void *stream) {
+    if (M < 0 || N < 0) return QNN_EINVAL;
+    if (M == 0 || N == 0) return QNN_OK;
+    if (acc == nullptr || scale == nullptr || out_f32 == nullptr) return QNN_EINVAL;
+    if (!aligned4(acc) || !aligned4(scale) || !aligned4(out_f32)) return QNN_EALIGN;
+    if (M > (((int64_t)1 << 40) - 1) / N) return QNN_EUNSUPPORTED;
+    return from_hip(launch_scale(acc, M * N, N, scale, out_f32, (hipStream_t)stream));
+}
+
+}  // extern "C"

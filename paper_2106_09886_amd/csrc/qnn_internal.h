@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libqnn (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "qnn.h"
+
+namespace qnn {
+
+// Arguments of the branch kernels (GEMM and 3x3 convolution).  All sizes were range
+// checked on the host; index arithmetic inside the kernels is 32-bit except for the
+// row base of the outputs.
+struct BranchArgs {
+    const uint32_t *A;    // activation planes [rows][AB][Cw]
+    const uint32_t *Wt;   // weight planes     [N][taps][WB][Cw]   (taps = 1 for GEMM)
+    int32_t *acc;         // int32 out [rows][N] or nullptr
+    const float *scale;   // fp32 [N] or nullptr
+    float *out;           // fp32 out [rows][N] or nullptr
+    int32_t *partial;     // where partial sums of a multi-chunk product live (acc, else out)
+    int rows;             // GEMM rows / output pixels
+    int N;                // output columns / filters
+    int Cw;               // words per (row, plane)
+    int H, W;             // image height and width in pixels (convolution only)
+    int kconst;           // (true K of one tap) * (2^AB - 1) * (2^WB - 1)
+    int rows_per_wave;    // contiguous rows handled by one wavefront
+    int col_tiles;        // ceil(N / 64)
+};
+
+struct Tuning {
+    int waves_per_simd;   // target resident wavefronts per SIMD when sizing rows_per_wave
+    int rows_per_wave;    // > 0 overrides the automatic choice
+};
+Tuning &tuning();
+
+int device_simd_count();  // 4 * number of compute units of the current device (cached)
+
+// Launchers, one translation unit per activation bit width AB (1..8).
+typedef hipError_t (*branch_launch_fn)(const BranchArgs &, int wb, hipStream_t);
+hipError_t launch_gemm_ab1(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab2(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab3(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab4(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab5(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab6(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab7(const BranchArgs &, int, hipStream_t);
+hipError_t launch_gemm_ab8(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab1(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab2(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab3(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab4(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab5(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab6(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab7(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_ab8(const BranchArgs &, int, hipStream_t);
+
+hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
+                       uint32_t *planes, int32_t *bad_count, bool validate, hipStream_t);
+hipError_t launch_scale(const int32_t *acc, int64_t total, int64_t N, const float *scale,
+                        float *out, hipStream_t);
+
+}  // namespace qnn

@@ -1,0 +1,152 @@
+"""The C-ABI library loads, exports every symbol include/qnn.h declares, and rejects bad
+arguments on the host before anything is launched (no GPU needed, no compute call made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2106_09886_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "qnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    from paper_2106_09886_amd import binding
+    names = declared_functions()
+    assert {"qnn_encode_pack", "qnn_branch_gemm", "qnn_conv2d_im2col", "qnn_scale_epilogue"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_status_strings(L):
+    seen = set()
+    for st in range(6):
+        s = L.qnn_status_string(st)
+        assert s and s not in seen
+        seen.add(s)
+    assert L.qnn_status_string(99) == b"unknown status"
+    assert L.qnn_version() >= 100
+
+
+P = 1 << 20          # a fake, 16-byte aligned, never dereferenced device address
+
+
+def test_encode_pack_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED
+    f = L.qnn_encode_pack
+    assert f(P, 1, 4, 64, 0, P, None, 0, None) == QNN_EINVAL          # bits
+    assert f(P, 1, 4, 64, 9, P, None, 0, None) == QNN_EINVAL
+    assert f(P, 3, 4, 64, 2, P, None, 0, None) == QNN_EINVAL          # code size
+    assert f(P, 1, 4, 64, 8, P, None, 0, None) == QNN_EINVAL          # 8 bits need int16
+    assert f(P, 1, -1, 64, 2, P, None, 0, None) == QNN_EINVAL
+    assert f(P, 1, 4, -5, 2, P, None, 0, None) == QNN_EINVAL
+    assert f(P, 1, 4, 64, 2, P, None, 2, None) == QNN_EINVAL          # unknown flag
+    assert f(None, 1, 4, 64, 2, P, None, 0, None) == QNN_EINVAL
+    assert f(P, 1, 4, 64, 2, None, None, 0, None) == QNN_EINVAL
+    assert f(P, 1, 4, 64, 2, P + 4, None, 0, None) == QNN_EALIGN
+    assert f(P + 1, 2, 4, 64, 2, P, None, 0, None) == QNN_EALIGN
+    assert f(P, 1, 4, 1 << 31, 2, P, None, 0, None) == QNN_EUNSUPPORTED
+    assert f(None, 1, 0, 64, 2, None, None, 0, None) == QNN_OK          # empty: nothing launched
+    assert f(None, 1, 4, 0, 2, None, None, 0, None) == QNN_OK
+
+
+def test_branch_gemm_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED
+    f = L.qnn_branch_gemm
+    assert f(P, 0, P, 2, 4, 4, 64, P, None, None, None) == QNN_EINVAL
+    assert f(P, 2, P, 9, 4, 4, 64, P, None, None, None) == QNN_EINVAL
+    assert f(P, 2, P, 2, -1, 4, 64, P, None, None, None) == QNN_EINVAL
+    assert f(P, 2, P, 2, 4, 4, 64, None, None, None, None) == QNN_EINVAL    # no output at all
+    assert f(P, 2, P, 2, 4, 4, 64, P, P, None, None) == QNN_EINVAL          # scale without out
+    assert f(P, 2, P, 2, 4, 4, 64, P, None, P, None) == QNN_EINVAL          # out without scale
+    assert f(None, 2, P, 2, 4, 4, 64, P, None, None, None) == QNN_EINVAL
+    assert f(P + 8, 2, P, 2, 4, 4, 64, P, None, None, None) == QNN_EALIGN
+    assert f(P, 2, P + 4, 2, 4, 4, 64, P, None, None, None) == QNN_EALIGN
+    assert f(P, 2, P, 2, 4, 4, 64, P + 2, None, None, None) == QNN_EALIGN
+    # K (2^8-1)^2 >= 2^31: the int32 result could overflow
+    assert f(P, 8, P, 8, 4, 4, 40000, P, None, None, None) == QNN_EUNSUPPORTED
+    assert f(P, 2, P, 2, 1 << 31, 4, 64, P, None, None, None) == QNN_EUNSUPPORTED
+    assert f(P, 2, P, 2, 0, 4, 64, P, None, None, None) == QNN_OK            # empty
+    assert f(P, 2, P, 2, 4, 0, 64, P, None, None, None) == QNN_OK
+
+
+def test_conv_argument_errors(L):
+    from paper_2106_09886_amd.binding import (QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED,
+                                              QNN_EWORKSPACE)
+    f = L.qnn_conv2d_im2col
+    need = L.qnn_conv2d_im2col_workspace_bytes(2, 8, 8, 64, 2)
+    assert need == 2 * 8 * 8 * 2 * 2 * 4
+    assert L.qnn_conv2d_im2col_workspace_bytes(2, 8, 8, 33, 4) == 2 * 8 * 8 * 4 * 2 * 4
+    assert L.qnn_conv2d_im2col_workspace_bytes(0, 8, 8, 64, 2) == 0
+    ok = dict(x=P, cb=1, ab=2, wt=P, wb=2, nb=2, h=8, w=8, c=64, co=64, acc=P, sc=None, out=None,
+              ws=P, wsb=need)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return f(a["x"], a["cb"], a["ab"], a["wt"], a["wb"], a["nb"], a["h"], a["w"], a["c"], a["co"],
+                 a["acc"], a["sc"], a["out"], a["ws"], a["wsb"], None)
+
+    assert call(ab=0) == QNN_EINVAL
+    assert call(wb=9) == QNN_EINVAL
+    assert call(cb=4) == QNN_EINVAL
+    assert call(ab=8, cb=1) == QNN_EINVAL
+    assert call(nb=-1) == QNN_EINVAL
+    assert call(x=None) == QNN_EINVAL
+    assert call(ws=None) == QNN_EINVAL
+    assert call(acc=None) == QNN_EINVAL
+    assert call(wt=None) == QNN_EINVAL
+    assert call(ws=P + 4) == QNN_EALIGN
+    assert call(wt=P + 8) == QNN_EALIGN
+    assert call(wsb=need - 1) == QNN_EWORKSPACE
+    assert call(nb=1 << 20, h=1 << 10, w=1 << 10) == QNN_EUNSUPPORTED
+    assert call(ab=8, cb=2, wb=8, c=1 << 16) == QNN_EUNSUPPORTED
+    assert call(nb=0) == QNN_OK
+    assert call(co=0) == QNN_OK
+    g = L.qnn_conv2d_packed
+    assert g(P, 2, P, 2, 2, 8, 8, 64, 64, None, None, None, None) == QNN_EINVAL
+    assert g(P + 4, 2, P, 2, 2, 8, 8, 64, 64, P, None, None, None) == QNN_EALIGN
+    assert g(P, 2, P, 2, 0, 8, 8, 64, 64, P, None, None, None) == QNN_OK
+
+
+def test_scale_epilogue_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK
+    f = L.qnn_scale_epilogue
+    assert f(None, 4, 4, P, P, None) == QNN_EINVAL
+    assert f(P, 4, 4, None, P, None) == QNN_EINVAL
+    assert f(P, 4, 4, P, None, None) == QNN_EINVAL
+    assert f(P, -4, 4, P, P, None) == QNN_EINVAL
+    assert f(P + 1, 4, 4, P, P, None) == QNN_EALIGN
+    assert f(P, 0, 4, P, P, None) == QNN_OK
+    assert f(P, 4, 0, P, P, None) == QNN_OK
+
+
+def test_tune_rejects_unknown_keys(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_OK
+    assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK
+    assert L.qnn_tune(2, 0) == QNN_OK
+    assert L.qnn_tune(99, 1) == QNN_EINVAL
+    assert L.qnn_tune(1, -1) == QNN_EINVAL
+
+
+def test_product_path_has_no_oracle_or_cpu_fallback():
+    """Nothing under the package may import the oracle."""
+    pkg = os.path.join(ROOT, "paper_2106_09886_amd")
+    for fn in os.listdir(pkg):
+        if fn.endswith(".py"):
+            src = open(os.path.join(pkg, fn)).read()
+            assert "import oracle" not in src and "from oracle" not in src, fn
