@@ -90,7 +90,8 @@ qnn_status qnn_encode_pack(const void *codes, int code_bytes, int64_t rows, int6
  *        out_f32[i][j] = (float)acc[i][j] * scale[j]  (one IEEE binary32 multiply).
  *        scale is fp32 [N]; out_f32 is fp32 [M][N].  Both NULL = no epilogue.
  *   M == 0 or N == 0 launches nothing.  K == 0 gives all zeros.
- * Limits: K*(2^ab-1)*(2^wb-1) < 2^31 (else QNN_EUNSUPPORTED), M, N < 2^31.
+ * Limits (else QNN_EUNSUPPORTED): K*(2^ab-1)*(2^wb-1) < 2^31; M < 2^31; N <= 2^24; each
+ *        plane buffer below 4 GiB (M*ab*Kw < 2^30 and N*wb*Kw < 2^30 words).
  */
 qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M,
                            int64_t N, int64_t K, int32_t *acc, const float *scale,
@@ -109,7 +110,8 @@ qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb
  *   workspace device scratch of at least qnn_conv2d_im2col_workspace_bytes() bytes,
  *             16-byte aligned; holds the per-pixel activation planes
  *             uint32 [Nb*H*W][ab][Cw] between the two kernels of this call.
- * Limits: 9*C*(2^ab-1)*(2^wb-1) < 2^31, Nb*H*W < 2^31, Cout < 2^31.
+ * Limits: 9*C*(2^ab-1)*(2^wb-1) < 2^31, Nb*H*W < 2^31, Cout <= 2^24, each plane buffer
+ *         below 4 GiB (Nb*H*W*ab*Cw < 2^30 and Cout*9*wb*Cw < 2^30 words).
  */
 size_t qnn_conv2d_im2col_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int ab);
 

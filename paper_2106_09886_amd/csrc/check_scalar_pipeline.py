@@ -1,0 +1,166 @@
+"""Static check of the hand-placed scalar loads in the generated gfx950 assembly.
+
+The branch kernels request activation words with s_load_dword* written as inline asm and
+wait for them with an explicit s_waitcnt; the compiler does not know the destination SGPRs
+are in flight in between.  This script compiles qnn_branch.hip to assembly for every
+activation bit width and verifies, kernel by kernel, that
+  * no scratch memory is used, and
+  * on no path of the control-flow graph does an instruction outside an asm block (a spill
+    to a VGPR lane included) name a requested SGPR between its s_load and the next
+    `s_waitcnt lgkmcnt(0)`.
+Run: python paper_2106_09886_amd/csrc/check_scalar_pipeline.py   (exit status 0 = clean)
+"""
+import os
+import re
+import subprocess
+import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def compile_asm(ab, out):
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-ffp-contract=off", "-Wno-unused-command-line-argument",
+           "-I", os.path.join(ROOT, "include"), "-I", HERE, "-DQNN_AB=%d" % ab, "-S", "--cuda-device-only",
+           os.path.join(HERE, "qnn_branch.hip"), "-o", out]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE)
+    return out
+
+
+def sregs(tok):
+    """SGPR numbers named by an operand token like s5 or s[8:15]."""
+    m = re.fullmatch(r"s(\d+)", tok)
+    if m:
+        return {int(m.group(1))}
+    m = re.fullmatch(r"s\[(\d+):(\d+)\]", tok)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    return set()
+
+
+def parse_kernel(lines):
+    """-> list of instructions (lineno, text, op, in_asm) and label -> instruction index."""
+    insts, labels = [], {}
+    in_asm = False
+    for ln, raw in lines:
+        l = raw.strip()
+        if l.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if l.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        m = re.match(r"^(\.LBB\d+_\d+):", l)
+        if m:
+            labels[m.group(1)] = len(insts)
+            continue
+        if not l or l.startswith(";") or l.startswith("."):
+            continue
+        l = l.split(";")[0].strip()
+        if not l:
+            continue
+        insts.append((ln, l, l.split()[0], in_asm))
+    return insts, labels
+
+
+def check_kernel(name, lines):
+    """Forward may-analysis over the control-flow graph: the set of SGPRs with a hand-issued
+    scalar load in flight.  A non-asm instruction that names one of them is a violation."""
+    insts, labels = parse_kernel(lines)
+    n = len(insts)
+    # The kernels have no lane-divergent control flow (blocks are always full, every branch
+    # condition is wave-uniform).  If nothing in the kernel writes EXEC, it stays all-ones and
+    # the EXEC-tested branches the compiler leaves behind are decided statically.
+    exec_const = not any(
+        op.startswith("v_cmpx") or "saveexec" in op or re.search(r"^\S+\s+exec(_lo|_hi)?\b", l)
+        for (_, l, op, _) in insts)
+    succ = [[] for _ in range(n)]
+    for i, (ln, l, op, _) in enumerate(insts):
+        if op == "s_endpgm":
+            continue
+        if op == "s_branch":
+            succ[i] = [labels[l.split()[1]]]
+        elif exec_const and op == "s_cbranch_execz":
+            succ[i] = [i + 1] if i + 1 < n else []
+        elif exec_const and op == "s_cbranch_execnz":
+            succ[i] = [labels[l.split()[1]]]
+        elif op.startswith("s_cbranch"):
+            succ[i] = [labels[l.split()[1]]] + ([i + 1] if i + 1 < n else [])
+        elif i + 1 < n:
+            succ[i] = [i + 1]
+    regs = [set().union(*[sregs(t) for t in re.findall(r"s\[\d+:\d+\]|\bs\d+\b", l)] or [set()])
+            for (_, l, _, _) in insts]
+    gen = [set() for _ in range(n)]
+    kill = [False] * n
+    for i, (ln, l, op, in_asm) in enumerate(insts):
+        if op == "s_waitcnt" and "lgkmcnt(0)" in l:
+            kill[i] = True
+        elif in_asm and op.startswith("s_load_dword"):
+            toks = re.findall(r"s\[\d+:\d+\]|\bs\d+\b", l)
+            gen[i] = sregs(toks[0])
+    pend_in = [set() for _ in range(n)]
+    work = list(range(n))
+    while work:
+        i = work.pop()
+        out = set() if kill[i] else (pend_in[i] | gen[i])
+        for j in succ[i]:
+            if not out <= pend_in[j]:
+                pend_in[j] |= out
+                work.append(j)
+    problems = []
+    for i, (ln, l, op, in_asm) in enumerate(insts):
+        if in_asm or kill[i]:
+            continue
+        hit = regs[i] & pend_in[i]
+        if hit:
+            problems.append("%s:%d touches in-flight s%s: %s" % (name, ln, sorted(hit), l))
+    spills = sum(1 for (_, _, op, _) in insts if op in ("v_writelane_b32", "v_readlane_b32"))
+    return problems, spills
+
+
+def check_file(path):
+    text = open(path).read().split("\n")
+    problems, nk, nspill = [], 0, 0
+    cur, name = None, None
+    for i, l in enumerate(text, 1):
+        m = re.match(r"^(_ZN3qnn\S*_kernel\S*):", l)
+        if m:
+            name, cur = m.group(1), []
+            continue
+        if cur is not None:
+            cur.append((i, l))
+            if "s_endpgm" in l:
+                p, sp = check_kernel(name, cur)
+                problems += p
+                nspill += sp
+                nk += 1
+                cur = None
+        m = re.match(r"^\s*\.amdhsa_private_segment_fixed_size\s+(\d+)", l)
+        if m and int(m.group(1)) != 0:
+            problems.append("%s: kernel uses %s bytes of scratch" % (path, m.group(1)))
+    return nk, problems, nspill
+
+
+def main():
+    tmp = tempfile.mkdtemp(prefix="qnn_asm_")
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        files = list(ex.map(lambda ab: compile_asm(ab, os.path.join(tmp, "ab%d.s" % ab)), range(1, 9)))
+    total, bad, spills = 0, [], 0
+    for f in files:
+        nk, p, sp = check_file(f)
+        total += nk
+        bad += p
+        spills += sp
+    print("%d kernels checked, %d problems (%d SGPR spill instructions, none touching a register in flight"
+          " unless listed)" % (total, len(bad), spills))
+    for p in bad[:40]:
+        print("  " + p)
+    return 1 if bad else 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -61,6 +61,13 @@ int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows) {
     return (int)rpw;
 }
 
+// One wavefront's output slice (rows_per_wave * N * 4 bytes) must stay below 2^31 bytes.
+int clamp_rows_per_wave(int rpw, int64_t N) {
+    const int64_t cap = (((int64_t)1 << 29) - 1) / (N > 0 ? N : 1);
+    if (rpw > cap) rpw = (int)(cap < 1 ? 1 : cap);
+    return rpw;
+}
+
 // Checks shared by the GEMM and convolution entry points.  k_tap = true inner length of one
 // tap (K for GEMM, C for conv), taps = 1 or 9.
 qnn_status check_branch(const void *A, int ab, const void *Wt, int wb, int64_t rows, int64_t N,
@@ -76,8 +83,11 @@ qnn_status check_branch(const void *A, int ab, const void *Wt, int wb, int64_t r
     const int64_t fa = ((int64_t)1 << ab) - 1, fw = ((int64_t)1 << wb) - 1;
     if (k_tap > kInt31 / (fa * fw * taps)) return QNN_EUNSUPPORTED;       // int32 result range
     const int64_t cw = (k_tap + 31) / 32;
-    if (rows > kInt31 || N > kInt31) return QNN_EUNSUPPORTED;
-    if (cw > 0 && (rows > kInt31 / (ab * cw) || N > kInt31 / (wb * cw * taps))) return QNN_EUNSUPPORTED;
+    // the kernels address the packed operands with 32-bit byte offsets and one output row with
+    // a 32-bit byte offset inside a wavefront's slice
+    const int64_t kWords30 = ((int64_t)1 << 30) - 1;
+    if (rows > kInt31 || N > ((int64_t)1 << 24)) return QNN_EUNSUPPORTED;
+    if (cw > 0 && (rows > kWords30 / (ab * cw) || N > kWords30 / (wb * cw * taps))) return QNN_EUNSUPPORTED;
     return QNN_OK;
 }
 
@@ -142,7 +152,7 @@ qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb
     g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1;
     g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((N + 63) / 64);
-    g.rows_per_wave = pick_rows_per_wave(M, g.col_tiles, 4);
+    g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N);
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -167,7 +177,7 @@ qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *W
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.rows_per_wave = pick_rows_per_wave(rows, g.col_tiles, 4);
+    g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 4), Cout);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
 }
 

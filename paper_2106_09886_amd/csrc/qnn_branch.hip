@@ -10,10 +10,12 @@
 //     v_bcnt_u32_b32 (popcount with fused accumulate);
 //   * branches with equal p+q share an accumulator; the 2^(p+q) weights are applied once
 //     per row and chunk with AB+WB-2 shift-adds (Eq. (8) regrouped by p+q);
-//   * stores are lane-contiguous: one 256-byte segment per row and wavefront.
+//   * stores are lane-contiguous: one 256-byte segment per row and wavefront, addressed
+//     through a buffer descriptor (wave-uniform row offset in an SGPR, no vector address math).
 // A product whose K extent does not fit the VGPR chunk is done in several chunk passes by
 // the same wavefront; partial sums round-trip through the output buffer (same lane, same
 // address, program order).
+#include <type_traits>
 #include "qnn_internal.h"
 
 #ifndef QNN_AB
@@ -32,22 +34,10 @@ __device__ __forceinline__ uniform_words as_uniform(const uint32_t *p) {
 }
 
 // part += popcount(x): v_bcnt_u32_b32 with its add operand.  Written as asm so that the
-// accumulate chain is not re-associated into separate popcounts and three-input adds.
+// accumulate chain is not re-associated into separate popcounts and three-input adds;
+// volatile so that it keeps its place between the scalar-load requests and waits below.
 __device__ __forceinline__ void popc_acc(int &part, uint32_t x) {
-    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(part) : "v"(x));
-}
-
-// One segment of CWT words: all AB*WB plane pairs; pairs with equal p+q share part[p+q].
-template <int AB, int WB, int CWT>
-__device__ __forceinline__ void seg_accum(const uint32_t (&a)[AB][CWT],
-                                          const uint32_t (&w)[WB][CWT],
-                                          int (&part)[AB + WB - 1]) {
-#pragma unroll
-    for (int q = 0; q < WB; ++q)
-#pragma unroll
-        for (int p = 0; p < AB; ++p)
-#pragma unroll
-            for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], a[p][j] ^ w[q][j]);
+    asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(part) : "v"(x));
 }
 
 // S = sum_s 2^s part[s]  (Eq. (8) weights, grouped by s = p + q)
@@ -59,17 +49,138 @@ __device__ __forceinline__ int weighted_sum(const int (&part)[NP]) {
     return s;
 }
 
-// Finish one row of one chunk pass for this lane's column.
-__device__ __forceinline__ void finish_row(const BranchArgs &g, int64_t row, int n, bool n_ok,
-                                           int val, bool first, bool last, float sc) {
-    const int64_t base = row * (int64_t)g.N;
-    if (!n_ok) return;
-    if (!first) val += (g.partial + base)[n];
-    if (!last) {
-        (g.partial + base)[n] = val;
+// ---------------------------------------------------------------------------------------
+// Scalar loads under manual control.
+//
+// Scalar loads return out of order, so the only wait a wavefront has is "all of them".  The
+// compiler places that wait before the first use of any loaded register and is free to sink
+// the loads towards their use, which serialises fetch and compute.  The activation words
+// are therefore requested with s_load_dword* written as asm (the compiler does not know the
+// destination registers are still in flight) and the wait is written explicitly: arrive()
+// is s_waitcnt lgkmcnt(0) with the registers as in/out operands, so every use of the words
+// is ordered after it.  Invariant, checked on the generated code: between a request and its
+// arrive nothing reads or moves the requested registers.
+// ---------------------------------------------------------------------------------------
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+template <int N> struct SVec;
+template <> struct SVec<1> { typedef uint32_t type; };
+template <> struct SVec<2> { typedef u32x2 type; };
+template <> struct SVec<4> { typedef u32x4 type; };
+template <> struct SVec<8> { typedef u32x8 type; };
+template <> struct SVec<16> { typedef u32x16 type; };
+
+// N consecutive words, fetched as the binary decomposition of N (x16, x8, x4, x2, x1).
+template <int N>
+struct SRun {
+    static constexpr int HEAD = N >= 16 ? 16 : N >= 8 ? 8 : N >= 4 ? 4 : N >= 2 ? 2 : 1;
+    typename SVec<HEAD>::type head;
+    SRun<N - HEAD> tail;
+
+    // words at byte address base + off + IMM ...
+    template <int IMM>
+    __device__ __forceinline__ void request(uint64_t base, uint32_t off_in) {
+        // wave-uniform by construction; this pins the value to an SGPR (no code if it already is)
+        const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off_in);
+        if constexpr (HEAD == 16)
+            asm volatile("s_load_dwordx16 %0, %1, %2 offset:%3" : "=s"(head) : "s"(base), "s"(off), "n"(IMM));
+        else if constexpr (HEAD == 8)
+            asm volatile("s_load_dwordx8 %0, %1, %2 offset:%3" : "=s"(head) : "s"(base), "s"(off), "n"(IMM));
+        else if constexpr (HEAD == 4)
+            asm volatile("s_load_dwordx4 %0, %1, %2 offset:%3" : "=s"(head) : "s"(base), "s"(off), "n"(IMM));
+        else if constexpr (HEAD == 2)
+            asm volatile("s_load_dwordx2 %0, %1, %2 offset:%3" : "=s"(head) : "s"(base), "s"(off), "n"(IMM));
+        else
+            asm volatile("s_load_dword %0, %1, %2 offset:%3" : "=s"(head) : "s"(base), "s"(off), "n"(IMM));
+        tail.template request<IMM + HEAD * 4>(base, off_in);
+    }
+    // WAIT: emit the s_waitcnt (first piece of a stage only); later pieces are just ordered
+    // after it.
+    template <bool WAIT>
+    __device__ __forceinline__ void arrive() {
+        if constexpr (WAIT) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(head));
+        else asm volatile("" : "+s"(head));
+        tail.template arrive<false>();
+    }
+    __device__ __forceinline__ uint32_t get(int i) const {
+        if constexpr (HEAD == 1) return i == 0 ? head : tail.get(i - 1);
+        else return i < HEAD ? head[i] : tail.get(i - HEAD);
+    }
+};
+template <>
+struct SRun<0> {
+    template <int IMM> __device__ __forceinline__ void request(uint64_t, uint32_t) {}
+    template <bool WAIT> __device__ __forceinline__ void arrive() {}
+    __device__ __forceinline__ uint32_t get(int) const { return 0u; }
+};
+
+// NR runs of LEN words each (one pipeline stage).
+template <int NR, int LEN>
+struct SStage {
+    SRun<LEN> run[NR];
+    template <bool WAIT>
+    __device__ __forceinline__ void arrive() {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            if (i == 0) run[i].template arrive<WAIT>();
+            else run[i].template arrive<false>();
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// Output addressing: buffer descriptors (base in SGPRs, wave-uniform byte offset in an SGPR,
+// the lane's column offset in a VGPR).  A descriptor covers the rows of one wavefront.
+// ---------------------------------------------------------------------------------------
+struct OutView {
+    __amdgpu_buffer_rsrc_t d0;   // int32 result if requested, else the fp32 result; also holds partial sums
+    __amdgpu_buffer_rsrc_t d1;   // the fp32 result when both outputs are requested
+    uint32_t flags;              // bit 0: int32 result requested, bit 1: fp32 result requested
+    uint32_t row_bytes;          // N * 4
+    int col_bytes;               // lane's column * 4.  Lanes past N compute column N-1 again (same
+                                 // weights, same scale) and store the identical value to it, so
+                                 // the epilogue needs no lane mask
+    float sc;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t bytes) {
+    // raw dword buffer: stride 0, num_records in bytes, 32-bit data format word for gfx9
+    return __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, 0x00020000);
+}
+
+__device__ __forceinline__ OutView make_out_view(const BranchArgs &g, int r0, int r1, int nload, float sc) {
+    OutView v;
+    const int64_t first = (int64_t)r0 * g.N;
+    const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;    // < 2^31, checked on the host
+    v.flags = (g.acc != nullptr ? 1u : 0u) | (g.out != nullptr ? 2u : 0u);
+    v.d0 = make_rsrc((void *)(g.partial + first), bytes);               // partial == acc if present, else out
+    v.d1 = make_rsrc((v.flags & 2u) ? (void *)(g.out + first) : (void *)(g.partial + first), bytes);
+    v.row_bytes = (uint32_t)g.N * 4u;
+    v.col_bytes = nload * 4;
+    v.sc = sc;
+    return v;
+}
+
+// Finish one row of one chunk pass for this lane's column.  rel_row = row - r0.  SINGLE: the
+// product has a single chunk pass (first and last are both true at compile time).
+template <bool SINGLE>
+__device__ __forceinline__ void finish_row(const OutView &v, int rel_row, int val, bool first, bool last) {
+    const int soff = (int)((uint32_t)rel_row * v.row_bytes);
+    if constexpr (!SINGLE) {
+        if (!first) val += __builtin_amdgcn_raw_buffer_load_b32(v.d0, v.col_bytes, soff, 0);
+        if (!last) {
+            __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
+            return;
+        }
+    }
+    const float y = (float)val * v.sc;
+    if (v.flags & 1u) {
+        __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
+        if (v.flags & 2u) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d1, v.col_bytes, soff, 0);
     } else {
-        if (g.acc) (g.acc + base)[n] = val;
-        if (g.out) (g.out + base)[n] = (float)val * sc;
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
     }
 }
 
@@ -77,14 +188,98 @@ __device__ __forceinline__ int wave_index() {
     return __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)));
 }
 
+// Two-buffer software pipeline: stages ST .. NS-1 of one row.  Stage s is consumed from
+// buffer (s + FLIP) & 1 while stage s+1 (or stage 0 of the next row) is in flight into the
+// other buffer.  On entry stage ST has been requested; on exit stage 0 of the next row has.
+template <int ST, bool FLIP, class Ctx>
+__device__ __forceinline__ void run_stages(Ctx &c) {
+    if constexpr (ST < Ctx::NS) {
+        constexpr bool cur_is_a = (((ST & 1) == 0) != FLIP);
+        auto &cur = cur_is_a ? c.bufA : c.bufB;
+        auto &nxt = cur_is_a ? c.bufB : c.bufA;
+        cur.template arrive<true>();
+        if constexpr (ST + 1 < Ctx::NS) c.template request<ST + 1>(nxt, false);
+        else c.template request<0>(nxt, true);
+        c.template consume<ST>(cur);
+        run_stages<ST + 1, FLIP>(c);
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // GEMM: acc[i][n] = sum_{p,q} 2^(p+q) (K - 2 popc(A[i][p] ^ Wt[n][q]))
-// Chunk = SEGS segments of CWT words.  GUARD = the chunk may run past Kw (tail chunk).
+// Chunk = SEGS segments (pipeline stages) of CWT words of every plane.
 // ---------------------------------------------------------------------------------------
-template <int AB, int WB, int SEGS, int CWT, bool GUARD>
-__device__ __forceinline__ void gemm_chunk(const BranchArgs &g, uniform_words As, int n, int nload,
-                                           bool n_ok, int r0, int r1, int k0, bool first,
-                                           bool last, float sc) {
+template <int AB, int WB, int SEGS, int CWT>
+struct GemmCtx {
+    static constexpr int NS = SEGS;
+    typedef SStage<AB, CWT> Buf;     // run p = plane p, CWT consecutive K words
+    uint64_t base;                   // byte address of A
+    uint32_t plane_bytes;            // Kw * 4
+    uint32_t off_cur, off_nxt;       // byte offset of (row, plane 0, word k0) for this / next row
+    uint32_t w[SEGS][WB][CWT];
+    int part[AB + WB - 1];
+    Buf bufA, bufB;
+
+    template <int ST>
+    __device__ __forceinline__ void request(Buf &b, bool next_row) {
+        const uint32_t off = (next_row ? off_nxt : off_cur);
+#pragma unroll
+        for (int p = 0; p < AB; ++p) b.run[p].template request<ST * CWT * 4>(base, off + (uint32_t)p * plane_bytes);
+    }
+    template <int ST>
+    __device__ __forceinline__ void consume(const Buf &b) {
+#pragma unroll
+        for (int q = 0; q < WB; ++q)
+#pragma unroll
+            for (int p = 0; p < AB; ++p)
+#pragma unroll
+                for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], b.run[p].get(j) ^ w[ST][q][j]);
+    }
+};
+
+// full chunk (all KC words inside Kw): pipelined
+template <int AB, int WB, int SEGS, int CWT>
+__device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, const OutView &ov, int nload, int r0,
+                                                int r1, int k0, bool first, bool last) {
+    GemmCtx<AB, WB, SEGS, CWT> c;
+    const int Kw = g.Cw;
+    c.base = (uint64_t)g.A;
+    c.plane_bytes = (uint32_t)Kw * 4u;
+#pragma unroll
+    for (int t = 0; t < SEGS; ++t)
+#pragma unroll
+        for (int q = 0; q < WB; ++q)
+#pragma unroll
+            for (int j = 0; j < CWT; ++j) c.w[t][q][j] = g.Wt[(nload * WB + q) * Kw + k0 + t * CWT + j];
+    const uint32_t row_bytes = (uint32_t)AB * c.plane_bytes;
+    c.off_cur = (uint32_t)r0 * row_bytes + (uint32_t)k0 * 4u;
+    c.off_nxt = c.off_cur;
+    c.template request<0>(c.bufA, false);
+    int r = r0;
+    auto one_row = [&](auto flip_tag) {
+        constexpr bool FLIP = decltype(flip_tag)::value;
+#pragma unroll
+        for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
+        c.off_nxt = (r + 1 < r1) ? c.off_cur + row_bytes : c.off_cur;   // last row prefetches itself
+        run_stages<0, FLIP>(c);
+        int val = -2 * weighted_sum(c.part);
+        if (first) val += g.kconst;
+        finish_row<false>(ov, r - r0, val, first, last);
+        c.off_cur = c.off_nxt;
+        ++r;
+    };
+    static_assert((SEGS & 1) == 0, "even stage count: stage 0 of every row uses the same buffer");
+    while (r < r1) one_row(std::integral_constant<bool, false>());
+    // Drain the prefetch issued by the last row.  Both buffers are named so that their
+    // registers stay reserved until the wait, whichever of them the prefetch went to.
+    c.bufA.template arrive<true>();
+    c.bufB.template arrive<false>();
+}
+
+// tail chunk (runs past Kw): plain loads with a guard per word
+template <int AB, int WB, int SEGS, int CWT>
+__device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, const OutView &ov, uniform_words As,
+                                                int nload, int r0, int r1, int k0, bool first, bool last) {
     const int Kw = g.Cw;
     uint32_t w[SEGS][WB][CWT];
 #pragma unroll
@@ -94,8 +289,7 @@ __device__ __forceinline__ void gemm_chunk(const BranchArgs &g, uniform_words As
 #pragma unroll
             for (int j = 0; j < CWT; ++j) {
                 const int k = k0 + t * CWT + j;
-                if (!GUARD || k < Kw) w[t][q][j] = g.Wt[(nload * WB + q) * Kw + k];
-                else w[t][q][j] = 0u;
+                w[t][q][j] = (k < Kw) ? g.Wt[(nload * WB + q) * Kw + k] : 0u;
             }
     for (int r = r0; r < r1; ++r) {
         int part[AB + WB - 1];
@@ -103,20 +297,26 @@ __device__ __forceinline__ void gemm_chunk(const BranchArgs &g, uniform_words As
         for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
 #pragma unroll
         for (int t = 0; t < SEGS; ++t) {
-            uint32_t a[AB][CWT];
+            if (k0 + t * CWT < Kw) {             // uniform: skip segments that are all padding
+                uint32_t a[AB][CWT];
 #pragma unroll
-            for (int p = 0; p < AB; ++p)
+                for (int p = 0; p < AB; ++p)
 #pragma unroll
-                for (int j = 0; j < CWT; ++j) {
-                    const int k = k0 + t * CWT + j;
-                    if (!GUARD || k < Kw) a[p][j] = As[(r * AB + p) * Kw + k];
-                    else a[p][j] = 0u;
-                }
-            seg_accum<AB, WB, CWT>(a, w[t], part);
+                    for (int j = 0; j < CWT; ++j) {
+                        const int k = k0 + t * CWT + j;
+                        a[p][j] = (k < Kw) ? As[(r * AB + p) * Kw + k] : 0u;
+                    }
+#pragma unroll
+                for (int q = 0; q < WB; ++q)
+#pragma unroll
+                    for (int p = 0; p < AB; ++p)
+#pragma unroll
+                        for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], a[p][j] ^ w[t][q][j]);
+            }
         }
         int val = -2 * weighted_sum(part);
         if (first) val += g.kconst;
-        finish_row(g, r, n, n_ok, val, first, last, sc);
+        finish_row<false>(ov, r - r0, val, first, last);
     }
 }
 
@@ -132,33 +332,247 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     const bool n_ok = n < g.N;
     const int nload = n_ok ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
+    const OutView ov = make_out_view(g, r0, r1, nload, sc);
     uniform_words As = as_uniform(g.A);
     constexpr int KC = SEGS * CWT;
     const int Kw = g.Cw;
     if (Kw == 0) {  // K == 0: every product is the empty sum
-        for (int r = r0; r < r1; ++r) finish_row(g, r, n, n_ok, 0, true, true, sc);
+        for (int r = r0; r < r1; ++r) finish_row<true>(ov, r - r0, 0, true, true);
         return;
     }
     for (int k0 = 0; k0 < Kw; k0 += KC) {
         const bool first = (k0 == 0);
         const bool last = (k0 + KC >= Kw);
-        if (k0 + KC <= Kw)
-            gemm_chunk<AB, WB, SEGS, CWT, false>(g, As, n, nload, n_ok, r0, r1, k0, first, last, sc);
-        else
-            gemm_chunk<AB, WB, SEGS, CWT, true>(g, As, n, nload, n_ok, r0, r1, k0, first, last, sc);
+        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, ov, nload, r0, r1, k0, first, last);
+        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, ov, As, nload, r0, r1, k0, first, last);
     }
 }
 
 // ---------------------------------------------------------------------------------------
 // 3x3 convolution, stride 1, pad 1.  Rows are output pixels in NHWC order; the K axis of a
-// pixel is the nine neighbouring pixels' plane words, never materialised.  A chunk is a block
-// of CWT channel words of all nine taps.  Taps outside the image are skipped (the pixel is
-// wave-uniform, so this is a scalar branch) and the constant term uses the count of valid taps.
+// pixel is the nine neighbouring pixels' plane words, never materialised.  Taps outside the
+// image contribute nothing: they are skipped, and the constant term of a pixel uses its
+// number of valid taps.
+//
+// Template shape:  CWS  words per (pixel, plane) if known at compile time, else 0;
+//                  CWT  channel words per chunk;  TPC  taps per chunk (9, 3 or 1);
+//                  GT   taps per pipeline stage (divides TPC, TPC/GT odd; GT == 3 only when
+//                       CWT == CWS, so that the three taps of a kernel row are contiguous).
+// A chunk = TPC taps x CWT channel words; its weight words (TPC*WB*CWT) stay in VGPRs.
 // ---------------------------------------------------------------------------------------
-template <int AB, int WB, int CWT, bool GUARD>
-__device__ __forceinline__ void conv_chunk(const BranchArgs &g, uniform_words As, int n, int nload,
-                                           bool n_ok, int r0, int r1, int c0, bool first,
-                                           bool last, float sc) {
+struct PixelPos {
+    int oh, ow;
+};
+
+__device__ __forceinline__ int tap_dh(int t) { return t / 3 - 1; }
+__device__ __forceinline__ int tap_dw(int t) { return t % 3 - 1; }
+
+// State of one chunk pass over a run of output pixels that lie in ONE image row and are not
+// in its first or last column.  For such a run the validity of a tap depends on its kernel
+// row only and is constant, and every +-1 column step stays inside the image row, so the
+// inner loop needs neither position tracking nor per-tap tests:
+//   stage_off[s]  byte offset of the first tap of stage s relative to the output pixel's own
+//                 words; a tap whose image row does not exist points at the pixel's own row
+//                 (in bounds) and is skipped when consumed;
+//   stage_ok[s]   whether the kernel row of stage s exists.
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+struct ConvCtx {
+    static constexpr int NS = TPC / GT;
+    static constexpr bool CONTIG = (CWS > 0 && CWT == CWS);   // a pixel's AB*CWT words are consecutive
+    // CONTIG: one run of GT*AB*CWT words (consecutive pixels are consecutive too);
+    // otherwise one run of CWT words per (tap, plane).
+    typedef typename std::conditional<CONTIG, SStage<1, GT * AB * CWT>, SStage<GT * AB, CWT>>::type Buf;
+    uint64_t base;                   // byte address of the activation planes
+    int Cw, c0, t0;                  // runtime words per plane, chunk's first channel word / tap
+    uint32_t off_cur, off_nxt;       // byte offset of (pixel, plane 0, word c0) for this / the next pixel
+    uint32_t stage_off[NS];
+    uint32_t stage_ok;               // bit s: the kernel row of stage s exists
+    uint32_t w[TPC][WB][CWT];
+    int part[AB + WB - 1];
+    Buf bufA, bufB;
+
+    __device__ __forceinline__ int plane_stride() const { return CWS > 0 ? CWS : Cw; }
+    __device__ __forceinline__ uint32_t pixel_bytes() const { return (uint32_t)(AB * plane_stride() * 4); }
+
+    __device__ __forceinline__ void set_image_row(int oh, int H, int W) {
+        stage_ok = 0u;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            const int dh = (TPC == 9) ? (st * GT) / 3 - 1 : tap_dh(t0 + st * GT);
+            const int dw = (TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1;
+            const bool ok = (unsigned)(oh + dh) < (unsigned)H;
+            if (ok) stage_ok |= 1u << st;
+            stage_off[st] = (uint32_t)((ok ? dh * W : 0) + dw) * pixel_bytes();
+        }
+    }
+
+    template <int ST>
+    __device__ __forceinline__ void request(Buf &b, bool next_row) {
+        const uint32_t off = (next_row ? off_nxt : off_cur) + stage_off[ST];
+        if constexpr (CONTIG) {
+            b.run[0].template request<0>(base, off);
+        } else {
+            const uint32_t psb = (uint32_t)plane_stride() * 4u;
+#pragma unroll
+            for (int i = 0; i < GT * AB; ++i) b.run[i].template request<0>(base, off + (uint32_t)i * psb);
+        }
+    }
+    __device__ __forceinline__ uint32_t word(const Buf &b, int i, int p, int j) const {
+        if constexpr (CONTIG) return b.run[0].get((i * AB + p) * CWT + j);
+        else return b.run[i * AB + p].get(j);
+    }
+    template <int ST>
+    __device__ __forceinline__ void consume(const Buf &b) {
+        if (stage_ok & (1u << ST)) {
+#pragma unroll
+            for (int i = 0; i < GT; ++i)
+#pragma unroll
+                for (int q = 0; q < WB; ++q)
+#pragma unroll
+                    for (int p = 0; p < AB; ++p)
+#pragma unroll
+                        for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], word(b, i, p, j) ^ w[ST * GT + i][q][j]);
+        }
+    }
+};
+
+__device__ __forceinline__ PixelPos next_pixel(PixelPos p, int H, int W) {
+    if (++p.ow == W) {
+        p.ow = 0;
+        if (++p.oh == H) p.oh = 0;
+    }
+    return p;
+}
+
+__device__ __forceinline__ PixelPos pixel_pos(int r, int H, int W) {
+    // integer division runs on the vector ALU; bring the (wave-uniform) results back to SGPRs
+    PixelPos p;
+    p.ow = __builtin_amdgcn_readfirstlane(r % W);
+    p.oh = __builtin_amdgcn_readfirstlane((r / W) % H);
+    return p;
+}
+
+// number of taps of the 3x3 window that fall inside the image
+__device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
+    const int nh = 3 - (p.oh == 0 ? 1 : 0) - (p.oh == H - 1 ? 1 : 0);
+    const int nw = 3 - (p.ow == 0 ? 1 : 0) - (p.ow == W - 1 ? 1 : 0);
+    return nh * nw;
+}
+
+// Pipelined pixels ra .. rb-1 of one chunk: all in image row oh, none in column 0 or W-1.
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+__device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT> &c,
+                                                   const BranchArgs &g, const OutView &ov, int r0, int ra,
+                                                   int rb, int oh, bool first, bool last) {
+    c.set_image_row(oh, g.H, g.W);
+    const int kadd = (3 - (oh == 0 ? 1 : 0) - (oh == g.H - 1 ? 1 : 0)) * 3 * g.kconst;
+    const uint32_t pb = c.pixel_bytes();
+    c.off_cur = (uint32_t)ra * pb + (uint32_t)c.c0 * 4u;
+    c.off_nxt = c.off_cur;
+    c.template request<0>(c.bufA, false);
+    int r = ra;
+    auto one_row = [&](auto flip_tag) {
+        constexpr bool FLIP = decltype(flip_tag)::value;
+#pragma unroll
+        for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
+        c.off_nxt = (r + 1 < rb) ? c.off_cur + pb : c.off_cur;   // last pixel prefetches itself (unused)
+        run_stages<0, FLIP>(c);
+        int val = -2 * weighted_sum(c.part);
+        if (first) val += kadd;
+        finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
+        c.off_cur = c.off_nxt;
+        ++r;
+    };
+    // pixels in pairs (the two buffers swap roles from one pixel to the next), then a last one
+    while (r + 1 < rb) {
+        one_row(std::integral_constant<bool, false>());
+        one_row(std::integral_constant<bool, true>());
+    }
+    if (r < rb) one_row(std::integral_constant<bool, false>());
+    // Drain the prefetch issued by the last pixel.  Both buffers are named so that their
+    // registers stay reserved until the wait, whichever of them the prefetch went to.
+    c.bufA.template arrive<true>();
+    c.bufB.template arrive<false>();
+}
+
+// One pixel of one chunk with every tap tested (first / last image column).
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+__device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT> &c, uniform_words As,
+                                                 const BranchArgs &g, const OutView &ov, int r0, int r,
+                                                 PixelPos pos, bool first, bool last) {
+#pragma unroll
+    for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
+#pragma unroll
+    for (int t = 0; t < TPC; ++t) {
+        const int dh = (TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t);
+        const int dw = (TPC == 1) ? tap_dw(c.t0) : t % 3 - 1;
+        const bool ok = (unsigned)(pos.oh + dh) < (unsigned)g.H && (unsigned)(pos.ow + dw) < (unsigned)g.W;
+        if (ok) {
+            const int pix = r + dh * g.W + dw;
+            uint32_t a[AB][CWT];
+#pragma unroll
+            for (int p = 0; p < AB; ++p)
+#pragma unroll
+                for (int j = 0; j < CWT; ++j) a[p][j] = As[(pix * AB + p) * c.plane_stride() + c.c0 + j];
+#pragma unroll
+            for (int q = 0; q < WB; ++q)
+#pragma unroll
+                for (int p = 0; p < AB; ++p)
+#pragma unroll
+                    for (int j = 0; j < CWT; ++j) popc_acc(c.part[p + q], a[p][j] ^ c.w[t][q][j]);
+        }
+    }
+    int val = -2 * weighted_sum(c.part);
+    if (first) val += valid_taps(pos, g.H, g.W) * g.kconst;
+    finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
+}
+
+// full chunk: every word c0 .. c0+CWT-1 exists.  The wavefront's pixel range is cut into
+// runs inside one image row; the first and last column go through the tested path.
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+__device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutView &ov, uniform_words As,
+                                                int nload, int r0, int r1, int c0, int t0, bool first,
+                                                bool last) {
+    static_assert(TPC % GT == 0 && ((TPC / GT) & 1) == 1, "odd number of stages per pixel");
+    ConvCtx<AB, WB, CWS, CWT, TPC, GT> c;
+    c.base = (uint64_t)g.A; c.Cw = g.Cw; c.c0 = c0; c.t0 = t0;
+    const int ps = c.plane_stride();
+#pragma unroll
+    for (int t = 0; t < TPC; ++t)
+#pragma unroll
+        for (int q = 0; q < WB; ++q)
+#pragma unroll
+            for (int j = 0; j < CWT; ++j) c.w[t][q][j] = g.Wt[((nload * 9 + t0 + t) * WB + q) * ps + c0 + j];
+    PixelPos pos = pixel_pos(r0, g.H, g.W);
+    int r = r0;
+    while (r < r1) {
+        const int row_end = r - pos.ow + g.W;            // first pixel of the next image row
+        const int e = min(r1, row_end);
+        if (pos.ow == 0) {
+            conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
+            ++r; ++pos.ow;
+        }
+        const int fe = min(e, row_end - 1);              // the last column is not in a fast run
+        if (r < fe) {
+            conv_run_pipelined(c, g, ov, r0, r, fe, pos.oh, first, last);
+            pos.ow += fe - r;
+            r = fe;
+        }
+        if (r < e) {                                     // r is the last column of the row
+            conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
+            ++r; ++pos.ow;
+        }
+        if (pos.ow == g.W) {
+            pos.ow = 0;
+            if (++pos.oh == g.H) pos.oh = 0;
+        }
+    }
+}
+
+// tail chunk (channel words past Cw are padding): plain loads with a guard per word
+template <int AB, int WB, int CWT>
+__device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OutView &ov, uniform_words As,
+                                                int nload, int r0, int r1, int c0, bool first, bool last) {
     const int Cw = g.Cw;
     uint32_t w[9][WB][CWT];
 #pragma unroll
@@ -166,55 +580,41 @@ __device__ __forceinline__ void conv_chunk(const BranchArgs &g, uniform_words As
 #pragma unroll
         for (int q = 0; q < WB; ++q)
 #pragma unroll
-            for (int j = 0; j < CWT; ++j) {
-                if (!GUARD || c0 + j < Cw) w[t][q][j] = g.Wt[((nload * 9 + t) * WB + q) * Cw + c0 + j];
-                else w[t][q][j] = 0u;
-            }
-    // position of the first pixel inside its image
-    int ow = r0 % g.W;
-    int oh = (r0 / g.W) % g.H;
+            for (int j = 0; j < CWT; ++j)
+                w[t][q][j] = (c0 + j < Cw) ? g.Wt[((nload * 9 + t) * WB + q) * Cw + c0 + j] : 0u;
+    PixelPos pos = pixel_pos(r0, g.H, g.W);
     for (int r = r0; r < r1; ++r) {
         int part[AB + WB - 1];
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
-        int nvalid = 0;
 #pragma unroll
-        for (int kh = 0; kh < 3; ++kh) {
-            const bool row_ok = (kh == 0) ? (oh > 0) : (kh == 2) ? (oh < g.H - 1) : true;
-            uint32_t a[3][AB][CWT];
-            bool ok[3];
-#pragma unroll
-            for (int kw = 0; kw < 3; ++kw) {
-                const bool col_ok = (kw == 0) ? (ow > 0) : (kw == 2) ? (ow < g.W - 1) : true;
-                ok[kw] = row_ok && col_ok;
-                // an invalid tap reads the centre pixel instead (always in bounds) and is skipped
-                const int pix = ok[kw] ? r + (kh - 1) * g.W + (kw - 1) : r;
+        for (int t = 0; t < 9; ++t) {
+            const int dh = t / 3 - 1, dw = t % 3 - 1;
+            const bool ok = (unsigned)(pos.oh + dh) < (unsigned)g.H && (unsigned)(pos.ow + dw) < (unsigned)g.W;
+            if (ok) {
+                const int pix = r + dh * g.W + dw;
+                uint32_t a[AB][CWT];
 #pragma unroll
                 for (int p = 0; p < AB; ++p)
 #pragma unroll
-                    for (int j = 0; j < CWT; ++j) {
-                        if (!GUARD || c0 + j < Cw) a[kw][p][j] = As[(pix * AB + p) * Cw + c0 + j];
-                        else a[kw][p][j] = 0u;
-                    }
-            }
+                    for (int j = 0; j < CWT; ++j)
+                        a[p][j] = (c0 + j < Cw) ? As[(pix * AB + p) * Cw + c0 + j] : 0u;
 #pragma unroll
-            for (int kw = 0; kw < 3; ++kw)
-                if (ok[kw]) {
-                    seg_accum<AB, WB, CWT>(a[kw], w[kh * 3 + kw], part);
-                    ++nvalid;
-                }
+                for (int q = 0; q < WB; ++q)
+#pragma unroll
+                    for (int p = 0; p < AB; ++p)
+#pragma unroll
+                        for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], a[p][j] ^ w[t][q][j]);
+            }
         }
         int val = -2 * weighted_sum(part);
-        if (first) val += nvalid * g.kconst;
-        finish_row(g, r, n, n_ok, val, first, last, sc);
-        if (++ow == g.W) {
-            ow = 0;
-            if (++oh == g.H) oh = 0;
-        }
+        if (first) val += valid_taps(pos, g.H, g.W) * g.kconst;
+        finish_row<false>(ov, r - r0, val, first, last);
+        pos = next_pixel(pos, g.H, g.W);
     }
 }
 
-template <int AB, int WB, int CWT>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     const int wave = wave_index();
     const int ct = wave % g.col_tiles;
@@ -226,29 +626,54 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     const bool n_ok = n < g.N;
     const int nload = n_ok ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
+    const OutView ov = make_out_view(g, r0, r1, nload, sc);
     uniform_words As = as_uniform(g.A);
-    const int Cw = g.Cw;
+    const int Cw = (CWS > 0) ? CWS : g.Cw;
     if (Cw == 0) {  // no input channels: every product is the empty sum
-        for (int r = r0; r < r1; ++r) finish_row(g, r, n, n_ok, 0, true, true, sc);
+        for (int r = r0; r < r1; ++r) finish_row<true>(ov, r - r0, 0, true, true);
         return;
     }
+    constexpr int TAP_CHUNKS = 9 / TPC;
+    // Very wide activations leave too few SGPRs for the two hand-managed stage buffers next to
+    // the runtime-stride address arithmetic; those (rare) shapes use compiler-managed loads.
+    constexpr bool PIPELINED = (CWS > 0) || (AB <= 4);
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
-        const bool first = (c0 == 0);
-        const bool last = (c0 + CWT >= Cw);
-        if (CWT == 1 || c0 + CWT <= Cw)
-            conv_chunk<AB, WB, CWT, false>(g, As, n, nload, n_ok, r0, r1, c0, first, last, sc);
-        else
-            conv_chunk<AB, WB, CWT, true>(g, As, n, nload, n_ok, r0, r1, c0, first, last, sc);
+        const bool full = (c0 + CWT <= Cw);
+        if constexpr (!PIPELINED) {
+            conv_chunk_tail<AB, WB, CWT>(g, ov, As, nload, r0, r1, c0, c0 == 0, c0 + CWT >= Cw);
+        } else if (full) {
+            for (int tc = 0; tc < TAP_CHUNKS; ++tc) {
+                const bool first = (c0 == 0) && (tc == 0);
+                const bool last = (c0 + CWT >= Cw) && (tc == TAP_CHUNKS - 1);
+                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT>(g, ov, As, nload, r0, r1, c0, tc * TPC, first, last);
+            }
+        } else if constexpr (CWS == 0 && CWT > 1) {
+            conv_chunk_tail<AB, WB, CWT>(g, ov, As, nload, r0, r1, c0, c0 == 0, true);
+        }
     }
 }
 
-// Chunk shapes.  GEMM: the activation words of one segment (AB*CWT) must fit comfortably in
-// SGPRs, the weight words of one chunk (WB*KC) in VGPRs.
-template <int AB> struct GemmShape {
-    static constexpr int CWT = (AB <= 2) ? 8 : (AB <= 4) ? 4 : 2;
-};
-template <int WB> struct GemmChunk {
+// ---------------------------------------------------------------------------------------
+// Chunk shapes.
+// ---------------------------------------------------------------------------------------
+constexpr int pow2_floor(int x) { return x >= 16 ? 16 : x >= 8 ? 8 : x >= 4 ? 4 : x >= 2 ? 2 : 1; }
+constexpr int imin(int a, int b) { return a < b ? a : b; }
+
+// GEMM: one stage holds AB*CWT activation words in SGPRs (<= 16, twice for the two buffers);
+// one chunk holds WB*KC weight words in VGPRs.
+template <int AB, int WB> struct GemmShape {
     static constexpr int KC = (WB <= 2) ? 32 : (WB <= 4) ? 16 : 8;
+    static constexpr int CWT = imin(pow2_floor(16 / AB), KC / 2);   // at least two stages per row
+    static constexpr int SEGS = KC / CWT;
+};
+
+// Convolution with a compile-time plane stride CWS (a power of two up to 16):
+//   chunk channel words CWT (stage SGPRs GT*AB*CWT <= 24), taps per chunk TPC (weight VGPRs
+//   TPC*WB*CWT <= 108), taps per stage GT.
+template <int AB, int WB, int CWS> struct ConvShape {
+    static constexpr int CWT = imin(CWS, pow2_floor(16 / AB));
+    static constexpr int TPC = (9 * WB * CWT <= 108) ? 9 : (3 * WB * CWT <= 108) ? 3 : 1;
+    static constexpr int GT = (TPC >= 3 && CWT == CWS && 3 * AB * CWT <= 24) ? 3 : 1;
 };
 
 inline dim3 grid_for(const BranchArgs &g) {
@@ -259,18 +684,37 @@ inline dim3 grid_for(const BranchArgs &g) {
 
 template <int AB, int WB>
 hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
-    constexpr int CWT = GemmShape<AB>::CWT;
-    constexpr int SEGS = GemmChunk<WB>::KC / CWT;
-    hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT>), grid_for(g), dim3(256), 0, s, g);
+    using S = GemmShape<AB, WB>;
+    hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT>), grid_for(g), dim3(256), 0, s, g);
+    return hipGetLastError();
+}
+
+template <int AB, int WB, int CWS>
+hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
+    using S = ConvShape<AB, WB, CWS>;
+    hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT>), grid_for(g), dim3(256), 0, s, g);
     return hipGetLastError();
 }
 
 template <int AB, int WB>
 hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
-    if (g.Cw == 1)
-        hipLaunchKernelGGL((conv_kernel<AB, WB, 1>), grid_for(g), dim3(256), 0, s, g);
-    else
-        hipLaunchKernelGGL((conv_kernel<AB, WB, 2>), grid_for(g), dim3(256), 0, s, g);
+    // plane strides with a dedicated instantiation (bit widths up to 4 only, to bound build time)
+    if constexpr (AB <= 4 && WB <= 4) {
+        switch (g.Cw) {
+            case 1: return launch_conv_fixed<AB, WB, 1>(g, s);
+            case 2: return launch_conv_fixed<AB, WB, 2>(g, s);
+            case 4: return launch_conv_fixed<AB, WB, 4>(g, s);
+            case 8: return launch_conv_fixed<AB, WB, 8>(g, s);
+            case 16: return launch_conv_fixed<AB, WB, 16>(g, s);
+            default: break;
+        }
+    }
+    // any other channel count: runtime stride, chunks of two channel words while the two stage
+    // buffers (2 * AB * CWT SGPRs) leave the allocator room, else one word
+    if (g.Cw == 1 || AB > 4)
+        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1>), grid_for(g), dim3(256), 0, s, g);
+    else if constexpr (AB <= 4)
+        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1>), grid_for(g), dim3(256), 0, s, g);
     return hipGetLastError();
 }
 
