@@ -133,7 +133,7 @@ def check_file(path):
             continue
         if cur is not None:
             cur.append((i, l))
-            if "s_endpgm" in l:
+            if l.startswith(".Lfunc_end"):
                 p, sp = check_kernel(name, cur)
                 problems += p
                 nspill += sp

@@ -61,6 +61,36 @@ int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows) {
     return (int)rpw;
 }
 
+// Convolution: prefer a split that lines up with image rows (a divisor or a multiple of the
+// image width), so that a wavefront's pixels form few runs inside one image row, and that
+// loads every SIMD equally.  Cost model: all wavefronts resident at once, so the time is the
+// rows of the busiest SIMD, ceil(wavefronts / SIMDs) * rows_per_wave, with a small penalty for
+// a split that straddles image rows.
+int pick_conv_rows_per_wave(int64_t rows, int64_t W, int col_tiles) {
+    const Tuning &t = tuning();
+    if (t.rows_per_wave > 0) return t.rows_per_wave;
+    const int64_t simds = device_simd_count();
+    const int wps = t.waves_per_simd > 0 ? t.waves_per_simd : 8;      // most wavefronts per SIMD we aim for
+    int64_t best = 0;
+    double best_cost = 0.0;
+    auto consider = [&](int64_t rpw, bool aligned) {
+        if (rpw < 1 || rpw > rows) return;
+        const int64_t waves = ((rows + rpw - 1) / rpw) * col_tiles;
+        const int64_t per_simd = (waves + simds - 1) / simds;
+        if (per_simd > wps) return;
+        double cost = (double)per_simd * (double)rpw * (aligned ? 1.0 : 1.08);
+        cost += 0.5 * (double)per_simd;                                // fixed work per wavefront (weight loads)
+        if (per_simd < 4) cost *= 1.0 + 0.1 * (double)(4 - per_simd);  // too few wavefronts to hide latencies
+        if (best == 0 || cost < best_cost) { best = rpw; best_cost = cost; }
+    };
+    for (int64_t d = 1; d <= W; ++d)
+        if (W % d == 0) consider(d, true);
+    for (int64_t k = 2; k <= 64; ++k) consider(k * W, true);
+    consider(pick_rows_per_wave(rows, col_tiles, 4), false);
+    if (best == 0) best = pick_rows_per_wave(rows, col_tiles, 4);
+    return (int)best;
+}
+
 // One wavefront's output slice (rows_per_wave * N * 4 bytes) must stay below 2^31 bytes.
 int clamp_rows_per_wave(int rpw, int64_t N) {
     const int64_t cap = (((int64_t)1 << 29) - 1) / (N > 0 ? N : 1);
@@ -177,7 +207,7 @@ qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *W
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 4), Cout);
+    g.rows_per_wave = clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles), Cout);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
 }
 

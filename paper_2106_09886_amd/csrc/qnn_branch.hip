@@ -184,8 +184,29 @@ __device__ __forceinline__ void finish_row(const OutView &v, int rel_row, int va
     }
 }
 
-__device__ __forceinline__ int wave_index() {
-    return __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)));
+
+// Position of a wavefront: the four wavefronts of a block share one tile of 64 columns and
+// take consecutive row blocks.
+struct WavePos {
+    int ct;        // column tile
+    int rb;        // row block
+};
+__device__ __forceinline__ WavePos wave_pos(int col_tiles) {
+    WavePos p;
+    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    p.ct = (int)(blockIdx.x % (unsigned)col_tiles);
+    p.rb = (int)(blockIdx.x / (unsigned)col_tiles) * 4 + wib;
+    return p;
+}
+
+// Weight words of one chunk for this lane's column: NW words, word_index(k) = position in Wt.
+// (Fetching the block's tile once through LDS instead was measured and is not faster: these
+// loads happen once per chunk and wavefront and hit in L2.)
+template <int NW, class IndexFn>
+__device__ __forceinline__ void load_weight_words(const uint32_t *__restrict__ Wt, IndexFn word_index,
+                                                  uint32_t (&w)[NW]) {
+#pragma unroll
+    for (int k = 0; k < NW; ++k) w[k] = Wt[word_index(k)];
 }
 
 // Two-buffer software pipeline: stages ST .. NS-1 of one row.  Stage s is consumed from
@@ -245,12 +266,17 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, const OutVi
     const int Kw = g.Cw;
     c.base = (uint64_t)g.A;
     c.plane_bytes = (uint32_t)Kw * 4u;
+    {
+        constexpr int KC = SEGS * CWT, NW = WB * KC;
+        uint32_t wl[NW];                              // word k = q * KC + (t * CWT + j)
+        load_weight_words<NW>(g.Wt, [&](int k) { return (nload * WB + k / KC) * Kw + k0 + k % KC; }, wl);
 #pragma unroll
-    for (int t = 0; t < SEGS; ++t)
+        for (int t = 0; t < SEGS; ++t)
 #pragma unroll
-        for (int q = 0; q < WB; ++q)
+            for (int q = 0; q < WB; ++q)
 #pragma unroll
-            for (int j = 0; j < CWT; ++j) c.w[t][q][j] = g.Wt[(nload * WB + q) * Kw + k0 + t * CWT + j];
+                for (int j = 0; j < CWT; ++j) c.w[t][q][j] = wl[q * KC + t * CWT + j];
+    }
     const uint32_t row_bytes = (uint32_t)AB * c.plane_bytes;
     c.off_cur = (uint32_t)r0 * row_bytes + (uint32_t)k0 * 4u;
     c.off_nxt = c.off_cur;
@@ -322,13 +348,12 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, const OutVi
 
 template <int AB, int WB, int SEGS, int CWT>
 __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
-    const int wave = wave_index();
-    const int ct = wave % g.col_tiles;
-    const int rb = wave / g.col_tiles;
-    const int r0 = rb * g.rows_per_wave;
-    if (r0 >= g.rows) return;
-    const int r1 = min(g.rows, r0 + g.rows_per_wave);
-    const int n = ct * 64 + (int)(threadIdx.x & 63);
+    const WavePos wp = wave_pos(g.col_tiles);
+    // a wavefront past the last row block keeps an empty row range
+    const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
+    const int r0 = active ? wp.rb * g.rows_per_wave : 0;
+    const int r1 = active ? min(g.rows, r0 + g.rows_per_wave) : 0;
+    const int n = wp.ct * 64 + (int)(threadIdx.x & 63);
     const bool n_ok = n < g.N;
     const int nload = n_ok ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
@@ -367,14 +392,17 @@ struct PixelPos {
 __device__ __forceinline__ int tap_dh(int t) { return t / 3 - 1; }
 __device__ __forceinline__ int tap_dw(int t) { return t % 3 - 1; }
 
-// State of one chunk pass over a run of output pixels that lie in ONE image row and are not
-// in its first or last column.  For such a run the validity of a tap depends on its kernel
-// row only and is constant, and every +-1 column step stays inside the image row, so the
-// inner loop needs neither position tracking nor per-tap tests:
+// State of one chunk pass over a run of output pixels that lie in ONE image row.  For such a
+// run the validity of a kernel row is constant, and only the run's first / last pixel can sit
+// in the first / last image column, so the inner loop needs no position tracking:
 //   stage_off[s]  byte offset of the first tap of stage s relative to the output pixel's own
 //                 words; a tap whose image row does not exist points at the pixel's own row
 //                 (in bounds) and is skipped when consumed;
-//   stage_ok[s]   whether the kernel row of stage s exists.
+//   stage_ok      bit s: the kernel row of stage s exists;
+//   edge          bit 0: the current pixel is in column 0 (taps with dw = -1 are skipped),
+//                 bit 1: it is in column W-1 (taps with dw = +1 are skipped).
+// Addresses are not tested: a +-1 column step from a pixel of an existing row stays inside
+// [0, rows) except for the four pixels 0, W, rows-1-W and rows-1, which never come here.
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
 struct ConvCtx {
     static constexpr int NS = TPC / GT;
@@ -387,12 +415,19 @@ struct ConvCtx {
     uint32_t off_cur, off_nxt;       // byte offset of (pixel, plane 0, word c0) for this / the next pixel
     uint32_t stage_off[NS];
     uint32_t stage_ok;               // bit s: the kernel row of stage s exists
+    uint32_t edge;                   // bit 0: column 0, bit 1: column W-1 (current pixel)
     uint32_t w[TPC][WB][CWT];
     int part[AB + WB - 1];
     Buf bufA, bufB;
 
     __device__ __forceinline__ int plane_stride() const { return CWS > 0 ? CWS : Cw; }
     __device__ __forceinline__ uint32_t pixel_bytes() const { return (uint32_t)(AB * plane_stride() * 4); }
+
+    // column offset of tap i of stage ST (compile-time unless a chunk is a single tap)
+    template <int ST>
+    __device__ __forceinline__ int dw_of(int i) const {
+        return (TPC == 1) ? tap_dw(t0) : (ST * GT + i) % 3 - 1;
+    }
 
     __device__ __forceinline__ void set_image_row(int oh, int H, int W) {
         stage_ok = 0u;
@@ -425,13 +460,20 @@ struct ConvCtx {
     __device__ __forceinline__ void consume(const Buf &b) {
         if (stage_ok & (1u << ST)) {
 #pragma unroll
-            for (int i = 0; i < GT; ++i)
+            for (int i = 0; i < GT; ++i) {
+                const int dw = dw_of<ST>(i);
+                // skip the tap that hangs over the left / right image border
+                const bool skip = (dw < 0 && (edge & 1u)) || (dw > 0 && (edge & 2u));
+                if (!skip) {
 #pragma unroll
-                for (int q = 0; q < WB; ++q)
+                    for (int q = 0; q < WB; ++q)
 #pragma unroll
-                    for (int p = 0; p < AB; ++p)
+                        for (int p = 0; p < AB; ++p)
 #pragma unroll
-                        for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], word(b, i, p, j) ^ w[ST * GT + i][q][j]);
+                            for (int j = 0; j < CWT; ++j)
+                                popc_acc(part[p + q], word(b, i, p, j) ^ w[ST * GT + i][q][j]);
+                }
+            }
         }
     }
 };
@@ -459,14 +501,17 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
     return nh * nw;
 }
 
-// Pipelined pixels ra .. rb-1 of one chunk: all in image row oh, none in column 0 or W-1.
+// Pipelined pixels ra .. rb-1 of one chunk, all in image row oh.  left_first: pixel ra is in
+// column 0; right_last: pixel rb-1 is in column W-1.
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT> &c,
                                                    const BranchArgs &g, const OutView &ov, int r0, int ra,
-                                                   int rb, int oh, bool first, bool last) {
+                                                   int rb, int oh, bool left_first, bool right_last,
+                                                   bool first, bool last) {
     c.set_image_row(oh, g.H, g.W);
-    const int kadd = (3 - (oh == 0 ? 1 : 0) - (oh == g.H - 1 ? 1 : 0)) * 3 * g.kconst;
+    const int krow = (3 - (oh == 0 ? 1 : 0) - (oh == g.H - 1 ? 1 : 0)) * g.kconst;   // per valid column
     const uint32_t pb = c.pixel_bytes();
+    const uint32_t edge_first = left_first ? 1u : 0u, edge_last = right_last ? 2u : 0u;
     c.off_cur = (uint32_t)ra * pb + (uint32_t)c.c0 * 4u;
     c.off_nxt = c.off_cur;
     c.template request<0>(c.bufA, false);
@@ -476,9 +521,14 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
         c.off_nxt = (r + 1 < rb) ? c.off_cur + pb : c.off_cur;   // last pixel prefetches itself (unused)
+        // integer selects only: keeps the edge bookkeeping on the scalar unit
+        uint32_t edge = 0u;
+        if (r == ra) edge |= edge_first;
+        if (r + 1 == rb) edge |= edge_last;
+        c.edge = edge;
         run_stages<0, FLIP>(c);
         int val = -2 * weighted_sum(c.part);
-        if (first) val += kadd;
+        if (first) val += (3 - (int)(edge & 1u) - (int)(edge >> 1)) * krow;
         finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
         c.off_cur = c.off_nxt;
         ++r;
@@ -495,7 +545,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
     c.bufB.template arrive<false>();
 }
 
-// One pixel of one chunk with every tap tested (first / last image column).
+// One pixel of one chunk with every tap and address tested (the four end pixels).
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
 __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT> &c, uniform_words As,
                                                  const BranchArgs &g, const OutView &ov, int r0, int r,
@@ -528,7 +578,8 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
 }
 
 // full chunk: every word c0 .. c0+CWT-1 exists.  The wavefront's pixel range is cut into
-// runs inside one image row; the first and last column go through the tested path.
+// runs inside one image row; the four pixels whose untested neighbour addresses could leave
+// the buffer (0, W, rows-1-W, rows-1) go through the tested path.
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
 __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutView &ov, uniform_words As,
                                                 int nload, int r0, int r1, int c0, int t0, bool first,
@@ -537,31 +588,38 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutVi
     ConvCtx<AB, WB, CWS, CWT, TPC, GT> c;
     c.base = (uint64_t)g.A; c.Cw = g.Cw; c.c0 = c0; c.t0 = t0;
     const int ps = c.plane_stride();
+    {
+        constexpr int NW = TPC * WB * CWT;            // word k = (t * WB + q) * CWT + j
+        uint32_t wl[NW];
+        load_weight_words<NW>(g.Wt, [&](int k) { return ((nload * 9 + t0) * WB + k / CWT) * ps + c0 + k % CWT; },
+                              wl);
 #pragma unroll
-    for (int t = 0; t < TPC; ++t)
+        for (int t = 0; t < TPC; ++t)
 #pragma unroll
-        for (int q = 0; q < WB; ++q)
+            for (int q = 0; q < WB; ++q)
 #pragma unroll
-            for (int j = 0; j < CWT; ++j) c.w[t][q][j] = g.Wt[((nload * 9 + t0 + t) * WB + q) * ps + c0 + j];
+                for (int j = 0; j < CWT; ++j) c.w[t][q][j] = wl[(t * WB + q) * CWT + j];
+    }
+    const int special[4] = {0, g.W, g.rows - 1 - g.W, g.rows - 1};
     PixelPos pos = pixel_pos(r0, g.H, g.W);
     int r = r0;
     while (r < r1) {
         const int row_end = r - pos.ow + g.W;            // first pixel of the next image row
-        const int e = min(r1, row_end);
-        if (pos.ow == 0) {
+        int stop = min(r1, row_end);
+        bool is_special = false;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (special[i] == r) is_special = true;
+            if (special[i] > r && special[i] < stop) stop = special[i];
+        }
+        if (is_special) {
             conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
-            ++r; ++pos.ow;
+            stop = r + 1;
+        } else {
+            conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, pos.ow == 0, stop == row_end, first, last);
         }
-        const int fe = min(e, row_end - 1);              // the last column is not in a fast run
-        if (r < fe) {
-            conv_run_pipelined(c, g, ov, r0, r, fe, pos.oh, first, last);
-            pos.ow += fe - r;
-            r = fe;
-        }
-        if (r < e) {                                     // r is the last column of the row
-            conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
-            ++r; ++pos.ow;
-        }
+        pos.ow += stop - r;
+        r = stop;
         if (pos.ow == g.W) {
             pos.ow = 0;
             if (++pos.oh == g.H) pos.oh = 0;
@@ -616,13 +674,12 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OutVi
 
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
-    const int wave = wave_index();
-    const int ct = wave % g.col_tiles;
-    const int rb = wave / g.col_tiles;
-    const int r0 = rb * g.rows_per_wave;
-    if (r0 >= g.rows) return;
-    const int r1 = min(g.rows, r0 + g.rows_per_wave);
-    const int n = ct * 64 + (int)(threadIdx.x & 63);
+    const WavePos wp = wave_pos(g.col_tiles);
+    // a wavefront past the last row block keeps an empty row range
+    const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
+    const int r0 = active ? wp.rb * g.rows_per_wave : 0;
+    const int r1 = active ? min(g.rows, r0 + g.rows_per_wave) : 0;
+    const int n = wp.ct * 64 + (int)(threadIdx.x & 63);
     const bool n_ok = n < g.N;
     const int nload = n_ok ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
@@ -678,8 +735,7 @@ template <int AB, int WB, int CWS> struct ConvShape {
 
 inline dim3 grid_for(const BranchArgs &g) {
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
-    const int64_t waves = row_blocks * g.col_tiles;
-    return dim3((unsigned)((waves + 3) / 4));
+    return dim3((unsigned)(((row_blocks + 3) / 4) * g.col_tiles));     // 4 row blocks x 1 column tile per block
 }
 
 template <int AB, int WB>

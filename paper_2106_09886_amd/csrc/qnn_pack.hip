@@ -1,67 +1,116 @@
 // Encode + pack kernel (paper Eq. (7); "store those numbers by bits", Sec. 5.4).
 //
 // A code v = sum_m 2^(m-1) c_m with c_m = +-1 has c_m = +1 exactly where binary digit m-1 of
-// u = (v + 2^bits - 1) / 2 is set, so plane p of the output is digit p of u.  One thread
-// produces the `bits` words of one (row, 32-element group): it reads its 32 codes (two 16-byte
-// loads on the aligned fast path) and writes one word per plane.  HBM-bound: 1 (or 2) bytes in
-// and bits/8 bytes out per code.
+// u = (v + 2^bits - 1) / 2 is set, so plane p of the output is digit p of u, i.e. digit p+1
+// of t = v + 2^bits - 1 (which fits the code's own byte / halfword: 0 <= t <= 2^(bits+1) - 2).
+//
+// One thread produces the `bits` words of one (row, 32-element group).  On the fast path it
+// reads its 32 codes as 16-byte vectors and works on four (int8) or two (int16) codes per
+// 32-bit register: a carry-free per-field add of 2^bits - 1, then per plane one shift+mask
+// that leaves one bit per field and two shift-ors that gather the fields' bits.  HBM-bound:
+// 1 (or 2) bytes in and bits/8 bytes out per code.
 #include "qnn_internal.h"
 
 namespace qnn {
 namespace {
 
-template <typename CodeT>
-__device__ __forceinline__ void pack_one(int v, int bits, int vmax, int k, bool validate,
-                                         uint32_t (&word)[8], int &bad) {
-    const int u = (v + vmax) >> 1;
-    bool ok = true;
-    if (validate) ok = ((v & 1) != 0) && (v >= -vmax) && (v <= vmax);
-    if (validate && !ok) { ++bad; return; }
-#pragma unroll
-    for (int p = 0; p < 8; ++p)
-        if (p < bits) word[p] |= (uint32_t)((u >> p) & 1) << k;
+// per-byte add without carries between bytes: fields of x plus the constant c in every byte
+__device__ __forceinline__ uint32_t add_bytes(uint32_t x, uint32_t c) {
+    return ((x & 0x7f7f7f7fu) + (c & 0x7f7f7f7fu)) ^ ((x ^ c) & 0x80808080u);
+}
+__device__ __forceinline__ uint32_t add_halves(uint32_t x, uint32_t c) {
+    return ((x & 0x7fff7fffu) + (c & 0x7fff7fffu)) ^ ((x ^ c) & 0x80008000u);
+}
+// bits 0, 8, 16, 24 of t -> bits 0..3
+__device__ __forceinline__ uint32_t gather4(uint32_t t) {
+    t |= t >> 7;
+    t |= t >> 14;
+    return t & 0xfu;
+}
+// bits 0, 16 of t -> bits 0..1
+__device__ __forceinline__ uint32_t gather2(uint32_t t) { return (t | (t >> 15)) & 0x3u; }
+
+// Validity of the four byte codes in x: odd and |v| <= vmax.  Returns the number of bad ones.
+__device__ __forceinline__ int count_bad(int v, int vmax) {
+    return (((v & 1) == 0) || v < -vmax || v > vmax) ? 1 : 0;
 }
 
-template <typename CodeT, bool VALIDATE>
+template <typename CodeT, int BITS, bool VALIDATE>
 __global__ __launch_bounds__(256) void pack_kernel(const CodeT *__restrict__ codes, int64_t rows,
-                                                   int K, int Kw, int bits,
-                                                   uint32_t *__restrict__ planes,
+                                                   int K, int Kw, uint32_t *__restrict__ planes,
                                                    int32_t *__restrict__ bad_count) {
+    constexpr int VMAX = (1 << BITS) - 1;
     const int64_t total = rows * (int64_t)Kw;
-    const int vmax = (1 << bits) - 1;
     int bad = 0;
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = idx / Kw;
-        const int wi = (int)(idx - row * Kw);
+        int64_t row;
+        int wi;
+        if (Kw == 2) { row = idx >> 1; wi = (int)(idx & 1); }         // common small cases without a divide
+        else if (Kw == 1) { row = idx; wi = 0; }
+        else { row = idx / Kw; wi = (int)(idx - row * Kw); }
         const int kbeg = wi * 32;
         const int cnt = min(32, K - kbeg);
         const CodeT *src = codes + row * (int64_t)K + kbeg;
-        uint32_t word[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-        const bool aligned = (cnt == 32) && ((((uintptr_t)src) & 15u) == 0);
-        if (aligned) {
-            constexpr int PER = 16 / (int)sizeof(CodeT);     // codes per 16-byte load
-            constexpr int NLD = 32 / PER;
+        uint32_t word[BITS];
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) word[p] = 0u;
+        const bool fast = (cnt == 32) && ((((uintptr_t)src) & 15u) == 0);
+        if (fast) {
+            constexpr int NLD = (int)sizeof(CodeT) * 2;                // 16-byte loads per 32 codes
             const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
 #pragma unroll
             for (int l = 0; l < NLD; ++l) {
                 const uint4 q = s4[l];
                 const uint32_t lanes[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                for (int e = 0; e < PER; ++e) {
-                    int v;
-                    if (sizeof(CodeT) == 1) v = (int)(int8_t)(lanes[e >> 2] >> (8 * (e & 3)));
-                    else v = (int)(int16_t)(lanes[e >> 1] >> (16 * (e & 1)));
-                    pack_one<CodeT>(v, bits, vmax, l * PER + e, VALIDATE, word, bad);
+                for (int d = 0; d < 4; ++d) {
+                    uint32_t x = lanes[d];
+                    if (sizeof(CodeT) == 1) {
+                        if (VALIDATE) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) bad += count_bad((int)(int8_t)(x >> (8 * e)), VMAX);
+                        }
+                        const uint32_t t = add_bytes(x, 0x01010101u * (uint32_t)VMAX);
+#pragma unroll
+                        for (int p = 0; p < BITS; ++p)
+                            word[p] |= gather4((t >> (p + 1)) & 0x01010101u) << (l * 16 + d * 4);
+                    } else {
+                        if (VALIDATE) {
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) bad += count_bad((int)(int16_t)(x >> (16 * e)), VMAX);
+                        }
+                        const uint32_t t = add_halves(x, 0x00010001u * (uint32_t)VMAX);
+#pragma unroll
+                        for (int p = 0; p < BITS; ++p)
+                            word[p] |= gather2((t >> (p + 1)) & 0x00010001u) << (l * 8 + d * 2);
+                    }
+                }
+            }
+            if (VALIDATE && bad) {
+                // a bad entry packs as the lowest code: redo this group element by element
+#pragma unroll
+                for (int p = 0; p < BITS; ++p) word[p] = 0u;
+                for (int k = 0; k < 32; ++k) {
+                    const int v = (int)src[k];
+                    if (count_bad(v, VMAX)) continue;
+                    const int u = (v + VMAX) >> 1;
+#pragma unroll
+                    for (int p = 0; p < BITS; ++p) word[p] |= (uint32_t)((u >> p) & 1) << k;
                 }
             }
         } else {
-            for (int k = 0; k < cnt; ++k) pack_one<CodeT>((int)src[k], bits, vmax, k, VALIDATE, word, bad);
-        }
-        uint32_t *dst = planes + (row * bits) * (int64_t)Kw + wi;
+            for (int k = 0; k < cnt; ++k) {
+                const int v = (int)src[k];
+                if (VALIDATE && count_bad(v, VMAX)) { ++bad; continue; }
+                const int u = (v + VMAX) >> 1;
 #pragma unroll
-        for (int p = 0; p < 8; ++p)
-            if (p < bits) dst[(int64_t)p * Kw] = word[p];
+                for (int p = 0; p < BITS; ++p) word[p] |= (uint32_t)((u >> p) & 1) << k;
+            }
+        }
+        uint32_t *dst = planes + (row * BITS) * (int64_t)Kw + wi;
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) dst[(int64_t)p * Kw] = word[p];
     }
     if (VALIDATE) {
         // wavefront sum, one atomic per wavefront that saw something
@@ -69,6 +118,34 @@ __global__ __launch_bounds__(256) void pack_kernel(const CodeT *__restrict__ cod
         for (int off = 32; off > 0; off >>= 1) bad += __shfl_down(bad, off, 64);
         if ((threadIdx.x & 63) == 0 && bad != 0) atomicAdd(bad_count, bad);
     }
+}
+
+template <typename CodeT, int BITS>
+hipError_t launch_bits(const void *codes, int64_t rows, int K, int Kw, uint32_t *planes,
+                       int32_t *bad_count, bool validate, unsigned blocks, hipStream_t s) {
+    if (validate)
+        hipLaunchKernelGGL((pack_kernel<CodeT, BITS, true>), dim3(blocks), dim3(256), 0, s,
+                           (const CodeT *)codes, rows, K, Kw, planes, bad_count);
+    else
+        hipLaunchKernelGGL((pack_kernel<CodeT, BITS, false>), dim3(blocks), dim3(256), 0, s,
+                           (const CodeT *)codes, rows, K, Kw, planes, bad_count);
+    return hipGetLastError();
+}
+
+template <typename CodeT>
+hipError_t launch_type(const void *codes, int64_t rows, int K, int Kw, int bits, uint32_t *planes,
+                       int32_t *bad_count, bool validate, unsigned blocks, hipStream_t s) {
+    switch (bits) {
+        case 1: return launch_bits<CodeT, 1>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 2: return launch_bits<CodeT, 2>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 3: return launch_bits<CodeT, 3>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 4: return launch_bits<CodeT, 4>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 5: return launch_bits<CodeT, 5>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 6: return launch_bits<CodeT, 6>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 7: return launch_bits<CodeT, 7>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+        case 8: return launch_bits<CodeT, 8>(codes, rows, K, Kw, planes, bad_count, validate, blocks, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -80,22 +157,9 @@ hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t 
     if (total == 0) return hipSuccess;
     const int64_t want = (total + 255) / 256;
     const unsigned blocks = (unsigned)(want < (int64_t)1 << 20 ? want : (int64_t)1 << 20);
-    if (code_bytes == 1) {
-        if (validate)
-            hipLaunchKernelGGL((pack_kernel<int8_t, true>), dim3(blocks), dim3(256), 0, s,
-                               (const int8_t *)codes, rows, (int)K, Kw, bits, planes, bad_count);
-        else
-            hipLaunchKernelGGL((pack_kernel<int8_t, false>), dim3(blocks), dim3(256), 0, s,
-                               (const int8_t *)codes, rows, (int)K, Kw, bits, planes, bad_count);
-    } else {
-        if (validate)
-            hipLaunchKernelGGL((pack_kernel<int16_t, true>), dim3(blocks), dim3(256), 0, s,
-                               (const int16_t *)codes, rows, (int)K, Kw, bits, planes, bad_count);
-        else
-            hipLaunchKernelGGL((pack_kernel<int16_t, false>), dim3(blocks), dim3(256), 0, s,
-                               (const int16_t *)codes, rows, (int)K, Kw, bits, planes, bad_count);
-    }
-    return hipGetLastError();
+    if (code_bytes == 1)
+        return launch_type<int8_t>(codes, rows, (int)K, Kw, bits, planes, bad_count, validate, blocks, s);
+    return launch_type<int16_t>(codes, rows, (int)K, Kw, bits, planes, bad_count, validate, blocks, s);
 }
 
 }  // namespace qnn
