@@ -105,19 +105,20 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps
 
-    # ---- the same K steps again with an event pair around every launch of the dominant kernel
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-            torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    for a, b, c in evs:
+    # ---- each kernel on its own: K back-to-back launches between one pair of events on the
+    # launch stream (average launch duration of that kernel, input planes resident)
+    def timed(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
         a.record()
-        pack()
+        for _ in range(args.steps):
+            fn()
         b.record()
-        conv()
-        c.record()
-    torch.cuda.synchronize()
-    pack_us = sum(a.elapsed_time(b) for a, b, c in evs) / args.steps * 1e3
-    conv_us = sum(b.elapsed_time(c) for a, b, c in evs) / args.steps * 1e3
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / args.steps * 1e3
+
+    conv_us = timed(conv)
+    pack_us = timed(pack)
 
     ops = 2.0 * rows * w.Cout * K                       # effective quantized operations per step
     lane_ops = 2.0 * B * rows * w.Cout * 9 * Cw         # xor + popcount-accumulate per 32-bit word and branch

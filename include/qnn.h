@@ -58,6 +58,16 @@ int qnn_version(void);
 #define QNN_TUNE_ROWS_PER_WAVE 2  /* rows (GEMM rows / output pixels) per wavefront        */
 int qnn_tune(int key, int value);
 
+/*
+ * Profiling aid.  With a non-NULL device buffer, every wavefront w < bytes/32 of the branch
+ * kernels launched afterwards (process-wide) writes four uint64 words at buffer + 32*w:
+ * {start clock, end clock, HW_ID | XCC_ID << 32, start real-time clock}: the first two are the
+ * shader clock of s_memtime (local to a compute unit), the last the chip-wide 100 MHz clock.
+ * NULL switches tracing off.  The buffer must be 8-byte aligned and stay valid while traced
+ * kernels run; results of the kernels do not change.
+ */
+int qnn_set_wave_trace(void *buffer, size_t bytes);
+
 /* flags of qnn_encode_pack */
 #define QNN_PACK_VALIDATE 1u /* count entries that are not codes into *bad_count */
 

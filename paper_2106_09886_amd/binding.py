@@ -18,7 +18,8 @@ QNN_PACK_VALIDATE = 1
 QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE = 1, 2
 
 EXPORTS = (
-    "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_encode_pack",
+    "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_set_wave_trace",
+    "qnn_encode_pack",
     "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col",
     "qnn_conv2d_packed", "qnn_scale_epilogue",
 )
@@ -54,6 +55,8 @@ def lib():
     L.qnn_version.restype = i32
     L.qnn_tune.argtypes = [i32, i32]
     L.qnn_tune.restype = i32
+    L.qnn_set_wave_trace.argtypes = [vp, sz]
+    L.qnn_set_wave_trace.restype = i32
     L.qnn_encode_pack.argtypes = [vp, i32, i64, i64, i32, vp, vp, u32, vp]
     L.qnn_encode_pack.restype = i32
     L.qnn_branch_gemm.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, vp]
@@ -98,6 +101,15 @@ def tune(waves_per_simd=None, rows_per_wave=None):
         _check(lib().qnn_tune(QNN_TUNE_WAVES_PER_SIMD, int(waves_per_simd)), "qnn_tune")
     if rows_per_wave is not None:
         _check(lib().qnn_tune(QNN_TUNE_ROWS_PER_WAVE, int(rows_per_wave)), "qnn_tune")
+
+
+def set_wave_trace(buf):
+    """buf: int64 GPU tensor receiving 4 words per wavefront, or None to switch tracing off."""
+    if buf is None:
+        _check(lib().qnn_set_wave_trace(None, 0), "qnn_set_wave_trace")
+    else:
+        _dev(buf, torch.int64, "buf")
+        _check(lib().qnn_set_wave_trace(_ptr(buf), buf.numel() * 8), "qnn_set_wave_trace")
 
 
 def encode_pack(codes, bits, validate=False, out=None):

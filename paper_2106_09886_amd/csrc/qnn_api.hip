@@ -5,7 +5,7 @@
 namespace qnn {
 
 Tuning &tuning() {
-    static Tuning t = {4, 0};
+    static Tuning t = {0, 0, nullptr, 0};
     return t;
 }
 
@@ -79,6 +79,7 @@ int pick_conv_rows_per_wave(int64_t rows, int64_t W, int col_tiles) {
         const int64_t per_simd = (waves + simds - 1) / simds;
         if (per_simd > wps) return;
         double cost = (double)per_simd * (double)rpw * (aligned ? 1.0 : 1.08);
+        if (rpw & 1) cost *= 1.03;                                     // pixel pairs: an odd run redoes a pixel
         cost += 0.5 * (double)per_simd;                                // fixed work per wavefront (weight loads)
         if (per_simd < 4) cost *= 1.0 + 0.1 * (double)(4 - per_simd);  // too few wavefronts to hide latencies
         if (best == 0 || cost < best_cost) { best = rpw; best_cost = cost; }
@@ -144,6 +145,13 @@ int qnn_last_hip_error(void) { return g_last_hip_error; }
 
 int qnn_version(void) { return 100; }
 
+int qnn_set_wave_trace(void *buffer, size_t bytes) {
+    if (buffer != nullptr && ((((uintptr_t)buffer) & 7u) || bytes < 32)) return QNN_EINVAL;
+    tuning().trace = static_cast<uint64_t *>(buffer);
+    tuning().trace_waves = buffer ? (uint32_t)(bytes / 32 > 0xffffffffu ? 0xffffffffu : bytes / 32) : 0;
+    return QNN_OK;
+}
+
 int qnn_tune(int key, int value) {
     if (value < 0) return QNN_EINVAL;
     switch (key) {
@@ -182,6 +190,7 @@ qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb
     g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1;
     g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((N + 63) / 64);
+    g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N);
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
 }
@@ -207,6 +216,7 @@ qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *W
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
+    g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles), Cout);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
 }

@@ -185,18 +185,36 @@ __device__ __forceinline__ void finish_row(const OutView &v, int rel_row, int va
 }
 
 
-// Position of a wavefront: the four wavefronts of a block share one tile of 64 columns and
-// take consecutive row blocks.
+// Position of a wavefront.  Consecutive wavefronts (the four of a block first) take
+// consecutive column tiles of the SAME row block: they request the same activation words, which
+// then hit in the scalar cache, while each loads its own weight tile once.
 struct WavePos {
     int ct;        // column tile
     int rb;        // row block
+    int index;     // wavefront number in the grid
 };
 __device__ __forceinline__ WavePos wave_pos(int col_tiles) {
     WavePos p;
-    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    p.ct = (int)(blockIdx.x % (unsigned)col_tiles);
-    p.rb = (int)(blockIdx.x / (unsigned)col_tiles) * 4 + wib;
+    p.index = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)));
+    p.ct = p.index % col_tiles;
+    p.rb = p.index / col_tiles;
     return p;
+}
+
+// Optional per-wavefront trace (see qnn_set_wave_trace): four 64-bit words per wavefront,
+// {start shader clock, end shader clock, HW_ID | XCC_ID << 32, start real-time clock}.
+__device__ __forceinline__ void trace_begin(const BranchArgs &g, const WavePos &wp) {
+    if (g.trace != nullptr && (uint32_t)wp.index < g.trace_waves && (threadIdx.x & 63) == 0) {
+        uint64_t *t = g.trace + 4 * (int64_t)wp.index;
+        t[0] = __builtin_amdgcn_s_memtime();                            // shader clock (local to the CU)
+        t[2] = (uint64_t)__builtin_amdgcn_s_getreg((31 << 11) | 4)      // HW_ID: wave, SIMD, CU, SH, SE ids
+             | ((uint64_t)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);   // XCC_ID
+        t[3] = __builtin_amdgcn_s_memrealtime();                        // constant 100 MHz clock (chip-wide)
+    }
+}
+__device__ __forceinline__ void trace_end(const BranchArgs &g, const WavePos &wp) {
+    if (g.trace != nullptr && (uint32_t)wp.index < g.trace_waves && (threadIdx.x & 63) == 0)
+        g.trace[4 * (int64_t)wp.index + 1] = __builtin_amdgcn_s_memtime();
 }
 
 // Weight words of one chunk for this lane's column: NW words, word_index(k) = position in Wt.
@@ -361,8 +379,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     uniform_words As = as_uniform(g.A);
     constexpr int KC = SEGS * CWT;
     const int Kw = g.Cw;
+    trace_begin(g, wp);
     if (Kw == 0) {  // K == 0: every product is the empty sum
         for (int r = r0; r < r1; ++r) finish_row<true>(ov, r - r0, 0, true, true);
+        trace_end(g, wp);
         return;
     }
     for (int k0 = 0; k0 < Kw; k0 += KC) {
@@ -371,6 +391,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
         if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, ov, nload, r0, r1, k0, first, last);
         else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, ov, As, nload, r0, r1, k0, first, last);
     }
+    trace_end(g, wp);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -382,7 +403,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
 // Template shape:  CWS  words per (pixel, plane) if known at compile time, else 0;
 //                  CWT  channel words per chunk;  TPC  taps per chunk (9, 3 or 1);
 //                  GT   taps per pipeline stage (divides TPC, TPC/GT odd; GT == 3 only when
-//                       CWT == CWS, so that the three taps of a kernel row are contiguous).
+//                       CWT == CWS, so that the three taps of a kernel row are contiguous);
+//                  P    output pixels per loop iteration (P > 1 only for single-chunk shapes
+//                       with GT == 3: the P pixels share the P+2 input pixels of each kernel row,
+//                       one scalar load and one wait per kernel row serve all of them).
 // A chunk = TPC taps x CWT channel words; its weight words (TPC*WB*CWT) stay in VGPRs.
 // ---------------------------------------------------------------------------------------
 struct PixelPos {
@@ -399,25 +423,26 @@ __device__ __forceinline__ int tap_dw(int t) { return t % 3 - 1; }
 //                 words; a tap whose image row does not exist points at the pixel's own row
 //                 (in bounds) and is skipped when consumed;
 //   stage_ok      bit s: the kernel row of stage s exists;
-//   edge          bit 0: the current pixel is in column 0 (taps with dw = -1 are skipped),
-//                 bit 1: it is in column W-1 (taps with dw = +1 are skipped).
+//   edge          bit 0: the first pixel of the current group is in column 0 (its taps with
+//                 dw = -1 are skipped), bit 1: the last one is in column W-1 (dw = +1 skipped).
 // Addresses are not tested: a +-1 column step from a pixel of an existing row stays inside
 // [0, rows) except for the four pixels 0, W, rows-1-W and rows-1, which never come here.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
 struct ConvCtx {
     static constexpr int NS = TPC / GT;
     static constexpr bool CONTIG = (CWS > 0 && CWT == CWS);   // a pixel's AB*CWT words are consecutive
     // CONTIG: one run of GT*AB*CWT words (consecutive pixels are consecutive too);
     // otherwise one run of CWT words per (tap, plane).
-    typedef typename std::conditional<CONTIG, SStage<1, GT * AB * CWT>, SStage<GT * AB, CWT>>::type Buf;
+    static_assert(P == 1 || (GT == 3 && CONTIG), "pixel groups need contiguous kernel rows");
+    typedef typename std::conditional<CONTIG, SStage<1, (GT + P - 1) * AB * CWT>, SStage<GT * AB, CWT>>::type Buf;
     uint64_t base;                   // byte address of the activation planes
     int Cw, c0, t0;                  // runtime words per plane, chunk's first channel word / tap
     uint32_t off_cur, off_nxt;       // byte offset of (pixel, plane 0, word c0) for this / the next pixel
     uint32_t stage_off[NS];
     uint32_t stage_ok;               // bit s: the kernel row of stage s exists
-    uint32_t edge;                   // bit 0: column 0, bit 1: column W-1 (current pixel)
+    uint32_t edge;                   // bit 0: column 0, bit 1: column W-1 (current group)
     uint32_t w[TPC][WB][CWT];
-    int part[AB + WB - 1];
+    int part[P][AB + WB - 1];
     Buf bufA, bufB;
 
     __device__ __forceinline__ int plane_stride() const { return CWS > 0 ? CWS : Cw; }
@@ -460,20 +485,22 @@ struct ConvCtx {
     __device__ __forceinline__ void consume(const Buf &b) {
         if (stage_ok & (1u << ST)) {
 #pragma unroll
-            for (int i = 0; i < GT; ++i) {
-                const int dw = dw_of<ST>(i);
-                // skip the tap that hangs over the left / right image border
-                const bool skip = (dw < 0 && (edge & 1u)) || (dw > 0 && (edge & 2u));
-                if (!skip) {
+            for (int x = 0; x < P; ++x)               // output pixel of the group
 #pragma unroll
-                    for (int q = 0; q < WB; ++q)
+                for (int i = 0; i < GT; ++i) {
+                    const int dw = dw_of<ST>(i);
+                    // skip the tap that hangs over the left / right image border
+                    const bool skip = (x == 0 && dw < 0 && (edge & 1u)) || (x == P - 1 && dw > 0 && (edge & 2u));
+                    if (!skip) {
 #pragma unroll
-                        for (int p = 0; p < AB; ++p)
+                        for (int q = 0; q < WB; ++q)
 #pragma unroll
-                            for (int j = 0; j < CWT; ++j)
-                                popc_acc(part[p + q], word(b, i, p, j) ^ w[ST * GT + i][q][j]);
+                            for (int p = 0; p < AB; ++p)
+#pragma unroll
+                                for (int j = 0; j < CWT; ++j)
+                                    popc_acc(part[x][p + q], word(b, x + i, p, j) ^ w[ST * GT + i][q][j]);
+                    }
                 }
-            }
         }
     }
 };
@@ -501,57 +528,77 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
     return nh * nw;
 }
 
-// Pipelined pixels ra .. rb-1 of one chunk, all in image row oh.  left_first: pixel ra is in
-// column 0; right_last: pixel rb-1 is in column W-1.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
-__device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT> &c,
+// Pipelined pixels ra .. rb-1 of one chunk, all in image row oh, rb - ra >= P.  left_first:
+// pixel ra is in column 0; right_last: pixel rb-1 is in column W-1.  Pixels are taken in
+// groups of P; if P does not divide the run, the last group is placed at rb-P and recomputes
+// pixels of the group before it (P > 1 is used for single-chunk shapes only, where a
+// recomputed pixel is simply stored again with the same value).
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
+__device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c,
                                                    const BranchArgs &g, const OutView &ov, int r0, int ra,
                                                    int rb, int oh, bool left_first, bool right_last,
                                                    bool first, bool last) {
+    constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
+    static_assert(P == 1 || SINGLE, "pixel groups only where a chunk pass is the whole product");
     c.set_image_row(oh, g.H, g.W);
     const int krow = (3 - (oh == 0 ? 1 : 0) - (oh == g.H - 1 ? 1 : 0)) * g.kconst;   // per valid column
     const uint32_t pb = c.pixel_bytes();
     const uint32_t edge_first = left_first ? 1u : 0u, edge_last = right_last ? 2u : 0u;
-    c.off_cur = (uint32_t)ra * pb + (uint32_t)c.c0 * 4u;
-    c.off_nxt = c.off_cur;
+    const uint32_t off_a = (uint32_t)ra * pb + (uint32_t)c.c0 * 4u;
+    const int r_last = rb - P;                       // start of the last group
+    c.off_cur = off_a;
+    c.off_nxt = off_a;
     c.template request<0>(c.bufA, false);
     int r = ra;
-    auto one_row = [&](auto flip_tag) {
+    auto one_group = [&](auto flip_tag) {
         constexpr bool FLIP = decltype(flip_tag)::value;
 #pragma unroll
-        for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
-        c.off_nxt = (r + 1 < rb) ? c.off_cur + pb : c.off_cur;   // last pixel prefetches itself (unused)
+        for (int x = 0; x < P; ++x)
+#pragma unroll
+            for (int s = 0; s < AB + WB - 1; ++s) c.part[x][s] = 0;
+        // the group after this one (the last group prefetches itself, unused)
+        const int rn = (r < r_last) ? min(r + P, r_last) : r;
+        c.off_nxt = off_a + (uint32_t)(rn - ra) * pb;
         // integer selects only: keeps the edge bookkeeping on the scalar unit
         uint32_t edge = 0u;
         if (r == ra) edge |= edge_first;
-        if (r + 1 == rb) edge |= edge_last;
+        if (r == r_last) edge |= edge_last;
         c.edge = edge;
         run_stages<0, FLIP>(c);
-        int val = -2 * weighted_sum(c.part);
-        if (first) val += (3 - (int)(edge & 1u) - (int)(edge >> 1)) * krow;
-        finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
+#pragma unroll
+        for (int x = 0; x < P; ++x) {
+            int val = -2 * weighted_sum(c.part[x]);
+            int ncols = 3;
+            if (x == 0) ncols -= (int)(edge & 1u);
+            if (x == P - 1) ncols -= (int)(edge >> 1);
+            if (first) val += ncols * krow;
+            finish_row<SINGLE>(ov, r - r0 + x, val, first, last);
+        }
         c.off_cur = c.off_nxt;
-        ++r;
+        r = rn;
     };
-    // pixels in pairs (the two buffers swap roles from one pixel to the next), then a last one
-    while (r + 1 < rb) {
-        one_row(std::integral_constant<bool, false>());
-        one_row(std::integral_constant<bool, true>());
+    // groups in pairs (the two buffers swap roles from one group to the next), then a last one
+    const int ngroups = (rb - ra + P - 1) / P;
+    int done = 0;
+    while (done + 1 < ngroups) {
+        one_group(std::integral_constant<bool, false>());
+        one_group(std::integral_constant<bool, true>());
+        done += 2;
     }
-    if (r < rb) one_row(std::integral_constant<bool, false>());
-    // Drain the prefetch issued by the last pixel.  Both buffers are named so that their
+    if (done < ngroups) one_group(std::integral_constant<bool, false>());
+    // Drain the prefetch issued by the last group.  Both buffers are named so that their
     // registers stay reserved until the wait, whichever of them the prefetch went to.
     c.bufA.template arrive<true>();
     c.bufB.template arrive<false>();
 }
 
 // One pixel of one chunk with every tap and address tested (the four end pixels).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
-__device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT> &c, uniform_words As,
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
+__device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c, uniform_words As,
                                                  const BranchArgs &g, const OutView &ov, int r0, int r,
                                                  PixelPos pos, bool first, bool last) {
 #pragma unroll
-    for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
+    for (int s = 0; s < AB + WB - 1; ++s) c.part[0][s] = 0;
 #pragma unroll
     for (int t = 0; t < TPC; ++t) {
         const int dh = (TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t);
@@ -569,10 +616,10 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
 #pragma unroll
                 for (int p = 0; p < AB; ++p)
 #pragma unroll
-                    for (int j = 0; j < CWT; ++j) popc_acc(c.part[p + q], a[p][j] ^ c.w[t][q][j]);
+                    for (int j = 0; j < CWT; ++j) popc_acc(c.part[0][p + q], a[p][j] ^ c.w[t][q][j]);
         }
     }
-    int val = -2 * weighted_sum(c.part);
+    int val = -2 * weighted_sum(c.part[0]);
     if (first) val += valid_taps(pos, g.H, g.W) * g.kconst;
     finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
 }
@@ -580,12 +627,12 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
 // full chunk: every word c0 .. c0+CWT-1 exists.  The wavefront's pixel range is cut into
 // runs inside one image row; the four pixels whose untested neighbour addresses could leave
 // the buffer (0, W, rows-1-W, rows-1) go through the tested path.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
 __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutView &ov, uniform_words As,
                                                 int nload, int r0, int r1, int c0, int t0, bool first,
                                                 bool last) {
     static_assert(TPC % GT == 0 && ((TPC / GT) & 1) == 1, "odd number of stages per pixel");
-    ConvCtx<AB, WB, CWS, CWT, TPC, GT> c;
+    ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> c;
     c.base = (uint64_t)g.A; c.Cw = g.Cw; c.c0 = c0; c.t0 = t0;
     const int ps = c.plane_stride();
     {
@@ -612,7 +659,7 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutVi
             if (special[i] == r) is_special = true;
             if (special[i] > r && special[i] < stop) stop = special[i];
         }
-        if (is_special) {
+        if (is_special || stop - r < P) {              // end pixels, and runs shorter than a group
             conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
             stop = r + 1;
         } else {
@@ -672,7 +719,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OutVi
     }
 }
 
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     const WavePos wp = wave_pos(g.col_tiles);
     // a wavefront past the last row block keeps an empty row range
@@ -686,8 +733,10 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     const OutView ov = make_out_view(g, r0, r1, nload, sc);
     uniform_words As = as_uniform(g.A);
     const int Cw = (CWS > 0) ? CWS : g.Cw;
+    trace_begin(g, wp);
     if (Cw == 0) {  // no input channels: every product is the empty sum
         for (int r = r0; r < r1; ++r) finish_row<true>(ov, r - r0, 0, true, true);
+        trace_end(g, wp);
         return;
     }
     constexpr int TAP_CHUNKS = 9 / TPC;
@@ -702,12 +751,13 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
             for (int tc = 0; tc < TAP_CHUNKS; ++tc) {
                 const bool first = (c0 == 0) && (tc == 0);
                 const bool last = (c0 + CWT >= Cw) && (tc == TAP_CHUNKS - 1);
-                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT>(g, ov, As, nload, r0, r1, c0, tc * TPC, first, last);
+                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P>(g, ov, As, nload, r0, r1, c0, tc * TPC, first, last);
             }
         } else if constexpr (CWS == 0 && CWT > 1) {
             conv_chunk_tail<AB, WB, CWT>(g, ov, As, nload, r0, r1, c0, c0 == 0, true);
         }
     }
+    trace_end(g, wp);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -731,11 +781,15 @@ template <int AB, int WB, int CWS> struct ConvShape {
     static constexpr int CWT = imin(CWS, pow2_floor(16 / AB));
     static constexpr int TPC = (9 * WB * CWT <= 108) ? 9 : (3 * WB * CWT <= 108) ? 3 : 1;
     static constexpr int GT = (TPC >= 3 && CWT == CWS && 3 * AB * CWT <= 24) ? 3 : 1;
+    // pixels per iteration: as many as keep one stage ((P+2) pixels) within 16 SGPRs
+    static constexpr bool GROUPS = (GT == 3 && TPC == 9 && CWT == CWS);
+    static constexpr int P = !GROUPS ? 1 : (6 * AB * CWT <= 16) ? 4 : (4 * AB * CWT <= 16) ? 2 : 1;
 };
 
 inline dim3 grid_for(const BranchArgs &g) {
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
-    return dim3((unsigned)(((row_blocks + 3) / 4) * g.col_tiles));     // 4 row blocks x 1 column tile per block
+    const int64_t waves = row_blocks * g.col_tiles;
+    return dim3((unsigned)((waves + 3) / 4));
 }
 
 template <int AB, int WB>
@@ -748,7 +802,7 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
-    hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT>), grid_for(g), dim3(256), 0, s, g);
+    hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P>), grid_for(g), dim3(256), 0, s, g);
     return hipGetLastError();
 }
 
@@ -768,9 +822,9 @@ hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
     // any other channel count: runtime stride, chunks of two channel words while the two stage
     // buffers (2 * AB * CWT SGPRs) leave the allocator room, else one word
     if (g.Cw == 1 || AB > 4)
-        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1>), grid_for(g), dim3(256), 0, s, g);
+        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1, 1>), grid_for(g), dim3(256), 0, s, g);
     else if constexpr (AB <= 4)
-        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1>), grid_for(g), dim3(256), 0, s, g);
+        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1, 1>), grid_for(g), dim3(256), 0, s, g);
     return hipGetLastError();
 }
 

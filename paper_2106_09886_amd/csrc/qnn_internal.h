@@ -23,11 +23,15 @@ struct BranchArgs {
     int kconst;           // (true K of one tap) * (2^AB - 1) * (2^WB - 1)
     int rows_per_wave;    // contiguous rows handled by one wavefront
     int col_tiles;        // ceil(N / 64)
+    uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
+    uint32_t trace_waves; // capacity of `trace` in wavefronts
 };
 
 struct Tuning {
     int waves_per_simd;   // target resident wavefronts per SIMD when sizing rows_per_wave
     int rows_per_wave;    // > 0 overrides the automatic choice
+    uint64_t *trace;      // device buffer for per-wavefront trace records, or nullptr
+    uint32_t trace_waves;
 };
 Tuning &tuning();
 
