@@ -27,6 +27,10 @@ sys.path.insert(0, ROOT)
 # and clock (v_xor_b32, v_bcnt_u32_b32 are full rate, not packed).
 PEAK_LANE_OPS = 256 * 64 * 2.4e9
 
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/ (scaled by the device-copy calibration described there).
+MEASURED_TRAFFIC = {"resnet18_s1": 61.6e6}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -157,7 +161,7 @@ def main():
             "unit": "Tlane-op/s",
             "peak_from": "256 CU x 64 lanes x 2.4 GHz, one 32-bit integer vector op per lane and clock",
             "frac": round(achieved / PEAK_LANE_OPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC.get(w.name),
         },
     }
 
