@@ -141,6 +141,22 @@ qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *W
                              int32_t *acc, const float *scale, float *out_f32, void *stream);
 
 /*
+ * Re-encoding between layers (Alg. 1 forward: the scaled output of layer l is encoded for layer
+ * l+1; Table 2 gives the rule for 2 bits): optional 2x2 max-pool (stride 2) of y, then each
+ * value is mapped to the odd code grid of `bits` bits,
+ *     a = |v|;  c = min(2*floor(a/2) + 1, 2^bits - 1);  code = (v > 0) ? +c : -c
+ * (so [2j, 2j+2) -> 2j+1 in magnitude, 0 -> -1, NaN -> -(2^bits-1)), and written as
+ *   codes   optional, [Nb][Ho][Wo][C] int8 (bits <= 7) or int16 (bits == 8);
+ *   planes  optional, per-pixel bit planes uint32 [Nb*Ho*Wo][bits][ceil(C/32)] as consumed by
+ *           qnn_conv2d_packed (16-byte aligned).
+ * y is fp32 NHWC [Nb][H][W][C]; Ho = H/2, Wo = W/2 with pooling (H, W even), else H, W.
+ * At least one of codes / planes must be given.  Outside the four entry points named by the
+ * task; it exists for layer chains.
+ */
+qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, int pool2x2,
+                            int bits, void *codes, uint32_t *planes, void *stream);
+
+/*
  * Stand-alone scale epilogue (Eq. (9); Eq. (19)): out_f32[i][j] = (float)acc[i][j] * scale[j],
  * acc int32 [M][N], scale fp32 [N], out fp32 [M][N].  One IEEE binary32 multiply per
  * element, no fused multiply-add.  M == 0 or N == 0 launches nothing.

@@ -21,7 +21,7 @@ EXPORTS = (
     "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_set_wave_trace",
     "qnn_encode_pack",
     "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col",
-    "qnn_conv2d_packed", "qnn_scale_epilogue",
+    "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
 )
 
 
@@ -67,6 +67,8 @@ def lib():
     L.qnn_conv2d_im2col.restype = i32
     L.qnn_conv2d_packed.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, i64, vp, vp, vp, vp]
     L.qnn_conv2d_packed.restype = i32
+    L.qnn_requant_pack.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp, vp, vp]
+    L.qnn_requant_pack.restype = i32
     L.qnn_scale_epilogue.argtypes = [vp, i64, i64, vp, vp, vp]
     L.qnn_scale_epilogue.restype = i32
     _lib = L
@@ -186,6 +188,20 @@ def conv2d_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, scale=None, want_acc=
                                  _ptr(o32), _stream())
     _check(st, "qnn_conv2d_packed")
     return acc, o32
+
+
+def requant_pack(y, bits, pool=False, want_codes=True, want_planes=True):
+    """y fp32 NHWC -> (codes int8/int16 NHWC | None, planes int32 [pixels][bits][Cw] | None)."""
+    _dev(y, torch.float32, "y")
+    Nb, H, W, C = y.shape
+    Ho, Wo = (H // 2, W // 2) if pool else (H, W)
+    codes = torch.empty((Nb, Ho, Wo, C), dtype=torch.int8 if bits <= 7 else torch.int16,
+                        device=y.device) if want_codes else None
+    planes = torch.empty((Nb * Ho * Wo, bits, (C + 31) // 32), dtype=torch.int32,
+                         device=y.device) if want_planes else None
+    st = lib().qnn_requant_pack(_ptr(y), Nb, H, W, C, 1 if pool else 0, bits, _ptr(codes), _ptr(planes), _stream())
+    _check(st, "qnn_requant_pack")
+    return codes, planes
 
 
 def scale_epilogue(acc, scale):

@@ -38,7 +38,8 @@ def build(jobs=None, verbose=False):
     os.makedirs(OBJ, exist_ok=True)
     work = [("qnn_api.hip", os.path.join(OBJ, "qnn_api.o"), []),
             ("qnn_pack.hip", os.path.join(OBJ, "qnn_pack.o"), []),
-            ("qnn_epilogue.hip", os.path.join(OBJ, "qnn_epilogue.o"), [])]
+            ("qnn_epilogue.hip", os.path.join(OBJ, "qnn_epilogue.o"), []),
+            ("qnn_requant.hip", os.path.join(OBJ, "qnn_requant.o"), [])]
     for ab in range(1, 9):
         work.append(("qnn_branch.hip", os.path.join(OBJ, "qnn_branch_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))
     jobs = jobs or min(8, os.cpu_count() or 1)

@@ -250,6 +250,20 @@ qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const 
     return qnn_conv2d_packed(planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, stream);
 }
 
+qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, int pool2x2, int bits,
+                            void *codes, uint32_t *planes, void *stream) {
+    if (!bits_ok(bits) || Nb < 0 || H < 0 || W < 0 || C < 0) return QNN_EINVAL;
+    if (pool2x2 != 0 && pool2x2 != 1) return QNN_EINVAL;
+    if (pool2x2 && ((H & 1) || (W & 1))) return QNN_EINVAL;
+    if (H > kInt31 || W > kInt31 || Nb > kInt31 || C > kInt31) return QNN_EUNSUPPORTED;
+    if (Nb == 0 || H == 0 || W == 0 || C == 0) return QNN_OK;
+    if (Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
+    if (y == nullptr || (codes == nullptr && planes == nullptr)) return QNN_EINVAL;
+    if (!aligned4(y) || !aligned16(planes)) return QNN_EALIGN;
+    if (bits == 8 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
+    return from_hip(launch_requant(y, Nb, H, W, C, pool2x2 != 0, bits, codes, planes, (hipStream_t)stream));
+}
+
 qnn_status qnn_scale_epilogue(const int32_t *acc, int64_t M, int64_t N, const float *scale,
                               float *out_f32, void *stream) {
     if (M < 0 || N < 0) return QNN_EINVAL;

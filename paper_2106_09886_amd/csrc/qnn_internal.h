@@ -58,6 +58,8 @@ hipError_t launch_conv_ab8(const BranchArgs &, int, hipStream_t);
 
 hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
                        uint32_t *planes, int32_t *bad_count, bool validate, hipStream_t);
+hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
+                          void *codes, uint32_t *planes, hipStream_t);
 hipError_t launch_scale(const int32_t *acc, int64_t total, int64_t N, const float *scale,
                         float *out, hipStream_t);
 

@@ -112,3 +112,38 @@ def make_conv(w, Nb=None):
         alpha = uniform_f32(ss, w.Cout, w.scale_lo, w.scale_hi)
         s = (alpha * np.float32(w.beta)).astype(np.float32)
     return X, Wt, s
+
+
+# ---------------------------------------------------------------------------
+# VGG-16-shaped stack of 13 3x3 convolutions (stride 1, pad 1) with a 2x2 max-pool after each
+# block.  First layer: 3 input channels of 8-bit codes; every other layer 4-bit activation
+# codes; 2-bit weights throughout.  Per-output-channel scales keep the re-encoded activations
+# spread over the 16 levels: with uniform codes var(w) = 5, var(a8) = 21845, var(a4) = 85, so
+#   layer 1:  s = U(0.8, 1.2) * 8 / sqrt(27 * 5 * 21845),   others:  s = U(0.8, 1.2) / sqrt(5 * 9 * Cin).
+# ---------------------------------------------------------------------------
+Stack = namedtuple("Stack", "name Nb H W C0 widths pool_after wb ab_first ab seeds")
+
+VGG16 = Stack("vgg16_stack", 16, 224, 224, 3,
+              (64, 64, 128, 128, 256, 256, 256, 512, 512, 512, 512, 512, 512),
+              (2, 4, 7, 10, 13), 2, 8, 4, (1005, 2005, 3005))
+
+
+def make_stack(w=VGG16, Nb=None, H=None, W=None):
+    """(X0 int16 codes NHWC, [(Wt int8 [Cout][3][3][Cin], scale fp32 [Cout], pool_after), ...])."""
+    Nb = w.Nb if Nb is None else Nb
+    H = w.H if H is None else H
+    W = w.W if W is None else W
+    sa, sw, ss = w.seeds
+    X0 = uniform_codes(sa, (Nb, H, W, w.C0), w.ab_first)
+    layers = []
+    cin = w.C0
+    for l, cout in enumerate(w.widths, start=1):
+        Wt = uniform_codes(sw + l, (cout, 3, 3, cin), w.wb)
+        jitter = uniform_f32(ss + l, cout, 0.8, 1.2)
+        if l == 1:
+            base = np.float32(8.0 / np.sqrt(27.0 * 5.0 * 21845.0))
+        else:
+            base = np.float32(1.0 / np.sqrt(5.0 * 9.0 * cin))
+        layers.append((Wt, (jitter * base).astype(np.float32), l in w.pool_after))
+        cin = cout
+    return X0, layers

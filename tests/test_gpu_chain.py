@@ -1,0 +1,112 @@
+"""GPU parity of the layer chain (conv -> scale -> [2x2 max-pool] -> re-encode -> pack) against
+the CPU oracle, layer by layer: int32 accumulators and codes bit-exact, fp32 outputs within 1e-6
+relative of the float64 product and bit-equal to the oracle's single binary32 multiply."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import dev, host, rand_codes, planes_u32, say  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def q():
+    import torch
+    assert torch.cuda.is_available(), "no GPU visible"
+    from paper_2106_09886_amd import binding
+    binding.lib()
+    return binding
+
+
+# ------------------------------------------------------------ re-encode kernel on its own
+@pytest.mark.parametrize("bits", [1, 2, 4, 7, 8])
+@pytest.mark.parametrize("shape,pool", [((1, 1, 1, 1), False), ((2, 3, 5, 7), False), ((1, 4, 6, 64), True),
+                                        ((2, 2, 2, 65), True), ((1, 6, 4, 130), False), ((3, 8, 8, 32), True)])
+def test_requant_pack(q, oracle, bits, shape, pool):
+    say("requant", bits, shape, pool)
+    rng = np.random.default_rng(bits * 100 + sum(shape))
+    m = (1 << bits) - 1
+    y = rng.normal(0, m / 1.5 + 1, size=shape).astype(np.float32)
+    flat = y.reshape(-1)
+    # exact grid points, zeros, ties and out-of-range values
+    special = np.array([0.0, -0.0, 2.0, -2.0, 1.0, -1.0, float(m), float(-m), m + 1.0, -(m + 1.0), 1e30, -1e30,
+                        float(m - 1), 3.9999999, 4.0], dtype=np.float32)
+    flat[: min(flat.size, special.size)] = special[: min(flat.size, special.size)]
+    want_y = oracle.maxpool2x2(y) if pool else y
+    want = oracle.requant(want_y, bits)
+    codes, planes = q.requant_pack(dev(y), bits, pool=pool)
+    got = host(codes)
+    assert got.shape == want.shape and (got.astype(np.int16) == want).all()
+    Nb, Ho, Wo, C = want.shape
+    want_planes, bad = oracle.pack_planes(want.reshape(Nb * Ho * Wo, C), bits)
+    assert bad == 0 and (planes_u32(planes) == want_planes).all()
+    # planes only / codes only give the same
+    _, p2 = q.requant_pack(dev(y), bits, pool=pool, want_codes=False)
+    c2, _ = q.requant_pack(dev(y), bits, pool=pool, want_planes=False)
+    assert (planes_u32(p2) == want_planes).all() and (host(c2) == got).all()
+
+
+# ------------------------------------------------------------------------- chains
+def run_stack(q, oracle, X0, layers, ab_first, ab, wb, report=False):
+    Nb, H, W, C = X0.shape
+    codes = X0                        # oracle side: codes of the current layer's input
+    x_planes = None                   # GPU side: packed input of the current layer
+    for l, (Wt, s, pool) in enumerate(layers, start=1):
+        Cout = Wt.shape[0]
+        bits_in = ab_first if l == 1 else ab
+        Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+        if l == 1:
+            acc, out = q.conv2d_im2col(dev(X0), bits_in, Wp, wb, Cout, scale=dev(s))
+        else:
+            acc, out = q.conv2d_packed(x_planes, bits_in, Wp, wb, Nb, H, W, C, Cout, scale=dev(s))
+        g_codes, x_planes = q.requant_pack(out, ab, pool=pool)
+        # oracle
+        o_acc = oracle.conv3x3(codes, Wt)
+        assert int(np.abs(o_acc).max()) < 2 ** 24
+        o_y = oracle.scale_f32(o_acc, s)
+        o_codes = oracle.requant(oracle.maxpool2x2(o_y) if pool else o_y, ab)
+        assert (host(acc).astype(np.int64) == o_acc).all(), "layer %d int32" % l
+        got_y = host(out)
+        assert (got_y == o_y).all(), "layer %d fp32" % l
+        y64 = oracle.scale_f64(o_acc, s)
+        assert (np.abs(got_y.astype(np.float64) - y64) <= 1e-6 * np.abs(y64)).all()
+        assert (host(g_codes).astype(np.int16) == o_codes).all(), "layer %d codes" % l
+        if report:
+            u = np.unique(o_codes)
+            say("layer %2d: %s -> %d ch, pool=%d, |acc|max %d, %d code levels" %
+                (l, (Nb, H, W, C), Cout, pool, int(np.abs(o_acc).max()), len(u)))
+        codes = o_codes
+        C = Cout
+        if pool:
+            H, W = H // 2, W // 2
+        del acc, out, g_codes
+
+
+def test_stack_small(q, oracle):
+    """The 13-layer VGG-16-shaped stack on 2 images of 32x32 (ends at 1x1 after five pools)."""
+    from paper_2106_09886_amd import inputs
+    w = inputs.VGG16
+    X0, layers = inputs.make_stack(w, Nb=2, H=32, W=32)
+    run_stack(q, oracle, X0, layers, w.ab_first, w.ab, w.wb)
+
+
+def test_stack_odd_sizes(q, oracle):
+    """A short chain with ragged channel counts and a non-square image."""
+    rng = np.random.default_rng(77)
+    X0 = rand_codes(rng, (2, 12, 20, 5), 8)
+    chans = [5, 33, 70, 64, 130]
+    layers = []
+    for l in range(1, len(chans)):
+        Wt = rand_codes(rng, (chans[l], 3, 3, chans[l - 1]), 2)
+        s = (rng.uniform(0.8, 1.2, chans[l]) / np.sqrt(45.0 * chans[l - 1] * (300.0 if l == 1 else 1.0))).astype(np.float32)
+        layers.append((Wt, s, l in (2, 3)))
+    run_stack(q, oracle, X0, layers, 8, 4, 2)
+
+
+def test_stack_config5_full(q, oracle):
+    """VGG-16-shaped stack, batch 16, 224x224x3 input, W2A4 (first layer W2A8)."""
+    from paper_2106_09886_amd import inputs
+    w = inputs.VGG16
+    X0, layers = inputs.make_stack(w)
+    say("vgg16 stack: oracle + gpu, layer by layer")
+    run_stack(q, oracle, X0, layers, w.ab_first, w.ab, w.wb, report=True)
