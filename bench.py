@@ -2,16 +2,19 @@
 """Benchmark of the {-1,+1} multi-branch binary product hot path on one MI355X.
 
 A "step" is one pass of the whole path over one batch of synthetic activations that are
-already resident in HBM: encode + pack the activation codes, then the implicit-im2col
-branch convolution with fused weighted accumulation and fp32 scale epilogue (int32 and fp32
-outputs).  The weights are static parameters and are packed once before the timed region.
+already resident in HBM: encode + pack the activation codes, then the branch product
+(implicit-im2col convolution or GEMM) with fused weighted accumulation and fp32 scale epilogue.
+The weights are static parameters and are packed once before the timed region.
+
+Default workload: `resnet18_s1`, the ResNet-18-stage-1-shaped W2A2 3x3 convolution the target
+is quoted on.  Other workloads (`--workload`): `resnet50_s3`, `fc4096`, `gemm64`, and
+`vgg16_stack` (13 chained layers: conv + scale, then max-pool / re-encode / pack per layer).
 
 Prints ONE JSON line.  `value` is the effective quantized throughput 2*M*N*K / t_step in
-GOPS (M output pixels, N filters, K = 9*C).  `roofline` prices the dominant kernel (the
-branch convolution) against the chip's integer vector-ALU rate; `cpu_baseline` is the CPU
-oracle timed on the host cores of this machine.
+GOPS.  `roofline` prices the dominant kernel (the branch kernel) against the chip's integer
+vector-ALU rate; `cpu_baseline` is the CPU oracle timed on the host cores of this machine.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18_s1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 """
 import argparse
 import ctypes
@@ -32,12 +35,25 @@ PEAK_LANE_OPS = 256 * 64 * 2.4e9
 MEASURED_TRAFFIC = {"resnet18_s1": 61.6e6}
 
 
+def timed(torch, fn, n):
+    """Average duration in microseconds of n back-to-back calls on the current stream."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(n):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / n * 1e3
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="resnet18_s1", choices=["resnet18_s1", "resnet50_s3"])
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="resnet18_s1",
+                    choices=["resnet18_s1", "resnet50_s3", "fc4096", "gemm64", "vgg16_stack"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of 256 MiB (a kernel of known HBM traffic) "
@@ -47,6 +63,9 @@ def main():
         print("bench.py: this build measures the path on ONE GPU only (it shards over the batch with "
               "no communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
         return 2
+    name = args.workload
+    steps = args.steps if args.steps is not None else (20 if name == "vgg16_stack" else 200)
+    warmup = args.warmup if args.warmup is not None else (3 if name == "vgg16_stack" else 20)
 
     import numpy as np
     import torch
@@ -56,36 +75,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     L = q.lib()                                   # raises if the HIP library is not built
-    w = inputs.WORKLOADS[args.workload]
-    X, Wt, s = inputs.make_conv(w)
-    rows = w.Nb * w.H * w.W
-    K = 9 * w.C
-    Cw = (w.C + 31) // 32
-    B = w.ab * w.wb
-
     dev = torch.device("cuda:0")
-    Xd = torch.from_numpy(X).to(dev)
-    Wp = q.encode_pack(torch.from_numpy(Wt.reshape(w.Cout * 9, w.C)).to(dev), w.wb)   # once: static weights
-    sd = torch.from_numpy(s).to(dev) if s is not None else None
-    acc = torch.empty((w.Nb, w.H, w.W, w.Cout), dtype=torch.int32, device=dev)
-    out = torch.empty((w.Nb, w.H, w.W, w.Cout), dtype=torch.float32, device=dev) if s is not None else None
-    planes = torch.empty((rows, w.ab, Cw), dtype=torch.int32, device=dev)
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     p = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())
-    pX, pW, pS, pA, pO, pP = p(Xd), p(Wp), p(sd), p(acc), p(out), p(planes)
-    esz = Xd.element_size()
-
-    def pack():
-        st = L.qnn_encode_pack(pX, esz, rows, w.C, w.ab, pP, None, 0, stream)
-        assert st == 0, st
-
-    def conv():
-        st = L.qnn_conv2d_packed(pP, w.ab, pW, w.wb, w.Nb, w.H, w.W, w.C, w.Cout, pA, pS, pO, stream)
-        assert st == 0, st
-
-    def step():
-        pack()
-        conv()
 
     if args.copy_calibration:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
@@ -95,47 +87,126 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
+    def check(st):
+        assert st == 0, L.qnn_status_string(st)
+
+    cpu = None
+    if name == "vgg16_stack":
+        w = inputs.VGG16
+        X0, layers = inputs.make_stack(w)
+        Nb, H, W, C = X0.shape
+        x0 = torch.from_numpy(X0).to(dev)
+        plan, ops, lane_ops, keep = [], 0.0, 0.0, []
+        h, wd, c = H, W, C
+        planes_in = torch.empty((Nb * h * wd, w.ab_first, 1), dtype=torch.int32, device=dev)
+        first_planes = planes_in
+        for l, (Wt, s, pool) in enumerate(layers, start=1):
+            cout = Wt.shape[0]
+            ab = w.ab_first if l == 1 else w.ab
+            Wp = q.encode_pack(torch.from_numpy(Wt.reshape(cout * 9, c)).to(dev), w.wb)
+            sd = torch.from_numpy(s).to(dev)
+            acc = torch.empty((Nb, h, wd, cout), dtype=torch.int32, device=dev)
+            out = torch.empty((Nb, h, wd, cout), dtype=torch.float32, device=dev)
+            ho, wo = (h // 2, wd // 2) if pool else (h, wd)
+            planes_out = torch.empty((Nb * ho * wo, w.ab, (cout + 31) // 32), dtype=torch.int32, device=dev)
+            plan.append((ab, p(planes_in), p(Wp), h, wd, c, cout, p(acc), p(sd), p(out), 1 if pool else 0,
+                         p(planes_out)))
+            keep.append((Wp, sd, acc, out, planes_in, planes_out))
+            ops += 2.0 * Nb * h * wd * cout * 9 * c
+            lane_ops += 2.0 * ab * w.wb * Nb * h * wd * cout * 9 * ((c + 31) // 32)
+            planes_in, h, wd, c = planes_out, ho, wo, cout
+        pX, pF = p(x0), p(first_planes)
+
+        def pack():
+            check(L.qnn_encode_pack(pX, 2, Nb * H * W, C, w.ab_first, pF, None, 0, stream))
+
+        def branch():
+            for (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout) in plan:
+                check(L.qnn_conv2d_packed(pin, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, stream))
+                check(L.qnn_requant_pack(po, Nb, h, wd, cout, pool, w.ab, None, pout, stream))
+
+        desc = ("vgg16_stack: 13 chained 3x3 conv layers, batch %d, %dx%dx%d input, W%dA%d (first layer A%d), "
+                "2x2 max-pool after each block, re-encode + pack between layers"
+                % (Nb, H, W, C, w.wb, w.ab, w.ab_first))
+        kernel_name = "13 x (conv_kernel + requant_pack_kernel); lane-ops of the conv kernels only"
+        B = None
+        outputs = "int32 + fp32 per layer"
+    else:
+        w = inputs.WORKLOADS[name]
+        is_conv = hasattr(w, "Cout")
+        if is_conv:
+            X, Wt, s = inputs.make_conv(w)
+            rows, N, K, Kw = w.Nb * w.H * w.W, w.Cout, 9 * w.C, 9 * ((w.C + 31) // 32)
+            kin, kbits = w.C, (w.C + 31) // 32
+            Wp = q.encode_pack(torch.from_numpy(Wt.reshape(w.Cout * 9, w.C)).to(dev), w.wb)
+            shape = (w.Nb, w.H, w.W, w.Cout)
+        else:
+            X, Wm, s = inputs.make_gemm(w)
+            rows, N, K, Kw = w.M, w.N, w.K, (w.K + 31) // 32
+            kin, kbits = w.K, Kw
+            Wp = q.encode_pack(torch.from_numpy(np.ascontiguousarray(Wm.T)).to(dev), w.wb)
+            shape = (w.M, w.N)
+        Xd = torch.from_numpy(X).to(dev)
+        B = w.ab * w.wb
+        sd = torch.from_numpy(s).to(dev) if s is not None else None
+        acc = torch.empty(shape, dtype=torch.int32, device=dev)
+        out = torch.empty(shape, dtype=torch.float32, device=dev) if s is not None else None
+        planes = torch.empty((rows, w.ab, kbits), dtype=torch.int32, device=dev)
+        pX, pW, pS, pA, pO, pP = p(Xd), p(Wp), p(sd), p(acc), p(out), p(planes)
+        esz = Xd.element_size()
+
+        def pack():
+            check(L.qnn_encode_pack(pX, esz, rows, kin, w.ab, pP, None, 0, stream))
+
+        if is_conv:
+            def branch():
+                check(L.qnn_conv2d_packed(pP, w.ab, pW, w.wb, w.Nb, w.H, w.W, w.C, w.Cout, pA, pS, pO, stream))
+            desc = "%s: 3x3 conv NHWC %dx%dx%dx%d -> %d filters, W%dA%d (M=%d, N=%d, K=%d)" % (
+                w.name, w.Nb, w.H, w.W, w.C, w.Cout, w.wb, w.ab, rows, N, K)
+            kernel_name = "conv_kernel (branch convolution)"
+        else:
+            def branch():
+                check(L.qnn_branch_gemm(pP, w.ab, pW, w.wb, w.M, w.N, w.K, pA, pS, pO, stream))
+            desc = "%s: GEMM C[%dx%d] = A[%dx%d] . W[%dx%d], W%dA%d" % (
+                w.name, w.M, w.N, w.M, w.K, w.K, w.N, w.wb, w.ab)
+            kernel_name = "gemm_kernel (branch GEMM)"
+        ops = 2.0 * rows * N * K                      # effective quantized operations per step
+        lane_ops = 2.0 * B * rows * N * Kw            # xor + popcount-accumulate per 32-bit word and branch
+        outputs = "int32" + (" + fp32 scaled" if s is not None else "")
+
+        def cpu():
+            import oracle
+            if is_conv:
+                o = oracle.conv3x3(X.astype(np.int16), Wt.astype(np.int16))
+            else:
+                o = oracle.gemm(X.astype(np.int16), Wm.astype(np.int16))
+            if s is not None:
+                oracle.scale_f64(o, s)
+
+    def step():
+        pack()
+        branch()
+
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-
+    ms_per_step = timed(torch, step, steps) / 1e3
     # ---- each kernel on its own: K back-to-back launches between one pair of events on the
-    # launch stream (average launch duration of that kernel, input planes resident)
-    def timed(fn):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        a.record()
-        for _ in range(args.steps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / args.steps * 1e3
+    # launch stream (average launch duration of that kernel, operands resident)
+    branch_us = timed(torch, branch, steps)
+    pack_us = timed(torch, pack, steps)
 
-    conv_us = timed(conv)
-    pack_us = timed(pack)
-
-    ops = 2.0 * rows * w.Cout * K                       # effective quantized operations per step
-    lane_ops = 2.0 * B * rows * w.Cout * 9 * Cw         # xor + popcount-accumulate per 32-bit word and branch
     value = ops / (ms_per_step * 1e-3) / 1e9
-    achieved = lane_ops / (conv_us * 1e-6)
-
+    achieved = lane_ops / (branch_us * 1e-6)
     res = {
-        "metric": "effective quantized GOPS (2*M*N*K/s), whole step: pack activations + branch conv + scale",
+        "metric": "effective quantized GOPS (2*M*N*K/s), whole step: pack activations + branch product + scale",
         "value": round(value, 1),
         "unit": "GOPS",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
         "scaling": "weak",
@@ -143,37 +214,33 @@ def main():
         "dtype": "u32 bit-planes, int32 accumulate, fp32 scale",
         "data": "synthetic",
         "config": {
-            "workload": "%s: 3x3 conv NHWC %dx%dx%dx%d -> %d filters, W%dA%d (M=%d, N=%d, K=%d)"
-                        % (w.name, w.Nb, w.H, w.W, w.C, w.Cout, w.wb, w.ab, rows, w.Cout, K),
+            "workload": desc,
             "branches": B,
             "weights": "packed once before the timed region (static parameters)",
-            "outputs": "int32" + (" + fp32 scaled" if s is not None else ""),
-            "bit_ops_per_s": round(2.0 * B * rows * w.Cout * K / (ms_per_step * 1e-3), 1),
+            "outputs": outputs,
+            "bit_ops_per_s": round(B * ops / (ms_per_step * 1e-3), 1) if B else None,
             "pack_kernel_us": round(pack_us, 2),
-            "branch_kernel_us": round(conv_us, 2),
-            "branch_kernel_effective_GOPS": round(ops / (conv_us * 1e-6) / 1e9, 1),
+            "branch_kernel_us": round(branch_us, 2),
+            "branch_kernel_effective_GOPS": round(ops / (branch_us * 1e-6) / 1e9, 1),
         },
         "roofline": {
             "bound": "alu",
-            "kernel": "conv_kernel (branch convolution)",
+            "kernel": kernel_name,
             "achieved": round(achieved / 1e12, 3),
             "peak": round(PEAK_LANE_OPS / 1e12, 3),
             "unit": "Tlane-op/s",
             "peak_from": "256 CU x 64 lanes x 2.4 GHz, one 32-bit integer vector op per lane and clock",
             "frac": round(achieved / PEAK_LANE_OPS, 4),
-            "traffic": MEASURED_TRAFFIC.get(w.name),
+            "traffic": MEASURED_TRAFFIC.get(name),
         },
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and cpu is not None:
         import oracle
         oracle.build(force=False)
-        X16, W16 = X.astype(np.int16), Wt.astype(np.int16)
         reps, t0 = 0, time.time()
         while True:
-            o = oracle.conv3x3(X16, W16)
-            if s is not None:
-                oracle.scale_f64(o, s)
+            cpu()
             reps += 1
             if time.time() - t0 > 1.5 or reps >= 20:
                 break
@@ -183,8 +250,7 @@ def main():
             "unit": "GOPS",
             "cores": oracle.threads(),
             "kind": "oracle",
-            "sample": "full workload (%d images), direct int64 convolution + float64 scale, mean of %d passes"
-                      % (w.Nb, reps),
+            "sample": "full workload, plain int64 product + float64 scale, mean of %d passes" % reps,
         }
     print(json.dumps(res))
     return 0

@@ -192,6 +192,19 @@ qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb
     g.col_tiles = (int)((N + 63) / 64);
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N);
+    g.split_k = 0;
+    // Long K and too few rows for every wavefront to amortise its weight chunks: let the four
+    // wavefronts of a block share rows and split the chunks instead.
+    const int chunks = (g.Cw + gemm_chunk_words(wb) - 1) / gemm_chunk_words(wb);
+    if (chunks >= 4 && g.rows_per_wave < 16 && tuning().rows_per_wave == 0) {
+        const int64_t target_blocks = (int64_t)device_simd_count();          // 4 blocks (16 wavefronts) per CU
+        int64_t rows_per_block = (M * g.col_tiles + target_blocks - 1) / target_blocks;
+        if (rows_per_block < 8) rows_per_block = 8;
+        if (rows_per_block > 32) rows_per_block = 32;
+        if (rows_per_block > M) rows_per_block = M;
+        g.split_k = 1;
+        g.rows_per_wave = (int)rows_per_block;
+    }
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -216,6 +229,7 @@ qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *W
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
+    g.split_k = 0;
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles), Cout);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));

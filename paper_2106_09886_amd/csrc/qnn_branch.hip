@@ -277,9 +277,10 @@ struct GemmCtx {
 };
 
 // full chunk (all KC words inside Kw): pipelined
-template <int AB, int WB, int SEGS, int CWT>
-__device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, const OutView &ov, int nload, int r0,
-                                                int r1, int k0, bool first, bool last) {
+// `sink(rel_row, v)` receives v = -2 * S of the chunk for row r0 + rel_row.
+template <int AB, int WB, int SEGS, int CWT, class Sink>
+__device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, int r0, int r1, int k0,
+                                                Sink sink) {
     GemmCtx<AB, WB, SEGS, CWT> c;
     const int Kw = g.Cw;
     c.base = (uint64_t)g.A;
@@ -306,9 +307,7 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, const OutVi
         for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
         c.off_nxt = (r + 1 < r1) ? c.off_cur + row_bytes : c.off_cur;   // last row prefetches itself
         run_stages<0, FLIP>(c);
-        int val = -2 * weighted_sum(c.part);
-        if (first) val += g.kconst;
-        finish_row<false>(ov, r - r0, val, first, last);
+        sink(r - r0, -2 * weighted_sum(c.part));
         c.off_cur = c.off_nxt;
         ++r;
     };
@@ -321,9 +320,9 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, const OutVi
 }
 
 // tail chunk (runs past Kw): plain loads with a guard per word
-template <int AB, int WB, int SEGS, int CWT>
-__device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, const OutView &ov, uniform_words As,
-                                                int nload, int r0, int r1, int k0, bool first, bool last) {
+template <int AB, int WB, int SEGS, int CWT, class Sink>
+__device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_words As, int nload, int r0,
+                                                int r1, int k0, Sink sink) {
     const int Kw = g.Cw;
     uint32_t w[SEGS][WB][CWT];
 #pragma unroll
@@ -358,9 +357,7 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, const OutVi
                         for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], a[p][j] ^ w[t][q][j]);
             }
         }
-        int val = -2 * weighted_sum(part);
-        if (first) val += g.kconst;
-        finish_row<false>(ov, r - r0, val, first, last);
+        sink(r - r0, -2 * weighted_sum(part));
     }
 }
 
@@ -388,8 +385,62 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     for (int k0 = 0; k0 < Kw; k0 += KC) {
         const bool first = (k0 == 0);
         const bool last = (k0 + KC >= Kw);
-        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, ov, nload, r0, r1, k0, first, last);
-        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, ov, As, nload, r0, r1, k0, first, last);
+        auto sink = [&](int rel_row, int v) {
+            if (first) v += g.kconst;
+            finish_row<false>(ov, rel_row, v, first, last);
+        };
+        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, sink);
+        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, sink);
+    }
+    trace_end(g, wp);
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM with the K chunks split over the four wavefronts of a block (long K, few rows, e.g. a
+// fully connected layer on a small batch).  All four wavefronts own the same 64 columns and
+// the same block of rows; wavefront v takes chunks v, v+4, ...  A weight chunk is therefore
+// loaded once per block and reused for every row of the block (four times the reuse of the
+// kernel above at the same number of wavefronts), and partial sums never touch global memory:
+// they are summed per wavefront in LDS and combined after one barrier.
+// ---------------------------------------------------------------------------------------
+constexpr int kSplitRowsMax = 32;
+
+template <int AB, int WB, int SEGS, int CWT>
+__global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
+    __shared__ int partial[4][kSplitRowsMax][64];
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    WavePos wp;
+    wp.index = (int)blockIdx.x * 4 + wv;
+    wp.ct = (int)(blockIdx.x % (unsigned)g.col_tiles);
+    wp.rb = (int)(blockIdx.x / (unsigned)g.col_tiles);
+    const int r0 = wp.rb * g.rows_per_wave;                   // rows per BLOCK here (<= kSplitRowsMax)
+    const int r1 = min(g.rows, r0 + g.rows_per_wave);
+    const int n = wp.ct * 64 + lane;
+    const int nload = (n < g.N) ? n : g.N - 1;
+    const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
+    const OutView ov = make_out_view(g, r0, r1, nload, sc);
+    uniform_words As = as_uniform(g.A);
+    constexpr int KC = SEGS * CWT;
+    const int Kw = g.Cw;
+    trace_begin(g, wp);
+    bool mine = false;                                        // has this wavefront written its slab yet
+    for (int k0 = wv * KC; k0 < Kw; k0 += 4 * KC) {
+        const bool first = !mine;
+        auto sink = [&](int rel_row, int v) {
+            if (!first) v += partial[wv][rel_row][lane];
+            partial[wv][rel_row][lane] = v;
+        };
+        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, sink);
+        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, sink);
+        mine = true;
+    }
+    if (!mine)
+        for (int r = 0; r < r1 - r0; ++r) partial[wv][r][lane] = 0;
+    __syncthreads();
+    for (int r = wv; r < r1 - r0; r += 4) {
+        const int v = g.kconst + partial[0][r][lane] + partial[1][r][lane] + partial[2][r][lane] + partial[3][r][lane];
+        finish_row<true>(ov, r, v, true, true);
     }
     trace_end(g, wp);
 }
@@ -774,12 +825,30 @@ template <int AB, int WB> struct GemmShape {
     static constexpr int SEGS = KC / CWT;
 };
 
-// Convolution with a compile-time plane stride CWS (a power of two up to 16):
-//   chunk channel words CWT (stage SGPRs GT*AB*CWT <= 24), taps per chunk TPC (weight VGPRs
-//   TPC*WB*CWT <= 108), taps per stage GT.
+// Convolution with a compile-time plane stride CWS (a power of two up to 16).  A chunk is
+// CWT channel words x TPC taps; its weight words (TPC*WB*CWT) must leave room in the VGPR file
+// for several wavefronts per SIMD (<= 80), one pipeline stage GT*AB*CWT must fit the SGPR
+// budget twice (<= 32), and among the shapes that fit the one with the most work per chunk
+// pass (CWT*TPC) wins, so that the round trip of partial sums is paid least often.
 template <int AB, int WB, int CWS> struct ConvShape {
-    static constexpr int CWT = imin(CWS, pow2_floor(16 / AB));
-    static constexpr int TPC = (9 * WB * CWT <= 108) ? 9 : (3 * WB * CWT <= 108) ? 3 : 1;
+    static constexpr int kMaxW = 80;
+    static constexpr int CMAX = imin(CWS, pow2_floor(32 / AB));
+    static constexpr int score(int cwt, int tpc) { return (cwt <= CMAX && tpc * WB * cwt <= kMaxW) ? cwt * tpc : 0; }
+    static constexpr int best_cwt() {
+        int bc = 1, bs = 0;
+        for (int cwt = 1; cwt <= CMAX; cwt *= 2)
+            for (int tpc = 1; tpc <= 9; tpc *= 3)
+                if (score(cwt, tpc) > bs || (score(cwt, tpc) == bs && bs > 0 && cwt > bc)) { bs = score(cwt, tpc); bc = cwt; }
+        return bc;
+    }
+    static constexpr int best_tpc() {
+        int bt = 1, bs = 0;
+        for (int tpc = 1; tpc <= 9; tpc *= 3)
+            if (score(best_cwt(), tpc) > bs) { bs = score(best_cwt(), tpc); bt = tpc; }
+        return bt;
+    }
+    static constexpr int CWT = best_cwt();
+    static constexpr int TPC = best_tpc();
     static constexpr int GT = (TPC >= 3 && CWT == CWS && 3 * AB * CWT <= 24) ? 3 : 1;
     // pixels per iteration: as many as keep one stage ((P+2) pixels) within 16 SGPRs
     static constexpr bool GROUPS = (GT == 3 && TPC == 9 && CWT == CWS);
@@ -795,9 +864,17 @@ inline dim3 grid_for(const BranchArgs &g) {
 template <int AB, int WB>
 hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     using S = GemmShape<AB, WB>;
-    hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT>), grid_for(g), dim3(256), 0, s, g);
+    if (g.split_k) {
+        const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
+        hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT>), dim3((unsigned)(row_blocks * g.col_tiles)),
+                           dim3(256), 0, s, g);
+    } else {
+        hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT>), grid_for(g), dim3(256), 0, s, g);
+    }
     return hipGetLastError();
 }
+
+
 
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {

@@ -23,6 +23,8 @@ struct BranchArgs {
     int kconst;           // (true K of one tap) * (2^AB - 1) * (2^WB - 1)
     int rows_per_wave;    // contiguous rows handled by one wavefront
     int col_tiles;        // ceil(N / 64)
+    int split_k;          // GEMM only: K chunks split over the wavefronts of a block; then
+                          // rows_per_wave is the number of rows per BLOCK
     uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
     uint32_t trace_waves; // capacity of `trace` in wavefronts
 };
@@ -35,7 +37,9 @@ struct Tuning {
 };
 Tuning &tuning();
 
-int device_simd_count();  // 4 * number of compute units of the current device (cached)
+int device_simd_count();
+// K words per weight chunk of the GEMM kernels (GemmShape::KC in qnn_branch.hip)
+inline int gemm_chunk_words(int wb) { return (wb <= 2) ? 32 : (wb <= 4) ? 16 : 8; }  // 4 * number of compute units of the current device (cached)
 
 // Launchers, one translation unit per activation bit width AB (1..8).
 typedef hipError_t (*branch_launch_fn)(const BranchArgs &, int wb, hipStream_t);
