@@ -117,12 +117,19 @@ def main():
             planes_in, h, wd, c = planes_out, ho, wo, cout
         pX, pF = p(x0), p(first_planes)
 
+        ws_bytes = int(L.qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, w.ab_first))
+        assert ws_bytes <= first_planes.numel() * 4
+
         def pack():
-            check(L.qnn_encode_pack(pX, 2, Nb * H * W, C, w.ab_first, pF, None, 0, stream))
+            pass                                  # the first layer packs inside qnn_conv2d_im2col
 
         def branch():
-            for (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout) in plan:
-                check(L.qnn_conv2d_packed(pin, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, stream))
+            for i, (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout) in enumerate(plan):
+                if i == 0:
+                    check(L.qnn_conv2d_im2col(pX, 2, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, pF, ws_bytes,
+                                              stream))
+                else:
+                    check(L.qnn_conv2d_packed(pin, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, stream))
                 check(L.qnn_requant_pack(po, Nb, h, wd, cout, pool, w.ab, None, pout, stream))
 
         desc = ("vgg16_stack: 13 chained 3x3 conv layers, batch %d, %dx%dx%d input, W%dA%d (first layer A%d), "

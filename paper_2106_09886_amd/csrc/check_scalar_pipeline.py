@@ -1,8 +1,8 @@
 """Static check of the hand-placed scalar loads in the generated gfx950 assembly.
 
-The branch kernels request activation words with s_load_dword* written as inline asm and
+The branch kernels (qnn_branch.hip, qnn_conv_small.hip) request activation words with s_load_dword* written as inline asm and
 wait for them with an explicit s_waitcnt; the compiler does not know the destination SGPRs
-are in flight in between.  This script compiles qnn_branch.hip to assembly for every
+are in flight in between.  This script compiles them to assembly for every
 activation bit width and verifies, kernel by kernel, that
   * no scratch memory is used, and
   * on no path of the control-flow graph does an instruction outside an asm block (a spill
@@ -22,11 +22,15 @@ ROOT = os.path.dirname(os.path.dirname(HERE))
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def compile_asm(ab, out):
+SOURCES = ("qnn_branch.hip", "qnn_conv_small.hip")
+
+
+def compile_asm(job):
+    src, ab, out = job
     cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
            "-packed-fp32-ops", "-ffp-contract=off", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", HERE, "-DQNN_AB=%d" % ab, "-S", "--cuda-device-only",
-           os.path.join(HERE, "qnn_branch.hip"), "-o", out]
+           os.path.join(HERE, src), "-o", out]
     subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE)
     return out
 
@@ -148,7 +152,9 @@ def check_file(path):
 def main():
     tmp = tempfile.mkdtemp(prefix="qnn_asm_")
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
-        files = list(ex.map(lambda ab: compile_asm(ab, os.path.join(tmp, "ab%d.s" % ab)), range(1, 9)))
+        jobs = [(src, ab, os.path.join(tmp, "%s_ab%d.s" % (src.split(".")[0], ab)))
+                for src in SOURCES for ab in range(1, 9)]
+        files = list(ex.map(compile_asm, jobs))
     total, bad, spills = 0, [], 0
     for f in files:
         nk, p, sp = check_file(f)

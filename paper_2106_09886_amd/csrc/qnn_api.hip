@@ -43,6 +43,13 @@ const branch_launch_fn k_gemm[8] = {launch_gemm_ab1, launch_gemm_ab2, launch_gem
 const branch_launch_fn k_conv[8] = {launch_conv_ab1, launch_conv_ab2, launch_conv_ab3, launch_conv_ab4,
                                     launch_conv_ab5, launch_conv_ab6, launch_conv_ab7, launch_conv_ab8};
 
+const branch_launch_fn k_conv_small[8] = {launch_conv_small_ab1, launch_conv_small_ab2, launch_conv_small_ab3,
+                                          launch_conv_small_ab4, launch_conv_small_ab5, launch_conv_small_ab6,
+                                          launch_conv_small_ab7, launch_conv_small_ab8};
+const im2col_launch_fn k_im2col[8] = {launch_im2col_pack_ab1, launch_im2col_pack_ab2, launch_im2col_pack_ab3,
+                                      launch_im2col_pack_ab4, launch_im2col_pack_ab5, launch_im2col_pack_ab6,
+                                      launch_im2col_pack_ab7, launch_im2col_pack_ab8};
+
 const int64_t kInt31 = ((int64_t)1 << 31) - 1;
 
 // Rows handled by one wavefront: enough wavefronts to give every SIMD of the chip
@@ -187,7 +194,7 @@ qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb
     BranchArgs g;
     g.A = A; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
-    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1;
+    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1; g.C = 0;
     g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((N + 63) / 64);
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
@@ -226,7 +233,7 @@ qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *W
     BranchArgs g;
     g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
-    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W;
+    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
     g.split_k = 0;
@@ -258,6 +265,23 @@ qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const 
     if (rows == 0 || Cout == 0) return QNN_OK;
     if (have_k) {
         if (workspace_bytes < qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab)) return QNN_EWORKSPACE;
+        if (9 * C <= 32) {
+            // few input channels: one im2col word per plane and pixel (same workspace size as the
+            // per-pixel planes, Cw == 1), then the single-word branch kernel
+            st = from_hip(k_im2col[ab - 1](x_codes, code_bytes, rows, (int)H, (int)W, (int)C, planes,
+                                           (hipStream_t)stream));
+            if (st != QNN_OK) return st;
+            BranchArgs g;
+            g.A = planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+            g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
+            g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
+            g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+            g.col_tiles = (int)((Cout + 63) / 64);
+            g.split_k = 0;
+            g.trace = nullptr; g.trace_waves = 0;
+            g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout);
+            return from_hip(k_conv_small[ab - 1](g, wb, (hipStream_t)stream));
+        }
         st = qnn_encode_pack(x_codes, code_bytes, rows, C, ab, planes, nullptr, 0, stream);
         if (st != QNN_OK) return st;
     }

@@ -20,6 +20,7 @@ struct BranchArgs {
     int N;                // output columns / filters
     int Cw;               // words per (row, plane)
     int H, W;             // image height and width in pixels (convolution only)
+    int C;                // input channels (small-channel convolution only)
     int kconst;           // (true K of one tap) * (2^AB - 1) * (2^WB - 1)
     int rows_per_wave;    // contiguous rows handled by one wavefront
     int col_tiles;        // ceil(N / 64)
@@ -59,6 +60,24 @@ hipError_t launch_conv_ab5(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_ab6(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_ab7(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_ab8(const BranchArgs &, int, hipStream_t);
+
+hipError_t launch_conv_small_ab1(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab2(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab3(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab4(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab5(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab6(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab7(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_small_ab8(const BranchArgs &, int, hipStream_t);
+hipError_t launch_im2col_pack_ab1(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab2(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab3(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab4(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab5(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab6(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab7(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+hipError_t launch_im2col_pack_ab8(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
+typedef hipError_t (*im2col_launch_fn)(const void *, int, int64_t, int, int, int, uint32_t *, hipStream_t);
 
 hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
                        uint32_t *planes, int32_t *bad_count, bool validate, hipStream_t);

@@ -191,6 +191,19 @@ def test_conv_shapes(q, oracle, shape, ab, wb):
     run_conv(q, oracle, X, Wt, ab, wb, rng.uniform(0.01, 0.1, Cout).astype(np.float32))
 
 
+@pytest.mark.parametrize("C", [1, 2, 3])
+@pytest.mark.parametrize("ab,wb", [(8, 2), (2, 2), (1, 1), (4, 3), (8, 8), (5, 7)])
+def test_conv_few_channels(q, oracle, C, ab, wb):
+    """9*C <= 32: the whole K axis of a pixel is one word per plane (explicit im2col word path)."""
+    say("conv few channels", C, ab, wb)
+    rng = np.random.default_rng(C * 100 + ab * 8 + wb)
+    for shape in ((1, 1, 1), (2, 3, 4), (1, 9, 7), (3, 16, 5), (1, 1, 6), (1, 5, 1)):
+        for Cout in (1, 64, 70):
+            X = rand_codes(rng, shape + (C,), ab)
+            Wt = rand_codes(rng, (Cout, 3, 3, C), wb)
+            run_conv(q, oracle, X, Wt, ab, wb, rng.uniform(0.01, 0.1, Cout).astype(np.float32))
+
+
 @pytest.mark.parametrize("ab", range(1, 9))
 @pytest.mark.parametrize("wb", range(1, 9))
 def test_conv_all_bit_widths(q, oracle, ab, wb):
