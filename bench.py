@@ -60,8 +60,9 @@ def main():
                          "so that a counter run can be scaled against it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures the path on ONE GPU only (it shards over the batch with "
-              "no communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures the path on ONE GPU only (the path shards over the batch "
+              "with no communication, so a second GPU would run the same kernel on its own share); "
+              "run with --gpus 1", file=sys.stderr)
         return 2
     name = args.workload
     steps = args.steps if args.steps is not None else (20 if name == "vgg16_stack" else 200)
