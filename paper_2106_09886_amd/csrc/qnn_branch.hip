@@ -404,6 +404,14 @@ struct ConvCtx {
     __device__ __forceinline__ int plane_stride() const { return CWS > 0 ? CWS : Cw; }
     __device__ __forceinline__ uint32_t pixel_bytes() const { return (uint32_t)(AB * plane_stride() * 4); }
 
+    // Stages that are whole kernel rows are taken centre row first: the centre tap of the
+    // centre row exists for every pixel, so it can initialise the accumulators (popc_set)
+    // instead of a zeroing pass.
+    static constexpr bool CENTER_FIRST = (TPC == 9 && GT == 3);
+    static constexpr int first_tap(int st) {           // first tap (kh*3 + kw) of stage st, TPC == 9
+        return CENTER_FIRST ? (st == 0 ? 3 : st == 1 ? 0 : 6) : st * GT;
+    }
+
     // column offset of tap i of stage ST (compile-time unless a chunk is a single tap)
     template <int ST>
     __device__ __forceinline__ int dw_of(int i) const {
@@ -414,7 +422,7 @@ struct ConvCtx {
         stage_ok = 0u;
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
-            const int dh = (TPC == 9) ? (st * GT) / 3 - 1 : tap_dh(t0 + st * GT);
+            const int dh = (TPC == 9) ? first_tap(st) / 3 - 1 : tap_dh(t0 + st * GT);
             const int dw = (TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1;
             const bool ok = (unsigned)(oh + dh) < (unsigned)H;
             if (ok) stage_ok |= 1u << st;
@@ -437,9 +445,34 @@ struct ConvCtx {
         if constexpr (CONTIG) return b.run[0].get((i * AB + p) * CWT + j);
         else return b.run[i * AB + p].get(j);
     }
+    // all branches of tap i of stage ST for output pixel x of the group; SET: first contribution
+    template <int ST, bool SET>
+    __device__ __forceinline__ void tap(const Buf &b, int x, int i) {
+        const int t = (TPC == 9) ? first_tap(ST) + i : ST * GT + i;      // index into w[]
+#pragma unroll
+        for (int q = 0; q < WB; ++q)
+#pragma unroll
+            for (int p = 0; p < AB; ++p)
+#pragma unroll
+                for (int j = 0; j < CWT; ++j) {
+                    const uint32_t v = word(b, x + i, p, j) ^ w[t][q][j];
+                    // accumulator p+q is first reached at j == 0 with the smallest q that pairs with it
+                    const bool first_hit = SET && j == 0 && q == ((p + q) < AB ? 0 : (p + q) - (AB - 1));
+                    if (first_hit) popc_set(part[x][p + q], v);
+                    else popc_acc(part[x][p + q], v);
+                }
+    }
     template <int ST>
     __device__ __forceinline__ void consume(const Buf &b) {
-        if (stage_ok & (1u << ST)) {
+        if constexpr (CENTER_FIRST && ST == 0) {
+            // centre kernel row: always exists; its centre tap goes first and sets the accumulators
+#pragma unroll
+            for (int x = 0; x < P; ++x) {
+                tap<ST, true>(b, x, 1);
+                if (!(x == 0 && (edge & 1u))) tap<ST, false>(b, x, 0);
+                if (!(x == P - 1 && (edge & 2u))) tap<ST, false>(b, x, 2);
+            }
+        } else if (stage_ok & (1u << ST)) {
 #pragma unroll
             for (int x = 0; x < P; ++x)               // output pixel of the group
 #pragma unroll
@@ -447,15 +480,7 @@ struct ConvCtx {
                     const int dw = dw_of<ST>(i);
                     // skip the tap that hangs over the left / right image border
                     const bool skip = (x == 0 && dw < 0 && (edge & 1u)) || (x == P - 1 && dw > 0 && (edge & 2u));
-                    if (!skip) {
-#pragma unroll
-                        for (int q = 0; q < WB; ++q)
-#pragma unroll
-                            for (int p = 0; p < AB; ++p)
-#pragma unroll
-                                for (int j = 0; j < CWT; ++j)
-                                    popc_acc(part[x][p + q], word(b, x + i, p, j) ^ w[ST * GT + i][q][j]);
-                    }
+                    if (!skip) tap<ST, false>(b, x, i);
                 }
         }
     }
@@ -508,10 +533,12 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
     int r = ra;
     auto one_group = [&](auto flip_tag) {
         constexpr bool FLIP = decltype(flip_tag)::value;
+        if constexpr (!ConvCtx<AB, WB, CWS, CWT, TPC, GT, P>::CENTER_FIRST) {
 #pragma unroll
-        for (int x = 0; x < P; ++x)
+            for (int x = 0; x < P; ++x)
 #pragma unroll
-            for (int s = 0; s < AB + WB - 1; ++s) c.part[x][s] = 0;
+                for (int s = 0; s < AB + WB - 1; ++s) c.part[x][s] = 0;
+        }
         // the group after this one (the last group prefetches itself, unused)
         const int rn = (r < r_last) ? min(r + P, r_last) : r;
         c.off_nxt = off_a + (uint32_t)(rn - ra) * pb;

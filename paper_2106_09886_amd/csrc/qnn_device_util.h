@@ -21,6 +21,11 @@ __device__ __forceinline__ void popc_acc(int &part, uint32_t x) {
     asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(part) : "v"(x));
 }
 
+// part = popcount(x): first contribution to an accumulator (saves zeroing it).
+__device__ __forceinline__ void popc_set(int &part, uint32_t x) {
+    asm volatile("v_bcnt_u32_b32 %0, %1, 0" : "=v"(part) : "v"(x));
+}
+
 // ---------------------------------------------------------------------------------------
 // Scalar loads under manual control.
 //

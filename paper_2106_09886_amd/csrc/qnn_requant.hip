@@ -26,7 +26,9 @@ __device__ __forceinline__ int round_odd(float y) {
     return (y > 0.0f) ? (int)c : -(int)c;
 }
 
-template <typename CodeT, int BITS, bool POOL>
+// U work items (pixel, 64-channel group) per loop trip: all their loads are issued before any
+// is consumed, so that a wavefront keeps U (4U with pooling) 256-byte rows in flight.
+template <typename CodeT, int BITS, bool POOL, int U>
 __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restrict__ y, int64_t out_pixels,
                                                            int Ho, int Wo, int C,
                                                            CodeT *__restrict__ codes,
@@ -36,42 +38,75 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
     const int cgroups = (C + 63) / 64;
     const int Cw = (C + 31) / 32;
     const int64_t items = out_pixels * cgroups;
-    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) +
+                          __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // wave-uniform
     const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
-    for (int64_t it = wave0; it < items; it += nwaves) {
-        const int64_t pix = it / cgroups;
-        const int cg = (int)(it - pix * cgroups);
-        const int c = cg * 64 + lane;
-        const bool valid = c < C;
-        float v = 0.0f;
-        if (valid) {
-            if (POOL) {
-                const int64_t n = pix / ((int64_t)Ho * Wo);
-                const int64_t rem = pix - n * (int64_t)Ho * Wo;
-                const int oh = (int)(rem / Wo), ow = (int)(rem - (int64_t)oh * Wo);
-                const int W = 2 * Wo;
-                const float *p00 = y + (((n * 2 * Ho + 2 * oh) * W) + 2 * ow) * (int64_t)C + c;
-                v = p00[0];
-                const float v01 = p00[C], v10 = p00[(int64_t)W * C], v11 = p00[(int64_t)W * C + C];
-                if (v01 > v) v = v01;
-                if (v10 > v) v = v10;
-                if (v11 > v) v = v11;
-            } else {
-                v = y[pix * (int64_t)C + c];
+    for (int64_t it0 = wave0 * U; it0 < items; it0 += nwaves * U) {
+        float v[U];
+        int64_t pix[U];
+        int cg[U];
+        bool valid[U];
+        // position of the first item, by division once per trip; the following items step from it
+        int64_t cur_pix = it0 / cgroups;
+        int cur_cg = (int)(it0 - cur_pix * cgroups);
+        int64_t cur_n = 0;
+        int cur_oh = 0, cur_ow = 0;
+        if (POOL) {
+            cur_n = cur_pix / ((int64_t)Ho * Wo);
+            const int64_t rem = cur_pix - cur_n * (int64_t)Ho * Wo;
+            cur_oh = (int)(rem / Wo);
+            cur_ow = (int)(rem - (int64_t)cur_oh * Wo);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool item_ok = it0 + u < items;
+            pix[u] = cur_pix;
+            cg[u] = cur_cg;
+            const int c = cur_cg * 64 + lane;
+            valid[u] = item_ok && c < C;
+            v[u] = 0.0f;
+            if (valid[u]) {
+                if (POOL) {
+                    const int W = 2 * Wo;
+                    const float *p00 = y + (((cur_n * 2 * Ho + 2 * cur_oh) * W) + 2 * cur_ow) * (int64_t)C + c;
+                    float m = p00[0];
+                    const float v01 = p00[C], v10 = p00[(int64_t)W * C], v11 = p00[(int64_t)W * C + C];
+                    if (v01 > m) m = v01;
+                    if (v10 > m) m = v10;
+                    if (v11 > m) m = v11;
+                    v[u] = m;
+                } else {
+                    v[u] = y[cur_pix * (int64_t)C + c];
+                }
+            }
+            if (++cur_cg == cgroups) {                       // next item
+                cur_cg = 0;
+                ++cur_pix;
+                if (POOL && ++cur_ow == Wo) {
+                    cur_ow = 0;
+                    if (++cur_oh == Ho) { cur_oh = 0; ++cur_n; }
+                }
             }
         }
-        const int code = round_odd<BITS>(v);
-        if (codes != nullptr && valid) codes[pix * (int64_t)C + c] = (CodeT)code;
-        if (planes != nullptr) {
-            const int u = (code + VMAX) >> 1;
-            uint32_t *dst = planes + pix * (int64_t)BITS * Cw + 2 * cg;
 #pragma unroll
-            for (int p = 0; p < BITS; ++p) {
-                const uint64_t mask = __ballot(valid && ((u >> p) & 1));
-                if (lane == 0) {
-                    dst[(int64_t)p * Cw] = (uint32_t)mask;
-                    if (2 * cg + 1 < Cw) dst[(int64_t)p * Cw + 1] = (uint32_t)(mask >> 32);
+        for (int u = 0; u < U; ++u) {
+            if (it0 + u >= items) break;                    // wave-uniform
+            const int code = round_odd<BITS>(v[u]);
+            const int c = cg[u] * 64 + lane;
+            if (codes != nullptr && valid[u]) codes[pix[u] * (int64_t)C + c] = (CodeT)code;
+            if (planes != nullptr) {
+                const int uidx = (code + VMAX) >> 1;
+                // lane 2p holds the low word of plane p, lane 2p+1 the high word: one store for all
+                uint32_t mine = 0u;
+#pragma unroll
+                for (int p = 0; p < BITS; ++p) {
+                    const uint64_t mask = __ballot(valid[u] && ((uidx >> p) & 1));
+                    if (lane == 2 * p) mine = (uint32_t)mask;
+                    if (lane == 2 * p + 1) mine = (uint32_t)(mask >> 32);
                 }
+                const int p = lane >> 1, h = lane & 1;
+                if (lane < 2 * BITS && 2 * cg[u] + h < Cw)
+                    planes[(pix[u] * BITS + p) * (int64_t)Cw + 2 * cg[u] + h] = mine;
             }
         }
     }
@@ -81,10 +116,10 @@ template <typename CodeT, int BITS>
 hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, void *codes,
                      uint32_t *planes, unsigned blocks, hipStream_t s) {
     if (pool)
-        hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true>), dim3(blocks), dim3(256), 0, s, y,
+        hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, (CodeT *)codes, planes);
     else
-        hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false>), dim3(blocks), dim3(256), 0, s, y,
+        hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, (CodeT *)codes, planes);
     return hipGetLastError();
 }
@@ -97,8 +132,10 @@ hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int6
     const int64_t out_pixels = Nb * Ho * (int64_t)Wo;
     const int64_t items = out_pixels * ((C + 63) / 64);
     if (items == 0) return hipSuccess;
+    // about 8 wavefronts per SIMD, each looping over its share of the items
     const int64_t want = (items + 3) / 4;
-    const unsigned blocks = (unsigned)(want < (int64_t)1 << 18 ? want : (int64_t)1 << 18);
+    const int64_t cap = (int64_t)device_simd_count() * 2;
+    const unsigned blocks = (unsigned)(want < cap ? want : cap);
 #define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, out_pixels, Ho, Wo, (int)C, pool, codes, planes, blocks, s)
     switch (bits) {
         QNN_RQ(1, int8_t); QNN_RQ(2, int8_t); QNN_RQ(3, int8_t); QNN_RQ(4, int8_t);

@@ -84,7 +84,14 @@ WORKLOADS = {
     # ResNet-50 stage-3 shaped 3x3 conv, 4-bit activations, 3-bit weights
     "resnet50_s3": Conv("resnet50_s3", 64, 14, 14, 256, 256, 4, 3, "uniform", None, None, None,
                         (1004, 2004, 3004)),
+    # the matrix product of the paper's efficiency experiment (Sec. 5.4): 8192 x 8192 x 8192
+    "gemm8192": Gemm("gemm8192", 8192, 8192, 8192, 2, 2, "uniform", None, None, None, (1006, 2006, 3006)),
 }
+
+
+def with_bits(w, bits):
+    """The same GEMM workload with `bits`-bit activations and weights."""
+    return w._replace(ab=bits, wb=bits, name="%s_w%da%d" % (w.name, bits, bits))
 
 
 def make_gemm(w, M=None):

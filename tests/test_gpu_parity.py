@@ -159,6 +159,26 @@ def test_gemm_config2_full(q, oracle):
     run_gemm(q, oracle, A, W, w.ab, w.wb, s)
 
 
+@pytest.mark.parametrize("bits", [1, 2, 4])
+def test_gemm_8192_sampled_rows(q, oracle, bits):
+    """The paper's efficiency workload (Sec. 5.4), 8192^3, in the launch shape the bench times;
+    the oracle recomputes sampled rows (every column of each)."""
+    from paper_2106_09886_amd import inputs
+    w = inputs.with_bits(inputs.WORKLOADS["gemm8192"], bits)
+    A, W, _ = inputs.make_gemm(w)
+    say("gemm8192 bits", bits)
+    Ap = q.encode_pack(dev(A), bits)
+    Wp = q.encode_pack(dev(np.ascontiguousarray(W.T)), bits)
+    acc, _ = q.branch_gemm(Ap, bits, Wp, bits, w.K)
+    got = host(acc)
+    rows = np.array([0, 1, 63, 64, 4095, 4096, 5000, 8190, 8191, 777, 3210, 6543])
+    want = oracle.gemm(A[rows], W)
+    assert (got[rows].astype(np.int64) == want).all()
+    # properties that hold for every element: parity of K odd*odd products and the magnitude bound
+    m = (1 << bits) - 1
+    assert ((got.astype(np.int64) - w.K) % 2 == 0).all() and (np.abs(got) <= w.K * m * m).all()
+
+
 # ------------------------------------------------------------------ convolution
 def run_conv(q, oracle, X, Wt, ab, wb, s=None, packed_too=True):
     Nb, H, W, C = X.shape
