@@ -157,6 +157,52 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
                             int bits, void *codes, uint32_t *planes, void *stream);
 
 /*
+ * Chained layers (Alg. 1 forward as one kernel: branch sum, scale, re-encode).  The *_requant
+ * variants of the three product entry points compute the same int32 product, multiply by
+ * scale[n] (scale == NULL: y = (float)acc), map y to the odd code grid of out_bits bits with the
+ * rule of qnn_requant_pack, and write the result as the next layer's activation planes
+ *   out_planes  uint32 [rows][out_bits][ceil(N/32)]   (rows = M, or Nb*H*W; N = Cout), 16-byte
+ *               aligned, in the bit-plane layout above — exactly what qnn_requant_pack would
+ *               produce from out_f32 without pooling.
+ * acc and out_f32 are optional extra outputs (out_f32 needs scale).  If neither is given the
+ * caller passes a workspace of qnn_requant_workspace_bytes(rows, N) bytes (16-byte aligned) that
+ * holds partial sums of products done in several passes; qnn_conv2d_im2col_requant takes ONE
+ * workspace of qnn_conv2d_im2col_requant_workspace_bytes() bytes for both purposes.
+ * Other arguments, limits and errors as for the plain entry points; additionally
+ * rows * out_bits * ceil(N/32) < 2^30.
+ */
+size_t qnn_requant_workspace_bytes(int64_t rows, int64_t N);
+
+qnn_status qnn_branch_gemm_requant(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M,
+                                   int64_t N, int64_t K, const float *scale, int out_bits,
+                                   uint32_t *out_planes, int32_t *acc, float *out_f32, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+qnn_status qnn_conv2d_packed_requant(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb,
+                                     int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                                     const float *scale, int out_bits, uint32_t *out_planes,
+                                     int32_t *acc, float *out_f32, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+size_t qnn_conv2d_im2col_requant_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int ab,
+                                                 int64_t Cout);
+
+qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt,
+                                     int wb, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                                     const float *scale, int out_bits, uint32_t *out_planes,
+                                     int32_t *acc, float *out_f32, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+/*
+ * 2x2 max-pool (stride 2) of activations that are already bit planes: planes uint32
+ * [Nb*H*W][bits][ceil(C/32)] -> out_planes [Nb*(H/2)*(W/2)][bits][ceil(C/32)], H and W even.
+ * The re-encoding rule is monotone, so pooling the codes equals re-encoding the pooled values
+ * (Alg. 1 places the encoder after the layer's output; a pooling layer commutes with it).
+ */
+qnn_status qnn_maxpool2x2_planes(const uint32_t *planes, int64_t Nb, int64_t H, int64_t W, int64_t C,
+                                 int bits, uint32_t *out_planes, void *stream);
+
+/*
  * Stand-alone scale epilogue (Eq. (9); Eq. (19)): out_f32[i][j] = (float)acc[i][j] * scale[j],
  * acc int32 [M][N], scale fp32 [N], out fp32 [M][N].  One IEEE binary32 multiply per
  * element, no fused multiply-add.  M == 0 or N == 0 launches nothing.

@@ -22,6 +22,8 @@ EXPORTS = (
     "qnn_encode_pack",
     "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col",
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
+    "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
+    "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
 )
 
 
@@ -71,6 +73,20 @@ def lib():
     L.qnn_requant_pack.restype = i32
     L.qnn_scale_epilogue.argtypes = [vp, i64, i64, vp, vp, vp]
     L.qnn_scale_epilogue.restype = i32
+    L.qnn_requant_workspace_bytes.argtypes = [i64, i64]
+    L.qnn_requant_workspace_bytes.restype = sz
+    L.qnn_branch_gemm_requant.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.qnn_branch_gemm_requant.restype = i32
+    L.qnn_conv2d_packed_requant.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, i64, vp, i32, vp, vp, vp, vp,
+                                            sz, vp]
+    L.qnn_conv2d_packed_requant.restype = i32
+    L.qnn_conv2d_im2col_requant_workspace_bytes.argtypes = [i64, i64, i64, i64, i32, i64]
+    L.qnn_conv2d_im2col_requant_workspace_bytes.restype = sz
+    L.qnn_conv2d_im2col_requant.argtypes = [vp, i32, i32, vp, i32, i64, i64, i64, i64, i64, vp, i32, vp, vp, vp,
+                                            vp, sz, vp]
+    L.qnn_conv2d_im2col_requant.restype = i32
+    L.qnn_maxpool2x2_planes.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp]
+    L.qnn_maxpool2x2_planes.restype = i32
     _lib = L
     return L
 
@@ -211,4 +227,78 @@ def scale_epilogue(acc, scale):
     M = acc.numel() // N if N else 0
     out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
     _check(lib().qnn_scale_epilogue(_ptr(acc), M, N, _ptr(scale), _ptr(out), _stream()), "qnn_scale_epilogue")
+    return out
+
+
+def _requant_outputs(rows_shape, N, device, scale, out_bits, want_acc, want_f32):
+    rows = 1
+    for d in rows_shape:
+        rows *= d
+    planes = torch.empty((rows, out_bits, (N + 31) // 32), dtype=torch.int32, device=device)
+    acc = torch.empty(tuple(rows_shape) + (N,), dtype=torch.int32, device=device) if want_acc else None
+    o32 = torch.empty(tuple(rows_shape) + (N,), dtype=torch.float32, device=device) if want_f32 else None
+    if want_f32 and scale is None:
+        raise ValueError("the fp32 output needs a scale")
+    return planes, acc, o32, rows
+
+
+def branch_gemm_requant(A, ab, Wt, wb, K, out_bits, scale=None, want_acc=False, want_f32=False):
+    """GEMM + scale + re-encode: -> (planes int32 [M][out_bits][Nw], acc | None, out fp32 | None)."""
+    _dev(A, torch.int32, "A")
+    _dev(Wt, torch.int32, "Wt")
+    M, N = A.shape[0], Wt.shape[0]
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    planes, acc, o32, rows = _requant_outputs((M,), N, A.device, scale, out_bits, want_acc, want_f32)
+    ws = None
+    if acc is None and o32 is None:
+        ws = torch.empty(max(16, int(lib().qnn_requant_workspace_bytes(rows, N))), dtype=torch.uint8, device=A.device)
+    st = lib().qnn_branch_gemm_requant(_ptr(A), ab, _ptr(Wt), wb, M, N, K, _ptr(scale), out_bits, _ptr(planes),
+                                       _ptr(acc), _ptr(o32), _ptr(ws), 0 if ws is None else ws.numel(), _stream())
+    _check(st, "qnn_branch_gemm_requant")
+    return planes, acc, o32
+
+
+def conv2d_packed_requant(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, out_bits, scale=None, want_acc=False,
+                          want_f32=False):
+    """3x3 conv from packed planes + scale + re-encode -> (planes [Nb*H*W][out_bits][CoutW], acc, out)."""
+    _dev(x_planes, torch.int32, "x_planes")
+    _dev(Wt, torch.int32, "Wt")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    planes, acc, o32, rows = _requant_outputs((Nb, H, W), Cout, x_planes.device, scale, out_bits, want_acc, want_f32)
+    ws = None
+    if acc is None and o32 is None:
+        ws = torch.empty(max(16, int(lib().qnn_requant_workspace_bytes(rows, Cout))), dtype=torch.uint8,
+                         device=x_planes.device)
+    st = lib().qnn_conv2d_packed_requant(_ptr(x_planes), ab, _ptr(Wt), wb, Nb, H, W, C, Cout, _ptr(scale), out_bits,
+                                         _ptr(planes), _ptr(acc), _ptr(o32), _ptr(ws),
+                                         0 if ws is None else ws.numel(), _stream())
+    _check(st, "qnn_conv2d_packed_requant")
+    return planes, acc, o32
+
+
+def conv2d_im2col_requant(x_codes, ab, Wt, wb, Cout, out_bits, scale=None, want_acc=False, want_f32=False):
+    """3x3 conv from codes + scale + re-encode -> (planes [Nb*H*W][out_bits][CoutW], acc, out)."""
+    _dev(x_codes, x_codes.dtype, "x_codes")
+    _dev(Wt, torch.int32, "Wt")
+    Nb, H, W, C = x_codes.shape
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    planes, acc, o32, rows = _requant_outputs((Nb, H, W), Cout, x_codes.device, scale, out_bits, want_acc, want_f32)
+    need = int(lib().qnn_conv2d_im2col_requant_workspace_bytes(Nb, H, W, C, ab, Cout))
+    ws = torch.empty(max(16, need), dtype=torch.uint8, device=x_codes.device)
+    st = lib().qnn_conv2d_im2col_requant(_ptr(x_codes), x_codes.element_size(), ab, _ptr(Wt), wb, Nb, H, W, C, Cout,
+                                         _ptr(scale), out_bits, _ptr(planes), _ptr(acc), _ptr(o32), _ptr(ws),
+                                         ws.numel(), _stream())
+    _check(st, "qnn_conv2d_im2col_requant")
+    return planes, acc, o32
+
+
+def maxpool2x2_planes(planes, Nb, H, W, C, bits):
+    """planes int32 [Nb*H*W][bits][Cw] -> [Nb*(H/2)*(W/2)][bits][Cw]."""
+    _dev(planes, torch.int32, "planes")
+    out = torch.empty((Nb * (H // 2) * (W // 2), bits, (C + 31) // 32), dtype=torch.int32, device=planes.device)
+    st = lib().qnn_maxpool2x2_planes(_ptr(planes), Nb, H, W, C, bits, _ptr(out), _stream())
+    _check(st, "qnn_maxpool2x2_planes")
     return out

@@ -108,13 +108,39 @@ int clamp_rows_per_wave(int rpw, int64_t N) {
 
 // Checks shared by the GEMM and convolution entry points.  k_tap = true inner length of one
 // tap (K for GEMM, C for conv), taps = 1 or 9.
+// The re-encoded output of a chained layer: planes of out_bits bits, or nothing (planes == nullptr).
+// Without an int32 / fp32 result buffer the partial sums of a multi-pass product need a workspace.
+struct Emit {
+    uint32_t *planes;
+    int bits;
+    void *workspace;
+    size_t workspace_bytes;
+};
+const Emit kNoEmit = {nullptr, 0, nullptr, 0};
+
 qnn_status check_branch(const void *A, int ab, const void *Wt, int wb, int64_t rows, int64_t N,
-                        int64_t k_tap, int taps, const void *acc, const void *scale, const void *out) {
+                        int64_t k_tap, int taps, const void *acc, const void *scale, const void *out,
+                        const Emit &e = kNoEmit) {
     if (!bits_ok(ab) || !bits_ok(wb)) return QNN_EINVAL;
     if (rows < 0 || N < 0 || k_tap < 0) return QNN_EINVAL;
-    if ((scale == nullptr) != (out == nullptr)) return QNN_EINVAL;
+    const bool emit = e.bits != 0;                     // a *_requant entry point
+    if (emit) {
+        if (!bits_ok(e.bits)) return QNN_EINVAL;
+        if (out != nullptr && scale == nullptr) return QNN_EINVAL;
+    } else if ((scale == nullptr) != (out == nullptr)) {
+        return QNN_EINVAL;
+    }
     if (rows == 0 || N == 0) return QNN_OK;            // empty output: nothing is dereferenced
-    if (acc == nullptr && out == nullptr) return QNN_EINVAL;
+    if (emit) {
+        if (e.planes == nullptr) return QNN_EINVAL;
+        if (!aligned16(e.planes)) return QNN_EALIGN;
+        if (acc == nullptr && out == nullptr) {
+            if (e.workspace == nullptr) return QNN_EINVAL;
+            if (!aligned16(e.workspace)) return QNN_EALIGN;
+        }
+    } else if (acc == nullptr && out == nullptr) {
+        return QNN_EINVAL;
+    }
     if ((A == nullptr || Wt == nullptr) && k_tap > 0) return QNN_EINVAL;
     if (!aligned16(A) || !aligned16(Wt)) return QNN_EALIGN;
     if (!aligned4(acc) || !aligned4(scale) || !aligned4(out)) return QNN_EALIGN;
@@ -126,7 +152,130 @@ qnn_status check_branch(const void *A, int ab, const void *Wt, int wb, int64_t r
     const int64_t kWords30 = ((int64_t)1 << 30) - 1;
     if (rows > kInt31 || N > ((int64_t)1 << 24)) return QNN_EUNSUPPORTED;
     if (cw > 0 && (rows > kWords30 / (ab * cw) || N > kWords30 / (wb * cw * taps))) return QNN_EUNSUPPORTED;
+    if (emit) {
+        if (rows > kWords30 / (e.bits * ((N + 31) / 32))) return QNN_EUNSUPPORTED;
+        if (acc == nullptr && out == nullptr && e.workspace_bytes < (size_t)(rows * N * 4)) return QNN_EWORKSPACE;
+    }
     return QNN_OK;
+}
+
+// where the partial sums of a multi-pass product live
+int32_t *partial_buffer(int32_t *acc, float *out, const Emit &e) {
+    return acc ? acc : out ? reinterpret_cast<int32_t *>(out) : static_cast<int32_t *>(e.workspace);
+}
+
+// A wavefront's slice of the emitted planes (rows_per_wave * out_bits * Nw * 4 bytes) must stay
+// below 2^31 bytes as well.
+int clamp_rows_for_emit(int rpw, int64_t N, const Emit &e) {
+    if (e.bits == 0) return rpw;
+    const int64_t cap = (((int64_t)1 << 29) - 1) / (e.bits * ((N + 31) / 32));
+    if (rpw > cap) rpw = (int)(cap < 1 ? 1 : cap);
+    return rpw;
+}
+
+qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M, int64_t N, int64_t K,
+                    int32_t *acc, const float *scale, float *out_f32, const Emit &e, void *stream) {
+    qnn_status st = check_branch(A, ab, Wt, wb, M, N, K, 1, acc, scale, out_f32, e);
+    if (st != QNN_OK || M == 0 || N == 0) return st;
+    BranchArgs g;
+    g.A = A; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+    g.partial = partial_buffer(acc, out_f32, e);
+    g.planes_out = e.planes; g.out_bits = e.bits;
+    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1; g.C = 0;
+    g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+    g.col_tiles = (int)((N + 63) / 64);
+    g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
+    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N), N, e);
+    g.split_k = 0;
+    // Long K and too few rows for every wavefront to amortise its weight chunks: let the four
+    // wavefronts of a block share rows and split the chunks instead.
+    const int chunks = (g.Cw + gemm_chunk_words(wb) - 1) / gemm_chunk_words(wb);
+    if (chunks >= 4 && g.rows_per_wave < 16 && tuning().rows_per_wave == 0) {
+        const int64_t target_blocks = (int64_t)device_simd_count();          // 4 blocks (16 wavefronts) per CU
+        int64_t rows_per_block = (M * g.col_tiles + target_blocks - 1) / target_blocks;
+        if (rows_per_block < 8) rows_per_block = 8;
+        if (rows_per_block > 32) rows_per_block = 32;
+        if (rows_per_block > M) rows_per_block = M;
+        g.split_k = 1;
+        g.rows_per_wave = (int)rows_per_block;
+    }
+    return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
+}
+
+qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout) {
+    if (Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
+    if (H > kInt31 || W > kInt31 || Nb > kInt31) return QNN_EUNSUPPORTED;
+    if (H > 0 && W > 0 && Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
+    return QNN_OK;
+}
+
+qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
+                           int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
+                           float *out_f32, const Emit &e, void *stream) {
+    qnn_status st = check_image(Nb, H, W, C, Cout);
+    if (st != QNN_OK) return st;
+    const int64_t rows = Nb * H * W;
+    st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32, e);
+    if (st != QNN_OK || rows == 0 || Cout == 0) return st;
+    BranchArgs g;
+    g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+    g.partial = partial_buffer(acc, out_f32, e);
+    g.planes_out = e.planes; g.out_bits = e.bits;
+    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
+    g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+    g.col_tiles = (int)((Cout + 63) / 64);
+    g.split_k = 0;
+    g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
+    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles), Cout),
+                                          Cout, e);
+    return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
+}
+
+qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
+                           int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
+                           float *out_f32, void *workspace, size_t workspace_bytes, const Emit &e,
+                           void *stream) {
+    qnn_status st = check_image(Nb, H, W, C, Cout);
+    if (st != QNN_OK) return st;
+    if (code_bytes != 1 && code_bytes != 2) return QNN_EINVAL;
+    if (code_bytes == 1 && ab == 8) return QNN_EINVAL;
+    const int64_t rows = Nb * H * W;
+    uint32_t *planes = static_cast<uint32_t *>(workspace);
+    // validate everything before the first launch, so that an error launches nothing
+    const bool have_k = C > 0;
+    if (have_k && rows > 0 && Cout > 0) {
+        if (x_codes == nullptr || workspace == nullptr) return QNN_EINVAL;
+        if (!aligned16(workspace)) return QNN_EALIGN;
+        if (code_bytes == 2 && (((uintptr_t)x_codes) & 1u)) return QNN_EALIGN;
+    }
+    st = check_branch(planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32, e);
+    if (st != QNN_OK) return st;
+    if (rows == 0 || Cout == 0) return QNN_OK;
+    if (have_k) {
+        if (workspace_bytes < qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab)) return QNN_EWORKSPACE;
+        if (9 * C <= 32) {
+            // few input channels: one im2col word per plane and pixel (same workspace size as the
+            // per-pixel planes, Cw == 1), then the single-word branch kernel
+            st = from_hip(k_im2col[ab - 1](x_codes, code_bytes, rows, (int)H, (int)W, (int)C, planes,
+                                           (hipStream_t)stream));
+            if (st != QNN_OK) return st;
+            BranchArgs g;
+            g.A = planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+            g.partial = partial_buffer(acc, out_f32, e);
+            g.planes_out = e.planes; g.out_bits = e.bits;
+            g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
+            g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+            g.col_tiles = (int)((Cout + 63) / 64);
+            g.split_k = 0;
+            g.trace = nullptr; g.trace_waves = 0;
+            g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
+                                                  Cout, e);
+            return from_hip(k_conv_small[ab - 1](g, wb, (hipStream_t)stream));
+        }
+        st = qnn_encode_pack(x_codes, code_bytes, rows, C, ab, planes, nullptr, 0, stream);
+        if (st != QNN_OK) return st;
+    }
+    return run_conv_packed(planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream);
 }
 
 }  // namespace
@@ -189,30 +338,7 @@ qnn_status qnn_encode_pack(const void *codes, int code_bytes, int64_t rows, int6
 
 qnn_status qnn_branch_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M, int64_t N,
                            int64_t K, int32_t *acc, const float *scale, float *out_f32, void *stream) {
-    qnn_status st = check_branch(A, ab, Wt, wb, M, N, K, 1, acc, scale, out_f32);
-    if (st != QNN_OK || M == 0 || N == 0) return st;
-    BranchArgs g;
-    g.A = A; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
-    g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
-    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1; g.C = 0;
-    g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
-    g.col_tiles = (int)((N + 63) / 64);
-    g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
-    g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N);
-    g.split_k = 0;
-    // Long K and too few rows for every wavefront to amortise its weight chunks: let the four
-    // wavefronts of a block share rows and split the chunks instead.
-    const int chunks = (g.Cw + gemm_chunk_words(wb) - 1) / gemm_chunk_words(wb);
-    if (chunks >= 4 && g.rows_per_wave < 16 && tuning().rows_per_wave == 0) {
-        const int64_t target_blocks = (int64_t)device_simd_count();          // 4 blocks (16 wavefronts) per CU
-        int64_t rows_per_block = (M * g.col_tiles + target_blocks - 1) / target_blocks;
-        if (rows_per_block < 8) rows_per_block = 8;
-        if (rows_per_block > 32) rows_per_block = 32;
-        if (rows_per_block > M) rows_per_block = M;
-        g.split_k = 1;
-        g.rows_per_wave = (int)rows_per_block;
-    }
-    return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
+    return run_gemm(A, ab, Wt, wb, M, N, K, acc, scale, out_f32, kNoEmit, stream);
 }
 
 size_t qnn_conv2d_im2col_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int ab) {
@@ -224,68 +350,61 @@ size_t qnn_conv2d_im2col_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64
 qnn_status qnn_conv2d_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
                              int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc,
                              const float *scale, float *out_f32, void *stream) {
-    if (Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
-    if (H > kInt31 || W > kInt31 || Nb > kInt31) return QNN_EUNSUPPORTED;
-    if (H > 0 && W > 0 && Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
-    const int64_t rows = Nb * H * W;
-    qnn_status st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32);
-    if (st != QNN_OK || rows == 0 || Cout == 0) return st;
-    BranchArgs g;
-    g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
-    g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
-    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
-    g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
-    g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0;
-    g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
-    g.rows_per_wave = clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles), Cout);
-    return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
+    return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, kNoEmit, stream);
 }
 
 qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt, int wb,
                              int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc,
                              const float *scale, float *out_f32, void *workspace,
                              size_t workspace_bytes, void *stream) {
-    if (Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
-    if (code_bytes != 1 && code_bytes != 2) return QNN_EINVAL;
-    if (code_bytes == 1 && ab == 8) return QNN_EINVAL;
-    if (H > kInt31 || W > kInt31 || Nb > kInt31) return QNN_EUNSUPPORTED;
-    if (H > 0 && W > 0 && Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
-    const int64_t rows = Nb * H * W;
-    uint32_t *planes = static_cast<uint32_t *>(workspace);
-    // validate everything before the first launch, so that an error launches nothing
-    const bool have_k = C > 0;
-    if (have_k && rows > 0 && Cout > 0) {
-        if (x_codes == nullptr || workspace == nullptr) return QNN_EINVAL;
-        if (!aligned16(workspace)) return QNN_EALIGN;
-        if (code_bytes == 2 && (((uintptr_t)x_codes) & 1u)) return QNN_EALIGN;
+    return run_conv_im2col(x_codes, code_bytes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, workspace,
+                           workspace_bytes, kNoEmit, stream);
+}
+
+size_t qnn_requant_workspace_bytes(int64_t rows, int64_t N) {
+    if (rows <= 0 || N <= 0) return 0;
+    return (size_t)(rows * N * 4);
+}
+
+qnn_status qnn_branch_gemm_requant(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M, int64_t N,
+                                   int64_t K, const float *scale, int out_bits, uint32_t *out_planes,
+                                   int32_t *acc, float *out_f32, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+    if (!bits_ok(out_bits)) return QNN_EINVAL;
+    const Emit e = {out_planes, out_bits, workspace, workspace_bytes};
+    return run_gemm(A, ab, Wt, wb, M, N, K, acc, scale, out_f32, e, stream);
+}
+
+qnn_status qnn_conv2d_packed_requant(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
+                                     int64_t H, int64_t W, int64_t C, int64_t Cout, const float *scale,
+                                     int out_bits, uint32_t *out_planes, int32_t *acc, float *out_f32,
+                                     void *workspace, size_t workspace_bytes, void *stream) {
+    if (!bits_ok(out_bits)) return QNN_EINVAL;
+    const Emit e = {out_planes, out_bits, workspace, workspace_bytes};
+    return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream);
+}
+
+size_t qnn_conv2d_im2col_requant_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int ab,
+                                                 int64_t Cout) {
+    const size_t a = (qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab) + 15) & ~(size_t)15;
+    return a + qnn_requant_workspace_bytes(Nb * H * W, Cout);
+}
+
+qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt, int wb,
+                                     int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                                     const float *scale, int out_bits, uint32_t *out_planes, int32_t *acc,
+                                     float *out_f32, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!bits_ok(out_bits)) return QNN_EINVAL;
+    if (check_image(Nb, H, W, C, Cout) != QNN_OK || !bits_ok(ab)) return QNN_EINVAL;
+    // the workspace holds the packed activations first, then (16-byte aligned) the partial sums
+    const size_t first = (qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab) + 15) & ~(size_t)15;
+    Emit e = {out_planes, out_bits, nullptr, 0};
+    if (workspace != nullptr) {
+        e.workspace = static_cast<char *>(workspace) + first;
+        e.workspace_bytes = workspace_bytes > first ? workspace_bytes - first : 0;
     }
-    qnn_status st = check_branch(planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32);
-    if (st != QNN_OK) return st;
-    if (rows == 0 || Cout == 0) return QNN_OK;
-    if (have_k) {
-        if (workspace_bytes < qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab)) return QNN_EWORKSPACE;
-        if (9 * C <= 32) {
-            // few input channels: one im2col word per plane and pixel (same workspace size as the
-            // per-pixel planes, Cw == 1), then the single-word branch kernel
-            st = from_hip(k_im2col[ab - 1](x_codes, code_bytes, rows, (int)H, (int)W, (int)C, planes,
-                                           (hipStream_t)stream));
-            if (st != QNN_OK) return st;
-            BranchArgs g;
-            g.A = planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
-            g.partial = acc ? acc : reinterpret_cast<int32_t *>(out_f32);
-            g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
-            g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
-            g.col_tiles = (int)((Cout + 63) / 64);
-            g.split_k = 0;
-            g.trace = nullptr; g.trace_waves = 0;
-            g.rows_per_wave = clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout);
-            return from_hip(k_conv_small[ab - 1](g, wb, (hipStream_t)stream));
-        }
-        st = qnn_encode_pack(x_codes, code_bytes, rows, C, ab, planes, nullptr, 0, stream);
-        if (st != QNN_OK) return st;
-    }
-    return qnn_conv2d_packed(planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, stream);
+    return run_conv_im2col(x_codes, code_bytes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, workspace,
+                           workspace_bytes < first ? workspace_bytes : first, e, stream);
 }
 
 qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, int pool2x2, int bits,
@@ -300,6 +419,20 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
     if (!aligned4(y) || !aligned16(planes)) return QNN_EALIGN;
     if (bits == 8 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
     return from_hip(launch_requant(y, Nb, H, W, C, pool2x2 != 0, bits, codes, planes, (hipStream_t)stream));
+}
+
+qnn_status qnn_maxpool2x2_planes(const uint32_t *planes, int64_t Nb, int64_t H, int64_t W, int64_t C, int bits,
+                                 uint32_t *out_planes, void *stream) {
+    if (!bits_ok(bits) || Nb < 0 || H < 0 || W < 0 || C < 0) return QNN_EINVAL;
+    if ((H & 1) || (W & 1)) return QNN_EINVAL;
+    if (H > kInt31 || W > kInt31 || Nb > kInt31 || C > kInt31) return QNN_EUNSUPPORTED;
+    if (Nb == 0 || H == 0 || W == 0 || C == 0) return QNN_OK;
+    if (Nb > kInt31 / H / W) return QNN_EUNSUPPORTED;
+    if (planes == nullptr || out_planes == nullptr) return QNN_EINVAL;
+    if (!aligned16(planes) || !aligned16(out_planes)) return QNN_EALIGN;
+    const int64_t cw = (C + 31) / 32;
+    if (Nb * H * W > (((int64_t)1 << 40) - 1) / (bits * cw)) return QNN_EUNSUPPORTED;
+    return from_hip(launch_pool_planes(planes, Nb, H / 2, W / 2, cw, bits, out_planes, (hipStream_t)stream));
 }
 
 qnn_status qnn_scale_epilogue(const int32_t *acc, int64_t M, int64_t N, const float *scale,

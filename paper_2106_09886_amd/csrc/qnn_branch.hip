@@ -35,61 +35,6 @@ __device__ __forceinline__ int weighted_sum(const int (&part)[NP]) {
     return s;
 }
 
-// ---------------------------------------------------------------------------------------
-// Output addressing: buffer descriptors (base in SGPRs, wave-uniform byte offset in an SGPR,
-// the lane's column offset in a VGPR).  A descriptor covers the rows of one wavefront.
-// ---------------------------------------------------------------------------------------
-struct OutView {
-    __amdgpu_buffer_rsrc_t d0;   // int32 result if requested, else the fp32 result; also holds partial sums
-    __amdgpu_buffer_rsrc_t d1;   // the fp32 result when both outputs are requested
-    uint32_t flags;              // bit 0: int32 result requested, bit 1: fp32 result requested
-    uint32_t row_bytes;          // N * 4
-    int col_bytes;               // lane's column * 4.  Lanes past N compute column N-1 again (same
-                                 // weights, same scale) and store the identical value to it, so
-                                 // the epilogue needs no lane mask
-    float sc;
-};
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t bytes) {
-    // raw dword buffer: stride 0, num_records in bytes, 32-bit data format word for gfx9
-    return __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, 0x00020000);
-}
-
-__device__ __forceinline__ OutView make_out_view(const BranchArgs &g, int r0, int r1, int nload, float sc) {
-    OutView v;
-    const int64_t first = (int64_t)r0 * g.N;
-    const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;    // < 2^31, checked on the host
-    v.flags = (g.acc != nullptr ? 1u : 0u) | (g.out != nullptr ? 2u : 0u);
-    v.d0 = make_rsrc((void *)(g.partial + first), bytes);               // partial == acc if present, else out
-    v.d1 = make_rsrc((v.flags & 2u) ? (void *)(g.out + first) : (void *)(g.partial + first), bytes);
-    v.row_bytes = (uint32_t)g.N * 4u;
-    v.col_bytes = nload * 4;
-    v.sc = sc;
-    return v;
-}
-
-// Finish one row of one chunk pass for this lane's column.  rel_row = row - r0.  SINGLE: the
-// product has a single chunk pass (first and last are both true at compile time).
-template <bool SINGLE>
-__device__ __forceinline__ void finish_row(const OutView &v, int rel_row, int val, bool first, bool last) {
-    const int soff = (int)((uint32_t)rel_row * v.row_bytes);
-    if constexpr (!SINGLE) {
-        if (!first) val += __builtin_amdgcn_raw_buffer_load_b32(v.d0, v.col_bytes, soff, 0);
-        if (!last) {
-            __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
-            return;
-        }
-    }
-    const float y = (float)val * v.sc;
-    if (v.flags & 1u) {
-        __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
-        if (v.flags & 2u) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d1, v.col_bytes, soff, 0);
-    } else {
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
-    }
-}
-
-
 // Position of a wavefront.  Consecutive wavefronts (the four of a block first) take
 // consecutive column tiles of the SAME row block: they request the same activation words, which
 // then hit in the scalar cache, while each loads its own weight tile once.
@@ -266,8 +211,9 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
     }
 }
 
-template <int AB, int WB, int SEGS, int CWT>
+template <int AB, int WB, int SEGS, int CWT, bool EMIT>
 __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
+    typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const WavePos wp = wave_pos(g.col_tiles);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
@@ -277,7 +223,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     const bool n_ok = n < g.N;
     const int nload = n_ok ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
-    const OutView ov = make_out_view(g, r0, r1, nload, sc);
+    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, wp.ct);
     uniform_words As = as_uniform(g.A);
     constexpr int KC = SEGS * CWT;
     const int Kw = g.Cw;
@@ -310,8 +256,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
 // ---------------------------------------------------------------------------------------
 constexpr int kSplitRowsMax = 32;
 
-template <int AB, int WB, int SEGS, int CWT>
+template <int AB, int WB, int SEGS, int CWT, bool EMIT>
 __global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
+    typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     __shared__ int partial[4][kSplitRowsMax][64];
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
@@ -324,7 +271,7 @@ __global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
     const int n = wp.ct * 64 + lane;
     const int nload = (n < g.N) ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
-    const OutView ov = make_out_view(g, r0, r1, nload, sc);
+    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, wp.ct);
     uniform_words As = as_uniform(g.A);
     constexpr int KC = SEGS * CWT;
     const int Kw = g.Cw;
@@ -514,9 +461,9 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
 // groups of P; if P does not divide the run, the last group is placed at rb-P and recomputes
 // pixels of the group before it (P > 1 is used for single-chunk shapes only, where a
 // recomputed pixel is simply stored again with the same value).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c,
-                                                   const BranchArgs &g, const OutView &ov, int r0, int ra,
+                                                   const BranchArgs &g, const OV &ov, int r0, int ra,
                                                    int rb, int oh, bool left_first, bool right_last,
                                                    bool first, bool last) {
     constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
@@ -576,9 +523,9 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
 }
 
 // One pixel of one chunk with every tap and address tested (the four end pixels).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
 __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c, uniform_words As,
-                                                 const BranchArgs &g, const OutView &ov, int r0, int r,
+                                                 const BranchArgs &g, const OV &ov, int r0, int r,
                                                  PixelPos pos, bool first, bool last) {
 #pragma unroll
     for (int s = 0; s < AB + WB - 1; ++s) c.part[0][s] = 0;
@@ -610,8 +557,8 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
 // full chunk: every word c0 .. c0+CWT-1 exists.  The wavefront's pixel range is cut into
 // runs inside one image row; the four pixels whose untested neighbour addresses could leave
 // the buffer (0, W, rows-1-W, rows-1) go through the tested path.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
-__device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutView &ov, uniform_words As,
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
+__device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &ov, uniform_words As,
                                                 int nload, int r0, int r1, int c0, int t0, bool first,
                                                 bool last) {
     static_assert(TPC % GT == 0 && ((TPC / GT) & 1) == 1, "odd number of stages per pixel");
@@ -658,8 +605,8 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OutVi
 }
 
 // tail chunk (channel words past Cw are padding): plain loads with a guard per word
-template <int AB, int WB, int CWT>
-__device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OutView &ov, uniform_words As,
+template <int AB, int WB, int CWT, class OV>
+__device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &ov, uniform_words As,
                                                 int nload, int r0, int r1, int c0, bool first, bool last) {
     const int Cw = g.Cw;
     uint32_t w[9][WB][CWT];
@@ -702,8 +649,9 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OutVi
     }
 }
 
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
+    typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const WavePos wp = wave_pos(g.col_tiles);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
@@ -713,7 +661,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     const bool n_ok = n < g.N;
     const int nload = n_ok ? n : g.N - 1;
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
-    const OutView ov = make_out_view(g, r0, r1, nload, sc);
+    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, wp.ct);
     uniform_words As = as_uniform(g.A);
     const int Cw = (CWS > 0) ? CWS : g.Cw;
     trace_begin(g, wp);
@@ -796,12 +744,15 @@ inline dim3 grid_for(const BranchArgs &g) {
 template <int AB, int WB>
 hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     using S = GemmShape<AB, WB>;
+    const bool emit = g.planes_out != nullptr;
     if (g.split_k) {
         const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
-        hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT>), dim3((unsigned)(row_blocks * g.col_tiles)),
-                           dim3(256), 0, s, g);
+        const dim3 grid((unsigned)(row_blocks * g.col_tiles));
+        if (emit) hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, true>), grid, dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, false>), grid, dim3(256), 0, s, g);
     } else {
-        hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT>), grid_for(g), dim3(256), 0, s, g);
+        if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT, true>), grid_for(g), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT, false>), grid_for(g), dim3(256), 0, s, g);
     }
     return hipGetLastError();
 }
@@ -811,7 +762,10 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
-    hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P>), grid_for(g), dim3(256), 0, s, g);
+    if (g.planes_out != nullptr)
+        hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true>), grid_for(g), dim3(256), 0, s, g);
+    else
+        hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, false>), grid_for(g), dim3(256), 0, s, g);
     return hipGetLastError();
 }
 
@@ -830,10 +784,14 @@ hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
     }
     // any other channel count: runtime stride, chunks of two channel words while the two stage
     // buffers (2 * AB * CWT SGPRs) leave the allocator room, else one word
-    if (g.Cw == 1 || AB > 4)
-        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1, 1>), grid_for(g), dim3(256), 0, s, g);
-    else if constexpr (AB <= 4)
-        hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1, 1>), grid_for(g), dim3(256), 0, s, g);
+    const bool emit = g.planes_out != nullptr;
+    if (g.Cw == 1 || AB > 4) {
+        if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+    } else if constexpr (AB <= 4) {
+        if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+    }
     return hipGetLastError();
 }
 

@@ -50,8 +50,9 @@ __global__ __launch_bounds__(256) void im2col_pack_kernel(const CodeT *__restric
     }
 }
 
-template <int AB, int WB>
+template <int AB, int WB, bool EMIT>
 __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
+    typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
@@ -83,16 +84,7 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
     }
     const uint32_t full = rowmask[0] | rowmask[1] | rowmask[2];
 
-    // outputs through buffer descriptors covering this wavefront's rows
-    const int64_t first = (int64_t)r0 * g.N;
-    const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;
-    const bool has_acc = g.acc != nullptr, has_out = g.out != nullptr;
-    __amdgpu_buffer_rsrc_t d_acc = __builtin_amdgcn_make_buffer_rsrc(
-        has_acc ? (void *)(g.acc + first) : (void *)(g.out + first), 0, bytes, 0x00020000);
-    __amdgpu_buffer_rsrc_t d_out = __builtin_amdgcn_make_buffer_rsrc(
-        has_out ? (void *)(g.out + first) : (void *)(g.acc + first), 0, bytes, 0x00020000);
-    const int col_bytes = nload * 4;
-    const uint32_t row_bytes = (uint32_t)g.N * 4u;
+    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, ct);
 
     int ow = __builtin_amdgcn_readfirstlane(r0 % g.W);
     int oh = __builtin_amdgcn_readfirstlane((r0 / g.W) % g.H);
@@ -129,12 +121,7 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
 #pragma unroll
         for (int i = AB + WB - 3; i >= 0; --i) sum = (sum << 1) + part[i];
         const int val = __builtin_popcount(m) * g.kconst - 2 * sum;     // kconst = (2^AB-1)(2^WB-1) per element
-        const int soff = (int)((uint32_t)(r - r0) * row_bytes);
-        if (has_acc) __builtin_amdgcn_raw_buffer_store_b32(val, d_acc, col_bytes, soff, 0);
-        if (has_out) {
-            const float y = (float)val * sc;
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), d_out, col_bytes, soff, 0);
-        }
+        finish_row<true>(ov, r - r0, val, true, true);
         if (++ow == g.W) {
             ow = 0;
             if (++oh == g.H) oh = 0;
@@ -154,7 +141,9 @@ template <int AB, int WB>
 hipError_t launch_small_t(const BranchArgs &g, hipStream_t s) {
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
     const int64_t waves = row_blocks * g.col_tiles;
-    hipLaunchKernelGGL((conv_small_kernel<AB, WB>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, g);
+    const dim3 grid((unsigned)((waves + 3) / 4));
+    if (g.planes_out != nullptr) hipLaunchKernelGGL((conv_small_kernel<AB, WB, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((conv_small_kernel<AB, WB, false>), grid, dim3(256), 0, s, g);
     return hipGetLastError();
 }
 

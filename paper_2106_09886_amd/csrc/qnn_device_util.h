@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
+#include "qnn_internal.h"
 
 namespace qnn {
 namespace {
@@ -24,6 +26,113 @@ __device__ __forceinline__ void popc_acc(int &part, uint32_t x) {
 // part = popcount(x): first contribution to an accumulator (saves zeroing it).
 __device__ __forceinline__ void popc_set(int &part, uint32_t x) {
     asm volatile("v_bcnt_u32_b32 %0, %1, 0" : "=v"(part) : "v"(x));
+}
+
+// Re-encoding of a real value on the odd code grid of 2^bits states (Table 2 gives the four
+// intervals for 2 bits, with their closures): a = |y|; c = min(2*floor(a/2) + 1, vmax);
+// code = (y > 0) ? +c : -c, so zero goes to -1 and NaN to -vmax.  Returns the stored index
+// u = (code + vmax) / 2, whose binary digits are the plane bits.  All steps are exact in
+// binary32 (halving, floor, doubling of values below 2^24; larger magnitudes clamp).
+__device__ __forceinline__ int round_odd_index(float y, int vmax) {
+    const float cmax = (float)vmax;
+    const float a = __builtin_fabsf(y);
+    float c = 2.0f * __builtin_floorf(a * 0.5f) + 1.0f;
+    c = (c <= cmax) ? c : cmax;                 // also catches inf / nan
+    const int ci = (int)c;
+    return (((y > 0.0f) ? ci : -ci) + vmax) >> 1;
+}
+
+// ---------------------------------------------------------------------------------------
+// Output addressing: buffer descriptors (base in SGPRs, wave-uniform byte offset in an SGPR,
+// the lane's column offset in a VGPR).  A descriptor covers the rows of one wavefront.
+// ---------------------------------------------------------------------------------------
+struct OutView {
+    __amdgpu_buffer_rsrc_t d0;   // int32 result if requested, else the fp32 result; also holds partial sums
+    __amdgpu_buffer_rsrc_t d1;   // the fp32 result when both outputs are requested
+    uint32_t flags;              // bit 0: int32 result requested, bit 1: fp32 result requested
+    uint32_t row_bytes;          // N * 4
+    int col_bytes;               // lane's column * 4.  Lanes past N compute column N-1 again (same
+                                 // weights, same scale) and store the identical value to it, so
+                                 // the epilogue needs no lane mask
+    float sc;
+};
+
+// The same plus the re-encoded result as bit planes of the next layer (Alg. 1 forward: the scaled
+// output is encoded again).  Row r of the product becomes out_bits * Nw words, Nw = ceil(N/32);
+// a wavefront owns columns 64*ct .. 64*ct+63, i.e. words 2*ct and 2*ct+1 of every plane.
+struct OutViewEmit : OutView {
+    __amdgpu_buffer_rsrc_t dp;   // plane words of the wavefront's rows
+    uint32_t prow_bytes;         // out_bits * Nw * 4
+    int bits;                    // out_bits
+    int vmax;                    // 2^out_bits - 1
+    int word_off;                // byte offset inside a row of the word this lane stores (lane 2p+h:
+                                 // half h of plane p), or -1 if the lane stores nothing
+    bool n_ok;                   // the lane's column exists
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t bytes) {
+    // raw dword buffer: stride 0, num_records in bytes, 32-bit data format word for gfx9
+    return __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, 0x00020000);
+}
+
+template <class OV>
+__device__ __forceinline__ OV make_out_view(const BranchArgs &g, int r0, int r1, int nload, float sc, int ct) {
+    OV v;
+    if constexpr (std::is_same<OV, OutViewEmit>::value) {
+        const int lane = (int)(threadIdx.x & 63);
+        const int Nw = (g.N + 31) >> 5;
+        v.bits = g.out_bits;
+        v.vmax = (1 << g.out_bits) - 1;
+        v.prow_bytes = (uint32_t)(g.out_bits * Nw) * 4u;
+        v.dp = make_rsrc((void *)(g.planes_out + (int64_t)r0 * g.out_bits * Nw), (uint32_t)(r1 - r0) * v.prow_bytes);
+        const int word = 2 * ct + (lane & 1);
+        v.word_off = ((lane >> 1) < g.out_bits && word < Nw) ? ((lane >> 1) * Nw + word) * 4 : -1;
+        v.n_ok = ct * 64 + lane < g.N;
+    }
+    const int64_t first = (int64_t)r0 * g.N;
+    const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;    // < 2^31, checked on the host
+    v.flags = (g.acc != nullptr ? 1u : 0u) | (g.out != nullptr ? 2u : 0u);
+    v.d0 = make_rsrc((void *)(g.partial + first), bytes);               // partial == acc if present, else out
+    v.d1 = make_rsrc((v.flags & 2u) ? (void *)(g.out + first) : (void *)(g.partial + first), bytes);
+    v.row_bytes = (uint32_t)g.N * 4u;
+    v.col_bytes = nload * 4;
+    v.sc = sc;
+    return v;
+}
+
+// Finish one row of one chunk pass for this lane's column.  rel_row = row - r0.  SINGLE: the
+// product has a single chunk pass (first and last are both true at compile time).
+template <bool SINGLE, class OV>
+__device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bool first, bool last) {
+    const int soff = (int)((uint32_t)rel_row * v.row_bytes);
+    if constexpr (!SINGLE) {
+        if (!first) val += __builtin_amdgcn_raw_buffer_load_b32(v.d0, v.col_bytes, soff, 0);
+        if (!last) {
+            __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
+            return;
+        }
+    }
+    const float y = (float)val * v.sc;
+    if (v.flags & 1u) {
+        __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
+        if (v.flags & 2u) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d1, v.col_bytes, soff, 0);
+    } else if (v.flags & 2u) {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
+    }
+    if constexpr (std::is_same<OV, OutViewEmit>::value) {
+        // Table 2 rule on y, then plane p of the 64 codes is one wave ballot = two packed words
+        const int u = v.n_ok ? round_odd_index(y, v.vmax) : 0;
+        const bool odd_lane = (threadIdx.x & 1u) != 0u;
+        const int my_plane = (int)((threadIdx.x & 63u) >> 1);
+        uint32_t mine = 0u;
+        for (int p = 0; p < v.bits; ++p) {
+            const uint64_t m = __builtin_amdgcn_ballot_w64(((u >> p) & 1) != 0);
+            const uint32_t half = odd_lane ? (uint32_t)(m >> 32) : (uint32_t)m;
+            if (my_plane == p) mine = half;
+        }
+        if (v.word_off >= 0)
+            __builtin_amdgcn_raw_buffer_store_b32((int)mine, v.dp, v.word_off, (int)((uint32_t)rel_row * v.prow_bytes), 0);
+    }
 }
 
 // ---------------------------------------------------------------------------------------

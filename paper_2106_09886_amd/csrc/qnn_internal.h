@@ -28,6 +28,9 @@ struct BranchArgs {
                           // rows_per_wave is the number of rows per BLOCK
     uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
     uint32_t trace_waves; // capacity of `trace` in wavefronts
+    uint32_t *planes_out; // optional: the scaled result re-encoded with out_bits bits, as bit planes
+                          // uint32 [rows][out_bits][ceil(N/32)] (the next layer's activations)
+    int out_bits;
 };
 
 struct Tuning {
@@ -83,6 +86,8 @@ hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t 
                        uint32_t *planes, int32_t *bad_count, bool validate, hipStream_t);
 hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
                           void *codes, uint32_t *planes, hipStream_t);
+hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, int64_t Wo, int64_t Cw, int bits,
+                              uint32_t *out, hipStream_t);
 hipError_t launch_scale(const int32_t *acc, int64_t total, int64_t N, const float *scale,
                         float *out, hipStream_t);
 

@@ -124,6 +124,67 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
     return hipGetLastError();
 }
 
+// 2x2 max-pool of codes that are already stored as bit planes.  The stored index
+// u = (code + 2^bits - 1)/2 is monotone in the code, so the maximum code is the maximum u, and
+// the maximum of bit-sliced numbers is a bitwise comparator run from the high plane down: one
+// thread handles 32 channels of one output pixel.
+// Keeps a value opaque to the optimiser.  The comparator below is a chain of three-input
+// boolean steps; folded across steps into v_bitop3_b32 truth tables by this compiler version
+// it gave wrong results for three planes and more, step by step it is correct.
+__device__ __forceinline__ uint32_t opaque(uint32_t x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+template <int BITS>
+__device__ __forceinline__ void planes_max(uint32_t (&a)[BITS], const uint32_t (&b)[BITS]) {
+    uint32_t gt = 0u, lt = 0u;                       // channels where a > b / a < b is already decided
+#pragma unroll
+    for (int p = BITS - 1; p >= 0; --p) {
+        const uint32_t undecided = opaque(~(gt | lt) & (a[p] ^ b[p]));
+        gt = opaque(gt | (undecided & a[p]));
+        lt = opaque(lt | (undecided & b[p]));
+    }
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) a[p] = opaque((a[p] & ~lt) | (b[p] & lt));
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void pool_planes_kernel(const uint32_t *__restrict__ in, int64_t items, int Ho,
+                                                          int Wo, int Cw, uint32_t *__restrict__ out) {
+    for (int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; it < items;
+         it += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t opix = it / Cw;
+        const int j = (int)(it - opix * Cw);
+        const int64_t n = opix / ((int64_t)Ho * Wo);
+        const int64_t rem = opix - n * (int64_t)Ho * Wo;
+        const int oh = (int)(rem / Wo), ow = (int)(rem - (int64_t)oh * Wo);
+        const int64_t p00 = (n * 2 * Ho + 2 * oh) * (2 * (int64_t)Wo) + 2 * ow;       // top-left input pixel
+        const int64_t src[4] = {p00, p00 + 1, p00 + 2 * (int64_t)Wo, p00 + 2 * (int64_t)Wo + 1};
+        uint32_t m[BITS], v[BITS];
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) m[p] = in[(src[0] * BITS + p) * Cw + j];
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) v[p] = in[(src[k] * BITS + p) * Cw + j];
+            planes_max<BITS>(m, v);
+        }
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) out[(opix * BITS + p) * Cw + j] = m[p];
+    }
+}
+
+template <int BITS>
+hipError_t launch_pool_planes_t(const uint32_t *in, int64_t items, int Ho, int Wo, int Cw, uint32_t *out,
+                                hipStream_t s) {
+    const int64_t want = (items + 255) / 256;
+    const int64_t cap = (int64_t)device_simd_count() * 8;
+    hipLaunchKernelGGL((pool_planes_kernel<BITS>), dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, s, in,
+                       items, Ho, Wo, Cw, out);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
@@ -142,6 +203,23 @@ hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int6
         QNN_RQ(5, int8_t); QNN_RQ(6, int8_t); QNN_RQ(7, int8_t); QNN_RQ(8, int16_t);
     }
 #undef QNN_RQ
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, int64_t Wo, int64_t Cw, int bits,
+                              uint32_t *out, hipStream_t s) {
+    const int64_t items = Nb * Ho * Wo * Cw;
+    if (items == 0) return hipSuccess;
+    switch (bits) {
+        case 1: return launch_pool_planes_t<1>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 2: return launch_pool_planes_t<2>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 3: return launch_pool_planes_t<3>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 4: return launch_pool_planes_t<4>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 5: return launch_pool_planes_t<5>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 6: return launch_pool_planes_t<6>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 7: return launch_pool_planes_t<7>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+        case 8: return launch_pool_planes_t<8>(planes, items, (int)Ho, (int)Wo, (int)Cw, out, s);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -135,6 +135,43 @@ def test_scale_epilogue_argument_errors(L):
     assert f(P, 4, 0, P, P, None) == QNN_OK
 
 
+def test_requant_variants_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EWORKSPACE, QNN_EUNSUPPORTED
+    g = L.qnn_branch_gemm_requant
+    #  A, ab, Wt, wb, M, N, K, scale, out_bits, out_planes, acc, out_f32, workspace, workspace_bytes, stream
+    assert g(P, 2, P, 2, 4, 8, 64, None, 0, P, P, None, None, 0, None) == QNN_EINVAL       # out_bits
+    assert g(P, 2, P, 2, 4, 8, 64, None, 9, P, P, None, None, 0, None) == QNN_EINVAL
+    assert g(P, 2, P, 2, 4, 8, 64, None, 4, None, P, None, None, 0, None) == QNN_EINVAL    # no planes
+    assert g(P, 2, P, 2, 4, 8, 64, None, 4, P + 4, P, None, None, 0, None) == QNN_EALIGN
+    assert g(P, 2, P, 2, 4, 8, 64, None, 4, P, None, P, None, 0, None) == QNN_EINVAL       # fp32 out needs a scale
+    assert g(P, 2, P, 2, 4, 8, 64, None, 4, P, None, None, None, 0, None) == QNN_EINVAL    # no result, no workspace
+    assert g(P, 2, P, 2, 4, 8, 64, None, 4, P, None, None, P, 4 * 8 * 4 - 1, None) == QNN_EWORKSPACE
+    assert g(P, 2, P, 2, 4, 8, 64, None, 4, P, None, None, P + 8, 1 << 20, None) == QNN_EALIGN
+    assert g(P, 2, P, 2, 0, 8, 64, None, 4, None, None, None, None, 0, None) == QNN_OK     # empty
+    assert L.qnn_requant_workspace_bytes(4, 8) == 128 and L.qnn_requant_workspace_bytes(0, 8) == 0
+    c = L.qnn_conv2d_packed_requant
+    #  x, ab, Wt, wb, Nb, H, W, C, Cout, scale, out_bits, out_planes, acc, out_f32, ws, ws_bytes, stream
+    assert c(P, 2, P, 2, 1, 4, 4, 64, 64, None, 4, P, None, None, None, 0, None) == QNN_EINVAL
+    assert c(P, 2, P, 2, 1, 4, 4, 64, 64, None, 4, P, None, None, P, 16 * 64 * 4 - 1, None) == QNN_EWORKSPACE
+    assert c(P, 2, P, 2, 1, 4, 4, 64, 64, None, 0, P, P, None, None, 0, None) == QNN_EINVAL
+    assert c(P, 2, P, 2, 1, -4, 4, 64, 64, None, 4, P, P, None, None, 0, None) == QNN_EINVAL
+    assert c(P, 2, P, 2, 1 << 20, 1 << 10, 1 << 10, 64, 64, None, 4, P, P, None, None, 0, None) == QNN_EUNSUPPORTED
+    i = L.qnn_conv2d_im2col_requant
+    need = L.qnn_conv2d_im2col_requant_workspace_bytes(1, 4, 4, 64, 2, 64)
+    assert need == 16 * 2 * 2 * 4 + 16 * 64 * 4
+    #  codes, code_bytes, ab, Wt, wb, Nb, H, W, C, Cout, scale, out_bits, planes, acc, out, ws, ws_bytes, stream
+    assert i(P, 1, 2, P, 2, 1, 4, 4, 64, 64, None, 4, P, None, None, P, need - 1, None) == QNN_EWORKSPACE
+    assert i(P, 1, 2, P, 2, 1, 4, 4, 64, 64, None, 4, P, None, None, None, 0, None) == QNN_EINVAL
+    assert i(P, 3, 2, P, 2, 1, 4, 4, 64, 64, None, 4, P, P, None, P, need, None) == QNN_EINVAL
+    assert i(P, 1, 2, P, 2, 1, 4, 4, 64, 64, None, 4, P, P, None, P, 16 * 2 * 2 * 4 - 1, None) == QNN_EWORKSPACE
+    m = L.qnn_maxpool2x2_planes
+    assert m(P, 1, 3, 4, 64, 4, P, None) == QNN_EINVAL              # odd height
+    assert m(P, 1, 4, 4, 64, 0, P, None) == QNN_EINVAL
+    assert m(None, 1, 4, 4, 64, 4, P, None) == QNN_EINVAL
+    assert m(P, 1, 4, 4, 64, 4, P + 4, None) == QNN_EALIGN
+    assert m(P, 0, 4, 4, 64, 4, None, None) == QNN_OK
+
+
 def test_tune_rejects_unknown_keys(L):
     from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_OK
     assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK
