@@ -53,7 +53,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="resnet18_s1",
-                    choices=["resnet18_s1", "resnet50_s3", "fc4096", "gemm64", "gemm8192", "vgg16_stack"])
+                    choices=["resnet18_s1", "resnet50_s3", "fc4096", "gemm64", "gemm8192", "vgg16_stack",
+                             "vgg16_stack_fused"])
     ap.add_argument("--bits", type=int, default=None,
                     help="gemm8192 only: activation = weight bit width (1..6 in the paper's sweep; default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -67,6 +68,9 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         return 2
     name = args.workload
+    fused = name == "vgg16_stack_fused"
+    if fused:
+        name = "vgg16_stack"
     big = name in ("vgg16_stack", "gemm8192")
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
@@ -113,9 +117,12 @@ def main():
             out = torch.empty((Nb, h, wd, cout), dtype=torch.float32, device=dev)
             ho, wo = (h // 2, wd // 2) if pool else (h, wd)
             planes_out = torch.empty((Nb * ho * wo, w.ab, (cout + 31) // 32), dtype=torch.int32, device=dev)
+            # fused variant: planes before pooling (the partial sums of multi-pass layers live in `acc`)
+            planes_mid = (torch.empty((Nb * h * wd, w.ab, (cout + 31) // 32), dtype=torch.int32, device=dev)
+                          if (fused and pool) else planes_out)
             plan.append((ab, p(planes_in), p(Wp), h, wd, c, cout, p(acc), p(sd), p(out), 1 if pool else 0,
-                         p(planes_out)))
-            keep.append((Wp, sd, acc, out, planes_in, planes_out))
+                         p(planes_out), p(planes_mid), acc.numel() * 4))
+            keep.append((Wp, sd, acc, out, planes_in, planes_out, planes_mid))
             ops += 2.0 * Nb * h * wd * cout * 9 * c
             lane_ops += 2.0 * ab * w.wb * Nb * h * wd * cout * 9 * ((c + 31) // 32)
             planes_in, h, wd, c = planes_out, ho, wo, cout
@@ -127,8 +134,27 @@ def main():
         def pack():
             pass                                  # the first layer packs inside qnn_conv2d_im2col
 
+        ws1 = None
+        if fused:
+            ws1_bytes = int(L.qnn_conv2d_im2col_requant_workspace_bytes(Nb, H, W, C, w.ab_first, layers[0][0].shape[0]))
+            ws1 = torch.empty(ws1_bytes, dtype=torch.uint8, device=dev)
+        pW1 = p(ws1)
+
+        def branch_fused():
+            for i, (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout, pmid, accb) in enumerate(plan):
+                if i == 0:
+                    check(L.qnn_conv2d_im2col_requant(pX, 2, ab, pw, w.wb, Nb, h, wd, c, cout, ps, w.ab, pmid, None,
+                                                      None, pW1, ws1_bytes, stream))
+                else:
+                    check(L.qnn_conv2d_packed_requant(pin, ab, pw, w.wb, Nb, h, wd, c, cout, ps, w.ab, pmid, None,
+                                                      None, pa, accb, stream))
+                if pool:
+                    check(L.qnn_maxpool2x2_planes(pmid, Nb, h, wd, cout, w.ab, pout, stream))
+
         def branch():
-            for i, (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout) in enumerate(plan):
+            if fused:
+                return branch_fused()
+            for i, (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout, _, _) in enumerate(plan):
                 if i == 0:
                     check(L.qnn_conv2d_im2col(pX, 2, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, pF, ws_bytes,
                                               stream))
@@ -142,6 +168,10 @@ def main():
         kernel_name = "13 x (conv_kernel + requant_pack_kernel); lane-ops of the conv kernels only"
         B = None
         outputs = "int32 + fp32 per layer"
+        if fused:
+            desc += "; fused kernels: only bit planes travel between layers"
+            kernel_name = "13 x fused conv_kernel (+ 5 x pool_planes_kernel); lane-ops of the conv kernels only"
+            outputs = "bit planes of the next layer only"
     else:
         w = inputs.WORKLOADS[name]
         if name == "gemm8192" and args.bits is not None:

@@ -33,13 +33,13 @@ __device__ __forceinline__ void popc_set(int &part, uint32_t x) {
 // code = (y > 0) ? +c : -c, so zero goes to -1 and NaN to -vmax.  Returns the stored index
 // u = (code + vmax) / 2, whose binary digits are the plane bits.  All steps are exact in
 // binary32 (halving, floor, doubling of values below 2^24; larger magnitudes clamp).
-__device__ __forceinline__ int round_odd_index(float y, int vmax) {
-    const float cmax = (float)vmax;
-    const float a = __builtin_fabsf(y);
-    float c = 2.0f * __builtin_floorf(a * 0.5f) + 1.0f;
-    c = (c <= cmax) ? c : cmax;                 // also catches inf / nan
-    const int ci = (int)c;
-    return (((y > 0.0f) ? ci : -ci) + vmax) >> 1;
+// With H = 2^(bits-1) and f = min(floor(a/2), H-1):  c = 2f+1,  u = H + f for y > 0 and
+// u = H-1-f = f xor (H-1) otherwise.
+__device__ __forceinline__ int round_odd_index(float y, int half_states /* H */) {
+    const float fmax = (float)(half_states - 1);
+    float t = __builtin_floorf(__builtin_fabsf(y) * 0.5f);
+    t = (t <= fmax) ? t : fmax;                 // also catches inf / nan
+    return (int)t ^ ((y > 0.0f) ? half_states : half_states - 1);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -64,15 +64,31 @@ struct OutViewEmit : OutView {
     __amdgpu_buffer_rsrc_t dp;   // plane words of the wavefront's rows
     uint32_t prow_bytes;         // out_bits * Nw * 4
     int bits;                    // out_bits
-    int vmax;                    // 2^out_bits - 1
-    int word_off;                // byte offset inside a row of the word this lane stores (lane 2p+h:
-                                 // half h of plane p), or -1 if the lane stores nothing
-    bool n_ok;                   // the lane's column exists
+    int half_states;             // 2^(out_bits - 1)
+    uint64_t valid;              // wave mask of the lanes whose column exists
+    int word_off;                // byte offset inside a row of the word this lane stores (lane 2k+h:
+                                 // half h of plane out_bits-1-k), or -1 if the lane stores nothing
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t bytes) {
     // raw dword buffer: stride 0, num_records in bytes, 32-bit data format word for gfx9
     return __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, 0x00020000);
+}
+
+// Step K of the plane emission.  The index of every lane sits at the top of `top`; doubling it
+// shifts out one plane per step, high plane first, and the carry-out of the 64 lanes IS that
+// plane's two packed words (one vector op per plane).  Lanes 2K and 2K+1 of `mine` receive the
+// low and high word of step K's plane (plane bits-1-K).
+template <int K>
+__device__ __forceinline__ void emit_steps(uint32_t &top, int &mine, uint64_t valid, int bits) {
+    uint64_t m;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0" : "+v"(top), "=s"(m));
+    m &= valid;                                  // lanes past N repeat column N-1: not part of the result
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(mine) : "s"((uint32_t)m), "n"(2 * K));
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(mine) : "s"((uint32_t)(m >> 32)), "n"(2 * K + 1));
+    if constexpr (K < 7) {
+        if (bits > K + 1) emit_steps<K + 1>(top, mine, valid, bits);
+    }
 }
 
 template <class OV>
@@ -82,12 +98,13 @@ __device__ __forceinline__ OV make_out_view(const BranchArgs &g, int r0, int r1,
         const int lane = (int)(threadIdx.x & 63);
         const int Nw = (g.N + 31) >> 5;
         v.bits = g.out_bits;
-        v.vmax = (1 << g.out_bits) - 1;
+        v.half_states = 1 << (g.out_bits - 1);
         v.prow_bytes = (uint32_t)(g.out_bits * Nw) * 4u;
         v.dp = make_rsrc((void *)(g.planes_out + (int64_t)r0 * g.out_bits * Nw), (uint32_t)(r1 - r0) * v.prow_bytes);
         const int word = 2 * ct + (lane & 1);
-        v.word_off = ((lane >> 1) < g.out_bits && word < Nw) ? ((lane >> 1) * Nw + word) * 4 : -1;
-        v.n_ok = ct * 64 + lane < g.N;
+        const int step = lane >> 1;                  // see emit_steps: step k carries plane out_bits-1-k
+        v.word_off = (step < g.out_bits && word < Nw) ? ((g.out_bits - 1 - step) * Nw + word) * 4 : -1;
+        v.valid = __builtin_amdgcn_ballot_w64(ct * 64 + lane < g.N);
     }
     const int64_t first = (int64_t)r0 * g.N;
     const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;    // < 2^31, checked on the host
@@ -120,18 +137,12 @@ __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bo
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
     }
     if constexpr (std::is_same<OV, OutViewEmit>::value) {
-        // Table 2 rule on y, then plane p of the 64 codes is one wave ballot = two packed words
-        const int u = v.n_ok ? round_odd_index(y, v.vmax) : 0;
-        const bool odd_lane = (threadIdx.x & 1u) != 0u;
-        const int my_plane = (int)((threadIdx.x & 63u) >> 1);
-        uint32_t mine = 0u;
-        for (int p = 0; p < v.bits; ++p) {
-            const uint64_t m = __builtin_amdgcn_ballot_w64(((u >> p) & 1) != 0);
-            const uint32_t half = odd_lane ? (uint32_t)(m >> 32) : (uint32_t)m;
-            if (my_plane == p) mine = half;
-        }
+        // Table 2 rule on y, then the planes of the 64 codes as wave masks
+        uint32_t top = (uint32_t)round_odd_index(y, v.half_states) << (32 - v.bits);
+        int mine = 0;
+        emit_steps<0>(top, mine, v.valid, v.bits);
         if (v.word_off >= 0)
-            __builtin_amdgcn_raw_buffer_store_b32((int)mine, v.dp, v.word_off, (int)((uint32_t)rel_row * v.prow_bytes), 0);
+            __builtin_amdgcn_raw_buffer_store_b32(mine, v.dp, v.word_off, (int)((uint32_t)rel_row * v.prow_bytes), 0);
     }
 }
 
