@@ -127,10 +127,12 @@ struct GemmCtx {
 };
 
 // full chunk (all KC words inside Kw): pipelined
-// `sink(rel_row, v)` receives v = -2 * S of the chunk for row r0 + rel_row.
-template <int AB, int WB, int SEGS, int CWT, class Sink>
+// `fetch(rel_row)` returns what earlier chunks left for row r0 + rel_row; it is asked for before
+// the row's products are formed, so that its latency hides behind them.
+// `sink(rel_row, v, prev)` receives v = -2 * S of the chunk and that value.
+template <int AB, int WB, int SEGS, int CWT, class Fetch, class Sink>
 __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, int r0, int r1, int k0,
-                                                Sink sink) {
+                                                Fetch fetch, Sink sink) {
     GemmCtx<AB, WB, SEGS, CWT> c;
     const int Kw = g.Cw;
     c.base = (uint64_t)g.A;
@@ -156,8 +158,9 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
         c.off_nxt = (r + 1 < r1) ? c.off_cur + row_bytes : c.off_cur;   // last row prefetches itself
+        const int prev = fetch(r - r0);
         run_stages<0, FLIP>(c);
-        sink(r - r0, -2 * weighted_sum(c.part));
+        sink(r - r0, -2 * weighted_sum(c.part), prev);
         c.off_cur = c.off_nxt;
         ++r;
     };
@@ -170,9 +173,9 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
 }
 
 // tail chunk (runs past Kw): plain loads with a guard per word
-template <int AB, int WB, int SEGS, int CWT, class Sink>
+template <int AB, int WB, int SEGS, int CWT, class Fetch, class Sink>
 __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_words As, int nload, int r0,
-                                                int r1, int k0, Sink sink) {
+                                                int r1, int k0, Fetch fetch, Sink sink) {
     const int Kw = g.Cw;
     uint32_t w[SEGS][WB][CWT];
 #pragma unroll
@@ -188,6 +191,7 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
         int part[AB + WB - 1];
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
+        const int prev = fetch(r - r0);
 #pragma unroll
         for (int t = 0; t < SEGS; ++t) {
             if (k0 + t * CWT < Kw) {             // uniform: skip segments that are all padding
@@ -207,7 +211,7 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
                         for (int j = 0; j < CWT; ++j) popc_acc(part[p + q], a[p][j] ^ w[t][q][j]);
             }
         }
-        sink(r - r0, -2 * weighted_sum(part));
+        sink(r - r0, -2 * weighted_sum(part), prev);
     }
 }
 
@@ -236,12 +240,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     for (int k0 = 0; k0 < Kw; k0 += KC) {
         const bool first = (k0 == 0);
         const bool last = (k0 + KC >= Kw);
-        auto sink = [&](int rel_row, int v) {
-            if (first) v += g.kconst;
-            finish_row<false>(ov, rel_row, v, first, last);
+        auto fetch = [&](int rel_row) -> int {
+            if (first) return g.kconst;
+            return __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)rel_row * ov.row_bytes), 0);
         };
-        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, sink);
-        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, sink);
+        auto sink = [&](int rel_row, int v, int prev) {
+            finish_row<false>(ov, rel_row, v + prev, /*first=*/true, last);   // the earlier part is already added
+        };
+        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, fetch, sink);
+        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, fetch, sink);
     }
     trace_end(g, wp);
 }
@@ -279,12 +286,10 @@ __global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
     bool mine = false;                                        // has this wavefront written its slab yet
     for (int k0 = wv * KC; k0 < Kw; k0 += 4 * KC) {
         const bool first = !mine;
-        auto sink = [&](int rel_row, int v) {
-            if (!first) v += partial[wv][rel_row][lane];
-            partial[wv][rel_row][lane] = v;
-        };
-        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, sink);
-        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, sink);
+        auto fetch = [&](int rel_row) -> int { return first ? 0 : partial[wv][rel_row][lane]; };
+        auto sink = [&](int rel_row, int v, int prev) { partial[wv][rel_row][lane] = v + prev; };
+        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, fetch, sink);
+        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, fetch, sink);
         mine = true;
     }
     if (!mine)
@@ -700,7 +705,7 @@ constexpr int imin(int a, int b) { return a < b ? a : b; }
 // GEMM: one stage holds AB*CWT activation words in SGPRs (<= 16, twice for the two buffers);
 // one chunk holds WB*KC weight words in VGPRs.
 template <int AB, int WB> struct GemmShape {
-    static constexpr int KC = (WB <= 2) ? 32 : (WB <= 4) ? 16 : 8;
+    static constexpr int KC = (WB == 1) ? 64 : (WB == 2) ? 32 : (WB <= 4) ? 16 : 8;
     static constexpr int CWT = imin(pow2_floor(16 / AB), KC / 2);   // at least two stages per row
     static constexpr int SEGS = KC / CWT;
 };

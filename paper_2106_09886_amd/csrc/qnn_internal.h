@@ -41,9 +41,9 @@ struct Tuning {
 };
 Tuning &tuning();
 
-int device_simd_count();
+int device_simd_count();  // 4 * number of compute units of the current device (cached)
 // K words per weight chunk of the GEMM kernels (GemmShape::KC in qnn_branch.hip)
-inline int gemm_chunk_words(int wb) { return (wb <= 2) ? 32 : (wb <= 4) ? 16 : 8; }  // 4 * number of compute units of the current device (cached)
+inline int gemm_chunk_words(int wb) { return (wb == 1) ? 64 : (wb == 2) ? 32 : (wb <= 4) ? 16 : 8; }
 
 // Launchers, one translation unit per activation bit width AB (1..8).
 typedef hipError_t (*branch_launch_fn)(const BranchArgs &, int wb, hipStream_t);
