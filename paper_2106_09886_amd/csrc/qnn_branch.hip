@@ -499,15 +499,21 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
         if (r == ra) edge |= edge_first;
         if (r == r_last) edge |= edge_last;
         c.edge = edge;
+        // what earlier chunk passes left for this pixel, asked for before its products are formed
+        int prev = 0;
+        if constexpr (!SINGLE) {
+            if (!first)
+                prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
+        }
         run_stages<0, FLIP>(c);
 #pragma unroll
         for (int x = 0; x < P; ++x) {
-            int val = -2 * weighted_sum(c.part[x]);
+            int val = -2 * weighted_sum(c.part[x]) + prev;
             int ncols = 3;
             if (x == 0) ncols -= (int)(edge & 1u);
             if (x == P - 1) ncols -= (int)(edge >> 1);
             if (first) val += ncols * krow;
-            finish_row<SINGLE>(ov, r - r0 + x, val, first, last);
+            finish_row<SINGLE>(ov, r - r0 + x, val, /*first=*/true, last);   // earlier part already added
         }
         c.off_cur = c.off_nxt;
         r = rn;
@@ -710,34 +716,11 @@ template <int AB, int WB> struct GemmShape {
     static constexpr int SEGS = KC / CWT;
 };
 
-// Convolution with a compile-time plane stride CWS (a power of two up to 16).  A chunk is
-// CWT channel words x TPC taps; its weight words (TPC*WB*CWT) must leave room in the VGPR file
-// for several wavefronts per SIMD (<= 80), one pipeline stage GT*AB*CWT must fit the SGPR
-// budget twice (<= 32), and among the shapes that fit the one with the most work per chunk
-// pass (CWT*TPC) wins, so that the round trip of partial sums is paid least often.
+// Convolution with a compile-time plane stride CWS: the chunk shape is conv_shape() of
+// qnn_internal.h (shared with the host, which sizes the launch from the number of passes).
 template <int AB, int WB, int CWS> struct ConvShape {
-    static constexpr int kMaxW = 80;
-    static constexpr int CMAX = imin(CWS, pow2_floor(32 / AB));
-    static constexpr int score(int cwt, int tpc) { return (cwt <= CMAX && tpc * WB * cwt <= kMaxW) ? cwt * tpc : 0; }
-    static constexpr int best_cwt() {
-        int bc = 1, bs = 0;
-        for (int cwt = 1; cwt <= CMAX; cwt *= 2)
-            for (int tpc = 1; tpc <= 9; tpc *= 3)
-                if (score(cwt, tpc) > bs || (score(cwt, tpc) == bs && bs > 0 && cwt > bc)) { bs = score(cwt, tpc); bc = cwt; }
-        return bc;
-    }
-    static constexpr int best_tpc() {
-        int bt = 1, bs = 0;
-        for (int tpc = 1; tpc <= 9; tpc *= 3)
-            if (score(best_cwt(), tpc) > bs) { bs = score(best_cwt(), tpc); bt = tpc; }
-        return bt;
-    }
-    static constexpr int CWT = best_cwt();
-    static constexpr int TPC = best_tpc();
-    static constexpr int GT = (TPC >= 3 && CWT == CWS && 3 * AB * CWT <= 24) ? 3 : 1;
-    // pixels per iteration: as many as keep one stage ((P+2) pixels) within 16 SGPRs
-    static constexpr bool GROUPS = (GT == 3 && TPC == 9 && CWT == CWS);
-    static constexpr int P = !GROUPS ? 1 : (6 * AB * CWT <= 16) ? 4 : (4 * AB * CWT <= 16) ? 2 : 1;
+    static constexpr ConvShapeV v = conv_shape(AB, WB, CWS);
+    static constexpr int CWT = v.cwt, TPC = v.tpc, GT = v.gt, P = v.p;
 };
 
 inline dim3 grid_for(const BranchArgs &g) {

@@ -30,17 +30,11 @@ __device__ __forceinline__ void popc_set(int &part, uint32_t x) {
 
 // Re-encoding of a real value on the odd code grid of 2^bits states (Table 2 gives the four
 // intervals for 2 bits, with their closures): a = |y|; c = min(2*floor(a/2) + 1, vmax);
-// code = (y > 0) ? +c : -c, so zero goes to -1 and NaN to -vmax.  Returns the stored index
-// u = (code + vmax) / 2, whose binary digits are the plane bits.  All steps are exact in
-// binary32 (halving, floor, doubling of values below 2^24; larger magnitudes clamp).
-// With H = 2^(bits-1) and f = min(floor(a/2), H-1):  c = 2f+1,  u = H + f for y > 0 and
-// u = H-1-f = f xor (H-1) otherwise.
-__device__ __forceinline__ int round_odd_index(float y, int half_states /* H */) {
-    const float fmax = (float)(half_states - 1);
-    float t = __builtin_floorf(__builtin_fabsf(y) * 0.5f);
-    t = (t <= fmax) ? t : fmax;                 // also catches inf / nan
-    return (int)t ^ ((y > 0.0f) ? half_states : half_states - 1);
-}
+// code = (y > 0) ? +c : -c, so zero goes to -1 and NaN to -vmax.  The stored index is
+// u = (code + vmax) / 2, whose binary digits are the plane bits.  With H = 2^(bits-1) and
+// f = min(floor(a/2), H-1):  c = 2f+1,  u = H + f for y > 0 and u = H-1-f = f xor (H-1)
+// otherwise, i.e. u = f xor (y > 0 ? H : H-1).  All steps are exact in binary32 (halving,
+// floor; larger magnitudes clamp; a NaN fails the comparison and clamps too).
 
 // ---------------------------------------------------------------------------------------
 // Output addressing: buffer descriptors (base in SGPRs, wave-uniform byte offset in an SGPR,
@@ -64,8 +58,11 @@ struct OutViewEmit : OutView {
     __amdgpu_buffer_rsrc_t dp;   // plane words of the wavefront's rows
     uint32_t prow_bytes;         // out_bits * Nw * 4
     int bits;                    // out_bits
-    int half_states;             // 2^(out_bits - 1)
-    uint64_t valid;              // wave mask of the lanes whose column exists
+    int shift;                   // 32 - out_bits: the index is handled at the top of a register
+    // per-lane constants; a lane whose column does not exist (it repeats column N-1) has all
+    // three zero, which makes its index zero = all plane bits zero
+    float fmax;                  // H - 1
+    uint32_t sel_pos, sel_neg;   // H and H - 1, shifted to the top
     int word_off;                // byte offset inside a row of the word this lane stores (lane 2k+h:
                                  // half h of plane out_bits-1-k), or -1 if the lane stores nothing
 };
@@ -78,17 +75,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t by
 // Step K of the plane emission.  The index of every lane sits at the top of `top`; doubling it
 // shifts out one plane per step, high plane first, and the carry-out of the 64 lanes IS that
 // plane's two packed words (one vector op per plane).  Lanes 2K and 2K+1 of `mine` receive the
-// low and high word of step K's plane (plane bits-1-K).
+// low and high word of step K's plane, which is plane out_bits-1-K.
 template <int K>
-__device__ __forceinline__ void emit_steps(uint32_t &top, int &mine, uint64_t valid, int bits) {
+__device__ __forceinline__ void emit_step(uint32_t &top, int &mine) {
     uint64_t m;
     asm volatile("v_add_co_u32 %0, %1, %0, %0" : "+v"(top), "=s"(m));
-    m &= valid;                                  // lanes past N repeat column N-1: not part of the result
     asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(mine) : "s"((uint32_t)m), "n"(2 * K));
     asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(mine) : "s"((uint32_t)(m >> 32)), "n"(2 * K + 1));
-    if constexpr (K < 7) {
-        if (bits > K + 1) emit_steps<K + 1>(top, mine, valid, bits);
-    }
 }
 
 template <class OV>
@@ -97,14 +90,18 @@ __device__ __forceinline__ OV make_out_view(const BranchArgs &g, int r0, int r1,
     if constexpr (std::is_same<OV, OutViewEmit>::value) {
         const int lane = (int)(threadIdx.x & 63);
         const int Nw = (g.N + 31) >> 5;
+        const bool n_ok = ct * 64 + lane < g.N;
+        const uint32_t H = 1u << (g.out_bits - 1);
         v.bits = g.out_bits;
-        v.half_states = 1 << (g.out_bits - 1);
+        v.shift = 32 - g.out_bits;
+        v.fmax = n_ok ? (float)(H - 1u) : 0.0f;
+        v.sel_pos = n_ok ? 0x80000000u : 0u;
+        v.sel_neg = n_ok ? (H - 1u) << (32 - g.out_bits) : 0u;
         v.prow_bytes = (uint32_t)(g.out_bits * Nw) * 4u;
         v.dp = make_rsrc((void *)(g.planes_out + (int64_t)r0 * g.out_bits * Nw), (uint32_t)(r1 - r0) * v.prow_bytes);
         const int word = 2 * ct + (lane & 1);
-        const int step = lane >> 1;                  // see emit_steps: step k carries plane out_bits-1-k
+        const int step = lane >> 1;                  // see emit_step: step k carries plane out_bits-1-k
         v.word_off = (step < g.out_bits && word < Nw) ? ((g.out_bits - 1 - step) * Nw + word) * 4 : -1;
-        v.valid = __builtin_amdgcn_ballot_w64(ct * 64 + lane < g.N);
     }
     const int64_t first = (int64_t)r0 * g.N;
     const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;    // < 2^31, checked on the host
@@ -137,10 +134,29 @@ __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bo
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
     }
     if constexpr (std::is_same<OV, OutViewEmit>::value) {
-        // Table 2 rule on y, then the planes of the 64 codes as wave masks
-        uint32_t top = (uint32_t)round_odd_index(y, v.half_states) << (32 - v.bits);
-        int mine = 0;
-        emit_steps<0>(top, mine, v.valid, v.bits);
+        // Table 2 rule on y (see the top of this file), index at the top of the register
+        float t = __builtin_floorf(__builtin_fabsf(y) * 0.5f);
+        t = (t <= v.fmax) ? t : v.fmax;
+        uint32_t top = ((uint32_t)t << v.shift) ^ ((y > 0.0f) ? v.sel_pos : v.sel_neg);
+        int mine = (int)top;                         // every lane that stores is overwritten below
+        int b = v.bits;
+        asm volatile("" : "+s"(b));                  // decided here, per call, on the scalar unit
+        // steps 0 .. bits-1, rounded up to 1, 2, 4 or 8 of them: a step past the last plane
+        // shifts out zeros into lanes that store nothing
+        emit_step<0>(top, mine);
+        if (b > 1) {
+            emit_step<1>(top, mine);
+            if (b > 2) {
+                emit_step<2>(top, mine);
+                emit_step<3>(top, mine);
+                if (b > 4) {
+                    emit_step<4>(top, mine);
+                    emit_step<5>(top, mine);
+                    emit_step<6>(top, mine);
+                    emit_step<7>(top, mine);
+                }
+            }
+        }
         if (v.word_off >= 0)
             __builtin_amdgcn_raw_buffer_store_b32(mine, v.dp, v.word_off, (int)((uint32_t)rel_row * v.prow_bytes), 0);
     }

@@ -45,6 +45,63 @@ int device_simd_count();  // 4 * number of compute units of the current device (
 // K words per weight chunk of the GEMM kernels (GemmShape::KC in qnn_branch.hip)
 inline int gemm_chunk_words(int wb) { return (wb == 1) ? 64 : (wb == 2) ? 32 : (wb <= 4) ? 16 : 8; }
 
+// Chunk shape of the convolution kernels with a compile-time plane stride cws (a power of two
+// up to 16; bit widths up to 4).  A chunk is cwt channel words x tpc taps; its weight words
+// (tpc*wb*cwt) must leave room in the VGPR file for several wavefronts per SIMD (<= 80), one
+// pipeline stage gt*ab*cwt must fit the SGPR budget twice (<= 32), and among the shapes that fit
+// the one with the most work per chunk pass (cwt*tpc) wins, so that the round trip of partial
+// sums is paid least often.  gt: taps per pipeline stage; p: output pixels per loop iteration.
+struct ConvShapeV {
+    int cwt, tpc, gt, p;
+};
+constexpr int conv_pow2_floor(int x) { return x >= 16 ? 16 : x >= 8 ? 8 : x >= 4 ? 4 : x >= 2 ? 2 : 1; }
+constexpr int conv_shape_score(int ab, int wb, int cws, int cwt, int tpc) {
+    const int cmax = cws < conv_pow2_floor(32 / ab) ? cws : conv_pow2_floor(32 / ab);
+    return (cwt <= cmax && tpc * wb * cwt <= 80) ? cwt * tpc : 0;
+}
+constexpr ConvShapeV conv_shape(int ab, int wb, int cws) {
+    int bc = 1, bs = 0;
+    for (int cwt = 1; cwt <= cws; cwt *= 2)
+        for (int tpc = 1; tpc <= 9; tpc *= 3) {
+            const int sc = conv_shape_score(ab, wb, cws, cwt, tpc);
+            if (sc > bs || (sc == bs && bs > 0 && cwt > bc)) { bs = sc; bc = cwt; }
+        }
+    int bt = 1;
+    bs = 0;
+    for (int tpc = 1; tpc <= 9; tpc *= 3) {
+        const int sc = conv_shape_score(ab, wb, cws, bc, tpc);
+        if (sc > bs) { bs = sc; bt = tpc; }
+    }
+    const int gt = (bt >= 3 && bc == cws && 3 * ab * bc <= 24) ? 3 : 1;
+    const bool groups = (gt == 3 && bt == 9 && bc == cws);
+    // pixels per iteration: as many as keep one stage ((p+2) pixels) within 16 SGPRs
+    const int p = !groups ? 1 : (6 * ab * bc <= 16) ? 4 : (4 * ab * bc <= 16) ? 2 : 1;
+    return ConvShapeV{bc, bt, gt, p};
+}
+static_assert(conv_shape(2, 2, 2).cwt == 2 && conv_shape(2, 2, 2).tpc == 9 && conv_shape(2, 2, 2).gt == 3 &&
+              conv_shape(2, 2, 2).p == 2, "ResNet-18 stage-1 shape: whole product in one pass, pixel pairs");
+static_assert(conv_shape(4, 3, 8).cwt == 8 && conv_shape(4, 3, 8).tpc == 3, "ResNet-50 stage-3 shape: one kernel row per pass");
+static_assert(conv_shape(4, 2, 16).cwt == 4 && conv_shape(4, 2, 16).tpc == 9, "512-channel W2A4: four passes of nine taps");
+// does the convolution launcher have an instantiation with this compile-time plane stride
+constexpr bool conv_has_fixed_shape(int ab, int wb, int cw) {
+    return ab <= 4 && wb <= 4 && (cw == 1 || cw == 2 || cw == 4 || cw == 8 || cw == 16);
+}
+// chunk passes a wavefront makes over its pixels
+constexpr int conv_passes(int ab, int wb, int cw) {
+    if (cw <= 0) return 1;
+    if (conv_has_fixed_shape(ab, wb, cw)) {
+        const ConvShapeV v = conv_shape(ab, wb, cw);
+        return (cw / v.cwt) * (9 / v.tpc);
+    }
+    const int cwt = (cw == 1 || ab > 4) ? 1 : 2;       // the runtime-stride kernels
+    return (cw + cwt - 1) / cwt;
+}
+
+// output pixels the convolution kernel takes per loop iteration
+constexpr int conv_group(int ab, int wb, int cw) {
+    return conv_has_fixed_shape(ab, wb, cw) ? conv_shape(ab, wb, cw).p : 1;
+}
+
 // Launchers, one translation unit per activation bit width AB (1..8).
 typedef hipError_t (*branch_launch_fn)(const BranchArgs &, int wb, hipStream_t);
 hipError_t launch_gemm_ab1(const BranchArgs &, int, hipStream_t);
