@@ -17,6 +17,7 @@ _LIB = os.path.join(_HERE, "libqnn_oracle.so")
 
 __all__ = [
     "build", "threads", "encode", "decode", "pack_planes", "gemm", "gemm_wt", "conv3x3",
+    "conv2d", "conv2d_transposed", "conv_out_size",
     "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
 ]
 
@@ -55,6 +56,11 @@ def _L():
         lib.qnn_oracle_gemm_wt.restype = None
         lib.qnn_oracle_conv3x3.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp]
         lib.qnn_oracle_conv3x3.restype = None
+        conv_args = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32, i32, i64, i64, vp]
+        lib.qnn_oracle_conv2d.argtypes = conv_args
+        lib.qnn_oracle_conv2d.restype = None
+        lib.qnn_oracle_conv2d_transposed.argtypes = conv_args
+        lib.qnn_oracle_conv2d_transposed.restype = None
         lib.qnn_oracle_branch_dot.argtypes = [vp, vp, i64, i32, i32, vp, vp]
         lib.qnn_oracle_branch_dot.restype = i64
         lib.qnn_oracle_scale_f64.argtypes = [vp, i64, i64, vp, vp]
@@ -142,6 +148,45 @@ def conv3x3(X, Wt):
     assert (kh, kw, C2) == (3, 3, C)
     O = np.zeros((Nb, H, W, Cout), dtype=np.int64)
     _L().qnn_oracle_conv3x3(_p(X), _p(Wt), Nb, H, W, C, Cout, _p(O))
+    return O
+
+
+def _pair(v):
+    return (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
+
+
+def conv_out_size(H, K, stride, pad, dil):
+    return (H + 2 * pad - dil * (K - 1) - 1) // stride + 1
+
+
+def conv2d(X, Wt, stride=1, pad=0, dilation=1):
+    """X NHWC, Wt [Cout][KH][KW][C] -> int64 NHWC [Nb][Ho][Wo][Cout]; zero padding, no kernel flip."""
+    X, Wt = _codes(X), _codes(Wt)
+    Nb, H, W, C = X.shape
+    Cout, KH, KW, C2 = Wt.shape
+    assert C2 == C
+    (sh, sw), (ph, pw), (dh, dw) = _pair(stride), _pair(pad), _pair(dilation)
+    Ho, Wo = conv_out_size(H, KH, sh, ph, dh), conv_out_size(W, KW, sw, pw, dw)
+    assert Ho > 0 and Wo > 0
+    O = np.zeros((Nb, Ho, Wo, Cout), dtype=np.int64)
+    _L().qnn_oracle_conv2d(_p(X), _p(Wt), Nb, H, W, C, Cout, KH, KW, sh, sw, ph, pw, dh, dw, Ho, Wo, _p(O))
+    return O
+
+
+def conv2d_transposed(X, Wt, stride=1, pad=0, dilation=1, output_padding=0):
+    """Transposed convolution: X NHWC, Wt [Cout][KH][KW][C] -> int64 NHWC [Nb][Ho][Wo][Cout],
+    Ho = (H-1)*sh - 2*ph + dh*(KH-1) + output_padding + 1."""
+    X, Wt = _codes(X), _codes(Wt)
+    Nb, H, W, C = X.shape
+    Cout, KH, KW, C2 = Wt.shape
+    assert C2 == C
+    (sh, sw), (ph, pw), (dh, dw), (oph, opw) = _pair(stride), _pair(pad), _pair(dilation), _pair(output_padding)
+    Ho = (H - 1) * sh - 2 * ph + dh * (KH - 1) + oph + 1
+    Wo = (W - 1) * sw - 2 * pw + dw * (KW - 1) + opw + 1
+    assert Ho > 0 and Wo > 0
+    O = np.zeros((Nb, Ho, Wo, Cout), dtype=np.int64)
+    _L().qnn_oracle_conv2d_transposed(_p(X), _p(Wt), Nb, H, W, C, Cout, KH, KW, sh, sw, ph, pw, dh, dw, Ho, Wo,
+                                      _p(O))
     return O
 
 

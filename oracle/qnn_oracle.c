@@ -133,6 +133,68 @@ void qnn_oracle_conv3x3(const int16_t *X, const int16_t *Wt, int64_t Nb, int64_t
     }
 }
 
+/* ---- general 2-D convolution and transposed convolution ------------------
+ * (Sec. 3.2: "Op" stands for the layer's linear operation; the networks of Sec. 5 use strided,
+ *  7x7, 1x1, dilated and transposed forms of it.)  NHWC, cross-correlation, X taken as 0 outside
+ *  the image.  Output size  Ho = (H + 2*ph - dh*(KH-1) - 1)/sh + 1  (likewise Wo):
+ *    O[n][oh][ow][f] = sum_{kh,kw,c} X[n][oh*sh - ph + kh*dh][ow*sw - pw + kw*dw][c] * Wt[f][kh][kw][c] */
+void qnn_oracle_conv2d(const int16_t *X, const int16_t *Wt, int64_t Nb, int64_t H, int64_t W, int64_t C,
+                       int64_t Cout, int KH, int KW, int sh, int sw, int ph, int pw, int dh, int dw,
+                       int64_t Ho, int64_t Wo, int64_t *O)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t nh = 0; nh < Nb * Ho; ++nh) {
+        int64_t n = nh / Ho, oh = nh % Ho;
+        for (int64_t ow = 0; ow < Wo; ++ow)
+            for (int64_t f = 0; f < Cout; ++f) {
+                int64_t s = 0;
+                for (int kh = 0; kh < KH; ++kh) {
+                    int64_t ih = oh * sh - ph + (int64_t)kh * dh;
+                    if (ih < 0 || ih >= H) continue;
+                    for (int kw = 0; kw < KW; ++kw) {
+                        int64_t iw = ow * sw - pw + (int64_t)kw * dw;
+                        if (iw < 0 || iw >= W) continue;
+                        const int16_t *x = X + ((n * H + ih) * W + iw) * C;
+                        const int16_t *w = Wt + ((f * KH + kh) * KW + kw) * C;
+                        for (int64_t c = 0; c < C; ++c) s += (int64_t)x[c] * (int64_t)w[c];
+                    }
+                }
+                O[((n * Ho + oh) * Wo + ow) * Cout + f] = s;
+            }
+    }
+}
+
+/* Transposed convolution ("deconvolution"), written as the scatter it is defined by: every input
+ * pixel (ih, iw) adds X[n][ih][iw][c] * Wt[f][kh][kw][c] to the output pixel
+ *   oh = ih*sh - ph + kh*dh,  ow = iw*sw - pw + kw*dw   (if inside the Ho x Wo output).
+ * O must hold Nb*Ho*Wo*Cout values; it is cleared here. */
+void qnn_oracle_conv2d_transposed(const int16_t *X, const int16_t *Wt, int64_t Nb, int64_t H, int64_t W,
+                                  int64_t C, int64_t Cout, int KH, int KW, int sh, int sw, int ph, int pw,
+                                  int dh, int dw, int64_t Ho, int64_t Wo, int64_t *O)
+{
+    for (int64_t i = 0; i < Nb * Ho * Wo * Cout; ++i) O[i] = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < Nb; ++n)
+        for (int64_t ih = 0; ih < H; ++ih)
+            for (int64_t iw = 0; iw < W; ++iw) {
+                const int16_t *x = X + ((n * H + ih) * W + iw) * C;
+                for (int kh = 0; kh < KH; ++kh) {
+                    int64_t oh = ih * sh - ph + (int64_t)kh * dh;
+                    if (oh < 0 || oh >= Ho) continue;
+                    for (int kw = 0; kw < KW; ++kw) {
+                        int64_t ow = iw * sw - pw + (int64_t)kw * dw;
+                        if (ow < 0 || ow >= Wo) continue;
+                        for (int64_t f = 0; f < Cout; ++f) {
+                            const int16_t *w = Wt + ((f * KH + kh) * KW + kw) * C;
+                            int64_t s = 0;
+                            for (int64_t c = 0; c < C; ++c) s += (int64_t)x[c] * (int64_t)w[c];
+                            O[((n * Ho + oh) * Wo + ow) * Cout + f] += s;
+                        }
+                    }
+                }
+            }
+}
+
 /* ---- Eq. (8): the multi-branch sum, written out literally --------------- */
 
 /* XnorPopcount of two {-1,+1} vectors: the number of positions where they

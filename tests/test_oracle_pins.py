@@ -380,3 +380,86 @@ def test_maxpool_and_requant_commute(oracle):
     a = oracle.requant(p, 4)
     b = oracle.maxpool2x2(oracle.requant(y, 4).astype(np.float32)).astype(np.int16)
     assert (a == b).all()
+
+
+# ------------------------------------------------- general and transposed convolution
+GEOMETRIES = [
+    # KH, KW, stride, pad, dilation
+    (1, 1, 1, 0, 1), (1, 1, 2, 0, 1), (3, 3, 2, 1, 1), (7, 7, 2, 3, 1), (5, 5, 1, 0, 1), (3, 3, 1, 2, 2),
+    (3, 1, (1, 2), (1, 0), 1), (2, 4, (2, 1), (0, 2), (1, 2)),
+]
+
+
+@pytest.mark.parametrize("geo", GEOMETRIES)
+def test_general_conv_against_torch(oracle, geo):
+    """Library cross-check (float64 is exact at these magnitudes): strides, paddings, dilations and
+    kernel sizes of the networks of Sec. 5, NHWC vs torch's NCHW."""
+    import torch
+    KH, KW, stride, pad, dil = geo
+    rng = np.random.default_rng(KH * 100 + KW)
+    X = (2 * rng.integers(0, 16, size=(2, 9, 11, 5)) - 15).astype(np.int16)
+    Wt = (2 * rng.integers(0, 4, size=(6, KH, KW, 5)) - 3).astype(np.int16)
+    got = oracle.conv2d(X, Wt, stride=stride, pad=pad, dilation=dil)
+    x = torch.from_numpy(X.astype(np.float64)).permute(0, 3, 1, 2)
+    w = torch.from_numpy(Wt.astype(np.float64)).permute(0, 3, 1, 2)
+    want = torch.nn.functional.conv2d(x, w, stride=stride, padding=pad, dilation=dil).permute(0, 2, 3, 1).numpy()
+    assert got.shape == want.shape and (got == want.astype(np.int64)).all()
+
+
+def test_general_conv_reduces_to_the_3x3_case_and_to_gemm(oracle):
+    rng = np.random.default_rng(3)
+    X = (2 * rng.integers(0, 4, size=(2, 6, 7, 8)) - 3).astype(np.int16)
+    Wt = (2 * rng.integers(0, 4, size=(5, 3, 3, 8)) - 3).astype(np.int16)
+    assert (oracle.conv2d(X, Wt, stride=1, pad=1) == oracle.conv3x3(X, Wt)).all()
+    W1 = (2 * rng.integers(0, 4, size=(5, 1, 1, 8)) - 3).astype(np.int16)
+    assert (oracle.conv2d(X, W1).reshape(-1, 5) == oracle.gemm(X.reshape(-1, 8), W1.reshape(5, 8).T.copy())).all()
+
+
+def test_general_conv_single_tap_positions(oracle):
+    """A kernel with a single 1 at (kh, kw) shifts the image by (kh*d - p, kw*d - p) and samples
+    every s-th pixel: fixes the roles of stride, pad and dilation and the absence of a flip."""
+    X = np.arange(1, 1 + 7 * 8, dtype=np.int16).reshape(1, 7, 8, 1)
+    for KH, KW, s, p, d in [(3, 3, 2, 1, 1), (3, 3, 1, 2, 2), (2, 2, 1, 0, 1)]:
+        for kh in range(KH):
+            for kw in range(KW):
+                K = np.zeros((1, KH, KW, 1), dtype=np.int16)
+                K[0, kh, kw, 0] = 1
+                O = oracle.conv2d(X, K, stride=s, pad=p, dilation=d)[0, :, :, 0]
+                for oh in range(O.shape[0]):
+                    for ow in range(O.shape[1]):
+                        ih, iw = oh * s - p + kh * d, ow * s - p + kw * d
+                        want = X[0, ih, iw, 0] if 0 <= ih < 7 and 0 <= iw < 8 else 0
+                        assert O[oh, ow] == want
+
+
+@pytest.mark.parametrize("geo", [(2, 2, 2, 0, 1, 0), (3, 3, 2, 1, 1, 1), (4, 4, 2, 1, 1, 0), (3, 3, 1, 1, 1, 0),
+                                 (3, 2, (2, 3), (1, 0), (1, 2), (1, 2))])
+def test_transposed_conv_against_torch(oracle, geo):
+    import torch
+    KH, KW, stride, pad, dil, opad = geo
+    rng = np.random.default_rng(KH * 10 + KW)
+    X = (2 * rng.integers(0, 16, size=(2, 5, 6, 4)) - 15).astype(np.int16)
+    Wt = (2 * rng.integers(0, 4, size=(3, KH, KW, 4)) - 3).astype(np.int16)
+    got = oracle.conv2d_transposed(X, Wt, stride=stride, pad=pad, dilation=dil, output_padding=opad)
+    x = torch.from_numpy(X.astype(np.float64)).permute(0, 3, 1, 2)
+    w = torch.from_numpy(Wt.astype(np.float64)).permute(3, 0, 1, 2)          # torch: [Cin][Cout][KH][KW]
+    want = torch.nn.functional.conv_transpose2d(x, w, stride=stride, padding=pad, dilation=dil,
+                                                output_padding=opad).permute(0, 2, 3, 1).numpy()
+    assert got.shape == want.shape and (got == want.astype(np.int64)).all()
+
+
+def test_transposed_conv_is_the_adjoint_of_conv(oracle):
+    """<conv(x), y> = <x, conv_transposed(y)> with input and output channels swapped: the defining
+    property of the transposed operation, independent of any library."""
+    rng = np.random.default_rng(11)
+    for (KH, KW, s, p, d) in [(3, 3, 2, 1, 1), (2, 2, 2, 0, 1), (3, 3, 1, 1, 2)]:
+        X = (2 * rng.integers(0, 8, size=(1, 7, 7, 3)) - 7).astype(np.int16)
+        Wt = (2 * rng.integers(0, 4, size=(4, KH, KW, 3)) - 3).astype(np.int16)      # [Cout=4][KH][KW][C=3]
+        Y0 = oracle.conv2d(X, Wt, stride=s, pad=p, dilation=d)
+        Y = (2 * rng.integers(0, 8, size=Y0.shape) - 7).astype(np.int16)
+        WtT = np.ascontiguousarray(Wt.transpose(3, 1, 2, 0))                          # [C=3][KH][KW][Cout=4]
+        Ho = (Y.shape[1] - 1) * s - 2 * p + d * (KH - 1) + 1
+        opad = 7 - Ho
+        Xb = oracle.conv2d_transposed(Y, WtT, stride=s, pad=p, dilation=d, output_padding=opad)
+        assert Xb.shape == X.shape
+        assert int((Y0 * Y.astype(np.int64)).sum()) == int((X.astype(np.int64) * Xb).sum())
