@@ -194,6 +194,49 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
                                      size_t workspace_bytes, void *stream);
 
 /*
+ * Convolution of any geometry (Sec. 3.2: "Op" is the layer's linear operation; the networks of
+ * Sec. 5 use 7x7 stride-2, strided 3x3 and 1x1, dilated and transposed convolutions), NHWC,
+ * cross-correlation, zero padding (taps outside the image contribute exactly 0).
+ *   h_geo  HOST pointer to the window geometry (read during the call only).
+ *          Convolution:  Ho = (H + 2*pad_h - dil_h*(kh-1) - 1) / stride_h + 1  (likewise Wo),
+ *            out[n][oh][ow][f] = sum_{i,j,c} x[n][oh*stride_h - pad_h + i*dil_h][ow*stride_w - pad_w + j*dil_w][c]
+ *                                            * w[f][i][j][c]
+ *          Transposed (transposed = 1):  Ho = (H-1)*stride_h - 2*pad_h + dil_h*(kh-1) + out_pad_h + 1,
+ *            input pixel (ih, iw) contributes x[n][ih][iw][c] * w[f][i][j][c] to the output pixel
+ *            (ih*stride_h - pad_h + i*dil_h, iw*stride_w - pad_w + j*dil_w).
+ *   x_planes  per-pixel activation planes uint32 [Nb*H*W][ab][ceil(C/32)] (qnn_encode_pack of the
+ *          codes viewed as [Nb*H*W][C]).
+ *   Wt     weight planes uint32 [Cout][kh*kw][wb][ceil(C/32)] = qnn_encode_pack of the weight
+ *          codes w[Cout][kh][kw][C] viewed as [Cout*kh*kw][C].
+ *   acc, scale, out_f32  as in qnn_conv2d_packed, NHWC [Nb][Ho][Wo][Cout].
+ *   out_bits, out_planes, workspace  optional re-encoded result as in the *_requant entry points
+ *          (out_bits = 0: none; then out_planes and workspace are ignored).
+ * qnn_conv2d_general_output_size writes Ho and Wo to HOST integers; both functions return
+ * QNN_EINVAL for a geometry that is not positive (kernel, stride, dilation >= 1, padding >= 0,
+ * out_pad only with transposed = 1 and smaller than max(stride, dilation), Ho, Wo >= 1).
+ * Limits as for qnn_conv2d_packed with 9 replaced by kh*kw, for input and output pixel counts.
+ * The 3x3 / stride 1 / pad 1 case is served faster by qnn_conv2d_packed, a 1x1 / stride 1
+ * convolution by qnn_branch_gemm.
+ */
+typedef struct {
+    int kh, kw;
+    int stride_h, stride_w;
+    int pad_h, pad_w;
+    int dil_h, dil_w;
+    int transposed;
+    int out_pad_h, out_pad_w;
+} qnn_conv_geometry;
+
+qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *h_geo,
+                                          int64_t *h_Ho, int64_t *h_Wo);
+
+qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
+                              int64_t H, int64_t W, int64_t C, int64_t Cout,
+                              const qnn_conv_geometry *h_geo, int32_t *acc, const float *scale,
+                              float *out_f32, int out_bits, uint32_t *out_planes, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
  * 2x2 max-pool (stride 2) of activations that are already bit planes: planes uint32
  * [Nb*H*W][bits][ceil(C/32)] -> out_planes [Nb*(H/2)*(W/2)][bits][ceil(C/32)], H and W even.
  * The re-encoding rule is monotone, so pooling the codes equals re-encoding the pooled values

@@ -24,7 +24,23 @@ EXPORTS = (
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
+    "qnn_conv2d_general_output_size", "qnn_conv2d_general",
 )
+
+
+class ConvGeometry(ctypes.Structure):
+    """qnn_conv_geometry of include/qnn.h."""
+    _fields_ = [(n, ctypes.c_int) for n in ("kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
+                                            "transposed", "out_pad_h", "out_pad_w")]
+
+
+def _pair(v):
+    return (int(v), int(v)) if isinstance(v, int) else (int(v[0]), int(v[1]))
+
+
+def conv_geometry(kh, kw, stride=1, pad=0, dilation=1, transposed=False, output_padding=0):
+    (sh, sw), (ph, pw), (dh, dw), (oh, ow) = _pair(stride), _pair(pad), _pair(dilation), _pair(output_padding)
+    return ConvGeometry(kh, kw, sh, sw, ph, pw, dh, dw, 1 if transposed else 0, oh, ow)
 
 
 class QnnError(RuntimeError):
@@ -87,6 +103,11 @@ def lib():
     L.qnn_conv2d_im2col_requant.restype = i32
     L.qnn_maxpool2x2_planes.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp]
     L.qnn_maxpool2x2_planes.restype = i32
+    gp = ctypes.POINTER(ConvGeometry)
+    L.qnn_conv2d_general_output_size.argtypes = [i64, i64, gp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.qnn_conv2d_general_output_size.restype = i32
+    L.qnn_conv2d_general.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, i64, gp, vp, vp, vp, i32, vp, vp, sz, vp]
+    L.qnn_conv2d_general.restype = i32
     _lib = L
     return L
 
@@ -302,3 +323,31 @@ def maxpool2x2_planes(planes, Nb, H, W, C, bits):
     st = lib().qnn_maxpool2x2_planes(_ptr(planes), Nb, H, W, C, bits, _ptr(out), _stream())
     _check(st, "qnn_maxpool2x2_planes")
     return out
+
+
+def conv2d_general_output_size(H, W, geo):
+    ho, wo = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().qnn_conv2d_general_output_size(H, W, ctypes.byref(geo), ctypes.byref(ho), ctypes.byref(wo)),
+           "qnn_conv2d_general_output_size")
+    return ho.value, wo.value
+
+
+def conv2d_general(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, geo, scale=None, want_acc=True, out_bits=0):
+    """Any-geometry convolution from packed planes -> (acc | None, out fp32 | None, planes | None)."""
+    _dev(x_planes, torch.int32, "x_planes")
+    _dev(Wt, torch.int32, "Wt")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    Ho, Wo = conv2d_general_output_size(H, W, geo)
+    acc, o32 = _outputs((Nb, Ho, Wo), Cout, x_planes.device, scale, want_acc)
+    planes = ws = None
+    if out_bits:
+        planes = torch.empty((Nb * Ho * Wo, out_bits, (Cout + 31) // 32), dtype=torch.int32, device=x_planes.device)
+        if acc is None and o32 is None:
+            ws = torch.empty(max(16, int(lib().qnn_requant_workspace_bytes(Nb * Ho * Wo, Cout))), dtype=torch.uint8,
+                             device=x_planes.device)
+    st = lib().qnn_conv2d_general(_ptr(x_planes), ab, _ptr(Wt), wb, Nb, H, W, C, Cout, ctypes.byref(geo), _ptr(acc),
+                                  _ptr(scale), _ptr(o32), out_bits, _ptr(planes), _ptr(ws),
+                                  0 if ws is None else ws.numel(), _stream())
+    _check(st, "qnn_conv2d_general")
+    return acc, o32, planes

@@ -43,6 +43,7 @@ def build(jobs=None, verbose=False):
     for ab in range(1, 9):
         work.append(("qnn_branch.hip", os.path.join(OBJ, "qnn_branch_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))
         work.append(("qnn_conv_small.hip", os.path.join(OBJ, "qnn_conv_small_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))
+        work.append(("qnn_conv_general.hip", os.path.join(OBJ, "qnn_conv_general_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))
     jobs = jobs or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         for out in ex.map(_compile, work):

@@ -44,6 +44,9 @@ const branch_launch_fn k_gemm[8] = {launch_gemm_ab1, launch_gemm_ab2, launch_gem
 const branch_launch_fn k_conv[8] = {launch_conv_ab1, launch_conv_ab2, launch_conv_ab3, launch_conv_ab4,
                                     launch_conv_ab5, launch_conv_ab6, launch_conv_ab7, launch_conv_ab8};
 
+const branch_launch_fn k_conv_general[8] = {launch_conv_general_ab1, launch_conv_general_ab2, launch_conv_general_ab3,
+                                            launch_conv_general_ab4, launch_conv_general_ab5, launch_conv_general_ab6,
+                                            launch_conv_general_ab7, launch_conv_general_ab8};
 const branch_launch_fn k_conv_small[8] = {launch_conv_small_ab1, launch_conv_small_ab2, launch_conv_small_ab3,
                                           launch_conv_small_ab4, launch_conv_small_ab5, launch_conv_small_ab6,
                                           launch_conv_small_ab7, launch_conv_small_ab8};
@@ -428,6 +431,77 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
     if (!aligned4(y) || !aligned16(planes)) return QNN_EALIGN;
     if (bits == 8 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
     return from_hip(launch_requant(y, Nb, H, W, C, pool2x2 != 0, bits, codes, planes, (hipStream_t)stream));
+}
+
+qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *q, int64_t *h_Ho,
+                                          int64_t *h_Wo) {
+    if (q == nullptr || h_Ho == nullptr || h_Wo == nullptr || H < 0 || W < 0) return QNN_EINVAL;
+    if (q->kh < 1 || q->kw < 1 || q->stride_h < 1 || q->stride_w < 1 || q->dil_h < 1 || q->dil_w < 1) return QNN_EINVAL;
+    if (q->pad_h < 0 || q->pad_w < 0 || (q->transposed != 0 && q->transposed != 1)) return QNN_EINVAL;
+    const int lim = 1 << 12;                               // keeps every coordinate sum and product inside int32
+    if (q->kh > lim || q->kw > lim || q->stride_h > lim || q->stride_w > lim || q->dil_h > lim || q->dil_w > lim ||
+        q->pad_h > lim || q->pad_w > lim)
+        return QNN_EUNSUPPORTED;
+    if (H > ((int64_t)1 << 30) || W > ((int64_t)1 << 30)) return QNN_EUNSUPPORTED;
+    int64_t Ho, Wo;
+    if (q->transposed) {
+        const int mh = q->stride_h > q->dil_h ? q->stride_h : q->dil_h, mw = q->stride_w > q->dil_w ? q->stride_w : q->dil_w;
+        if (q->out_pad_h < 0 || q->out_pad_w < 0 || q->out_pad_h >= mh || q->out_pad_w >= mw) return QNN_EINVAL;
+        Ho = (H - 1) * q->stride_h - 2 * (int64_t)q->pad_h + (int64_t)q->dil_h * (q->kh - 1) + q->out_pad_h + 1;
+        Wo = (W - 1) * q->stride_w - 2 * (int64_t)q->pad_w + (int64_t)q->dil_w * (q->kw - 1) + q->out_pad_w + 1;
+    } else {
+        if (q->out_pad_h != 0 || q->out_pad_w != 0) return QNN_EINVAL;
+        const int64_t nh = H + 2 * (int64_t)q->pad_h - (int64_t)q->dil_h * (q->kh - 1) - 1;
+        const int64_t nw = W + 2 * (int64_t)q->pad_w - (int64_t)q->dil_w * (q->kw - 1) - 1;
+        if (nh < 0 || nw < 0) return QNN_EINVAL;
+        Ho = nh / q->stride_h + 1;
+        Wo = nw / q->stride_w + 1;
+    }
+    if (H == 0 || W == 0) { Ho = 0; Wo = 0; }
+    if ((H > 0 && W > 0) && (Ho < 1 || Wo < 1)) return QNN_EINVAL;
+    if (Ho > ((int64_t)1 << 30) || Wo > ((int64_t)1 << 30)) return QNN_EUNSUPPORTED;
+    *h_Ho = Ho;
+    *h_Wo = Wo;
+    return QNN_OK;
+}
+
+qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
+                              int64_t W, int64_t C, int64_t Cout, const qnn_conv_geometry *q, int32_t *acc,
+                              const float *scale, float *out_f32, int out_bits, uint32_t *out_planes,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    if (out_bits != 0 && !bits_ok(out_bits)) return QNN_EINVAL;
+    qnn_status st = check_image(Nb, H, W, C, Cout);
+    if (st != QNN_OK) return st;
+    int64_t Ho = 0, Wo = 0;
+    st = qnn_conv2d_general_output_size(H, W, q, &Ho, &Wo);
+    if (st != QNN_OK) return st;
+    if (Ho > 0 && Wo > 0 && Nb > kInt31 / Ho / Wo) return QNN_EUNSUPPORTED;
+    const int64_t rows = Nb * Ho * Wo, taps = (int64_t)q->kh * q->kw;
+    if (taps > (1 << 20)) return QNN_EUNSUPPORTED;
+    const Emit e = (out_bits != 0) ? Emit{out_planes, out_bits, workspace, workspace_bytes} : kNoEmit;
+    st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, (int)taps, acc, scale, out_f32, e);
+    if (st != QNN_OK || rows == 0 || Cout == 0) return st;
+    const int64_t cw = (C + 31) / 32;
+    if (cw > 0 && Nb * H * W > ((((int64_t)1 << 30) - 1) / (ab * cw))) return QNN_EUNSUPPORTED;   // input planes
+    BranchArgs g;
+    g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
+    g.partial = partial_buffer(acc, out_f32, e);
+    g.planes_out = e.planes; g.out_bits = e.bits;
+    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
+    g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+    g.col_tiles = (int)((Cout + 63) / 64);
+    g.split_k = 0;
+    g.trace = nullptr; g.trace_waves = 0;
+    g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
+    g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;
+    g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = q->transposed;
+    // about 16 wavefronts per SIMD, handed out as earlier ones finish
+    const int64_t target = (int64_t)device_simd_count() * 16 / g.col_tiles;
+    int64_t rpw = tuning().rows_per_wave > 0 ? tuning().rows_per_wave : (rows + (target > 0 ? target : 1) - 1) / (target > 0 ? target : 1);
+    if (rpw < 4) rpw = 4;
+    if (rpw > rows) rpw = rows;
+    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw, Cout), Cout, e);
+    return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
 }
 
 qnn_status qnn_maxpool2x2_planes(const uint32_t *planes, int64_t Nb, int64_t H, int64_t W, int64_t C, int bits,

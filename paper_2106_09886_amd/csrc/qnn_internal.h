@@ -6,6 +6,16 @@
 
 namespace qnn {
 
+// Window geometry of the general convolution kernel (all run-time values).
+struct ConvGeom {
+    int KH, KW;           // kernel size
+    int sh, sw;           // stride
+    int ph, pw;           // zero padding
+    int dh, dw;           // dilation
+    int Ho, Wo;           // output image size
+    int transposed;       // 0: convolution, 1: transposed convolution
+};
+
 // Arguments of the branch kernels (GEMM and 3x3 convolution).  All sizes were range
 // checked on the host; index arithmetic inside the kernels is 32-bit except for the
 // row base of the outputs.
@@ -31,6 +41,7 @@ struct BranchArgs {
     uint32_t *planes_out; // optional: the scaled result re-encoded with out_bits bits, as bit planes
                           // uint32 [rows][out_bits][ceil(N/32)] (the next layer's activations)
     int out_bits;
+    ConvGeom geo;         // general convolution only
 };
 
 struct Tuning {
@@ -120,6 +131,15 @@ hipError_t launch_conv_ab5(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_ab6(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_ab7(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_ab8(const BranchArgs &, int, hipStream_t);
+
+hipError_t launch_conv_general_ab1(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab2(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab3(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab4(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab5(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab6(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab7(const BranchArgs &, int, hipStream_t);
+hipError_t launch_conv_general_ab8(const BranchArgs &, int, hipStream_t);
 
 hipError_t launch_conv_small_ab1(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_small_ab2(const BranchArgs &, int, hipStream_t);

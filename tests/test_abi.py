@@ -172,6 +172,38 @@ def test_requant_variants_argument_errors(L):
     assert m(P, 0, 4, 4, 64, 4, None, None) == QNN_OK
 
 
+def test_general_conv_geometry_and_argument_errors(L):
+    import ctypes
+    from paper_2106_09886_amd.binding import (QNN_EINVAL, QNN_OK, QNN_EUNSUPPORTED, QNN_EWORKSPACE, conv_geometry,
+                                              conv2d_general_output_size, QnnError)
+    assert conv2d_general_output_size(224, 224, conv_geometry(7, 7, stride=2, pad=3)) == (112, 112)
+    assert conv2d_general_output_size(56, 56, conv_geometry(3, 3, stride=2, pad=1)) == (28, 28)
+    assert conv2d_general_output_size(56, 57, conv_geometry(1, 1, stride=2)) == (28, 29)
+    assert conv2d_general_output_size(33, 33, conv_geometry(3, 3, pad=4, dilation=4)) == (33, 33)
+    assert conv2d_general_output_size(28, 28, conv_geometry(5, 5)) == (24, 24)
+    assert conv2d_general_output_size(14, 14, conv_geometry(2, 2, stride=2, transposed=True)) == (28, 28)
+    assert conv2d_general_output_size(14, 14, conv_geometry(3, 3, stride=2, pad=1, transposed=True,
+                                                            output_padding=1)) == (28, 28)
+    for bad in (conv_geometry(0, 3), conv_geometry(3, 3, stride=0), conv_geometry(3, 3, dilation=0),
+                conv_geometry(3, 3, pad=-1), conv_geometry(3, 3, output_padding=1),
+                conv_geometry(3, 3, stride=2, transposed=True, output_padding=2), conv_geometry(9, 9)):
+        with pytest.raises(QnnError):
+            conv2d_general_output_size(4, 4, bad)
+    with pytest.raises(QnnError) as ei:
+        conv2d_general_output_size(4, 4, conv_geometry(5000, 1, pad=3000))
+    assert ei.value.status == QNN_EUNSUPPORTED
+    f = L.qnn_conv2d_general
+    g = conv_geometry(3, 3, stride=2, pad=1)
+    gp = ctypes.byref(g)
+    #  x, ab, Wt, wb, Nb, H, W, C, Cout, geo, acc, scale, out, out_bits, planes, ws, ws_bytes, stream
+    assert f(P, 2, P, 2, 1, 8, 8, 64, 64, None, P, None, None, 0, None, None, 0, None) == QNN_EINVAL
+    assert f(P, 2, P, 2, 1, 8, 8, 64, 64, gp, None, None, None, 0, None, None, 0, None) == QNN_EINVAL
+    assert f(None, 2, P, 2, 1, 8, 8, 64, 64, gp, P, None, None, 0, None, None, 0, None) == QNN_EINVAL
+    assert f(P, 2, P, 2, 1, 8, 8, 64, 64, gp, P, None, None, 9, P, None, 0, None) == QNN_EINVAL
+    assert f(P, 2, P, 2, 1, 8, 8, 64, 64, gp, None, None, None, 4, P, P, 16 * 64 * 4 - 1, None) == QNN_EWORKSPACE
+    assert f(P, 2, P, 2, 0, 8, 8, 64, 64, gp, None, None, None, 0, None, None, 0, None) == QNN_OK
+
+
 def test_tune_rejects_unknown_keys(L):
     from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_OK
     assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK

@@ -1,0 +1,127 @@
+"""GPU parity of the any-geometry convolution (strides, paddings, dilations, kernel sizes,
+transposed form) against the CPU oracle: int32 results bit-exact, fp32 results bit-equal to the
+oracle's single binary32 multiply, emitted planes equal to the oracle's re-encoding."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import dev, host, rand_codes, planes_u32, say  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def q():
+    import torch
+    assert torch.cuda.is_available(), "no GPU visible"
+    from paper_2106_09886_amd import binding
+    binding.lib()
+    return binding
+
+
+def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dilation=1, transposed=False,
+             output_padding=0, out_bits=0, seed=0):
+    rng = np.random.default_rng(seed + Nb * 7 + H * 5 + C * 3 + Cout + KH * 11 + KW)
+    X = rand_codes(rng, (Nb, H, W, C), ab)
+    Wt = rand_codes(rng, (Cout, KH, KW, C), wb)
+    if transposed:
+        want = oracle.conv2d_transposed(X, Wt, stride=stride, pad=pad, dilation=dilation, output_padding=output_padding)
+    else:
+        want = oracle.conv2d(X, Wt, stride=stride, pad=pad, dilation=dilation)
+    rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2))) + 1.0
+    s = (rng.uniform(0.5, 1.5, Cout) * ((1 << max(out_bits, 2)) / rms)).astype(np.float32)
+    geo = q.conv_geometry(KH, KW, stride=stride, pad=pad, dilation=dilation, transposed=transposed,
+                          output_padding=output_padding)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * KH * KW, C)), wb)
+    acc, y, planes = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=dev(s), out_bits=out_bits)
+    assert tuple(acc.shape) == want.shape
+    assert (host(acc).astype(np.int64) == want).all()
+    y_want = oracle.scale_f32(want, s)
+    assert (host(y) == y_want).all()
+    y64 = oracle.scale_f64(want, s)
+    assert (np.abs(host(y).astype(np.float64) - y64) <= 1e-6 * np.abs(y64)).all()
+    if out_bits:
+        codes = oracle.requant(y_want, out_bits)
+        pw, bad = oracle.pack_planes(codes.reshape(-1, Cout), out_bits)
+        assert bad == 0 and (planes_u32(planes) == pw).all()
+    return want
+
+
+CASES = [
+    # the geometries of the networks the paper evaluates
+    dict(Nb=2, H=20, W=22, C=3, Cout=64, ab=8, wb=2, KH=7, KW=7, stride=2, pad=3),          # ResNet stem
+    dict(Nb=2, H=12, W=12, C=64, Cout=128, ab=2, wb=2, KH=3, KW=3, stride=2, pad=1),        # strided 3x3
+    dict(Nb=2, H=9, W=9, C=256, Cout=64, ab=4, wb=3, KH=1, KW=1),                           # bottleneck 1x1
+    dict(Nb=1, H=10, W=11, C=128, Cout=70, ab=4, wb=2, KH=1, KW=1, stride=2),               # strided 1x1 shortcut
+    dict(Nb=2, H=28, W=28, C=1, Cout=20, ab=8, wb=4, KH=5, KW=5),                           # LeNet conv1
+    dict(Nb=2, H=12, W=12, C=20, Cout=50, ab=4, wb=4, KH=5, KW=5),                          # LeNet conv2
+    dict(Nb=1, H=13, W=13, C=96, Cout=33, ab=3, wb=3, KH=3, KW=3, pad=2, dilation=2),       # atrous conv
+    dict(Nb=1, H=17, W=15, C=40, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=4, dilation=4),
+    dict(Nb=1, H=9, W=14, C=64, Cout=64, ab=2, wb=1, KH=3, KW=1, stride=(1, 2), pad=(1, 0)),
+    dict(Nb=2, H=8, W=10, C=100, Cout=130, ab=1, wb=1, KH=2, KW=4, stride=(2, 1), pad=(0, 2), dilation=(1, 2)),
+    dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=6, wb=2, KH=3, KW=3, pad=1),                     # wide activations
+    dict(Nb=1, H=7, W=7, C=512, Cout=64, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1),          # many channel chunks
+    dict(Nb=3, H=16, W=16, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),                   # several wavefronts per image
+    # transposed
+    dict(Nb=2, H=7, W=7, C=64, Cout=32, ab=2, wb=2, KH=2, KW=2, stride=2, transposed=True),
+    dict(Nb=1, H=6, W=8, C=128, Cout=64, ab=4, wb=2, KH=4, KW=4, stride=2, pad=1, transposed=True),
+    dict(Nb=1, H=5, W=5, C=40, Cout=21, ab=4, wb=4, KH=3, KW=3, stride=2, pad=1, transposed=True, output_padding=1),
+    dict(Nb=1, H=6, W=5, C=32, Cout=64, ab=2, wb=2, KH=3, KW=2, stride=(2, 3), pad=(1, 0), dilation=(1, 2),
+         transposed=True, output_padding=(1, 2)),
+    dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, stride=1, pad=1, transposed=True),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join("%s%s" % (k, v) for k, v in c.items() if k in
+                                                               ("H", "C", "Cout", "ab", "wb", "KH", "stride", "transposed")))
+def test_conv2d_general(q, oracle, case):
+    say("conv2d_general", case)
+    run_case(q, oracle, **case)
+
+
+@pytest.mark.parametrize("out_bits", [1, 2, 4, 8])
+def test_conv2d_general_requant(q, oracle, out_bits):
+    say("conv2d_general requant", out_bits)
+    run_case(q, oracle, Nb=2, H=12, W=12, C=64, Cout=70, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1, out_bits=out_bits)
+    run_case(q, oracle, Nb=1, H=6, W=6, C=256, Cout=64, ab=2, wb=2, KH=2, KW=2, stride=2, transposed=True,
+             out_bits=out_bits)
+
+
+def test_conv2d_general_planes_only(q, oracle):
+    """No int32 / fp32 result requested: the partial sums live in the workspace."""
+    rng = np.random.default_rng(9)
+    Nb, H, W, C, Cout, ab, wb, ob = 2, 10, 10, 128, 96, 4, 2, 4
+    X = rand_codes(rng, (Nb, H, W, C), ab)
+    Wt = rand_codes(rng, (Cout, 3, 3, C), wb)
+    want = oracle.conv2d(X, Wt, stride=2, pad=1)
+    s = (rng.uniform(0.5, 1.5, Cout) * 16.0 / (np.sqrt(np.mean(want.astype(np.float64) ** 2)) + 1)).astype(np.float32)
+    codes = oracle.requant(oracle.scale_f32(want, s), ob)
+    pw, _ = oracle.pack_planes(codes.reshape(-1, Cout), ob)
+    geo = q.conv_geometry(3, 3, stride=2, pad=1)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    import torch
+    Ho, Wo = q.conv2d_general_output_size(H, W, geo)
+    planes = torch.empty((Nb * Ho * Wo, ob, (Cout + 31) // 32), dtype=torch.int32, device="cuda")
+    ws = torch.empty(Nb * Ho * Wo * Cout * 4, dtype=torch.uint8, device="cuda")
+    import ctypes
+    st = q.lib().qnn_conv2d_general(ctypes.c_void_p(Xp.data_ptr()), ab, ctypes.c_void_p(Wp.data_ptr()), wb, Nb, H, W,
+                                    C, Cout, ctypes.byref(geo), None, ctypes.c_void_p(dev(s).data_ptr()), None, ob,
+                                    ctypes.c_void_p(planes.data_ptr()), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
+                                    None)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert (planes_u32(planes) == pw).all()
+
+
+def test_general_equals_the_3x3_kernels(q, oracle):
+    """Same product through the dedicated 3x3 kernels and through the general one."""
+    rng = np.random.default_rng(21)
+    Nb, H, W, C, Cout, ab, wb = 2, 14, 14, 64, 64, 2, 2
+    X = rand_codes(rng, (Nb, H, W, C), ab)
+    Wt = rand_codes(rng, (Cout, 3, 3, C), wb)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    a1, _ = q.conv2d_packed(Xp, ab, Wp, wb, Nb, H, W, C, Cout)
+    a2, _, _ = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, q.conv_geometry(3, 3, pad=1))
+    assert (host(a1) == host(a2)).all() and (host(a1).astype(np.int64) == oracle.conv3x3(X, Wt)).all()
