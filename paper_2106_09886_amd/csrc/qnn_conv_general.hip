@@ -36,6 +36,128 @@ __device__ __forceinline__ bool tap_coord(bool transposed, int o, int stride, in
     return (unsigned)i < (unsigned)size;
 }
 
+// offset of kernel element k along one axis: see tap_coord
+__device__ __forceinline__ int tap_off(bool transposed, int k, int dil, int pad) {
+    return transposed ? pad - k * dil : k * dil - pad;
+}
+
+// State of one chunk (TT taps x CWT channel words) on the fast path: the taps whose kernel row
+// exists (okmask) are inside the image for every pixel of the run, so nothing is tested.
+template <int AB, int WB, int CWT, int TT>
+struct GenCtx {
+    uint64_t base;                   // byte address of the activation planes
+    uint32_t plane_bytes;            // Cw * 4
+    uint32_t toff[TT];               // byte offset of tap i relative to the window origin (a tap that is
+                                     // not used points at a used one: in bounds, skipped when consumed)
+    uint32_t okmask;                 // bit i: tap i is used
+    uint32_t w[TT][WB][CWT];
+};
+
+// CWT consecutive words at a wave-uniform byte address (4-byte aligned): one scalar load
+template <int CWT>
+__device__ __forceinline__ void load_words(uint64_t addr, uint32_t (&out)[CWT]) {
+    typedef uint32_t vec_t __attribute__((ext_vector_type(CWT), aligned(4)));
+    typedef const vec_t __attribute__((address_space(4))) *ptr_t;
+    if constexpr (CWT == 1) {
+        out[0] = *(uniform_words)addr;
+    } else {
+        const vec_t v = *(ptr_t)addr;
+#pragma unroll
+        for (int j = 0; j < CWT; ++j) out[j] = v[j];
+    }
+}
+
+// Output pixels ra .. rb-1 (one output row, every used tap inside the image).  off_a: byte offset
+// of the window origin of pixel ra (plane 0, word c0); step: bytes between the origins of
+// neighbouring output pixels; kadd: constant term of this chunk.  All words of a pixel are
+// requested before any is used; other wavefronts of the SIMD cover the latency.
+template <int AB, int WB, int CWT, int TT, class OV>
+__device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int r0, int ra, int rb,
+                                             uint32_t off_a, uint32_t step, int kadd, bool first, bool last) {
+    uint32_t off = off_a;
+    for (int r = ra; r < rb; ++r) {
+        int prev = 0;
+        if (!first)
+            prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
+        uint32_t a[TT][AB][CWT];
+#pragma unroll
+        for (int i = 0; i < TT; ++i)
+#pragma unroll
+            for (int p = 0; p < AB; ++p)
+                load_words<CWT>(c.base + (uint32_t)(off + c.toff[i] + (uint32_t)p * c.plane_bytes), a[i][p]);
+        int part[AB + WB - 1];
+#pragma unroll
+        for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
+#pragma unroll
+        for (int i = 0; i < TT; ++i)
+            if (c.okmask & (1u << i)) {
+#pragma unroll
+                for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+                    for (int p = 0; p < AB; ++p)
+#pragma unroll
+                        for (int j = 0; j < CWT; ++j) popc_acc(part[p + qq], a[i][p][j] ^ c.w[i][qq][j]);
+            }
+        int s = part[AB + WB - 2];
+#pragma unroll
+        for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
+        finish_row<false>(ov, r - r0, prev + kadd - 2 * s, /*first=*/true, last);   // earlier part already added
+        off += step;
+    }
+}
+
+// One output pixel of one chunk with every tap tested (image borders, transposed convolution,
+// chunks with padding words).
+template <int AB, int WB, int CWT, int TT, class OV>
+__device__ __forceinline__ void gen_pixel_checked(const BranchArgs &g, const OV &ov, uniform_words As,
+                                                  const uint32_t (&w)[TT][WB][CWT], const int (&offh)[TT],
+                                                  const int (&offw)[TT], int r0, int r, int img, int oh, int ow,
+                                                  int c0, int t0, bool first, bool last) {
+    const ConvGeom &q = g.geo;
+    const int T = q.KH * q.KW, Cw = g.Cw;
+    const bool transposed = q.transposed != 0;
+    int prev = 0;
+    if (!first)
+        prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
+    int part[AB + WB - 1];
+#pragma unroll
+    for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
+    int nvalid = 0;
+#pragma unroll
+    for (int i = 0; i < TT; ++i) {
+        int ih, iw;
+        const bool ok = (t0 + i < T) && tap_coord(transposed, oh, q.sh, offh[i], g.H, ih) &&
+                        tap_coord(transposed, ow, q.sw, offw[i], g.W, iw);
+        if (ok) {                           // uniform
+            const int pix = (img * g.H + ih) * g.W + iw;
+            uint32_t a[AB][CWT];
+#pragma unroll
+            for (int p = 0; p < AB; ++p)
+#pragma unroll
+                for (int j = 0; j < CWT; ++j)
+                    a[p][j] = (CWT == 1 || c0 + j < Cw) ? As[(pix * AB + p) * Cw + c0 + j] : 0u;
+#pragma unroll
+            for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+                for (int p = 0; p < AB; ++p)
+#pragma unroll
+                    for (int j = 0; j < CWT; ++j) popc_acc(part[p + qq], a[p][j] ^ w[i][qq][j]);
+            ++nvalid;
+        }
+    }
+    int s = part[AB + WB - 2];
+#pragma unroll
+    for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
+    int val = prev - 2 * s;
+    if (c0 == 0) val += nvalid * g.kconst;  // kconst = C * (2^AB-1) * (2^WB-1), once per tap
+    finish_row<false>(ov, r - r0, val, /*first=*/true, last);   // the earlier part is already added
+}
+
+__device__ __forceinline__ int floor_div(int a, int b) {       // b > 0
+    const int qd = a / b;
+    return (a % b != 0 && a < 0) ? qd - 1 : qd;
+}
+
 template <int AB, int WB, int CWT, int TT, bool EMIT>
 __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
@@ -62,63 +184,81 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     const int ow0 = __builtin_amdgcn_readfirstlane(r0 % q.Wo);
     const int oh0 = __builtin_amdgcn_readfirstlane((r0 / q.Wo) % q.Ho);
     const int n0 = __builtin_amdgcn_readfirstlane(r0 / (q.Wo * q.Ho));
+    const uint32_t pixel_bytes = (uint32_t)(AB * Cw) * 4u;
 
+    GenCtx<AB, WB, CWT, TT> c;
+    c.base = (uint64_t)g.A;
+    c.plane_bytes = (uint32_t)Cw * 4u;
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
         for (int t0 = 0; t0 < T; t0 += TT) {
             const bool first = (c0 == 0 && t0 == 0);
             const bool last = (c0 + CWT >= Cw && t0 + TT >= T);
-            uint32_t w[TT][WB][CWT];
-            int offh[TT], offw[TT];
+            int offh[TT], offw[TT];         // offsets of the chunk's taps along both axes (see tap_coord)
+            // output columns for which every tap of the chunk is inside the image: [lo, hi)
+            int lo = 0, hi = q.Wo;
 #pragma unroll
             for (int i = 0; i < TT; ++i) {
                 const int t = t0 + i;
                 const int kh = t / q.KW, kw = t - kh * q.KW;
-                offh[i] = transposed ? q.ph - kh * q.dh : kh * q.dh - q.ph;
-                offw[i] = transposed ? q.pw - kw * q.dw : kw * q.dw - q.pw;
+                offh[i] = tap_off(transposed, kh, q.dh, q.ph);
+                offw[i] = tap_off(transposed, kw, q.dw, q.pw);
+                if (t < T) {
+                    lo = max(lo, -floor_div(offw[i], q.sw));                  // ceil(-off / s)
+                    hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
+                }
 #pragma unroll
                 for (int qq = 0; qq < WB; ++qq)
 #pragma unroll
                     for (int j = 0; j < CWT; ++j)
-                        w[i][qq][j] = (t < T && c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
+                        c.w[i][qq][j] = (t < T && c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
             }
+            lo = __builtin_amdgcn_readfirstlane(lo);
+            hi = __builtin_amdgcn_readfirstlane(hi);
+            const bool fast_chunk = !transposed && (c0 + CWT <= Cw);
             int ow = ow0, oh = oh0, img = n0;
-            for (int r = r0; r < r1; ++r) {
-                int prev = 0;
-                if (!first)
-                    prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
-                int part[AB + WB - 1];
+            int r = r0;
+            while (r < r1) {
+                const int row_end = min(r1, r - ow + q.Wo);                   // end of this output row within the range
+                // fast interval of this row in pixel numbers
+                int fa = r, fb = r;
+                if (fast_chunk) {
+                    // taps of the chunk whose kernel row exists for this output row; their offsets
+                    uint32_t okmask = 0u, safe_off = 0u;
 #pragma unroll
-                for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
-                int nvalid = 0;
+                    for (int i = 0; i < TT; ++i) {
+                        const bool ok = (t0 + i < T) && (unsigned)(oh * q.sh + offh[i]) < (unsigned)g.H;
+                        c.toff[i] = (uint32_t)(offh[i] * g.W + offw[i]) * pixel_bytes;
+                        if (ok) {
+                            if (okmask == 0u) safe_off = c.toff[i];
+                            okmask |= 1u << i;
+                        }
+                    }
+                    if (okmask != 0u) {
+                        fa = max(r, r - ow + lo);
+                        fb = min(row_end, r - ow + hi);
+                        if (fb <= fa) { fa = r; fb = r; }
+                        else {
+                            c.okmask = okmask;
 #pragma unroll
-                for (int i = 0; i < TT; ++i) {
-                    int ih, iw;
-                    const bool ok = (t0 + i < T) && tap_coord(transposed, oh, q.sh, offh[i], g.H, ih) &&
-                                    tap_coord(transposed, ow, q.sw, offw[i], g.W, iw);
-                    if (ok) {                           // uniform
-                        const int pix = (img * g.H + ih) * g.W + iw;
-                        uint32_t a[AB][CWT];
-#pragma unroll
-                        for (int p = 0; p < AB; ++p)
-#pragma unroll
-                            for (int j = 0; j < CWT; ++j)
-                                a[p][j] = (CWT == 1 || c0 + j < Cw) ? As[(pix * AB + p) * Cw + c0 + j] : 0u;
-#pragma unroll
-                        for (int qq = 0; qq < WB; ++qq)
-#pragma unroll
-                            for (int p = 0; p < AB; ++p)
-#pragma unroll
-                                for (int j = 0; j < CWT; ++j) popc_acc(part[p + qq], a[p][j] ^ w[i][qq][j]);
-                        ++nvalid;
+                            for (int i = 0; i < TT; ++i)
+                                if (!(okmask & (1u << i))) c.toff[i] = safe_off;   // in bounds, skipped when consumed
+                        }
                     }
                 }
-                int s = part[AB + WB - 2];
-#pragma unroll
-                for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
-                int val = prev - 2 * s;
-                if (c0 == 0) val += nvalid * g.kconst;  // kconst = C * (2^AB-1) * (2^WB-1), once per tap
-                finish_row<false>(ov, r - r0, val, /*first=*/true, last);   // the earlier part is already added
-                if (++ow == q.Wo) {
+                // [r, fa) tested, [fa, fb) fast, [fb, row_end) tested
+                for (int x = r; x < fa; ++x)
+                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, offh, offw, r0, x, img, oh, ow + (x - r), c0, t0, first, last);
+                if (fb > fa) {
+                    const int owa = ow + (fa - r);
+                    const uint32_t off_a = (uint32_t)((img * g.H + oh * q.sh) * g.W + owa * q.sw) * pixel_bytes + (uint32_t)c0 * 4u;
+                    const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
+                    gen_run_fast<AB, WB, CWT, TT>(c, ov, r0, fa, fb, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
+                }
+                for (int x = max(fb, fa); x < row_end; ++x)
+                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, offh, offw, r0, x, img, oh, ow + (x - r), c0, t0, first, last);
+                ow += row_end - r;
+                r = row_end;
+                if (ow == q.Wo) {
                     ow = 0;
                     if (++oh == q.Ho) { oh = 0; ++img; }
                 }
@@ -127,22 +267,27 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     }
 }
 
+constexpr int imin3(int a, int b, int c) { return a < b ? (a < c ? a : c) : (b < c ? b : c); }
+
+template <int AB, int WB, int CWT>
+void launch_general_shape(const BranchArgs &g, dim3 grid, bool emit, hipStream_t s) {
+    constexpr int TT = imin3(6, 64 / (WB * CWT), 24 / (AB * CWT));
+    if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, false>), grid, dim3(256), 0, s, g);
+}
+
 template <int AB, int WB>
 hipError_t launch_general_t(const BranchArgs &g, hipStream_t s) {
-    // taps per chunk so that TT * WB * CWT weight words stay at or below 64
-    constexpr int TT = (WB <= 2) ? 8 : (WB <= 4) ? 4 : 2;
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
     const dim3 grid((unsigned)((row_blocks * g.col_tiles + 3) / 4));
     const bool emit = g.planes_out != nullptr;
-    if (g.Cw <= 1 || AB > 4) {
-        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, 1, TT, true>), grid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, 1, TT, false>), grid, dim3(256), 0, s, g);
-    } else if constexpr (AB <= 4) {
-        constexpr int CWT = (AB <= 2) ? 4 : 2;
-        constexpr int TT4 = (TT * CWT > 16) ? 16 / CWT : TT;
-        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT4, true>), grid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT4, false>), grid, dim3(256), 0, s, g);
-    }
+    // channel words per chunk (at most AB*CWT = 8 and no more than there are), then taps per chunk
+    // such that the chunk's weight words (TT*WB*CWT) stay at or below 64 VGPRs and one pixel's
+    // activation words (TT*AB*CWT) at or below 24 SGPRs
+    constexpr int CMAX = (AB <= 2) ? 4 : (AB <= 4) ? 2 : 1;
+    if (g.Cw >= 4 && CMAX >= 4) launch_general_shape<AB, WB, (CMAX >= 4 ? 4 : 1)>(g, grid, emit, s);
+    else if (g.Cw >= 2 && CMAX >= 2) launch_general_shape<AB, WB, (CMAX >= 2 ? 2 : 1)>(g, grid, emit, s);
+    else launch_general_shape<AB, WB, 1>(g, grid, emit, s);
     return hipGetLastError();
 }
 
