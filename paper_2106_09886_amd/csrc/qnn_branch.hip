@@ -729,6 +729,15 @@ inline dim3 grid_for(const BranchArgs &g) {
     return dim3((unsigned)((waves + 3) / 4));
 }
 
+// GEMM kernel with a chunk of KC words (two or more pipeline stages of CWT words)
+template <int AB, int WB, int KC>
+void launch_gemm_short(const BranchArgs &g, bool emit, hipStream_t s) {
+    constexpr int CWT = imin(pow2_floor(16 / AB), KC / 2);
+    constexpr int SEGS = KC / CWT;
+    if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true>), grid_for(g), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false>), grid_for(g), dim3(256), 0, s, g);
+}
+
 template <int AB, int WB>
 hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     using S = GemmShape<AB, WB>;
@@ -739,6 +748,18 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
         if (emit) hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, true>), grid, dim3(256), 0, s, g);
         else hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, false>), grid, dim3(256), 0, s, g);
     } else {
+        // A product shorter than the regular chunk (1x1 convolutions, narrow layers) would run
+        // entirely through the guarded tail path: take the largest shorter chunk that fits instead
+        // (bit widths up to 4 only, to bound build time).
+        if constexpr (AB <= 4 && WB <= 4) {
+            if (g.Cw < S::KC && g.Cw >= 2) {
+                if (S::KC > 16 && g.Cw >= 16) launch_gemm_short<AB, WB, 16>(g, emit, s);
+                else if (S::KC > 8 && g.Cw >= 8) launch_gemm_short<AB, WB, 8>(g, emit, s);
+                else if (g.Cw >= 4) launch_gemm_short<AB, WB, 4>(g, emit, s);
+                else launch_gemm_short<AB, WB, 2>(g, emit, s);
+                return hipGetLastError();
+            }
+        }
         if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT, true>), grid_for(g), dim3(256), 0, s, g);
         else hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT, false>), grid_for(g), dim3(256), 0, s, g);
     }

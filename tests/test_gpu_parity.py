@@ -110,6 +110,18 @@ def test_gemm_shapes(q, oracle, M, N, K, ab, wb):
              rng.uniform(0.01, 0.1, N).astype(np.float32))
 
 
+@pytest.mark.parametrize("K", [64, 96, 128, 160, 256, 288, 512, 544, 1000, 1024])
+@pytest.mark.parametrize("ab,wb", [(1, 1), (2, 2), (4, 2), (3, 3), (4, 4), (2, 5)])
+def test_gemm_short_products(q, oracle, K, ab, wb):
+    """Inner lengths below one regular weight chunk (1x1 convolutions, narrow layers): the
+    shorter-chunk kernels and their ragged remainders."""
+    say("gemm short K", K, "bits", ab, wb)
+    rng = np.random.default_rng(K + ab * 16 + wb)
+    M, N = 150, 70
+    run_gemm(q, oracle, rand_codes(rng, (M, K), ab), rand_codes(rng, (K, N), wb), ab, wb,
+             rng.uniform(0.01, 0.1, N).astype(np.float32))
+
+
 @pytest.mark.parametrize("rpw", [1, 3, 64])
 def test_gemm_any_rows_per_wave(q, oracle, rpw):
     """The launch partition is a performance knob only."""
