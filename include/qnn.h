@@ -209,8 +209,13 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  *   Wt     weight planes uint32 [Cout][kh*kw][wb][ceil(C/32)] = qnn_encode_pack of the weight
  *          codes w[Cout][kh][kw][C] viewed as [Cout*kh*kw][C].
  *   acc, scale, out_f32  as in qnn_conv2d_packed, NHWC [Nb][Ho][Wo][Cout].
- *   out_bits, out_planes, workspace  optional re-encoded result as in the *_requant entry points
- *          (out_bits = 0: none; then out_planes and workspace are ignored).
+ *   out_bits, out_planes  optional re-encoded result as in the *_requant entry points (out_bits = 0:
+ *          none; then out_planes is ignored).
+ *   workspace  optional device scratch (16-byte aligned).  It is REQUIRED (at least
+ *          Nb*Ho*Wo*Cout*4 bytes) only when out_bits != 0 and neither acc nor out_f32 is given.
+ *          With qnn_conv2d_general_workspace_bytes() bytes it also enables the packed-window path
+ *          for few input channels (C <= 32, kh*kw*C <= 256, wb <= 4, not transposed: e.g. a 7x7x3
+ *          stem), which is several times faster; without it the result is the same.
  * qnn_conv2d_general_output_size writes Ho and Wo to HOST integers; both functions return
  * QNN_EINVAL for a geometry that is not positive (kernel, stride, dilation >= 1, padding >= 0,
  * out_pad only with transposed = 1 and smaller than max(stride, dilation), Ho, Wo >= 1).
@@ -229,6 +234,9 @@ typedef struct {
 
 qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *h_geo,
                                           int64_t *h_Ho, int64_t *h_Wo);
+
+size_t qnn_conv2d_general_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout, int ab,
+                                          int wb, const qnn_conv_geometry *h_geo);
 
 qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
                               int64_t H, int64_t W, int64_t C, int64_t Cout,

@@ -24,7 +24,7 @@ EXPORTS = (
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
-    "qnn_conv2d_general_output_size", "qnn_conv2d_general",
+    "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
 )
 
 
@@ -106,6 +106,8 @@ def lib():
     gp = ctypes.POINTER(ConvGeometry)
     L.qnn_conv2d_general_output_size.argtypes = [i64, i64, gp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.qnn_conv2d_general_output_size.restype = i32
+    L.qnn_conv2d_general_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, i32, i32, gp]
+    L.qnn_conv2d_general_workspace_bytes.restype = sz
     L.qnn_conv2d_general.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, i64, gp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.qnn_conv2d_general.restype = i32
     _lib = L
@@ -332,8 +334,10 @@ def conv2d_general_output_size(H, W, geo):
     return ho.value, wo.value
 
 
-def conv2d_general(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, geo, scale=None, want_acc=True, out_bits=0):
-    """Any-geometry convolution from packed planes -> (acc | None, out fp32 | None, planes | None)."""
+def conv2d_general(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, geo, scale=None, want_acc=True, out_bits=0,
+                   workspace=True):
+    """Any-geometry convolution from packed planes -> (acc | None, out fp32 | None, planes | None).
+    workspace=False withholds the scratch that enables the packed-window path."""
     _dev(x_planes, torch.int32, "x_planes")
     _dev(Wt, torch.int32, "Wt")
     if scale is not None:
@@ -343,9 +347,13 @@ def conv2d_general(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, geo, scale=None, wan
     planes = ws = None
     if out_bits:
         planes = torch.empty((Nb * Ho * Wo, out_bits, (Cout + 31) // 32), dtype=torch.int32, device=x_planes.device)
-        if acc is None and o32 is None:
-            ws = torch.empty(max(16, int(lib().qnn_requant_workspace_bytes(Nb * Ho * Wo, Cout))), dtype=torch.uint8,
-                             device=x_planes.device)
+    if workspace:
+        ws = torch.empty(max(16, int(lib().qnn_conv2d_general_workspace_bytes(Nb, H, W, C, Cout, ab, wb,
+                                                                              ctypes.byref(geo)))),
+                         dtype=torch.uint8, device=x_planes.device)
+    elif out_bits and acc is None and o32 is None:
+        ws = torch.empty(max(16, int(lib().qnn_requant_workspace_bytes(Nb * Ho * Wo, Cout))), dtype=torch.uint8,
+                         device=x_planes.device)
     st = lib().qnn_conv2d_general(_ptr(x_planes), ab, _ptr(Wt), wb, Nb, H, W, C, Cout, ctypes.byref(geo), _ptr(acc),
                                   _ptr(scale), _ptr(o32), out_bits, _ptr(planes), _ptr(ws),
                                   0 if ws is None else ws.numel(), _stream())

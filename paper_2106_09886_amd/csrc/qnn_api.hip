@@ -47,6 +47,9 @@ const branch_launch_fn k_conv[8] = {launch_conv_ab1, launch_conv_ab2, launch_con
 const branch_launch_fn k_conv_general[8] = {launch_conv_general_ab1, launch_conv_general_ab2, launch_conv_general_ab3,
                                             launch_conv_general_ab4, launch_conv_general_ab5, launch_conv_general_ab6,
                                             launch_conv_general_ab7, launch_conv_general_ab8};
+const branch_launch_fn k_conv_window[8] = {launch_conv_window_ab1, launch_conv_window_ab2, launch_conv_window_ab3,
+                                           launch_conv_window_ab4, launch_conv_window_ab5, launch_conv_window_ab6,
+                                           launch_conv_window_ab7, launch_conv_window_ab8};
 const branch_launch_fn k_conv_small[8] = {launch_conv_small_ab1, launch_conv_small_ab2, launch_conv_small_ab3,
                                           launch_conv_small_ab4, launch_conv_small_ab5, launch_conv_small_ab6,
                                           launch_conv_small_ab7, launch_conv_small_ab8};
@@ -213,6 +216,9 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     }
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
 }
+
+// bytes of the packed im2col rows [rows][ab + 1][kwp]
+size_t window_workspace_bytes(int64_t rows, int ab, int kwp) { return (size_t)rows * (size_t)(ab + 1) * (size_t)kwp * 4u; }
 
 qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout) {
     if (Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
@@ -465,6 +471,18 @@ qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_g
     return QNN_OK;
 }
 
+size_t qnn_conv2d_general_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout, int ab,
+                                          int wb, const qnn_conv_geometry *q) {
+    int64_t Ho = 0, Wo = 0;
+    if (!bits_ok(ab) || !bits_ok(wb) || Nb <= 0 || C <= 0 || Cout <= 0) return 0;
+    if (qnn_conv2d_general_output_size(H, W, q, &Ho, &Wo) != QNN_OK) return 0;
+    const int64_t rows = Nb * Ho * Wo, taps = (int64_t)q->kh * q->kw;
+    const int kwp = (!q->transposed && C <= 32 && taps >= 2 && wb <= 4) ? window_words(taps * C) : 0;
+    const size_t win = kwp > 0 ? window_workspace_bytes(rows, ab, kwp) : 0;
+    const size_t part = (size_t)(rows * Cout * 4);
+    return win > part ? win : part;
+}
+
 qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
                               int64_t W, int64_t C, int64_t Cout, const qnn_conv_geometry *q, int32_t *acc,
                               const float *scale, float *out_f32, int out_bits, uint32_t *out_planes,
@@ -495,6 +513,29 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
     g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;
     g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = q->transposed;
+    // Few input channels and a window of at most 256 bits: packed im2col rows, if the caller gave
+    // the workspace for them (else the general kernel below does the same, a word per tap).
+    const int kwp = (!q->transposed && C <= 32 && taps >= 2 && wb <= 4) ? window_words(taps * C) : 0;
+    if (kwp > 0) {
+        const size_t need = window_workspace_bytes(rows, ab, kwp);
+        if (workspace != nullptr && aligned16(workspace) && workspace_bytes >= need && need < ((size_t)1 << 32)) {
+            uint32_t *win = static_cast<uint32_t *>(workspace);
+            st = from_hip(launch_window_pack(x_planes, rows, g.geo, (int)H, (int)W, (int)C, ab, kwp, win,
+                                             (hipStream_t)stream));
+            if (st != QNN_OK) return st;
+            g.A = win;
+            g.Cw = kwp;
+            g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
+            int64_t rpw2 = tuning().rows_per_wave;
+            if (rpw2 <= 0) {
+                rpw2 = rows * g.col_tiles / ((int64_t)device_simd_count() * 8);
+                if (rpw2 < 16) rpw2 = 16;
+            }
+            if (rpw2 > rows) rpw2 = rows;
+            g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw2, Cout), Cout, e);
+            return from_hip(k_conv_window[ab - 1](g, wb, (hipStream_t)stream));
+        }
+    }
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the
     // wavefront's weight words, which has to be spread over enough pixels (measured optimum 14-16
     // on layers of 25 k to 100 k pixels)

@@ -267,6 +267,99 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Few input channels (C <= 32) and a window of at most 256 bits (KH*KW*C): the K axis of an
+// output pixel is materialised as a packed im2col row of KWP words per plane (bit t*C + c =
+// tap t, channel c; see window_pack_kernel), so a 7x7x3 stem costs 5 words per plane instead
+// of 49.  The row carries one more "plane": the mask of bits whose tap lies inside the image.
+// Bits of taps outside are zero in the activation words, and the weights are and-ed with the
+// mask, so such taps contribute nothing; the constant term counts the mask bits.
+// ---------------------------------------------------------------------------------------
+template <int AB, int WB, int KWP, bool EMIT>
+__global__ __launch_bounds__(256) void conv_window_kernel(const BranchArgs g) {
+    typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    const int ct = wave % g.col_tiles;
+    const int rb = wave / g.col_tiles;
+    if ((int64_t)rb * g.rows_per_wave >= g.rows) return;
+    const int r0 = rb * g.rows_per_wave;
+    const int r1 = min(g.rows, r0 + g.rows_per_wave);
+    const int lane = (int)(threadIdx.x & 63);
+    const int n = ct * 64 + lane;
+    const int nload = (n < g.N) ? n : g.N - 1;         // lanes past N redo column N-1 (same value, same address)
+    const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
+    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, ct);
+    const int T = g.geo.KH * g.geo.KW, C = g.C;
+
+    // the filter's window bits per weight plane, assembled from its per-tap words (C bits each)
+    uint32_t w[WB][KWP];
+#pragma unroll
+    for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+        for (int k = 0; k < KWP; ++k) w[qq][k] = 0u;
+    for (int t = 0; t < T; ++t) {
+        const int bit = t * C, wi = bit >> 5, sh = bit & 31;
+#pragma unroll
+        for (int qq = 0; qq < WB; ++qq) {
+            const uint32_t x = g.Wt[(nload * T + t) * WB + qq];
+            const uint32_t lo = x << sh, hi = sh ? x >> (32 - sh) : 0u;      // hi: the part that spills into the next word
+#pragma unroll
+            for (int k = 0; k < KWP; ++k) {
+                if (k == wi) w[qq][k] |= lo;
+                if (k == wi + 1) w[qq][k] |= hi;
+            }
+        }
+    }
+    const uint64_t base = (uint64_t)g.A;
+    constexpr uint32_t kRowBytes = (uint32_t)((AB + 1) * KWP) * 4u;
+    for (int r = r0; r < r1; ++r) {
+        const uint64_t row = base + (uint64_t)((uint32_t)r * kRowBytes);     // < 4 GiB, checked on the host
+        uint32_t m[KWP], a[AB][KWP];
+        load_words<KWP>(row + (uint32_t)(AB * KWP) * 4u, m);
+#pragma unroll
+        for (int p = 0; p < AB; ++p) load_words<KWP>(row + (uint32_t)(p * KWP) * 4u, a[p]);
+        int nvalid = 0;
+#pragma unroll
+        for (int k = 0; k < KWP; ++k) nvalid += __builtin_popcount(m[k]);
+        int part[AB + WB - 1];
+#pragma unroll
+        for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
+#pragma unroll
+        for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+            for (int k = 0; k < KWP; ++k) {
+                const uint32_t wm = w[qq][k] & m[k];
+#pragma unroll
+                for (int p = 0; p < AB; ++p) popc_acc(part[p + qq], a[p][k] ^ wm);
+            }
+        int s = part[AB + WB - 2];
+#pragma unroll
+        for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
+        finish_row<true>(ov, r - r0, nvalid * g.kconst - 2 * s, true, true);   // kconst = (2^AB-1)(2^WB-1) per element
+    }
+}
+
+template <int AB, int WB, int KWP>
+void launch_window_shape(const BranchArgs &g, dim3 grid, hipStream_t s) {
+    if (g.planes_out != nullptr) hipLaunchKernelGGL((conv_window_kernel<AB, WB, KWP, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((conv_window_kernel<AB, WB, KWP, false>), grid, dim3(256), 0, s, g);
+}
+
+template <int AB, int WB>
+hipError_t launch_window_t(const BranchArgs &g, hipStream_t s) {
+    const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
+    const dim3 grid((unsigned)((row_blocks * g.col_tiles + 3) / 4));
+    switch (g.Cw) {                                    // words per plane of the packed window
+        case 1: launch_window_shape<AB, WB, 1>(g, grid, s); break;
+        case 2: launch_window_shape<AB, WB, 2>(g, grid, s); break;
+        case 3: launch_window_shape<AB, WB, 3>(g, grid, s); break;
+        case 5: launch_window_shape<AB, WB, 5>(g, grid, s); break;
+        case 8: launch_window_shape<AB, WB, 8>(g, grid, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 constexpr int imin3(int a, int b, int c) { return a < b ? (a < c ? a : c) : (b < c ? b : c); }
 
 template <int AB, int WB, int CWT>
@@ -306,6 +399,16 @@ hipError_t QNN_CAT(launch_conv_general_ab, QNN_AB)(const BranchArgs &g, int wb, 
         case 6: return launch_general_t<QNN_AB, 6>(g, s);
         case 7: return launch_general_t<QNN_AB, 7>(g, s);
         case 8: return launch_general_t<QNN_AB, 8>(g, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t QNN_CAT(launch_conv_window_ab, QNN_AB)(const BranchArgs &g, int wb, hipStream_t s) {
+    switch (wb) {
+        case 1: return launch_window_t<QNN_AB, 1>(g, s);
+        case 2: return launch_window_t<QNN_AB, 2>(g, s);
+        case 3: return launch_window_t<QNN_AB, 3>(g, s);
+        case 4: return launch_window_t<QNN_AB, 4>(g, s);
     }
     return hipErrorInvalidValue;
 }

@@ -148,6 +148,49 @@ hipError_t launch_type(const void *codes, int64_t rows, int K, int Kw, int bits,
     return hipErrorInvalidValue;
 }
 
+// Packed im2col rows for convolutions with few input channels (C <= 32, window of at most 256
+// bits): from per-pixel planes [pix_in][AB] (one word per plane) to [pix_out][AB+1][KWP], where
+// bit t*C + c of plane p is the plane bit of tap t = (kh, kw), channel c, zero if the tap lies
+// outside the image, and "plane" AB is the mask of the bits whose tap lies inside.
+// One thread = one (output pixel, plane).
+__global__ __launch_bounds__(256) void window_pack_kernel(const uint32_t *__restrict__ planes, int64_t items,
+                                                          ConvGeom q, int H, int W, int C, int AB, int KWP,
+                                                          uint32_t *__restrict__ out) {
+    const uint32_t cmask = (C >= 32) ? 0xffffffffu : ((1u << C) - 1u);
+    for (int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; it < items;
+         it += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t opix = it / (AB + 1);
+        const int p = (int)(it - opix * (AB + 1));
+        const int ow = (int)(opix % q.Wo);
+        const int oh = (int)((opix / q.Wo) % q.Ho);
+        const int64_t img = opix / ((int64_t)q.Wo * q.Ho);
+        uint32_t acc[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] = 0u;
+        int t = 0;
+        for (int kh = 0; kh < q.KH; ++kh) {
+            const int ih = oh * q.sh - q.ph + kh * q.dh;
+            for (int kw = 0; kw < q.KW; ++kw, ++t) {
+                const int iw = ow * q.sw - q.pw + kw * q.dw;
+                if ((unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W) {
+                    const int64_t ipix = (img * H + ih) * W + iw;
+                    const uint32_t x = (p < AB) ? (planes[ipix * AB + p] & cmask) : cmask;
+                    const int bit = t * C, wi = bit >> 5, sh = bit & 31;
+                    const uint32_t lo = x << sh, hi = sh ? x >> (32 - sh) : 0u;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        if (k == wi) acc[k] |= lo;
+                        if (k == wi + 1) acc[k] |= hi;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k < KWP) out[it * KWP + k] = acc[k];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
@@ -160,6 +203,16 @@ hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t 
     if (code_bytes == 1)
         return launch_type<int8_t>(codes, rows, (int)K, Kw, bits, planes, bad_count, validate, blocks, s);
     return launch_type<int16_t>(codes, rows, (int)K, Kw, bits, planes, bad_count, validate, blocks, s);
+}
+
+hipError_t launch_window_pack(const uint32_t *planes, int64_t out_pixels, const ConvGeom &q, int H, int W, int C,
+                              int ab, int kwp, uint32_t *out, hipStream_t s) {
+    const int64_t items = out_pixels * (ab + 1);
+    if (items == 0) return hipSuccess;
+    const int64_t want = (items + 255) / 256;
+    const unsigned blocks = (unsigned)(want < (int64_t)1 << 20 ? want : (int64_t)1 << 20);
+    hipLaunchKernelGGL(window_pack_kernel, dim3(blocks), dim3(256), 0, s, planes, items, q, H, W, C, ab, kwp, out);
+    return hipGetLastError();
 }
 
 }  // namespace qnn

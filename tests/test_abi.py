@@ -192,6 +192,12 @@ def test_general_conv_geometry_and_argument_errors(L):
     with pytest.raises(QnnError) as ei:
         conv2d_general_output_size(4, 4, conv_geometry(5000, 1, pad=3000))
     assert ei.value.status == QNN_EUNSUPPORTED
+    stem = conv_geometry(7, 7, stride=2, pad=3)
+    # the larger of the packed windows (7x7x3 = 147 bits = 5 words per plane, 8 planes + mask) and the partial sums
+    assert L.qnn_conv2d_general_workspace_bytes(1, 224, 224, 3, 16, 8, 2, ctypes.byref(stem)) == 112 * 112 * 9 * 5 * 4
+    assert L.qnn_conv2d_general_workspace_bytes(1, 224, 224, 3, 64, 8, 2, ctypes.byref(stem)) == 112 * 112 * 64 * 4
+    assert L.qnn_conv2d_general_workspace_bytes(1, 224, 224, 64, 64, 2, 2, ctypes.byref(stem)) == 112 * 112 * 64 * 4
+    assert L.qnn_conv2d_general_workspace_bytes(1, 224, 224, 3, 64, 9, 2, ctypes.byref(stem)) == 0
     f = L.qnn_conv2d_general
     g = conv_geometry(3, 3, stride=2, pad=1)
     gp = ctypes.byref(g)

@@ -19,7 +19,7 @@ def q():
 
 
 def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dilation=1, transposed=False,
-             output_padding=0, out_bits=0, seed=0):
+             output_padding=0, out_bits=0, seed=0, workspace=True):
     rng = np.random.default_rng(seed + Nb * 7 + H * 5 + C * 3 + Cout + KH * 11 + KW)
     X = rand_codes(rng, (Nb, H, W, C), ab)
     Wt = rand_codes(rng, (Cout, KH, KW, C), wb)
@@ -33,7 +33,8 @@ def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dila
                           output_padding=output_padding)
     Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
     Wp = q.encode_pack(dev(Wt.reshape(Cout * KH * KW, C)), wb)
-    acc, y, planes = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=dev(s), out_bits=out_bits)
+    acc, y, planes = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=dev(s), out_bits=out_bits,
+                                      workspace=workspace)
     assert tuple(acc.shape) == want.shape
     assert (host(acc).astype(np.int64) == want).all()
     y_want = oracle.scale_f32(want, s)
@@ -77,6 +78,29 @@ CASES = [
 def test_conv2d_general(q, oracle, case):
     say("conv2d_general", case)
     run_case(q, oracle, **case)
+
+
+WINDOW_CASES = [
+    # few input channels: the packed-window path (and, without workspace, the general kernel)
+    dict(Nb=2, H=20, W=22, C=3, Cout=64, ab=8, wb=2, KH=7, KW=7, stride=2, pad=3),          # 147 bits, 5 words
+    dict(Nb=2, H=11, W=9, C=3, Cout=20, ab=8, wb=2, KH=3, KW=3, stride=2, pad=1),           # 27 bits, 1 word
+    dict(Nb=1, H=12, W=12, C=6, Cout=70, ab=4, wb=4, KH=5, KW=5, pad=2),                    # 150 bits, 5 words
+    dict(Nb=1, H=9, W=10, C=10, Cout=33, ab=2, wb=3, KH=3, KW=3, pad=2, dilation=2),        # 90 bits, 3 words
+    dict(Nb=2, H=6, W=6, C=32, Cout=64, ab=2, wb=2, KH=2, KW=2),                            # 128 bits, whole words per tap
+    dict(Nb=1, H=8, W=7, C=32, Cout=16, ab=3, wb=1, KH=4, KW=2, pad=1),                     # 256 bits, 8 words
+    dict(Nb=1, H=8, W=8, C=7, Cout=130, ab=5, wb=2, KH=3, KW=3, stride=(2, 1), pad=1),      # 63 bits, 2 words
+    dict(Nb=3, H=28, W=28, C=1, Cout=20, ab=8, wb=4, KH=5, KW=5),                           # LeNet conv1, 25 bits
+    dict(Nb=1, H=5, W=5, C=11, Cout=8, ab=1, wb=1, KH=1, KW=3, pad=(0, 1)),                 # 33 bits: one bit in word 1
+]
+
+
+@pytest.mark.parametrize("case", WINDOW_CASES, ids=lambda c: "C%d-k%dx%d-ab%d-wb%d" % (c["C"], c["KH"], c["KW"],
+                                                                                        c["ab"], c["wb"]))
+@pytest.mark.parametrize("workspace", [True, False])
+def test_conv2d_few_channels(q, oracle, case, workspace):
+    say("conv2d few channels", case, "workspace", workspace)
+    run_case(q, oracle, workspace=workspace, **case)
+    run_case(q, oracle, workspace=workspace, out_bits=4, seed=5, **case)
 
 
 @pytest.mark.parametrize("out_bits", [1, 2, 4, 8])
