@@ -294,3 +294,66 @@ def test_scale_epilogue(q, oracle, M, N):
     s = rng.uniform(0.0005, 0.005, N).astype(np.float32)
     out = q.scale_epilogue(dev(acc), dev(s))
     check_scaled(oracle, out, acc.astype(np.int64), s)
+
+
+# ---------------------------------------------------------------- largest supported operands
+def test_gemm_activation_planes_just_below_4gib(q, oracle):
+    """The kernels address packed operands with 32-bit byte offsets; the documented limit is a
+    plane buffer below 4 GiB.  A [M][8][127] with M*8*127 just below 2^30 words: sampled rows
+    (first, last, around every 1 GiB boundary) are packed from known codes and checked against
+    the oracle; all other rows hold random bits and are checked through parity and bound."""
+    import torch
+    ab, wb, Kw = 8, 1, 127
+    K = Kw * 32
+    M = ((1 << 30) - 1) // (ab * Kw)
+    N = 64
+    say("gemm at the operand limit: M", M, "K", K)
+    rng = np.random.default_rng(2024)
+    A = torch.randint(-2 ** 31, 2 ** 31 - 1, (M, ab, Kw), dtype=torch.int32, device="cuda")
+    words_per_gib = (1 << 28) // (ab * Kw)                       # rows per GiB of planes
+    rows = sorted({0, 1, M - 2, M - 1, M // 2, words_per_gib - 1, words_per_gib, 2 * words_per_gib, 3 * words_per_gib,
+                   3 * words_per_gib + 1, 12345, M - 777})
+    codes = rand_codes(rng, (len(rows), K), ab)
+    planes, bad = oracle.pack_planes(codes, ab)
+    assert bad == 0
+    A[torch.tensor(rows, device="cuda")] = torch.from_numpy(planes.view(np.int32)).cuda()
+    W = rand_codes(rng, (K, N), wb)
+    Wp = q.encode_pack(dev(np.ascontiguousarray(W.T)), wb)
+    acc, _ = q.branch_gemm(A, ab, Wp, wb, K)
+    torch.cuda.synchronize()
+    got = acc[torch.tensor(rows, device="cuda")].cpu().numpy()
+    assert (got.astype(np.int64) == oracle.gemm(codes, W)).all()
+    # every element: parity of a sum of K odd products, magnitude bound
+    bound = K * 255
+    assert bool((((acc - K) % 2) == 0).all()) and int(acc.abs().max()) <= bound
+    # one more row would exceed the limit and is refused before any launch
+    import ctypes
+    st = q.lib().qnn_branch_gemm(ctypes.c_void_p(A.data_ptr()), ab, ctypes.c_void_p(Wp.data_ptr()), wb, M + 2, N, K,
+                                 ctypes.c_void_p(acc.data_ptr()), None, None, None)
+    assert st == q.QNN_EUNSUPPORTED
+
+
+def test_conv_activation_planes_just_below_4gib(q, oracle):
+    """Same for the 3x3 convolution: x_planes [Nb*H*W][4][16] just below 2^30 words (512 channels);
+    the first and last image and one in the middle are packed from known codes and checked."""
+    import torch
+    ab, wb, C, Cout, H, W = 4, 1, 512, 64, 32, 32
+    Cw = C // 32
+    Nb = ((1 << 30) - 1) // (H * W * ab * Cw)
+    say("conv at the operand limit: Nb", Nb)
+    rng = np.random.default_rng(2025)
+    X = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * H * W, ab, Cw), dtype=torch.int32, device="cuda")
+    imgs = [0, Nb // 2, Nb - 1]
+    codes = rand_codes(rng, (len(imgs), H, W, C), ab)
+    planes, bad = oracle.pack_planes(codes.reshape(-1, C), ab)
+    assert bad == 0
+    planes = planes.reshape(len(imgs), H * W, ab, Cw)
+    for i, n in enumerate(imgs):
+        X[n * H * W:(n + 1) * H * W] = torch.from_numpy(planes[i].view(np.int32)).cuda()
+    Wt = rand_codes(rng, (Cout, 3, 3, C), wb)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    acc, _ = q.conv2d_packed(X, ab, Wp, wb, Nb, H, W, C, Cout)
+    torch.cuda.synchronize()
+    want = oracle.conv3x3(codes, Wt)
+    for i, n in enumerate(imgs):
+        assert (acc[n].cpu().numpy().astype(np.int64) == want[i]).all(), n
