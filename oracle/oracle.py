@@ -17,7 +17,7 @@ _LIB = os.path.join(_HERE, "libqnn_oracle.so")
 
 __all__ = [
     "build", "threads", "encode", "decode", "pack_planes", "gemm", "gemm_wt", "conv3x3",
-    "conv2d", "conv2d_transposed", "conv_out_size",
+    "conv2d", "conv2d_transposed", "conv_out_size", "encode_real",
     "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
 ]
 
@@ -67,6 +67,8 @@ def _L():
         lib.qnn_oracle_scale_f64.restype = None
         lib.qnn_oracle_scale_f32.argtypes = [vp, i64, i64, vp, vp]
         lib.qnn_oracle_scale_f32.restype = None
+        lib.qnn_oracle_encode_real.argtypes = [vp, i64, i32, i32, vp]
+        lib.qnn_oracle_encode_real.restype = None
         lib.qnn_oracle_maxpool2x2.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.qnn_oracle_maxpool2x2.restype = None
         lib.qnn_oracle_round_odd.argtypes = [ctypes.c_float, i32]
@@ -245,3 +247,12 @@ def requant(y, bits):
     codes = np.zeros(y.shape, dtype=np.int16)
     _L().qnn_oracle_requant(_p(y), y.size, int(bits), _p(codes))
     return codes
+
+
+def encode_real(x, bits, hrelu=False):
+    """Real values (nominally in [-1,1], or [0,1] after HReLU) -> odd codes int16, same shape."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.zeros(x.shape, dtype=np.int16)
+    _L().qnn_oracle_encode_real(_p(x), x.size, int(bits), 1 if hrelu else 0, _p(codes))
+    return codes
+

@@ -290,3 +290,23 @@ void qnn_oracle_requant(const float *y, int64_t n, int bits, int16_t *codes)
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) codes[i] = qnn_oracle_round_odd(y[i], bits);
 }
+
+/* ---- real-valued front end (Sec. 3.2: clip, then encode) -------------------
+ * Table 1 limits the data to [-1,1] (HTanh) or [0,1] (HReLU); Table 2 then maps the number
+ * space to the encoded states (for 2 bits: [-1,-2/3] -> -1, (-2/3,0] -> -1/3, (0,2/3) -> 1/3,
+ * [2/3,1] -> 1, i.e. odd codes over alpha = 2^bits - 1).  The product x * alpha is formed in
+ * binary32 (one rounding, volatile so that it is not contracted or widened): that is the
+ * precision in which the interval decision is taken; everything after it is exact.
+ * hrelu != 0 clips to [0,1] first (x <= 0 and NaN -> 0); values beyond +-1 clamp in round_odd. */
+void qnn_oracle_encode_real(const float *x, int64_t n, int bits, int hrelu, int16_t *codes)
+{
+    const float alpha = (float)(((int64_t)1 << bits) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        float v = x[i];
+        if (hrelu) v = (v > 0.0f) ? v : 0.0f;
+        volatile float y = v * alpha;
+        codes[i] = qnn_oracle_round_odd(y, bits);
+    }
+}
+

@@ -463,3 +463,48 @@ def test_transposed_conv_is_the_adjoint_of_conv(oracle):
         Xb = oracle.conv2d_transposed(Y, WtT, stride=s, pad=p, dilation=d, output_padding=opad)
         assert Xb.shape == X.shape
         assert int((Y0 * Y.astype(np.int64)).sum()) == int((X.astype(np.int64) * Xb).sum())
+
+
+# ------------------------------------------------------------------ real-valued front end
+def test_encode_real_reproduces_table2(oracle):
+    """Table 2 on the unscaled number space [-1,1] with its printed closures (2 bits, alpha = 3)."""
+    x = np.array([-1.0, -0.9, -2.0 / 3.0, -0.6666, -0.3, -1e-30, 0.0, 1e-30, 0.3, 0.6666, 2.0 / 3.0, 0.9, 1.0],
+                 dtype=np.float32)
+    want = np.array([-3, -3, -3, -1, -1, -1, -1, 1, 1, 1, 3, 3, 3])
+    assert (oracle.encode_real(x, 2) == want).all()
+    # Table 1: HTanh clips to [-1,1] (beyond it the extreme states), HReLU to [0,1] (nothing below the state of 0)
+    big = np.array([-7.5, -1.0001, 1.0001, 40.0, np.inf, -np.inf], dtype=np.float32)
+    assert (oracle.encode_real(big, 2) == np.array([-3, -3, 3, 3, 3, -3])).all()
+    neg = np.array([-5.0, -0.5, -0.0, 0.0, 0.2, 0.7, 3.0, np.nan], dtype=np.float32)
+    assert (oracle.encode_real(neg, 2, hrelu=True) == np.array([-1, -1, -1, -1, 1, 3, 3, -1])).all()
+
+
+@pytest.mark.parametrize("bits", range(1, 7))
+def test_encode_real_agrees_with_the_trigonometric_encoder(oracle, bits):
+    """Eq. (10) at generic points of (-1,1): element m of the code is sign(+-sin((2^M-1)/2^m pi x)).
+    Points within 1e-4 of an interval boundary 2j/(2^M-1) are left out (the sine vanishes there)."""
+    M, alpha = bits, (1 << bits) - 1
+    rng = np.random.default_rng(M)
+    x = rng.uniform(-1, 1, 4000).astype(np.float32)
+    pos = x.astype(np.float64) * alpha / 2.0
+    x = x[np.abs(pos - np.round(pos)) > 1e-4 * alpha]
+    codes = oracle.encode_real(x, M)
+    for xi, v in zip(x.tolist(), codes.tolist()):
+        c = oracle.encode(int(v), M)
+        for m in range(1, M + 1):
+            s = math.sin(alpha / (1 << m) * math.pi * xi)
+            if m != M:
+                s = -s
+            assert (1 if s > 0 else -1) == int(c[m - 1]), (M, m, xi, v)
+
+
+def test_encode_real_is_the_scaled_reencoder(oracle):
+    """encode_real(x) = requant(x * alpha) with the product formed in binary32; quantised points
+    v/alpha come back as v for every bit width (round trip through the number space)."""
+    for bits in range(1, 9):
+        alpha = (1 << bits) - 1
+        v = np.array(all_codes(bits), dtype=np.int16)
+        x = (v.astype(np.float64) / alpha).astype(np.float32)
+        assert (oracle.encode_real(x, bits) == v).all(), bits
+        y = np.random.default_rng(bits).normal(0, 0.7, 500).astype(np.float32)
+        assert (oracle.encode_real(y, bits) == oracle.requant(y * np.float32(alpha), bits)).all()
