@@ -157,6 +157,18 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
                             int bits, void *codes, uint32_t *planes, void *stream);
 
 /*
+ * Real-valued front end (Sec. 3.2: the data is limited to a fixed range, Table 1, and then mapped
+ * to its encoded state, Table 2 / the look-up form of the MBitEncoder of Eq. (10)).
+ *   x      fp32 [rows][K], nominally in [-1,1];  hrelu = 1 first clips to [0,1] (x <= 0 and NaN -> 0).
+ *   y = x * (2^bits - 1) in binary32 (one multiply), then the rule of qnn_requant_pack: values
+ *   beyond +-1 take the extreme states (the HTanh clip), [2j, 2j+2)/(2^bits-1) -> code 2j+1,
+ *   zero -> -1.  Outputs as in qnn_requant_pack: codes int8/int16 [rows][K] and/or planes
+ *   uint32 [rows][bits][ceil(K/32)]; at least one must be given.
+ */
+qnn_status qnn_encode_real(const float *x, int64_t rows, int64_t K, int bits, int hrelu, void *codes,
+                           uint32_t *planes, void *stream);
+
+/*
  * Chained layers (Alg. 1 forward as one kernel: branch sum, scale, re-encode).  The *_requant
  * variants of the three product entry points compute the same int32 product, multiply by
  * scale[n] (scale == NULL: y = (float)acc), map y to the odd code grid of out_bits bits with the

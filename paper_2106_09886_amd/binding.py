@@ -24,7 +24,7 @@ EXPORTS = (
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
-    "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
+    "qnn_encode_real", "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
 )
 
 
@@ -103,6 +103,8 @@ def lib():
     L.qnn_conv2d_im2col_requant.restype = i32
     L.qnn_maxpool2x2_planes.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp]
     L.qnn_maxpool2x2_planes.restype = i32
+    L.qnn_encode_real.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+    L.qnn_encode_real.restype = i32
     gp = ctypes.POINTER(ConvGeometry)
     L.qnn_conv2d_general_output_size.argtypes = [i64, i64, gp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.qnn_conv2d_general_output_size.restype = i32
@@ -359,3 +361,15 @@ def conv2d_general(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, geo, scale=None, wan
                                   0 if ws is None else ws.numel(), _stream())
     _check(st, "qnn_conv2d_general")
     return acc, o32, planes
+
+
+def encode_real(x, bits, hrelu=False, want_codes=True, want_planes=True):
+    """x fp32 [rows][K] -> (codes int8/int16 | None, planes int32 [rows][bits][Kw] | None)."""
+    _dev(x, torch.float32, "x")
+    rows, K = x.shape
+    codes = torch.empty((rows, K), dtype=torch.int8 if bits <= 7 else torch.int16, device=x.device) if want_codes else None
+    planes = torch.empty((rows, bits, (K + 31) // 32), dtype=torch.int32, device=x.device) if want_planes else None
+    st = lib().qnn_encode_real(_ptr(x), rows, K, bits, 1 if hrelu else 0, _ptr(codes), _ptr(planes), _stream())
+    _check(st, "qnn_encode_real")
+    return codes, planes
+

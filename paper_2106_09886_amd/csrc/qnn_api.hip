@@ -436,7 +436,19 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
     if (y == nullptr || (codes == nullptr && planes == nullptr)) return QNN_EINVAL;
     if (!aligned4(y) || !aligned16(planes)) return QNN_EALIGN;
     if (bits == 8 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
-    return from_hip(launch_requant(y, Nb, H, W, C, pool2x2 != 0, bits, codes, planes, (hipStream_t)stream));
+    return from_hip(launch_requant(y, Nb, H, W, C, pool2x2 != 0, bits, 1.0f, 0, codes, planes, (hipStream_t)stream));
+}
+
+qnn_status qnn_encode_real(const float *x, int64_t rows, int64_t K, int bits, int hrelu, void *codes,
+                           uint32_t *planes, void *stream) {
+    if (!bits_ok(bits) || rows < 0 || K < 0 || (hrelu != 0 && hrelu != 1)) return QNN_EINVAL;
+    if (rows > kInt31 || K > kInt31) return QNN_EUNSUPPORTED;
+    if (rows == 0 || K == 0) return QNN_OK;
+    if (x == nullptr || (codes == nullptr && planes == nullptr)) return QNN_EINVAL;
+    if (!aligned4(x) || !aligned16(planes)) return QNN_EALIGN;
+    if (bits == 8 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
+    const float alpha = (float)((1 << bits) - 1);
+    return from_hip(launch_requant(x, 1, 1, rows, K, false, bits, alpha, hrelu, codes, planes, (hipStream_t)stream));
 }
 
 qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *q, int64_t *h_Ho,

@@ -177,7 +177,7 @@ typedef hipError_t (*im2col_launch_fn)(const void *, int, int64_t, int, int, int
 hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
                        uint32_t *planes, int32_t *bad_count, bool validate, hipStream_t);
 hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
-                          void *codes, uint32_t *planes, hipStream_t);
+                          float premul, int hrelu, void *codes, uint32_t *planes, hipStream_t);
 hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, int64_t Wo, int64_t Cw, int bits,
                               uint32_t *out, hipStream_t);
 hipError_t launch_scale(const int32_t *acc, int64_t total, int64_t N, const float *scale,

@@ -30,7 +30,7 @@ __device__ __forceinline__ int round_odd(float y) {
 // is consumed, so that a wavefront keeps U (4U with pooling) 256-byte rows in flight.
 template <typename CodeT, int BITS, bool POOL, int U>
 __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restrict__ y, int64_t out_pixels,
-                                                           int Ho, int Wo, int C,
+                                                           int Ho, int Wo, int C, float premul, int hrelu,
                                                            CodeT *__restrict__ codes,
                                                            uint32_t *__restrict__ planes) {
     constexpr int VMAX = (1 << BITS) - 1;
@@ -91,7 +91,11 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (it0 + u >= items) break;                    // wave-uniform
-            const int code = round_odd<BITS>(v[u]);
+            // real-valued front end (Table 1, Table 2): clip to [0,1] if asked, then one binary32
+            // multiply by 2^bits - 1 brings the number space onto the code grid (re-encoding: x 1)
+            float val = v[u];
+            if (hrelu) val = (val > 0.0f) ? val : 0.0f;
+            const int code = round_odd<BITS>(val * premul);
             const int c = cg[u] * 64 + lane;
             if (codes != nullptr && valid[u]) codes[pix[u] * (int64_t)C + c] = (CodeT)code;
             if (planes != nullptr) {
@@ -113,14 +117,14 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
 }
 
 template <typename CodeT, int BITS>
-hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, void *codes,
-                     uint32_t *planes, unsigned blocks, hipStream_t s) {
+hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, float premul, int hrelu,
+                     void *codes, uint32_t *planes, unsigned blocks, hipStream_t s) {
     if (pool)
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
-                           out_pixels, Ho, Wo, C, (CodeT *)codes, planes);
+                           out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
     else
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
-                           out_pixels, Ho, Wo, C, (CodeT *)codes, planes);
+                           out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
     return hipGetLastError();
 }
 
@@ -188,7 +192,7 @@ hipError_t launch_pool_planes_t(const uint32_t *in, int64_t items, int Ho, int W
 }  // namespace
 
 hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
-                          void *codes, uint32_t *planes, hipStream_t s) {
+                          float premul, int hrelu, void *codes, uint32_t *planes, hipStream_t s) {
     const int Ho = (int)(pool ? H / 2 : H), Wo = (int)(pool ? W / 2 : W);
     const int64_t out_pixels = Nb * Ho * (int64_t)Wo;
     const int64_t items = out_pixels * ((C + 63) / 64);
@@ -197,7 +201,7 @@ hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int6
     const int64_t want = (items + 3) / 4;
     const int64_t cap = (int64_t)device_simd_count() * 2;
     const unsigned blocks = (unsigned)(want < cap ? want : cap);
-#define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, out_pixels, Ho, Wo, (int)C, pool, codes, planes, blocks, s)
+#define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, out_pixels, Ho, Wo, (int)C, pool, premul, hrelu, codes, planes, blocks, s)
     switch (bits) {
         QNN_RQ(1, int8_t); QNN_RQ(2, int8_t); QNN_RQ(3, int8_t); QNN_RQ(4, int8_t);
         QNN_RQ(5, int8_t); QNN_RQ(6, int8_t); QNN_RQ(7, int8_t); QNN_RQ(8, int16_t);

@@ -210,6 +210,19 @@ def test_general_conv_geometry_and_argument_errors(L):
     assert f(P, 2, P, 2, 0, 8, 8, 64, 64, gp, None, None, None, 0, None, None, 0, None) == QNN_OK
 
 
+def test_encode_real_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK
+    f = L.qnn_encode_real
+    assert f(P, 4, 64, 0, 0, P, P, None) == QNN_EINVAL
+    assert f(P, 4, 64, 2, 2, P, P, None) == QNN_EINVAL            # hrelu is 0 or 1
+    assert f(P, -1, 64, 2, 0, P, P, None) == QNN_EINVAL
+    assert f(None, 4, 64, 2, 0, P, P, None) == QNN_EINVAL
+    assert f(P, 4, 64, 2, 0, None, None, None) == QNN_EINVAL
+    assert f(P + 2, 4, 64, 2, 0, P, P, None) == QNN_EALIGN
+    assert f(P, 4, 64, 2, 0, P, P + 4, None) == QNN_EALIGN
+    assert f(P, 0, 64, 2, 0, None, None, None) == QNN_OK
+
+
 def test_tune_rejects_unknown_keys(L):
     from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_OK
     assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK

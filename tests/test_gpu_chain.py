@@ -46,6 +46,29 @@ def test_requant_pack(q, oracle, bits, shape, pool):
     assert (planes_u32(p2) == want_planes).all() and (host(c2) == got).all()
 
 
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 7, 8])
+@pytest.mark.parametrize("hrelu", [False, True])
+@pytest.mark.parametrize("shape", [(1, 1), (7, 33), (64, 64), (5, 200), (300, 70)])
+def test_encode_real(q, oracle, bits, hrelu, shape):
+    """Real-valued front end: clip, scale by 2^bits - 1 in binary32, Table 2 rule, planes."""
+    say("encode_real", bits, hrelu, shape)
+    rng = np.random.default_rng(bits * 10 + shape[0] + shape[1] + int(hrelu))
+    alpha = (1 << bits) - 1
+    x = rng.normal(0, 0.6, size=shape).astype(np.float32)
+    flat = x.reshape(-1)
+    # interval boundaries 2j/alpha (as binary32), zeros, the ends of the range and values beyond it
+    special = [0.0, -0.0, 1.0, -1.0, 1.5, -1.5, float("inf"), float("-inf"), float("nan"), 1e-38, -1e-38]
+    special += [2.0 * j / alpha for j in range(-(alpha // 2) - 1, alpha // 2 + 2)][:40]
+    special = np.array(special, dtype=np.float32)
+    n = min(flat.size, special.size)
+    flat[:n] = special[:n]
+    want = oracle.encode_real(x, bits, hrelu=hrelu)
+    codes, planes = q.encode_real(dev(x), bits, hrelu=hrelu)
+    assert (host(codes).astype(np.int16) == want).all()
+    wp, bad = oracle.pack_planes(want, bits)
+    assert bad == 0 and (planes_u32(planes) == wp).all()
+
+
 # ------------------------------------------------------------------------- chains
 def run_stack(q, oracle, X0, layers, ab_first, ab, wb, report=False):
     Nb, H, W, C = X0.shape
