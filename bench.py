@@ -271,6 +271,22 @@ def main():
             cs[0].copy_(planes)
         cold_us = timed(torch, branch_cold, max(steps, n_sets))
 
+    # comparison line (GEMM workloads with codes that fit int8): the same decoded product on the
+    # int8 matrix cores, operands arranged once beforehand
+    compare = None
+    if name in ("gemm8192", "fc4096") and w.ab <= 7 and w.wb <= 7:
+        Aa = q.compare_mfma_arrange(Xd)
+        Wa = q.compare_mfma_arrange(torch.from_numpy(np.ascontiguousarray(Wm.T)).to(dev))
+        pAa, pWa = p(Aa), p(Wa)
+
+        def mfma():
+            check(L.qnn_compare_mfma_gemm(pAa, pWa, w.M, w.N, w.K, pA, stream))
+        mfma_us = timed(torch, mfma, steps)
+        compare = {"what": "same decoded int8 product on v_mfma_i32_32x32x32_i8 (comparison line, untuned kernel)",
+                   "us": round(mfma_us, 2), "GOPS": round(ops / (mfma_us * 1e-6) / 1e9, 1),
+                   "frac_of_int8_mfma_peak_5000_TOPS": round(ops / (mfma_us * 1e-6) / 5.0e15, 4)}
+        branch()                                  # leave the branch result in the output buffer
+
     value = ops / (ms_per_step * 1e-3) / 1e9
     achieved = lane_ops / (branch_us * 1e-6)
     res = {
@@ -296,6 +312,7 @@ def main():
             "branch_kernel_us": round(branch_us, 2),
             "branch_kernel_cold_us": None if cold_us is None else round(cold_us, 2),
             "branch_kernel_effective_GOPS": round(ops / (branch_us * 1e-6) / 1e9, 1),
+            "comparison_int8_mfma": compare,
         },
         "roofline": {
             "bound": "alu",

@@ -266,6 +266,21 @@ qnn_status qnn_maxpool2x2_planes(const uint32_t *planes, int64_t Nb, int64_t H, 
                                  int bits, uint32_t *out_planes, void *stream);
 
 /*
+ * COMPARISON LINE, not part of the method: the same integer product of decoded int8 codes on the
+ * int8 matrix cores, so that a benchmark can report what the decomposition costs on this chip.
+ *   qnn_compare_mfma_arrange  codes int8 [rows][K] (any int8 values) -> `arranged`, an opaque
+ *       buffer of qnn_compare_mfma_arranged_bytes(rows, K) bytes, 16-byte aligned (rows and K are
+ *       padded to multiples of 32 with zeros).  Use it for A (rows = M) and for the transposed
+ *       weights (rows = N).
+ *   qnn_compare_mfma_gemm     acc int32 [M][N] = A . Wt^T from two arranged buffers.
+ * Limits: K * 127 * 127 < 2^31, M, N < 2^31.
+ */
+size_t qnn_compare_mfma_arranged_bytes(int64_t rows, int64_t K);
+qnn_status qnn_compare_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, void *arranged, void *stream);
+qnn_status qnn_compare_mfma_gemm(const void *A_arranged, const void *Wt_arranged, int64_t M, int64_t N,
+                                 int64_t K, int32_t *acc, void *stream);
+
+/*
  * Stand-alone scale epilogue (Eq. (9); Eq. (19)): out_f32[i][j] = (float)acc[i][j] * scale[j],
  * acc int32 [M][N], scale fp32 [N], out fp32 [M][N].  One IEEE binary32 multiply per
  * element, no fused multiply-add.  M == 0 or N == 0 launches nothing.

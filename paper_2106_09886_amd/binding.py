@@ -24,7 +24,8 @@ EXPORTS = (
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
-    "qnn_encode_real", "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
+    "qnn_encode_real", "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
+    "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
 )
 
 
@@ -103,6 +104,12 @@ def lib():
     L.qnn_conv2d_im2col_requant.restype = i32
     L.qnn_maxpool2x2_planes.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp]
     L.qnn_maxpool2x2_planes.restype = i32
+    L.qnn_compare_mfma_arranged_bytes.argtypes = [i64, i64]
+    L.qnn_compare_mfma_arranged_bytes.restype = sz
+    L.qnn_compare_mfma_arrange.argtypes = [vp, i64, i64, vp, vp]
+    L.qnn_compare_mfma_arrange.restype = i32
+    L.qnn_compare_mfma_gemm.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    L.qnn_compare_mfma_gemm.restype = i32
     L.qnn_encode_real.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
     L.qnn_encode_real.restype = i32
     gp = ctypes.POINTER(ConvGeometry)
@@ -372,4 +379,21 @@ def encode_real(x, bits, hrelu=False, want_codes=True, want_planes=True):
     st = lib().qnn_encode_real(_ptr(x), rows, K, bits, 1 if hrelu else 0, _ptr(codes), _ptr(planes), _stream())
     _check(st, "qnn_encode_real")
     return codes, planes
+
+
+def compare_mfma_arrange(codes):
+    """Comparison line: int8 codes [rows][K] -> opaque matrix-core operand buffer."""
+    _dev(codes, torch.int8, "codes")
+    rows, K = codes.shape
+    out = torch.empty(max(16, int(lib().qnn_compare_mfma_arranged_bytes(rows, K))), dtype=torch.uint8, device=codes.device)
+    _check(lib().qnn_compare_mfma_arrange(_ptr(codes), rows, K, _ptr(out), _stream()), "qnn_compare_mfma_arrange")
+    return out
+
+
+def compare_mfma_gemm(A_arranged, Wt_arranged, M, N, K, out=None):
+    """Comparison line: acc int32 [M][N] of the decoded product on the int8 matrix cores."""
+    acc = out if out is not None else torch.empty((M, N), dtype=torch.int32, device=A_arranged.device)
+    _check(lib().qnn_compare_mfma_gemm(_ptr(A_arranged), _ptr(Wt_arranged), M, N, K, _ptr(acc), _stream()),
+           "qnn_compare_mfma_gemm")
+    return acc
 

@@ -39,7 +39,8 @@ def build(jobs=None, verbose=False):
     work = [("qnn_api.hip", os.path.join(OBJ, "qnn_api.o"), []),
             ("qnn_pack.hip", os.path.join(OBJ, "qnn_pack.o"), []),
             ("qnn_epilogue.hip", os.path.join(OBJ, "qnn_epilogue.o"), []),
-            ("qnn_requant.hip", os.path.join(OBJ, "qnn_requant.o"), [])]
+            ("qnn_requant.hip", os.path.join(OBJ, "qnn_requant.o"), []),
+            ("qnn_compare_mfma.hip", os.path.join(OBJ, "qnn_compare_mfma.o"), [])]
     for ab in range(1, 9):
         work.append(("qnn_branch.hip", os.path.join(OBJ, "qnn_branch_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))
         work.append(("qnn_conv_small.hip", os.path.join(OBJ, "qnn_conv_small_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))

@@ -575,6 +575,30 @@ qnn_status qnn_maxpool2x2_planes(const uint32_t *planes, int64_t Nb, int64_t H, 
     return from_hip(launch_pool_planes(planes, Nb, H / 2, W / 2, cw, bits, out_planes, (hipStream_t)stream));
 }
 
+size_t qnn_compare_mfma_arranged_bytes(int64_t rows, int64_t K) {
+    if (rows <= 0 || K <= 0) return 0;
+    return (size_t)(((rows + 31) / 32) * ((K + 31) / 32) * 1024);
+}
+
+qnn_status qnn_compare_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, void *arranged, void *stream) {
+    if (rows < 0 || K < 0) return QNN_EINVAL;
+    if (rows == 0 || K == 0) return QNN_OK;
+    if (codes == nullptr || arranged == nullptr) return QNN_EINVAL;
+    if (!aligned16(arranged)) return QNN_EALIGN;
+    if (rows > kInt31 || K > kInt31 / (127 * 127)) return QNN_EUNSUPPORTED;
+    return from_hip(launch_mfma_arrange(codes, rows, K, arranged, (hipStream_t)stream));
+}
+
+qnn_status qnn_compare_mfma_gemm(const void *A_arranged, const void *Wt_arranged, int64_t M, int64_t N, int64_t K,
+                                 int32_t *acc, void *stream) {
+    if (M < 0 || N < 0 || K < 0) return QNN_EINVAL;
+    if (M == 0 || N == 0) return QNN_OK;
+    if (acc == nullptr || ((A_arranged == nullptr || Wt_arranged == nullptr) && K > 0)) return QNN_EINVAL;
+    if (!aligned16(A_arranged) || !aligned16(Wt_arranged) || !aligned4(acc)) return QNN_EALIGN;
+    if (M > kInt31 || N > kInt31 || K > kInt31 / (127 * 127)) return QNN_EUNSUPPORTED;
+    return from_hip(launch_mfma_gemm(A_arranged, Wt_arranged, M, N, K, acc, (hipStream_t)stream));
+}
+
 qnn_status qnn_scale_epilogue(const int32_t *acc, int64_t M, int64_t N, const float *scale,
                               float *out_f32, void *stream) {
     if (M < 0 || N < 0) return QNN_EINVAL;

@@ -357,3 +357,19 @@ def test_conv_activation_planes_just_below_4gib(q, oracle):
     want = oracle.conv3x3(codes, Wt)
     for i, n in enumerate(imgs):
         assert (acc[n].cpu().numpy().astype(np.int64) == want[i]).all(), n
+
+
+# ------------------------------------------------ comparison line: int8 matrix cores
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (32, 32, 32), (33, 65, 100), (128, 64, 256), (300, 200, 1000),
+                                   (257, 129, 64), (64, 640, 4096)])
+def test_compare_mfma_gemm(q, oracle, M, N, K):
+    """The int8 matrix-core evaluation of the decoded product gives the same integers."""
+    say("compare mfma", M, N, K)
+    rng = np.random.default_rng(M + N + K)
+    A = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    W = rng.integers(-127, 128, size=(K, N)).astype(np.int8)
+    Aa = q.compare_mfma_arrange(dev(A))
+    Wa = q.compare_mfma_arrange(dev(np.ascontiguousarray(W.T)))
+    got = host(q.compare_mfma_gemm(Aa, Wa, M, N, K))
+    assert (got.astype(np.int64) == oracle.gemm(A.astype(np.int16), W.astype(np.int16))).all()
+
