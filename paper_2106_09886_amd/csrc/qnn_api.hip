@@ -202,6 +202,11 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N), N, e);
     g.split_k = 0;
+    // Many rows per wavefront, several chunks and little arithmetic per chunk (one or two branches):
+    // keep the partial sums of a group of rows on chip instead of passing the whole output through
+    // memory once per chunk.  With more branches the round trip hides behind the arithmetic and the
+    // extra weight reloads of the row groups cost more than they save (measured on 8192^3).
+    g.row_groups = (g.rows_per_wave >= 64 && ab * wb <= 2) ? 1 : 0;
     // Long K and too few rows for every wavefront to amortise its weight chunks: let the four
     // wavefronts of a block share rows and split the chunks instead.
     const int chunks = (g.Cw + gemm_chunk_words(wb) - 1) / gemm_chunk_words(wb);
@@ -212,6 +217,7 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
         if (rows_per_block > 32) rows_per_block = 32;
         if (rows_per_block > M) rows_per_block = M;
         g.split_k = 1;
+        g.row_groups = 0;
         g.rows_per_wave = (int)rows_per_block;
     }
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
@@ -242,7 +248,7 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0;
+    g.split_k = 0; g.row_groups = 0;
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles, conv_passes(ab, wb, g.Cw), conv_group(ab, wb, g.Cw)), Cout),
                                           Cout, e);
@@ -284,7 +290,7 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
             g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
             g.col_tiles = (int)((Cout + 63) / 64);
-            g.split_k = 0;
+            g.split_k = 0; g.row_groups = 0;
             g.trace = nullptr; g.trace_waves = 0;
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
                                                   Cout, e);
@@ -520,7 +526,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0;
+    g.split_k = 0; g.row_groups = 0;
     g.trace = nullptr; g.trace_waves = 0;
     g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
     g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;

@@ -36,6 +36,7 @@ struct BranchArgs {
     int col_tiles;        // ceil(N / 64)
     int split_k;          // GEMM only: K chunks split over the wavefronts of a block; then
                           // rows_per_wave is the number of rows per BLOCK
+    int row_groups;       // GEMM only: run all K chunks over groups of rows, partial sums in LDS
     uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
     uint32_t trace_waves; // capacity of `trace` in wavefronts
     uint32_t *planes_out; // optional: the scaled result re-encoded with out_bits bits, as bit planes
