@@ -8,10 +8,12 @@
 // values below 2^24; larger magnitudes clamp), so the decision equals the one taken in
 // double precision on the same binary32 input.
 //
-// One wavefront handles one output pixel and 64 channels (lane = channel): the loads are
+// One work item is one output pixel and 64 channels (lane = channel): the loads are
 // contiguous 256-byte rows, and plane p of the 64 codes is the 64-bit ballot of "digit p of
-// u = (code + 2^bits - 1)/2 is set", i.e. two packed words at once.  HBM-bound: 4 (16 with
-// pooling) bytes in and bits/8 (+1 with codes) bytes out per output element.
+// u = (code + 2^bits - 1)/2 is set", i.e. two packed words at once.  A wavefront keeps several
+// items in flight.  HBM-bound: 4 (16 with pooling) bytes in and bits/8 (+1 with codes) bytes
+// out per output element.  The same kernel serves the real-valued front end (qnn_encode_real):
+// an optional clip to [0,1] and one binary32 multiply by 2^bits - 1 before the rule.
 #include "qnn_internal.h"
 
 namespace qnn {
@@ -128,10 +130,13 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
 // 2x2 max-pool of codes that are already stored as bit planes.  The stored index
 // u = (code + 2^bits - 1)/2 is monotone in the code, so the maximum code is the maximum u, and
 // the maximum of bit-sliced numbers is a bitwise comparator run from the high plane down: one
 // thread handles 32 channels of one output pixel.
+// ---------------------------------------------------------------------------------------
+
 // Keeps a value opaque to the optimiser.  The comparator below is a chain of three-input
 // boolean steps; folded across steps into v_bitop3_b32 truth tables by this compiler version
 // it gave wrong results for three planes and more, step by step it is correct.
