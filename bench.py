@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--bits", type=int, default=None,
                     help="gemm8192 only: activation = weight bit width (1..6 in the paper's sweep; default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="additionally capture one step into a HIP graph and report the time per replay "
+                         "(config.graph_ms_per_step); the headline value stays the eagerly launched step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of 256 MiB (a kernel of known HBM traffic) "
                          "so that a counter run can be scaled against it")
@@ -287,6 +290,22 @@ def main():
                    "frac_of_int8_mfma_peak_5000_TOPS": round(ops / (mfma_us * 1e-6) / 5.0e15, 4)}
         branch()                                  # leave the branch result in the output buffer
 
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            stream = ctypes.c_void_p(side.cuda_stream)      # the closures launch on `stream`
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+            step()
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        graph_ms = timed(torch, gr.replay, steps) / 1e3
+
     value = ops / (ms_per_step * 1e-3) / 1e9
     achieved = lane_ops / (branch_us * 1e-6)
     res = {
@@ -313,6 +332,7 @@ def main():
             "branch_kernel_cold_us": None if cold_us is None else round(cold_us, 2),
             "branch_kernel_effective_GOPS": round(ops / (branch_us * 1e-6) / 1e9, 1),
             "comparison_int8_mfma": compare,
+            "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
         },
         "roofline": {
             "bound": "alu",

@@ -133,3 +133,50 @@ def test_stack_config5_full(q, oracle):
     X0, layers = inputs.make_stack(w)
     say("vgg16 stack: oracle + gpu, layer by layer")
     run_stack(q, oracle, X0, layers, w.ab_first, w.ab, w.wb, report=True)
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_layer_under_graph_capture(q, oracle):
+    """The entry points only enqueue kernels on the given stream (no allocation, no memset, no
+    synchronisation), so a layer can be captured into a HIP graph.  The graph is replayed several
+    times with new inputs and eager work between the replays; every replay must equal the oracle."""
+    import torch
+    rng = np.random.default_rng(31)
+    Nb, H, W, C, Cout, ab, wb, ob = 2, 12, 12, 64, 70, 2, 2, 4
+    Wt = rand_codes(rng, (Cout, 3, 3, C), wb)
+    s = rng.uniform(0.01, 0.05, Cout).astype(np.float32)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    sd = dev(s)
+    x_static = torch.empty((Nb, H, W, C), dtype=torch.int8, device="cuda")
+    X0 = rand_codes(rng, (Nb, H, W, C), ab)
+    x_static.copy_(dev(X0))
+    side = torch.cuda.Stream()                       # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                    # warm-up outside capture, as torch asks
+        xp = q.encode_pack(x_static.reshape(Nb * H * W, C), ab)
+        q.conv2d_packed_requant(xp, ab, Wp, wb, Nb, H, W, C, Cout, ob, scale=sd, want_acc=True, want_f32=True)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        xp = q.encode_pack(x_static.reshape(Nb * H * W, C), ab)
+        planes, acc, y = q.conv2d_packed_requant(xp, ab, Wp, wb, Nb, H, W, C, Cout, ob, scale=sd, want_acc=True,
+                                                 want_f32=True)
+        pooled = q.maxpool2x2_planes(planes, Nb, H, W, Cout, ob)
+    for rep in range(4):
+        X = rand_codes(rng, (Nb, H, W, C), ab)
+        x_static.copy_(dev(X))
+        junk = torch.randn(1 << 16, device="cuda").sum()      # unrelated eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.conv3x3(X, Wt)
+        assert (host(acc).astype(np.int64) == want).all(), rep
+        yw = oracle.scale_f32(want, s)
+        assert (host(y) == yw).all(), rep
+        codes = oracle.requant(yw, ob)
+        pw, _ = oracle.pack_planes(codes.reshape(-1, Cout), ob)
+        assert (planes_u32(planes) == pw).all(), rep
+        pooled_codes = oracle.requant(oracle.maxpool2x2(yw), ob)
+        ppw, _ = oracle.pack_planes(pooled_codes.reshape(-1, Cout), ob)
+        assert (planes_u32(pooled) == ppw).all(), rep
+        del junk
