@@ -215,3 +215,38 @@ def test_stack_config5_full_fused(q, oracle):
     X0, layers = inputs.make_stack(w)
     say("vgg16 stack, fused kernels: oracle + gpu, layer by layer")
     run_stack_fused(q, oracle, X0, layers, w.ab_first, w.ab, w.wb, report=True)
+
+
+def test_stack_mixed_precision(q, oracle):
+    """Per-layer bit widths (Sec. 5: activations at 4 bits with 5/3/2/2/6-bit weights; here also a
+    change of the activation width along the chain): every layer's out_bits is the next one's ab."""
+    rng = np.random.default_rng(404)
+    Nb, H, W = 2, 16, 16
+    chans = [3, 32, 64, 64, 96, 40]
+    wbs = [5, 3, 2, 2, 6]
+    abs_in = [8, 4, 4, 3, 4]          # activation width each layer reads
+    ab_out = [4, 4, 3, 4, 2]          # = width the next layer reads (the last one is free)
+    pools = [False, True, False, True, False]
+    codes = rand_codes(rng, (Nb, H, W, chans[0]), abs_in[0])
+    x_planes = None
+    C = chans[0]
+    for l in range(5):
+        Cout, wb, ab, ob, pool = chans[l + 1], wbs[l], abs_in[l], ab_out[l], pools[l]
+        Wt = rand_codes(rng, (Cout, 3, 3, C), wb)
+        o_acc = oracle.conv3x3(codes, Wt)
+        s = scales_for(rng, o_acc, ob, Cout)
+        Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+        if l == 0:
+            x_planes, _, _ = q.conv2d_im2col_requant(dev(codes), ab, Wp, wb, Cout, ob, scale=dev(s))
+        else:
+            x_planes, _, _ = q.conv2d_packed_requant(x_planes, ab, Wp, wb, Nb, H, W, C, Cout, ob, scale=dev(s))
+        if pool:
+            x_planes = q.maxpool2x2_planes(x_planes, Nb, H, W, Cout, ob)
+        o_y = oracle.scale_f32(o_acc, s)
+        codes = oracle.requant(oracle.maxpool2x2(o_y) if pool else o_y, ob)
+        want, bad = oracle.pack_planes(codes.reshape(-1, Cout), ob)
+        assert bad == 0 and (planes_u32(x_planes) == want).all(), "layer %d" % (l + 1)
+        assert len(np.unique(codes)) > 1
+        C = Cout
+        if pool:
+            H, W = H // 2, W // 2
