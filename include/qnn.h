@@ -72,7 +72,7 @@ int qnn_set_wave_trace(void *buffer, size_t bytes);
 #define QNN_PACK_VALIDATE 1u /* count entries that are not codes into *bad_count */
 
 /*
- * Encode + pack (Eq. (7); the "store those numbers by bits" step of Sec. 5.4).
+ * Encode + pack (Eq. (7); the bit-wise storage of the encoded matrices that Sec. 5.4 starts from).
  *   codes      [rows][K] row-major integer codes; element size code_bytes = 1 (int8,
  *              bits <= 7) or 2 (int16, any bits).  A valid code is odd with
  *              |v| <= 2^bits - 1.

@@ -52,7 +52,7 @@ int64_t qnn_oracle_decode(const int8_t *c, int bits)
     return v;
 }
 
-/* ---- bit-plane store (Sec. 3.1 bit-plane rows; Sec. 5.4 "store by bits") - */
+/* ---- bit-plane store (Sec. 3.1 bit-plane rows; Sec. 5.4 bit-wise storage) - */
 
 /* codes[rows][K] -> planes[rows][bits][Kw], Kw = ceil(K/32).
  * Plane p (0-based) holds element c_{p+1}; element k of a row is bit (k mod 32)

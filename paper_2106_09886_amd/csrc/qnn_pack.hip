@@ -1,4 +1,4 @@
-// Encode + pack kernel (paper Eq. (7); "store those numbers by bits", Sec. 5.4).
+// Encode + pack kernel (paper Eq. (7); the bit-wise storage of the encoded matrices, Sec. 5.4).
 //
 // A code v = sum_m 2^(m-1) c_m with c_m = +-1 has c_m = +1 exactly where binary digit m-1 of
 // u = (v + 2^bits - 1) / 2 is set, so plane p of the output is digit p of u, i.e. digit p+1
