@@ -164,30 +164,32 @@ __global__ __launch_bounds__(256) void window_pack_kernel(const uint32_t *__rest
         const int ow = (int)(opix % q.Wo);
         const int oh = (int)((opix / q.Wo) % q.Ho);
         const int64_t img = opix / ((int64_t)q.Wo * q.Ho);
-        uint32_t acc[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] = 0u;
-        int t = 0;
+        // The bit position t*C grows with the tap number, so the row is built as a stream: a 64-bit
+        // window collects taps and its low word is written out whenever it is complete.
+        uint32_t *dst = out + it * KWP;
+        uint64_t win = 0;                                // bits [32*wcur, 32*wcur + 64) of the row
+        int wcur = 0, t = 0;
         for (int kh = 0; kh < q.KH; ++kh) {
             const int ih = oh * q.sh - q.ph + kh * q.dh;
+            const bool row_ok = (unsigned)ih < (unsigned)H;
             for (int kw = 0; kw < q.KW; ++kw, ++t) {
                 const int iw = ow * q.sw - q.pw + kw * q.dw;
-                if ((unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W) {
+                const int bit = t * C - 32 * wcur;       // < 32 on entry: completed words were flushed
+                if (row_ok && (unsigned)iw < (unsigned)W) {
                     const int64_t ipix = (img * H + ih) * W + iw;
                     const uint32_t x = (p < AB) ? (planes[ipix * AB + p] & cmask) : cmask;
-                    const int bit = t * C, wi = bit >> 5, sh = bit & 31;
-                    const uint32_t lo = x << sh, hi = sh ? x >> (32 - sh) : 0u;
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        if (k == wi) acc[k] |= lo;
-                        if (k == wi + 1) acc[k] |= hi;
-                    }
+                    win |= (uint64_t)x << bit;
+                }
+                if (bit + C >= 32) {                     // the low word is complete
+                    dst[wcur++] = (uint32_t)win;
+                    win >>= 32;
                 }
             }
         }
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (k < KWP) out[it * KWP + k] = acc[k];
+        for (; wcur < KWP; ++wcur) {                     // the partly filled word, then padding words
+            dst[wcur] = (uint32_t)win;
+            win >>= 32;
+        }
     }
 }
 
