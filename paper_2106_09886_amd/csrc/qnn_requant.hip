@@ -15,17 +15,30 @@
 // out per output element.  The same kernel serves the real-valued front end (qnn_encode_real):
 // an optional clip to [0,1] and one binary32 multiply by 2^bits - 1 before the rule.
 #include "qnn_internal.h"
+#include "qnn_device_util.h"
 
 namespace qnn {
 namespace {
 
+// Stored index u = (code + 2^BITS - 1) / 2 of the rule above: with H = 2^(BITS-1) and
+// f = min(floor(|y|/2), H-1),  u = f xor (y > 0 ? H : H-1)  (and code = 2u - (2^BITS - 1)).
 template <int BITS>
-__device__ __forceinline__ int round_odd(float y) {
-    constexpr float CMAX = (float)((1 << BITS) - 1);
-    const float a = fabsf(y);
-    float c = 2.0f * floorf(a * 0.5f) + 1.0f;
-    c = (c <= CMAX) ? c : CMAX;                 // also catches inf / nan
-    return (y > 0.0f) ? (int)c : -(int)c;
+__device__ __forceinline__ uint32_t round_odd_index(float y) {
+    constexpr uint32_t H = 1u << (BITS - 1);
+    constexpr float FMAX = (float)(H - 1u);
+    float t = floorf(fabsf(y) * 0.5f);
+    t = (t <= FMAX) ? t : FMAX;                 // also catches inf / nan
+    return (uint32_t)t ^ ((y > 0.0f) ? H : H - 1u);
+}
+
+// Steps 0 .. BITS-1 of the plane emission (emit_step of qnn_device_util.h): lanes 2k, 2k+1 of
+// `mine` receive the two words of plane BITS-1-k.
+template <int BITS, int K = 0>
+__device__ __forceinline__ void emit_all(uint32_t &top, int &mine) {
+    if constexpr (K < BITS) {
+        emit_step<K>(top, mine);
+        emit_all<BITS, K + 1>(top, mine);
+    }
 }
 
 // U work items (pixel, 64-channel group) per loop trip: all their loads are issued before any
@@ -97,22 +110,72 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
             // multiply by 2^bits - 1 brings the number space onto the code grid (re-encoding: x 1)
             float val = v[u];
             if (hrelu) val = (val > 0.0f) ? val : 0.0f;
-            const int code = round_odd<BITS>(val * premul);
+            const uint32_t uidx = valid[u] ? round_odd_index<BITS>(val * premul) : 0u;   // 0: all plane bits clear
             const int c = cg[u] * 64 + lane;
-            if (codes != nullptr && valid[u]) codes[pix[u] * (int64_t)C + c] = (CodeT)code;
+            if (codes != nullptr && valid[u]) codes[pix[u] * (int64_t)C + c] = (CodeT)(2 * (int)uidx - VMAX);
             if (planes != nullptr) {
-                const int uidx = (code + VMAX) >> 1;
-                // lane 2p holds the low word of plane p, lane 2p+1 the high word: one store for all
-                uint32_t mine = 0u;
-#pragma unroll
-                for (int p = 0; p < BITS; ++p) {
-                    const uint64_t mask = __ballot(valid[u] && ((uidx >> p) & 1));
-                    if (lane == 2 * p) mine = (uint32_t)mask;
-                    if (lane == 2 * p + 1) mine = (uint32_t)(mask >> 32);
-                }
-                const int p = lane >> 1, h = lane & 1;
+                // index at the top of the register; each doubling shifts out one plane, high plane
+                // first, as the carry mask of the wavefront = the plane's two packed words
+                uint32_t top = uidx << (32 - BITS);
+                int mine = (int)top;                          // every lane that stores is overwritten
+                emit_all<BITS>(top, mine);
+                const int p = BITS - 1 - (lane >> 1), h = lane & 1;
                 if (lane < 2 * BITS && 2 * cg[u] + h < Cw)
-                    planes[(pix[u] * BITS + p) * (int64_t)Cw + 2 * cg[u] + h] = mine;
+                    planes[(pix[u] * BITS + p) * (int64_t)Cw + 2 * cg[u] + h] = (uint32_t)mine;
+            }
+        }
+    }
+}
+
+// The same without pooling when C is a multiple of 64: item i is the 64 consecutive floats
+// y[64 i ..], i.e. (pixel i / (C/64), channel group i % (C/64)), and its plane words are
+// planes[(pixel*BITS + p)*Cw + 2*group + h].  All addressing is wave-uniform (scalar unit) plus
+// a per-lane constant, through buffer descriptors; the vector ALU only sees the rule itself.
+template <typename CodeT, int BITS, int U>
+__global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restrict__ y, int64_t items, int cgroups,
+                                                           float premul, int hrelu, CodeT *__restrict__ codes,
+                                                           uint32_t *__restrict__ planes) {
+    constexpr int VMAX = (1 << BITS) - 1;
+    const int lane = (int)(threadIdx.x & 63);
+    const int Cw = 2 * cgroups;
+    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) +
+                          __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // wave-uniform
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    // lane 2k+h stores half h of plane BITS-1-k (see emit_step)
+    const int store_off = ((BITS - 1 - (lane >> 1)) * Cw + (lane & 1)) * 4;
+    const bool stores = lane < 2 * BITS;
+    for (int64_t it0 = wave0 * U; it0 < items; it0 += nwaves * U) {
+        const int n = (int)((items - it0 < U) ? items - it0 : U);           // items of this trip, wave-uniform
+        const __amdgpu_buffer_rsrc_t src = make_rsrc((void *)(y + it0 * 64), (uint32_t)n * 256u);
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            v[u] = 0.0f;
+            if (u < n) v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4 + u * 256, 0, 0));
+        }
+        int64_t pix = it0 / cgroups;
+        int cg = (int)(it0 - pix * cgroups);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (u < n) {
+                float val = v[u];
+                if (hrelu) val = (val > 0.0f) ? val : 0.0f;
+                const uint32_t uidx = round_odd_index<BITS>(val * premul);
+                if (codes != nullptr) {
+                    const __amdgpu_buffer_rsrc_t dc = make_rsrc((void *)(codes + (it0 + u) * 64), 64u * (uint32_t)sizeof(CodeT));
+                    const int code = 2 * (int)uidx - VMAX;
+                    if (sizeof(CodeT) == 1) __builtin_amdgcn_raw_buffer_store_b8((char)code, dc, lane, 0, 0);
+                    else __builtin_amdgcn_raw_buffer_store_b16((short)code, dc, lane * 2, 0, 0);
+                }
+                if (planes != nullptr) {
+                    uint32_t top = uidx << (32 - BITS);
+                    int mine = (int)top;                      // every lane that stores is overwritten
+                    emit_all<BITS>(top, mine);
+                    uint32_t *dst = planes + (pix * BITS) * Cw + 2 * cg;    // wave-uniform
+                    const __amdgpu_buffer_rsrc_t dp = make_rsrc((void *)dst, (uint32_t)(BITS * Cw) * 4u);
+                    if (stores) __builtin_amdgcn_raw_buffer_store_b32(mine, dp, store_off, 0, 0);
+                }
+                if (++cg == cgroups) { cg = 0; ++pix; }
             }
         }
     }
@@ -124,6 +187,9 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
     if (pool)
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
+    else if (C % 64 == 0)
+        hipLaunchKernelGGL((requant_flat_kernel<CodeT, BITS, 16>), dim3(blocks), dim3(256), 0, s, y,
+                           out_pixels * (C / 64), C / 64, premul, hrelu, (CodeT *)codes, planes);
     else
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
