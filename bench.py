@@ -47,6 +47,81 @@ def timed(torch, fn, n):
     return a.elapsed_time(b) / n * 1e3
 
 
+def side_suites(name, args, steps, warmup, torch, np, q, dev):
+    """Micro-benchmarks outside the headline: the memory-bound kernels at sizes that fill the chip,
+    and qnn_conv2d_general on layer shapes of the networks the paper evaluates.  One JSON line."""
+    def avg_us(fn):
+        for _ in range(warmup):
+            fn()
+        return timed(torch, fn, steps)
+
+    rows = []
+    if name == "hbm_kernels":
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        t = avg_us(lambda: dst.copy_(src))
+        rows.append({"kernel": "device copy 1 GiB (reference)", "us": round(t, 1), "GBps": round(2 * (1 << 30) / t / 1e3, 1)})
+        del src, dst
+        for bits in (2, 4):
+            r, K = 65536, 8192
+            codes = (torch.randint(0, 1 << bits, (r, K), dtype=torch.int8, device=dev) * 2 - ((1 << bits) - 1)).to(torch.int8)
+            out = torch.empty((r, bits, K // 32), dtype=torch.int32, device=dev)
+            t = avg_us(lambda: q.encode_pack(codes, bits, out=out))
+            rows.append({"kernel": "qnn_encode_pack int8 %dx%d, %d bits" % (r, K, bits), "us": round(t, 1),
+                         "GBps": round(r * K * (1 + bits / 8) / t / 1e3, 1)})
+            del codes, out
+        for (Nb, H, W, C, pool) in ((16, 224, 224, 64, False), (16, 224, 224, 64, True), (64, 56, 56, 256, False)):
+            y = torch.randn((Nb, H, W, C), device=dev) * 5
+            t = avg_us(lambda: q.requant_pack(y, 4, pool=pool, want_codes=False))
+            n_out = Nb * H * W * C / (4 if pool else 1)
+            rows.append({"kernel": "qnn_requant_pack %dx%dx%dx%d -> 4-bit planes%s" % (Nb, H, W, C, ", 2x2 pool" if pool else ""),
+                         "us": round(t, 1), "GBps": round((Nb * H * W * C * 4 + n_out / 2) / t / 1e3, 1)})
+            del y
+        x = torch.randn((65536, 4096), device=dev)
+        t = avg_us(lambda: q.encode_real(x, 4, want_codes=False))
+        rows.append({"kernel": "qnn_encode_real 65536x4096 -> 4-bit planes", "us": round(t, 1),
+                     "GBps": round(x.numel() * 4.5 / t / 1e3, 1)})
+        del x
+        acc = torch.randint(-1000, 1000, (65536, 4096), dtype=torch.int32, device=dev)
+        s = torch.rand(4096, device=dev)
+        t = avg_us(lambda: q.scale_epilogue(acc, s))
+        rows.append({"kernel": "qnn_scale_epilogue 65536x4096", "us": round(t, 1), "GBps": round(acc.numel() * 8 / t / 1e3, 1)})
+        head = rows[1]
+        res = {"metric": "GB/s of qnn_encode_pack (algorithmic bytes: codes in + planes out)", "value": head["GBps"],
+               "unit": "GB/s", "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": head["GBps"], "peak": 8000.0,
+                                            "unit": "GB/s", "frac": round(head["GBps"] / 8000.0, 4), "traffic": None}}
+    else:
+        cases = [("ResNet stem 7x7 stride 2, 3->64, 224^2, W2A8", 32, 224, 224, 3, 64, 8, 2, 7, 7, 2, 3, 1, False),
+                 ("3x3 stride 2, 128->128, 56^2, W2A2", 32, 56, 56, 128, 128, 2, 2, 3, 3, 2, 1, 1, False),
+                 ("1x1 stride 2, 256->512, 56^2, W2A2", 32, 56, 56, 256, 512, 2, 2, 1, 1, 2, 0, 1, False),
+                 ("3x3 stride 1, 64->64, 56^2, W2A2 (general kernel on the headline shape)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
+                 ("3x3 dilation 2, 256->256, 33^2, W3A4", 16, 33, 33, 256, 256, 4, 3, 3, 3, 1, 2, 2, False),
+                 ("4x4 stride 2 transposed, 256->128, 28^2, W2A2", 16, 28, 28, 256, 128, 2, 2, 4, 4, 2, 1, 1, True)]
+        for (label, Nb, H, W, C, Cout, ab, wb, KH, KW, st, pd, dl, tr) in cases:
+            Cw = (C + 31) // 32
+            Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * H * W, ab, Cw), dtype=torch.int32, device=dev)
+            if C < 32:
+                Xp &= (1 << C) - 1
+            Wp = torch.randint(0, 1 << min(C, 30), (Cout, KH * KW, wb, Cw), dtype=torch.int32, device=dev)
+            sd = torch.rand(Cout, device=dev)
+            geo = q.conv_geometry(KH, KW, stride=st, pad=pd, dilation=dl, transposed=tr)
+            Ho, Wo = q.conv2d_general_output_size(H, W, geo)
+            t = avg_us(lambda: q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=sd))
+            taps = KH * KW / (st * st if tr else 1)
+            ops = 2.0 * Nb * Ho * Wo * Cout * taps * C
+            rows.append({"layer": label, "out": "%dx%d" % (Ho, Wo), "us": round(t, 1), "effective_GOPS": round(ops / t / 1e3, 1),
+                         # word-per-tap lane-ops; not meaningful on the packed-window path (few channels)
+                         "frac_of_lane_op_peak": None if C < 32 else round(
+                             2.0 * ab * wb * Nb * Ho * Wo * Cout * taps * Cw / (t * 1e-6) / PEAK_LANE_OPS, 3)})
+            del Xp, Wp
+        res = {"metric": "effective quantized GOPS of qnn_conv2d_general, first listed layer", "value": rows[0]["effective_GOPS"],
+               "unit": "GOPS"}
+    res.update({"n_gpus": 1, "steps": steps, "warmup": warmup, "higher_is_better": True, "scaling": "weak",
+                "vs_baseline": None, "data": "synthetic", "config": {"workload": name, "results": rows}})
+    print(json.dumps(res))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,7 +129,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="resnet18_s1",
                     choices=["resnet18_s1", "resnet50_s3", "fc4096", "gemm64", "gemm8192", "vgg16_stack",
-                             "vgg16_stack_fused"])
+                             "vgg16_stack_fused", "hbm_kernels", "conv_geometries"])
     ap.add_argument("--bits", type=int, default=None,
                     help="gemm8192 only: activation = weight bit width (1..6 in the paper's sweep; default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -100,6 +175,9 @@ def main():
 
     def check(st):
         assert st == 0, L.qnn_status_string(st)
+
+    if name in ("hbm_kernels", "conv_geometries"):
+        return side_suites(name, args, steps, warmup, torch, np, q, dev)
 
     cpu = None
     if name == "vgg16_stack":
