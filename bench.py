@@ -7,8 +7,11 @@ already resident in HBM: encode + pack the activation codes, then the branch pro
 The weights are static parameters and are packed once before the timed region.
 
 Default workload: `resnet18_s1`, the ResNet-18-stage-1-shaped W2A2 3x3 convolution the target
-is quoted on.  Other workloads (`--workload`): `resnet50_s3`, `fc4096`, `gemm64`, and
-`vgg16_stack` (13 chained layers: conv + scale, then max-pool / re-encode / pack per layer).
+is quoted on.  Other workloads (`--workload`): `resnet50_s3`, `fc4096`, `gemm64`, `gemm8192`
+(`--bits b`, with the int8 matrix-core comparison line), `vgg16_stack` (13 chained layers: conv +
+scale, then max-pool / re-encode / pack per layer), `vgg16_stack_fused` (the same through the
+fused kernels), and two side suites that print their own tables: `hbm_kernels` (the
+memory-bound kernels at chip-filling sizes) and `conv_geometries` (`qnn_conv2d_general`).
 
 Prints ONE JSON line.  `value` is the effective quantized throughput 2*M*N*K / t_step in
 GOPS.  `roofline` prices the dominant kernel (the branch kernel) against the chip's integer
@@ -117,7 +120,7 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
         res = {"metric": "effective quantized GOPS of qnn_conv2d_general, first listed layer", "value": rows[0]["effective_GOPS"],
                "unit": "GOPS"}
     res.update({"n_gpus": 1, "steps": steps, "warmup": warmup, "higher_is_better": True, "scaling": "weak",
-                "vs_baseline": None, "data": "synthetic", "config": {"workload": name, "results": rows}})
+                "vs_baseline": None, "dtype": "u32", "data": "synthetic", "config": {"workload": name, "results": rows}})
     print(json.dumps(res))
     return 0
 
@@ -397,11 +400,12 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 bit-planes, int32 accumulate, fp32 scale",
+        "dtype": "u32",
         "data": "synthetic",
         "config": {
             "workload": desc,
             "branches": B,
+            "arithmetic": "xor + popcount on u32 bit-plane words, int32 accumulation, one fp32 multiply per output",
             "weights": "packed once before the timed region (static parameters)",
             "outputs": outputs,
             "bit_ops_per_s": round(B * ops / (ms_per_step * 1e-3), 1) if B else None,
