@@ -21,24 +21,28 @@
 namespace qnn {
 namespace {
 
-// Input coordinate of one tap along one axis.  Forward: i = o*stride + off (off = k*dil - pad).
-// Transposed: o = i*stride - pad + k*dil, so i = (o + off) / stride with off = pad - k*dil, if
-// that division is exact.  Returns false if the tap does not touch the image.
-__device__ __forceinline__ bool tap_coord(bool transposed, int o, int stride, int off, int size, int &i) {
-    if (!transposed) {
-        i = o * stride + off;
-    } else {
-        const int num = o + off;
-        if (num < 0) return false;
-        i = num / stride;
-        if (i * stride != num) return false;
-    }
-    return (unsigned)i < (unsigned)size;
+// Transposed convolution, one axis.  Output o gets a contribution of kernel element k from the
+// input i with o = i*stride - pad + k*dil, i.e. i = (o + off) / stride with off = pad - k*dil, if
+// that division is exact.  With o = oq*stride + om and off = fq*stride + fm (0 <= om, fm < stride)
+// it is exact iff om + fm is 0 or stride, and then i = oq + fq + (om + fm == stride): no division
+// per tap.
+struct AxisSplit {
+    int q, m;             // value = q * stride + m, 0 <= m < stride
+};
+__device__ __forceinline__ int floor_div(int a, int b) {       // b > 0
+    const int qd = a / b;
+    return (a % b != 0 && a < 0) ? qd - 1 : qd;
 }
-
-// offset of kernel element k along one axis: see tap_coord
-__device__ __forceinline__ int tap_off(bool transposed, int k, int dil, int pad) {
-    return transposed ? pad - k * dil : k * dil - pad;
+__device__ __forceinline__ AxisSplit split(int v, int stride) {
+    AxisSplit s;
+    s.q = floor_div(v, stride);
+    s.m = v - s.q * stride;
+    return s;
+}
+__device__ __forceinline__ bool transposed_coord(AxisSplit o, AxisSplit f, int stride, int size, int &i) {
+    const int sum = o.m + f.m;
+    i = o.q + f.q + (sum == stride ? 1 : 0);
+    return (sum == 0 || sum == stride) && (unsigned)i < (unsigned)size;
 }
 
 // State of one chunk (TT taps x CWT channel words) on the fast path: the taps whose kernel row
@@ -108,14 +112,13 @@ __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, c
 
 // One output pixel of one chunk with every tap tested (image borders, transposed convolution,
 // chunks with padding words).
-template <int AB, int WB, int CWT, int TT, class OV>
+// `tap(i, ih, iw)` says whether tap i of the chunk touches the image for this output pixel and
+// where.
+template <int AB, int WB, int CWT, int TT, class OV, class TapFn>
 __device__ __forceinline__ void gen_pixel_checked(const BranchArgs &g, const OV &ov, uniform_words As,
-                                                  const uint32_t (&w)[TT][WB][CWT], const int (&offh)[TT],
-                                                  const int (&offw)[TT], int r0, int r, int img, int oh, int ow,
-                                                  int c0, int t0, bool first, bool last) {
-    const ConvGeom &q = g.geo;
-    const int T = q.KH * q.KW, Cw = g.Cw;
-    const bool transposed = q.transposed != 0;
+                                                  const uint32_t (&w)[TT][WB][CWT], TapFn tap, int r0, int r,
+                                                  int img, int c0, bool first, bool last) {
+    const int Cw = g.Cw;
     int prev = 0;
     if (!first)
         prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
@@ -126,9 +129,7 @@ __device__ __forceinline__ void gen_pixel_checked(const BranchArgs &g, const OV 
 #pragma unroll
     for (int i = 0; i < TT; ++i) {
         int ih, iw;
-        const bool ok = (t0 + i < T) && tap_coord(transposed, oh, q.sh, offh[i], g.H, ih) &&
-                        tap_coord(transposed, ow, q.sw, offw[i], g.W, iw);
-        if (ok) {                           // uniform
+        if (tap(i, ih, iw)) {               // uniform
             const int pix = (img * g.H + ih) * g.W + iw;
             uint32_t a[AB][CWT];
 #pragma unroll
@@ -153,12 +154,7 @@ __device__ __forceinline__ void gen_pixel_checked(const BranchArgs &g, const OV 
     finish_row<false>(ov, r - r0, val, /*first=*/true, last);   // the earlier part is already added
 }
 
-__device__ __forceinline__ int floor_div(int a, int b) {       // b > 0
-    const int qd = a / b;
-    return (a % b != 0 && a < 0) ? qd - 1 : qd;
-}
-
-template <int AB, int WB, int CWT, int TT, bool EMIT>
+template <int AB, int WB, int CWT, int TT, bool TR, bool EMIT>
 __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
@@ -175,7 +171,6 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     uniform_words As = as_uniform(g.A);
     const ConvGeom &q = g.geo;
     const int T = q.KH * q.KW, Cw = g.Cw;
-    const bool transposed = q.transposed != 0;
     if (Cw == 0 || T == 0) {                            // empty sum
         for (int r = r0; r < r1; ++r) finish_row<true>(ov, r - r0, 0, true, true);
         return;
@@ -193,18 +188,29 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
         for (int t0 = 0; t0 < T; t0 += TT) {
             const bool first = (c0 == 0 && t0 == 0);
             const bool last = (c0 + CWT >= Cw && t0 + TT >= T);
-            int offh[TT], offw[TT];         // offsets of the chunk's taps along both axes (see tap_coord)
-            // output columns for which every tap of the chunk is inside the image: [lo, hi)
+            // offsets of the chunk's taps along both axes: forward, input = output*stride + off with
+            // off = k*dil - pad; transposed, off = pad - k*dil split by the stride (see AxisSplit)
+            int offh[TT], offw[TT];
+            AxisSplit fh[TR ? TT : 1], fw[TR ? TT : 1];
+            // forward: output columns for which every tap of the chunk is inside the image, [lo, hi)
             int lo = 0, hi = q.Wo;
 #pragma unroll
             for (int i = 0; i < TT; ++i) {
                 const int t = t0 + i;
                 const int kh = t / q.KW, kw = t - kh * q.KW;
-                offh[i] = tap_off(transposed, kh, q.dh, q.ph);
-                offw[i] = tap_off(transposed, kw, q.dw, q.pw);
-                if (t < T) {
-                    lo = max(lo, -floor_div(offw[i], q.sw));                  // ceil(-off / s)
-                    hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
+                if constexpr (TR) {
+                    fh[i] = split(q.ph - kh * q.dh, q.sh);
+                    fw[i] = split(q.pw - kw * q.dw, q.sw);
+                    fh[i].q = __builtin_amdgcn_readfirstlane(fh[i].q); fh[i].m = __builtin_amdgcn_readfirstlane(fh[i].m);
+                    fw[i].q = __builtin_amdgcn_readfirstlane(fw[i].q); fw[i].m = __builtin_amdgcn_readfirstlane(fw[i].m);
+                    offh[i] = offw[i] = 0;
+                } else {
+                    offh[i] = kh * q.dh - q.ph;
+                    offw[i] = kw * q.dw - q.pw;
+                    if (t < T) {
+                        lo = max(lo, -floor_div(offw[i], q.sw));              // ceil(-off / s)
+                        hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
+                    }
                 }
 #pragma unroll
                 for (int qq = 0; qq < WB; ++qq)
@@ -212,55 +218,82 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
                     for (int j = 0; j < CWT; ++j)
                         c.w[i][qq][j] = (t < T && c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
             }
-            lo = __builtin_amdgcn_readfirstlane(lo);
-            hi = __builtin_amdgcn_readfirstlane(hi);
-            const bool fast_chunk = !transposed && (c0 + CWT <= Cw);
             int ow = ow0, oh = oh0, img = n0;
             int r = r0;
-            while (r < r1) {
-                const int row_end = min(r1, r - ow + q.Wo);                   // end of this output row within the range
-                // fast interval of this row in pixel numbers
-                int fa = r, fb = r;
-                if (fast_chunk) {
-                    // taps of the chunk whose kernel row exists for this output row; their offsets
-                    uint32_t okmask = 0u, safe_off = 0u;
-#pragma unroll
-                    for (int i = 0; i < TT; ++i) {
-                        const bool ok = (t0 + i < T) && (unsigned)(oh * q.sh + offh[i]) < (unsigned)g.H;
-                        c.toff[i] = (uint32_t)(offh[i] * g.W + offw[i]) * pixel_bytes;
-                        if (ok) {
-                            if (okmask == 0u) safe_off = c.toff[i];
-                            okmask |= 1u << i;
-                        }
-                    }
-                    if (okmask != 0u) {
-                        fa = max(r, r - ow + lo);
-                        fb = min(row_end, r - ow + hi);
-                        if (fb <= fa) { fa = r; fb = r; }
-                        else {
-                            c.okmask = okmask;
-#pragma unroll
-                            for (int i = 0; i < TT; ++i)
-                                if (!(okmask & (1u << i))) c.toff[i] = safe_off;   // in bounds, skipped when consumed
-                        }
+            if constexpr (TR) {
+                // every pixel is tested; the output coordinates are kept split by the stride
+                AxisSplit so = split(oh, q.sh), sw0 = split(ow, q.sw);
+                so.q = __builtin_amdgcn_readfirstlane(so.q); so.m = __builtin_amdgcn_readfirstlane(so.m);
+                AxisSplit sx;
+                sx.q = __builtin_amdgcn_readfirstlane(sw0.q); sx.m = __builtin_amdgcn_readfirstlane(sw0.m);
+                for (; r < r1; ++r) {
+                    auto tap = [&](int i, int &ih, int &iw) {
+                        return (t0 + i < T) && transposed_coord(so, fh[i], q.sh, g.H, ih) &&
+                               transposed_coord(sx, fw[i], q.sw, g.W, iw);
+                    };
+                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, r0, r, img, c0, first, last);
+                    if (++sx.m == q.sw) { sx.m = 0; ++sx.q; }
+                    if (++ow == q.Wo) {
+                        ow = 0; sx.q = 0; sx.m = 0;
+                        if (++so.m == q.sh) { so.m = 0; ++so.q; }
+                        if (++oh == q.Ho) { oh = 0; so.q = 0; so.m = 0; ++img; }
                     }
                 }
-                // [r, fa) tested, [fa, fb) fast, [fb, row_end) tested
-                for (int x = r; x < fa; ++x)
-                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, offh, offw, r0, x, img, oh, ow + (x - r), c0, t0, first, last);
-                if (fb > fa) {
-                    const int owa = ow + (fa - r);
-                    const uint32_t off_a = (uint32_t)((img * g.H + oh * q.sh) * g.W + owa * q.sw) * pixel_bytes + (uint32_t)c0 * 4u;
-                    const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
-                    gen_run_fast<AB, WB, CWT, TT>(c, ov, r0, fa, fb, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
-                }
-                for (int x = max(fb, fa); x < row_end; ++x)
-                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, offh, offw, r0, x, img, oh, ow + (x - r), c0, t0, first, last);
-                ow += row_end - r;
-                r = row_end;
-                if (ow == q.Wo) {
-                    ow = 0;
-                    if (++oh == q.Ho) { oh = 0; ++img; }
+            } else {
+                lo = __builtin_amdgcn_readfirstlane(lo);
+                hi = __builtin_amdgcn_readfirstlane(hi);
+                const bool fast_chunk = (c0 + CWT <= Cw);
+                auto checked = [&](int x, int oh_x, int ow_x) {
+                    auto tap = [&](int i, int &ih, int &iw) {
+                        ih = oh_x * q.sh + offh[i];
+                        iw = ow_x * q.sw + offw[i];
+                        return (t0 + i < T) && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+                    };
+                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, r0, x, img, c0, first, last);
+                };
+                while (r < r1) {
+                    const int row_end = min(r1, r - ow + q.Wo);               // end of this output row within the range
+                    // fast interval of this row in pixel numbers
+                    int fa = r, fb = r;
+                    if (fast_chunk) {
+                        // taps of the chunk whose kernel row exists for this output row; their offsets
+                        uint32_t okmask = 0u, safe_off = 0u;
+#pragma unroll
+                        for (int i = 0; i < TT; ++i) {
+                            const bool ok = (t0 + i < T) && (unsigned)(oh * q.sh + offh[i]) < (unsigned)g.H;
+                            c.toff[i] = (uint32_t)(offh[i] * g.W + offw[i]) * pixel_bytes;
+                            if (ok) {
+                                if (okmask == 0u) safe_off = c.toff[i];
+                                okmask |= 1u << i;
+                            }
+                        }
+                        if (okmask != 0u) {
+                            fa = max(r, r - ow + lo);
+                            fb = min(row_end, r - ow + hi);
+                            if (fb <= fa) { fa = r; fb = r; }
+                            else {
+                                c.okmask = okmask;
+#pragma unroll
+                                for (int i = 0; i < TT; ++i)
+                                    if (!(okmask & (1u << i))) c.toff[i] = safe_off;   // in bounds, skipped when consumed
+                            }
+                        }
+                    }
+                    // [r, fa) tested, [fa, fb) fast, [fb, row_end) tested
+                    for (int x = r; x < fa; ++x) checked(x, oh, ow + (x - r));
+                    if (fb > fa) {
+                        const int owa = ow + (fa - r);
+                        const uint32_t off_a = (uint32_t)((img * g.H + oh * q.sh) * g.W + owa * q.sw) * pixel_bytes + (uint32_t)c0 * 4u;
+                        const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
+                        gen_run_fast<AB, WB, CWT, TT>(c, ov, r0, fa, fb, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
+                    }
+                    for (int x = max(fb, fa); x < row_end; ++x) checked(x, oh, ow + (x - r));
+                    ow += row_end - r;
+                    r = row_end;
+                    if (ow == q.Wo) {
+                        ow = 0;
+                        if (++oh == q.Ho) { oh = 0; ++img; }
+                    }
                 }
             }
         }
@@ -365,8 +398,13 @@ constexpr int imin3(int a, int b, int c) { return a < b ? (a < c ? a : c) : (b <
 template <int AB, int WB, int CWT>
 void launch_general_shape(const BranchArgs &g, dim3 grid, bool emit, hipStream_t s) {
     constexpr int TT = imin3(6, 64 / (WB * CWT), 24 / (AB * CWT));
-    if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, true>), grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, false>), grid, dim3(256), 0, s, g);
+    if (g.geo.transposed) {
+        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, true, true>), grid, dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, true, false>), grid, dim3(256), 0, s, g);
+    } else {
+        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, false, true>), grid, dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, false, false>), grid, dim3(256), 0, s, g);
+    }
 }
 
 template <int AB, int WB>
