@@ -561,6 +561,8 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     if (rpw <= 0) {
         rpw = rows * g.col_tiles / ((int64_t)device_simd_count() * 6);
         if (rpw < 14) rpw = 14;
+        // transposed: a wavefront visits its pixels once per output phase with a sub-kernel each
+        if (q->transposed && rpw < 14 * (int64_t)q->stride_h * q->stride_w) rpw = 14 * (int64_t)q->stride_h * q->stride_w;
     }
     if (rpw > rows) rpw = rows;
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw, Cout), Cout, e);

@@ -71,18 +71,21 @@ __device__ __forceinline__ void load_words(uint64_t addr, uint32_t (&out)[CWT]) 
     }
 }
 
-// Output pixels ra .. rb-1 (one output row, every used tap inside the image).  off_a: byte offset
-// of the window origin of pixel ra (plane 0, word c0); step: bytes between the origins of
-// neighbouring output pixels; kadd: constant term of this chunk.  All words of a pixel are
-// requested before any is used; other wavefronts of the SIMD cover the latency.
+// `count` output pixels of one output row, every used tap inside the image; pixel x has output
+// number r0 + rel0 + x * rel_step.  off_a: byte offset of the window origin of the first pixel
+// (plane 0, word c0); step: bytes between the origins of successive pixels; kadd: constant term
+// of this chunk.  All words of a pixel are requested before any is used; other wavefronts of
+// the SIMD cover the latency.
 template <int AB, int WB, int CWT, int TT, class OV>
-__device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int r0, int ra, int rb,
-                                             uint32_t off_a, uint32_t step, int kadd, bool first, bool last) {
+__device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int rel0, int count,
+                                             int rel_step, uint32_t off_a, uint32_t step, int kadd, bool first,
+                                             bool last) {
     uint32_t off = off_a;
-    for (int r = ra; r < rb; ++r) {
+    int rel = rel0;
+    for (int x = 0; x < count; ++x) {
         int prev = 0;
         if (!first)
-            prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
+            prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)rel * ov.row_bytes), 0);
         uint32_t a[TT][AB][CWT];
 #pragma unroll
         for (int i = 0; i < TT; ++i)
@@ -105,8 +108,9 @@ __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, c
         int s = part[AB + WB - 2];
 #pragma unroll
         for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
-        finish_row<false>(ov, r - r0, prev + kadd - 2 * s, /*first=*/true, last);   // earlier part already added
+        finish_row<false>(ov, rel, prev + kadd - 2 * s, /*first=*/true, last);   // earlier part already added
         off += step;
+        rel += rel_step;
     }
 }
 
@@ -116,12 +120,12 @@ __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, c
 // where.
 template <int AB, int WB, int CWT, int TT, class OV, class TapFn>
 __device__ __forceinline__ void gen_pixel_checked(const BranchArgs &g, const OV &ov, uniform_words As,
-                                                  const uint32_t (&w)[TT][WB][CWT], TapFn tap, int r0, int r,
-                                                  int img, int c0, bool first, bool last) {
+                                                  const uint32_t (&w)[TT][WB][CWT], TapFn tap, int rel, int img,
+                                                  int c0, bool first, bool last) {
     const int Cw = g.Cw;
     int prev = 0;
     if (!first)
-        prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
+        prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)rel * ov.row_bytes), 0);
     int part[AB + WB - 1];
 #pragma unroll
     for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
@@ -151,7 +155,172 @@ __device__ __forceinline__ void gen_pixel_checked(const BranchArgs &g, const OV 
     for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
     int val = prev - 2 * s;
     if (c0 == 0) val += nvalid * g.kconst;  // kconst = C * (2^AB-1) * (2^WB-1), once per tap
-    finish_row<false>(ov, r - r0, val, /*first=*/true, last);   // the earlier part is already added
+    finish_row<false>(ov, rel, val, /*first=*/true, last);      // the earlier part is already added
+}
+
+// Transposed convolution by output phase.  Output pixel (oh, ow) receives kernel element (kh, kw)
+// only if oh + ph - kh*dh is a multiple of the stride (likewise in w), so the pixels of one phase
+// (pa, pb) = ((oh + ph) mod sh, (ow + pw) mod sw) all use the same sub-kernel, and along a row the
+// input column of a tap advances by one per phase pixel: a stride-1 run in the input, written to
+// every sw-th output pixel.  Per phase the sub-kernel is taken in chunks of TT taps like the
+// forward kernel's; interior phase pixels go through the untested run, the others are tested.
+// k*dil written as Q*stride + res (0 <= res < stride), stepped from one kernel element to the next
+// without a division
+struct TapWalk {
+    int Q, res;
+};
+__device__ __forceinline__ void step(TapWalk &w, AxisSplit dil, int stride) {   // dil = dil_q*stride + dil_m
+    w.Q += dil.q;
+    w.res += dil.m;
+    if (w.res >= stride) { w.res -= stride; ++w.Q; }
+}
+
+template <int AB, int WB, int CWT, int TT, class OV>
+__device__ __forceinline__ void transposed_body(const BranchArgs &g, const OV &ov, uniform_words As,
+                                                GenCtx<AB, WB, CWT, TT> &c, int nload, int r0, int r1, int oh0,
+                                                int ow0, int n0) {
+    const ConvGeom &q = g.geo;
+    const int T = q.KH * q.KW, Cw = g.Cw;
+    const uint32_t pixel_bytes = (uint32_t)(AB * Cw) * 4u;
+    // the few divisions of this function: stride splits of the dilation, the padding and the first pixel
+    AxisSplit dh_s = split(q.dh, q.sh), dw_s = split(q.dw, q.sw);
+    AxisSplit ph_s = split(q.ph, q.sh), pw_s = split(q.pw, q.sw);                 // (0 + pad) split: start of a row / image
+    AxisSplit oh_first = split(oh0 + q.ph, q.sh), ow_first = split(ow0 + q.pw, q.sw);
+#define QNN_UNIFORM(v) v.q = __builtin_amdgcn_readfirstlane(v.q); v.m = __builtin_amdgcn_readfirstlane(v.m)
+    QNN_UNIFORM(dh_s); QNN_UNIFORM(dw_s); QNN_UNIFORM(ph_s); QNN_UNIFORM(pw_s); QNN_UNIFORM(oh_first); QNN_UNIFORM(ow_first);
+#undef QNN_UNIFORM
+    for (int pa = 0; pa < q.sh; ++pa)
+        for (int pb = 0; pb < q.sw; ++pb) {
+            // taps of this phase: kh*dh = pa and kw*dw = pb modulo the stride
+            int ntaps = 0;
+            {
+                TapWalk wh = {0, 0}, ww = {0, 0};
+                int kw = 0;
+                for (int t = 0; t < T; ++t) {
+                    if (wh.res == pa && ww.res == pb) ++ntaps;
+                    step(ww, dw_s, q.sw);
+                    if (++kw == q.KW) { kw = 0; ww.Q = 0; ww.res = 0; step(wh, dh_s, q.sh); }
+                }
+            }
+            const int nchunks = (ntaps + TT - 1) / TT;             // 0: the phase's pixels are plain zeros
+            for (int c0 = 0; c0 < ((nchunks == 0) ? 1 : Cw); c0 += CWT)
+                for (int lc = 0; lc < ((nchunks == 0) ? 1 : nchunks); ++lc) {
+                    const bool first = (c0 == 0 && lc == 0);
+                    const bool last = (nchunks == 0) || (c0 + CWT >= Cw && lc + 1 >= nchunks);
+                    // taps lc*TT .. of the phase's list: weight index and input offset in input pixels
+                    // relative to (Iq, Jq) = ((oh + ph - pa) / sh, (ow + pw - pb) / sw); for a tap of the
+                    // phase (pa - kh*dh) / sh = -Q exactly
+                    int dqh[TT], dqw[TT];
+                    uint32_t used = 0u;                             // bit i: slot i holds a tap
+#pragma unroll
+                    for (int i = 0; i < TT; ++i) {
+                        dqh[i] = 0; dqw[i] = 0;
+#pragma unroll
+                        for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+                            for (int j = 0; j < CWT; ++j) c.w[i][qq][j] = 0u;
+                    }
+                    {
+                        TapWalk wh = {0, 0}, ww = {0, 0};
+                        int kw = 0, seen = 0, slot = 0;
+                        for (int t = 0; t < T && slot < TT && nchunks > 0; ++t) {
+                            if (wh.res == pa && ww.res == pb) {
+                                if (seen >= lc * TT) {
+#pragma unroll
+                                    for (int i = 0; i < TT; ++i)
+                                        if (i == slot) {
+                                            dqh[i] = -wh.Q;
+                                            dqw[i] = -ww.Q;
+#pragma unroll
+                                            for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+                                                for (int j = 0; j < CWT; ++j)
+                                                    c.w[i][qq][j] = (c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
+                                        }
+                                    used |= 1u << slot;
+                                    ++slot;
+                                }
+                                ++seen;
+                            }
+                            step(ww, dw_s, q.sw);
+                            if (++kw == q.KW) { kw = 0; ww.Q = 0; ww.res = 0; step(wh, dh_s, q.sh); }
+                        }
+                    }
+                    // columns of the phase whose taps are all inside the image: Jq in [jlo, jhi)
+                    int jlo = 0, jhi = g.W;
+#pragma unroll
+                    for (int i = 0; i < TT; ++i)
+                        if (used & (1u << i)) {
+                            jlo = max(jlo, -dqw[i]);
+                            jhi = min(jhi, g.W - dqw[i]);
+                        }
+                    const bool fast_chunk = (c0 + CWT <= Cw) && used != 0u;
+                    // rows of the wavefront's range; (oh + ph) and (ow + pw) are kept split by the stride
+                    int r = r0, ow = ow0, img = n0, oh = oh0;
+                    AxisSplit ohs = oh_first, ows = ow_first;
+                    while (r < r1) {
+                        const int row_end = min(r1, r - ow + q.Wo);
+                        if (ohs.m == pa) {
+                            const int Iq = ohs.q;
+                            // first column >= ow of this phase and the phase pixels up to the row's end here
+                            const int wrap = (pb < ows.m) ? 1 : 0;
+                            const int need = pb - ows.m + wrap * q.sw;               // ow + need has phase pb
+                            const int Jq0 = ows.q + wrap;
+                            const int span = (row_end - r) - need;                    // pixels from the first phase pixel on
+                            const int count = (span > 0) ? __builtin_amdgcn_readfirstlane((span + q.sw - 1) / q.sw) : 0;
+                            const int rel0 = r + need - r0;
+                            // phase pixels x in [xa, xb) run untested
+                            int xa = 0, xb = 0;
+                            if (fast_chunk && count > 0) {
+                                uint32_t okmask = 0u, safe_off = 0u;
+#pragma unroll
+                                for (int i = 0; i < TT; ++i) {
+                                    const bool ok = (used & (1u << i)) && (unsigned)(Iq + dqh[i]) < (unsigned)g.H;
+                                    c.toff[i] = (uint32_t)(dqh[i] * g.W + dqw[i]) * pixel_bytes;
+                                    if (ok) {
+                                        if (okmask == 0u) safe_off = c.toff[i];
+                                        okmask |= 1u << i;
+                                    }
+                                }
+                                if (okmask != 0u) {
+                                    xa = max(0, jlo - Jq0);
+                                    xb = min(count, jhi - Jq0);
+                                    if (xb <= xa) { xa = 0; xb = 0; }
+                                    else {
+                                        c.okmask = okmask;
+#pragma unroll
+                                        for (int i = 0; i < TT; ++i)
+                                            if (!(okmask & (1u << i))) c.toff[i] = safe_off;
+                                    }
+                                }
+                            }
+                            auto checked = [&](int x) {
+                                auto tap = [&](int i, int &ih, int &iw) {
+                                    ih = Iq + dqh[i];
+                                    iw = Jq0 + x + dqw[i];
+                                    return (used & (1u << i)) && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+                                };
+                                gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, rel0 + x * q.sw, img, c0, first, last);
+                            };
+                            for (int x = 0; x < xa; ++x) checked(x);
+                            if (xb > xa) {
+                                const uint32_t off_a = (uint32_t)((img * g.H + Iq) * g.W + Jq0 + xa) * pixel_bytes + (uint32_t)c0 * 4u;
+                                const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
+                                gen_run_fast<AB, WB, CWT, TT>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
+                            }
+                            for (int x = max(xb, xa); x < count; ++x) checked(x);
+                        }
+                        ow += row_end - r;
+                        r = row_end;
+                        if (ow == q.Wo) {                              // next row (a range ends inside a row only at r1)
+                            ow = 0;
+                            ows = pw_s;
+                            if (++ohs.m == q.sh) { ohs.m = 0; ++ohs.q; }
+                            if (++oh == q.Ho) { oh = 0; ohs = ph_s; ++img; }
+                        }
+                    }
+                }
+        }
 }
 
 template <int AB, int WB, int CWT, int TT, bool TR, bool EMIT>
@@ -184,33 +353,27 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     GenCtx<AB, WB, CWT, TT> c;
     c.base = (uint64_t)g.A;
     c.plane_bytes = (uint32_t)Cw * 4u;
+    if constexpr (TR) {
+        transposed_body<AB, WB, CWT, TT>(g, ov, As, c, nload, r0, r1, oh0, ow0, n0);
+        return;
+    }
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
         for (int t0 = 0; t0 < T; t0 += TT) {
             const bool first = (c0 == 0 && t0 == 0);
             const bool last = (c0 + CWT >= Cw && t0 + TT >= T);
-            // offsets of the chunk's taps along both axes: forward, input = output*stride + off with
-            // off = k*dil - pad; transposed, off = pad - k*dil split by the stride (see AxisSplit)
+            // offsets of the chunk's taps along both axes: input = output*stride + off, off = k*dil - pad
             int offh[TT], offw[TT];
-            AxisSplit fh[TR ? TT : 1], fw[TR ? TT : 1];
-            // forward: output columns for which every tap of the chunk is inside the image, [lo, hi)
+            // output columns for which every tap of the chunk is inside the image, [lo, hi)
             int lo = 0, hi = q.Wo;
 #pragma unroll
             for (int i = 0; i < TT; ++i) {
                 const int t = t0 + i;
                 const int kh = t / q.KW, kw = t - kh * q.KW;
-                if constexpr (TR) {
-                    fh[i] = split(q.ph - kh * q.dh, q.sh);
-                    fw[i] = split(q.pw - kw * q.dw, q.sw);
-                    fh[i].q = __builtin_amdgcn_readfirstlane(fh[i].q); fh[i].m = __builtin_amdgcn_readfirstlane(fh[i].m);
-                    fw[i].q = __builtin_amdgcn_readfirstlane(fw[i].q); fw[i].m = __builtin_amdgcn_readfirstlane(fw[i].m);
-                    offh[i] = offw[i] = 0;
-                } else {
-                    offh[i] = kh * q.dh - q.ph;
-                    offw[i] = kw * q.dw - q.pw;
-                    if (t < T) {
-                        lo = max(lo, -floor_div(offw[i], q.sw));              // ceil(-off / s)
-                        hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
-                    }
+                offh[i] = kh * q.dh - q.ph;
+                offw[i] = kw * q.dw - q.pw;
+                if (t < T) {
+                    lo = max(lo, -floor_div(offw[i], q.sw));                  // ceil(-off / s)
+                    hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
                 }
 #pragma unroll
                 for (int qq = 0; qq < WB; ++qq)
@@ -220,26 +383,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
             }
             int ow = ow0, oh = oh0, img = n0;
             int r = r0;
-            if constexpr (TR) {
-                // every pixel is tested; the output coordinates are kept split by the stride
-                AxisSplit so = split(oh, q.sh), sw0 = split(ow, q.sw);
-                so.q = __builtin_amdgcn_readfirstlane(so.q); so.m = __builtin_amdgcn_readfirstlane(so.m);
-                AxisSplit sx;
-                sx.q = __builtin_amdgcn_readfirstlane(sw0.q); sx.m = __builtin_amdgcn_readfirstlane(sw0.m);
-                for (; r < r1; ++r) {
-                    auto tap = [&](int i, int &ih, int &iw) {
-                        return (t0 + i < T) && transposed_coord(so, fh[i], q.sh, g.H, ih) &&
-                               transposed_coord(sx, fw[i], q.sw, g.W, iw);
-                    };
-                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, r0, r, img, c0, first, last);
-                    if (++sx.m == q.sw) { sx.m = 0; ++sx.q; }
-                    if (++ow == q.Wo) {
-                        ow = 0; sx.q = 0; sx.m = 0;
-                        if (++so.m == q.sh) { so.m = 0; ++so.q; }
-                        if (++oh == q.Ho) { oh = 0; so.q = 0; so.m = 0; ++img; }
-                    }
-                }
-            } else {
+            {
                 lo = __builtin_amdgcn_readfirstlane(lo);
                 hi = __builtin_amdgcn_readfirstlane(hi);
                 const bool fast_chunk = (c0 + CWT <= Cw);
@@ -249,7 +393,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
                         iw = ow_x * q.sw + offw[i];
                         return (t0 + i < T) && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
                     };
-                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, r0, x, img, c0, first, last);
+                    gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, x - r0, img, c0, first, last);
                 };
                 while (r < r1) {
                     const int row_end = min(r1, r - ow + q.Wo);               // end of this output row within the range
@@ -285,7 +429,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
                         const int owa = ow + (fa - r);
                         const uint32_t off_a = (uint32_t)((img * g.H + oh * q.sh) * g.W + owa * q.sw) * pixel_bytes + (uint32_t)c0 * 4u;
                         const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
-                        gen_run_fast<AB, WB, CWT, TT>(c, ov, r0, fa, fb, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
+                        gen_run_fast<AB, WB, CWT, TT>(c, ov, fa - r0, fb - fa, 1, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
                     }
                     for (int x = max(fb, fa); x < row_end; ++x) checked(x, oh, ow + (x - r));
                     ow += row_end - r;

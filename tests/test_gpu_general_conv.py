@@ -70,6 +70,14 @@ CASES = [
     dict(Nb=1, H=6, W=5, C=32, Cout=64, ab=2, wb=2, KH=3, KW=2, stride=(2, 3), pad=(1, 0), dilation=(1, 2),
          transposed=True, output_padding=(1, 2)),
     dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, stride=1, pad=1, transposed=True),
+    # output phases without any tap (kernel smaller than the stride): their pixels are zero sums
+    dict(Nb=2, H=5, W=6, C=64, Cout=32, ab=2, wb=2, KH=1, KW=1, stride=2, transposed=True, output_padding=1),
+    dict(Nb=1, H=4, W=5, C=33, Cout=70, ab=3, wb=2, KH=2, KW=2, stride=3, pad=1, transposed=True),
+    # dilation above the stride; a phase with more taps than one chunk holds; wavefronts that start inside a row
+    dict(Nb=1, H=6, W=7, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, stride=2, pad=2, dilation=3, transposed=True),
+    dict(Nb=1, H=6, W=6, C=96, Cout=64, ab=2, wb=2, KH=5, KW=5, stride=2, pad=2, transposed=True, output_padding=1),
+    dict(Nb=3, H=14, W=13, C=64, Cout=130, ab=2, wb=2, KH=4, KW=4, stride=2, pad=1, transposed=True),
+    dict(Nb=2, H=9, W=9, C=128, Cout=64, ab=1, wb=1, KH=3, KW=3, stride=(1, 2), pad=(1, 0), transposed=True),
 ]
 
 
