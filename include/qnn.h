@@ -232,8 +232,9 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  * QNN_EINVAL for a geometry that is not positive (kernel, stride, dilation >= 1, padding >= 0,
  * out_pad only with transposed = 1 and smaller than max(stride, dilation), Ho, Wo >= 1).
  * Limits as for qnn_conv2d_packed with 9 replaced by kh*kw, for input and output pixel counts.
- * The 3x3 / stride 1 / pad 1 case is served faster by qnn_conv2d_packed, a 1x1 / stride 1
- * convolution by qnn_branch_gemm.
+ * The 3x3 / stride 1 / pad 1 case is served faster by qnn_conv2d_packed.  A 1x1 convolution
+ * without padding runs on the kernels of qnn_branch_gemm (rows = output pixels; with a stride and
+ * bit widths up to 4 the rows are the strided selection of the input pixels).
  */
 typedef struct {
     int kh, kw;

@@ -188,15 +188,20 @@ int clamp_rows_for_emit(int rpw, int64_t N, const Emit &e) {
     return rpw;
 }
 
+// `gather` (with the input image size H x W): row r of A is not row r of the buffer but the input
+// pixel that output pixel r of a single-tap strided convolution reads (bit widths up to 4).
 qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64_t M, int64_t N, int64_t K,
-                    int32_t *acc, const float *scale, float *out_f32, const Emit &e, void *stream) {
+                    int32_t *acc, const float *scale, float *out_f32, const Emit &e, void *stream,
+                    const ConvGeom *gather = nullptr, int H = 1, int W = 1) {
     qnn_status st = check_branch(A, ab, Wt, wb, M, N, K, 1, acc, scale, out_f32, e);
     if (st != QNN_OK || M == 0 || N == 0) return st;
     BranchArgs g;
     g.A = A; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = partial_buffer(acc, out_f32, e);
     g.planes_out = e.planes; g.out_bits = e.bits;
-    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = 1; g.W = 1; g.C = 0;
+    g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = H; g.W = W; g.C = 0;
+    g.gather_rows = (gather != nullptr) ? 1 : 0;
+    if (gather != nullptr) g.geo = *gather;
     g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((N + 63) / 64);
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
@@ -206,11 +211,11 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     // keep the partial sums of a group of rows on chip instead of passing the whole output through
     // memory once per chunk.  With more branches the round trip hides behind the arithmetic and the
     // extra weight reloads of the row groups cost more than they save (measured on 8192^3).
-    g.row_groups = (g.rows_per_wave >= 64 && ab * wb <= 2) ? 1 : 0;
+    g.row_groups = (g.rows_per_wave >= 64 && ab * wb <= 2 && !g.gather_rows) ? 1 : 0;
     // Long K and too few rows for every wavefront to amortise its weight chunks: let the four
     // wavefronts of a block share rows and split the chunks instead.
     const int chunks = (g.Cw + gemm_chunk_words(wb) - 1) / gemm_chunk_words(wb);
-    if (chunks >= 4 && g.rows_per_wave < 16 && tuning().rows_per_wave == 0) {
+    if (chunks >= 4 && g.rows_per_wave < 16 && tuning().rows_per_wave == 0 && !g.gather_rows) {
         const int64_t target_blocks = (int64_t)device_simd_count();          // 4 blocks (16 wavefronts) per CU
         int64_t rows_per_block = (M * g.col_tiles + target_blocks - 1) / target_blocks;
         if (rows_per_block < 8) rows_per_block = 8;
@@ -248,7 +253,7 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.row_groups = 0;
+    g.split_k = 0; g.row_groups = 0; g.gather_rows = 0;
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles, conv_passes(ab, wb, g.Cw), conv_group(ab, wb, g.Cw)), Cout),
                                           Cout, e);
@@ -290,7 +295,7 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
             g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
             g.col_tiles = (int)((Cout + 63) / 64);
-            g.split_k = 0; g.row_groups = 0;
+            g.split_k = 0; g.row_groups = 0; g.gather_rows = 0;
             g.trace = nullptr; g.trace_waves = 0;
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
                                                   Cout, e);
@@ -517,8 +522,20 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     const Emit e = (out_bits != 0) ? Emit{out_planes, out_bits, workspace, workspace_bytes} : kNoEmit;
     st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, (int)taps, acc, scale, out_f32, e);
     if (st != QNN_OK || rows == 0 || Cout == 0) return st;
+    // A single tap at stride 1 without padding reads pixel r for output pixel r: the product of the
+    // [pixels][C] matrix with the [Cout][C] weights, whichever way the transposed flag is set.
+    if (taps == 1 && q->stride_h == 1 && q->stride_w == 1 && q->pad_h == 0 && q->pad_w == 0)
+        return run_gemm(x_planes, ab, Wt, wb, rows, Cout, C, acc, scale, out_f32, e, stream);
     const int64_t cw = (C + 31) / 32;
     if (cw > 0 && Nb * H * W > ((((int64_t)1 << 30) - 1) / (ab * cw))) return QNN_EUNSUPPORTED;   // input planes
+    // A single tap with a stride (the shortcut convolutions of the residual networks): the same
+    // product over a strided selection of the pixels.
+    if (taps == 1 && !q->transposed && q->pad_h == 0 && q->pad_w == 0 && ab <= 4 && wb <= 4 && cw > 0) {
+        ConvGeom cg;
+        cg.KH = 1; cg.KW = 1; cg.sh = q->stride_h; cg.sw = q->stride_w; cg.ph = 0; cg.pw = 0; cg.dh = 1; cg.dw = 1;
+        cg.Ho = (int)Ho; cg.Wo = (int)Wo; cg.transposed = 0;
+        return run_gemm(x_planes, ab, Wt, wb, rows, Cout, C, acc, scale, out_f32, e, stream, &cg, (int)H, (int)W);
+    }
     BranchArgs g;
     g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = partial_buffer(acc, out_f32, e);
@@ -526,7 +543,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.row_groups = 0;
+    g.split_k = 0; g.row_groups = 0; g.gather_rows = 0;
     g.trace = nullptr; g.trace_waves = 0;
     g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
     g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;

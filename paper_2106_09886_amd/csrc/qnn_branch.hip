@@ -130,9 +130,40 @@ struct GemmCtx {
 // `fetch(rel_row)` returns what earlier chunks left for row r0 + rel_row; it is asked for before
 // the row's products are formed, so that its latency hides behind them.
 // `sink(rel_row, v, prev)` receives v = -2 * S of the chunk and that value.
-template <int AB, int WB, int SEGS, int CWT, class Fetch, class Sink>
+//
+// GATHER: row r of the product is output pixel r of a single-tap strided convolution, i.e. the
+// activation row of input pixel (oh*sh, ow*sw) of its image.  `walk` is the state for row r0:
+// byte offset of that pixel and its position; stepping to the next row is two additions and
+// compares on the scalar unit, no division.
+struct RowWalk {
+    uint32_t off;      // byte offset of the row's activation words (plane 0, word 0)
+    int ow, oh;        // output column and row inside the image
+};
+__device__ __forceinline__ RowWalk row_walk_at(const BranchArgs &g, int r, uint32_t row_bytes) {
+    const ConvGeom &q = g.geo;
+    RowWalk w;
+    const int img = r / (q.Ho * q.Wo), rem = r - img * q.Ho * q.Wo;
+    w.oh = __builtin_amdgcn_readfirstlane(rem / q.Wo);
+    w.ow = __builtin_amdgcn_readfirstlane(rem - (rem / q.Wo) * q.Wo);
+    w.off = __builtin_amdgcn_readfirstlane((uint32_t)((img * g.H + w.oh * q.sh) * g.W + w.ow * q.sw) * row_bytes);
+    return w;
+}
+__device__ __forceinline__ void row_walk_step(const BranchArgs &g, RowWalk &w, uint32_t row_bytes) {
+    const ConvGeom &q = g.geo;
+    w.off += (uint32_t)q.sw * row_bytes;
+    if (++w.ow == q.Wo) {                       // next output row: back Wo*sw pixels, down sh input rows
+        w.ow = 0;
+        w.off += (uint32_t)(q.sh * g.W - q.Wo * q.sw) * row_bytes;          // modulo 2^32 on purpose
+        if (++w.oh == q.Ho) {                   // next image
+            w.oh = 0;
+            w.off += (uint32_t)((g.H - q.Ho * q.sh) * g.W) * row_bytes;
+        }
+    }
+}
+
+template <int AB, int WB, int SEGS, int CWT, bool GATHER = false, class Fetch, class Sink>
 __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, int r0, int r1, int k0,
-                                                Fetch fetch, Sink sink) {
+                                                Fetch fetch, Sink sink, RowWalk walk = RowWalk()) {
     GemmCtx<AB, WB, SEGS, CWT> c;
     const int Kw = g.Cw;
     c.base = (uint64_t)g.A;
@@ -149,7 +180,7 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
                 for (int j = 0; j < CWT; ++j) c.w[t][q][j] = wl[q * KC + t * CWT + j];
     }
     const uint32_t row_bytes = (uint32_t)AB * c.plane_bytes;
-    c.off_cur = (uint32_t)r0 * row_bytes + (uint32_t)k0 * 4u;
+    c.off_cur = (GATHER ? walk.off : (uint32_t)r0 * row_bytes) + (uint32_t)k0 * 4u;
     c.off_nxt = c.off_cur;
     c.template request<0>(c.bufA, false);
     int r = r0;
@@ -157,7 +188,12 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
         constexpr bool FLIP = decltype(flip_tag)::value;
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) c.part[s] = 0;
-        c.off_nxt = (r + 1 < r1) ? c.off_cur + row_bytes : c.off_cur;   // last row prefetches itself
+        if constexpr (GATHER) {
+            row_walk_step(g, walk, row_bytes);
+            c.off_nxt = (r + 1 < r1) ? walk.off + (uint32_t)k0 * 4u : c.off_cur;
+        } else {
+            c.off_nxt = (r + 1 < r1) ? c.off_cur + row_bytes : c.off_cur;   // last row prefetches itself
+        }
         const int prev = fetch(r - r0);
         run_stages<0, FLIP>(c);
         sink(r - r0, -2 * weighted_sum(c.part), prev);
@@ -173,9 +209,9 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
 }
 
 // tail chunk (runs past Kw): plain loads with a guard per word
-template <int AB, int WB, int SEGS, int CWT, class Fetch, class Sink>
+template <int AB, int WB, int SEGS, int CWT, bool GATHER = false, class Fetch, class Sink>
 __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_words As, int nload, int r0,
-                                                int r1, int k0, Fetch fetch, Sink sink) {
+                                                int r1, int k0, Fetch fetch, Sink sink, RowWalk walk = RowWalk()) {
     const int Kw = g.Cw;
     uint32_t w[SEGS][WB][CWT];
 #pragma unroll
@@ -192,6 +228,8 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
         const int prev = fetch(r - r0);
+        const int row_word = GATHER ? (int)(walk.off >> 2) : r * AB * Kw;    // first word of the row
+        if constexpr (GATHER) row_walk_step(g, walk, (uint32_t)(AB * Kw) * 4u);
 #pragma unroll
         for (int t = 0; t < SEGS; ++t) {
             if (k0 + t * CWT < Kw) {             // uniform: skip segments that are all padding
@@ -201,7 +239,7 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
 #pragma unroll
                     for (int j = 0; j < CWT; ++j) {
                         const int k = k0 + t * CWT + j;
-                        a[p][j] = (k < Kw) ? As[(r * AB + p) * Kw + k] : 0u;
+                        a[p][j] = (k < Kw) ? As[row_word + p * Kw + k] : 0u;
                     }
 #pragma unroll
                 for (int q = 0; q < WB; ++q)
@@ -215,7 +253,7 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
     }
 }
 
-template <int AB, int WB, int SEGS, int CWT, bool EMIT>
+template <int AB, int WB, int SEGS, int CWT, bool EMIT, bool GATHER = false>
 __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const WavePos wp = wave_pos(g.col_tiles);
@@ -237,6 +275,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
         trace_end(g, wp);
         return;
     }
+    RowWalk walk = RowWalk();
+    if constexpr (GATHER) walk = row_walk_at(g, r0, (uint32_t)(AB * Kw) * 4u);
     for (int k0 = 0; k0 < Kw; k0 += KC) {
         const bool first = (k0 == 0);
         const bool last = (k0 + KC >= Kw);
@@ -247,8 +287,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
         auto sink = [&](int rel_row, int v, int prev) {
             finish_row<false>(ov, rel_row, v + prev, /*first=*/true, last);   // the earlier part is already added
         };
-        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, r0, r1, k0, fetch, sink);
-        else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, r0, r1, k0, fetch, sink);
+        if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT, GATHER>(g, nload, r0, r1, k0, fetch, sink, walk);
+        else gemm_chunk_tail<AB, WB, SEGS, CWT, GATHER>(g, As, nload, r0, r1, k0, fetch, sink, walk);
     }
     trace_end(g, wp);
 }
@@ -775,18 +815,31 @@ inline dim3 grid_for(const BranchArgs &g) {
 }
 
 // GEMM kernel with a chunk of KC words (two or more pipeline stages of CWT words)
+template <int AB, int WB, int SEGS, int CWT>
+void launch_gemm_plain(const BranchArgs &g, bool emit, hipStream_t s) {
+    if constexpr (AB <= 4 && WB <= 4) {       // strided rows: bit widths up to 4 only, to bound build time
+        if (g.gather_rows) {
+            if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true, true>), grid_for(g), dim3(256), 0, s, g);
+            else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false, true>), grid_for(g), dim3(256), 0, s, g);
+            return;
+        }
+    }
+    if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true>), grid_for(g), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false>), grid_for(g), dim3(256), 0, s, g);
+}
+
 template <int AB, int WB, int KC>
 void launch_gemm_short(const BranchArgs &g, bool emit, hipStream_t s) {
     constexpr int CWT = imin(pow2_floor(16 / AB), KC / 2);
     constexpr int SEGS = KC / CWT;
-    if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true>), grid_for(g), dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false>), grid_for(g), dim3(256), 0, s, g);
+    launch_gemm_plain<AB, WB, SEGS, CWT>(g, emit, s);
 }
 
 template <int AB, int WB>
 hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     using S = GemmShape<AB, WB>;
     const bool emit = g.planes_out != nullptr;
+    if (g.gather_rows && (AB > 4 || WB > 4 || g.split_k || g.row_groups)) return hipErrorInvalidValue;   // host bug
     if (g.split_k) {
         const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
         const dim3 grid((unsigned)(row_blocks * g.col_tiles));
@@ -810,8 +863,7 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
             else hipLaunchKernelGGL((gemm_rowgroup_kernel<AB, WB, S::SEGS, S::CWT, false>), grid_for(g), dim3(256), 0, s, g);
             return hipGetLastError();
         }
-        if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT, true>), grid_for(g), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((gemm_kernel<AB, WB, S::SEGS, S::CWT, false>), grid_for(g), dim3(256), 0, s, g);
+        launch_gemm_plain<AB, WB, S::SEGS, S::CWT>(g, emit, s);
     }
     return hipGetLastError();
 }

@@ -63,6 +63,13 @@ CASES = [
     dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=6, wb=2, KH=3, KW=3, pad=1),                     # wide activations
     dict(Nb=1, H=7, W=7, C=512, Cout=64, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1),          # many channel chunks
     dict(Nb=3, H=16, W=16, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),                   # several wavefronts per image
+    # single tap: the GEMM kernels, with strided row selection when there is a stride
+    dict(Nb=3, H=7, W=7, C=256, Cout=64, ab=2, wb=2, KH=1, KW=1, stride=2),                 # Ho*stride > H
+    dict(Nb=2, H=9, W=8, C=96, Cout=130, ab=1, wb=1, KH=1, KW=1, stride=(2, 3)),
+    dict(Nb=2, H=6, W=7, C=1100, Cout=64, ab=2, wb=2, KH=1, KW=1, stride=(3, 2)),           # two chunks, the second ragged
+    dict(Nb=5, H=5, W=5, C=40, Cout=64, ab=4, wb=4, KH=1, KW=1, stride=(1, 2), dilation=3),
+    dict(Nb=2, H=8, W=8, C=64, Cout=64, ab=6, wb=2, KH=1, KW=1, stride=2),                  # wide activations: general kernel
+    dict(Nb=2, H=8, W=8, C=64, Cout=64, ab=2, wb=2, KH=1, KW=1, stride=2, pad=1),           # padded: general kernel
     # transposed
     dict(Nb=2, H=7, W=7, C=64, Cout=32, ab=2, wb=2, KH=2, KW=2, stride=2, transposed=True),
     dict(Nb=1, H=6, W=8, C=128, Cout=64, ab=4, wb=2, KH=4, KW=4, stride=2, pad=1, transposed=True),
@@ -117,6 +124,8 @@ def test_conv2d_general_requant(q, oracle, out_bits):
     run_case(q, oracle, Nb=2, H=12, W=12, C=64, Cout=70, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1, out_bits=out_bits)
     run_case(q, oracle, Nb=1, H=6, W=6, C=256, Cout=64, ab=2, wb=2, KH=2, KW=2, stride=2, transposed=True,
              out_bits=out_bits)
+    run_case(q, oracle, Nb=2, H=9, W=9, C=128, Cout=70, ab=2, wb=2, KH=1, KW=1, stride=2, out_bits=out_bits)
+    run_case(q, oracle, Nb=2, H=5, W=6, C=128, Cout=64, ab=4, wb=2, KH=1, KW=1, out_bits=out_bits)
 
 
 def test_conv2d_general_planes_only(q, oracle):
