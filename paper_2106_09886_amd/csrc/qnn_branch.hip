@@ -67,16 +67,6 @@ __device__ __forceinline__ void trace_end(const BranchArgs &g, const WavePos &wp
         g.trace[4 * (int64_t)wp.index + 1] = __builtin_amdgcn_s_memtime();
 }
 
-// Weight words of one chunk for this lane's column: NW words, word_index(k) = position in Wt.
-// (Fetching the block's tile once through LDS instead was measured and is not faster: these
-// loads happen once per chunk and wavefront and hit in L2.)
-template <int NW, class IndexFn>
-__device__ __forceinline__ void load_weight_words(const uint32_t *__restrict__ Wt, IndexFn word_index,
-                                                  uint32_t (&w)[NW]) {
-#pragma unroll
-    for (int k = 0; k < NW; ++k) w[k] = Wt[word_index(k)];
-}
-
 // Two-buffer software pipeline: stages ST .. NS-1 of one row.  Stage s is consumed from
 // buffer (s + FLIP) & 1 while stage s+1 (or stage 0 of the next row) is in flight into the
 // other buffer.  On entry stage ST has been requested; on exit stage 0 of the next row has.
@@ -171,7 +161,10 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
     {
         constexpr int KC = SEGS * CWT, NW = WB * KC;
         uint32_t wl[NW];                              // word k = q * KC + (t * CWT + j)
-        load_weight_words<NW>(g.Wt, [&](int k) { return (nload * WB + k / KC) * Kw + k0 + k % KC; }, wl);
+        // (Fetching the block's tile once through LDS instead was measured and is not faster: these
+        // loads happen once per chunk and wavefront and hit in L2.)
+#pragma unroll
+        for (int q = 0; q < WB; ++q) load_run<KC>(g.Wt + (nload * WB + q) * Kw + k0, wl + q * KC);
 #pragma unroll
         for (int t = 0; t < SEGS; ++t)
 #pragma unroll
@@ -664,8 +657,12 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     {
         constexpr int NW = TPC * WB * CWT;            // word k = (t * WB + q) * CWT + j
         uint32_t wl[NW];
-        load_weight_words<NW>(g.Wt, [&](int k) { return ((nload * 9 + t0) * WB + k / CWT) * ps + c0 + k % CWT; },
-                              wl);
+        if constexpr (CWS > 0 && CWT == CWS) {        // the chunk takes every channel word: one contiguous run
+            load_run<NW>(g.Wt + (nload * 9 + t0) * WB * CWS, wl);
+        } else {
+#pragma unroll
+            for (int k = 0; k < TPC * WB; ++k) load_run<CWT>(g.Wt + ((nload * 9 + t0) * WB + k) * ps + c0, wl + k * CWT);
+        }
 #pragma unroll
         for (int t = 0; t < TPC; ++t)
 #pragma unroll

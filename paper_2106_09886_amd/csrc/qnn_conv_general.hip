@@ -76,35 +76,43 @@ __device__ __forceinline__ void load_words(uint64_t addr, uint32_t (&out)[CWT]) 
 // (plane 0, word c0); step: bytes between the origins of successive pixels; kadd: constant term
 // of this chunk.  All words of a pixel are requested before any is used; other wavefronts of
 // the SIMD cover the latency.
-template <int AB, int WB, int CWT, int TT, class OV>
+// The chunk's taps are taken in groups of LG (LG divides TT): the words of a group are requested
+// together, which bounds the scalar registers a pixel needs while the chunk's weights (TT taps)
+// stay in vector registers; a group without a used tap is skipped.
+template <int AB, int WB, int CWT, int TT, int LG, class OV>
 __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int rel0, int count,
                                              int rel_step, uint32_t off_a, uint32_t step, int kadd, bool first,
                                              bool last) {
+    static_assert(TT % LG == 0, "whole load groups");
     uint32_t off = off_a;
     int rel = rel0;
     for (int x = 0; x < count; ++x) {
         int prev = 0;
         if (!first)
             prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)rel * ov.row_bytes), 0);
-        uint32_t a[TT][AB][CWT];
-#pragma unroll
-        for (int i = 0; i < TT; ++i)
-#pragma unroll
-            for (int p = 0; p < AB; ++p)
-                load_words<CWT>(c.base + (uint32_t)(off + c.toff[i] + (uint32_t)p * c.plane_bytes), a[i][p]);
         int part[AB + WB - 1];
 #pragma unroll
         for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
 #pragma unroll
-        for (int i = 0; i < TT; ++i)
-            if (c.okmask & (1u << i)) {
+        for (int g0 = 0; g0 < TT; g0 += LG) {
+            if (TT > LG && !(c.okmask & (((1u << LG) - 1u) << g0))) continue;
+            uint32_t a[LG][AB][CWT];
 #pragma unroll
-                for (int qq = 0; qq < WB; ++qq)
+            for (int i = 0; i < LG; ++i)
 #pragma unroll
-                    for (int p = 0; p < AB; ++p)
+                for (int p = 0; p < AB; ++p)
+                    load_words<CWT>(c.base + (uint32_t)(off + c.toff[g0 + i] + (uint32_t)p * c.plane_bytes), a[i][p]);
 #pragma unroll
-                        for (int j = 0; j < CWT; ++j) popc_acc(part[p + qq], a[i][p][j] ^ c.w[i][qq][j]);
-            }
+            for (int i = 0; i < LG; ++i)
+                if (c.okmask & (1u << (g0 + i))) {
+#pragma unroll
+                    for (int qq = 0; qq < WB; ++qq)
+#pragma unroll
+                        for (int p = 0; p < AB; ++p)
+#pragma unroll
+                            for (int j = 0; j < CWT; ++j) popc_acc(part[p + qq], a[i][p][j] ^ c.w[g0 + i][qq][j]);
+                }
+        }
         int s = part[AB + WB - 2];
 #pragma unroll
         for (int i = AB + WB - 3; i >= 0; --i) s = (s << 1) + part[i];
@@ -232,10 +240,15 @@ __device__ __forceinline__ void transposed_body(const BranchArgs &g, const OV &o
                                             dqh[i] = -wh.Q;
                                             dqw[i] = -ww.Q;
 #pragma unroll
-                                            for (int qq = 0; qq < WB; ++qq)
+                                            for (int qq = 0; qq < WB; ++qq) {
+                                                if (c0 + CWT <= Cw) {
+                                                    load_run<CWT>(g.Wt + ((nload * T + t) * WB + qq) * Cw + c0, c.w[i][qq]);
+                                                } else {
 #pragma unroll
-                                                for (int j = 0; j < CWT; ++j)
-                                                    c.w[i][qq][j] = (c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
+                                                    for (int j = 0; j < CWT; ++j)
+                                                        c.w[i][qq][j] = (c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
+                                                }
+                                            }
                                         }
                                     used |= 1u << slot;
                                     ++slot;
@@ -306,7 +319,7 @@ __device__ __forceinline__ void transposed_body(const BranchArgs &g, const OV &o
                             if (xb > xa) {
                                 const uint32_t off_a = (uint32_t)((img * g.H + Iq) * g.W + Jq0 + xa) * pixel_bytes + (uint32_t)c0 * 4u;
                                 const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
-                                gen_run_fast<AB, WB, CWT, TT>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
+                                gen_run_fast<AB, WB, CWT, TT, TT>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
                             }
                             for (int x = max(xb, xa); x < count; ++x) checked(x);
                         }
@@ -323,7 +336,7 @@ __device__ __forceinline__ void transposed_body(const BranchArgs &g, const OV &o
         }
 }
 
-template <int AB, int WB, int CWT, int TT, bool TR, bool EMIT>
+template <int AB, int WB, int CWT, int TT, int LG, bool TR, bool EMIT>
 __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
@@ -376,10 +389,15 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
                     hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
                 }
 #pragma unroll
-                for (int qq = 0; qq < WB; ++qq)
+                for (int qq = 0; qq < WB; ++qq) {
+                    if (t < T && c0 + CWT <= Cw) {
+                        load_run<CWT>(g.Wt + ((nload * T + t) * WB + qq) * Cw + c0, c.w[i][qq]);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < CWT; ++j)
-                        c.w[i][qq][j] = (t < T && c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
+                        for (int j = 0; j < CWT; ++j)
+                            c.w[i][qq][j] = (t < T && c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
+                    }
+                }
             }
             int ow = ow0, oh = oh0, img = n0;
             int r = r0;
@@ -429,7 +447,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
                         const int owa = ow + (fa - r);
                         const uint32_t off_a = (uint32_t)((img * g.H + oh * q.sh) * g.W + owa * q.sw) * pixel_bytes + (uint32_t)c0 * 4u;
                         const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
-                        gen_run_fast<AB, WB, CWT, TT>(c, ov, fa - r0, fb - fa, 1, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
+                        gen_run_fast<AB, WB, CWT, TT, LG>(c, ov, fa - r0, fb - fa, 1, off_a, (uint32_t)q.sw * pixel_bytes, kadd, first, last);
                     }
                     for (int x = max(fb, fa); x < row_end; ++x) checked(x, oh, ow + (x - r));
                     ow += row_end - r;
@@ -474,18 +492,29 @@ __global__ __launch_bounds__(256) void conv_window_kernel(const BranchArgs g) {
     for (int qq = 0; qq < WB; ++qq)
 #pragma unroll
         for (int k = 0; k < KWP; ++k) w[qq][k] = 0u;
-    for (int t = 0; t < T; ++t) {
+    auto place = [&](int t, const uint32_t *x) {       // tap t: C bits per plane at window bit t*C
         const int bit = t * C, wi = bit >> 5, sh = bit & 31;
 #pragma unroll
         for (int qq = 0; qq < WB; ++qq) {
-            const uint32_t x = g.Wt[(nload * T + t) * WB + qq];
-            const uint32_t lo = x << sh, hi = sh ? x >> (32 - sh) : 0u;      // hi: the part that spills into the next word
+            const uint32_t lo = x[qq] << sh, hi = sh ? x[qq] >> (32 - sh) : 0u;   // hi: the part that spills into the next word
 #pragma unroll
             for (int k = 0; k < KWP; ++k) {
                 if (k == wi) w[qq][k] |= lo;
                 if (k == wi + 1) w[qq][k] |= hi;
             }
         }
+    };
+    int t = 0;
+    for (; t + 2 <= T; t += 2) {                       // the filter's words are contiguous: two taps per load run
+        uint32_t x[2 * WB];
+        load_run<2 * WB>(g.Wt + (nload * T + t) * WB, x);
+        place(t, x);
+        place(t + 1, x + WB);
+    }
+    if (t < T) {
+        uint32_t x[WB];
+        load_run<WB>(g.Wt + (nload * T + t) * WB, x);
+        place(t, x);
     }
     const uint64_t base = (uint64_t)g.A;
     constexpr uint32_t kRowBytes = (uint32_t)((AB + 1) * KWP) * 4u;
@@ -541,14 +570,29 @@ constexpr int imin3(int a, int b, int c) { return a < b ? (a < c ? a : c) : (b <
 
 template <int AB, int WB, int CWT>
 void launch_general_shape(const BranchArgs &g, dim3 grid, bool emit, hipStream_t s) {
+    // taps whose activation words are requested together (scalar registers), also the weight chunk
+    // of the plain variant
     constexpr int TT = imin3(6, 64 / (WB * CWT), 24 / (AB * CWT));
+    // wide variant for kernels with more taps than that: up to three groups of (at most 3) taps per
+    // weight chunk while the chunk stays below 96 vector registers; fewer passes over the output
+    // and fewer weight reloads (forward convolution, one or two activation bits: measured 15 %
+    // faster on 3x3 and 5x5 layers with 64..96 channels, 5 % slower with four activation bits)
+    constexpr int LGW = TT < 3 ? TT : 3;
+    constexpr int NGW = imin3(3, 96 / (WB * CWT * LGW), 3);
     if (g.geo.transposed) {
-        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, true, true>), grid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, true, false>), grid, dim3(256), 0, s, g);
-    } else {
-        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, false, true>), grid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, false, false>), grid, dim3(256), 0, s, g);
+        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, true>), grid, dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, false>), grid, dim3(256), 0, s, g);
+        return;
     }
+    if constexpr (AB <= 2 && WB <= 4 && NGW >= 2) {
+        if (g.geo.KH * g.geo.KW > TT) {
+            if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, NGW * LGW, LGW, false, true>), grid, dim3(256), 0, s, g);
+            else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, NGW * LGW, LGW, false, false>), grid, dim3(256), 0, s, g);
+            return;
+        }
+    }
+    if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, false, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, false, false>), grid, dim3(256), 0, s, g);
 }
 
 template <int AB, int WB>
@@ -559,9 +603,14 @@ hipError_t launch_general_t(const BranchArgs &g, hipStream_t s) {
     // channel words per chunk (at most AB*CWT = 8 and no more than there are), then taps per chunk
     // such that the chunk's weight words (TT*WB*CWT) stay at or below 64 VGPRs and one pixel's
     // activation words (TT*AB*CWT) at or below 24 SGPRs
+    // A chunk that runs past the last channel word takes the tested path for every pixel, so the
+    // chunk width divides the word count where a width of 4, 2 or 1 does (C = 96: three chunks of
+    // one word); only beyond 16 words is a ragged last chunk the smaller cost.
     constexpr int CMAX = (AB <= 2) ? 4 : (AB <= 4) ? 2 : 1;
-    if (g.Cw >= 4 && CMAX >= 4) launch_general_shape<AB, WB, (CMAX >= 4 ? 4 : 1)>(g, grid, emit, s);
-    else if (g.Cw >= 2 && CMAX >= 2) launch_general_shape<AB, WB, (CMAX >= 2 ? 2 : 1)>(g, grid, emit, s);
+    const bool any = g.Cw > 16;
+    if (CMAX >= 4 && g.Cw >= 4 && (any || g.Cw % 4 == 0)) launch_general_shape<AB, WB, (CMAX >= 4 ? 4 : 1)>(g, grid, emit, s);
+    else if (CMAX >= 4 && g.Cw % 3 == 0) launch_general_shape<AB, WB, (CMAX >= 4 ? 3 : 1)>(g, grid, emit, s);   // C = 96, 192, 288
+    else if (CMAX >= 2 && g.Cw >= 2 && (any || g.Cw % 2 == 0)) launch_general_shape<AB, WB, (CMAX >= 2 ? 2 : 1)>(g, grid, emit, s);
     else launch_general_shape<AB, WB, 1>(g, grid, emit, s);
     return hipGetLastError();
 }

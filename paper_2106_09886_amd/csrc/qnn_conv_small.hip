@@ -68,11 +68,15 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
 
     // the filter's 9*C-bit word per weight plane, assembled from the per-tap words
     uint32_t wq[WB];
+    {
+        uint32_t taps[9 * WB];                         // the filter's words are contiguous: [tap][plane]
+        load_run<9 * WB>(g.Wt + nload * 9 * WB, taps);
 #pragma unroll
-    for (int q = 0; q < WB; ++q) {
-        wq[q] = 0u;
+        for (int q = 0; q < WB; ++q) {
+            wq[q] = 0u;
 #pragma unroll
-        for (int t = 0; t < 9; ++t) wq[q] |= g.Wt[(nload * 9 + t) * WB + q] << (t * C);
+            for (int t = 0; t < 9; ++t) wq[q] |= taps[t * WB + q] << (t * C);
+        }
     }
     // valid-tap masks
     const uint32_t tapbits = (1u << C) - 1u;

@@ -63,6 +63,12 @@ CASES = [
     dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=6, wb=2, KH=3, KW=3, pad=1),                     # wide activations
     dict(Nb=1, H=7, W=7, C=512, Cout=64, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1),          # many channel chunks
     dict(Nb=3, H=16, W=16, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),                   # several wavefronts per image
+    # channel counts whose word count is a multiple of 3 (chunks of three words) or odd (one word)
+    dict(Nb=2, H=9, W=10, C=96, Cout=64, ab=2, wb=2, KH=5, KW=5, pad=2),
+    dict(Nb=1, H=8, W=8, C=192, Cout=70, ab=2, wb=3, KH=3, KW=3, stride=2, pad=1),
+    dict(Nb=1, H=7, W=9, C=288, Cout=64, ab=1, wb=1, KH=3, KW=3, pad=1, dilation=1),
+    dict(Nb=1, H=7, W=7, C=160, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),                    # five words
+    dict(Nb=1, H=6, W=6, C=90, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1, transposed=True, stride=2, output_padding=1),
     # single tap: the GEMM kernels, with strided row selection when there is a stride
     dict(Nb=3, H=7, W=7, C=256, Cout=64, ab=2, wb=2, KH=1, KW=1, stride=2),                 # Ho*stride > H
     dict(Nb=2, H=9, W=8, C=96, Cout=130, ab=1, wb=1, KH=1, KW=1, stride=(2, 3)),
