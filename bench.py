@@ -358,7 +358,7 @@ def main():
 
     # comparison line (GEMM workloads with codes that fit int8): the same decoded product on the
     # int8 matrix cores, operands arranged once beforehand
-    compare = None
+    compare = compare_dot = None
     if name in ("gemm8192", "fc4096") and w.ab <= 7 and w.wb <= 7:
         Aa = q.compare_mfma_arrange(Xd)
         Wa = q.compare_mfma_arrange(torch.from_numpy(np.ascontiguousarray(Wm.T)).to(dev))
@@ -370,6 +370,16 @@ def main():
         compare = {"what": "same decoded int8 product on v_mfma_i32_32x32x32_i8 (comparison line, untuned kernel)",
                    "us": round(mfma_us, 2), "GOPS": round(ops / (mfma_us * 1e-6) / 1e9, 1),
                    "frac_of_int8_mfma_peak_5000_TOPS": round(ops / (mfma_us * 1e-6) / 5.0e15, 4)}
+        # second comparison line: the packed int8 dot product of the vector ALU (v_dot4_i32_i8)
+        if w.K % 4 == 0:
+            Wtd = torch.from_numpy(np.ascontiguousarray(Wm.T)).to(dev)
+            pXc, pWc = p(Xd), p(Wtd)
+
+            def dot4():
+                check(L.qnn_compare_dot4_gemm(pXc, pWc, w.M, w.N, w.K, pA, stream))
+            dot_us = timed(torch, dot4, steps)
+            compare_dot = {"what": "same decoded int8 product with v_dot4_i32_i8 (comparison line)",
+                           "us": round(dot_us, 2), "GOPS": round(ops / (dot_us * 1e-6) / 1e9, 1)}
         branch()                                  # leave the branch result in the output buffer
 
     graph_ms = None
@@ -415,6 +425,7 @@ def main():
             "branch_kernel_cold_us": None if cold_us is None else round(cold_us, 2),
             "branch_kernel_effective_GOPS": round(ops / (branch_us * 1e-6) / 1e9, 1),
             "comparison_int8_mfma": compare,
+            "comparison_int8_dot4": compare_dot,
             "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
         },
         "roofline": {

@@ -282,6 +282,16 @@ qnn_status qnn_compare_mfma_gemm(const void *A_arranged, const void *Wt_arranged
                                  int64_t K, int32_t *acc, void *stream);
 
 /*
+ * COMPARISON LINE, not part of the method: the same integer product of decoded int8 codes with
+ * the vector ALU's packed int8 dot product (four multiply-adds per lane and instruction).
+ *   A_codes int8 [M][K], Wt_codes int8 [N][K] (the weight matrix transposed), both row-major and
+ *   4-byte aligned; acc int32 [M][N] = A . Wt^T.
+ * Limits: K a multiple of 4 (else QNN_EUNSUPPORTED), K * 127 * 127 < 2^31, M, N < 2^31.
+ */
+qnn_status qnn_compare_dot4_gemm(const int8_t *A_codes, const int8_t *Wt_codes, int64_t M, int64_t N,
+                                 int64_t K, int32_t *acc, void *stream);
+
+/*
  * Stand-alone scale epilogue (Eq. (9); Eq. (19)): out_f32[i][j] = (float)acc[i][j] * scale[j],
  * acc int32 [M][N], scale fp32 [N], out fp32 [M][N].  One IEEE binary32 multiply per
  * element, no fused multiply-add.  M == 0 or N == 0 launches nothing.

@@ -25,6 +25,7 @@ EXPORTS = (
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
     "qnn_encode_real", "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
+    "qnn_compare_dot4_gemm",
     "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
 )
 
@@ -110,6 +111,8 @@ def lib():
     L.qnn_compare_mfma_arrange.restype = i32
     L.qnn_compare_mfma_gemm.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     L.qnn_compare_mfma_gemm.restype = i32
+    L.qnn_compare_dot4_gemm.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    L.qnn_compare_dot4_gemm.restype = i32
     L.qnn_encode_real.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
     L.qnn_encode_real.restype = i32
     gp = ctypes.POINTER(ConvGeometry)
@@ -397,3 +400,17 @@ def compare_mfma_gemm(A_arranged, Wt_arranged, M, N, K, out=None):
            "qnn_compare_mfma_gemm")
     return acc
 
+
+def compare_dot4_gemm(A_codes, Wt_codes, out=None):
+    """Comparison line: acc int32 [M][N] of the decoded product with the packed int8 dot product.
+    A_codes int8 [M][K], Wt_codes int8 [N][K], K a multiple of 4."""
+    _dev(A_codes, torch.int8, "A_codes")
+    _dev(Wt_codes, torch.int8, "Wt_codes")
+    M, K = A_codes.shape
+    N, K2 = Wt_codes.shape
+    if K != K2:
+        raise ValueError("A_codes and Wt_codes disagree on K")
+    acc = out if out is not None else torch.empty((M, N), dtype=torch.int32, device=A_codes.device)
+    _check(lib().qnn_compare_dot4_gemm(_ptr(A_codes), _ptr(Wt_codes), M, N, K, _ptr(acc), _stream()),
+           "qnn_compare_dot4_gemm")
+    return acc

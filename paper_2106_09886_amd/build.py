@@ -40,7 +40,8 @@ def build(jobs=None, verbose=False):
             ("qnn_pack.hip", os.path.join(OBJ, "qnn_pack.o"), []),
             ("qnn_epilogue.hip", os.path.join(OBJ, "qnn_epilogue.o"), []),
             ("qnn_requant.hip", os.path.join(OBJ, "qnn_requant.o"), []),
-            ("qnn_compare_mfma.hip", os.path.join(OBJ, "qnn_compare_mfma.o"), [])]
+            ("qnn_compare_mfma.hip", os.path.join(OBJ, "qnn_compare_mfma.o"), []),
+            ("qnn_compare_dot.hip", os.path.join(OBJ, "qnn_compare_dot.o"), [])]
     for ab in range(1, 9):
         work.append(("qnn_branch.hip", os.path.join(OBJ, "qnn_branch_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))
         work.append(("qnn_conv_small.hip", os.path.join(OBJ, "qnn_conv_small_ab%d.o" % ab), ["-DQNN_AB=%d" % ab]))

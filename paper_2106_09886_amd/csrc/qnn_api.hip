@@ -624,6 +624,17 @@ qnn_status qnn_compare_mfma_gemm(const void *A_arranged, const void *Wt_arranged
     return from_hip(launch_mfma_gemm(A_arranged, Wt_arranged, M, N, K, acc, (hipStream_t)stream));
 }
 
+qnn_status qnn_compare_dot4_gemm(const int8_t *A_codes, const int8_t *Wt_codes, int64_t M, int64_t N, int64_t K,
+                                 int32_t *acc, void *stream) {
+    if (M < 0 || N < 0 || K < 0) return QNN_EINVAL;
+    if (M == 0 || N == 0) return QNN_OK;
+    if (acc == nullptr || ((A_codes == nullptr || Wt_codes == nullptr) && K > 0)) return QNN_EINVAL;
+    if (!aligned4(A_codes) || !aligned4(Wt_codes) || !aligned4(acc)) return QNN_EALIGN;
+    if ((K & 3) != 0) return QNN_EUNSUPPORTED;
+    if (M > kInt31 || N > kInt31 || K > kInt31 / (127 * 127)) return QNN_EUNSUPPORTED;
+    return from_hip(launch_dot4_gemm(A_codes, Wt_codes, M, N, K, acc, (hipStream_t)stream));
+}
+
 qnn_status qnn_scale_epilogue(const int32_t *acc, int64_t M, int64_t N, const float *scale,
                               float *out_f32, void *stream) {
     if (M < 0 || N < 0) return QNN_EINVAL;

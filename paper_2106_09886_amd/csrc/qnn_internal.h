@@ -185,6 +185,8 @@ hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, in
                               uint32_t *out, hipStream_t);
 hipError_t launch_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, void *out, hipStream_t);
 hipError_t launch_mfma_gemm(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int32_t *C, hipStream_t);
+hipError_t launch_dot4_gemm(const int8_t *A, const int8_t *Wt, int64_t M, int64_t N, int64_t K, int32_t *C,
+                            hipStream_t s);
 hipError_t launch_scale(const int32_t *acc, int64_t total, int64_t N, const float *scale,
                         float *out, hipStream_t);
 

@@ -223,6 +223,18 @@ def test_encode_real_argument_errors(L):
     assert f(P, 0, 64, 2, 0, None, None, None) == QNN_OK
 
 
+def test_compare_dot4_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_EUNSUPPORTED, QNN_OK
+    f = L.qnn_compare_dot4_gemm
+    assert f(None, P, 4, 4, 8, P, None) == QNN_EINVAL
+    assert f(P, P, 4, 4, 8, None, None) == QNN_EINVAL
+    assert f(P, P, -1, 4, 8, P, None) == QNN_EINVAL
+    assert f(P + 1, P, 4, 4, 8, P, None) == QNN_EALIGN
+    assert f(P, P, 4, 4, 6, P, None) == QNN_EUNSUPPORTED          # K not a multiple of 4
+    assert f(P, P, 4, 4, 1 << 20, P, None) == QNN_EUNSUPPORTED    # K * 127^2 overflows int32
+    assert f(P, P, 0, 4, 8, P, None) == QNN_OK
+
+
 def test_tune_rejects_unknown_keys(L):
     from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_OK
     assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK

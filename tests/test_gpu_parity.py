@@ -373,3 +373,13 @@ def test_compare_mfma_gemm(q, oracle, M, N, K):
     got = host(q.compare_mfma_gemm(Aa, Wa, M, N, K))
     assert (got.astype(np.int64) == oracle.gemm(A.astype(np.int16), W.astype(np.int16))).all()
 
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 4), (70, 130, 260), (33, 64, 128), (300, 96, 1000), (64, 200, 4096)])
+def test_compare_dot4_gemm(q, oracle, M, N, K):
+    """The packed int8 dot-product evaluation of the decoded product gives the same integers."""
+    say("compare dot4", M, N, K)
+    rng = np.random.default_rng(M + N + K)
+    A = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    W = rng.integers(-127, 128, size=(K, N)).astype(np.int8)
+    got = host(q.compare_dot4_gemm(dev(A), dev(np.ascontiguousarray(W.T))))
+    assert (got.astype(np.int64) == oracle.gemm(A.astype(np.int16), W.astype(np.int16))).all()
