@@ -62,10 +62,11 @@ const int64_t kInt31 = ((int64_t)1 << 31) - 1;
 // Rows handled by one wavefront: enough wavefronts to give every SIMD of the chip
 // `waves_per_simd` of them, but never fewer than `min_rows` rows each (the weight chunk a
 // wavefront loads is reused for all of its rows).
-int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows) {
+int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows, int default_waves_per_simd = 4) {
     const Tuning &t = tuning();
     if (t.rows_per_wave > 0) return t.rows_per_wave;
-    const int64_t target_waves = (int64_t)device_simd_count() * (t.waves_per_simd > 0 ? t.waves_per_simd : 4);
+    const int64_t target_waves =
+        (int64_t)device_simd_count() * (t.waves_per_simd > 0 ? t.waves_per_simd : default_waves_per_simd);
     int64_t row_blocks = target_waves / col_tiles;
     if (row_blocks < 1) row_blocks = 1;
     int64_t rpw = (rows + row_blocks - 1) / row_blocks;
@@ -205,24 +206,35 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((N + 63) / 64);
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
-    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(M, g.col_tiles, 4), N), N, e);
+    // Rows per wavefront.  Many short wavefronts (about 32 per SIMD over the launch) balance the
+    // load and hide the latency of the partial sums that pass through the output between chunks;
+    // the floor keeps a wavefront's products per weight chunk at about 1500 vector instructions or
+    // more, below which reloading the weights costs more than the balance gains.  Measured on
+    // products from 100352 x 64 x 256 to 8192^3 at one to four bits: 0.90-0.96 of the lane-op peak
+    // at 16-32 wavefronts per SIMD against 0.82-0.87 at four, and at least the rate of a variant
+    // that kept the partial sums of 32-row groups in LDS (dropped: its LDS slab capped the
+    // resident wavefronts at five per SIMD).
+    {
+        const int kc = gemm_chunk_words(wb);
+        const int64_t per_row = 2 * (int64_t)ab * wb * (g.Cw < kc ? (g.Cw > 0 ? g.Cw : 1) : kc);
+        int min_rows = (int)((1536 + per_row - 1) / per_row);
+        const int at_four = pick_rows_per_wave(M, g.col_tiles, 4, 4);      // the floor never leaves fewer than
+        if (min_rows > at_four) min_rows = at_four;                         // four wavefronts per SIMD
+        const int rpw = pick_rows_per_wave(M, g.col_tiles, min_rows < 4 ? 4 : min_rows, 32);
+        g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(rpw, N), N, e);
+    }
     g.split_k = 0;
-    // Many rows per wavefront, several chunks and little arithmetic per chunk (one or two branches):
-    // keep the partial sums of a group of rows on chip instead of passing the whole output through
-    // memory once per chunk.  With more branches the round trip hides behind the arithmetic and the
-    // extra weight reloads of the row groups cost more than they save (measured on 8192^3).
-    g.row_groups = (g.rows_per_wave >= 64 && ab * wb <= 2 && !g.gather_rows) ? 1 : 0;
-    // Long K and too few rows for every wavefront to amortise its weight chunks: let the four
-    // wavefronts of a block share rows and split the chunks instead.
+    // Long K and too few rows (under 16 per wavefront at four wavefronts per SIMD) for every
+    // wavefront to amortise its weight chunks: let the four wavefronts of a block share rows and
+    // split the chunks instead.
     const int chunks = (g.Cw + gemm_chunk_words(wb) - 1) / gemm_chunk_words(wb);
-    if (chunks >= 4 && g.rows_per_wave < 16 && tuning().rows_per_wave == 0 && !g.gather_rows) {
+    if (chunks >= 4 && pick_rows_per_wave(M, g.col_tiles, 4) < 16 && tuning().rows_per_wave == 0 && !g.gather_rows) {
         const int64_t target_blocks = (int64_t)device_simd_count();          // 4 blocks (16 wavefronts) per CU
         int64_t rows_per_block = (M * g.col_tiles + target_blocks - 1) / target_blocks;
         if (rows_per_block < 8) rows_per_block = 8;
         if (rows_per_block > 32) rows_per_block = 32;
         if (rows_per_block > M) rows_per_block = M;
         g.split_k = 1;
-        g.row_groups = 0;
         g.rows_per_wave = (int)rows_per_block;
     }
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
@@ -253,7 +265,7 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.row_groups = 0; g.gather_rows = 0;
+    g.split_k = 0; g.gather_rows = 0;
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles, conv_passes(ab, wb, g.Cw), conv_group(ab, wb, g.Cw)), Cout),
                                           Cout, e);
@@ -295,7 +307,7 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
             g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
             g.col_tiles = (int)((Cout + 63) / 64);
-            g.split_k = 0; g.row_groups = 0; g.gather_rows = 0;
+            g.split_k = 0; g.gather_rows = 0;
             g.trace = nullptr; g.trace_waves = 0;
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
                                                   Cout, e);
@@ -543,7 +555,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.row_groups = 0; g.gather_rows = 0;
+    g.split_k = 0; g.gather_rows = 0;
     g.trace = nullptr; g.trace_waves = 0;
     g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
     g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;

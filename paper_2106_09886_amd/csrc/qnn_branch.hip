@@ -287,51 +287,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------
-// GEMM with many rows AND several K chunks (the 8192^3 products of the efficiency experiment,
-// Sec. 5.4): with the kernel above every chunk pass reads and rewrites the whole output through
-// HBM.  Here a wavefront takes its rows in groups of kGroupRows, runs ALL chunks over one group
-// before the next, and keeps the group's partial sums in LDS (its own 32 x 64 slab: same lane
-// writes and reads an entry, no synchronisation).  The output is written once; the price is a
-// weight chunk reloaded per group instead of per wavefront (from L2).
-// ---------------------------------------------------------------------------------------
-constexpr int kGroupRows = 32;
-
-template <int AB, int WB, int SEGS, int CWT, bool EMIT>
-__global__ __launch_bounds__(256) void gemm_rowgroup_kernel(const BranchArgs g) {
-    typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    __shared__ int slab[4][kGroupRows][64];
-    const WavePos wp = wave_pos(g.col_tiles);
-    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int lane = (int)(threadIdx.x & 63);
-    const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
-    const int r0 = active ? wp.rb * g.rows_per_wave : 0;
-    const int r1 = active ? min(g.rows, r0 + g.rows_per_wave) : 0;
-    const int n = wp.ct * 64 + lane;
-    const int nload = (n < g.N) ? n : g.N - 1;
-    const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
-    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, wp.ct);
-    uniform_words As = as_uniform(g.A);
-    constexpr int KC = SEGS * CWT;
-    const int Kw = g.Cw;                                   // > KC, guaranteed by the host
-    trace_begin(g, wp);
-    for (int g0 = r0; g0 < r1; g0 += kGroupRows) {
-        const int g1 = min(r1, g0 + kGroupRows);
-        for (int k0 = 0; k0 < Kw; k0 += KC) {
-            const bool first = (k0 == 0);
-            const bool last = (k0 + KC >= Kw);
-            auto fetch = [&](int rel_row) -> int { return first ? g.kconst : slab[wv][rel_row][lane]; };
-            auto sink = [&](int rel_row, int v, int prev) {
-                if (last) finish_row<true>(ov, g0 - r0 + rel_row, v + prev, true, true);
-                else slab[wv][rel_row][lane] = v + prev;
-            };
-            if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT>(g, nload, g0, g1, k0, fetch, sink);
-            else gemm_chunk_tail<AB, WB, SEGS, CWT>(g, As, nload, g0, g1, k0, fetch, sink);
-        }
-    }
-    trace_end(g, wp);
-}
-
-// ---------------------------------------------------------------------------------------
 // GEMM with the K chunks split over the four wavefronts of a block (long K, few rows, e.g. a
 // fully connected layer on a small batch).  All four wavefronts own the same 64 columns and
 // the same block of rows; wavefront v takes chunks v, v+4, ...  A weight chunk is therefore
@@ -836,7 +791,7 @@ template <int AB, int WB>
 hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     using S = GemmShape<AB, WB>;
     const bool emit = g.planes_out != nullptr;
-    if (g.gather_rows && (AB > 4 || WB > 4 || g.split_k || g.row_groups)) return hipErrorInvalidValue;   // host bug
+    if (g.gather_rows && (AB > 4 || WB > 4 || g.split_k)) return hipErrorInvalidValue;   // host bug
     if (g.split_k) {
         const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
         const dim3 grid((unsigned)(row_blocks * g.col_tiles));
@@ -854,11 +809,6 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
                 else launch_gemm_short<AB, WB, 2>(g, emit, s);
                 return hipGetLastError();
             }
-        }
-        if (g.row_groups && g.Cw > S::KC) {
-            if (emit) hipLaunchKernelGGL((gemm_rowgroup_kernel<AB, WB, S::SEGS, S::CWT, true>), grid_for(g), dim3(256), 0, s, g);
-            else hipLaunchKernelGGL((gemm_rowgroup_kernel<AB, WB, S::SEGS, S::CWT, false>), grid_for(g), dim3(256), 0, s, g);
-            return hipGetLastError();
         }
         launch_gemm_plain<AB, WB, S::SEGS, S::CWT>(g, emit, s);
     }

@@ -36,9 +36,8 @@ struct BranchArgs {
     int col_tiles;        // ceil(N / 64)
     int split_k;          // GEMM only: K chunks split over the wavefronts of a block; then
                           // rows_per_wave is the number of rows per BLOCK
-    int row_groups;       // GEMM only: run all K chunks over groups of rows, partial sums in LDS
     int gather_rows;      // GEMM only: row r is output pixel r of a single-tap strided convolution (geo, H, W);
-                          // bit widths up to 4, not with split_k or row_groups
+                          // bit widths up to 4, not with split_k
     uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
     uint32_t trace_waves; // capacity of `trace` in wavefronts
     uint32_t *planes_out; // optional: the scaled result re-encoded with out_bits bits, as bit planes
