@@ -5,11 +5,15 @@
 //
 // Same mapping as the 3x3 kernels (lane = filter, a wavefront owns 64 filters and a run of
 // output pixels, weight words of the current chunk in VGPRs, the pixel's activation words
-// wave-uniform through scalar loads), but everything about the window is a run-time value:
-// a chunk is TT taps x CWT channel words, every tap of every pixel is tested against the image,
-// taps outside contribute nothing and the constant term counts the taps that are inside.
-// Partial sums of the chunks round-trip through the output buffer (same lane, same address).
-// This is the general path: the 3x3 / stride 1 / pad 1 case has its own, faster kernels.
+// wave-uniform through scalar loads), but everything about the window is a run-time value.
+// A chunk is TT taps x CWT channel words.  Per output row the pixels for which every tap of the
+// chunk lies inside the image run without any test (gen_run_fast); the others (borders, chunks
+// with padding words) test every tap, taps outside contribute nothing and the constant term
+// counts the taps that are inside (gen_pixel_checked).  Partial sums of the chunks round-trip
+// through the output buffer (same lane, same address).  The transposed form walks the output
+// by phase (transposed_body).  Few input channels take the packed-window kernel at the end of
+// the file.  This is the general path: the 3x3 / stride 1 / pad 1 case has its own, faster
+// kernels, and single-tap convolutions without padding run on the GEMM kernels.
 #include <type_traits>
 #include "qnn_internal.h"
 #include "qnn_device_util.h"

@@ -124,6 +124,26 @@ def test_conv2d_few_channels(q, oracle, case, workspace):
     run_case(q, oracle, workspace=workspace, out_bits=4, seed=5, **case)
 
 
+# the layers bench.py times (`--workload conv_geometries`), at their full sizes and in the launch
+# configuration the library picks for them; the oracle computes the whole layer
+FULL_SIZE_CASES = [
+    dict(Nb=32, H=224, W=224, C=3, Cout=64, ab=8, wb=2, KH=7, KW=7, stride=2, pad=3),
+    dict(Nb=32, H=56, W=56, C=128, Cout=128, ab=2, wb=2, KH=3, KW=3, stride=2, pad=1),
+    dict(Nb=32, H=56, W=56, C=256, Cout=512, ab=2, wb=2, KH=1, KW=1, stride=2),
+    dict(Nb=32, H=56, W=56, C=256, Cout=64, ab=2, wb=2, KH=1, KW=1),
+    dict(Nb=32, H=56, W=56, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),
+    dict(Nb=16, H=33, W=33, C=256, Cout=256, ab=4, wb=3, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=16, H=28, W=28, C=256, Cout=128, ab=2, wb=2, KH=4, KW=4, stride=2, pad=1, transposed=True),
+]
+
+
+@pytest.mark.parametrize("case", FULL_SIZE_CASES, ids=lambda c: "full-%dx%d-C%d-k%d-s%s%s" % (
+    c["H"], c["W"], c["C"], c["KH"], c.get("stride", 1), "-T" if c.get("transposed") else ""))
+def test_conv2d_general_full_size(q, oracle, case):
+    say("conv2d_general full size", case)
+    run_case(q, oracle, **case)
+
+
 @pytest.mark.parametrize("out_bits", [1, 2, 4, 8])
 def test_conv2d_general_requant(q, oracle, out_bits):
     say("conv2d_general requant", out_bits)
