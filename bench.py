@@ -50,6 +50,46 @@ def timed(torch, fn, n):
     return a.elapsed_time(b) / n * 1e3
 
 
+def traced_launch(torch, np, q, launch):
+    """One launch with the per-wavefront trace on: every wavefront records its start and end on
+    the shader clock (s_memtime), its hardware position and its start on the chip-wide 100 MHz
+    clock.  The ratio of the two clocks between the first and the last wavefront of a SIMD is
+    the shader clock the kernel really ran at."""
+    cap = 1 << 20
+    buf = torch.zeros(cap * 4, dtype=torch.int64, device="cuda")
+    q.set_wave_trace(buf)
+    launch()
+    torch.cuda.synchronize()
+    q.set_wave_trace(None)
+    t = buf.cpu().numpy().reshape(cap, 4)
+    t = t[t[:, 0] != 0]
+    if len(t) == 0:
+        return None
+    start, end, hw, rt = t[:, 0], t[:, 1], t[:, 2] & 0xffffffff, t[:, 3]
+    xcc = (t[:, 2] >> 32) & 15
+    simd, cu, sh, se = (hw >> 4) & 3, (hw >> 8) & 15, (hw >> 12) & 1, (hw >> 13) & 7
+    key = ((((xcc * 8 + se) * 2 + sh) * 16 + cu) * 4 + simd).astype(np.int64)
+    ids, idx = np.unique(key, return_inverse=True)
+    big = np.iinfo(np.int64).max
+
+    def per_simd(values, fn, init):
+        out = np.full(len(ids), init, dtype=np.int64)
+        fn.at(out, idx, values)
+        return out
+    first_start, last_start = per_simd(start, np.minimum, big), per_simd(start, np.maximum, 0)
+    first_rt, last_rt = per_simd(rt, np.minimum, big), per_simd(rt, np.maximum, 0)
+    last_end = per_simd(end, np.maximum, 0)
+    counts = np.bincount(idx, minlength=len(ids))
+    window = last_end - first_start
+    spread = (last_rt - first_rt) > 500                      # SIMDs whose wavefront starts span > 5 us
+    ghz = float(np.median((last_start - first_start)[spread] / (last_rt - first_rt)[spread])) / 10.0 if spread.any() else None
+    return {"wavefronts": int(len(t)), "simds": int(len(ids)),
+            "wavefronts_per_simd_min_max": [int(counts.min()), int(counts.max())],
+            "simd_active_window_cycles_p0_p50_p100": [int(x) for x in np.percentile(window, [0, 50, 100])],
+            "first_start_spread_us": round(float(first_rt.max() - first_rt.min()) / 100.0, 2),
+            "shader_clock_GHz": None if ghz is None else round(ghz, 3)}
+
+
 def side_suites(name, args, steps, warmup, torch, np, q, dev):
     """Micro-benchmarks outside the headline: the memory-bound kernels at sizes that fill the chip,
     and qnn_conv2d_general on layer shapes of the networks the paper evaluates.  One JSON line."""
@@ -143,6 +183,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of 256 MiB (a kernel of known HBM traffic) "
                          "so that a counter run can be scaled against it")
+    ap.add_argument("--wave-trace", action="store_true",
+                    help="additionally run ONE launch of the branch kernel with the per-wavefront trace "
+                         "(qnn_set_wave_trace) and report config.wave_trace: wavefronts per SIMD, the SIMDs' "
+                         "active windows in shader cycles and the shader clock during the kernel")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the path on ONE GPU only (the path shards over the batch "
@@ -382,6 +426,10 @@ def main():
                            "us": round(dot_us, 2), "GOPS": round(ops / (dot_us * 1e-6) / 1e9, 1)}
         branch()                                  # leave the branch result in the output buffer
 
+    wave_trace = None
+    if args.wave_trace and name != "vgg16_stack":
+        wave_trace = traced_launch(torch, np, q, branch)
+
     graph_ms = None
     if args.graph:
         side = torch.cuda.Stream()
@@ -427,6 +475,7 @@ def main():
             "comparison_int8_mfma": compare,
             "comparison_int8_dot4": compare_dot,
             "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
+            "wave_trace": wave_trace,
         },
         "roofline": {
             "bound": "alu",
