@@ -192,3 +192,47 @@ def test_general_equals_the_3x3_kernels(q, oracle):
     a1, _ = q.conv2d_packed(Xp, ab, Wp, wb, Nb, H, W, C, Cout)
     a2, _, _ = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, q.conv_geometry(3, 3, pad=1))
     assert (host(a1) == host(a2)).all() and (host(a1).astype(np.int64) == oracle.conv3x3(X, Wt)).all()
+
+
+def random_case(rng):
+    """A small random layer: any geometry the entry point accepts, sizes that keep the oracle quick."""
+    transposed = bool(rng.integers(0, 3) == 0)
+    KH, KW = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    stride = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+    dilation = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+    pad = (int(rng.integers(0, 4)), int(rng.integers(0, 4)))
+    H, W = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+    C = int(rng.choice([1, 3, 8, 31, 32, 33, 64, 96, 100, 128, 160, 192, 300]))
+    Cout = int(rng.choice([1, 5, 32, 63, 64, 65, 100, 130]))
+    ab, wb = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    case = dict(Nb=int(rng.integers(1, 4)), H=H, W=W, C=C, Cout=Cout, ab=ab, wb=wb, KH=KH, KW=KW, stride=stride,
+                pad=pad, dilation=dilation, transposed=transposed)
+    if transposed:
+        case["output_padding"] = (int(rng.integers(0, max(stride[0], dilation[0]))),
+                                  int(rng.integers(0, max(stride[1], dilation[1]))))
+    return case
+
+
+def test_conv2d_general_random_geometries(q, oracle):
+    """Seeded random geometries, channel counts and bit widths, with and without re-encoding."""
+    rng = np.random.default_rng(20240607)
+    done = 0
+    for i in range(400):
+        case = random_case(rng)
+        sh, sw = case["stride"]
+        dh, dw = case["dilation"]
+        ph, pw = case["pad"]
+        if case["transposed"]:
+            oph, opw = case["output_padding"]
+            Ho = (case["H"] - 1) * sh - 2 * ph + dh * (case["KH"] - 1) + oph + 1
+            Wo = (case["W"] - 1) * sw - 2 * pw + dw * (case["KW"] - 1) + opw + 1
+        else:
+            Ho = (case["H"] + 2 * ph - dh * (case["KH"] - 1) - 1) // sh + 1
+            Wo = (case["W"] + 2 * pw - dw * (case["KW"] - 1) - 1) // sw + 1
+        if Ho < 1 or Wo < 1 or case["KH"] * case["KW"] * case["C"] * 255 * 255 >= 2 ** 31:
+            continue
+        out_bits = int(rng.choice([0, 0, 1, 3, 4, 8]))
+        say("random geometry", i, case, "out_bits", out_bits)
+        run_case(q, oracle, out_bits=out_bits, seed=i, workspace=bool(rng.integers(0, 2)), **case)
+        done += 1
+    assert done >= 200

@@ -122,6 +122,21 @@ def test_gemm_short_products(q, oracle, K, ab, wb):
              rng.uniform(0.01, 0.1, N).astype(np.float32))
 
 
+def test_gemm_random_shapes(q, oracle):
+    """Seeded random shapes and bit widths: every launch path (plain, shorter chunks, split K)."""
+    rng = np.random.default_rng(777)
+    for i in range(150):
+        ab, wb = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        M = int(rng.choice([1, 2, 7, 33, 100, 257, 600, 2500]))
+        N = int(rng.choice([1, 5, 64, 65, 130, 300]))
+        K = int(rng.choice([1, 31, 32, 64, 100, 257, 512, 1000, 2100, 4096]))
+        if K * ((1 << ab) - 1) * ((1 << wb) - 1) >= 2 ** 31:
+            continue
+        say("random gemm", i, M, N, K, "bits", ab, wb)
+        s = rng.uniform(0.01, 0.1, N).astype(np.float32) if rng.integers(0, 2) else None
+        run_gemm(q, oracle, rand_codes(rng, (M, K), ab), rand_codes(rng, (K, N), wb), ab, wb, s)
+
+
 @pytest.mark.parametrize("rpw", [1, 3, 64])
 def test_gemm_any_rows_per_wave(q, oracle, rpw):
     """The launch partition is a performance knob only."""
