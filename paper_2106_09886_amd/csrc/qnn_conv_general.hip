@@ -375,23 +375,32 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
         return;
     }
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
+        int kh_next = 0, kw_next = 0;                    // kernel element of tap t0: counted, never divided
         for (int t0 = 0; t0 < T; t0 += TT) {
             const bool first = (c0 == 0 && t0 == 0);
             const bool last = (c0 + CWT >= Cw && t0 + TT >= T);
             // offsets of the chunk's taps along both axes: input = output*stride + off, off = k*dil - pad
+            // (all on the scalar unit, so that tap tests and addresses stay there too)
             int offh[TT], offw[TT];
-            // output columns for which every tap of the chunk is inside the image, [lo, hi)
-            int lo = 0, hi = q.Wo;
+            int kw_min = q.KW, kw_max = -1;
 #pragma unroll
             for (int i = 0; i < TT; ++i) {
                 const int t = t0 + i;
-                const int kh = t / q.KW, kw = t - kh * q.KW;
-                offh[i] = kh * q.dh - q.ph;
-                offw[i] = kw * q.dw - q.pw;
+                offh[i] = kh_next * q.dh - q.ph;
+                offw[i] = kw_next * q.dw - q.pw;
                 if (t < T) {
-                    lo = max(lo, -floor_div(offw[i], q.sw));                  // ceil(-off / s)
-                    hi = min(hi, floor_div(g.W - 1 - offw[i], q.sw) + 1);
+                    kw_min = min(kw_min, kw_next);
+                    kw_max = max(kw_max, kw_next);
                 }
+                if (++kw_next == q.KW) { kw_next = 0; ++kh_next; }
+            }
+            // output columns for which every tap of the chunk is inside the image, [lo, hi): the
+            // left end is set by the leftmost kernel column of the chunk, the right end by the rightmost
+            const int lo = max(0, __builtin_amdgcn_readfirstlane(-floor_div(kw_min * q.dw - q.pw, q.sw)));   // ceil(-off / s)
+            const int hi = min(q.Wo, __builtin_amdgcn_readfirstlane(floor_div(g.W - 1 - (kw_max * q.dw - q.pw), q.sw) + 1));
+#pragma unroll
+            for (int i = 0; i < TT; ++i) {
+                const int t = t0 + i;
 #pragma unroll
                 for (int qq = 0; qq < WB; ++qq) {
                     if (t < T && c0 + CWT <= Cw) {
@@ -406,8 +415,6 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
             int ow = ow0, oh = oh0, img = n0;
             int r = r0;
             {
-                lo = __builtin_amdgcn_readfirstlane(lo);
-                hi = __builtin_amdgcn_readfirstlane(hi);
                 const bool fast_chunk = (c0 + CWT <= Cw);
                 auto checked = [&](int x, int oh_x, int ow_x) {
                     auto tap = [&](int i, int &ih, int &iw) {
