@@ -83,10 +83,12 @@ __device__ __forceinline__ void load_words(uint64_t addr, uint32_t (&out)[CWT]) 
 // The chunk's taps are taken in groups of LG (LG divides TT): the words of a group are requested
 // together, which bounds the scalar registers a pixel needs while the chunk's weights (TT taps)
 // stay in vector registers; a group without a used tap is skipped.
-template <int AB, int WB, int CWT, int TT, int LG, class OV>
-__device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int rel0, int count,
-                                             int rel_step, uint32_t off_a, uint32_t step, int kadd, bool first,
-                                             bool last) {
+// ALL: every tap of the chunk is used (the usual case away from the top and bottom image rows):
+// no test per tap or group.
+template <int AB, int WB, int CWT, int TT, int LG, bool ALL, class OV>
+__device__ __forceinline__ void gen_run_fast_t(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int rel0, int count,
+                                               int rel_step, uint32_t off_a, uint32_t step, int kadd, bool first,
+                                               bool last) {
     static_assert(TT % LG == 0, "whole load groups");
     uint32_t off = off_a;
     int rel = rel0;
@@ -99,7 +101,7 @@ __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, c
         for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
 #pragma unroll
         for (int g0 = 0; g0 < TT; g0 += LG) {
-            if (TT > LG && !(c.okmask & (((1u << LG) - 1u) << g0))) continue;
+            if (!ALL && TT > LG && !(c.okmask & (((1u << LG) - 1u) << g0))) continue;
             uint32_t a[LG][AB][CWT];
 #pragma unroll
             for (int i = 0; i < LG; ++i)
@@ -108,7 +110,7 @@ __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, c
                     load_words<CWT>(c.base + (uint32_t)(off + c.toff[g0 + i] + (uint32_t)p * c.plane_bytes), a[i][p]);
 #pragma unroll
             for (int i = 0; i < LG; ++i)
-                if (c.okmask & (1u << (g0 + i))) {
+                if (ALL || (c.okmask & (1u << (g0 + i)))) {
 #pragma unroll
                     for (int qq = 0; qq < WB; ++qq)
 #pragma unroll
@@ -124,6 +126,14 @@ __device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, c
         off += step;
         rel += rel_step;
     }
+}
+
+template <int AB, int WB, int CWT, int TT, int LG, class OV>
+__device__ __forceinline__ void gen_run_fast(const GenCtx<AB, WB, CWT, TT> &c, const OV &ov, int rel0, int count,
+                                             int rel_step, uint32_t off_a, uint32_t step, int kadd, bool first,
+                                             bool last) {
+    if (c.okmask == (1u << TT) - 1u) gen_run_fast_t<AB, WB, CWT, TT, LG, true>(c, ov, rel0, count, rel_step, off_a, step, kadd, first, last);
+    else gen_run_fast_t<AB, WB, CWT, TT, LG, false>(c, ov, rel0, count, rel_step, off_a, step, kadd, first, last);
 }
 
 // One output pixel of one chunk with every tap tested (image borders, transposed convolution,
