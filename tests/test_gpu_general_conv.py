@@ -181,6 +181,37 @@ def test_conv2d_general_planes_only(q, oracle):
     assert (planes_u32(planes) == pw).all()
 
 
+@pytest.mark.parametrize("stride,C", [(1, 1100), (2, 1100), (2, 256), (3, 40)])
+def test_conv2d_single_tap_planes_only(q, oracle, stride, C):
+    """1x1 convolutions (the GEMM kernels, with the row walker when strided) with only the next
+    layer's planes requested; the workspace is sized by qnn_conv2d_general_workspace_bytes."""
+    say("single tap planes only", stride, C)
+    import ctypes
+    import torch
+    rng = np.random.default_rng(stride * 1000 + C)
+    Nb, H, W, Cout, ab, wb, ob = 2, 9, 7, 70, 2, 2, 4
+    X = rand_codes(rng, (Nb, H, W, C), ab)
+    Wt = rand_codes(rng, (Cout, 1, 1, C), wb)
+    want = oracle.conv2d(X, Wt, stride=stride)
+    s = (rng.uniform(0.5, 1.5, Cout) * 16.0 / (np.sqrt(np.mean(want.astype(np.float64) ** 2)) + 1)).astype(np.float32)
+    codes = oracle.requant(oracle.scale_f32(want, s), ob)
+    pw, _ = oracle.pack_planes(codes.reshape(-1, Cout), ob)
+    geo = q.conv_geometry(1, 1, stride=stride)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout, C)), wb)
+    Ho, Wo = q.conv2d_general_output_size(H, W, geo)
+    planes = torch.empty((Nb * Ho * Wo, ob, (Cout + 31) // 32), dtype=torch.int32, device="cuda")
+    need = int(q.lib().qnn_conv2d_general_workspace_bytes(Nb, H, W, C, Cout, ab, wb, ctypes.byref(geo)))
+    ws = torch.empty(max(16, need), dtype=torch.uint8, device="cuda")
+    sd = dev(s)
+    st = q.lib().qnn_conv2d_general(ctypes.c_void_p(Xp.data_ptr()), ab, ctypes.c_void_p(Wp.data_ptr()), wb, Nb, H, W,
+                                    C, Cout, ctypes.byref(geo), None, ctypes.c_void_p(sd.data_ptr()), None, ob,
+                                    ctypes.c_void_p(planes.data_ptr()), ctypes.c_void_p(ws.data_ptr()), need, None)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert (planes_u32(planes) == pw).all()
+
+
 def test_general_equals_the_3x3_kernels(q, oracle):
     """Same product through the dedicated 3x3 kernels and through the general one."""
     rng = np.random.default_rng(21)
