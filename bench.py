@@ -94,6 +94,11 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
     """Micro-benchmarks outside the headline: the memory-bound kernels at sizes that fill the chip,
     and qnn_conv2d_general on layer shapes of the networks the paper evaluates.  One JSON line."""
     def avg_us(fn):
+        t_end = time.time() + 0.1                       # untimed: let the clocks settle under this kernel
+        while time.time() < t_end:
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
         for _ in range(warmup):
             fn()
         return timed(torch, fn, steps)
