@@ -559,7 +559,8 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.trace = nullptr; g.trace_waves = 0;
     g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
     g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;
-    g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = q->transposed;
+    g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo;
+    g.geo.transposed = (q->transposed && cw > 0) ? 1 : 0;      // an empty sum needs no phases
     // Few input channels and a window of at most 256 bits: packed im2col rows, if the caller gave
     // the workspace for them (else the general kernel below does the same, a word per tap).
     const int kwp = (!q->transposed && C <= 32 && taps >= 2 && wb <= 4) ? window_words(taps * C) : 0;
@@ -590,12 +591,10 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     if (rpw <= 0) {
         rpw = rows * g.col_tiles / ((int64_t)device_simd_count() * 6);
         if (rpw < 14) rpw = 14;
-        // transposed: a wavefront visits its pixels once per output phase with a sub-kernel each
-        if (q->transposed && rpw < 14 * (int64_t)q->stride_h * q->stride_w) rpw = 14 * (int64_t)q->stride_h * q->stride_w;
         // With only a few wavefronts per SIMD the kernel lasts as long as the SIMDs that got one
         // more than the others: around that count (down to 10 pixels) take the one that fills the
         // last round best (3.5 wavefronts per SIMD at 14 pixels cost 12 % on a strided ResNet layer).
-        if (!q->transposed) {
+        if (!g.geo.transposed) {
             const int64_t base = rpw;
             double best = -1.0;
             for (int64_t cand = (base - 4 < 10 ? 10 : base - 4); cand <= base + 2; ++cand) {
@@ -605,7 +604,32 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
             }
         }
     }
+    if (g.geo.transposed && tuning().rows_per_wave <= 0) {
+        // pixels of one phase per wavefront: a divisor of the phase's row length near 16, so that
+        // runs do not straddle phase rows (measured on 2x2, 3x3 and 4x4 stride-2 layers), else 20
+        const int64_t wp = (Wo + q->stride_w - 1) / q->stride_w;
+        rpw = 20;
+        int64_t best = 1 << 30;
+        for (int64_t cand = 12; cand <= 32; ++cand)
+            if (wp % cand == 0 && (cand > 16 ? cand - 16 : 16 - cand) < best) {
+                best = cand > 16 ? cand - 16 : 16 - cand;
+                rpw = cand;
+            }
+    }
     if (rpw > rows) rpw = rows;
+    if (g.geo.transposed) {
+        // The launch is phase-major: rows_per_wave counts pixels of ONE output phase, which lie
+        // stride_w apart in a row and stride_h rows apart.  The output slice a wavefront addresses
+        // spans at most (rpw + 3) * stride_h + 1 output rows; it has to stay below 2^31 bytes like
+        // any other wavefront's slice.
+        const int64_t span_rows = (rpw + 3) * (int64_t)q->stride_h + 1;
+        if (span_rows > kInt31 / Wo) return QNN_EUNSUPPORTED;
+        const int64_t span = span_rows * Wo;
+        if (span > kInt31 || clamp_rows_for_emit(clamp_rows_per_wave((int)span, Cout), Cout, e) != (int)span)
+            return QNN_EUNSUPPORTED;
+        g.rows_per_wave = (int)rpw;
+        return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
+    }
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw, Cout), Cout, e);
     return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
 }

@@ -11,7 +11,7 @@
 // with padding words) test every tap, taps outside contribute nothing and the constant term
 // counts the taps that are inside (gen_pixel_checked).  Partial sums of the chunks round-trip
 // through the output buffer (same lane, same address).  The transposed form walks the output
-// by phase (transposed_body).  Few input channels take the packed-window kernel at the end of
+// by phase (transposed_phases).  Few input channels take the packed-window kernel at the end of
 // the file.  This is the general path: the 3x3 / stride 1 / pad 1 case has its own, faster
 // kernels, and single-tap convolutions without padding run on the GEMM kernels.
 #include <type_traits>
@@ -197,157 +197,173 @@ __device__ __forceinline__ void step(TapWalk &w, AxisSplit dil, int stride) {   
     if (w.res >= stride) { w.res -= stride; ++w.Q; }
 }
 
+// The launch is phase-major: blockIdx.y walks the sh*sw phases, and within a phase the wavefronts
+// split its pixels (all images, sub-rows and sub-columns of that phase, in this order) into runs
+// of rows_per_wave, so a wavefront has ONE sub-kernel and every SIMD gets its share whatever the
+// stride.  Sub-row i, sub-column j of phase (pa, pb) is output pixel (a0 + i*sh, b0 + j*sw), with
+// a0 the first row of the phase, and reads input pixel (i + qa, j + qb) shifted by the tap.
 template <int AB, int WB, int CWT, int TT, class OV>
-__device__ __forceinline__ void transposed_body(const BranchArgs &g, const OV &ov, uniform_words As,
-                                                GenCtx<AB, WB, CWT, TT> &c, int nload, int r0, int r1, int oh0,
-                                                int ow0, int n0) {
+__device__ __forceinline__ void transposed_phases(const BranchArgs &g, uniform_words As, int nload, float sc, int ct,
+                                                  int wave_x) {
     const ConvGeom &q = g.geo;
     const int T = q.KH * q.KW, Cw = g.Cw;
     const uint32_t pixel_bytes = (uint32_t)(AB * Cw) * 4u;
-    // the few divisions of this function: stride splits of the dilation, the padding and the first pixel
+    const int Nb = __builtin_amdgcn_readfirstlane(g.rows / (q.Ho * q.Wo));
+    // the divisions of this function are per wavefront (or per phase), never per tap or pixel
     AxisSplit dh_s = split(q.dh, q.sh), dw_s = split(q.dw, q.sw);
-    AxisSplit ph_s = split(q.ph, q.sh), pw_s = split(q.pw, q.sw);                 // (0 + pad) split: start of a row / image
-    AxisSplit oh_first = split(oh0 + q.ph, q.sh), ow_first = split(ow0 + q.pw, q.sw);
-#define QNN_UNIFORM(v) v.q = __builtin_amdgcn_readfirstlane(v.q); v.m = __builtin_amdgcn_readfirstlane(v.m)
-    QNN_UNIFORM(dh_s); QNN_UNIFORM(dw_s); QNN_UNIFORM(ph_s); QNN_UNIFORM(pw_s); QNN_UNIFORM(oh_first); QNN_UNIFORM(ow_first);
-#undef QNN_UNIFORM
-    for (int pa = 0; pa < q.sh; ++pa)
-        for (int pb = 0; pb < q.sw; ++pb) {
-            // taps of this phase: kh*dh = pa and kw*dw = pb modulo the stride
-            int ntaps = 0;
-            {
-                TapWalk wh = {0, 0}, ww = {0, 0};
-                int kw = 0;
-                for (int t = 0; t < T; ++t) {
-                    if (wh.res == pa && ww.res == pb) ++ntaps;
-                    step(ww, dw_s, q.sw);
-                    if (++kw == q.KW) { kw = 0; ww.Q = 0; ww.res = 0; step(wh, dh_s, q.sh); }
-                }
+    dh_s.q = __builtin_amdgcn_readfirstlane(dh_s.q); dh_s.m = __builtin_amdgcn_readfirstlane(dh_s.m);
+    dw_s.q = __builtin_amdgcn_readfirstlane(dw_s.q); dw_s.m = __builtin_amdgcn_readfirstlane(dw_s.m);
+    const int ph_m = __builtin_amdgcn_readfirstlane(q.ph % q.sh), pw_m = __builtin_amdgcn_readfirstlane(q.pw % q.sw);
+    GenCtx<AB, WB, CWT, TT> c;
+    c.base = (uint64_t)g.A;
+    c.plane_bytes = (uint32_t)Cw * 4u;
+    for (int phase = (int)blockIdx.y; phase < q.sh * q.sw; phase += (int)gridDim.y) {
+        const int pa = __builtin_amdgcn_readfirstlane(phase / q.sw), pb = phase - pa * q.sw;
+        // first output row / column of the phase: the smallest o >= 0 with (o + pad) mod s == p
+        const int a0 = (pa >= ph_m) ? pa - ph_m : pa - ph_m + q.sh;
+        const int b0 = (pb >= pw_m) ? pb - pw_m : pb - pw_m + q.sw;
+        if (a0 >= q.Ho || b0 >= q.Wo) continue;                           // no pixel has this phase
+        const int Hp = __builtin_amdgcn_readfirstlane((q.Ho - a0 + q.sh - 1) / q.sh);
+        const int Wp = __builtin_amdgcn_readfirstlane((q.Wo - b0 + q.sw - 1) / q.sw);
+        const int items = Nb * Hp * Wp;
+        const int it0 = wave_x * g.rows_per_wave;
+        if (wave_x >= (items + g.rows_per_wave - 1) / g.rows_per_wave) continue;
+        const int it1 = min(items, it0 + g.rows_per_wave);
+        const int qa = __builtin_amdgcn_readfirstlane((a0 + q.ph - pa) / q.sh);   // exact by construction
+        const int qb = __builtin_amdgcn_readfirstlane((b0 + q.pw - pb) / q.sw);
+        auto decode = [&](int it, int &n, int &i, int &j) {
+            n = __builtin_amdgcn_readfirstlane(it / (Hp * Wp));
+            const int rem = it - n * Hp * Wp;
+            i = __builtin_amdgcn_readfirstlane(rem / Wp);
+            j = rem - i * Wp;
+        };
+        auto out_pixel = [&](int n, int i, int j) { return (n * q.Ho + a0 + i * q.sh) * q.Wo + b0 + j * q.sw; };
+        int n0, i0, j0, n9, i9, j9;
+        decode(it0, n0, i0, j0);
+        decode(it1 - 1, n9, i9, j9);
+        const int first_pix = out_pixel(n0, i0, j0);
+        const OV ov = make_out_view<OV>(g, first_pix, out_pixel(n9, i9, j9) + 1, nload, sc, ct);
+
+        // taps of this phase: kh*dh = pa and kw*dw = pb modulo the stride
+        int ntaps = 0;
+        {
+            TapWalk wh = {0, 0}, ww = {0, 0};
+            int kw = 0;
+            for (int t = 0; t < T; ++t) {
+                if (wh.res == pa && ww.res == pb) ++ntaps;
+                step(ww, dw_s, q.sw);
+                if (++kw == q.KW) { kw = 0; ww.Q = 0; ww.res = 0; step(wh, dh_s, q.sh); }
             }
-            const int nchunks = (ntaps + TT - 1) / TT;             // 0: the phase's pixels are plain zeros
-            for (int c0 = 0; c0 < ((nchunks == 0) ? 1 : Cw); c0 += CWT)
-                for (int lc = 0; lc < ((nchunks == 0) ? 1 : nchunks); ++lc) {
-                    const bool first = (c0 == 0 && lc == 0);
-                    const bool last = (nchunks == 0) || (c0 + CWT >= Cw && lc + 1 >= nchunks);
-                    // taps lc*TT .. of the phase's list: weight index and input offset in input pixels
-                    // relative to (Iq, Jq) = ((oh + ph - pa) / sh, (ow + pw - pb) / sw); for a tap of the
-                    // phase (pa - kh*dh) / sh = -Q exactly
-                    int dqh[TT], dqw[TT];
-                    uint32_t used = 0u;                             // bit i: slot i holds a tap
+        }
+        const int nchunks = (ntaps + TT - 1) / TT;             // 0: the phase's pixels are plain zeros
+        for (int c0 = 0; c0 < ((nchunks == 0) ? 1 : Cw); c0 += CWT)
+            for (int lc = 0; lc < ((nchunks == 0) ? 1 : nchunks); ++lc) {
+                const bool first = (c0 == 0 && lc == 0);
+                const bool last = (nchunks == 0) || (c0 + CWT >= Cw && lc + 1 >= nchunks);
+                // taps lc*TT .. of the phase's list: weight index and input offset in input pixels
+                // relative to (i + qa, j + qb); for a tap of the phase (pa - kh*dh) / sh = -Q exactly
+                int dqh[TT], dqw[TT];
+                uint32_t used = 0u;                             // bit i: slot i holds a tap
 #pragma unroll
-                    for (int i = 0; i < TT; ++i) {
-                        dqh[i] = 0; dqw[i] = 0;
+                for (int i = 0; i < TT; ++i) {
+                    dqh[i] = 0; dqw[i] = 0;
 #pragma unroll
-                        for (int qq = 0; qq < WB; ++qq)
+                    for (int qq = 0; qq < WB; ++qq)
 #pragma unroll
-                            for (int j = 0; j < CWT; ++j) c.w[i][qq][j] = 0u;
-                    }
-                    {
-                        TapWalk wh = {0, 0}, ww = {0, 0};
-                        int kw = 0, seen = 0, slot = 0;
-                        for (int t = 0; t < T && slot < TT && nchunks > 0; ++t) {
-                            if (wh.res == pa && ww.res == pb) {
-                                if (seen >= lc * TT) {
+                        for (int j = 0; j < CWT; ++j) c.w[i][qq][j] = 0u;
+                }
+                {
+                    TapWalk wh = {0, 0}, ww = {0, 0};
+                    int kw = 0, seen = 0, slot = 0;
+                    for (int t = 0; t < T && slot < TT && nchunks > 0; ++t) {
+                        if (wh.res == pa && ww.res == pb) {
+                            if (seen >= lc * TT) {
 #pragma unroll
-                                    for (int i = 0; i < TT; ++i)
-                                        if (i == slot) {
-                                            dqh[i] = -wh.Q;
-                                            dqw[i] = -ww.Q;
+                                for (int i = 0; i < TT; ++i)
+                                    if (i == slot) {
+                                        dqh[i] = -wh.Q;
+                                        dqw[i] = -ww.Q;
 #pragma unroll
-                                            for (int qq = 0; qq < WB; ++qq) {
-                                                if (c0 + CWT <= Cw) {
-                                                    load_run<CWT>(g.Wt + ((nload * T + t) * WB + qq) * Cw + c0, c.w[i][qq]);
-                                                } else {
+                                        for (int qq = 0; qq < WB; ++qq) {
+                                            if (c0 + CWT <= Cw) {
+                                                load_run<CWT>(g.Wt + ((nload * T + t) * WB + qq) * Cw + c0, c.w[i][qq]);
+                                            } else {
 #pragma unroll
-                                                    for (int j = 0; j < CWT; ++j)
-                                                        c.w[i][qq][j] = (c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
-                                                }
+                                                for (int j = 0; j < CWT; ++j)
+                                                    c.w[i][qq][j] = (c0 + j < Cw) ? g.Wt[((nload * T + t) * WB + qq) * Cw + c0 + j] : 0u;
                                             }
                                         }
-                                    used |= 1u << slot;
-                                    ++slot;
-                                }
-                                ++seen;
-                            }
-                            step(ww, dw_s, q.sw);
-                            if (++kw == q.KW) { kw = 0; ww.Q = 0; ww.res = 0; step(wh, dh_s, q.sh); }
-                        }
-                    }
-                    // columns of the phase whose taps are all inside the image: Jq in [jlo, jhi)
-                    int jlo = 0, jhi = g.W;
-#pragma unroll
-                    for (int i = 0; i < TT; ++i)
-                        if (used & (1u << i)) {
-                            jlo = max(jlo, -dqw[i]);
-                            jhi = min(jhi, g.W - dqw[i]);
-                        }
-                    const bool fast_chunk = (c0 + CWT <= Cw) && used != 0u;
-                    // rows of the wavefront's range; (oh + ph) and (ow + pw) are kept split by the stride
-                    int r = r0, ow = ow0, img = n0, oh = oh0;
-                    AxisSplit ohs = oh_first, ows = ow_first;
-                    while (r < r1) {
-                        const int row_end = min(r1, r - ow + q.Wo);
-                        if (ohs.m == pa) {
-                            const int Iq = ohs.q;
-                            // first column >= ow of this phase and the phase pixels up to the row's end here
-                            const int wrap = (pb < ows.m) ? 1 : 0;
-                            const int need = pb - ows.m + wrap * q.sw;               // ow + need has phase pb
-                            const int Jq0 = ows.q + wrap;
-                            const int span = (row_end - r) - need;                    // pixels from the first phase pixel on
-                            const int count = (span > 0) ? __builtin_amdgcn_readfirstlane((span + q.sw - 1) / q.sw) : 0;
-                            const int rel0 = r + need - r0;
-                            // phase pixels x in [xa, xb) run untested
-                            int xa = 0, xb = 0;
-                            if (fast_chunk && count > 0) {
-                                uint32_t okmask = 0u, safe_off = 0u;
-#pragma unroll
-                                for (int i = 0; i < TT; ++i) {
-                                    const bool ok = (used & (1u << i)) && (unsigned)(Iq + dqh[i]) < (unsigned)g.H;
-                                    c.toff[i] = (uint32_t)(dqh[i] * g.W + dqw[i]) * pixel_bytes;
-                                    if (ok) {
-                                        if (okmask == 0u) safe_off = c.toff[i];
-                                        okmask |= 1u << i;
                                     }
-                                }
-                                if (okmask != 0u) {
-                                    xa = max(0, jlo - Jq0);
-                                    xb = min(count, jhi - Jq0);
-                                    if (xb <= xa) { xa = 0; xb = 0; }
-                                    else {
-                                        c.okmask = okmask;
-#pragma unroll
-                                        for (int i = 0; i < TT; ++i)
-                                            if (!(okmask & (1u << i))) c.toff[i] = safe_off;
-                                    }
-                                }
+                                used |= 1u << slot;
+                                ++slot;
                             }
-                            auto checked = [&](int x) {
-                                auto tap = [&](int i, int &ih, int &iw) {
-                                    ih = Iq + dqh[i];
-                                    iw = Jq0 + x + dqw[i];
-                                    return (used & (1u << i)) && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
-                                };
-                                gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, rel0 + x * q.sw, img, c0, first, last);
-                            };
-                            for (int x = 0; x < xa; ++x) checked(x);
-                            if (xb > xa) {
-                                const uint32_t off_a = (uint32_t)((img * g.H + Iq) * g.W + Jq0 + xa) * pixel_bytes + (uint32_t)c0 * 4u;
-                                const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
-                                gen_run_fast<AB, WB, CWT, TT, TT>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
-                            }
-                            for (int x = max(xb, xa); x < count; ++x) checked(x);
+                            ++seen;
                         }
-                        ow += row_end - r;
-                        r = row_end;
-                        if (ow == q.Wo) {                              // next row (a range ends inside a row only at r1)
-                            ow = 0;
-                            ows = pw_s;
-                            if (++ohs.m == q.sh) { ohs.m = 0; ++ohs.q; }
-                            if (++oh == q.Ho) { oh = 0; ohs = ph_s; ++img; }
-                        }
+                        step(ww, dw_s, q.sw);
+                        if (++kw == q.KW) { kw = 0; ww.Q = 0; ww.res = 0; step(wh, dh_s, q.sh); }
                     }
                 }
-        }
+                // sub-columns of the phase whose taps are all inside the image: j + qb in [jlo, jhi)
+                int jlo = 0, jhi = g.W;
+#pragma unroll
+                for (int i = 0; i < TT; ++i)
+                    if (used & (1u << i)) {
+                        jlo = max(jlo, -dqw[i]);
+                        jhi = min(jhi, g.W - dqw[i]);
+                    }
+                const bool fast_chunk = (c0 + CWT <= Cw) && used != 0u;
+                int n = n0, i = i0, j = j0, it = it0;
+                while (it < it1) {
+                    const int seg_end = min(it1, it - j + Wp);        // end of this sub-row within the range
+                    const int count = seg_end - it;
+                    const int Iq = i + qa, Jq0 = j + qb;
+                    const int rel0 = out_pixel(n, i, j) - first_pix;
+                    // phase pixels x in [xa, xb) run untested
+                    int xa = 0, xb = 0;
+                    if (fast_chunk) {
+                        uint32_t okmask = 0u, safe_off = 0u;
+#pragma unroll
+                        for (int k = 0; k < TT; ++k) {
+                            const bool ok = (used & (1u << k)) && (unsigned)(Iq + dqh[k]) < (unsigned)g.H;
+                            c.toff[k] = (uint32_t)(dqh[k] * g.W + dqw[k]) * pixel_bytes;
+                            if (ok) {
+                                if (okmask == 0u) safe_off = c.toff[k];
+                                okmask |= 1u << k;
+                            }
+                        }
+                        if (okmask != 0u) {
+                            xa = max(0, jlo - Jq0);
+                            xb = min(count, jhi - Jq0);
+                            if (xb <= xa) { xa = 0; xb = 0; }
+                            else {
+                                c.okmask = okmask;
+#pragma unroll
+                                for (int k = 0; k < TT; ++k)
+                                    if (!(okmask & (1u << k))) c.toff[k] = safe_off;
+                            }
+                        }
+                    }
+                    auto checked = [&](int x) {
+                        auto tap = [&](int k, int &ih, int &iw) {
+                            ih = Iq + dqh[k];
+                            iw = Jq0 + x + dqw[k];
+                            return (used & (1u << k)) && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+                        };
+                        gen_pixel_checked<AB, WB, CWT, TT>(g, ov, As, c.w, tap, rel0 + x * q.sw, n, c0, first, last);
+                    };
+                    for (int x = 0; x < xa; ++x) checked(x);
+                    if (xb > xa) {
+                        const uint32_t off_a = (uint32_t)((n * g.H + Iq) * g.W + Jq0 + xa) * pixel_bytes + (uint32_t)c0 * 4u;
+                        const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
+                        gen_run_fast<AB, WB, CWT, TT, TT>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
+                    }
+                    for (int x = max(xb, xa); x < count; ++x) checked(x);
+                    it = seg_end;
+                    j = 0;
+                    if (++i == Hp) { i = 0; ++n; }
+                }
+            }
+    }
 }
 
 template <int AB, int WB, int CWT, int TT, int LG, bool TR, bool EMIT>
@@ -356,17 +372,23 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
-    if ((int64_t)rb * g.rows_per_wave >= g.rows) return;
-    const int r0 = rb * g.rows_per_wave;
-    const int r1 = min(g.rows, r0 + g.rows_per_wave);
     const int lane = (int)(threadIdx.x & 63);
     const int n = ct * 64 + lane;
     const int nload = (n < g.N) ? n : g.N - 1;         // lanes past N redo column N-1 (same value, same address)
     const float sc = (g.scale != nullptr) ? g.scale[nload] : 1.0f;
-    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, ct);
     uniform_words As = as_uniform(g.A);
     const ConvGeom &q = g.geo;
     const int T = q.KH * q.KW, Cw = g.Cw;
+    if constexpr (TR) {
+        if (Cw != 0 && T != 0) {                        // (the empty sum takes the plain row split below)
+            transposed_phases<AB, WB, CWT, TT, OV>(g, As, nload, sc, ct, rb);
+            return;
+        }
+    }
+    if ((int64_t)rb * g.rows_per_wave >= g.rows) return;
+    const int r0 = rb * g.rows_per_wave;
+    const int r1 = min(g.rows, r0 + g.rows_per_wave);
+    const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, ct);
     if (Cw == 0 || T == 0) {                            // empty sum
         for (int r = r0; r < r1; ++r) finish_row<true>(ov, r - r0, 0, true, true);
         return;
@@ -380,10 +402,6 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     GenCtx<AB, WB, CWT, TT> c;
     c.base = (uint64_t)g.A;
     c.plane_bytes = (uint32_t)Cw * 4u;
-    if constexpr (TR) {
-        transposed_body<AB, WB, CWT, TT>(g, ov, As, c, nload, r0, r1, oh0, ow0, n0);
-        return;
-    }
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
         int kh_next = 0, kw_next = 0;                    // kernel element of tap t0: counted, never divided
         for (int t0 = 0; t0 < T; t0 += TT) {
@@ -601,8 +619,15 @@ void launch_general_shape(const BranchArgs &g, dim3 grid, bool emit, hipStream_t
     constexpr int LGW = TT < 3 ? TT : 3;
     constexpr int NGW = imin3(3, 96 / (WB * CWT * LGW), 3);
     if (g.geo.transposed) {
-        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, true>), grid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, false>), grid, dim3(256), 0, s, g);
+        // phase-major grid: y walks the phases, x the wavefronts of the largest phase (all images)
+        const ConvGeom &q = g.geo;
+        const int64_t nb = (int64_t)g.rows / ((int64_t)q.Ho * q.Wo);
+        const int64_t hp = (q.Ho + q.sh - 1) / q.sh, wp = (q.Wo + q.sw - 1) / q.sw;
+        const int64_t waves = ((nb * hp * wp + g.rows_per_wave - 1) / g.rows_per_wave) * g.col_tiles;
+        const int64_t phases = (int64_t)q.sh * q.sw;
+        const dim3 tgrid((unsigned)((waves + 3) / 4), (unsigned)(phases < 65535 ? phases : 65535));
+        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, true>), tgrid, dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, false>), tgrid, dim3(256), 0, s, g);
         return;
     }
     if constexpr (AB <= 2 && WB <= 4 && NGW >= 2) {
