@@ -146,14 +146,23 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
                  ("3x3 stride 1, 64->64, 56^2, W2A2 (general kernel on the headline shape)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
                  ("3x3 dilation 2, 256->256, 33^2, W3A4", 16, 33, 33, 256, 256, 4, 3, 3, 3, 1, 2, 2, False),
                  ("4x4 stride 2 transposed, 256->128, 28^2, W2A2", 16, 28, 28, 256, 128, 2, 2, 4, 4, 2, 1, 1, True)]
+        cases.insert(1, ("ResNet stem 7x7 stride 2, 3->64, 224^2, W2A8, row-dense input", 32, 224, 224, 3, 64, 8, 2,
+                         7, 7, 2, 3, 1, False))
         for (label, Nb, H, W, C, Cout, ab, wb, KH, KW, st, pd, dl, tr) in cases:
             Cw = (C + 31) // 32
-            Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * H * W, ab, Cw), dtype=torch.int32, device=dev)
-            if C < 32:
-                Xp &= (1 << C) - 1
+            dense = label.endswith("row-dense input")
+            if dense:                                  # one packed row per image row, W*C bits (tail bits zero)
+                Rw = (W * C + 31) // 32
+                Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * H, ab, Rw), dtype=torch.int32, device=dev)
+                if (W * C) % 32:
+                    Xp[:, :, -1] &= (1 << ((W * C) % 32)) - 1
+            else:
+                Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * H * W, ab, Cw), dtype=torch.int32, device=dev)
+                if C < 32:
+                    Xp &= (1 << C) - 1
             Wp = torch.randint(0, 1 << min(C, 30), (Cout, KH * KW, wb, Cw), dtype=torch.int32, device=dev)
             sd = torch.rand(Cout, device=dev)
-            geo = q.conv_geometry(KH, KW, stride=st, pad=pd, dilation=dl, transposed=tr)
+            geo = q.conv_geometry(KH, KW, stride=st, pad=pd, dilation=dl, transposed=tr, dense_rows=dense)
             Ho, Wo = q.conv2d_general_output_size(H, W, geo)
             t = avg_us(lambda: q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=sd))
             taps = KH * KW / (st * st if tr else 1)

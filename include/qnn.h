@@ -232,6 +232,12 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  * QNN_EINVAL for a geometry that is not positive (kernel, stride, dilation >= 1, padding >= 0,
  * out_pad only with transposed = 1 and smaller than max(stride, dilation), Ho, Wo >= 1).
  * Limits as for qnn_conv2d_packed with 9 replaced by kh*kw, for input and output pixel counts.
+ * dense_rows = 1 (images with few channels, e.g. the 3-channel input of a network's stem): the
+ * activations are packed per image ROW instead of per pixel, x_planes = qnn_encode_pack(codes
+ * viewed as [Nb*H][W*C], bits = ab) = uint32 [Nb*H][ab][ceil(W*C/32)], an eighth of the per-pixel
+ * size for C = 3, and a kernel row of the window is a run of KW*C consecutive bits.  Accepted
+ * only where the packed-window path applies (forward convolution, C <= 32, kh*kw*C <= 256,
+ * wb <= 4) and with its workspace; QNN_EUNSUPPORTED otherwise.
  * The 3x3 / stride 1 / pad 1 case is served faster by qnn_conv2d_packed.  A 1x1 convolution
  * without padding runs on the kernels of qnn_branch_gemm (rows = output pixels; with a stride and
  * bit widths up to 4 the rows are the strided selection of the input pixels).
@@ -243,6 +249,7 @@ typedef struct {
     int dil_h, dil_w;
     int transposed;
     int out_pad_h, out_pad_w;
+    int dense_rows;   /* 1: x_planes is ROW-DENSE, see below (few input channels only); else 0 */
 } qnn_conv_geometry;
 
 qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *h_geo,

@@ -33,16 +33,16 @@ EXPORTS = (
 class ConvGeometry(ctypes.Structure):
     """qnn_conv_geometry of include/qnn.h."""
     _fields_ = [(n, ctypes.c_int) for n in ("kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
-                                            "transposed", "out_pad_h", "out_pad_w")]
+                                            "transposed", "out_pad_h", "out_pad_w", "dense_rows")]
 
 
 def _pair(v):
     return (int(v), int(v)) if isinstance(v, int) else (int(v[0]), int(v[1]))
 
 
-def conv_geometry(kh, kw, stride=1, pad=0, dilation=1, transposed=False, output_padding=0):
+def conv_geometry(kh, kw, stride=1, pad=0, dilation=1, transposed=False, output_padding=0, dense_rows=False):
     (sh, sw), (ph, pw), (dh, dw), (oh, ow) = _pair(stride), _pair(pad), _pair(dilation), _pair(output_padding)
-    return ConvGeometry(kh, kw, sh, sw, ph, pw, dh, dw, 1 if transposed else 0, oh, ow)
+    return ConvGeometry(kh, kw, sh, sw, ph, pw, dh, dw, 1 if transposed else 0, oh, ow, 1 if dense_rows else 0)
 
 
 class QnnError(RuntimeError):

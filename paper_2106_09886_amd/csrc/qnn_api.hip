@@ -479,6 +479,7 @@ qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_g
     if (q == nullptr || h_Ho == nullptr || h_Wo == nullptr || H < 0 || W < 0) return QNN_EINVAL;
     if (q->kh < 1 || q->kw < 1 || q->stride_h < 1 || q->stride_w < 1 || q->dil_h < 1 || q->dil_w < 1) return QNN_EINVAL;
     if (q->pad_h < 0 || q->pad_w < 0 || (q->transposed != 0 && q->transposed != 1)) return QNN_EINVAL;
+    if (q->dense_rows != 0 && q->dense_rows != 1) return QNN_EINVAL;
     const int lim = 1 << 12;                               // keeps every coordinate sum and product inside int32
     if (q->kh > lim || q->kw > lim || q->stride_h > lim || q->stride_w > lim || q->dil_h > lim || q->dil_w > lim ||
         q->pad_h > lim || q->pad_w > lim)
@@ -534,6 +535,9 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     const Emit e = (out_bits != 0) ? Emit{out_planes, out_bits, workspace, workspace_bytes} : kNoEmit;
     st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, (int)taps, acc, scale, out_f32, e);
     if (st != QNN_OK || rows == 0 || Cout == 0) return st;
+    // row-dense input exists for the packed-window path only
+    if (q->dense_rows && (q->transposed || C > 32 || taps < 2 || wb > 4 || window_words(taps * C) == 0))
+        return QNN_EUNSUPPORTED;
     // A single tap at stride 1 without padding reads pixel r for output pixel r: the product of the
     // [pixels][C] matrix with the [Cout][C] weights, whichever way the transposed flag is set.
     if (taps == 1 && q->stride_h == 1 && q->stride_w == 1 && q->pad_h == 0 && q->pad_w == 0)
@@ -568,8 +572,8 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
         const size_t need = window_workspace_bytes(rows, ab, kwp);
         if (workspace != nullptr && aligned16(workspace) && workspace_bytes >= need && need < ((size_t)1 << 32)) {
             uint32_t *win = static_cast<uint32_t *>(workspace);
-            st = from_hip(launch_window_pack(x_planes, rows, g.geo, (int)H, (int)W, (int)C, ab, kwp, win,
-                                             (hipStream_t)stream));
+            st = from_hip(launch_window_pack(x_planes, rows, g.geo, (int)H, (int)W, (int)C, ab, kwp,
+                                             q->dense_rows != 0, win, (hipStream_t)stream));
             if (st != QNN_OK) return st;
             g.A = win;
             g.Cw = kwp;
@@ -584,6 +588,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
             return from_hip(k_conv_window[ab - 1](g, wb, (hipStream_t)stream));
         }
     }
+    if (q->dense_rows) return (kwp > 0) ? QNN_EWORKSPACE : QNN_EUNSUPPORTED;   // only the window path reads row-dense input
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the
     // wavefront's weight words, which has to be spread over enough pixels (measured optimum 14-16
     // on layers of 25 k to 100 k pixels)

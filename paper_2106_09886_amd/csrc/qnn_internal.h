@@ -152,7 +152,7 @@ hipError_t launch_conv_window_ab6(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_window_ab7(const BranchArgs &, int, hipStream_t);
 hipError_t launch_conv_window_ab8(const BranchArgs &, int, hipStream_t);
 hipError_t launch_window_pack(const uint32_t *planes, int64_t out_pixels, const ConvGeom &q, int H, int W, int C,
-                              int ab, int kwp, uint32_t *out, hipStream_t);
+                              int ab, int kwp, bool dense_rows, uint32_t *out, hipStream_t s);
 // words per plane of a packed window of `bits` = KH*KW*C bits (the instantiated sizes), 0 if none fits
 inline int window_words(int64_t bits) {
     return bits <= 32 ? 1 : bits <= 64 ? 2 : bits <= 96 ? 3 : bits <= 160 ? 5 : bits <= 256 ? 8 : 0;

@@ -208,6 +208,17 @@ def test_general_conv_geometry_and_argument_errors(L):
     assert f(P, 2, P, 2, 1, 8, 8, 64, 64, gp, P, None, None, 9, P, None, 0, None) == QNN_EINVAL
     assert f(P, 2, P, 2, 1, 8, 8, 64, 64, gp, None, None, None, 4, P, P, 16 * 64 * 4 - 1, None) == QNN_EWORKSPACE
     assert f(P, 2, P, 2, 0, 8, 8, 64, 64, gp, None, None, None, 0, None, None, 0, None) == QNN_OK
+    # row-dense input: a flag of 0 or 1, and only where the packed-window path applies, with its workspace
+    bad = conv_geometry(3, 3, pad=1)
+    bad.dense_rows = 2
+    assert f(P, 2, P, 2, 1, 8, 8, 3, 64, ctypes.byref(bad), P, None, None, 0, None, None, 0, None) == QNN_EINVAL
+    dense = conv_geometry(3, 3, pad=1, dense_rows=True)
+    dp = ctypes.byref(dense)
+    assert f(P, 2, P, 2, 1, 8, 8, 64, 64, dp, P, None, None, 0, None, P, 1 << 20, None) == QNN_EUNSUPPORTED   # 64 channels
+    assert f(P, 2, P, 5, 1, 8, 8, 3, 64, dp, P, None, None, 0, None, P, 1 << 20, None) == QNN_EUNSUPPORTED    # 5 weight bits
+    assert f(P, 2, P, 2, 1, 8, 8, 3, 64, dp, P, None, None, 0, None, None, 0, None) == QNN_EWORKSPACE
+    one = conv_geometry(1, 1, dense_rows=True)
+    assert f(P, 2, P, 2, 1, 8, 8, 3, 64, ctypes.byref(one), P, None, None, 0, None, P, 1 << 20, None) == QNN_EUNSUPPORTED
 
 
 def test_encode_real_argument_errors(L):

@@ -19,7 +19,7 @@ def q():
 
 
 def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dilation=1, transposed=False,
-             output_padding=0, out_bits=0, seed=0, workspace=True):
+             output_padding=0, out_bits=0, seed=0, workspace=True, dense_rows=False):
     rng = np.random.default_rng(seed + Nb * 7 + H * 5 + C * 3 + Cout + KH * 11 + KW)
     X = rand_codes(rng, (Nb, H, W, C), ab)
     Wt = rand_codes(rng, (Cout, KH, KW, C), wb)
@@ -30,8 +30,9 @@ def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dila
     rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2))) + 1.0
     s = (rng.uniform(0.5, 1.5, Cout) * ((1 << max(out_bits, 2)) / rms)).astype(np.float32)
     geo = q.conv_geometry(KH, KW, stride=stride, pad=pad, dilation=dilation, transposed=transposed,
-                          output_padding=output_padding)
-    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+                          output_padding=output_padding, dense_rows=dense_rows)
+    # row-dense: one packed row per image row (bit w*C + c), else one per pixel
+    Xp = q.encode_pack(dev(X.reshape(Nb * H, W * C) if dense_rows else X.reshape(Nb * H * W, C)), ab)
     Wp = q.encode_pack(dev(Wt.reshape(Cout * KH * KW, C)), wb)
     acc, y, planes = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=dev(s), out_bits=out_bits,
                                       workspace=workspace)
@@ -128,6 +129,7 @@ def test_conv2d_few_channels(q, oracle, case, workspace):
 # configuration the library picks for them; the oracle computes the whole layer
 FULL_SIZE_CASES = [
     dict(Nb=32, H=224, W=224, C=3, Cout=64, ab=8, wb=2, KH=7, KW=7, stride=2, pad=3),
+    dict(Nb=32, H=224, W=224, C=3, Cout=64, ab=8, wb=2, KH=7, KW=7, stride=2, pad=3, dense_rows=True),
     dict(Nb=32, H=56, W=56, C=128, Cout=128, ab=2, wb=2, KH=3, KW=3, stride=2, pad=1),
     dict(Nb=32, H=56, W=56, C=256, Cout=512, ab=2, wb=2, KH=1, KW=1, stride=2),
     dict(Nb=32, H=56, W=56, C=256, Cout=64, ab=2, wb=2, KH=1, KW=1),
@@ -137,11 +139,36 @@ FULL_SIZE_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", FULL_SIZE_CASES, ids=lambda c: "full-%dx%d-C%d-k%d-s%s%s" % (
-    c["H"], c["W"], c["C"], c["KH"], c.get("stride", 1), "-T" if c.get("transposed") else ""))
+@pytest.mark.parametrize("case", FULL_SIZE_CASES, ids=lambda c: "full-%dx%d-C%d-k%d-s%s%s%s" % (
+    c["H"], c["W"], c["C"], c["KH"], c.get("stride", 1), "-T" if c.get("transposed") else "",
+    "-dense" if c.get("dense_rows") else ""))
 def test_conv2d_general_full_size(q, oracle, case):
     say("conv2d_general full size", case)
     run_case(q, oracle, **case)
+
+
+@pytest.mark.parametrize("case", WINDOW_CASES + [
+    dict(Nb=2, H=9, W=13, C=3, Cout=64, ab=8, wb=2, KH=7, KW=7, stride=2, pad=3, dilation=(1, 2)),   # dilated along w: tap by tap
+    dict(Nb=1, H=5, W=40, C=5, Cout=33, ab=2, wb=2, KH=2, KW=9, pad=(0, 4)),                          # 45 bits per kernel row: two groups
+    dict(Nb=2, H=4, W=3, C=32, Cout=64, ab=1, wb=1, KH=2, KW=3, pad=1),                                # whole words per tap
+], ids=lambda c: "dense-C%d-k%dx%d-ab%d-wb%d" % (c["C"], c["KH"], c["KW"], c["ab"], c["wb"]))
+def test_conv2d_few_channels_dense_rows(q, oracle, case):
+    """The packed-window path fed from row-dense planes (one packed row per image row)."""
+    say("conv2d few channels, dense rows", case)
+    run_case(q, oracle, dense_rows=True, **case)
+    run_case(q, oracle, dense_rows=True, out_bits=4, seed=7, **case)
+
+
+def test_conv2d_dense_rows_rejected_elsewhere(q):
+    """Row-dense input is refused where the packed-window path does not apply, or without its workspace."""
+    import torch
+    x = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    w = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    for kwargs, C, workspace in ((dict(kh=3, kw=3, pad=1), 64, True), (dict(kh=1, kw=1), 3, True),
+                                 (dict(kh=3, kw=3, pad=1, transposed=True), 3, True), (dict(kh=3, kw=3, pad=1), 3, False)):
+        geo = q.conv_geometry(kwargs.pop("kh"), kwargs.pop("kw"), dense_rows=True, **kwargs)
+        with pytest.raises(q.QnnError):
+            q.conv2d_general(x, 2, w, 2, 1, 4, 4, C, 8, geo, workspace=workspace)
 
 
 @pytest.mark.parametrize("out_bits", [1, 2, 4, 8])
