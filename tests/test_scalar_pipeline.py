@@ -1,0 +1,70 @@
+"""The static checker of the hand-issued scalar loads (csrc/check_scalar_pipeline.py): first the
+checker itself on tiny hand-written assembly (a planted violation must be found, on a straight
+path and around a loop), then one real compilation of the branch kernels."""
+import os
+import shutil
+import sys
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, os.path.join(ROOT, "paper_2106_09886_amd", "csrc"))
+import check_scalar_pipeline as chk  # noqa: E402
+
+
+def kernel(body):
+    lines = ["_ZN3qnn4test_kernelEv:"] + body + ["\ts_endpgm", ".Lfunc_end0:"]
+    name = lines[0][:-1]
+    return chk.check_kernel(name, list(enumerate(lines[1:], 2)))[0]
+
+
+ASM_LOAD = [";;#ASMSTART", "\ts_load_dwordx4 s[8:11], s[0:1], s2 offset:0", ";;#ASMEND"]
+ASM_WAIT = [";;#ASMSTART", "\ts_waitcnt lgkmcnt(0)", ";;#ASMEND"]
+
+
+def test_checker_accepts_a_use_after_the_wait():
+    assert kernel(ASM_LOAD + ["\tv_mov_b32_e32 v1, s3"] + ASM_WAIT + ["\tv_xor_b32_e32 v0, s8, v1"]) == []
+
+
+def test_checker_flags_a_use_before_the_wait():
+    p = kernel(ASM_LOAD + ["\tv_xor_b32_e32 v0, s9, v1"] + ASM_WAIT)
+    assert len(p) == 1 and "[9]" in p[0] and "v_xor_b32_e32" in p[0]
+
+
+def test_checker_flags_a_spill_of_a_register_in_flight():
+    p = kernel(ASM_LOAD + ["\tv_writelane_b32 v40, s10, 3"] + ASM_WAIT)
+    assert len(p) == 1 and "v_writelane_b32" in p[0]
+
+
+def test_checker_follows_the_back_edge_of_a_loop():
+    # the load at the bottom of the loop body is still in flight at its top on the second trip
+    body = [".LBB0_1:", "\tv_xor_b32_e32 v0, s8, v1"] + ASM_LOAD + ["\ts_cmp_lg_u32 s4, 0", "\ts_cbranch_scc1 .LBB0_1"] + ASM_WAIT
+    p = kernel(body)
+    assert len(p) == 1 and "v_xor_b32_e32" in p[0]
+    # with the wait at the top of the body the same loop is clean
+    body = [".LBB0_1:"] + ASM_WAIT + ["\tv_xor_b32_e32 v0, s8, v1"] + ASM_LOAD + ["\ts_cmp_lg_u32 s4, 0", "\ts_cbranch_scc1 .LBB0_1"] + ASM_WAIT
+    assert kernel(body) == []
+
+
+def test_checker_ignores_compiler_issued_loads():
+    # a load outside an asm block is tracked by the compiler's own waits
+    assert kernel(["\ts_load_dwordx2 s[8:9], s[0:1], 0x0", "\ts_waitcnt lgkmcnt(0)", "\tv_mov_b32_e32 v0, s8"]) == []
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.skipif(shutil.which(chk.HIPCC) is None and not os.path.exists(chk.HIPCC), reason="hipcc not available")
+def test_branch_kernels_of_one_activation_width_are_clean():
+    """Compiles the 3x3 / GEMM kernels for 2-bit activations (every weight width, every chunk
+    shape: about 130 kernels) and the small-channel kernels to assembly and checks them."""
+    tmp = tempfile.mkdtemp(prefix="qnn_asm_test_")
+    try:
+        total = 0
+        for src in chk.SOURCES:
+            out = chk.compile_asm((src, 2, os.path.join(tmp, src.split(".")[0] + ".s")))
+            nk, problems, _ = chk.check_file(out)
+            assert problems == [], problems[:5]
+            total += nk
+        assert total >= 100
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
