@@ -193,8 +193,15 @@ __device__ __forceinline__ void gemm_chunk_full(const BranchArgs &g, int nload, 
         c.off_cur = c.off_nxt;
         ++r;
     };
-    static_assert((SEGS & 1) == 0, "even stage count: stage 0 of every row uses the same buffer");
-    while (r < r1) one_row(std::integral_constant<bool, false>());
+    if constexpr ((SEGS & 1) == 0) {                   // stage 0 of every row uses the same buffer
+        while (r < r1) one_row(std::integral_constant<bool, false>());
+    } else {                                           // the starting buffer alternates from row to row
+        while (r + 2 <= r1) {
+            one_row(std::integral_constant<bool, false>());
+            one_row(std::integral_constant<bool, true>());
+        }
+        if (r < r1) one_row(std::integral_constant<bool, false>());
+    }
     // Drain the prefetch issued by the last row.  Both buffers are named so that their
     // registers stay reserved until the wait, whichever of them the prefetch went to.
     c.bufA.template arrive<true>();
@@ -782,7 +789,9 @@ void launch_gemm_plain(const BranchArgs &g, bool emit, hipStream_t s) {
 
 template <int AB, int WB, int KC>
 void launch_gemm_short(const BranchArgs &g, bool emit, hipStream_t s) {
-    constexpr int CWT = imin(pow2_floor(16 / AB), KC / 2);
+    // one stage per row where the row's words fit a stage (16 SGPRs): a stage of 2*AB*WB*KC vector
+    // instructions covers a scalar load better than two of half the length
+    constexpr int CWT = imin(pow2_floor(16 / AB), KC);
     constexpr int SEGS = KC / CWT;
     launch_gemm_plain<AB, WB, SEGS, CWT>(g, emit, s);
 }
