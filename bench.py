@@ -190,6 +190,9 @@ def main():
                              "vgg16_stack_fused", "hbm_kernels", "conv_geometries"])
     ap.add_argument("--bits", type=int, default=None,
                     help="gemm8192 only: activation = weight bit width (1..6 in the paper's sweep; default 2)")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="resnet18_s1 / resnet50_s3 only: run the same layer on this many images instead of the "
+                         "configuration's batch (a side measurement: how much of a launch is fixed cost)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="additionally capture one step into a HIP graph and report the time per replay "
@@ -320,6 +323,11 @@ def main():
         if name == "gemm8192" and args.bits is not None:
             w = inputs.with_bits(w, args.bits)
         is_conv = hasattr(w, "Cout")
+        if args.batch is not None:
+            if not is_conv or args.batch < 1:
+                print("bench.py: --batch applies to the convolution workloads", file=sys.stderr)
+                return 2
+            w = w._replace(Nb=args.batch, name="%s_batch%d" % (w.name, args.batch))
         if is_conv:
             X, Wt, s = inputs.make_conv(w)
             rows, N, K, Kw = w.Nb * w.H * w.W, w.Cout, 9 * w.C, 9 * ((w.C + 31) // 32)
@@ -507,7 +515,7 @@ def main():
             "unit": "Tlane-op/s",
             "peak_from": "256 CU x 64 lanes x 2.4 GHz, one 32-bit integer vector op per lane and clock",
             "frac": round(achieved / PEAK_LANE_OPS, 4),
-            "traffic": MEASURED_TRAFFIC.get(name),
+            "traffic": MEASURED_TRAFFIC.get(name) if args.batch is None else None,
         },
     }
 
