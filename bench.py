@@ -8,7 +8,7 @@ The weights are static parameters and are packed once before the timed region.
 
 Default workload: `resnet18_s1`, the ResNet-18-stage-1-shaped W2A2 3x3 convolution the target
 is quoted on.  Other workloads (`--workload`): `resnet50_s3`, `fc4096`, `gemm64`, `gemm8192`
-(`--bits b`, with the int8 matrix-core comparison line), `vgg16_stack` (13 chained layers: conv +
+(`--bits b`, with the two comparison lines: int8 matrix cores and packed int8 dot product), `vgg16_stack` (13 chained layers: conv +
 scale, then max-pool / re-encode / pack per layer), `vgg16_stack_fused` (the same through the
 fused kernels), and two side suites that print their own tables: `hbm_kernels` (the
 memory-bound kernels at chip-filling sizes) and `conv_geometries` (`qnn_conv2d_general`).
@@ -16,6 +16,11 @@ memory-bound kernels at chip-filling sizes) and `conv_geometries` (`qnn_conv2d_g
 Prints ONE JSON line.  `value` is the effective quantized throughput 2*M*N*K / t_step in
 GOPS.  `roofline` prices the dominant kernel (the branch kernel) against the chip's integer
 vector-ALU rate; `cpu_baseline` is the CPU oracle timed on the host cores of this machine.
+
+Before the W warm-up steps the device is kept busy with the same step for a quarter of a
+second, untimed, so that its clocks have settled.  Extras: `--wave-trace` (one traced launch:
+wavefronts per SIMD, active windows, shader clock), `--batch N` (the convolution workloads on
+another number of images: fixed cost of a launch), `--graph`, `--copy-calibration`.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 """
