@@ -256,6 +256,12 @@ def main():
         Nb, H, W, C = X0.shape
         x0 = torch.from_numpy(X0).to(dev)
         plan, ops, lane_ops, keep = [], 0.0, 0.0, []
+
+        def kwords(c):
+            """32-bit words per plane of one output pixel's K axis: nine per-tap runs, or the single
+            word of the few-channel first layer (9 * c <= 32 bits)."""
+            return 1 if 9 * c <= 32 else 9 * ((c + 31) // 32)
+
         h, wd, c = H, W, C
         planes_in = torch.empty((Nb * h * wd, w.ab_first, 1), dtype=torch.int32, device=dev)
         first_planes = planes_in
@@ -275,7 +281,7 @@ def main():
                          p(planes_out), p(planes_mid), acc.numel() * 4))
             keep.append((Wp, sd, acc, out, planes_in, planes_out, planes_mid))
             ops += 2.0 * Nb * h * wd * cout * 9 * c
-            lane_ops += 2.0 * ab * w.wb * Nb * h * wd * cout * 9 * ((c + 31) // 32)
+            lane_ops += 2.0 * ab * w.wb * Nb * h * wd * cout * kwords(c)
             planes_in, h, wd, c = planes_out, ho, wo, cout
         pX, pF = p(x0), p(first_planes)
 
@@ -291,8 +297,10 @@ def main():
             ws1 = torch.empty(ws1_bytes, dtype=torch.uint8, device=dev)
         pW1 = p(ws1)
 
-        def branch_fused():
-            for i, (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout, pmid, accb) in enumerate(plan):
+        def layer(i):
+            """Every launch of layer i (product, re-encoding, pooling)."""
+            ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout, pmid, accb = plan[i]
+            if fused:
                 if i == 0:
                     check(L.qnn_conv2d_im2col_requant(pX, 2, ab, pw, w.wb, Nb, h, wd, c, cout, ps, w.ab, pmid, None,
                                                       None, pW1, ws1_bytes, stream))
@@ -301,17 +309,28 @@ def main():
                                                       None, pa, accb, stream))
                 if pool:
                     check(L.qnn_maxpool2x2_planes(pmid, Nb, h, wd, cout, w.ab, pout, stream))
-
-        def branch():
-            if fused:
-                return branch_fused()
-            for i, (ab, pin, pw, h, wd, c, cout, pa, ps, po, pool, pout, _, _) in enumerate(plan):
+            else:
                 if i == 0:
                     check(L.qnn_conv2d_im2col(pX, 2, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, pF, ws_bytes,
                                               stream))
                 else:
                     check(L.qnn_conv2d_packed(pin, ab, pw, w.wb, Nb, h, wd, c, cout, pa, ps, po, stream))
                 check(L.qnn_requant_pack(po, Nb, h, wd, cout, pool, w.ab, None, pout, stream))
+
+        def branch():
+            for i in range(len(plan)):
+                layer(i)
+
+        def per_layer_table():
+            """Each layer on its own, K back-to-back repetitions (inputs are whatever the last full
+            pass left in the buffers: the kernels' cost does not depend on the data)."""
+            rows_ = []
+            for i, (ab, _, _, h, wd, c, cout, *_rest) in enumerate(plan):
+                us = timed(torch, lambda i=i: layer(i), steps)
+                lo = 2.0 * ab * w.wb * Nb * h * wd * cout * kwords(c)
+                rows_.append({"layer": i + 1, "shape": "%dx%dx%d -> %d" % (h, wd, c, cout), "us": round(us, 1),
+                              "frac_of_lane_op_peak": round(lo / (us * 1e-6) / PEAK_LANE_OPS, 3)})
+            return rows_
 
         desc = ("vgg16_stack: 13 chained 3x3 conv layers, batch %d, %dx%dx%d input, W%dA%d (first layer A%d), "
                 "2x2 max-pool after each block, re-encode + pack between layers"
@@ -461,6 +480,7 @@ def main():
                            "us": round(dot_us, 2), "GOPS": round(ops / (dot_us * 1e-6) / 1e9, 1)}
         branch()                                  # leave the branch result in the output buffer
 
+    layers_table = per_layer_table() if name == "vgg16_stack" else None
     wave_trace = None
     if args.wave_trace and name != "vgg16_stack":
         wave_trace = traced_launch(torch, np, q, branch)
@@ -511,6 +531,7 @@ def main():
             "comparison_int8_dot4": compare_dot,
             "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
             "wave_trace": wave_trace,
+            "layers": layers_table,
         },
         "roofline": {
             "bound": "alu",

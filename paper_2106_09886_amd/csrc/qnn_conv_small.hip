@@ -107,20 +107,20 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
         if (oh == g.H - 1) m &= ~rowmask[2];
         if (ow == 0) m &= ~colmask[0];
         if (ow == g.W - 1) m &= ~colmask[2];
-        int part[AB + WB - 1];
-#pragma unroll
-        for (int s = 0; s < AB + WB - 1; ++s) part[s] = 0;
-        if (m == full) {
+        int part[AB + WB - 1];                             // part[s]: branches with p + q = s
+        auto add_branches = [&](auto masked) {
 #pragma unroll
             for (int q = 0; q < WB; ++q)
 #pragma unroll
-                for (int p = 0; p < AB; ++p) popc_acc(part[p + q], cur.get(p) ^ wq[q]);
-        } else {
-#pragma unroll
-            for (int q = 0; q < WB; ++q)
-#pragma unroll
-                for (int p = 0; p < AB; ++p) popc_acc(part[p + q], (cur.get(p) ^ wq[q]) & m);
-        }
+                for (int p = 0; p < AB; ++p) {
+                    uint32_t x = cur.get(p) ^ wq[q];
+                    if constexpr (decltype(masked)::value) x &= m;
+                    if (q == 0 || p == AB - 1) popc_set(part[p + q], x);   // first branch of its sum
+                    else popc_acc(part[p + q], x);
+                }
+        };
+        if (m == full) add_branches(std::false_type());
+        else add_branches(std::true_type());
         int sum = part[AB + WB - 2];
 #pragma unroll
         for (int i = AB + WB - 3; i >= 0; --i) sum = (sum << 1) + part[i];
