@@ -148,7 +148,8 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
                  ("3x3 stride 2, 128->128, 56^2, W2A2", 32, 56, 56, 128, 128, 2, 2, 3, 3, 2, 1, 1, False),
                  ("1x1 stride 2, 256->512, 56^2, W2A2", 32, 56, 56, 256, 512, 2, 2, 1, 1, 2, 0, 1, False),
                  ("1x1 stride 1, 256->64, 56^2, W2A2", 32, 56, 56, 256, 64, 2, 2, 1, 1, 1, 0, 1, False),
-                 ("3x3 stride 1, 64->64, 56^2, W2A2 (general kernel on the headline shape)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
+                 ("3x3 stride 1, 64->64, 56^2, W2A2 (general kernel kept on the headline shape)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
+                 ("3x3 stride 1, 64->64, 56^2, W2A2 (as called: handed to the 3x3 kernel)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
                  ("3x3 dilation 2, 256->256, 33^2, W3A4", 16, 33, 33, 256, 256, 4, 3, 3, 3, 1, 2, 2, False),
                  ("4x4 stride 2 transposed, 256->128, 28^2, W2A2", 16, 28, 28, 256, 128, 2, 2, 4, 4, 2, 1, 1, True)]
         cases.insert(1, ("ResNet stem 7x7 stride 2, 3->64, 224^2, W2A8, row-dense input", 32, 224, 224, 3, 64, 8, 2,
@@ -169,7 +170,9 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
             sd = torch.rand(Cout, device=dev)
             geo = q.conv_geometry(KH, KW, stride=st, pad=pd, dilation=dl, transposed=tr, dense_rows=dense)
             Ho, Wo = q.conv2d_general_output_size(H, W, geo)
+            q.tune(general_only=1 if "general kernel kept" in label else 0)
             t = avg_us(lambda: q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=sd))
+            q.tune(general_only=0)
             taps = KH * KW / (st * st if tr else 1)
             ops = 2.0 * Nb * Ho * Wo * Cout * taps * C
             rows.append({"layer": label, "out": "%dx%d" % (Ho, Wo), "us": round(t, 1), "effective_GOPS": round(ops / t / 1e3, 1),

@@ -56,6 +56,9 @@ int qnn_version(void);
  */
 #define QNN_TUNE_WAVES_PER_SIMD 1 /* resident wavefronts per SIMD the launch sizing aims for */
 #define QNN_TUNE_ROWS_PER_WAVE 2  /* rows (GEMM rows / output pixels) per wavefront        */
+#define QNN_TUNE_GENERAL_ONLY 3   /* nonzero: qnn_conv2d_general keeps a 3x3 stride-1 pad-1  */
+                                  /* window in its own kernel instead of handing it to the   */
+                                  /* kernel behind qnn_conv2d_packed (for comparisons)       */
 int qnn_tune(int key, int value);
 
 /*
@@ -238,7 +241,9 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  * size for C = 3, and a kernel row of the window is a run of KW*C consecutive bits.  Accepted
  * only where the packed-window path applies (forward convolution, C <= 32, kh*kw*C <= 256,
  * wb <= 4) and with its workspace; QNN_EUNSUPPORTED otherwise.
- * The 3x3 / stride 1 / pad 1 case is served faster by qnn_conv2d_packed.  A 1x1 convolution
+ * The 3x3 / stride 1 / pad 1 / dilation 1 convolution with more than 32 channels, or without
+ * the window workspace, runs on the kernel of qnn_conv2d_packed (same operands, same outputs;
+ * QNN_TUNE_GENERAL_ONLY keeps it here).  A 1x1 convolution
  * without padding runs on the kernels of qnn_branch_gemm (rows = output pixels; with a stride and
  * bit widths up to 4 the rows are the strided selection of the input pixels).
  */

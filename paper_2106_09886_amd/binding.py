@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libqnn.so")
 
 QNN_OK, QNN_EINVAL, QNN_EALIGN, QNN_EUNSUPPORTED, QNN_EWORKSPACE, QNN_EHIP = range(6)
 QNN_PACK_VALIDATE = 1
-QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE = 1, 2
+QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE, QNN_TUNE_GENERAL_ONLY = 1, 2, 3
 
 EXPORTS = (
     "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_set_wave_trace",
@@ -149,7 +149,9 @@ def _dev(t, dtype, name):
     return t
 
 
-def tune(waves_per_simd=None, rows_per_wave=None):
+def tune(waves_per_simd=None, rows_per_wave=None, general_only=None):
+    if general_only is not None:
+        _check(lib().qnn_tune(QNN_TUNE_GENERAL_ONLY, int(general_only)), "qnn_tune")
     if waves_per_simd is not None:
         _check(lib().qnn_tune(QNN_TUNE_WAVES_PER_SIMD, int(waves_per_simd)), "qnn_tune")
     if rows_per_wave is not None:

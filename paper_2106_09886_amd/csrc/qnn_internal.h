@@ -51,6 +51,7 @@ struct Tuning {
     int rows_per_wave;    // > 0 overrides the automatic choice
     uint64_t *trace;      // device buffer for per-wavefront trace records, or nullptr
     uint32_t trace_waves;
+    int general_only;     // qnn_conv2d_general hands no 3x3 stride-1 pad-1 window to the 3x3 kernel
 };
 Tuning &tuning();
 

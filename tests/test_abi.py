@@ -250,6 +250,7 @@ def test_tune_rejects_unknown_keys(L):
     from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_OK
     assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK
     assert L.qnn_tune(2, 0) == QNN_OK
+    assert L.qnn_tune(3, 1) == QNN_OK and L.qnn_tune(3, 0) == QNN_OK
     assert L.qnn_tune(99, 1) == QNN_EINVAL
     assert L.qnn_tune(1, -1) == QNN_EINVAL
 

@@ -34,18 +34,28 @@ def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dila
     # row-dense: one packed row per image row (bit w*C + c), else one per pixel
     Xp = q.encode_pack(dev(X.reshape(Nb * H, W * C) if dense_rows else X.reshape(Nb * H * W, C)), ab)
     Wp = q.encode_pack(dev(Wt.reshape(Cout * KH * KW, C)), wb)
-    acc, y, planes = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=dev(s), out_bits=out_bits,
-                                      workspace=workspace)
-    assert tuple(acc.shape) == want.shape
-    assert (host(acc).astype(np.int64) == want).all()
     y_want = oracle.scale_f32(want, s)
-    assert (host(y) == y_want).all()
     y64 = oracle.scale_f64(want, s)
-    assert (np.abs(host(y).astype(np.float64) - y64) <= 1e-6 * np.abs(y64)).all()
-    if out_bits:
-        codes = oracle.requant(y_want, out_bits)
-        pw, bad = oracle.pack_planes(codes.reshape(-1, Cout), out_bits)
-        assert bad == 0 and (planes_u32(planes) == pw).all()
+    # a 3x3 window at stride 1, padding 1 goes to the dedicated 3x3 kernel unless told otherwise:
+    # such a case runs both ways
+    pair = lambda v: tuple(v) if isinstance(v, (tuple, list)) else (v, v)
+    handed_over = (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) == (1, 1)
+                   and pair(pad) == (1, 1) and pair(dilation) == (1, 1))
+    for general_only in ((1, 0) if handed_over else (0,)):
+        q.tune(general_only=general_only)
+        try:
+            acc, y, planes = q.conv2d_general(Xp, ab, Wp, wb, Nb, H, W, C, Cout, geo, scale=dev(s),
+                                              out_bits=out_bits, workspace=workspace)
+        finally:
+            q.tune(general_only=0)
+        assert tuple(acc.shape) == want.shape
+        assert (host(acc).astype(np.int64) == want).all()
+        assert (host(y) == y_want).all()
+        assert (np.abs(host(y).astype(np.float64) - y64) <= 1e-6 * np.abs(y64)).all()
+        if out_bits:
+            codes = oracle.requant(y_want, out_bits)
+            pw, bad = oracle.pack_planes(codes.reshape(-1, Cout), out_bits)
+            assert bad == 0 and (planes_u32(planes) == pw).all()
     return want
 
 
