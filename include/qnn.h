@@ -59,6 +59,8 @@ int qnn_version(void);
 #define QNN_TUNE_GENERAL_ONLY 3   /* nonzero: qnn_conv2d_general keeps a 3x3 stride-1 pad-1  */
                                   /* window in its own kernel instead of handing it to the   */
                                   /* kernel behind qnn_conv2d_packed (for comparisons)       */
+#define QNN_TUNE_BLOCK_ORDER 4    /* convolution kernels: 1 plain block numbers, 2 one         */
+                                  /* contiguous range of blocks (of pixels) per XCD            */
 int qnn_tune(int key, int value);
 
 /*

@@ -43,9 +43,11 @@ struct WavePos {
     int rb;        // row block
     int index;     // wavefront number in the grid
 };
-__device__ __forceinline__ WavePos wave_pos(int col_tiles) {
+template <bool XCD_RANGES = false>                   // number the blocks by xcd_block()
+__device__ __forceinline__ WavePos wave_pos(int col_tiles, int xcd_ranges = 0) {
     WavePos p;
-    p.index = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)));
+    const uint32_t block = XCD_RANGES ? xcd_block(xcd_ranges) : blockIdx.x;
+    p.index = __builtin_amdgcn_readfirstlane((int)(block * (blockDim.x >> 6) + (threadIdx.x >> 6)));
     p.ct = p.index % col_tiles;
     p.rb = p.index / col_tiles;
     return p;
@@ -707,7 +709,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const WavePos wp = wave_pos(g.col_tiles);
+    const WavePos wp = wave_pos<true>(g.col_tiles, g.xcd_ranges);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
     const int r0 = active ? wp.rb * g.rows_per_wave : 0;

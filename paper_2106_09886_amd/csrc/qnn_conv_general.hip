@@ -369,7 +369,9 @@ __device__ __forceinline__ void transposed_phases(const BranchArgs &g, uniform_w
 template <int AB, int WB, int CWT, int TT, int LG, bool TR, bool EMIT>
 __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    // forward: blocks numbered per XCD; the transposed launch is two-dimensional and keeps blockIdx
+    const uint32_t block = TR ? blockIdx.x : xcd_block(g.xcd_ranges);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(block * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
     const int lane = (int)(threadIdx.x & 63);
@@ -512,7 +514,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
 template <int AB, int WB, int KWP, bool EMIT>
 __global__ __launch_bounds__(256) void conv_window_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges) * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
     if ((int64_t)rb * g.rows_per_wave >= g.rows) return;

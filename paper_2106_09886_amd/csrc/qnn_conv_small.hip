@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void im2col_pack_kernel(const CodeT *__restric
 template <int AB, int WB, bool EMIT>
 __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges) * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
     const bool active = (int64_t)rb * g.rows_per_wave < g.rows;

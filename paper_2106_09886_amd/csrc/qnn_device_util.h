@@ -184,6 +184,22 @@ __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bo
 }
 
 // ---------------------------------------------------------------------------------------
+// Block numbering for the convolution kernels.  The blocks of a launch are handed to the chip's
+// eight XCDs in turn (block b runs on XCD b % 8), and every XCD has an L2 of its own.  With the
+// plain numbering each XCD works on pixels from all over the batch and its L2 fetches the whole
+// set of activation planes; numbered as below, XCD x works on one contiguous part of the blocks,
+// i.e. of the pixels, and fetches that part only.  With q = gridDim.x / 8 and r = gridDim.x % 8,
+// XCD x receives q + (x < r) blocks, and they are given the numbers x*q + min(x, r) + (b / 8):
+// consecutive ranges that tile [0, gridDim.x) exactly.  (1-D grids only.)
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t xcd_block(int on) {
+    const uint32_t nb = gridDim.x, b = blockIdx.x;
+    if (!on) return b;
+    const uint32_t q = nb >> 3, r = nb & 7u, x = b & 7u;
+    return x * q + (x < r ? x : r) + (b >> 3);
+}
+
+// ---------------------------------------------------------------------------------------
 // Scalar loads under manual control.
 //
 // Scalar loads return out of order, so the only wait a wavefront has is "all of them".  The

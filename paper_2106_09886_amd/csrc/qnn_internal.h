@@ -38,6 +38,7 @@ struct BranchArgs {
                           // rows_per_wave is the number of rows per BLOCK
     int gather_rows;      // GEMM only: row r is output pixel r of a single-tap strided convolution (geo, H, W);
                           // bit widths up to 4, not with split_k
+    int xcd_ranges;       // convolution kernels: number the blocks so that each XCD takes one contiguous range
     uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
     uint32_t trace_waves; // capacity of `trace` in wavefronts
     uint32_t *planes_out; // optional: the scaled result re-encoded with out_bits bits, as bit planes
@@ -52,6 +53,7 @@ struct Tuning {
     uint64_t *trace;      // device buffer for per-wavefront trace records, or nullptr
     uint32_t trace_waves;
     int general_only;     // qnn_conv2d_general hands no 3x3 stride-1 pad-1 window to the 3x3 kernel
+    int block_order;      // 0: automatic, 1: plain block numbers, 2: a contiguous range per XCD
 };
 Tuning &tuning();
 

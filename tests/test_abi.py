@@ -251,6 +251,8 @@ def test_tune_rejects_unknown_keys(L):
     assert L.qnn_tune(1, 4) == QNN_OK and L.qnn_tune(1, 0) == QNN_OK
     assert L.qnn_tune(2, 0) == QNN_OK
     assert L.qnn_tune(3, 1) == QNN_OK and L.qnn_tune(3, 0) == QNN_OK
+    assert L.qnn_tune(4, 2) == QNN_OK and L.qnn_tune(4, 1) == QNN_OK and L.qnn_tune(4, 0) == QNN_OK
+    assert L.qnn_tune(4, 3) == QNN_EINVAL
     assert L.qnn_tune(99, 1) == QNN_EINVAL
     assert L.qnn_tune(1, -1) == QNN_EINVAL
 

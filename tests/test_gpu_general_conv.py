@@ -281,6 +281,17 @@ def random_case(rng):
     return case
 
 
+@pytest.mark.parametrize("idx", [0, 1, 6, 13])
+def test_conv2d_general_plain_block_order(q, oracle, idx):
+    """These kernels number their blocks per XCD unless told otherwise; the plain numbering gives the same."""
+    say("plain block order", CASES[idx])
+    q.tune(block_order=1)
+    try:
+        run_case(q, oracle, **CASES[idx])
+    finally:
+        q.tune(block_order=0)
+
+
 def test_conv2d_general_random_geometries(q, oracle):
     """Seeded random geometries, channel counts and bit widths, with and without re-encoding."""
     rng = np.random.default_rng(20240607)

@@ -19,7 +19,7 @@ def q():
     from paper_2106_09886_amd import binding
     binding.lib()
     yield binding
-    binding.tune(waves_per_simd=0, rows_per_wave=0)
+    binding.tune(waves_per_simd=0, rows_per_wave=0, block_order=0)
 
 
 from gpu_util import dev, host, rand_codes, planes_u32, say  # noqa: E402
@@ -269,6 +269,23 @@ def test_conv_any_rows_per_wave(q, oracle, rpw):
         run_conv(q, oracle, rand_codes(rng, (3, 6, 7, 130), 2), rand_codes(rng, (64, 3, 3, 130), 2), 2, 2)
     finally:
         q.tune(rows_per_wave=0)
+
+
+@pytest.mark.parametrize("order", [1, 2])
+def test_conv_any_block_order(q, oracle, order):
+    """The numbering of the blocks (plain, or one contiguous range per XCD) is a performance knob
+    only: block counts below, at and above eight, and not divisible by eight."""
+    rng = np.random.default_rng(40 + order)
+    q.tune(block_order=order)
+    try:
+        for (Nb, H, W, C, Cout, rpw) in [(1, 3, 4, 64, 64, 0), (2, 9, 7, 64, 64, 4), (3, 11, 13, 40, 130, 3),
+                                         (2, 16, 16, 64, 300, 5), (2, 20, 22, 3, 64, 7)]:
+            say("block order", order, Nb, H, W, C, Cout, rpw)
+            q.tune(rows_per_wave=rpw)
+            ab = 8 if C == 3 else 2
+            run_conv(q, oracle, rand_codes(rng, (Nb, H, W, C), ab), rand_codes(rng, (Cout, 3, 3, C), 2), ab, 2)
+    finally:
+        q.tune(rows_per_wave=0, block_order=0)
 
 
 def test_conv_borders_zero_padding(q, oracle):
