@@ -61,6 +61,8 @@ int qnn_version(void);
                                   /* kernel behind qnn_conv2d_packed (for comparisons)       */
 #define QNN_TUNE_BLOCK_ORDER 4    /* convolution kernels: 1 plain block numbers, 2 one         */
                                   /* contiguous range of blocks (of pixels) per XCD            */
+#define QNN_TUNE_LDS_PARTIALS 5   /* GEMM with several K chunks per wavefront: 1 partial sums   */
+                                  /* through the output buffer, 2 in LDS where possible        */
 int qnn_tune(int key, int value);
 
 /*

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libqnn.so")
 
 QNN_OK, QNN_EINVAL, QNN_EALIGN, QNN_EUNSUPPORTED, QNN_EWORKSPACE, QNN_EHIP = range(6)
 QNN_PACK_VALIDATE = 1
-QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE, QNN_TUNE_GENERAL_ONLY, QNN_TUNE_BLOCK_ORDER = 1, 2, 3, 4
+QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE, QNN_TUNE_GENERAL_ONLY, QNN_TUNE_BLOCK_ORDER, QNN_TUNE_LDS_PARTIALS = 1, 2, 3, 4, 5
 
 EXPORTS = (
     "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_set_wave_trace",
@@ -149,7 +149,9 @@ def _dev(t, dtype, name):
     return t
 
 
-def tune(waves_per_simd=None, rows_per_wave=None, general_only=None, block_order=None):
+def tune(waves_per_simd=None, rows_per_wave=None, general_only=None, block_order=None, lds_partials=None):
+    if lds_partials is not None:
+        _check(lib().qnn_tune(QNN_TUNE_LDS_PARTIALS, int(lds_partials)), "qnn_tune")
     if block_order is not None:
         _check(lib().qnn_tune(QNN_TUNE_BLOCK_ORDER, int(block_order)), "qnn_tune")
     if general_only is not None:

@@ -6,7 +6,7 @@
 namespace qnn {
 
 Tuning &tuning() {
-    static Tuning t = {0, 0, nullptr, 0, 0, 0};
+    static Tuning t = {0, 0, nullptr, 0, 0, 0, 0};
     return t;
 }
 
@@ -212,7 +212,8 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     g.planes_out = e.planes; g.out_bits = e.bits;
     g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = H; g.W = W; g.C = 0;
     g.gather_rows = (gather != nullptr) ? 1 : 0;
-    g.xcd_ranges = 0;
+    g.xcd_ranges = 0; g.grid_blocks = 0;
+    g.lds_partials = 0;
     if (gather != nullptr) g.geo = *gather;
     g.kconst = (int)(K * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((N + 63) / 64);
@@ -248,6 +249,19 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
         g.split_k = 1;
         g.rows_per_wave = (int)rows_per_block;
     }
+    // Several chunk passes per wavefront: keep the partial sums of its rows in LDS rather than
+    // sending them through the output buffer (at 8192^3 the partials of the resident wavefronts
+    // do not stay in the L2s, and the kernel moved 2 GB per launch for 0.3 GB of operands and result).
+    // Measured at 8192^3: 1 bit 1042 -> 949 us, 2 bits equal, 3 and 4 bits 1 % slower (fewer rows per
+    // wavefront, and their round trip is small against the products of a chunk), hence the limit
+    // of 256 vector instructions per row and chunk for the automatic choice.
+    const bool lds_auto = 2 * ab * wb * gemm_chunk_words(wb) <= 256;
+    if (!g.split_k && !g.gather_rows && chunks >= 2 && ab <= 4 && wb <= 4 &&
+        (tuning().lds_partials == 2 || (tuning().lds_partials == 0 && lds_auto)) &&
+        (tuning().rows_per_wave == 0 || tuning().rows_per_wave <= kLdsPartialRows)) {
+        g.lds_partials = 1;
+        if (g.rows_per_wave > kLdsPartialRows) g.rows_per_wave = kLdsPartialRows;
+    }
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -276,10 +290,11 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.gather_rows = 0; g.xcd_ranges = xcd_ranges_for(g.col_tiles >= 4);
+    g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0; g.xcd_ranges = xcd_ranges_for(g.col_tiles >= 4);
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles, conv_passes(ab, wb, g.Cw), conv_group(ab, wb, g.Cw)), Cout),
                                           Cout, e);
+    g.grid_blocks = wave_grid_blocks(g);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -318,10 +333,11 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
             g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
             g.col_tiles = (int)((Cout + 63) / 64);
-            g.split_k = 0; g.gather_rows = 0; g.xcd_ranges = xcd_ranges_for(false);
+            g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0; g.xcd_ranges = xcd_ranges_for(false);
             g.trace = nullptr; g.trace_waves = 0;
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
                                                   Cout, e);
+            g.grid_blocks = wave_grid_blocks(g);
             return from_hip(k_conv_small[ab - 1](g, wb, (hipStream_t)stream));
         }
         st = qnn_encode_pack(x_codes, code_bytes, rows, C, ab, planes, nullptr, 0, stream);
@@ -366,6 +382,10 @@ int qnn_tune(int key, int value) {
         case QNN_TUNE_WAVES_PER_SIMD: tuning().waves_per_simd = value; return QNN_OK;
         case QNN_TUNE_ROWS_PER_WAVE: tuning().rows_per_wave = value; return QNN_OK;
         case QNN_TUNE_GENERAL_ONLY: tuning().general_only = value; return QNN_OK;
+        case QNN_TUNE_LDS_PARTIALS:
+            if (value > 2) return QNN_EINVAL;
+            tuning().lds_partials = value;
+            return QNN_OK;
         case QNN_TUNE_BLOCK_ORDER:
             if (value > 2) return QNN_EINVAL;
             tuning().block_order = value;
@@ -575,7 +595,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.gather_rows = 0; g.xcd_ranges = xcd_ranges_for(true);
+    g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0; g.xcd_ranges = xcd_ranges_for(true);
     g.trace = nullptr; g.trace_waves = 0;
     g.geo.KH = q->kh; g.geo.KW = q->kw; g.geo.sh = q->stride_h; g.geo.sw = q->stride_w;
     g.geo.ph = q->pad_h; g.geo.pw = q->pad_w; g.geo.dh = q->dil_h; g.geo.dw = q->dil_w;
@@ -601,6 +621,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
             }
             if (rpw2 > rows) rpw2 = rows;
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw2, Cout), Cout, e);
+            g.grid_blocks = wave_grid_blocks(g);
             return from_hip(k_conv_window[ab - 1](g, wb, (hipStream_t)stream));
         }
     }
@@ -654,9 +675,11 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
         if (span > kInt31 || clamp_rows_for_emit(clamp_rows_per_wave((int)span, Cout), Cout, e) != (int)span)
             return QNN_EUNSUPPORTED;
         g.rows_per_wave = (int)rpw;
+        g.xcd_ranges = 0; g.grid_blocks = 0;          // two-dimensional launch: plain block numbers
         return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
     }
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw, Cout), Cout, e);
+    g.grid_blocks = wave_grid_blocks(g);
     return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
 }
 

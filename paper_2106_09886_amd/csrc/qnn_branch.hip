@@ -44,9 +44,9 @@ struct WavePos {
     int index;     // wavefront number in the grid
 };
 template <bool XCD_RANGES = false>                   // number the blocks by xcd_block()
-__device__ __forceinline__ WavePos wave_pos(int col_tiles, int xcd_ranges = 0) {
+__device__ __forceinline__ WavePos wave_pos(int col_tiles, int xcd_ranges = 0, uint32_t grid_blocks = 0) {
     WavePos p;
-    const uint32_t block = XCD_RANGES ? xcd_block(xcd_ranges) : blockIdx.x;
+    const uint32_t block = XCD_RANGES ? xcd_block(xcd_ranges, grid_blocks) : blockIdx.x;
     p.index = __builtin_amdgcn_readfirstlane((int)(block * (blockDim.x >> 6) + (threadIdx.x >> 6)));
     p.ct = p.index % col_tiles;
     p.rb = p.index / col_tiles;
@@ -255,9 +255,26 @@ __device__ __forceinline__ void gemm_chunk_tail(const BranchArgs &g, uniform_wor
     }
 }
 
-template <int AB, int WB, int SEGS, int CWT, bool EMIT, bool GATHER = false>
+// Partial sums between the chunk passes of a wavefront, kept on chip: kLdsPartialRows rows x 64
+// columns of int32 per wavefront (24 KB per block, six blocks per compute unit).  Every lane
+// reads only what it wrote itself, so no barrier is involved.
+template <bool ON> struct PartialSlab {
+    __device__ static __forceinline__ int *mine() { return nullptr; }
+};
+template <> struct PartialSlab<true> {
+    __device__ static __forceinline__ int *mine() {
+        __shared__ int slab[4 * kLdsPartialRows * 64];
+        return slab + (threadIdx.x >> 6) * (kLdsPartialRows * 64) + (threadIdx.x & 63);
+    }
+};
+
+// LDSP: the partial sums of rows_per_wave <= kLdsPartialRows rows stay in LDS between chunk
+// passes instead of passing through the output buffer.
+template <int AB, int WB, int SEGS, int CWT, bool EMIT, bool GATHER = false, bool LDSP = false>
 __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
+    static_assert(!(GATHER && LDSP), "not combined");
+    int *const slab = PartialSlab<LDSP>::mine();
     const WavePos wp = wave_pos(g.col_tiles);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
@@ -284,9 +301,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
         const bool last = (k0 + KC >= Kw);
         auto fetch = [&](int rel_row) -> int {
             if (first) return g.kconst;
-            return __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)rel_row * ov.row_bytes), 0);
+            if constexpr (LDSP) return slab[rel_row * 64];
+            else return __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)rel_row * ov.row_bytes), 0);
         };
         auto sink = [&](int rel_row, int v, int prev) {
+            if constexpr (LDSP) {
+                if (!last) {
+                    slab[rel_row * 64] = v + prev;
+                    return;
+                }
+            }
             finish_row<false>(ov, rel_row, v + prev, /*first=*/true, last);   // the earlier part is already added
         };
         if (k0 + KC <= Kw) gemm_chunk_full<AB, WB, SEGS, CWT, GATHER>(g, nload, r0, r1, k0, fetch, sink, walk);
@@ -709,7 +733,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const WavePos wp = wave_pos<true>(g.col_tiles, g.xcd_ranges);
+    const WavePos wp = wave_pos<true>(g.col_tiles, g.xcd_ranges, g.grid_blocks);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
     const int r0 = active ? wp.rb * g.rows_per_wave : 0;
@@ -785,6 +809,13 @@ void launch_gemm_plain(const BranchArgs &g, bool emit, hipStream_t s) {
             return;
         }
     }
+    if constexpr (AB <= 4 && WB <= 4) {
+        if (g.lds_partials) {
+            if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true, false, true>), grid_for(g), dim3(256), 0, s, g);
+            else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false, false, true>), grid_for(g), dim3(256), 0, s, g);
+            return;
+        }
+    }
     if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true>), grid_for(g), dim3(256), 0, s, g);
     else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false>), grid_for(g), dim3(256), 0, s, g);
 }
@@ -803,6 +834,8 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     using S = GemmShape<AB, WB>;
     const bool emit = g.planes_out != nullptr;
     if (g.gather_rows && (AB > 4 || WB > 4 || g.split_k)) return hipErrorInvalidValue;   // host bug
+    if (g.lds_partials && (AB > 4 || WB > 4 || g.split_k || g.gather_rows || g.rows_per_wave > kLdsPartialRows))
+        return hipErrorInvalidValue;                                                       // host bug
     if (g.split_k) {
         const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
         const dim3 grid((unsigned)(row_blocks * g.col_tiles));
@@ -884,6 +917,7 @@ hipError_t QNN_CAT(launch_gemm_ab, QNN_AB)(const BranchArgs &g, int wb, hipStrea
 }
 
 hipError_t QNN_CAT(launch_conv_ab, QNN_AB)(const BranchArgs &g, int wb, hipStream_t s) {
+    if (g.xcd_ranges && g.grid_blocks != grid_for(g).x) return hipErrorInvalidValue;   // host bug
     switch (wb) {
         case 1: return launch_conv_t<QNN_AB, 1>(g, s);
         case 2: return launch_conv_t<QNN_AB, 2>(g, s);

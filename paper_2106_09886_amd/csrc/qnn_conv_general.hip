@@ -370,7 +370,7 @@ template <int AB, int WB, int CWT, int TT, int LG, bool TR, bool EMIT>
 __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     // forward: blocks numbered per XCD; the transposed launch is two-dimensional and keeps blockIdx
-    const uint32_t block = TR ? blockIdx.x : xcd_block(g.xcd_ranges);
+    const uint32_t block = TR ? blockIdx.x : xcd_block(g.xcd_ranges, g.grid_blocks);
     const int wave = __builtin_amdgcn_readfirstlane((int)(block * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
@@ -514,7 +514,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
 template <int AB, int WB, int KWP, bool EMIT>
 __global__ __launch_bounds__(256) void conv_window_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges) * 4 + (threadIdx.x >> 6)));
+    const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges, g.grid_blocks) * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
     if ((int64_t)rb * g.rows_per_wave >= g.rows) return;
@@ -596,6 +596,7 @@ template <int AB, int WB>
 hipError_t launch_window_t(const BranchArgs &g, hipStream_t s) {
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
     const dim3 grid((unsigned)((row_blocks * g.col_tiles + 3) / 4));
+    if (g.xcd_ranges && g.grid_blocks != grid.x) return hipErrorInvalidValue;             // host bug
     switch (g.Cw) {                                    // words per plane of the packed window
         case 1: launch_window_shape<AB, WB, 1>(g, grid, s); break;
         case 2: launch_window_shape<AB, WB, 2>(g, grid, s); break;
@@ -647,6 +648,7 @@ template <int AB, int WB>
 hipError_t launch_general_t(const BranchArgs &g, hipStream_t s) {
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
     const dim3 grid((unsigned)((row_blocks * g.col_tiles + 3) / 4));
+    if (g.xcd_ranges && g.grid_blocks != grid.x) return hipErrorInvalidValue;             // host bug
     const bool emit = g.planes_out != nullptr;
     // channel words per chunk (at most AB*CWT = 8 and no more than there are), then taps per chunk
     // such that the chunk's weight words (TT*WB*CWT) stay at or below 64 VGPRs and one pixel's

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void im2col_pack_kernel(const CodeT *__restric
 template <int AB, int WB, bool EMIT>
 __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges) * 4 + (threadIdx.x >> 6)));
+    const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges, g.grid_blocks) * 4 + (threadIdx.x >> 6)));
     const int ct = wave % g.col_tiles;
     const int rb = wave / g.col_tiles;
     const bool active = (int64_t)rb * g.rows_per_wave < g.rows;
@@ -146,6 +146,7 @@ hipError_t launch_small_t(const BranchArgs &g, hipStream_t s) {
     const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
     const int64_t waves = row_blocks * g.col_tiles;
     const dim3 grid((unsigned)((waves + 3) / 4));
+    if (g.xcd_ranges && g.grid_blocks != grid.x) return hipErrorInvalidValue;             // host bug
     if (g.planes_out != nullptr) hipLaunchKernelGGL((conv_small_kernel<AB, WB, true>), grid, dim3(256), 0, s, g);
     else hipLaunchKernelGGL((conv_small_kernel<AB, WB, false>), grid, dim3(256), 0, s, g);
     return hipGetLastError();

@@ -190,10 +190,12 @@ __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bo
 // set of activation planes; numbered as below, XCD x works on one contiguous part of the blocks,
 // i.e. of the pixels, and fetches that part only.  With q = gridDim.x / 8 and r = gridDim.x % 8,
 // XCD x receives q + (x < r) blocks, and they are given the numbers x*q + min(x, r) + (b / 8):
-// consecutive ranges that tile [0, gridDim.x) exactly.  (1-D grids only.)
+// consecutive ranges that tile [0, gridDim.x) exactly.  (1-D grids only.)  The grid size comes in
+// with the kernel arguments (nb; the launchers check it against the grid they launch): reading
+// gridDim.x costs a vector load and a wait at the start of every wavefront.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t xcd_block(int on) {
-    const uint32_t nb = gridDim.x, b = blockIdx.x;
+__device__ __forceinline__ uint32_t xcd_block(int on, uint32_t nb) {
+    const uint32_t b = blockIdx.x;
     if (!on) return b;
     const uint32_t q = nb >> 3, r = nb & 7u, x = b & 7u;
     return x * q + (x < r ? x : r) + (b >> 3);

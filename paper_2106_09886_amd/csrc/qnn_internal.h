@@ -38,7 +38,10 @@ struct BranchArgs {
                           // rows_per_wave is the number of rows per BLOCK
     int gather_rows;      // GEMM only: row r is output pixel r of a single-tap strided convolution (geo, H, W);
                           // bit widths up to 4, not with split_k
+    int lds_partials;     // GEMM only: partial sums between chunk passes stay in LDS (rows_per_wave <=
+                          // kLdsPartialRows, bit widths up to 4, not with split_k or gather_rows)
     int xcd_ranges;       // convolution kernels: number the blocks so that each XCD takes one contiguous range
+    unsigned grid_blocks; // blocks of the launch (wave_grid_blocks), read by the kernels when xcd_ranges is set
     uint64_t *trace;      // optional per-wavefront trace records (4 x uint64 each), or nullptr
     uint32_t trace_waves; // capacity of `trace` in wavefronts
     uint32_t *planes_out; // optional: the scaled result re-encoded with out_bits bits, as bit planes
@@ -47,6 +50,14 @@ struct BranchArgs {
     ConvGeom geo;         // general convolution only
 };
 
+constexpr int kLdsPartialRows = 24;   // rows per wavefront whose partial sums the GEMM kernel keeps in LDS
+
+// Blocks of four wavefronts in a launch that gives one wavefront to every (row block, column tile).
+inline unsigned wave_grid_blocks(const BranchArgs &g) {
+    const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
+    return (unsigned)((row_blocks * g.col_tiles + 3) / 4);
+}
+
 struct Tuning {
     int waves_per_simd;   // target resident wavefronts per SIMD when sizing rows_per_wave
     int rows_per_wave;    // > 0 overrides the automatic choice
@@ -54,6 +65,7 @@ struct Tuning {
     uint32_t trace_waves;
     int general_only;     // qnn_conv2d_general hands no 3x3 stride-1 pad-1 window to the 3x3 kernel
     int block_order;      // 0: automatic, 1: plain block numbers, 2: a contiguous range per XCD
+    int lds_partials;     // 0: automatic, 1: GEMM partial sums through the output buffer, 2: in LDS where possible
 };
 Tuning &tuning();
 

@@ -253,6 +253,7 @@ def test_tune_rejects_unknown_keys(L):
     assert L.qnn_tune(3, 1) == QNN_OK and L.qnn_tune(3, 0) == QNN_OK
     assert L.qnn_tune(4, 2) == QNN_OK and L.qnn_tune(4, 1) == QNN_OK and L.qnn_tune(4, 0) == QNN_OK
     assert L.qnn_tune(4, 3) == QNN_EINVAL
+    assert L.qnn_tune(5, 2) == QNN_OK and L.qnn_tune(5, 0) == QNN_OK and L.qnn_tune(5, 3) == QNN_EINVAL
     assert L.qnn_tune(99, 1) == QNN_EINVAL
     assert L.qnn_tune(1, -1) == QNN_EINVAL
 

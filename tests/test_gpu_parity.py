@@ -19,7 +19,7 @@ def q():
     from paper_2106_09886_amd import binding
     binding.lib()
     yield binding
-    binding.tune(waves_per_simd=0, rows_per_wave=0, block_order=0)
+    binding.tune(waves_per_simd=0, rows_per_wave=0, block_order=0, lds_partials=0)
 
 
 from gpu_util import dev, host, rand_codes, planes_u32, say  # noqa: E402
@@ -146,6 +146,23 @@ def test_gemm_any_rows_per_wave(q, oracle, rpw):
         run_gemm(q, oracle, rand_codes(rng, (70, 2200), 2), rand_codes(rng, (2200, 130), 2), 2, 2)
     finally:
         q.tune(rows_per_wave=0)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_gemm_partial_sums_either_way(q, oracle, mode):
+    """Several K chunks per wavefront: the partial sums pass through the output buffer or stay in
+    LDS; whole and ragged last chunks, rows per wavefront at and around the LDS limit."""
+    rng = np.random.default_rng(900 + mode)
+    q.tune(lds_partials=mode)
+    try:
+        for (M, N, K, ab, wb, rpw) in [(100, 70, 4100, 1, 1, 0), (70, 130, 2200, 2, 2, 24), (53, 64, 2048, 2, 2, 25),
+                                       (40, 65, 1100, 4, 3, 7), (30, 64, 1025, 3, 4, 0), (200, 64, 6000, 1, 2, 1)]:
+            say("partial sums", mode, M, N, K, ab, wb, rpw)
+            q.tune(rows_per_wave=rpw)
+            s = rng.uniform(0.01, 0.1, N).astype(np.float32)
+            run_gemm(q, oracle, rand_codes(rng, (M, K), ab), rand_codes(rng, (K, N), wb), ab, wb, s)
+    finally:
+        q.tune(rows_per_wave=0, lds_partials=0)
 
 
 def test_gemm_degenerate(q, oracle):
