@@ -223,9 +223,7 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     // the floor keeps a wavefront's products per weight chunk at about 1500 vector instructions or
     // more, below which reloading the weights costs more than the balance gains.  Measured on
     // products from 100352 x 64 x 256 to 8192^3 at one to four bits: 0.90-0.96 of the lane-op peak
-    // at 16-32 wavefronts per SIMD against 0.82-0.87 at four, and at least the rate of a variant
-    // that kept the partial sums of 32-row groups in LDS (dropped: its LDS slab capped the
-    // resident wavefronts at five per SIMD).
+    // at 16-32 wavefronts per SIMD against 0.82-0.87 at four.
     {
         const int kc = gemm_chunk_words(wb);
         const int64_t per_row = 2 * (int64_t)ab * wb * (g.Cw < kc ? (g.Cw > 0 ? g.Cw : 1) : kc);
