@@ -119,7 +119,9 @@ int pick_conv_rows_per_wave(int64_t rows, int64_t W, int col_tiles, int passes, 
 // blocks per XCD keeps each XCD's L2 to its own part of the activation planes (on the
 // ResNet-18-shaped layer the kernel then fetches 3.5 MB instead of 10.2 MB).  Measured effect on
 // the time: the general and window kernels gain up to 8 %, the 3x3 kernel gains 1-2 % from four
-// column tiles on and loses 0.2-0.4 % below, the few-channel 3x3 kernel loses 3 %.
+// column tiles on and loses 0.2-0.4 % below, the few-channel 3x3 kernel loses 3 %.  (The 3x3
+// kernel has the numbering as a compile-time variant for channel counts of 64, 128, 256 and 512
+// and ignores the request otherwise.)
 int xcd_ranges_for(bool automatic) {
     const int o = tuning().block_order;
     return (o == 2 || (o == 0 && automatic)) ? 1 : 0;

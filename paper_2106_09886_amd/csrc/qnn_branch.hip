@@ -730,10 +730,13 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
     }
 }
 
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT>
+// XR: the blocks are numbered so that each XCD takes one contiguous range of them (xcd_block();
+// a compile-time choice: even a wave-uniform test of it at the start of every wavefront showed
+// in the time of the ResNet-18-shaped layer).
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const WavePos wp = wave_pos<true>(g.col_tiles, g.xcd_ranges, g.grid_blocks);
+    const WavePos wp = wave_pos<XR>(g.col_tiles, 1, g.grid_blocks);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
     const int r0 = active ? wp.rb * g.rows_per_wave : 0;
@@ -864,6 +867,15 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
+    if constexpr (CWS >= 2) {      // 64 channels and more: the automatic choice asks for it from 256 filters on
+        if (g.xcd_ranges) {
+            if (g.planes_out != nullptr)
+                hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true, true>), grid_for(g), dim3(256), 0, s, g);
+            else
+                hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, false, true>), grid_for(g), dim3(256), 0, s, g);
+            return hipGetLastError();
+        }
+    }
     if (g.planes_out != nullptr)
         hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true>), grid_for(g), dim3(256), 0, s, g);
     else

@@ -296,7 +296,8 @@ def test_conv_any_block_order(q, oracle, order):
     q.tune(block_order=order)
     try:
         for (Nb, H, W, C, Cout, rpw) in [(1, 3, 4, 64, 64, 0), (2, 9, 7, 64, 64, 4), (3, 11, 13, 40, 130, 3),
-                                         (2, 16, 16, 64, 300, 5), (2, 20, 22, 3, 64, 7)]:
+                                         (2, 16, 16, 64, 300, 5), (2, 20, 22, 3, 64, 7), (2, 6, 6, 128, 300, 3),
+                                         (1, 5, 7, 256, 64, 2), (1, 9, 9, 512, 256, 0)]:
             say("block order", order, Nb, H, W, C, Cout, rpw)
             q.tune(rows_per_wave=rpw)
             ab = 8 if C == 3 else 2
