@@ -40,7 +40,11 @@ PEAK_LANE_OPS = 256 * 64 * 2.4e9
 
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/ (scaled by the device-copy calibration described there).
-MEASURED_TRAFFIC = {"resnet18_s1": 61.6e6}
+MEASURED_TRAFFIC = {"resnet18_s1": 61.6e6,          # 10.2 MB fetched + 51.4 MB written
+                    "resnet50_s3": 31.0e6,          # 18.2 + 12.8 MB
+                    "fc4096": 16.9e6,               # 8.5 + 8.4 MB
+                    "gemm8192/1": 412e6,            # 144 + 268 MB (bits = 1)
+                    "gemm8192/2": 556e6}            # 288 + 268 MB (bits = 2)
 
 
 def timed(torch, fn, n):
@@ -544,7 +548,8 @@ def main():
             "unit": "Tlane-op/s",
             "peak_from": "256 CU x 64 lanes x 2.4 GHz, one 32-bit integer vector op per lane and clock",
             "frac": round(achieved / PEAK_LANE_OPS, 4),
-            "traffic": MEASURED_TRAFFIC.get(name) if args.batch is None else None,
+            "traffic": (MEASURED_TRAFFIC.get("gemm8192/%d" % (args.bits or 2) if name == "gemm8192" else name)
+                        if args.batch is None else None),
         },
     }
 
