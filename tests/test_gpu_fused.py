@@ -47,6 +47,8 @@ CONV_CASES = [
     (1, 4, 4, 40, 20, 6, 2, 8),          # wide activations (unpipelined path), 8-bit result
     (1, 3, 10, 256, 64, 4, 3, 7),        # taps in separate chunks
     (3, 14, 14, 64, 64, 2, 2, 2),        # several wavefronts per image
+    (1, 5, 5, 64, 256, 2, 2, 2),         # four column tiles: blocks numbered per XCD
+    (2, 4, 6, 256, 260, 4, 2, 4),        # the same with two chunk passes and a ragged fifth tile
 ]
 
 
