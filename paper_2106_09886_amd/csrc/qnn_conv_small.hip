@@ -98,16 +98,17 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
     bufA.template request<0>(base, (uint32_t)r0 * kPixelBytes);
 
     int r = r0;
+    // Pixels from here on that are known to see all nine taps: in an image row that is neither the
+    // first nor the last, everything between the first and the last column.  While the count runs,
+    // a pixel costs no mask work at all; at 0 the masks are worked out from (oh, ow).
+    int full_left = 0;
+    const int kfull = __builtin_popcount(full) * g.kconst;
     auto one_pixel = [&](SRun<AB> &cur, SRun<AB> &nxt) {
         cur.template arrive<true>();
         const int rn = (r + 1 < r1) ? r + 1 : r;           // the last pixel prefetches itself (unused)
         nxt.template request<0>(base, (uint32_t)rn * kPixelBytes);
-        uint32_t m = full;
-        if (oh == 0) m &= ~rowmask[0];
-        if (oh == g.H - 1) m &= ~rowmask[2];
-        if (ow == 0) m &= ~colmask[0];
-        if (ow == g.W - 1) m &= ~colmask[2];
         int part[AB + WB - 1];                             // part[s]: branches with p + q = s
+        uint32_t m = full;
         auto add_branches = [&](auto masked) {
 #pragma unroll
             for (int q = 0; q < WB; ++q)
@@ -119,17 +120,32 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
                     else popc_acc(part[p + q], x);
                 }
         };
-        if (m == full) add_branches(std::false_type());
-        else add_branches(std::true_type());
+        int konst = kfull;
+        if (full_left > 0) {
+            --full_left;
+            ++ow;                                          // stays below W - 1 while the count runs
+            add_branches(std::false_type());
+        } else {
+            if (oh == 0) m &= ~rowmask[0];
+            if (oh == g.H - 1) m &= ~rowmask[2];
+            if (ow == 0) m &= ~colmask[0];
+            if (ow == g.W - 1) m &= ~colmask[2];
+            if (m == full) {
+                add_branches(std::false_type());
+            } else {
+                add_branches(std::true_type());
+                konst = __builtin_popcount(m) * g.kconst;   // kconst = (2^AB-1)(2^WB-1) per element
+            }
+            if (++ow == g.W) {
+                ow = 0;
+                if (++oh == g.H) oh = 0;
+            }
+            if (oh > 0 && oh < g.H - 1 && ow >= 1 && ow < g.W - 1) full_left = g.W - 1 - ow;   // columns ow .. W-2
+        }
         int sum = part[AB + WB - 2];
 #pragma unroll
         for (int i = AB + WB - 3; i >= 0; --i) sum = (sum << 1) + part[i];
-        const int val = __builtin_popcount(m) * g.kconst - 2 * sum;     // kconst = (2^AB-1)(2^WB-1) per element
-        finish_row<true>(ov, r - r0, val, true, true);
-        if (++ow == g.W) {
-            ow = 0;
-            if (++oh == g.H) oh = 0;
-        }
+        finish_row<true>(ov, r - r0, konst - 2 * sum, true, true);
         ++r;
     };
     while (r + 1 < r1) {
