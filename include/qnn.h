@@ -138,6 +138,25 @@ qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const 
                              size_t workspace_bytes, void *stream);
 
 /*
+ * qnn_conv2d_im2col for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same two
+ * kernels, with the per-pixel activation planes in a scratch array that is part of the library
+ * image (QNN_STATIC_SCRATCH_BYTES of device memory on every GPU the library runs on, held until the
+ * process ends).  Arguments, results, limits and errors as for qnn_conv2d_im2col without the two
+ * workspace arguments; additionally QNN_EUNSUPPORTED if the planes do not fit:
+ *     Nb*H*W * ab * ceil(C/32) * 4  >  QNN_STATIC_SCRATCH_BYTES.
+ * The call allocates and frees nothing.  The first call on a GPU looks up the array's address on
+ * that GPU (the current device); make that call outside a stream capture.  All calls on one GPU
+ * share the array: two calls that can overlap there (different streams, different threads) race on
+ * it; calls on one stream are ordered and safe.  Nothing needs to start at zero: every word a call
+ * reads was written by its own first kernel.
+ */
+#define QNN_STATIC_SCRATCH_BYTES (8u << 20)
+qnn_status qnn_conv2d_im2col_static(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt,
+                                    int wb, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout,
+                                    int32_t *acc, const float *scale, float *out_f32, void *stream);
+
+/*
  * The same convolution from activations that are already packed per pixel
  * (x_planes = qnn_encode_pack(codes viewed as [Nb*H*W][C], bits = ab), uint32
  * [Nb*H*W][ab][Cw]).  This is the second kernel of qnn_conv2d_im2col on its own; it is

@@ -20,7 +20,7 @@ QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE, QNN_TUNE_GENERAL_ONLY, QNN_TUNE
 EXPORTS = (
     "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_set_wave_trace",
     "qnn_encode_pack",
-    "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col",
+    "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col", "qnn_conv2d_im2col_static",
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
@@ -85,6 +85,8 @@ def lib():
     L.qnn_conv2d_im2col_workspace_bytes.restype = sz
     L.qnn_conv2d_im2col.argtypes = [vp, i32, i32, vp, i32, i64, i64, i64, i64, i64, vp, vp, vp, vp, sz, vp]
     L.qnn_conv2d_im2col.restype = i32
+    L.qnn_conv2d_im2col_static.argtypes = [vp, i32, i32, vp, i32, i64, i64, i64, i64, i64, vp, vp, vp, vp]
+    L.qnn_conv2d_im2col_static.restype = i32
     L.qnn_conv2d_packed.argtypes = [vp, i32, vp, i32, i64, i64, i64, i64, i64, vp, vp, vp, vp]
     L.qnn_conv2d_packed.restype = i32
     L.qnn_requant_pack.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp, vp, vp]
@@ -229,6 +231,27 @@ def conv2d_im2col(x_codes, ab, Wt, wb, Cout, scale=None, want_acc=True, workspac
                                  _ptr(acc), _ptr(scale), _ptr(o32), _ptr(workspace), workspace.numel(),
                                  _stream())
     _check(st, "qnn_conv2d_im2col")
+    return acc, o32
+
+
+QNN_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def conv2d_im2col_static(x_codes, ab, Wt, wb, Cout, scale=None, want_acc=True, out=None):
+    """qnn_conv2d_im2col without a workspace: the library's own static scratch holds the planes.
+    With out=(acc, out_f32) the call itself touches no allocator at all."""
+    _dev(x_codes, x_codes.dtype, "x_codes")
+    _dev(Wt, torch.int32, "Wt")
+    Nb, H, W, C = x_codes.shape
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    if out is None:
+        acc, o32 = _outputs((Nb, H, W), Cout, x_codes.device, scale, want_acc)
+    else:
+        acc, o32 = out
+    st = lib().qnn_conv2d_im2col_static(_ptr(x_codes), x_codes.element_size(), ab, _ptr(Wt), wb, Nb, H, W, C, Cout,
+                                        _ptr(acc), _ptr(scale), _ptr(o32), _stream())
+    _check(st, "qnn_conv2d_im2col_static")
     return acc, o32
 
 

@@ -3,6 +3,11 @@
 #include <cmath>
 #include "qnn_internal.h"
 
+// Scratch of qnn_conv2d_im2col_static: the per-pixel activation planes between its two kernels.
+// One copy per GPU, held until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; the kernels get the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[QNN_STATIC_SCRATCH_BYTES];
+
 namespace qnn {
 
 Tuning &tuning() {
@@ -28,6 +33,9 @@ int device_simd_count() {
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+constexpr size_t kStaticScratchBytes = QNN_STATIC_SCRATCH_BYTES;
+std::atomic<void *> g_scratch_ptr[64];       // per device: address of `scratch` on that GPU, once resolved
 
 qnn_status from_hip(hipError_t e) {
     if (e == hipSuccess) return QNN_OK;
@@ -301,7 +309,9 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
 qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt, int wb, int64_t Nb,
                            int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
                            float *out_f32, void *workspace, size_t workspace_bytes, const Emit &e,
-                           void *stream) {
+                           void *stream, bool *dry_run = nullptr) {
+    // dry_run: only the host-side checks; *dry_run says whether the call would launch anything
+    if (dry_run) *dry_run = false;
     qnn_status st = check_image(Nb, H, W, C, Cout);
     if (st != QNN_OK) return st;
     if (code_bytes != 1 && code_bytes != 2) return QNN_EINVAL;
@@ -320,6 +330,12 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
     if (rows == 0 || Cout == 0) return QNN_OK;
     if (have_k) {
         if (workspace_bytes < qnn_conv2d_im2col_workspace_bytes(Nb, H, W, C, ab)) return QNN_EWORKSPACE;
+    }
+    if (dry_run) {
+        *dry_run = true;
+        return QNN_OK;
+    }
+    if (have_k) {
         if (9 * C <= 32) {
             // few input channels: one im2col word per plane and pixel (same workspace size as the
             // per-pixel planes, Cw == 1), then the single-word branch kernel
@@ -436,6 +452,32 @@ qnn_status qnn_conv2d_im2col(const void *x_codes, int code_bytes, int ab, const 
                              size_t workspace_bytes, void *stream) {
     return run_conv_im2col(x_codes, code_bytes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, workspace,
                            workspace_bytes, kNoEmit, stream);
+}
+
+qnn_status qnn_conv2d_im2col_static(const void *x_codes, int code_bytes, int ab, const uint32_t *Wt, int wb,
+                                    int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout, int32_t *acc,
+                                    const float *scale, float *out_f32, void *stream) {
+    // Every host-side check first, with a stand-in for the scratch address: they need no GPU, and
+    // nothing may be looked up or launched for a call that fails them.
+    alignas(16) static char stand_in;
+    bool launches = false;
+    const qnn_status st = run_conv_im2col(x_codes, code_bytes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32,
+                                          &stand_in, kStaticScratchBytes, kNoEmit, stream, &launches);
+    if (st == QNN_EWORKSPACE) return QNN_EUNSUPPORTED;          // the planes do not fit the static scratch
+    if (st != QNN_OK || !launches) return st;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return from_hip(hipErrorInvalidDevice);
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        // first call on this GPU (it is the current device): every GPU has its own copy of the array
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) return from_hip(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    // Both kernels overwrite every word of the planes they use (tail bits included), so the
+    // contents a previous call left behind need no clearing.
+    return run_conv_im2col(x_codes, code_bytes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, ptr,
+                           kStaticScratchBytes, kNoEmit, stream);
 }
 
 size_t qnn_requant_workspace_bytes(int64_t rows, int64_t N) {

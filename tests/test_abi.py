@@ -265,3 +265,21 @@ def test_product_path_has_no_oracle_or_cpu_fallback():
         if fn.endswith(".py"):
             src = open(os.path.join(pkg, fn)).read()
             assert "import oracle" not in src and "from oracle" not in src, fn
+
+
+def test_static_scratch_entry_point_checks_on_the_host(L):
+    """The entry point without a workspace validates like qnn_conv2d_im2col and refuses planes that
+    do not fit its static scratch, all before any GPU call."""
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED, QNN_STATIC_SCRATCH_BYTES
+    f = L.qnn_conv2d_im2col_static
+    text = open(os.path.join(ROOT, "include", "qnn.h")).read()
+    m = re.search(r"#define\s+QNN_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert m and (int(m.group(1)) << int(m.group(2))) == QNN_STATIC_SCRATCH_BYTES
+    fits = QNN_STATIC_SCRATCH_BYTES // 16                      # W2A2, 64 channels: 16 bytes of planes per pixel
+    assert f(P, 1, 2, P, 2, 1, 1, fits + 1, 64, 64, P, None, None, None) == QNN_EUNSUPPORTED
+    assert f(P, 1, 0, P, 2, 1, 4, 4, 64, 64, P, None, None, None) == QNN_EINVAL          # bits
+    assert f(P, 3, 2, P, 2, 1, 4, 4, 64, 64, P, None, None, None) == QNN_EINVAL          # code size
+    assert f(None, 1, 2, P, 2, 1, 4, 4, 64, 64, P, None, None, None) == QNN_EINVAL
+    assert f(P, 1, 2, P, 2, 1, 4, 4, 64, 64, None, None, None, None) == QNN_EINVAL       # no output
+    assert f(P, 1, 2, P + 4, 2, 1, 4, 4, 64, 64, P, None, None, None) == QNN_EALIGN
+    assert f(None, 1, 2, None, 2, 0, 4, 4, 64, 64, None, None, None, None) == QNN_OK     # empty: nothing launched
