@@ -26,25 +26,112 @@ another number of images: fixed cost of a launch), `--graph`, `--copy-calibratio
 """
 import argparse
 import ctypes
+import hashlib
 import json
+import math
 import os
+import statistics
+import subprocess
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# MI355X: 256 compute units x 64 vector lanes x 2.4 GHz = one 32-bit integer lane-op per lane
-# and clock (v_xor_b32, v_bcnt_u32_b32 are full rate, not packed).
-PEAK_LANE_OPS = 256 * 64 * 2.4e9
+# Integer vector-ALU peak: compute units x 64 lanes x shader clock, one 32-bit integer lane-op per
+# lane and clock (v_xor_b32, v_bcnt_u32_b32 are full rate, not packed).  The counts come from the
+# device the run is on (device_peak); these are MI355X's published figures, used as the fallback.
+NOMINAL_CUS, NOMINAL_GHZ = 256, 2.4
+PEAK_LANE_OPS = NOMINAL_CUS * 64 * NOMINAL_GHZ * 1e9
 
-# HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/ (scaled by the device-copy calibration described there).
-MEASURED_TRAFFIC = {"resnet18_s1": 61.6e6,          # 10.2 MB fetched + 51.4 MB written
-                    "resnet50_s3": 31.0e6,          # 18.2 + 12.8 MB
-                    "fc4096": 16.9e6,               # 8.5 + 8.4 MB
-                    "gemm8192/1": 412e6,            # 144 + 268 MB (bits = 1)
-                    "gemm8192/2": 556e6}            # 288 + 268 MB (bits = 2)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SOURCES = ("include/qnn.h", "paper_2106_09886_amd/csrc")
+
+
+def device_peak(q):
+    """(lane-op/s, description): CU count and peak shader clock as the HIP runtime reports them."""
+    global PEAK_LANE_OPS
+    try:
+        cus, khz = q.device_info()
+    except RuntimeError:
+        cus, khz = 0, 0
+    cus = cus or NOMINAL_CUS
+    ghz = float(khz) / 1e6 if khz else None
+    said = "device"
+    if not ghz or not (0.5 < ghz < 5.0):
+        ghz, said = NOMINAL_GHZ, "nominal (the runtime reported none)"
+    PEAK_LANE_OPS = cus * 64 * ghz * 1e9
+    return PEAK_LANE_OPS, "%d CU x 64 lanes x %.3f GHz (%s clock), one 32-bit integer vector op per lane and clock" % (
+        cus, ghz, said)
+
+
+def kernel_source_hash():
+    """sha256 over the kernel sources: ties a stored traffic figure to the code it was measured on."""
+    h = hashlib.sha256()
+    files = []
+    for rel in KERNEL_SOURCES:
+        path = os.path.join(ROOT, rel)
+        if os.path.isdir(path):
+            files += [os.path.join(path, f) for f in sorted(os.listdir(path)) if f.endswith((".hip", ".h"))]
+        else:
+            files.append(path)
+    for f in files:
+        h.update(os.path.relpath(f, ROOT).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def stored_traffic(key):
+    """HBM bytes per launch of the dominant kernel of workload `key`, from the counter runs recorded in
+    profiles/traffic.json (written by --record-traffic) -- or None when the kernel sources have changed
+    since (a stale figure is worse than none)."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None
+    if rec.get("source_sha256") != kernel_source_hash():
+        return None
+    e = rec.get("workloads", {}).get(key)
+    return None if e is None else e.get("bytes_per_launch")
+
+
+def record_traffic(args):
+    """--record-traffic KEY KERNEL FETCH.csv WRITE.csv: read two rocprofv3 --pmc counter CSVs (FETCH_SIZE
+    and WRITE_SIZE, KiB per dispatch; each run made with --copy-calibration), scale them by what the same
+    counter shows for the 256 MiB device copy in that run, and store the per-launch bytes of the kernel
+    whose name contains KERNEL in profiles/traffic.json together with the hash of the kernel sources."""
+    import csv
+    key, kernel, fetch_csv, write_csv = args
+
+    def per_dispatch(path, counter):
+        rows = list(csv.DictReader(open(path)))
+        vals = lambda sub: [float(r["Counter_Value"]) for r in rows
+                            if r.get("Counter_Name") == counter and sub in r.get("Kernel_Name", "")]
+        cal, ker = vals("copyBuffer"), vals(kernel)
+        if not cal or not ker:
+            raise SystemExit("%s: no %s rows for the copy or for '%s'" % (path, counter, kernel))
+        factor = (256 << 10) / statistics.median(cal)             # the copy moves 262144 KiB each way
+        return statistics.median(ker) * 1024.0 * factor, factor, len(ker)
+    fb, ff, nf = per_dispatch(fetch_csv, "FETCH_SIZE")
+    wb, wf, nw = per_dispatch(write_csv, "WRITE_SIZE")
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        rec = {}
+    src = kernel_source_hash()
+    if rec.get("source_sha256") != src:
+        rec = {"source_sha256": src, "workloads": {}}
+    try:
+        rec["git_head_when_recorded"] = subprocess.run(["git", "-C", ROOT, "rev-parse", "HEAD"], capture_output=True,
+                                                       text=True).stdout.strip() or None
+    except OSError:
+        rec["git_head_when_recorded"] = None
+    rec["workloads"][key] = {"kernel": kernel, "bytes_per_launch": round(fb + wb), "fetch_bytes": round(fb),
+                             "write_bytes": round(wb), "fetch_scale": round(ff, 4), "write_scale": round(wf, 4),
+                             "dispatches": [nf, nw]}
+    json.dump(rec, open(TRAFFIC_FILE, "w"), indent=1, sort_keys=True)
+    print(json.dumps(rec["workloads"][key]))
+    return 0
 
 
 def timed(torch, fn, n):
@@ -57,6 +144,62 @@ def timed(torch, fn, n):
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) / n * 1e3
+
+
+def timed_regions(torch, fn, k, min_samples=100, min_ms=50.0, lead_in=3, max_regions=400):
+    """Timed regions of EXACTLY k calls each, repeated until at least min_samples calls and min_ms of
+    device time have been measured, so that the result does not depend on the caller's k.  A region is
+    bracketed by synchronisations; inside, `lead_in` untimed calls go first so that the queue is not
+    empty when the first event is reached (otherwise each region also times one launch latency).
+    Returns microseconds per call: median, min and mean over the regions."""
+    per_call, total_ms = [], 0.0
+    while len(per_call) < max_regions and (len(per_call) * k < min_samples or total_ms < min_ms):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        for _ in range(lead_in):
+            fn()
+        a.record()
+        for _ in range(k):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b)
+        total_ms += ms
+        per_call.append(ms / k * 1e3)
+    return {"median": statistics.median(per_call), "min": min(per_call), "mean": statistics.fmean(per_call),
+            "regions": len(per_call), "calls_per_region": k}
+
+
+def conv_tap_pixels(Nb, H, W):
+    """(output pixel, tap) pairs of a 3x3 / stride 1 / pad 1 layer whose tap lies inside the image: the
+    products the kernels really form (taps outside are skipped, they contribute exactly 0)."""
+    vh = 3 * H - 2 if H >= 2 else H
+    vw = 3 * W - 2 if W >= 2 else W
+    return Nb * vh * vw
+
+
+def axis_taps(size_in, size_out, k, stride, pad, dil, transposed):
+    """Sum over the output positions of one axis of the number of kernel elements that meet the image."""
+    n = 0
+    for o in range(size_out):
+        for j in range(k):
+            if transposed:
+                num = o + pad - j * dil
+                if num % stride == 0 and 0 <= num // stride < size_in:
+                    n += 1
+            elif 0 <= o * stride - pad + j * dil < size_in:
+                n += 1
+    return n
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
 
 
 def traced_launch(torch, np, q, launch):
@@ -110,7 +253,7 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
             torch.cuda.synchronize()
         for _ in range(warmup):
             fn()
-        return timed(torch, fn, steps)
+        return timed_regions(torch, fn, steps, min_samples=60, min_ms=20.0)["median"]
 
     rows = []
     if name == "hbm_kernels":
@@ -179,9 +322,13 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
             q.tune(general_only=0)
             taps = KH * KW / (st * st if tr else 1)
             ops = 2.0 * Nb * Ho * Wo * Cout * taps * C
+            # (output pixel, tap) pairs that meet the image: the products the kernel forms
+            tap_pixels = Nb * axis_taps(H, Ho, KH, st, pd, dl, tr) * axis_taps(W, Wo, KW, st, pd, dl, tr)
             rows.append({"layer": label, "out": "%dx%d" % (Ho, Wo), "us": round(t, 1), "effective_GOPS": round(ops / t / 1e3, 1),
                          # word-per-tap lane-ops; not meaningful on the packed-window path (few channels)
                          "frac_of_lane_op_peak": None if C < 32 else round(
+                             2.0 * ab * wb * tap_pixels * Cout * Cw / (t * 1e-6) / PEAK_LANE_OPS, 3),
+                         "frac_if_padded_taps_counted": None if C < 32 else round(
                              2.0 * ab * wb * Nb * Ho * Wo * Cout * taps * Cw / (t * 1e-6) / PEAK_LANE_OPS, 3)})
             del Xp, Wp
         res = {"metric": "effective quantized GOPS of qnn_conv2d_general, first listed layer", "value": rows[0]["effective_GOPS"],
@@ -212,11 +359,16 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of 256 MiB (a kernel of known HBM traffic) "
                          "so that a counter run can be scaled against it")
+    ap.add_argument("--record-traffic", nargs=4, metavar=("KEY", "KERNEL", "FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU: turn two rocprofv3 --pmc counter CSVs (FETCH_SIZE, WRITE_SIZE; runs made with "
+                         "--copy-calibration) into the entry KEY of profiles/traffic.json, which roofline.traffic reads")
     ap.add_argument("--wave-trace", action="store_true",
                     help="additionally run ONE launch of the branch kernel with the per-wavefront trace "
                          "(qnn_set_wave_trace) and report config.wave_trace: wavefronts per SIMD, the SIMDs' "
                          "active windows in shader cycles and the shader clock during the kernel")
     args = ap.parse_args()
+    if args.record_traffic:
+        return record_traffic(args.record_traffic)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the path on ONE GPU only (the path shards over the batch "
               "with no communication, so a second GPU would run the same kernel on its own share); "
@@ -239,6 +391,7 @@ def main():
         return 2
     L = q.lib()                                   # raises if the HIP library is not built
     dev = torch.device("cuda:0")
+    peak, peak_from = device_peak(q)
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     p = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())
 
@@ -256,7 +409,7 @@ def main():
     if name in ("hbm_kernels", "conv_geometries"):
         return side_suites(name, args, steps, warmup, torch, np, q, dev)
 
-    cpu = None
+    cpu = cpu1 = None
     if name == "vgg16_stack":
         w = inputs.VGG16
         X0, layers = inputs.make_stack(w)
@@ -268,6 +421,13 @@ def main():
             """32-bit words per plane of one output pixel's K axis: nine per-tap runs, or the single
             word of the few-channel first layer (9 * c <= 32 bits)."""
             return 1 if 9 * c <= 32 else 9 * ((c + 31) // 32)
+
+        def layer_lane_ops(ab, h, wd, c, cout):
+            """xor + popcount per word, branch and tap that lies inside the image (the few-channel first
+            layer works on one word per plane and pixel whatever the border)."""
+            if 9 * c <= 32:
+                return 2.0 * ab * w.wb * Nb * h * wd * cout
+            return 2.0 * ab * w.wb * conv_tap_pixels(Nb, h, wd) * cout * ((c + 31) // 32)
 
         h, wd, c = H, W, C
         planes_in = torch.empty((Nb * h * wd, w.ab_first, 1), dtype=torch.int32, device=dev)
@@ -288,7 +448,7 @@ def main():
                          p(planes_out), p(planes_mid), acc.numel() * 4))
             keep.append((Wp, sd, acc, out, planes_in, planes_out, planes_mid))
             ops += 2.0 * Nb * h * wd * cout * 9 * c
-            lane_ops += 2.0 * ab * w.wb * Nb * h * wd * cout * kwords(c)
+            lane_ops += layer_lane_ops(ab, h, wd, c, cout)
             planes_in, h, wd, c = planes_out, ho, wo, cout
         pX, pF = p(x0), p(first_planes)
 
@@ -333,8 +493,8 @@ def main():
             pass left in the buffers: the kernels' cost does not depend on the data)."""
             rows_ = []
             for i, (ab, _, _, h, wd, c, cout, *_rest) in enumerate(plan):
-                us = timed(torch, lambda i=i: layer(i), steps)
-                lo = 2.0 * ab * w.wb * Nb * h * wd * cout * kwords(c)
+                us = timed_regions(torch, lambda i=i: layer(i), steps, min_samples=40, min_ms=20.0)["median"]
+                lo = layer_lane_ops(ab, h, wd, c, cout)
                 rows_.append({"layer": i + 1, "shape": "%dx%dx%d -> %d" % (h, wd, c, cout), "us": round(us, 1),
                               "frac_of_lane_op_peak": round(lo / (us * 1e-6) / PEAK_LANE_OPS, 3)})
             return rows_
@@ -417,7 +577,10 @@ def main():
                 w.name, w.M, w.N, w.M, w.K, w.K, w.N, w.wb, w.ab)
             kernel_name = "gemm_kernel (branch GEMM)"
         ops = 2.0 * rows * N * K                      # effective quantized operations per step
-        lane_ops = 2.0 * B * rows * N * Kw            # xor + popcount-accumulate per 32-bit word and branch
+        # xor + popcount-accumulate per 32-bit word and branch; a convolution forms no product for a
+        # tap outside the image, so only (pixel, tap) pairs inside it count
+        lane_ops_padded = 2.0 * B * rows * N * Kw
+        lane_ops = (2.0 * B * conv_tap_pixels(w.Nb, w.H, w.W) * N * kbits) if is_conv else lane_ops_padded
         outputs = "int32" + (" + fp32 scaled" if s is not None else "")
 
         cpu_rows = rows if rows * N * K <= 2e10 else max(1, int(2e10 / (N * K)))   # bound the CPU work
@@ -431,6 +594,26 @@ def main():
                 o = oracle.gemm(X[:cpu_rows].astype(np.int16), Wm.astype(np.int16))
             if s is not None:
                 oracle.scale_f64(o, s)
+
+        # one-thread sample: about 1.5e9 multiply-adds (whole images / whole rows)
+        if is_conv:
+            n1 = max(1, min(w.Nb, int(1.5e9 / (w.H * w.W * N * K))))
+            cpu1_sample = "first %d of %d images" % (n1, w.Nb)
+        else:
+            n1 = max(1, min(rows, int(1.5e9 / (N * K))))
+            cpu1_sample = "first %d of %d rows" % (n1, rows)
+
+        def cpu1():
+            import oracle
+            if is_conv:
+                o = oracle.conv3x3(X[:n1].astype(np.int16), Wt.astype(np.int16))
+                done = 2.0 * n1 * w.H * w.W * N * K
+            else:
+                o = oracle.gemm(X[:n1].astype(np.int16), Wm.astype(np.int16))
+                done = 2.0 * n1 * N * K
+            if s is not None:
+                oracle.scale_f64(o, s)
+            return done
 
     def step():
         pack()
@@ -448,18 +631,21 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps
-    ms_per_step = timed(torch, step, steps) / 1e3
-    # ---- each kernel on its own: K back-to-back launches between one pair of events on the
-    # launch stream (average launch duration of that kernel, operands resident)
-    branch_us = timed(torch, branch, steps)
-    pack_us = timed(torch, pack, steps)
+    # ---- timed regions of exactly K steps each, repeated until >= 100 steps and >= 50 ms are on
+    # record; the reported time per step is the median region (min and mean beside it)
+    t_step = timed_regions(torch, step, steps)
+    ms_per_step = t_step["median"] / 1e3
+    # ---- each kernel on its own, same protocol: regions of K back-to-back launches between one pair
+    # of events on the launch stream (launch duration of that kernel, operands resident)
+    t_branch = timed_regions(torch, branch, steps)
+    branch_us = t_branch["median"]
+    pack_us = timed_regions(torch, pack, steps, min_ms=10.0)["median"]
     cold_us = None
     if name != "vgg16_stack" and cold_sets:
         pack()                                    # planes of every set hold the packed activations
         for cs in cold_sets:
             cs[0].copy_(planes)
-        cold_us = timed(torch, branch_cold, max(steps, n_sets))
+        cold_us = timed_regions(torch, branch_cold, max(steps, n_sets), min_ms=10.0)["median"]
 
     # comparison line (GEMM workloads with codes that fit int8): the same decoded product on the
     # int8 matrix cores, operands arranged once beforehand
@@ -471,7 +657,7 @@ def main():
 
         def mfma():
             check(L.qnn_compare_mfma_gemm(pAa, pWa, w.M, w.N, w.K, pA, stream))
-        mfma_us = timed(torch, mfma, steps)
+        mfma_us = timed_regions(torch, mfma, steps, min_samples=40, min_ms=20.0)["median"]
         compare = {"what": "same decoded int8 product on v_mfma_i32_32x32x32_i8 (comparison line, untuned kernel)",
                    "us": round(mfma_us, 2), "GOPS": round(ops / (mfma_us * 1e-6) / 1e9, 1),
                    "frac_of_int8_mfma_peak_5000_TOPS": round(ops / (mfma_us * 1e-6) / 5.0e15, 4)}
@@ -482,7 +668,7 @@ def main():
 
             def dot4():
                 check(L.qnn_compare_dot4_gemm(pXc, pWc, w.M, w.N, w.K, pA, stream))
-            dot_us = timed(torch, dot4, steps)
+            dot_us = timed_regions(torch, dot4, steps, min_samples=40, min_ms=20.0)["median"]
             compare_dot = {"what": "same decoded int8 product with v_dot4_i32_i8 (comparison line)",
                            "us": round(dot_us, 2), "GOPS": round(ops / (dot_us * 1e-6) / 1e9, 1)}
         branch()                                  # leave the branch result in the output buffer
@@ -506,10 +692,12 @@ def main():
             stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
             step()
         stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
-        graph_ms = timed(torch, gr.replay, steps) / 1e3
+        graph_ms = timed_regions(torch, gr.replay, steps)["median"] / 1e3
 
     value = ops / (ms_per_step * 1e-3) / 1e9
     achieved = lane_ops / (branch_us * 1e-6)
+    rnd = lambda t: {k: (round(v, 3) if isinstance(v, float) else v) for k, v in t.items()}
+    traffic_key = ("gemm8192/%d" % (args.bits or 2)) if name == "gemm8192" else name
     res = {
         "metric": "effective quantized GOPS (2*M*N*K/s), whole step: pack activations + branch product + scale",
         "value": round(value, 1),
@@ -530,6 +718,11 @@ def main():
             "weights": "packed once before the timed region (static parameters)",
             "outputs": outputs,
             "bit_ops_per_s": round(B * ops / (ms_per_step * 1e-3), 1) if B else None,
+            "timing": "regions of exactly `steps` steps between two events on the launch stream, each bracketed by "
+                      "synchronisations (3 untimed steps lead in), repeated until >= 100 steps and >= 50 ms; "
+                      "ms_per_step and value are the median region",
+            "step_us": rnd(t_step),
+            "branch_kernel_us_stats": rnd(t_branch),
             "pack_kernel_us": round(pack_us, 2),
             "branch_kernel_us": round(branch_us, 2),
             "branch_kernel_cold_us": None if cold_us is None else round(cold_us, 2),
@@ -544,12 +737,18 @@ def main():
             "bound": "alu",
             "kernel": kernel_name,
             "achieved": round(achieved / 1e12, 3),
-            "peak": round(PEAK_LANE_OPS / 1e12, 3),
+            "peak": round(peak / 1e12, 3),
             "unit": "Tlane-op/s",
-            "peak_from": "256 CU x 64 lanes x 2.4 GHz, one 32-bit integer vector op per lane and clock",
-            "frac": round(achieved / PEAK_LANE_OPS, 4),
-            "traffic": (MEASURED_TRAFFIC.get("gemm8192/%d" % (args.bits or 2) if name == "gemm8192" else name)
-                        if args.batch is None else None),
+            "peak_from": peak_from,
+            "frac": round(achieved / peak, 4),
+            "lane_ops_per_launch": lane_ops,
+            "counts": "xor + popcount per 32-bit word, branch and tap inside the image (taps in the zero padding "
+                      "are skipped, not computed)",
+            "frac_if_padded_taps_counted": (round(lane_ops_padded / (branch_us * 1e-6) / peak, 4)
+                                            if name != "vgg16_stack" else None),
+            "traffic": stored_traffic(traffic_key) if args.batch is None else None,
+            "traffic_from": "profiles/traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a device copy; "
+                            "null when the kernel sources differ from the ones it was measured on)",
         },
     }
 
@@ -570,9 +769,27 @@ def main():
             "unit": "GOPS",
             "cores": oracle.threads(),
             "kind": "oracle",
+            "cpu_model": cpu_model(),
             "sample": ("full workload" if cpu_rows == rows else "first %d of %d rows" % (cpu_rows, rows))
                       + ", plain int64 product + float64 scale, mean of %d passes" % reps,
         }
+        if cpu1 is not None:
+            # the same oracle on ONE thread, on a smaller sample (about 5 s of work)
+            try:
+                gomp = ctypes.CDLL("libgomp.so.1")
+                gomp.omp_set_num_threads(1)
+                reps1, t0 = 0, time.time()
+                while True:
+                    ops1 = cpu1()
+                    reps1 += 1
+                    if time.time() - t0 > 5.0 or reps1 >= 50:
+                        break
+                dt1 = (time.time() - t0) / reps1
+                gomp.omp_set_num_threads(oracle.threads())
+                res["cpu_baseline"]["one_thread"] = {"value": round(ops1 / dt1 / 1e9, 2), "unit": "GOPS", "cores": 1,
+                                                     "sample": cpu1_sample + ", mean of %d passes" % reps1}
+            except OSError:
+                pass
     print(json.dumps(res))
     return 0
 

@@ -51,6 +51,14 @@ int qnn_last_hip_error(void);
 int qnn_version(void);
 
 /*
+ * Compute units and peak shader clock (kHz) of the current GPU as the HIP runtime reports them,
+ * written to HOST integers: the two factors of the integer vector-ALU peak (units x 64 lanes x
+ * clock) that a benchmark prices the branch kernels against.  QNN_EINVAL for a NULL pointer,
+ * QNN_EHIP if the runtime cannot be asked (no GPU).
+ */
+qnn_status qnn_device_info(int *h_compute_units, int *h_clock_khz);
+
+/*
  * Performance knobs (process-wide; results never depend on them).  value 0 restores the
  * automatic choice.  Returns QNN_OK or QNN_EINVAL.  Not thread-safe against running calls.
  */

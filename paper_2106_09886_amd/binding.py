@@ -18,7 +18,7 @@ QNN_PACK_VALIDATE = 1
 QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE, QNN_TUNE_GENERAL_ONLY, QNN_TUNE_BLOCK_ORDER, QNN_TUNE_LDS_PARTIALS = 1, 2, 3, 4, 5
 
 EXPORTS = (
-    "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_tune", "qnn_set_wave_trace",
+    "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_device_info", "qnn_tune", "qnn_set_wave_trace",
     "qnn_encode_pack",
     "qnn_branch_gemm", "qnn_conv2d_im2col_workspace_bytes", "qnn_conv2d_im2col", "qnn_conv2d_im2col_static",
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
@@ -73,6 +73,8 @@ def lib():
     L.qnn_last_hip_error.restype = i32
     L.qnn_version.argtypes = []
     L.qnn_version.restype = i32
+    L.qnn_device_info.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.qnn_device_info.restype = i32
     L.qnn_tune.argtypes = [i32, i32]
     L.qnn_tune.restype = i32
     L.qnn_set_wave_trace.argtypes = [vp, sz]
@@ -149,6 +151,13 @@ def _dev(t, dtype, name):
     if not t.is_contiguous():
         raise ValueError("%s must be contiguous" % name)
     return t
+
+
+def device_info():
+    """(compute units, peak shader clock in kHz) of the current GPU."""
+    cus, khz = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().qnn_device_info(ctypes.byref(cus), ctypes.byref(khz)), "qnn_device_info")
+    return cus.value, khz.value
 
 
 def tune(waves_per_simd=None, rows_per_wave=None, general_only=None, block_order=None, lds_partials=None):

@@ -383,7 +383,16 @@ const char *qnn_status_string(int status) {
 
 int qnn_last_hip_error(void) { return g_last_hip_error; }
 
-int qnn_version(void) { return 100; }
+int qnn_version(void) { return 101; }
+
+qnn_status qnn_device_info(int *h_compute_units, int *h_clock_khz) {
+    if (h_compute_units == nullptr || h_clock_khz == nullptr) return QNN_EINVAL;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(h_compute_units, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(h_clock_khz, hipDeviceAttributeClockRate, dev);
+    return from_hip(e);
+}
 
 int qnn_set_wave_trace(void *buffer, size_t bytes) {
     if (buffer != nullptr && ((((uintptr_t)buffer) & 7u) || bytes < 32)) return QNN_EINVAL;

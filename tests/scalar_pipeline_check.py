@@ -2,13 +2,16 @@
 
 The branch kernels (qnn_branch.hip, qnn_conv_small.hip) request activation words with s_load_dword* written as inline asm and
 wait for them with an explicit s_waitcnt; the compiler does not know the destination SGPRs
-are in flight in between.  This script compiles them to assembly for every
-activation bit width and verifies, kernel by kernel, that
+are in flight in between.  This module takes their assembly for every activation bit width --
+the files the library build keeps beside its objects (the very code that was linked), or a
+compilation of its own where those are missing or older than the sources -- and verifies,
+kernel by kernel, that
   * no scratch memory is used, and
   * on no path of the control-flow graph does an instruction outside an asm block (a spill
     to a VGPR lane included) name a requested SGPR between its s_load and the next
     `s_waitcnt lgkmcnt(0)`.
-Run: python paper_2106_09886_amd/csrc/check_scalar_pipeline.py   (exit status 0 = clean)
+Run: python tests/scalar_pipeline_check.py   (exit status 0 = clean); tests/test_scalar_pipeline.py
+runs the same check for all eight widths in the CPU suite.
 """
 import os
 import re
@@ -17,8 +20,9 @@ import sys
 import tempfile
 from concurrent.futures import ThreadPoolExecutor
 
-HERE = os.path.dirname(os.path.abspath(__file__))
-ROOT = os.path.dirname(os.path.dirname(HERE))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HERE = os.path.join(ROOT, "paper_2106_09886_amd", "csrc")          # the kernel sources
+BUILD = os.path.join(ROOT, "paper_2106_09886_amd", "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
@@ -32,6 +36,35 @@ def compile_asm(job):
            "-I", os.path.join(ROOT, "include"), "-I", HERE, "-DQNN_AB=%d" % ab, "-S", "--cuda-device-only",
            os.path.join(HERE, src), "-o", out]
     subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE)
+    return out
+
+
+def built_asm(src, ab):
+    """The assembly the library build kept for (source, activation width), or None if it is missing
+    or older than any kernel source."""
+    path = os.path.join(BUILD, "ab%d" % ab, src.split(".")[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+    if not os.path.exists(path):
+        return None
+    deps = [os.path.join(HERE, f) for f in os.listdir(HERE) if f.endswith((".hip", ".h"))]
+    deps.append(os.path.join(ROOT, "include", "qnn.h"))
+    return path if os.path.getmtime(path) >= max(os.path.getmtime(d) for d in deps) else None
+
+
+def asm_files(tmpdir, widths=range(1, 9)):
+    """{(source, ab): path} for every width: the build's files where fresh, else compiled here
+    (in parallel: a compilation takes one to two minutes)."""
+    out, jobs = {}, []
+    for src in SOURCES:
+        for ab in widths:
+            p = built_asm(src, ab)
+            if p is not None:
+                out[(src, ab)] = p
+            else:
+                jobs.append((src, ab, os.path.join(tmpdir, "%s_ab%d.s" % (src.split(".")[0], ab))))
+    if jobs:
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            for job, path in zip(jobs, ex.map(compile_asm, jobs)):
+                out[(job[0], job[1])] = path
     return out
 
 
@@ -151,10 +184,7 @@ def check_file(path):
 
 def main():
     tmp = tempfile.mkdtemp(prefix="qnn_asm_")
-    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
-        jobs = [(src, ab, os.path.join(tmp, "%s_ab%d.s" % (src.split(".")[0], ab)))
-                for src in SOURCES for ab in range(1, 9)]
-        files = list(ex.map(compile_asm, jobs))
+    files = list(asm_files(tmp).values())
     total, bad, spills = 0, [], 0
     for f in files:
         nk, p, sp = check_file(f)

@@ -1,6 +1,7 @@
-"""The static checker of the hand-issued scalar loads (csrc/check_scalar_pipeline.py): first the
+"""The static checker of the hand-issued scalar loads (tests/scalar_pipeline_check.py): first the
 checker itself on tiny hand-written assembly (a planted violation must be found, on a straight
-path and around a loop), then one real compilation of the branch kernels."""
+path and around a loop), then the branch kernels of all eight activation widths -- the assembly
+the library build kept beside its objects, i.e. the code that is in libqnn.so."""
 import os
 import shutil
 import sys
@@ -9,8 +10,8 @@ import tempfile
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-sys.path.insert(0, os.path.join(ROOT, "paper_2106_09886_amd", "csrc"))
-import check_scalar_pipeline as chk  # noqa: E402
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import scalar_pipeline_check as chk  # noqa: E402
 
 
 def kernel(body):
@@ -52,19 +53,24 @@ def test_checker_ignores_compiler_issued_loads():
     assert kernel(["\ts_load_dwordx2 s[8:9], s[0:1], 0x0", "\ts_waitcnt lgkmcnt(0)", "\tv_mov_b32_e32 v0, s8"]) == []
 
 
-@pytest.mark.timeout(900)
-@pytest.mark.skipif(shutil.which(chk.HIPCC) is None and not os.path.exists(chk.HIPCC), reason="hipcc not available")
-def test_branch_kernels_of_one_activation_width_are_clean():
-    """Compiles the 3x3 / GEMM kernels for 2-bit activations (every weight width, every chunk
-    shape: about 130 kernels) and the small-channel kernels to assembly and checks them."""
+@pytest.fixture(scope="module")
+def asm():
     tmp = tempfile.mkdtemp(prefix="qnn_asm_test_")
     try:
-        total = 0
-        for src in chk.SOURCES:
-            out = chk.compile_asm((src, 2, os.path.join(tmp, src.split(".")[0] + ".s")))
-            nk, problems, _ = chk.check_file(out)
-            assert problems == [], problems[:5]
-            total += nk
-        assert total >= 100
+        yield chk.asm_files(tmp)
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
+
+
+@pytest.mark.timeout(1800)
+@pytest.mark.skipif(shutil.which(chk.HIPCC) is None and not os.path.exists(chk.HIPCC), reason="hipcc not available")
+@pytest.mark.parametrize("ab", range(1, 9))
+def test_branch_kernels_are_clean(asm, ab):
+    """Every 3x3 / GEMM kernel (all weight widths, all chunk shapes) and the small-channel kernels of
+    one activation width: no register with a hand-issued load in flight is touched, no scratch."""
+    total = 0
+    for src in chk.SOURCES:
+        nk, problems, _ = chk.check_file(asm[(src, ab)])
+        assert problems == [], problems[:5]
+        total += nk
+    assert total >= 60
