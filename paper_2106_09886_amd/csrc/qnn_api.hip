@@ -219,6 +219,7 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     BranchArgs g;
     g.A = A; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = partial_buffer(acc, out_f32, e);
+    g.out_flags = (acc != nullptr ? 1u : 0u) | (out_f32 != nullptr ? 2u : 0u);
     g.planes_out = e.planes; g.out_bits = e.bits;
     g.rows = (int)M; g.N = (int)N; g.Cw = (int)((K + 31) / 32); g.H = H; g.W = W; g.C = 0;
     g.gather_rows = (gather != nullptr) ? 1 : 0;
@@ -270,6 +271,7 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
         g.lds_partials = 1;
         if (g.rows_per_wave > kLdsPartialRows) g.rows_per_wave = kLdsPartialRows;
     }
+    set_divisors(g, /*output_image=*/g.gather_rows != 0);
     return from_hip(k_gemm[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -294,6 +296,7 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     BranchArgs g;
     g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = partial_buffer(acc, out_f32, e);
+    g.out_flags = (acc != nullptr ? 1u : 0u) | (out_f32 != nullptr ? 2u : 0u);
     g.planes_out = e.planes; g.out_bits = e.bits;
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
@@ -303,6 +306,7 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles, conv_passes(ab, wb, g.Cw), conv_group(ab, wb, g.Cw)), Cout),
                                           Cout, e);
     g.grid_blocks = wave_grid_blocks(g);
+    set_divisors(g);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -345,6 +349,7 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             BranchArgs g;
             g.A = planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
             g.partial = partial_buffer(acc, out_f32, e);
+    g.out_flags = (acc != nullptr ? 1u : 0u) | (out_f32 != nullptr ? 2u : 0u);
             g.planes_out = e.planes; g.out_bits = e.bits;
             g.rows = (int)rows; g.N = (int)Cout; g.Cw = 1; g.H = (int)H; g.W = (int)W; g.C = (int)C;
             g.kconst = (int)((((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
@@ -354,6 +359,7 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
                                                   Cout, e);
             g.grid_blocks = wave_grid_blocks(g);
+            set_divisors(g);
             return from_hip(k_conv_small[ab - 1](g, wb, (hipStream_t)stream));
         }
         st = qnn_encode_pack(x_codes, code_bytes, rows, C, ab, planes, nullptr, 0, stream);
@@ -642,6 +648,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     BranchArgs g;
     g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = partial_buffer(acc, out_f32, e);
+    g.out_flags = (acc != nullptr ? 1u : 0u) | (out_f32 != nullptr ? 2u : 0u);
     g.planes_out = e.planes; g.out_bits = e.bits;
     g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
@@ -673,6 +680,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
             if (rpw2 > rows) rpw2 = rows;
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw2, Cout), Cout, e);
             g.grid_blocks = wave_grid_blocks(g);
+            set_divisors(g, true);
             return from_hip(k_conv_window[ab - 1](g, wb, (hipStream_t)stream));
         }
     }
@@ -727,10 +735,12 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
             return QNN_EUNSUPPORTED;
         g.rows_per_wave = (int)rpw;
         g.xcd_ranges = 0; g.grid_blocks = 0;          // two-dimensional launch: plain block numbers
+        set_divisors(g, true);
         return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
     }
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave((int)rpw, Cout), Cout, e);
     g.grid_blocks = wave_grid_blocks(g);
+    set_divisors(g, true);
     return from_hip(k_conv_general[ab - 1](g, wb, (hipStream_t)stream));
 }
 

@@ -44,12 +44,11 @@ struct WavePos {
     int index;     // wavefront number in the grid
 };
 template <bool XCD_RANGES = false>                   // number the blocks by xcd_block()
-__device__ __forceinline__ WavePos wave_pos(int col_tiles, int xcd_ranges = 0, uint32_t grid_blocks = 0) {
+__device__ __forceinline__ WavePos wave_pos(const FastDiv &col_tiles, int xcd_ranges = 0, uint32_t grid_blocks = 0) {
     WavePos p;
     const uint32_t block = XCD_RANGES ? xcd_block(xcd_ranges, grid_blocks) : blockIdx.x;
-    p.index = __builtin_amdgcn_readfirstlane((int)(block * (blockDim.x >> 6) + (threadIdx.x >> 6)));
-    p.ct = p.index % col_tiles;
-    p.rb = p.index / col_tiles;
+    p.index = __builtin_amdgcn_readfirstlane((int)(block * 4u + (threadIdx.x >> 6)));   // blocks of four wavefronts
+    fast_divmod((uint32_t)p.index, col_tiles, p.rb, p.ct);
     return p;
 }
 
@@ -134,9 +133,9 @@ struct RowWalk {
 __device__ __forceinline__ RowWalk row_walk_at(const BranchArgs &g, int r, uint32_t row_bytes) {
     const ConvGeom &q = g.geo;
     RowWalk w;
-    const int img = r / (q.Ho * q.Wo), rem = r - img * q.Ho * q.Wo;
-    w.oh = __builtin_amdgcn_readfirstlane(rem / q.Wo);
-    w.ow = __builtin_amdgcn_readfirstlane(rem - (rem / q.Wo) * q.Wo);
+    int line, img;                                  // output row counted over all images
+    fast_divmod((uint32_t)r, g.div_w, line, w.ow);
+    fast_divmod((uint32_t)line, g.div_h, img, w.oh);
     w.off = __builtin_amdgcn_readfirstlane((uint32_t)((img * g.H + w.oh * q.sh) * g.W + w.ow * q.sw) * row_bytes);
     return w;
 }
@@ -275,7 +274,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     static_assert(!(GATHER && LDSP), "not combined");
     int *const slab = PartialSlab<LDSP>::mine();
-    const WavePos wp = wave_pos(g.col_tiles);
+    const WavePos wp = wave_pos(g.div_tiles);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
     const int r0 = active ? wp.rb * g.rows_per_wave : 0;
@@ -337,8 +336,7 @@ __global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
     const int lane = (int)(threadIdx.x & 63);
     WavePos wp;
     wp.index = (int)blockIdx.x * 4 + wv;
-    wp.ct = (int)(blockIdx.x % (unsigned)g.col_tiles);
-    wp.rb = (int)(blockIdx.x / (unsigned)g.col_tiles);
+    fast_divmod(blockIdx.x, g.div_tiles, wp.rb, wp.ct);
     const int r0 = wp.rb * g.rows_per_wave;                   // rows per BLOCK here (<= kSplitRowsMax)
     const int r1 = min(g.rows, r0 + g.rows_per_wave);
     const int n = wp.ct * 64 + lane;
@@ -446,6 +444,7 @@ struct ConvCtx {
             if (ok) stage_ok |= 1u << st;
             stage_off[st] = (uint32_t)((ok ? dh * W : 0) + dw) * pixel_bytes();
         }
+        stage_ok = spin(stage_ok);
     }
 
     template <int ST>
@@ -487,17 +486,17 @@ struct ConvCtx {
 #pragma unroll
             for (int x = 0; x < P; ++x) {
                 tap<ST, true>(b, x, 1);
-                if (!(x == 0 && (edge & 1u))) tap<ST, false>(b, x, 0);
-                if (!(x == P - 1 && (edge & 2u))) tap<ST, false>(b, x, 2);
+                if (!(x == 0 && sflag(edge, 1u))) tap<ST, false>(b, x, 0);
+                if (!(x == P - 1 && sflag(edge, 2u))) tap<ST, false>(b, x, 2);
             }
-        } else if (stage_ok & (1u << ST)) {
+        } else if (sflag(stage_ok, 1u << ST)) {
 #pragma unroll
             for (int x = 0; x < P; ++x)               // output pixel of the group
 #pragma unroll
                 for (int i = 0; i < GT; ++i) {
                     const int dw = dw_of<ST>(i);
                     // skip the tap that hangs over the left / right image border
-                    const bool skip = (x == 0 && dw < 0 && (edge & 1u)) || (x == P - 1 && dw > 0 && (edge & 2u));
+                    const bool skip = (x == 0 && dw < 0 && sflag(edge, 1u)) || (x == P - 1 && dw > 0 && sflag(edge, 2u));
                     if (!skip) tap<ST, false>(b, x, i);
                 }
         }
@@ -512,11 +511,11 @@ __device__ __forceinline__ PixelPos next_pixel(PixelPos p, int H, int W) {
     return p;
 }
 
-__device__ __forceinline__ PixelPos pixel_pos(int r, int H, int W) {
-    // integer division runs on the vector ALU; bring the (wave-uniform) results back to SGPRs
+__device__ __forceinline__ PixelPos pixel_pos(int r, const BranchArgs &g) {
     PixelPos p;
-    p.ow = __builtin_amdgcn_readfirstlane(r % W);
-    p.oh = __builtin_amdgcn_readfirstlane((r / W) % H);
+    int line, img;
+    fast_divmod((uint32_t)r, g.div_w, line, p.ow);
+    fast_divmod((uint32_t)line, g.div_h, img, p.oh);
     return p;
 }
 
@@ -527,22 +526,23 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
     return nh * nw;
 }
 
-// Pipelined pixels ra .. rb-1 of one chunk, all in image row oh, rb - ra >= P.  left_first:
-// pixel ra is in column 0; right_last: pixel rb-1 is in column W-1.  Pixels are taken in
+// Pipelined pixels ra .. rb-1 of one chunk, all in image row oh, rb - ra >= P.  left_first = 1:
+// pixel ra is in column 0; right_last = 2: pixel rb-1 is in column W-1 (else 0; flag words, made
+// where the comparison is, see sflag()).  Pixels are taken in
 // groups of P; if P does not divide the run, the last group is placed at rb-P and recomputes
 // pixels of the group before it (P > 1 is used for single-chunk shapes only, where a
 // recomputed pixel is simply stored again with the same value).
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c,
                                                    const BranchArgs &g, const OV &ov, int r0, int ra,
-                                                   int rb, int oh, bool left_first, bool right_last,
+                                                   int rb, int oh, uint32_t left_first, uint32_t right_last,
                                                    bool first, bool last) {
     constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
     static_assert(P == 1 || SINGLE, "pixel groups only where a chunk pass is the whole product");
     c.set_image_row(oh, g.H, g.W);
     const int krow = (3 - (oh == 0 ? 1 : 0) - (oh == g.H - 1 ? 1 : 0)) * g.kconst;   // per valid column
     const uint32_t pb = c.pixel_bytes();
-    const uint32_t edge_first = left_first ? 1u : 0u, edge_last = right_last ? 2u : 0u;
+    const uint32_t edge_first = left_first, edge_last = right_last;
     const uint32_t off_a = (uint32_t)ra * pb + (uint32_t)c.c0 * 4u;
     const int r_last = rb - P;                       // start of the last group
     c.off_cur = off_a;
@@ -564,7 +564,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
         uint32_t edge = 0u;
         if (r == ra) edge |= edge_first;
         if (r == r_last) edge |= edge_last;
-        c.edge = edge;
+        c.edge = edge = spin(edge);
         // what earlier chunk passes left for this pixel, asked for before its products are formed
         int prev = 0;
         if constexpr (!SINGLE) {
@@ -659,7 +659,7 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
                 for (int j = 0; j < CWT; ++j) c.w[t][q][j] = wl[(t * WB + q) * CWT + j];
     }
     const int special[4] = {0, g.W, g.rows - 1 - g.W, g.rows - 1};
-    PixelPos pos = pixel_pos(r0, g.H, g.W);
+    PixelPos pos = pixel_pos(r0, g);
     int r = r0;
     while (r < r1) {
         const int row_end = r - pos.ow + g.W;            // first pixel of the next image row
@@ -674,7 +674,8 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
             conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
             stop = r + 1;
         } else {
-            conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, pos.ow == 0, stop == row_end, first, last);
+            conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, spin(pos.ow == 0 ? 1u : 0u),
+                               spin(stop == row_end ? 2u : 0u), first, last);
         }
         pos.ow += stop - r;
         r = stop;
@@ -698,7 +699,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 #pragma unroll
             for (int j = 0; j < CWT; ++j)
                 w[t][q][j] = (c0 + j < Cw) ? g.Wt[((nload * 9 + t) * WB + q) * Cw + c0 + j] : 0u;
-    PixelPos pos = pixel_pos(r0, g.H, g.W);
+    PixelPos pos = pixel_pos(r0, g);
     for (int r = r0; r < r1; ++r) {
         int part[AB + WB - 1];
 #pragma unroll
@@ -736,7 +737,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
-    const WavePos wp = wave_pos<XR>(g.col_tiles, 1, g.grid_blocks);
+    const WavePos wp = wave_pos<XR>(g.div_tiles, 1, g.grid_blocks);
     // a wavefront past the last row block keeps an empty row range
     const bool active = (int64_t)wp.rb * g.rows_per_wave < g.rows;
     const int r0 = active ? wp.rb * g.rows_per_wave : 0;

@@ -372,8 +372,8 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     // forward: blocks numbered per XCD; the transposed launch is two-dimensional and keeps blockIdx
     const uint32_t block = TR ? blockIdx.x : xcd_block(g.xcd_ranges, g.grid_blocks);
     const int wave = __builtin_amdgcn_readfirstlane((int)(block * 4 + (threadIdx.x >> 6)));
-    const int ct = wave % g.col_tiles;
-    const int rb = wave / g.col_tiles;
+    int ct, rb;
+    fast_divmod((uint32_t)wave, g.div_tiles, rb, ct);
     const int lane = (int)(threadIdx.x & 63);
     const int n = ct * 64 + lane;
     const int nload = (n < g.N) ? n : g.N - 1;         // lanes past N redo column N-1 (same value, same address)
@@ -396,9 +396,9 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
         return;
     }
     // position of the first output pixel (integer division runs on the vector ALU)
-    const int ow0 = __builtin_amdgcn_readfirstlane(r0 % q.Wo);
-    const int oh0 = __builtin_amdgcn_readfirstlane((r0 / q.Wo) % q.Ho);
-    const int n0 = __builtin_amdgcn_readfirstlane(r0 / (q.Wo * q.Ho));
+    int ow0, oh0, n0, line0;                            // divisions by the output image size: scalar unit
+    fast_divmod((uint32_t)r0, g.div_w, line0, ow0);
+    fast_divmod((uint32_t)line0, g.div_h, n0, oh0);
     const uint32_t pixel_bytes = (uint32_t)(AB * Cw) * 4u;
 
     GenCtx<AB, WB, CWT, TT> c;
@@ -515,8 +515,8 @@ template <int AB, int WB, int KWP, bool EMIT>
 __global__ __launch_bounds__(256) void conv_window_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges, g.grid_blocks) * 4 + (threadIdx.x >> 6)));
-    const int ct = wave % g.col_tiles;
-    const int rb = wave / g.col_tiles;
+    int ct, rb;
+    fast_divmod((uint32_t)wave, g.div_tiles, rb, ct);
     if ((int64_t)rb * g.rows_per_wave >= g.rows) return;
     const int r0 = rb * g.rows_per_wave;
     const int r1 = min(g.rows, r0 + g.rows_per_wave);

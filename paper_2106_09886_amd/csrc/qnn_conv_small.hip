@@ -54,8 +54,8 @@ template <int AB, int WB, bool EMIT>
 __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const int wave = __builtin_amdgcn_readfirstlane((int)(xcd_block(g.xcd_ranges, g.grid_blocks) * 4 + (threadIdx.x >> 6)));
-    const int ct = wave % g.col_tiles;
-    const int rb = wave / g.col_tiles;
+    int ct, rb;
+    fast_divmod((uint32_t)wave, g.div_tiles, rb, ct);
     const bool active = (int64_t)rb * g.rows_per_wave < g.rows;
     if (!active) return;
     const int r0 = rb * g.rows_per_wave;
@@ -90,8 +90,9 @@ __global__ __launch_bounds__(256) void conv_small_kernel(const BranchArgs g) {
 
     const OV ov = make_out_view<OV>(g, r0, r1, nload, sc, ct);
 
-    int ow = __builtin_amdgcn_readfirstlane(r0 % g.W);
-    int oh = __builtin_amdgcn_readfirstlane((r0 / g.W) % g.H);
+    int ow, oh, line0, img0;
+    fast_divmod((uint32_t)r0, g.div_w, line0, ow);
+    fast_divmod((uint32_t)line0, g.div_h, img0, oh);
     const uint64_t base = (uint64_t)g.A;
     constexpr uint32_t kPixelBytes = AB * 4u;
     SRun<AB> bufA, bufB;                                   // the pixel's AB consecutive words, in SGPRs

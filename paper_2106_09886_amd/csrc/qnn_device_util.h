@@ -28,6 +28,34 @@ __device__ __forceinline__ void popc_set(int &part, uint32_t x) {
     asm volatile("v_bcnt_u32_b32 %0, %1, 0" : "=v"(part) : "v"(x));
 }
 
+// A wave-uniform flag test that stays on the scalar unit.  The word is pinned to an SGPR at the
+// point of use (an empty asm the optimiser cannot look through), so the comparison is neither
+// hoisted out of the loop nor kept as a lane mask across basic blocks -- testing such a mask again
+// costs two VECTOR instructions (a select and a compare) every time.
+__device__ __forceinline__ bool sflag(uint32_t word_in, uint32_t mask) {
+    uint32_t word = (uint32_t)__builtin_amdgcn_readfirstlane((int)word_in);   // no code if it is in an SGPR already
+    asm volatile("" : "+s"(word));
+    return (word & mask) != 0u;
+}
+// The other half of the same trick: a flag word built from comparisons is pinned right where it is
+// built, so that later tests see an opaque integer and not the comparisons behind it.
+__device__ __forceinline__ uint32_t spin(uint32_t word_in) {
+    uint32_t word = (uint32_t)__builtin_amdgcn_readfirstlane((int)word_in);
+    asm volatile("" : "+s"(word));
+    return word;
+}
+
+// n / f.d and n % f.d for a wave-uniform n < 2^31 (see FastDiv): scalar-unit instructions only.
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv &f) {
+    const uint32_t q = __umulhi(n, f.m) >> f.sh;
+    return f.m != 0u ? q : n;
+}
+__device__ __forceinline__ void fast_divmod(uint32_t n, const FastDiv &f, int &quot, int &rem) {
+    const uint32_t q = fast_div(n, f);
+    quot = (int)q;
+    rem = (int)(n - q * f.d);
+}
+
 // N consecutive words at a per-lane address (4-byte aligned only): 16- and 8-byte vector loads
 // where N allows.  A lane's weight words are contiguous in memory while different lanes are a
 // whole filter apart, so every load instruction touches 64 cache lines whatever its width:
@@ -126,9 +154,9 @@ __device__ __forceinline__ OV make_out_view(const BranchArgs &g, int r0, int r1,
     }
     const int64_t first = (int64_t)r0 * g.N;
     const uint32_t bytes = (uint32_t)(r1 - r0) * (uint32_t)g.N * 4u;    // < 2^31, checked on the host
-    v.flags = (g.acc != nullptr ? 1u : 0u) | (g.out != nullptr ? 2u : 0u);
+    v.flags = g.out_flags;                                              // set by the host: a plain kernel argument
     v.d0 = make_rsrc((void *)(g.partial + first), bytes);               // partial == acc if present, else out
-    v.d1 = make_rsrc((v.flags & 2u) ? (void *)(g.out + first) : (void *)(g.partial + first), bytes);
+    v.d1 = make_rsrc((g.out != nullptr) ? (void *)(g.out + first) : (void *)(g.partial + first), bytes);
     v.row_bytes = (uint32_t)g.N * 4u;
     v.col_bytes = nload * 4;
     v.sc = sc;
@@ -148,10 +176,10 @@ __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bo
         }
     }
     const float y = (float)val * v.sc;
-    if (v.flags & 1u) {
+    if (sflag(v.flags, 1u)) {
         __builtin_amdgcn_raw_buffer_store_b32(val, v.d0, v.col_bytes, soff, 0);
-        if (v.flags & 2u) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d1, v.col_bytes, soff, 0);
-    } else if (v.flags & 2u) {
+        if (sflag(v.flags, 2u)) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d1, v.col_bytes, soff, 0);
+    } else if (sflag(v.flags, 2u)) {
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
     }
     if constexpr (std::is_same<OV, OutViewEmit>::value) {

@@ -16,6 +16,28 @@ struct ConvGeom {
     int transposed;       // 0: convolution, 1: transposed convolution
 };
 
+// Division of a wave-uniform number n < 2^31 by a launch constant d >= 1 without the vector ALU
+// (there is no integer divide instruction; the compiler's expansion is some 25 vector
+// instructions per division, and a wavefront's set-up has four of them).  The host prepares
+// m = ceil(2^(31+L) / d), L = ceil(log2 d); then n / d = (n * m) >> (31 + L) exactly, because the
+// error n * (m*d - 2^(31+L)) stays below 2^(31+L) for n < 2^31.  The kernel needs one
+// s_mul_hi_u32 and a shift.  d = 1 is coded as m = 0.
+struct FastDiv {
+    uint32_t d, m, sh;
+};
+inline FastDiv fast_div_for(int64_t d_in) {
+    FastDiv f;
+    const uint64_t d = d_in < 1 ? 1 : (uint64_t)d_in;
+    f.d = (uint32_t)d;
+    if (d == 1) { f.m = 0; f.sh = 0; return f; }
+    int L = 0;
+    while (((uint64_t)1 << L) < d) ++L;                        // L = ceil(log2 d) >= 1
+    const uint64_t two_k = (uint64_t)1 << (31 + L);            // d < 2^31, so L <= 31
+    f.m = (uint32_t)((two_k + d - 1) / d);                     // < 2^32 (= 2^31 for a power of two)
+    f.sh = (uint32_t)(L - 1);                                  // after taking the high word
+    return f;
+}
+
 // Arguments of the branch kernels (GEMM and 3x3 convolution).  All sizes were range
 // checked on the host; index arithmetic inside the kernels is 32-bit except for the
 // row base of the outputs.
@@ -26,6 +48,8 @@ struct BranchArgs {
     const float *scale;   // fp32 [N] or nullptr
     float *out;           // fp32 out [rows][N] or nullptr
     int32_t *partial;     // where partial sums of a multi-chunk product live (acc, else out)
+    uint32_t out_flags;   // bit 0: acc != nullptr, bit 1: out != nullptr (the kernels test this word on the
+                          // scalar unit instead of comparing the pointers)
     int rows;             // GEMM rows / output pixels
     int N;                // output columns / filters
     int Cw;               // words per (row, plane)
@@ -48,7 +72,15 @@ struct BranchArgs {
                           // uint32 [rows][out_bits][ceil(N/32)] (the next layer's activations)
     int out_bits;
     ConvGeom geo;         // general convolution only
+    FastDiv div_tiles;    // col_tiles
+    FastDiv div_w, div_h; // W and H (3x3 convolution), Wo and Ho (general convolution, strided rows)
 };
+// fills the division constants from the fields they belong to (call last, before the launch)
+inline void set_divisors(BranchArgs &g, bool output_image = false) {
+    g.div_tiles = fast_div_for(g.col_tiles);
+    g.div_w = fast_div_for(output_image ? g.geo.Wo : g.W);
+    g.div_h = fast_div_for(output_image ? g.geo.Ho : g.H);
+}
 
 constexpr int kLdsPartialRows = 24;   // rows per wavefront whose partial sums the GEMM kernel keeps in LDS
 
