@@ -356,8 +356,11 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             g.col_tiles = (int)((Cout + 63) / 64);
             g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0; g.xcd_ranges = xcd_ranges_for(false);
             g.trace = nullptr; g.trace_waves = 0;
-            g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_rows_per_wave(rows, g.col_tiles, 16), Cout),
-                                                  Cout, e);
+            // Short wavefronts that stream through the SIMDs: measured on the 16 x 224 x 224 x 3 -> 64
+            // layer, 16 pixels each are best with int32 + fp32 outputs (95 us; 123 us at 196 pixels, where
+            // four wavefronts per SIMD are all there is) and 28 with emitted planes only (99.5 us).
+            const int small_rpw = tuning().rows_per_wave > 0 ? tuning().rows_per_wave : (e.bits != 0 ? 28 : 16);
+            g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(small_rpw, Cout), Cout, e);
             g.grid_blocks = wave_grid_blocks(g);
             set_divisors(g);
             return from_hip(k_conv_small[ab - 1](g, wb, (hipStream_t)stream));
