@@ -110,7 +110,7 @@ struct OutViewEmit : OutView {
     int shift;                   // 32 - out_bits: the index is handled at the top of a register
     // per-lane constants; a lane whose column does not exist (it repeats column N-1) has all
     // three zero, which makes its index zero = all plane bits zero
-    float fmax;                  // H - 1
+    float fmax;                  // H - 1/2: floor(min(|y|/2, fmax)) is the clamped magnitude index
     uint32_t sel_pos, sel_neg;   // H and H - 1, shifted to the top
     int word_off;                // byte offset inside a row of the word this lane stores (lane 2k+h:
                                  // half h of plane out_bits-1-k), or -1 if the lane stores nothing
@@ -121,16 +121,98 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t by
     return __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, 0x00020000);
 }
 
-// Step K of the plane emission.  The index of every lane sits at the top of `top`; doubling it
-// shifts out one plane per step, high plane first, and the carry-out of the 64 lanes IS that
-// plane's two packed words (one vector op per plane).  Lanes 2K and 2K+1 of `mine` receive the
-// low and high word of step K's plane, which is plane out_bits-1-K.
+// Plane emission.  The index of every lane sits at the top of `top`; doubling it shifts out one
+// plane per step, high plane first, and the carry-out of the 64 lanes IS that plane's two packed
+// words (one vector op per plane).  All N doublings are issued first, each carry mask into its own
+// SGPR pair, then lanes 2k and 2k+1 of the result receive the low and high word of step k's plane
+// (plane out_bits-1-k): the writes no longer wait on the mask just produced, and the register that
+// held the indices is dead by then and takes the words itself.
+// The same one step at a time, for code that is short of scalar registers (the branch kernels'
+// epilogue: holding all masks at once cost them 1 %): step K of the emission, lanes 2K and 2K+1 of
+// `mine` receive the two words of plane out_bits-1-K.
 template <int K>
 __device__ __forceinline__ void emit_step(uint32_t &top, int &mine) {
     uint64_t m;
     asm volatile("v_add_co_u32 %0, %1, %0, %0" : "+v"(top), "=s"(m));
-    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(mine) : "s"((uint32_t)m), "n"(2 * K));
-    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(mine) : "s"((uint32_t)(m >> 32)), "n"(2 * K + 1));
+    asm volatile("v_writelane_b32 %0, %1, %2\n\tv_writelane_b32 %0, %3, %4"
+                 : "+v"(mine) : "s"((uint32_t)m), "n"(2 * K), "s"((uint32_t)(m >> 32)), "n"(2 * K + 1));
+}
+
+template <int N>
+__device__ __forceinline__ int emit_planes(uint32_t top);
+// One asm statement for the N doublings and one for the 2N lane writes: between separate asm
+// statements the compiler pads with a wait state each, which costs the wavefront an issue slot per
+// instruction.  (No wait state is required here: the masks are read as data, not as lane selects.)
+template <>
+__device__ __forceinline__ int emit_planes<1>(uint32_t top) {
+    uint64_t m0;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0" : "+v"(top), "=&s"(m0));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<2>(uint32_t top) {
+    uint64_t m0, m1;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<3>(uint32_t top) {
+    uint64_t m0, m1, m2;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3\n\tv_writelane_b32 %0, %5, 4\n\tv_writelane_b32 %0, %6, 5" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<4>(uint32_t top) {
+    uint64_t m0, m1, m2, m3;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3\n\tv_writelane_b32 %0, %5, 4\n\tv_writelane_b32 %0, %6, 5\n\tv_writelane_b32 %0, %7, 6\n\tv_writelane_b32 %0, %8, 7" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<5>(uint32_t top) {
+    uint64_t m0, m1, m2, m3, m4;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3\n\tv_writelane_b32 %0, %5, 4\n\tv_writelane_b32 %0, %6, 5\n\tv_writelane_b32 %0, %7, 6\n\tv_writelane_b32 %0, %8, 7\n\tv_writelane_b32 %0, %9, 8\n\tv_writelane_b32 %0, %10, 9" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<6>(uint32_t top) {
+    uint64_t m0, m1, m2, m3, m4, m5;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0\n\tv_add_co_u32 %0, %6, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3\n\tv_writelane_b32 %0, %5, 4\n\tv_writelane_b32 %0, %6, 5\n\tv_writelane_b32 %0, %7, 6\n\tv_writelane_b32 %0, %8, 7\n\tv_writelane_b32 %0, %9, 8\n\tv_writelane_b32 %0, %10, 9\n\tv_writelane_b32 %0, %11, 10\n\tv_writelane_b32 %0, %12, 11" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "s"((uint32_t)m5), "s"((uint32_t)(m5 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<7>(uint32_t top) {
+    uint64_t m0, m1, m2, m3, m4, m5, m6;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0\n\tv_add_co_u32 %0, %6, %0, %0\n\tv_add_co_u32 %0, %7, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3\n\tv_writelane_b32 %0, %5, 4\n\tv_writelane_b32 %0, %6, 5\n\tv_writelane_b32 %0, %7, 6\n\tv_writelane_b32 %0, %8, 7\n\tv_writelane_b32 %0, %9, 8\n\tv_writelane_b32 %0, %10, 9\n\tv_writelane_b32 %0, %11, 10\n\tv_writelane_b32 %0, %12, 11\n\tv_writelane_b32 %0, %13, 12\n\tv_writelane_b32 %0, %14, 13" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "s"((uint32_t)m5), "s"((uint32_t)(m5 >> 32)), "s"((uint32_t)m6), "s"((uint32_t)(m6 >> 32)));
+    return mine;
+}
+template <>
+__device__ __forceinline__ int emit_planes<8>(uint32_t top) {
+    uint64_t m0, m1, m2, m3, m4, m5, m6, m7;
+    asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0\n\tv_add_co_u32 %0, %6, %0, %0\n\tv_add_co_u32 %0, %7, %0, %0\n\tv_add_co_u32 %0, %8, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6), "=&s"(m7));
+    int mine = (int)top;
+    asm volatile("v_writelane_b32 %0, %1, 0\n\tv_writelane_b32 %0, %2, 1\n\tv_writelane_b32 %0, %3, 2\n\tv_writelane_b32 %0, %4, 3\n\tv_writelane_b32 %0, %5, 4\n\tv_writelane_b32 %0, %6, 5\n\tv_writelane_b32 %0, %7, 6\n\tv_writelane_b32 %0, %8, 7\n\tv_writelane_b32 %0, %9, 8\n\tv_writelane_b32 %0, %10, 9\n\tv_writelane_b32 %0, %11, 10\n\tv_writelane_b32 %0, %12, 11\n\tv_writelane_b32 %0, %13, 12\n\tv_writelane_b32 %0, %14, 13\n\tv_writelane_b32 %0, %15, 14\n\tv_writelane_b32 %0, %16, 15" : "+v"(mine) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "s"((uint32_t)m5), "s"((uint32_t)(m5 >> 32)), "s"((uint32_t)m6), "s"((uint32_t)(m6 >> 32)), "s"((uint32_t)m7), "s"((uint32_t)(m7 >> 32)));
+    return mine;
+}
+
+// floor of a non-negative binary32 value as an integer, one instruction
+__device__ __forceinline__ int floor_to_int(float t) {
+    int f;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(f) : "v"(t));
+    return f;
 }
 
 template <class OV>
@@ -143,13 +225,13 @@ __device__ __forceinline__ OV make_out_view(const BranchArgs &g, int r0, int r1,
         const uint32_t H = 1u << (g.out_bits - 1);
         v.bits = g.out_bits;
         v.shift = 32 - g.out_bits;
-        v.fmax = n_ok ? (float)(H - 1u) : 0.0f;
+        v.fmax = n_ok ? (float)(H - 1u) + 0.5f : 0.0f;
         v.sel_pos = n_ok ? 0x80000000u : 0u;
         v.sel_neg = n_ok ? (H - 1u) << (32 - g.out_bits) : 0u;
         v.prow_bytes = (uint32_t)(g.out_bits * Nw) * 4u;
         v.dp = make_rsrc((void *)(g.planes_out + (int64_t)r0 * g.out_bits * Nw), (uint32_t)(r1 - r0) * v.prow_bytes);
         const int word = 2 * ct + (lane & 1);
-        const int step = lane >> 1;                  // see emit_step: step k carries plane out_bits-1-k
+        const int step = lane >> 1;                  // see emit_planes: step k carries plane out_bits-1-k
         v.word_off = (step < g.out_bits && word < Nw) ? ((g.out_bits - 1 - step) * Nw + word) * 4 : -1;
     }
     const int64_t first = (int64_t)r0 * g.N;
@@ -183,10 +265,10 @@ __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bo
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, y), v.d0, v.col_bytes, soff, 0);
     }
     if constexpr (std::is_same<OV, OutViewEmit>::value) {
-        // Table 2 rule on y (see the top of this file), index at the top of the register
-        float t = __builtin_floorf(__builtin_fabsf(y) * 0.5f);
-        t = (t <= v.fmax) ? t : v.fmax;
-        uint32_t top = ((uint32_t)t << v.shift) ^ ((y > 0.0f) ? v.sel_pos : v.sel_neg);
+        // Table 2 rule on y (see the top of this file), index at the top of the register:
+        // f = floor(min(|y|/2, H - 1/2)) (the minimum also catches inf and NaN), u = f xor (H or H-1)
+        const int f = floor_to_int(__builtin_fminf(__builtin_fabsf(y) * 0.5f, v.fmax));
+        uint32_t top = ((uint32_t)f << v.shift) ^ ((y > 0.0f) ? v.sel_pos : v.sel_neg);
         int mine = (int)top;                         // every lane that stores is overwritten below
         int b = v.bits;
         asm volatile("" : "+s"(b));                  // decided here, per call, on the scalar unit

@@ -25,20 +25,10 @@ namespace {
 template <int BITS>
 __device__ __forceinline__ uint32_t round_odd_index(float y) {
     constexpr uint32_t H = 1u << (BITS - 1);
-    constexpr float FMAX = (float)(H - 1u);
-    float t = floorf(fabsf(y) * 0.5f);
-    t = (t <= FMAX) ? t : FMAX;                 // also catches inf / nan
-    return (uint32_t)t ^ ((y > 0.0f) ? H : H - 1u);
-}
-
-// Steps 0 .. BITS-1 of the plane emission (emit_step of qnn_device_util.h): lanes 2k, 2k+1 of
-// `mine` receive the two words of plane BITS-1-k.
-template <int BITS, int K = 0>
-__device__ __forceinline__ void emit_all(uint32_t &top, int &mine) {
-    if constexpr (K < BITS) {
-        emit_step<K>(top, mine);
-        emit_all<BITS, K + 1>(top, mine);
-    }
+    constexpr float FMAX = (float)(H - 1u) + 0.5f;
+    // floor(min(|y|/2, H - 1/2)): the minimum clamps, and returns its second operand for inf / nan
+    const int f = floor_to_int(__builtin_fminf(__builtin_fabsf(y) * 0.5f, FMAX));
+    return (uint32_t)f ^ ((y > 0.0f) ? H : H - 1u);
 }
 
 // U work items (pixel, 64-channel group) per loop trip: all their loads are issued before any
@@ -116,9 +106,7 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
             if (planes != nullptr) {
                 // index at the top of the register; each doubling shifts out one plane, high plane
                 // first, as the carry mask of the wavefront = the plane's two packed words
-                uint32_t top = uidx << (32 - BITS);
-                int mine = (int)top;                          // every lane that stores is overwritten
-                emit_all<BITS>(top, mine);
+                const int mine = emit_planes<BITS>(uidx << (32 - BITS));
                 const int p = BITS - 1 - (lane >> 1), h = lane & 1;
                 if (lane < 2 * BITS && 2 * cg[u] + h < Cw)
                     planes[(pix[u] * BITS + p) * (int64_t)Cw + 2 * cg[u] + h] = (uint32_t)mine;
@@ -131,52 +119,72 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
 // y[64 i ..], i.e. (pixel i / (C/64), channel group i % (C/64)), and its plane words are
 // planes[(pixel*BITS + p)*Cw + 2*group + h].  All addressing is wave-uniform (scalar unit) plus
 // a per-lane constant, through buffer descriptors; the vector ALU only sees the rule itself.
-template <typename CodeT, int BITS, int U>
-__global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restrict__ y, int64_t items, int cgroups,
-                                                           float premul, int hrelu, CodeT *__restrict__ codes,
-                                                           uint32_t *__restrict__ planes) {
+// FRONT: the real-valued front end (clip, multiply) before the rule; the plain re-encoder skips it.
+// CODES / PLANES: which outputs are written (compile-time, so a trip carries no test for them).
+// Everything but the rule itself is kept on the scalar unit: item numbers are 32-bit (the host sends
+// larger problems to the general kernel), a full trip of U items has no per-item tests, and the
+// pixel / channel-group position is divided out once per trip with the host's constants and then
+// stepped.  Per item the vector ALU sees 7 instructions for the rule and 3 per plane.
+template <typename CodeT, int BITS, int U, bool FRONT, bool CODES, bool PLANES>
+__global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restrict__ y, int items, int cgroups,
+                                                           FastDiv div_groups, float premul, int hrelu,
+                                                           CodeT *__restrict__ codes, uint32_t *__restrict__ planes) {
     constexpr int VMAX = (1 << BITS) - 1;
     const int lane = (int)(threadIdx.x & 63);
     const int Cw = 2 * cgroups;
-    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) +
-                          __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // wave-uniform
-    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
-    // lane 2k+h stores half h of plane BITS-1-k (see emit_step)
+    const int wave0 = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4u + (threadIdx.x >> 6)));
+    const int nwaves = (int)gridDim.x * 4;
+    // lane 2k+h stores half h of plane BITS-1-k (see emit_planes)
     const int store_off = ((BITS - 1 - (lane >> 1)) * Cw + (lane & 1)) * 4;
     const bool stores = lane < 2 * BITS;
-    for (int64_t it0 = wave0 * U; it0 < items; it0 += nwaves * U) {
-        const int n = (int)((items - it0 < U) ? items - it0 : U);           // items of this trip, wave-uniform
-        const __amdgpu_buffer_rsrc_t src = make_rsrc((void *)(y + it0 * 64), (uint32_t)n * 256u);
+    const uint32_t pixel_bytes = (uint32_t)(BITS * Cw) * 4u;             // plane words of one pixel
+    // trips of U items; a wavefront takes every nwaves-th trip
+    for (int it0 = wave0 * U; it0 < items; it0 += nwaves * U) {
+        const int n = __builtin_amdgcn_readfirstlane(min(items - it0, U));
+        const __amdgpu_buffer_rsrc_t src = make_rsrc((void *)(y + (int64_t)it0 * 64), (uint32_t)n * 256u);
         float v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            v[u] = 0.0f;
-            if (u < n) v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4 + u * 256, 0, 0));
+        for (int u = 0; u < U; ++u)         // reads past the descriptor's n*256 bytes return 0
+            v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, u * 256, 0));
+        int pix, cg;
+        fast_divmod((uint32_t)it0, div_groups, pix, cg);
+        // outputs of the trip through descriptors based at its first item; offsets are stepped
+        __amdgpu_buffer_rsrc_t dc, dp;
+        if constexpr (CODES) dc = make_rsrc((void *)(codes + (int64_t)it0 * 64), (uint32_t)n * 64u * (uint32_t)sizeof(CodeT));
+        uint32_t poff = 0u;                                              // bytes from the first item's plane words
+        if constexpr (PLANES) {
+            // the trip spans at most U/cgroups + 2 pixels
+            dp = make_rsrc((void *)(planes + ((int64_t)pix * BITS) * Cw + 2 * cg), 0xffffffffu);
         }
-        int64_t pix = it0 / cgroups;
-        int cg = (int)(it0 - pix * cgroups);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (u < n) {
-                float val = v[u];
+        auto item = [&](int u) {
+            float val = v[u];
+            if constexpr (FRONT) {
                 if (hrelu) val = (val > 0.0f) ? val : 0.0f;
-                const uint32_t uidx = round_odd_index<BITS>(val * premul);
-                if (codes != nullptr) {
-                    const __amdgpu_buffer_rsrc_t dc = make_rsrc((void *)(codes + (it0 + u) * 64), 64u * (uint32_t)sizeof(CodeT));
-                    const int code = 2 * (int)uidx - VMAX;
-                    if (sizeof(CodeT) == 1) __builtin_amdgcn_raw_buffer_store_b8((char)code, dc, lane, 0, 0);
-                    else __builtin_amdgcn_raw_buffer_store_b16((short)code, dc, lane * 2, 0, 0);
-                }
-                if (planes != nullptr) {
-                    uint32_t top = uidx << (32 - BITS);
-                    int mine = (int)top;                      // every lane that stores is overwritten
-                    emit_all<BITS>(top, mine);
-                    uint32_t *dst = planes + (pix * BITS) * Cw + 2 * cg;    // wave-uniform
-                    const __amdgpu_buffer_rsrc_t dp = make_rsrc((void *)dst, (uint32_t)(BITS * Cw) * 4u);
-                    if (stores) __builtin_amdgcn_raw_buffer_store_b32(mine, dp, store_off, 0, 0);
-                }
-                if (++cg == cgroups) { cg = 0; ++pix; }
+                val *= premul;
             }
+            const uint32_t uidx = round_odd_index<BITS>(val);
+            if constexpr (CODES) {
+                const int code = 2 * (int)uidx - VMAX;
+                if (sizeof(CodeT) == 1) __builtin_amdgcn_raw_buffer_store_b8((char)code, dc, lane, u * 64, 0);
+                else __builtin_amdgcn_raw_buffer_store_b16((short)code, dc, lane * 2, u * 128, 0);
+            }
+            if constexpr (PLANES) {
+                const int mine = emit_planes<BITS>(uidx << (32 - BITS));
+                if (stores) __builtin_amdgcn_raw_buffer_store_b32(mine, dp, store_off, (int)poff, 0);
+                poff += 8u;                                              // next channel group: two words on
+                if (++cg == cgroups) {                                   // next pixel
+                    cg = 0;
+                    poff += pixel_bytes - 8u * (uint32_t)cgroups;
+                }
+            }
+        };
+        if (n == U) {                                                    // a full trip: no test per item
+#pragma unroll
+            for (int u = 0; u < U; ++u) item(u);
+        } else {                                                         // the short last trip
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (u < n) item(u);
         }
     }
 }
@@ -187,9 +195,24 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
     if (pool)
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
-    else if (C % 64 == 0)
-        hipLaunchKernelGGL((requant_flat_kernel<CodeT, BITS, 16>), dim3(blocks), dim3(256), 0, s, y,
-                           out_pixels * (C / 64), C / 64, premul, hrelu, (CodeT *)codes, planes);
+    else if (C % 64 == 0 && out_pixels * (C / 64) < ((int64_t)1 << 30)) {
+        const int items = (int)(out_pixels * (C / 64)), groups = C / 64;
+        const FastDiv dg = fast_div_for(groups);
+        const bool front = hrelu || premul != 1.0f;
+        CodeT *cp = (CodeT *)codes;
+#define QNN_FLAT(F, CO, PL) hipLaunchKernelGGL((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL>), dim3(blocks), dim3(256), 0, s, \
+                                               y, items, groups, dg, premul, hrelu, cp, planes)
+        if (front) {
+            if (cp && planes) QNN_FLAT(true, true, true);
+            else if (planes) QNN_FLAT(true, false, true);
+            else QNN_FLAT(true, true, false);
+        } else {
+            if (cp && planes) QNN_FLAT(false, true, true);
+            else if (planes) QNN_FLAT(false, false, true);
+            else QNN_FLAT(false, true, false);
+        }
+#undef QNN_FLAT
+    }
     else
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
