@@ -290,6 +290,69 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
         res = {"metric": "GB/s of qnn_encode_pack (algorithmic bytes: codes in + planes out)", "value": head["GBps"],
                "unit": "GB/s", "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": head["GBps"], "peak": 8000.0,
                                             "unit": "GB/s", "frac": round(head["GBps"] / 8000.0, 4), "traffic": None}}
+    elif name == "resnet18_mixed":
+        # The paper's mixed-precision example (Sec. 5.1, Table 4, second precision column): ResNet-18 with
+        # 4-bit activations and 5 / 3 / 2 / 2-bit weights in the four residual stages, a 6-bit fully
+        # connected layer and an 8-bit first convolution (the table's Conv1 entry is garbled; the first
+        # layer is taken at 8-bit activations and weights like the table's other column).  Every
+        # convolution of the network once, batch 32; operands are random bit patterns (the cost does not
+        # depend on the data; parity of these shapes and widths is in tests/test_gpu_general_conv.py).
+        Nb = 32
+        net = [("conv1 7x7/2 3->64 (row-dense input)", 1, 224, 3, 64, 8, 8, 7, 2, 3)]
+        for (stage, cin, cout, hw, wb_) in (("conv2_x", 64, 64, 56, 5), ("conv3_x", 64, 128, 56, 3),
+                                            ("conv4_x", 128, 256, 28, 2), ("conv5_x", 256, 512, 14, 2)):
+            if cin == cout:
+                net.append(("%s 3x3 %d->%d" % (stage, cin, cout), 4, hw, cin, cout, 4, wb_, 3, 1, 1))
+            else:
+                net.append(("%s 3x3/2 %d->%d" % (stage, cin, cout), 1, hw, cin, cout, 4, wb_, 3, 2, 1))
+                net.append(("%s shortcut 1x1/2 %d->%d" % (stage, cin, cout), 1, hw, cin, cout, 4, wb_, 1, 2, 0))
+                net.append(("%s 3x3 %d->%d" % (stage, cout, cout), 3, hw // 2, cout, cout, 4, wb_, 3, 1, 1))
+        total_us, total_lane, total_ops = 0.0, 0.0, 0.0
+        for (label, count, hw, C, Cout, ab, wb, k, st, pd) in net:
+            Cw = (C + 31) // 32
+            dense = C < 32
+            if dense:
+                Rw = (hw * C + 31) // 32
+                Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * hw, ab, Rw), dtype=torch.int32, device=dev)
+                if (hw * C) % 32:
+                    Xp[:, :, -1] &= (1 << ((hw * C) % 32)) - 1
+            else:
+                Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb * hw * hw, ab, Cw), dtype=torch.int32, device=dev)
+            Wp = torch.randint(0, 1 << min(C, 30), (Cout, k * k, wb, Cw), dtype=torch.int32, device=dev)
+            sd = torch.rand(Cout, device=dev)
+            geo = q.conv_geometry(k, k, stride=st, pad=pd, dense_rows=dense)
+            Ho, Wo = q.conv2d_general_output_size(hw, hw, geo)
+            t = avg_us(lambda: q.conv2d_general(Xp, ab, Wp, wb, Nb, hw, hw, C, Cout, geo, scale=sd))
+            tap_pixels = Nb * axis_taps(hw, Ho, k, st, pd, 1, False) ** 2
+            # packed-window layers (few channels) work on window words, not on a word per tap
+            kw_words = tap_pixels * Cw if not dense else Nb * Ho * Wo * (-(-(k * k * C) // 32))
+            lane = 2.0 * ab * wb * kw_words * Cout
+            ops = 2.0 * Nb * Ho * Wo * Cout * k * k * C
+            rows.append({"layer": label, "times_in_network": count, "W%dA%d" % (wb, ab): True, "out": "%dx%d" % (Ho, Wo),
+                         "us": round(t, 1), "effective_GOPS": round(ops / t / 1e3, 1),
+                         "frac_of_lane_op_peak": round(lane / (t * 1e-6) / PEAK_LANE_OPS, 3)})
+            total_us += count * t
+            total_lane += count * lane
+            total_ops += count * ops
+            del Xp, Wp
+        # the fully connected layer: 512 -> 1000, 4-bit activations, 6-bit weights
+        A = torch.randint(-2 ** 31, 2 ** 31 - 1, (Nb, 4, 16), dtype=torch.int32, device=dev)
+        Wf = torch.randint(-2 ** 31, 2 ** 31 - 1, (1000, 6, 16), dtype=torch.int32, device=dev)
+        sd = torch.rand(1000, device=dev)
+        t = avg_us(lambda: q.branch_gemm(A, 4, Wf, 6, 512, scale=sd))
+        rows.append({"layer": "fc 512->1000", "times_in_network": 1, "W6A4": True, "out": "32x1000", "us": round(t, 1),
+                     "effective_GOPS": round(2.0 * Nb * 1000 * 512 / t / 1e3, 1),
+                     "frac_of_lane_op_peak": round(2.0 * 24 * Nb * 1000 * 16 / (t * 1e-6) / PEAK_LANE_OPS, 3),
+                     "note": "launch-latency bound at this size"})
+        total_us += t
+        total_ops += 2.0 * Nb * 1000 * 512
+        total_lane += 2.0 * 24 * Nb * 1000 * 16
+        res = {"metric": "effective quantized GOPS over every convolution and the FC layer of the mixed-precision ResNet-18 "
+                         "(sum of the layers' times, each timed on its own)",
+               "value": round(total_ops / total_us / 1e3, 1), "unit": "GOPS", "ms_per_step": round(total_us / 1e3, 4),
+               "roofline": {"bound": "alu", "kernel": "all branch kernels of the network", "achieved": round(total_lane / (total_us * 1e-6) / 1e12, 3),
+                            "peak": round(PEAK_LANE_OPS / 1e12, 3), "unit": "Tlane-op/s",
+                            "frac": round(total_lane / (total_us * 1e-6) / PEAK_LANE_OPS, 4), "traffic": None}}
     else:
         cases = [("ResNet stem 7x7 stride 2, 3->64, 224^2, W2A8", 32, 224, 224, 3, 64, 8, 2, 7, 7, 2, 3, 1, False),
                  ("3x3 stride 2, 128->128, 56^2, W2A2", 32, 56, 56, 128, 128, 2, 2, 3, 3, 2, 1, 1, False),
@@ -346,7 +409,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="resnet18_s1",
                     choices=["resnet18_s1", "resnet50_s3", "fc4096", "gemm64", "gemm8192", "vgg16_stack",
-                             "vgg16_stack_fused", "hbm_kernels", "conv_geometries"])
+                             "vgg16_stack_fused", "hbm_kernels", "conv_geometries", "resnet18_mixed"])
     ap.add_argument("--bits", type=int, default=None,
                     help="gemm8192 only: activation = weight bit width (1..6 in the paper's sweep; default 2)")
     ap.add_argument("--batch", type=int, default=None,
@@ -406,7 +469,7 @@ def main():
     def check(st):
         assert st == 0, L.qnn_status_string(st)
 
-    if name in ("hbm_kernels", "conv_geometries"):
+    if name in ("hbm_kernels", "conv_geometries", "resnet18_mixed"):
         return side_suites(name, args, steps, warmup, torch, np, q, dev)
 
     cpu = cpu1 = None

@@ -260,7 +260,7 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  *   workspace  optional device scratch (16-byte aligned).  It is REQUIRED (at least
  *          Nb*Ho*Wo*Cout*4 bytes) only when out_bits != 0 and neither acc nor out_f32 is given.
  *          With qnn_conv2d_general_workspace_bytes() bytes it also enables the packed-window path
- *          for few input channels (C <= 32, kh*kw*C <= 256, wb <= 4, not transposed: e.g. a 7x7x3
+ *          for few input channels (C <= 32, kh*kw*C <= 256, not transposed: e.g. a 7x7x3
  *          stem), which is several times faster; without it the result is the same.
  * qnn_conv2d_general_output_size writes Ho and Wo to HOST integers; both functions return
  * QNN_EINVAL for a geometry that is not positive (kernel, stride, dilation >= 1, padding >= 0,
@@ -270,8 +270,8 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  * activations are packed per image ROW instead of per pixel, x_planes = qnn_encode_pack(codes
  * viewed as [Nb*H][W*C], bits = ab) = uint32 [Nb*H][ab][ceil(W*C/32)], an eighth of the per-pixel
  * size for C = 3, and a kernel row of the window is a run of KW*C consecutive bits.  Accepted
- * only where the packed-window path applies (forward convolution, C <= 32, kh*kw*C <= 256,
- * wb <= 4) and with its workspace; QNN_EUNSUPPORTED otherwise.
+ * only where the packed-window path applies (forward convolution, C <= 32, kh*kw*C <= 256)
+ * and with its workspace; QNN_EUNSUPPORTED otherwise.
  * The 3x3 / stride 1 / pad 1 / dilation 1 convolution with more than 32 channels, or without
  * the window workspace, runs on the kernel of qnn_conv2d_packed (same operands, same outputs;
  * QNN_TUNE_GENERAL_ONLY keeps it here).  A 1x1 convolution

@@ -609,7 +609,7 @@ size_t qnn_conv2d_general_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int6
     if (!bits_ok(ab) || !bits_ok(wb) || Nb <= 0 || C <= 0 || Cout <= 0) return 0;
     if (qnn_conv2d_general_output_size(H, W, q, &Ho, &Wo) != QNN_OK) return 0;
     const int64_t rows = Nb * Ho * Wo, taps = (int64_t)q->kh * q->kw;
-    const int kwp = (!q->transposed && C <= 32 && taps >= 2 && wb <= 4) ? window_words(taps * C) : 0;
+    const int kwp = (!q->transposed && C <= 32 && taps >= 2) ? window_words(taps * C) : 0;
     const size_t win = kwp > 0 ? window_workspace_bytes(rows, ab, kwp) : 0;
     const size_t part = (size_t)(rows * Cout * 4);
     return win > part ? win : part;
@@ -632,7 +632,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, (int)taps, acc, scale, out_f32, e);
     if (st != QNN_OK || rows == 0 || Cout == 0) return st;
     // row-dense input exists for the packed-window path only
-    if (q->dense_rows && (q->transposed || C > 32 || taps < 2 || wb > 4 || window_words(taps * C) == 0))
+    if (q->dense_rows && (q->transposed || C > 32 || taps < 2 || window_words(taps * C) == 0))
         return QNN_EUNSUPPORTED;
     // A single tap at stride 1 without padding reads pixel r for output pixel r: the product of the
     // [pixels][C] matrix with the [Cout][C] weights, whichever way the transposed flag is set.
@@ -664,7 +664,7 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     g.geo.transposed = (q->transposed && cw > 0) ? 1 : 0;      // an empty sum needs no phases
     // Few input channels and a window of at most 256 bits: packed im2col rows, if the caller gave
     // the workspace for them (else the general kernel below does the same, a word per tap).
-    const int kwp = (!q->transposed && C <= 32 && taps >= 2 && wb <= 4) ? window_words(taps * C) : 0;
+    const int kwp = (!q->transposed && C <= 32 && taps >= 2) ? window_words(taps * C) : 0;
     if (kwp > 0) {
         const size_t need = window_workspace_bytes(rows, ab, kwp);
         if (workspace != nullptr && aligned16(workspace) && workspace_bytes >= need && need < ((size_t)1 << 32)) {

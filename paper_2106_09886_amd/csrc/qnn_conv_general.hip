@@ -690,6 +690,10 @@ hipError_t QNN_CAT(launch_conv_window_ab, QNN_AB)(const BranchArgs &g, int wb, h
         case 2: return launch_window_t<QNN_AB, 2>(g, s);
         case 3: return launch_window_t<QNN_AB, 3>(g, s);
         case 4: return launch_window_t<QNN_AB, 4>(g, s);
+        case 5: return launch_window_t<QNN_AB, 5>(g, s);
+        case 6: return launch_window_t<QNN_AB, 6>(g, s);
+        case 7: return launch_window_t<QNN_AB, 7>(g, s);
+        case 8: return launch_window_t<QNN_AB, 8>(g, s);
     }
     return hipErrorInvalidValue;
 }

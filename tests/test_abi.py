@@ -215,7 +215,6 @@ def test_general_conv_geometry_and_argument_errors(L):
     dense = conv_geometry(3, 3, pad=1, dense_rows=True)
     dp = ctypes.byref(dense)
     assert f(P, 2, P, 2, 1, 8, 8, 64, 64, dp, P, None, None, 0, None, P, 1 << 20, None) == QNN_EUNSUPPORTED   # 64 channels
-    assert f(P, 2, P, 5, 1, 8, 8, 3, 64, dp, P, None, None, 0, None, P, 1 << 20, None) == QNN_EUNSUPPORTED    # 5 weight bits
     assert f(P, 2, P, 2, 1, 8, 8, 3, 64, dp, P, None, None, 0, None, None, 0, None) == QNN_EWORKSPACE
     one = conv_geometry(1, 1, dense_rows=True)
     assert f(P, 2, P, 2, 1, 8, 8, 3, 64, ctypes.byref(one), P, None, None, 0, None, P, 1 << 20, None) == QNN_EUNSUPPORTED

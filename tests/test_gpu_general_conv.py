@@ -123,6 +123,8 @@ WINDOW_CASES = [
     dict(Nb=1, H=8, W=8, C=7, Cout=130, ab=5, wb=2, KH=3, KW=3, stride=(2, 1), pad=1),      # 63 bits, 2 words
     dict(Nb=3, H=28, W=28, C=1, Cout=20, ab=8, wb=4, KH=5, KW=5),                           # LeNet conv1, 25 bits
     dict(Nb=1, H=5, W=5, C=11, Cout=8, ab=1, wb=1, KH=1, KW=3, pad=(0, 1)),                 # 33 bits: one bit in word 1
+    dict(Nb=2, H=20, W=22, C=3, Cout=64, ab=8, wb=8, KH=7, KW=7, stride=2, pad=3),          # 8-bit stem (Table 4's first layer)
+    dict(Nb=1, H=9, W=9, C=3, Cout=70, ab=4, wb=6, KH=3, KW=3, pad=1),                      # wide weights, one word
 ]
 
 
