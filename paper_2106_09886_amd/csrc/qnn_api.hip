@@ -285,28 +285,36 @@ qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout
     return QNN_OK;
 }
 
+// stride: 1, or 2 where the 3x3 kernel has a fixed-shape instantiation (conv_has_fixed_shape)
 qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
                            int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
-                           float *out_f32, const Emit &e, void *stream) {
+                           float *out_f32, const Emit &e, void *stream, int stride = 1) {
     qnn_status st = check_image(Nb, H, W, C, Cout);
     if (st != QNN_OK) return st;
-    const int64_t rows = Nb * H * W;
+    const int64_t Ho = (H > 0) ? (H - 1) / stride + 1 : 0, Wo = (W > 0) ? (W - 1) / stride + 1 : 0;
+    const int64_t rows = Nb * Ho * Wo;
     st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32, e);
     if (st != QNN_OK || rows == 0 || Cout == 0) return st;
+    const int64_t cw = (C + 31) / 32;
+    if (cw > 0 && Nb * H * W > ((((int64_t)1 << 30) - 1) / (ab * cw))) return QNN_EUNSUPPORTED;      // input planes
     BranchArgs g;
     g.A = x_planes; g.Wt = Wt; g.acc = acc; g.scale = scale; g.out = out_f32;
     g.partial = partial_buffer(acc, out_f32, e);
     g.out_flags = (acc != nullptr ? 1u : 0u) | (out_f32 != nullptr ? 2u : 0u);
     g.planes_out = e.planes; g.out_bits = e.bits;
-    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)((C + 31) / 32); g.H = (int)H; g.W = (int)W; g.C = (int)C;
+    g.rows = (int)rows; g.N = (int)Cout; g.Cw = (int)cw; g.H = (int)H; g.W = (int)W; g.C = (int)C;
     g.kconst = (int)(C * (((int64_t)1 << ab) - 1) * (((int64_t)1 << wb) - 1));
     g.col_tiles = (int)((Cout + 63) / 64);
-    g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0; g.xcd_ranges = xcd_ranges_for(g.col_tiles >= 4);
+    g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0;
+    g.xcd_ranges = (stride == 1) ? xcd_ranges_for(g.col_tiles >= 4) : 0;        // the strided variant keeps plain numbers
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
-    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, W, g.col_tiles, conv_passes(ab, wb, g.Cw), conv_group(ab, wb, g.Cw)), Cout),
+    g.geo.KH = 3; g.geo.KW = 3; g.geo.sh = stride; g.geo.sw = stride; g.geo.ph = 1; g.geo.pw = 1; g.geo.dh = 1; g.geo.dw = 1;
+    g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = 0;
+    const int group = (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
+    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, conv_passes(ab, wb, g.Cw), group), Cout),
                                           Cout, e);
     g.grid_blocks = wave_grid_blocks(g);
-    set_divisors(g);
+    set_divisors(g, /*output_image=*/true);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
 }
 
@@ -690,9 +698,13 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     if (q->dense_rows) return (kwp > 0) ? QNN_EWORKSPACE : QNN_EUNSUPPORTED;   // only the window path reads row-dense input
     // The 3x3 window at stride 1 with one pixel of padding has a kernel of its own (the same
     // operands, the same outputs; about 1.5x faster on a ResNet-18-shaped layer).
-    if (!q->transposed && q->kh == 3 && q->kw == 3 && q->stride_h == 1 && q->stride_w == 1 && q->pad_h == 1 &&
+    // At stride 2 the same kernel serves the channel counts it is instantiated for with a compile-time
+    // plane stride (the strided layers of the residual networks: 64 ... 512 channels).
+    const bool s1 = q->stride_h == 1 && q->stride_w == 1;
+    const bool s2 = q->stride_h == 2 && q->stride_w == 2 && conv_has_fixed_shape(ab, wb, (int)cw);
+    if (!q->transposed && q->kh == 3 && q->kw == 3 && (s1 || s2) && q->pad_h == 1 &&
         q->pad_w == 1 && q->dil_h == 1 && q->dil_w == 1 && cw > 0 && !tuning().general_only)
-        return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream);
+        return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, s1 ? 1 : 2);
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the
     // wavefront's weight words, which has to be spread over enough pixels (measured optimum 14-16
     // on layers of 25 k to 100 k pixels)

@@ -367,8 +367,9 @@ __global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------
-// 3x3 convolution, stride 1, pad 1.  Rows are output pixels in NHWC order; the K axis of a
-// pixel is the nine neighbouring pixels' plane words, never materialised.  Taps outside the
+// 3x3 convolution, pad 1, stride S = 1 or 2 (both axes).  Rows are output pixels in NHWC order;
+// the K axis of a pixel is the plane words of the nine input pixels around (S*oh, S*ow), never
+// materialised.  Taps outside the
 // image contribute nothing: they are skipped, and the constant term of a pixel uses its
 // number of valid taps.
 //
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(256) void gemm_splitk_kernel(const BranchArgs g) {
 // A chunk = TPC taps x CWT channel words; its weight words (TPC*WB*CWT) stay in VGPRs.
 // ---------------------------------------------------------------------------------------
 struct PixelPos {
-    int oh, ow;
+    int n, oh, ow;        // image, output row, output column
 };
 
 __device__ __forceinline__ int tap_dh(int t) { return t / 3 - 1; }
@@ -399,14 +400,15 @@ __device__ __forceinline__ int tap_dw(int t) { return t % 3 - 1; }
 //                 dw = -1 are skipped), bit 1: the last one is in column W-1 (dw = +1 skipped).
 // Addresses are not tested: a +-1 column step from a pixel of an existing row stays inside
 // [0, rows) except for the four pixels 0, W, rows-1-W and rows-1, which never come here.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S = 1>
 struct ConvCtx {
     static constexpr int NS = TPC / GT;
     static constexpr bool CONTIG = (CWS > 0 && CWT == CWS);   // a pixel's AB*CWT words are consecutive
     // CONTIG: one run of GT*AB*CWT words (consecutive pixels are consecutive too);
     // otherwise one run of CWT words per (tap, plane).
     static_assert(P == 1 || (GT == 3 && CONTIG), "pixel groups need contiguous kernel rows");
-    typedef typename std::conditional<CONTIG, SStage<1, (GT + P - 1) * AB * CWT>, SStage<GT * AB, CWT>>::type Buf;
+    // the P output pixels of a group are S input pixels apart: a kernel row spans GT + S*(P-1) input pixels
+    typedef typename std::conditional<CONTIG, SStage<1, (GT + S * (P - 1)) * AB * CWT>, SStage<GT * AB, CWT>>::type Buf;
     uint64_t base;                   // byte address of the activation planes
     int Cw, c0, t0;                  // runtime words per plane, chunk's first channel word / tap
     uint32_t off_cur, off_nxt;       // byte offset of (pixel, plane 0, word c0) for this / the next pixel
@@ -440,7 +442,7 @@ struct ConvCtx {
         for (int st = 0; st < NS; ++st) {
             const int dh = (TPC == 9) ? first_tap(st) / 3 - 1 : tap_dh(t0 + st * GT);
             const int dw = (TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1;
-            const bool ok = (unsigned)(oh + dh) < (unsigned)H;
+            const bool ok = (unsigned)(S * oh + dh) < (unsigned)H;
             if (ok) stage_ok |= 1u << st;
             stage_off[st] = (uint32_t)((ok ? dh * W : 0) + dw) * pixel_bytes();
         }
@@ -472,7 +474,7 @@ struct ConvCtx {
             for (int p = 0; p < AB; ++p)
 #pragma unroll
                 for (int j = 0; j < CWT; ++j) {
-                    const uint32_t v = word(b, x + i, p, j) ^ w[t][q][j];
+                    const uint32_t v = word(b, x * S + i, p, j) ^ w[t][q][j];
                     // accumulator p+q is first reached at j == 0 with the smallest q that pairs with it
                     const bool first_hit = SET && j == 0 && q == ((p + q) < AB ? 0 : (p + q) - (AB - 1));
                     if (first_hit) popc_set(part[x][p + q], v);
@@ -503,26 +505,27 @@ struct ConvCtx {
     }
 };
 
-__device__ __forceinline__ PixelPos next_pixel(PixelPos p, int H, int W) {
-    if (++p.ow == W) {
+__device__ __forceinline__ PixelPos next_pixel(PixelPos p, int Ho, int Wo) {
+    if (++p.ow == Wo) {
         p.ow = 0;
-        if (++p.oh == H) p.oh = 0;
+        if (++p.oh == Ho) { p.oh = 0; ++p.n; }
     }
     return p;
 }
 
-__device__ __forceinline__ PixelPos pixel_pos(int r, const BranchArgs &g) {
+__device__ __forceinline__ PixelPos pixel_pos(int r, const BranchArgs &g) {     // divisors: the OUTPUT image size
     PixelPos p;
-    int line, img;
+    int line;
     fast_divmod((uint32_t)r, g.div_w, line, p.ow);
-    fast_divmod((uint32_t)line, g.div_h, img, p.oh);
+    fast_divmod((uint32_t)line, g.div_h, p.n, p.oh);
     return p;
 }
 
-// number of taps of the 3x3 window that fall inside the image
+// number of taps of the 3x3 window of an output pixel that fall inside the image
+template <int S>
 __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
-    const int nh = 3 - (p.oh == 0 ? 1 : 0) - (p.oh == H - 1 ? 1 : 0);
-    const int nw = 3 - (p.ow == 0 ? 1 : 0) - (p.ow == W - 1 ? 1 : 0);
+    const int nh = 3 - (S * p.oh == 0 ? 1 : 0) - (S * p.oh + 1 >= H ? 1 : 0);
+    const int nw = 3 - (S * p.ow == 0 ? 1 : 0) - (S * p.ow + 1 >= W ? 1 : 0);
     return nh * nw;
 }
 
@@ -532,18 +535,19 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
 // groups of P; if P does not divide the run, the last group is placed at rb-P and recomputes
 // pixels of the group before it (P > 1 is used for single-chunk shapes only, where a
 // recomputed pixel is simply stored again with the same value).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
-__device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c,
+// in_a: number of the input pixel under output pixel ra, (n*H + S*oh)*W + S*ow.
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
+__device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c,
                                                    const BranchArgs &g, const OV &ov, int r0, int ra,
-                                                   int rb, int oh, uint32_t left_first, uint32_t right_last,
+                                                   int rb, int oh, int in_a, uint32_t left_first, uint32_t right_last,
                                                    bool first, bool last) {
     constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
     static_assert(P == 1 || SINGLE, "pixel groups only where a chunk pass is the whole product");
     c.set_image_row(oh, g.H, g.W);
-    const int krow = (3 - (oh == 0 ? 1 : 0) - (oh == g.H - 1 ? 1 : 0)) * g.kconst;   // per valid column
+    const int krow = (3 - (S * oh == 0 ? 1 : 0) - (S * oh + 1 >= g.H ? 1 : 0)) * g.kconst;   // per valid column
     const uint32_t pb = c.pixel_bytes();
     const uint32_t edge_first = left_first, edge_last = right_last;
-    const uint32_t off_a = (uint32_t)ra * pb + (uint32_t)c.c0 * 4u;
+    const uint32_t off_a = (uint32_t)in_a * pb + (uint32_t)c.c0 * 4u;
     const int r_last = rb - P;                       // start of the last group
     c.off_cur = off_a;
     c.off_nxt = off_a;
@@ -551,7 +555,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
     int r = ra;
     auto one_group = [&](auto flip_tag) {
         constexpr bool FLIP = decltype(flip_tag)::value;
-        if constexpr (!ConvCtx<AB, WB, CWS, CWT, TPC, GT, P>::CENTER_FIRST) {
+        if constexpr (!ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S>::CENTER_FIRST) {
 #pragma unroll
             for (int x = 0; x < P; ++x)
 #pragma unroll
@@ -559,7 +563,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
         }
         // the group after this one (the last group prefetches itself, unused)
         const int rn = (r < r_last) ? min(r + P, r_last) : r;
-        c.off_nxt = off_a + (uint32_t)(rn - ra) * pb;
+        c.off_nxt = off_a + (uint32_t)((rn - ra) * S) * pb;
         // integer selects only: keeps the edge bookkeeping on the scalar unit
         uint32_t edge = 0u;
         if (r == ra) edge |= edge_first;
@@ -600,8 +604,8 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
 }
 
 // One pixel of one chunk with every tap and address tested (the four end pixels).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
-__device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> &c, uniform_words As,
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
+__device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c, uniform_words As,
                                                  const BranchArgs &g, const OV &ov, int r0, int r,
                                                  PixelPos pos, bool first, bool last) {
 #pragma unroll
@@ -610,9 +614,10 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
     for (int t = 0; t < TPC; ++t) {
         const int dh = (TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t);
         const int dw = (TPC == 1) ? tap_dw(c.t0) : t % 3 - 1;
-        const bool ok = (unsigned)(pos.oh + dh) < (unsigned)g.H && (unsigned)(pos.ow + dw) < (unsigned)g.W;
+        const int ih = S * pos.oh + dh, iw = S * pos.ow + dw;
+        const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
         if (ok) {
-            const int pix = r + dh * g.W + dw;
+            const int pix = (pos.n * g.H + ih) * g.W + iw;
             uint32_t a[AB][CWT];
 #pragma unroll
             for (int p = 0; p < AB; ++p)
@@ -627,19 +632,19 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
         }
     }
     int val = -2 * weighted_sum(c.part[0]);
-    if (first) val += valid_taps(pos, g.H, g.W) * g.kconst;
+    if (first) val += valid_taps<S>(pos, g.H, g.W) * g.kconst;
     finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
 }
 
 // full chunk: every word c0 .. c0+CWT-1 exists.  The wavefront's pixel range is cut into
 // runs inside one image row; the four pixels whose untested neighbour addresses could leave
 // the buffer (0, W, rows-1-W, rows-1) go through the tested path.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, class OV>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
 __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &ov, uniform_words As,
                                                 int nload, int r0, int r1, int c0, int t0, bool first,
                                                 bool last) {
     static_assert(TPC % GT == 0 && ((TPC / GT) & 1) == 1, "odd number of stages per pixel");
-    ConvCtx<AB, WB, CWS, CWT, TPC, GT, P> c;
+    ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> c;
     c.base = (uint64_t)g.A; c.Cw = g.Cw; c.c0 = c0; c.t0 = t0;
     const int ps = c.plane_stride();
     {
@@ -658,11 +663,27 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
 #pragma unroll
                 for (int j = 0; j < CWT; ++j) c.w[t][q][j] = wl[(t * WB + q) * CWT + j];
     }
-    const int special[4] = {0, g.W, g.rows - 1 - g.W, g.rows - 1};
+    // Output pixels whose untested window addresses could leave the plane buffer go through the
+    // tested path.  Below 0: the window of the very first input pixel, read by output pixel 0 (and,
+    // at stride 1, by pixel Wo from its upper kernel row).  Past the end: a window that sits on the
+    // last input row of the last image and whose right column is W, which happens for the last
+    // output column when (W - 1) is a multiple of the stride, in the output rows with
+    // |S*oh - (H - 1)| <= 1 (the last one or two).
+    const int Ho = g.geo.Ho, Wo = g.geo.Wo;
+    int special[4] = {0, (S == 1) ? Wo : -1, -1, -1};
+    if ((g.W - 1) % S == 0) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int oh = Ho - 1 - k;
+            if (oh >= 0 && S * oh + 1 >= g.H - 1) special[2 + k] = g.rows - 1 - k * Wo;    // S*oh <= H-1 always
+        }
+    }
+    // the right-hand tap of the last output column is outside the image exactly in that case
+    const bool right_edge = ((g.W - 1) % S == 0);
     PixelPos pos = pixel_pos(r0, g);
     int r = r0;
     while (r < r1) {
-        const int row_end = r - pos.ow + g.W;            // first pixel of the next image row
+        const int row_end = r - pos.ow + Wo;             // first pixel of the next output row
         int stop = min(r1, row_end);
         bool is_special = false;
 #pragma unroll
@@ -674,14 +695,15 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
             conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
             stop = r + 1;
         } else {
-            conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, spin(pos.ow == 0 ? 1u : 0u),
-                               spin(stop == row_end ? 2u : 0u), first, last);
+            conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, (pos.n * g.H + S * pos.oh) * g.W + S * pos.ow,
+                               spin(pos.ow == 0 ? 1u : 0u), spin((stop == row_end && right_edge) ? 2u : 0u), first,
+                               last);
         }
         pos.ow += stop - r;
         r = stop;
-        if (pos.ow == g.W) {
+        if (pos.ow == Wo) {
             pos.ow = 0;
-            if (++pos.oh == g.H) pos.oh = 0;
+            if (++pos.oh == Ho) { pos.oh = 0; ++pos.n; }
         }
     }
 }
@@ -709,7 +731,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
             const int dh = t / 3 - 1, dw = t % 3 - 1;
             const bool ok = (unsigned)(pos.oh + dh) < (unsigned)g.H && (unsigned)(pos.ow + dw) < (unsigned)g.W;
             if (ok) {
-                const int pix = r + dh * g.W + dw;
+                const int pix = r + dh * g.W + dw;                         // stride 1: output pixel r sits on input pixel r
                 uint32_t a[AB][CWT];
 #pragma unroll
                 for (int p = 0; p < AB; ++p)
@@ -725,7 +747,7 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
             }
         }
         int val = -2 * weighted_sum(part);
-        if (first) val += valid_taps(pos, g.H, g.W) * g.kconst;
+        if (first) val += valid_taps<1>(pos, g.H, g.W) * g.kconst;
         finish_row<false>(ov, r - r0, val, first, last);
         pos = next_pixel(pos, g.H, g.W);
     }
@@ -734,8 +756,10 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 // XR: the blocks are numbered so that each XCD takes one contiguous range of them (xcd_block();
 // a compile-time choice: even a wave-uniform test of it at the start of every wavefront showed
 // in the time of the ResNet-18-shaped layer).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false>
+// S: stride (1, or 2 for the fixed-shape instantiations; the tail paths are stride 1 only).
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false, int S = 1>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
+    static_assert(S == 1 || CWS > 0, "strided: compile-time plane strides only");
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const WavePos wp = wave_pos<XR>(g.div_tiles, 1, g.grid_blocks);
     // a wavefront past the last row block keeps an empty row range
@@ -767,7 +791,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
             for (int tc = 0; tc < TAP_CHUNKS; ++tc) {
                 const bool first = (c0 == 0) && (tc == 0);
                 const bool last = (c0 + CWT >= Cw) && (tc == TAP_CHUNKS - 1);
-                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P>(g, ov, As, nload, r0, r1, c0, tc * TPC, first, last);
+                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, ov, As, nload, r0, r1, c0, tc * TPC, first, last);
             }
         } else if constexpr (CWS == 0 && CWT > 1) {
             conv_chunk_tail<AB, WB, CWT>(g, ov, As, nload, r0, r1, c0, c0 == 0, true);
@@ -868,6 +892,14 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
+    if (g.geo.sh == 2) {           // stride 2: pixel groups of two only where five input pixels fit a stage
+        constexpr int P2 = conv_group_strided(AB, WB, CWS);
+        if (g.planes_out != nullptr)
+            hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, P2, true, false, 2>), grid_for(g), dim3(256), 0, s, g);
+        else
+            hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, P2, false, false, 2>), grid_for(g), dim3(256), 0, s, g);
+        return hipGetLastError();
+    }
     if constexpr (CWS >= 2) {      // 64 channels and more: the automatic choice asks for it from 256 filters on
         if (g.xcd_ranges) {
             if (g.planes_out != nullptr)
@@ -897,6 +929,7 @@ hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
             default: break;
         }
     }
+    if (g.geo.sh != 1) return hipErrorInvalidValue;                  // host bug: strided needs a fixed shape
     // any other channel count: runtime stride, chunks of two channel words while the two stage
     // buffers (2 * AB * CWT SGPRs) leave the allocator room, else one word
     const bool emit = g.planes_out != nullptr;
@@ -931,6 +964,7 @@ hipError_t QNN_CAT(launch_gemm_ab, QNN_AB)(const BranchArgs &g, int wb, hipStrea
 
 hipError_t QNN_CAT(launch_conv_ab, QNN_AB)(const BranchArgs &g, int wb, hipStream_t s) {
     if (g.xcd_ranges && g.grid_blocks != grid_for(g).x) return hipErrorInvalidValue;   // host bug
+    if (g.geo.sh != g.geo.sw || (g.geo.sh != 1 && g.geo.sh != 2)) return hipErrorInvalidValue;
     switch (wb) {
         case 1: return launch_conv_t<QNN_AB, 1>(g, s);
         case 2: return launch_conv_t<QNN_AB, 2>(g, s);

@@ -162,6 +162,12 @@ constexpr int conv_group(int ab, int wb, int cw) {
     return conv_has_fixed_shape(ab, wb, cw) ? conv_shape(ab, wb, cw).p : 1;
 }
 
+// the same for the stride-2 variant of the 3x3 kernel: two output pixels share a stage of five input
+// pixels where those fit the scalar registers of a stage, else one pixel per iteration
+constexpr int conv_group_strided(int ab, int wb, int cw) {
+    return (conv_has_fixed_shape(ab, wb, cw) && conv_shape(ab, wb, cw).p >= 2 && 5 * ab * conv_shape(ab, wb, cw).cwt <= 20) ? 2 : 1;
+}
+
 // Launchers, one translation unit per activation bit width AB (1..8).
 typedef hipError_t (*branch_launch_fn)(const BranchArgs &, int wb, hipStream_t);
 hipError_t launch_gemm_ab1(const BranchArgs &, int, hipStream_t);

@@ -39,7 +39,7 @@ def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dila
     # a 3x3 window at stride 1, padding 1 goes to the dedicated 3x3 kernel unless told otherwise:
     # such a case runs both ways
     pair = lambda v: tuple(v) if isinstance(v, (tuple, list)) else (v, v)
-    handed_over = (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) == (1, 1)
+    handed_over = (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) in ((1, 1), (2, 2))
                    and pair(pad) == (1, 1) and pair(dilation) == (1, 1))
     for general_only in ((1, 0) if handed_over else (0,)):
         q.tune(general_only=general_only)
@@ -135,6 +135,33 @@ def test_conv2d_few_channels(q, oracle, case, workspace):
     say("conv2d few channels", case, "workspace", workspace)
     run_case(q, oracle, workspace=workspace, **case)
     run_case(q, oracle, workspace=workspace, out_bits=4, seed=5, **case)
+
+
+# 3x3 at stride 2 with padding 1 on the 3x3 kernel's strided variant: even and odd image sizes (an
+# odd width puts the last column's right-hand tap outside), one-pixel images, several images,
+# channel counts with one and with several chunk passes, pixel groups of two (W2A2, 64 channels)
+STRIDE2_CASES = [(1, 1, 1, 64, 64, 2, 2), (1, 2, 2, 64, 64, 2, 2), (2, 3, 3, 64, 70, 2, 2), (3, 8, 8, 64, 64, 2, 2),
+                 (2, 9, 7, 64, 64, 2, 2), (2, 7, 10, 64, 130, 2, 2), (1, 56, 56, 64, 128, 4, 3),
+                 (2, 13, 14, 128, 64, 2, 2), (1, 14, 13, 256, 70, 4, 2), (2, 7, 7, 512, 64, 4, 2),
+                 (1, 5, 6, 32, 33, 1, 1), (1, 28, 28, 128, 256, 4, 2), (2, 11, 11, 256, 64, 3, 4)]
+
+
+@pytest.mark.parametrize("case", STRIDE2_CASES, ids=lambda c: "s2-%dx%dx%d-C%d-N%d-a%dw%d" % c)
+def test_conv3x3_stride2(q, oracle, case):
+    Nb, H, W, C, Cout, ab, wb = case
+    say("conv 3x3 stride 2", case)
+    run_case(q, oracle, Nb=Nb, H=H, W=W, C=C, Cout=Cout, ab=ab, wb=wb, KH=3, KW=3, stride=2, pad=1)
+    run_case(q, oracle, Nb=Nb, H=H, W=W, C=C, Cout=Cout, ab=ab, wb=wb, KH=3, KW=3, stride=2, pad=1, out_bits=4, seed=3)
+
+
+@pytest.mark.parametrize("rpw", [1, 2, 3, 5, 1000])
+def test_conv3x3_stride2_any_rows_per_wave(q, oracle, rpw):
+    q.tune(rows_per_wave=rpw)
+    try:
+        run_case(q, oracle, Nb=2, H=9, W=11, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, stride=2, pad=1)
+        run_case(q, oracle, Nb=2, H=10, W=8, C=256, Cout=70, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1)
+    finally:
+        q.tune(rows_per_wave=0)
 
 
 # the layers bench.py times (`--workload conv_geometries`), at their full sizes and in the launch
