@@ -19,6 +19,7 @@ __all__ = [
     "build", "threads", "encode", "decode", "pack_planes", "gemm", "gemm_wt", "conv3x3",
     "conv2d", "conv2d_transposed", "conv_out_size", "encode_real",
     "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
+    "encode_smooth", "encoder_backward", "binarize", "binarize_backward", "quantize_k", "quantize_k_backward",
 ]
 
 
@@ -69,6 +70,18 @@ def _L():
         lib.qnn_oracle_scale_f32.restype = None
         lib.qnn_oracle_encode_real.argtypes = [vp, i64, i32, i32, vp]
         lib.qnn_oracle_encode_real.restype = None
+        lib.qnn_oracle_encode_smooth.argtypes = [vp, i64, i32, i32, vp, vp]
+        lib.qnn_oracle_encode_smooth.restype = None
+        lib.qnn_oracle_encoder_backward.argtypes = [vp, vp, i64, i32, vp]
+        lib.qnn_oracle_encoder_backward.restype = None
+        lib.qnn_oracle_binarize.argtypes = [vp, i64, vp]
+        lib.qnn_oracle_binarize.restype = None
+        lib.qnn_oracle_binarize_backward.argtypes = [vp, vp, i64, vp]
+        lib.qnn_oracle_binarize_backward.restype = None
+        lib.qnn_oracle_quantize_k.argtypes = [vp, i64, i32, ctypes.c_float, vp, vp]
+        lib.qnn_oracle_quantize_k.restype = None
+        lib.qnn_oracle_quantize_k_backward.argtypes = [vp, vp, i64, ctypes.c_float, vp]
+        lib.qnn_oracle_quantize_k_backward.restype = None
         lib.qnn_oracle_maxpool2x2.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.qnn_oracle_maxpool2x2.restype = None
         lib.qnn_oracle_round_odd.argtypes = [ctypes.c_float, i32]
@@ -256,3 +269,55 @@ def encode_real(x, bits, hrelu=False):
     _L().qnn_oracle_encode_real(_p(x), x.size, int(bits), 1 if hrelu else 0, _p(codes))
     return codes
 
+
+
+def encode_smooth(x, bits, clip):
+    """Tanh ("tanh") or Sigmoid ("sigmoid") of Table 1, then the encoder -> (codes int16, limited fp32)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.zeros(x.shape, dtype=np.int16)
+    limited = np.zeros(x.shape, dtype=np.float32)
+    _L().qnn_oracle_encode_smooth(_p(x), x.size, int(bits), {"tanh": 2, "sigmoid": 3}[clip], _p(codes), _p(limited))
+    return codes, limited
+
+
+def encoder_backward(x, g):
+    """x fp32 [n], g fp32 [M][n] (gradients of the M encoded bits, low bit first) -> g_x float64 [n]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    M = g.shape[0]
+    assert g.shape[1:] == x.shape
+    out = np.zeros(x.shape, dtype=np.float64)
+    _L().qnn_oracle_encoder_backward(_p(x), _p(g), x.size, int(M), _p(out))
+    return out
+
+
+def binarize(w):
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    out = np.zeros(w.shape, dtype=np.int8)
+    _L().qnn_oracle_binarize(_p(w), w.size, _p(out))
+    return out
+
+
+def binarize_backward(w, g_wb):
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    g_wb = np.ascontiguousarray(g_wb, dtype=np.float32)
+    out = np.zeros(w.shape, dtype=np.float32)
+    _L().qnn_oracle_binarize_backward(_p(w), _p(g_wb), w.size, _p(out))
+    return out
+
+
+def quantize_k(x, K, t):
+    """-> (quantized fp32, integer levels int32)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.zeros(x.shape, dtype=np.float32)
+    lv = np.zeros(x.shape, dtype=np.int32)
+    _L().qnn_oracle_quantize_k(_p(x), x.size, int(K), ctypes.c_float(t), _p(q), _p(lv))
+    return q, lv
+
+
+def quantize_k_backward(x, g_q, t):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    g_q = np.ascontiguousarray(g_q, dtype=np.float32)
+    out = np.zeros(x.shape, dtype=np.float32)
+    _L().qnn_oracle_quantize_k_backward(_p(x), _p(g_q), x.size, ctypes.c_float(t), _p(out))
+    return out

@@ -310,3 +310,91 @@ void qnn_oracle_encode_real(const float *x, int64_t n, int bits, int hrelu, int1
     }
 }
 
+/* The smooth range limiters of Table 1 in front of the same encoder: Tanh(x) (range (-1,1), then
+ * the number space of Table 2 as after HTanh) and Sigmoid(x) (range (0,1), as after HReLU).
+ * The limiter is evaluated in double precision with the C library and rounded once to binary32;
+ * that value times alpha (one binary32 multiply) is what the interval rule sees.
+ * clip: 2 = Tanh, 3 = Sigmoid.  Also returns the limited value in binary32 (`limited`, may be
+ * NULL) so that a test can tell how far an element is from an interval boundary.             */
+void qnn_oracle_encode_smooth(const float *x, int64_t n, int bits, int clip, int16_t *codes, float *limited)
+{
+    const float alpha = (float)(((int64_t)1 << bits) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const double xd = (double)x[i];
+        const double l = (clip == 2) ? tanh(xd) : 1.0 / (1.0 + exp(-xd));
+        const float v = (float)l;
+        if (limited) limited[i] = v;
+        volatile float y = v * alpha;
+        codes[i] = qnn_oracle_round_odd(y, bits);
+    }
+}
+
+/* ---- training-side element-wise pieces (Sec. 4) ----------------------------------------------
+ * Derivative of the M-bit encoder used in back-propagation (Eq. (12); Eq. (13) prints the 2-bit
+ * case): for bit m = 1..M (m = 1 the low bit), with c_m = (2^M - 1) / 2^m,
+ *     d phi_M^m / dx = +c_m pi cos(c_m pi x)  for m = M,   -c_m pi cos(c_m pi x)  for m < M,
+ * inside -1 <= x <= 1 and 0 outside.  Alg. 1's BackMBitEncoder sums the M incoming gradients:
+ *     g_x[i] = sum_m g[m-1][i] * d phi_M^m / dx (x[i]).
+ * g is [M][n] (bit-major, low bit first), all in double precision.                            */
+void qnn_oracle_encoder_backward(const float *x, const float *g, int64_t n, int M, double *gx)
+{
+    const double pi = 3.14159265358979323846;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const double xv = (double)x[i];
+        double acc = 0.0;
+        if (xv >= -1.0 && xv <= 1.0) {
+            for (int m = 1; m <= M; ++m) {
+                const double c = (double)(((int64_t)1 << M) - 1) / (double)((int64_t)1 << m);
+                const double d = c * pi * cos(c * pi * xv);
+                acc += (double)g[(int64_t)(m - 1) * n + i] * ((m == M) ? d : -d);
+            }
+        }
+        gx[i] = acc;
+    }
+}
+
+/* Binarize(w) = sign(HTanh(w)) (Eq. (14)), the weight binarisation of Alg. 1.  HTanh keeps the
+ * sign, so this is the sign of w; sign(0) = +1 as in the binarised networks the section follows
+ * (a NaN compares false and gives -1).  Its gradient passes where HTanh is the identity:
+ *     g_w = g_wb  for |w| <= 1,   0 otherwise.                                                */
+void qnn_oracle_binarize(const float *w, int64_t n, int8_t *wb)
+{
+    for (int64_t i = 0; i < n; ++i) wb[i] = (w[i] >= 0.0f) ? 1 : -1;
+}
+
+void qnn_oracle_binarize_backward(const float *w, const float *g_wb, int64_t n, float *g_w)
+{
+    for (int64_t i = 0; i < n; ++i) g_w[i] = (w[i] >= -1.0f && w[i] <= 1.0f) ? g_wb[i] : 0.0f;
+}
+
+/* Quantize_K(x) = round(clamp(x / t, 1) * (2^(K-1) - 1)) * d,  d = t / (2^(K-1) - 1)  (Eq. (15)),
+ * K >= 2, t > 0.  Every step is one binary32 operation (division, clamp to [-1,1], multiply,
+ * round to nearest with ties to even, multiply); the volatile temporaries keep the compiler from
+ * contracting or widening them.  levels (may be NULL) receives the integer state.  The
+ * straight-through gradient passes inside the clamp: g_x = g_q for |x / t| <= 1, else 0.        */
+void qnn_oracle_quantize_k(const float *x, int64_t n, int K, float t, float *q, int32_t *levels)
+{
+    const float nlev = (float)(((int64_t)1 << (K - 1)) - 1);
+    volatile float d = t / nlev;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float r = x[i] / t;
+        float c = r;
+        if (!(c <= 1.0f)) c = 1.0f;          /* also a NaN clamps to +1 */
+        if (c < -1.0f) c = -1.0f;
+        volatile float sc = c * nlev;
+        const float k = rintf(sc);           /* default rounding mode: ties to even */
+        volatile float out = k * d;
+        q[i] = out;
+        if (levels) levels[i] = (int32_t)k;
+    }
+}
+
+void qnn_oracle_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float r = x[i] / t;
+        g_x[i] = (r >= -1.0f && r <= 1.0f) ? g_q[i] : 0.0f;
+    }
+}

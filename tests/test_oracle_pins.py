@@ -508,3 +508,133 @@ def test_encode_real_is_the_scaled_reencoder(oracle):
         assert (oracle.encode_real(x, bits) == v).all(), bits
         y = np.random.default_rng(bits).normal(0, 0.7, 500).astype(np.float32)
         assert (oracle.encode_real(y, bits) == oracle.requant(y * np.float32(alpha), bits)).all()
+
+
+# ------------------------------------------------------------------ front end: Tanh / Sigmoid of Table 1
+def _consts():
+    out = {}
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            if not line.startswith("#") and line.strip():
+                k, v = line.split()
+                out[k] = v
+    return out
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+def test_encode_smooth_against_numpy(oracle, bits):
+    """Tanh / Sigmoid of Table 1 followed by the Table 2 rule: away from the interval boundaries the
+    codes equal the rule applied to numpy's float64 tanh / logistic; Sigmoid only reaches the
+    positive codes (its range is (0,1), like HReLU's); Tanh is odd."""
+    r = rng(60 + bits)
+    x = r.uniform(-4, 4, 20000).astype(np.float32)
+    alpha = (1 << bits) - 1
+    for clip, fn in (("tanh", np.tanh), ("sigmoid", lambda v: 1.0 / (1.0 + np.exp(-v)))):
+        codes, limited = oracle.encode_smooth(x, bits, clip)
+        y = fn(x.astype(np.float64)) * alpha
+        assert np.abs(limited.astype(np.float64) - fn(x.astype(np.float64))).max() < 1e-7
+        clear = np.abs(y - 2 * np.round(y / 2)) > 1e-4            # not within 1e-4 of an interval boundary
+        mag = np.minimum(2 * np.floor(np.abs(y) / 2) + 1, alpha)
+        want = np.where(y > 0, mag, -mag)
+        assert clear.mean() > 0.99
+        assert (codes[clear] == want[clear]).all()
+        if clip == "sigmoid":
+            assert (codes >= 1).all()
+        else:
+            back, _ = oracle.encode_smooth(-x, bits, clip)
+            assert (back[clear] == -codes[clear]).all()
+    # saturation: far out the limiters reach the extreme states
+    far = np.array([-30.0, 30.0], dtype=np.float32)
+    assert (oracle.encode_smooth(far, bits, "tanh")[0] == np.array([-alpha, alpha])).all()
+    assert oracle.encode_smooth(far, bits, "sigmoid")[0][1] == alpha
+
+
+# ------------------------------------------------------------------ training-side pieces (Sec. 4)
+def test_encoder_backward_printed_two_bit_case(oracle):
+    """Eq. (13): at x = 0 the high bit's derivative is (3/4) pi and the low bit's -(3/2) pi; outside
+    [-1, 1] both vanish."""
+    c = _consts()
+    hi, lo = float(Fraction(c["enc2_dhigh_at0_over_pi"])), float(Fraction(c["enc2_dlow_at0_over_pi"]))
+    x = np.array([0.0, 0.0, 1.5, -1.0001], dtype=np.float32)
+    only_low = np.array([[1, 0, 1, 1], [0, 0, 0, 0]], dtype=np.float32)
+    only_high = np.array([[0, 0, 0, 0], [1, 1, 1, 1]], dtype=np.float32)
+    assert np.allclose(oracle.encoder_backward(x, only_low), [lo * np.pi, 0, 0, 0], rtol=1e-12, atol=0)
+    assert np.allclose(oracle.encoder_backward(x, only_high), [hi * np.pi, hi * np.pi, 0, 0], rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8])
+def test_encoder_backward_is_the_slope_of_the_trigonometric_encoder(oracle, M):
+    """Eq. (12) is the derivative of the function under the sign in Eq. (10): central differences of
+    +-sin((2^M - 1) / 2^m pi x) in float64 reproduce every bit's term, and the terms add up linearly."""
+    r = rng(70 + M)
+    x = r.uniform(-1, 1, 500).astype(np.float32)
+    g = r.normal(size=(M, x.size)).astype(np.float32)
+    xd = x.astype(np.float64)
+    h = 1e-6
+    want = np.zeros_like(xd)
+    for m in range(1, M + 1):
+        c = (2 ** M - 1) / 2 ** m * np.pi
+        f = (lambda v: np.sin(c * v)) if m == M else (lambda v: -np.sin(c * v))
+        want += g[m - 1] * (f(xd + h) - f(xd - h)) / (2 * h)
+    got = oracle.encoder_backward(x, g)
+    assert np.abs(got - want).max() <= 1e-4 * (1 + np.abs(want).max())
+    assert (oracle.encoder_backward(np.array([1.01, -7.0, 2.0], dtype=np.float32), np.ones((M, 3), np.float32)) == 0).all()
+    # the ends of the interval belong to it
+    assert (oracle.encoder_backward(np.array([1.0, -1.0], dtype=np.float32), np.ones((M, 2), np.float32)) != 0).all()
+
+
+def test_binarize_and_its_gradient(oracle):
+    """Eq. (14): sign(HTanh(w)), values in {-1,+1}, zero on the + side; the gradient passes exactly
+    where HTanh is the identity."""
+    w = np.array([-3.0, -1.0, -0.2, -0.0, 0.0, 1e-30, 0.7, 1.0, 1.0001, 5.0], dtype=np.float32)
+    wb = oracle.binarize(w)
+    assert (wb == np.array([-1, -1, -1, 1, 1, 1, 1, 1, 1, 1])).all()
+    htanh = np.clip(w, -1, 1)
+    nz = htanh != 0
+    assert (wb[nz] == np.sign(htanh[nz])).all()
+    g = np.arange(1, 11, dtype=np.float32)
+    assert (oracle.binarize_backward(w, g) == np.array([0, 2, 3, 4, 5, 6, 7, 8, 0, 0], dtype=np.float32)).all()
+    # with one bit the code of a non-zero weight is the Eq. (7) code of its sign
+    r = rng(81)
+    v = r.normal(size=1000).astype(np.float32)
+    assert (oracle.binarize(v) == np.where(v >= 0, 1, -1)).all()
+
+
+@pytest.mark.parametrize("K", [2, 3, 4, 8])
+def test_quantize_k_properties(oracle, K):
+    """Eq. (15): 2^K - 1 equally spaced states k * d with |k| <= 2^(K-1) - 1 and d = t / (2^(K-1) - 1);
+    within the clamp the error is at most d / 2; the map is monotone and idempotent; the ends are
+    +-t; midpoints go to the even state (the reading of `round`); numpy's float32 arithmetic with
+    rint gives the same values."""
+    r = rng(90 + K)
+    t = np.float32(0.75)
+    n = 2 ** (K - 1) - 1
+    d = np.float32(t / np.float32(n))
+    x = np.sort(r.uniform(-1.5, 1.5, 5000).astype(np.float32))
+    q, lv = oracle.quantize_k(x, K, t)
+    assert set(np.unique(lv)) == set(range(-n, n + 1))
+    assert (q == lv.astype(np.float32) * d).all()
+    inside = np.abs(x) <= t
+    assert (np.abs(q[inside].astype(np.float64) - x[inside]) <= float(d) / 2 * (1 + 1e-6)).all()
+    assert (np.diff(q) >= 0).all()
+    assert (oracle.quantize_k(q, K, t)[0] == q).all()
+    assert (oracle.quantize_k(np.array([t, -t, 9.0, -9.0], dtype=np.float32), K, t)[0] == np.array([t, -t, t, -t])).all()
+    want = np.rint(np.clip(x / t, np.float32(-1), np.float32(1)) * np.float32(n)).astype(np.float32) * d
+    assert (q == want).all()
+    if n >= 2:
+        half = np.array([0.5, 1.5, -0.5, -1.5], dtype=np.float32) / np.float32(n)      # x/t*n exactly at midpoints (t = 1)
+        assert (oracle.quantize_k(half, K, 1.0)[1] == np.array([0, 2, 0, -2])).all()
+    g = np.ones_like(x)
+    assert (oracle.quantize_k_backward(x, g, t) == (np.abs(x / t) <= 1).astype(np.float32)).all()
+
+
+def test_speedup_model_reading(oracle):
+    """Eq. (16) with the constants of Sec. 5.4 (gamma = 1.91, L = 64, beta = gamma / 2) at N = 8192
+    reproduces the printed 2-bit figure; this is the reading quoted as context beside the measured
+    8192^3 sweep."""
+    c = _consts()
+    gamma, L = float(c["gamma"]), int(c["register_bits"])
+    beta = gamma / 2
+    S = lambda M, K, N: N * gamma / (M * K * (gamma + 2 * -(-N // L)) + (M * K - 1) * beta)
+    assert abs(S(2, 2, 8192) - float(c["speedup_2bit"])) < 0.01          # 15.125 against the printed ~15.13
+    assert S(1, 1, 8192) > S(2, 2, 8192) > S(3, 3, 8192) > S(6, 6, 8192) > 1.0
