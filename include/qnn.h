@@ -193,14 +193,54 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
 /*
  * Real-valued front end (Sec. 3.2: the data is limited to a fixed range, Table 1, and then mapped
  * to its encoded state, Table 2 / the look-up form of the MBitEncoder of Eq. (10)).
- *   x      fp32 [rows][K], nominally in [-1,1];  hrelu = 1 first clips to [0,1] (x <= 0 and NaN -> 0).
- *   y = x * (2^bits - 1) in binary32 (one multiply), then the rule of qnn_requant_pack: values
- *   beyond +-1 take the extreme states (the HTanh clip), [2j, 2j+2)/(2^bits-1) -> code 2j+1,
- *   zero -> -1.  Outputs as in qnn_requant_pack: codes int8/int16 [rows][K] and/or planes
- *   uint32 [rows][bits][ceil(K/32)]; at least one must be given.
+ *   x      fp32 [rows][K];  clip selects the range limiter of Table 1:
+ *            QNN_CLIP_HTANH    values beyond +-1 take the extreme states (the clamp of the rule below),
+ *            QNN_CLIP_HRELU    first clips to [0,1] (x <= 0 and NaN -> 0),
+ *            QNN_CLIP_TANH     x -> tanh(x),
+ *            QNN_CLIP_SIGMOID  x -> 1 / (1 + exp(-x))
+ *          (the two smooth ones in binary32 with the device math library, accurate to a few units of
+ *          the last place: an input whose limited value lies within about 1e-6 of an interval
+ *          boundary may land in the neighbouring state).
+ *   y = limited x * (2^bits - 1) in binary32 (one multiply), then the rule of qnn_requant_pack:
+ *   [2j, 2j+2)/(2^bits-1) -> code 2j+1, zero -> -1.  Outputs as in qnn_requant_pack: codes
+ *   int8/int16 [rows][K] and/or planes uint32 [rows][bits][ceil(K/32)]; at least one must be given.
  */
-qnn_status qnn_encode_real(const float *x, int64_t rows, int64_t K, int bits, int hrelu, void *codes,
+#define QNN_CLIP_HTANH 0
+#define QNN_CLIP_HRELU 1
+#define QNN_CLIP_TANH 2
+#define QNN_CLIP_SIGMOID 3
+qnn_status qnn_encode_real(const float *x, int64_t rows, int64_t K, int bits, int clip, void *codes,
                            uint32_t *planes, void *stream);
+
+/*
+ * Element-wise pieces of the training procedures of Sec. 4 (none of them is on the inference path).
+ *
+ * qnn_encoder_backward   Eq. (12) / Alg. 1 "BackMBitEncoder": the gradient with respect to the real
+ *   activation x from the gradients of its `bits` encoded elements,
+ *       g_x[i] = sum_{m=1..bits} g_bits[m-1][i] * d phi^m / dx (x[i]),
+ *       d phi^m / dx = s_m c_m pi cos(c_m pi x) for -1 <= x <= 1, else 0,
+ *       c_m = (2^bits - 1) / 2^m,  s_m = +1 for m = bits (the high element), -1 otherwise.
+ *   x fp32 [n], g_bits fp32 [bits][n] (low element first), g_x fp32 [n].
+ *
+ * qnn_binarize           Eq. (14): w_b = sign(HTanh(w)) with sign(0) = +1 (NaN -> -1), w fp32 [rows][K].
+ *   codes   optional int8 [rows][K], values -1 / +1;
+ *   planes  optional 1-bit planes uint32 [rows][1][ceil(K/32)] (16-byte aligned) in the layout of
+ *           qnn_encode_pack, i.e. directly usable as the weight operand of the product entry points.
+ * qnn_binarize_backward  g_w = g_wb where |w| <= 1 (HTanh is the identity there), else 0; fp32 [n].
+ *
+ * qnn_quantize_k         Eq. (15): q = round(clamp(x / t, 1) * (2^(bits-1) - 1)) * d with
+ *   d = t / (2^(bits-1) - 1), every step one binary32 operation, round = to nearest, ties to even;
+ *   2 <= bits <= 24, t > 0 finite (else QNN_EINVAL).  q fp32 [n] and/or levels int32 [n] (the integer
+ *   state in -(2^(bits-1)-1) .. 2^(bits-1)-1); at least one must be given.
+ * qnn_quantize_k_backward  straight-through gradient: g_x = g_q where |x / t| <= 1, else 0.
+ *
+ * n == 0 (rows == 0 or K == 0) launches nothing.  Limits: n * bits < 2^40.
+ */
+qnn_status qnn_encoder_backward(const float *x, const float *g_bits, int64_t n, int bits, float *g_x, void *stream);
+qnn_status qnn_binarize(const float *w, int64_t rows, int64_t K, int8_t *codes, uint32_t *planes, void *stream);
+qnn_status qnn_binarize_backward(const float *w, const float *g_wb, int64_t n, float *g_w, void *stream);
+qnn_status qnn_quantize_k(const float *x, int64_t n, int bits, float t, float *q, int32_t *levels, void *stream);
+qnn_status qnn_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x, void *stream);
 
 /*
  * Chained layers (Alg. 1 forward as one kernel: branch sum, scale, re-encode).  The *_requant

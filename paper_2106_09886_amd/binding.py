@@ -24,7 +24,8 @@ EXPORTS = (
     "qnn_conv2d_packed", "qnn_requant_pack", "qnn_scale_epilogue",
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
-    "qnn_encode_real", "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
+    "qnn_encode_real", "qnn_encoder_backward", "qnn_binarize", "qnn_binarize_backward", "qnn_quantize_k",
+    "qnn_quantize_k_backward", "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
     "qnn_compare_dot4_gemm",
     "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
 )
@@ -119,6 +120,16 @@ def lib():
     L.qnn_compare_dot4_gemm.restype = i32
     L.qnn_encode_real.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
     L.qnn_encode_real.restype = i32
+    L.qnn_encoder_backward.argtypes = [vp, vp, i64, i32, vp, vp]
+    L.qnn_encoder_backward.restype = i32
+    L.qnn_binarize.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.qnn_binarize.restype = i32
+    L.qnn_binarize_backward.argtypes = [vp, vp, i64, vp, vp]
+    L.qnn_binarize_backward.restype = i32
+    L.qnn_quantize_k.argtypes = [vp, i64, i32, ctypes.c_float, vp, vp, vp]
+    L.qnn_quantize_k.restype = i32
+    L.qnn_quantize_k_backward.argtypes = [vp, vp, i64, ctypes.c_float, vp, vp]
+    L.qnn_quantize_k_backward.restype = i32
     gp = ctypes.POINTER(ConvGeometry)
     L.qnn_conv2d_general_output_size.argtypes = [i64, i64, gp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.qnn_conv2d_general_output_size.restype = i32
@@ -411,15 +422,67 @@ def conv2d_general(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, geo, scale=None, wan
     return acc, o32, planes
 
 
-def encode_real(x, bits, hrelu=False, want_codes=True, want_planes=True):
-    """x fp32 [rows][K] -> (codes int8/int16 | None, planes int32 [rows][bits][Kw] | None)."""
+CLIPS = {"htanh": 0, "hrelu": 1, "tanh": 2, "sigmoid": 3}
+
+
+def encode_real(x, bits, hrelu=False, want_codes=True, want_planes=True, clip=None):
+    """x fp32 [rows][K] -> (codes int8/int16 | None, planes int32 [rows][bits][Kw] | None).
+    clip: "htanh" (default), "hrelu", "tanh" or "sigmoid" (Table 1); hrelu=True is "hrelu"."""
     _dev(x, torch.float32, "x")
     rows, K = x.shape
+    mode = CLIPS[clip] if clip is not None else (1 if hrelu else 0)
     codes = torch.empty((rows, K), dtype=torch.int8 if bits <= 7 else torch.int16, device=x.device) if want_codes else None
     planes = torch.empty((rows, bits, (K + 31) // 32), dtype=torch.int32, device=x.device) if want_planes else None
-    st = lib().qnn_encode_real(_ptr(x), rows, K, bits, 1 if hrelu else 0, _ptr(codes), _ptr(planes), _stream())
+    st = lib().qnn_encode_real(_ptr(x), rows, K, bits, mode, _ptr(codes), _ptr(planes), _stream())
     _check(st, "qnn_encode_real")
     return codes, planes
+
+
+def encoder_backward(x, g_bits):
+    """x fp32 [n], g_bits fp32 [bits][n] -> g_x fp32 [n] (Eq. (12))."""
+    _dev(x, torch.float32, "x")
+    _dev(g_bits, torch.float32, "g_bits")
+    out = torch.empty_like(x)
+    _check(lib().qnn_encoder_backward(_ptr(x), _ptr(g_bits), x.numel(), g_bits.shape[0], _ptr(out), _stream()),
+           "qnn_encoder_backward")
+    return out
+
+
+def binarize(w, want_codes=True, want_planes=True):
+    """w fp32 [rows][K] -> (codes int8 +-1 | None, planes int32 [rows][1][Kw] | None) (Eq. (14))."""
+    _dev(w, torch.float32, "w")
+    rows, K = w.shape
+    codes = torch.empty((rows, K), dtype=torch.int8, device=w.device) if want_codes else None
+    planes = torch.empty((rows, 1, (K + 31) // 32), dtype=torch.int32, device=w.device) if want_planes else None
+    _check(lib().qnn_binarize(_ptr(w), rows, K, _ptr(codes), _ptr(planes), _stream()), "qnn_binarize")
+    return codes, planes
+
+
+def binarize_backward(w, g_wb):
+    _dev(w, torch.float32, "w")
+    _dev(g_wb, torch.float32, "g_wb")
+    out = torch.empty_like(w)
+    _check(lib().qnn_binarize_backward(_ptr(w), _ptr(g_wb), w.numel(), _ptr(out), _stream()), "qnn_binarize_backward")
+    return out
+
+
+def quantize_k(x, bits, t):
+    """-> (q fp32, levels int32) of Eq. (15)."""
+    _dev(x, torch.float32, "x")
+    q = torch.empty_like(x)
+    lv = torch.empty(x.shape, dtype=torch.int32, device=x.device)
+    _check(lib().qnn_quantize_k(_ptr(x), x.numel(), bits, ctypes.c_float(t), _ptr(q), _ptr(lv), _stream()),
+           "qnn_quantize_k")
+    return q, lv
+
+
+def quantize_k_backward(x, g_q, t):
+    _dev(x, torch.float32, "x")
+    _dev(g_q, torch.float32, "g_q")
+    out = torch.empty_like(x)
+    _check(lib().qnn_quantize_k_backward(_ptr(x), _ptr(g_q), x.numel(), ctypes.c_float(t), _ptr(out), _stream()),
+           "qnn_quantize_k_backward")
+    return out
 
 
 def compare_mfma_arrange(codes):

@@ -566,16 +566,58 @@ qnn_status qnn_requant_pack(const float *y, int64_t Nb, int64_t H, int64_t W, in
     return from_hip(launch_requant(y, Nb, H, W, C, pool2x2 != 0, bits, 1.0f, 0, codes, planes, (hipStream_t)stream));
 }
 
-qnn_status qnn_encode_real(const float *x, int64_t rows, int64_t K, int bits, int hrelu, void *codes,
+qnn_status qnn_encode_real(const float *x, int64_t rows, int64_t K, int bits, int clip, void *codes,
                            uint32_t *planes, void *stream) {
-    if (!bits_ok(bits) || rows < 0 || K < 0 || (hrelu != 0 && hrelu != 1)) return QNN_EINVAL;
+    if (!bits_ok(bits) || rows < 0 || K < 0 || clip < QNN_CLIP_HTANH || clip > QNN_CLIP_SIGMOID) return QNN_EINVAL;
     if (rows > kInt31 || K > kInt31) return QNN_EUNSUPPORTED;
     if (rows == 0 || K == 0) return QNN_OK;
     if (x == nullptr || (codes == nullptr && planes == nullptr)) return QNN_EINVAL;
     if (!aligned4(x) || !aligned16(planes)) return QNN_EALIGN;
     if (bits == 8 && (((uintptr_t)codes) & 1u)) return QNN_EALIGN;
     const float alpha = (float)((1 << bits) - 1);
-    return from_hip(launch_requant(x, 1, 1, rows, K, false, bits, alpha, hrelu, codes, planes, (hipStream_t)stream));
+    return from_hip(launch_requant(x, 1, 1, rows, K, false, bits, alpha, clip, codes, planes, (hipStream_t)stream));
+}
+
+qnn_status qnn_encoder_backward(const float *x, const float *g_bits, int64_t n, int bits, float *g_x, void *stream) {
+    if (!bits_ok(bits) || n < 0) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (x == nullptr || g_bits == nullptr || g_x == nullptr) return QNN_EINVAL;
+    if (!aligned4(x) || !aligned4(g_bits) || !aligned4(g_x)) return QNN_EALIGN;
+    if (n > (((int64_t)1 << 40) - 1) / bits) return QNN_EUNSUPPORTED;
+    return from_hip(launch_encoder_backward(x, g_bits, n, bits, g_x, (hipStream_t)stream));
+}
+
+qnn_status qnn_binarize(const float *w, int64_t rows, int64_t K, int8_t *codes, uint32_t *planes, void *stream) {
+    if (rows < 0 || K < 0) return QNN_EINVAL;
+    if (K > kInt31 || rows > kInt31) return QNN_EUNSUPPORTED;
+    if (rows == 0 || K == 0) return QNN_OK;
+    if (w == nullptr || (codes == nullptr && planes == nullptr)) return QNN_EINVAL;
+    if (!aligned4(w) || !aligned16(planes)) return QNN_EALIGN;
+    return from_hip(launch_binarize(w, rows, K, codes, planes, (hipStream_t)stream));
+}
+
+qnn_status qnn_binarize_backward(const float *w, const float *g_wb, int64_t n, float *g_w, void *stream) {
+    if (n < 0) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (w == nullptr || g_wb == nullptr || g_w == nullptr) return QNN_EINVAL;
+    if (!aligned4(w) || !aligned4(g_wb) || !aligned4(g_w)) return QNN_EALIGN;
+    return from_hip(launch_binarize_backward(w, g_wb, n, g_w, (hipStream_t)stream));
+}
+
+qnn_status qnn_quantize_k(const float *x, int64_t n, int bits, float t, float *q, int32_t *levels, void *stream) {
+    if (bits < 2 || bits > 24 || n < 0 || !(t > 0.0f) || !(t <= 3.0e38f)) return QNN_EINVAL;   // one bit has no state besides 0
+    if (n == 0) return QNN_OK;
+    if (x == nullptr || (q == nullptr && levels == nullptr)) return QNN_EINVAL;
+    if (!aligned4(x) || !aligned4(q) || !aligned4(levels)) return QNN_EALIGN;
+    return from_hip(launch_quantize_k(x, n, bits, t, q, levels, (hipStream_t)stream));
+}
+
+qnn_status qnn_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x, void *stream) {
+    if (n < 0 || !(t > 0.0f) || !(t <= 3.0e38f)) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (x == nullptr || g_q == nullptr || g_x == nullptr) return QNN_EINVAL;
+    if (!aligned4(x) || !aligned4(g_q) || !aligned4(g_x)) return QNN_EALIGN;
+    return from_hip(launch_quantize_k_backward(x, g_q, n, t, g_x, (hipStream_t)stream));
 }
 
 qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *q, int64_t *h_Ho,

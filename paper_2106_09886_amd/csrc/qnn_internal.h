@@ -232,7 +232,12 @@ typedef hipError_t (*im2col_launch_fn)(const void *, int, int64_t, int, int, int
 hipError_t launch_pack(const void *codes, int code_bytes, int64_t rows, int64_t K, int bits,
                        uint32_t *planes, int32_t *bad_count, bool validate, hipStream_t);
 hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
-                          float premul, int hrelu, void *codes, uint32_t *planes, hipStream_t);
+                          float premul, int clip, void *codes, uint32_t *planes, hipStream_t);
+hipError_t launch_encoder_backward(const float *x, const float *g, int64_t n, int bits, float *gx, hipStream_t);
+hipError_t launch_binarize(const float *w, int64_t rows, int64_t K, int8_t *codes, uint32_t *planes, hipStream_t);
+hipError_t launch_binarize_backward(const float *w, const float *g_wb, int64_t n, float *g_w, hipStream_t);
+hipError_t launch_quantize_k(const float *x, int64_t n, int bits, float t, float *q, int32_t *levels, hipStream_t);
+hipError_t launch_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x, hipStream_t);
 hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, int64_t Wo, int64_t Cw, int bits,
                               uint32_t *out, hipStream_t);
 hipError_t launch_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, void *out, hipStream_t);

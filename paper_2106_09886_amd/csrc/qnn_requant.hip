@@ -22,6 +22,15 @@ namespace {
 
 // Stored index u = (code + 2^BITS - 1) / 2 of the rule above: with H = 2^(BITS-1) and
 // f = min(floor(|y|/2), H-1),  u = f xor (y > 0 ? H : H-1)  (and code = 2u - (2^BITS - 1)).
+// The range limiters of Table 1 in front of the encoder: 0 HTanh (the clamp of the rule itself),
+// 1 HReLU (x <= 0 and NaN -> 0), 2 Tanh, 3 Sigmoid (binary32, device math library).
+__device__ __forceinline__ float limit_range(float v, int clip) {
+    if (clip == 1) return (v > 0.0f) ? v : 0.0f;
+    if (clip == 2) return tanhf(v);
+    if (clip == 3) return 1.0f / (1.0f + expf(-v));
+    return v;
+}
+
 template <int BITS>
 __device__ __forceinline__ uint32_t round_odd_index(float y) {
     constexpr uint32_t H = 1u << (BITS - 1);
@@ -35,7 +44,7 @@ __device__ __forceinline__ uint32_t round_odd_index(float y) {
 // is consumed, so that a wavefront keeps U (4U with pooling) 256-byte rows in flight.
 template <typename CodeT, int BITS, bool POOL, int U>
 __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restrict__ y, int64_t out_pixels,
-                                                           int Ho, int Wo, int C, float premul, int hrelu,
+                                                           int Ho, int Wo, int C, float premul, int clip,
                                                            CodeT *__restrict__ codes,
                                                            uint32_t *__restrict__ planes) {
     constexpr int VMAX = (1 << BITS) - 1;
@@ -98,8 +107,7 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
             if (it0 + u >= items) break;                    // wave-uniform
             // real-valued front end (Table 1, Table 2): clip to [0,1] if asked, then one binary32
             // multiply by 2^bits - 1 brings the number space onto the code grid (re-encoding: x 1)
-            float val = v[u];
-            if (hrelu) val = (val > 0.0f) ? val : 0.0f;
+            const float val = limit_range(v[u], clip);
             const uint32_t uidx = valid[u] ? round_odd_index<BITS>(val * premul) : 0u;   // 0: all plane bits clear
             const int c = cg[u] * 64 + lane;
             if (codes != nullptr && valid[u]) codes[pix[u] * (int64_t)C + c] = (CodeT)(2 * (int)uidx - VMAX);
@@ -127,7 +135,7 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
 // stepped.  Per item the vector ALU sees 7 instructions for the rule and 3 per plane.
 template <typename CodeT, int BITS, int U, bool FRONT, bool CODES, bool PLANES>
 __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restrict__ y, int items, int cgroups,
-                                                           FastDiv div_groups, float premul, int hrelu,
+                                                           FastDiv div_groups, float premul, int clip,
                                                            CodeT *__restrict__ codes, uint32_t *__restrict__ planes) {
     constexpr int VMAX = (1 << BITS) - 1;
     const int lane = (int)(threadIdx.x & 63);
@@ -158,10 +166,7 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
         }
         auto item = [&](int u) {
             float val = v[u];
-            if constexpr (FRONT) {
-                if (hrelu) val = (val > 0.0f) ? val : 0.0f;
-                val *= premul;
-            }
+            if constexpr (FRONT) val = limit_range(val, clip) * premul;
             const uint32_t uidx = round_odd_index<BITS>(val);
             if constexpr (CODES) {
                 const int code = 2 * (int)uidx - VMAX;
@@ -190,18 +195,18 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
 }
 
 template <typename CodeT, int BITS>
-hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, float premul, int hrelu,
+hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, float premul, int clip,
                      void *codes, uint32_t *planes, unsigned blocks, hipStream_t s) {
     if (pool)
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
-                           out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
+                           out_pixels, Ho, Wo, C, premul, clip, (CodeT *)codes, planes);
     else if (C % 64 == 0 && out_pixels * (C / 64) < ((int64_t)1 << 30)) {
         const int items = (int)(out_pixels * (C / 64)), groups = C / 64;
         const FastDiv dg = fast_div_for(groups);
-        const bool front = hrelu || premul != 1.0f;
+        const bool front = clip || premul != 1.0f;
         CodeT *cp = (CodeT *)codes;
 #define QNN_FLAT(F, CO, PL) hipLaunchKernelGGL((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL>), dim3(blocks), dim3(256), 0, s, \
-                                               y, items, groups, dg, premul, hrelu, cp, planes)
+                                               y, items, groups, dg, premul, clip, cp, planes)
         if (front) {
             if (cp && planes) QNN_FLAT(true, true, true);
             else if (planes) QNN_FLAT(true, false, true);
@@ -215,7 +220,7 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
     }
     else
         hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
-                           out_pixels, Ho, Wo, C, premul, hrelu, (CodeT *)codes, planes);
+                           out_pixels, Ho, Wo, C, premul, clip, (CodeT *)codes, planes);
     return hipGetLastError();
 }
 
@@ -286,7 +291,7 @@ hipError_t launch_pool_planes_t(const uint32_t *in, int64_t items, int Ho, int W
 }  // namespace
 
 hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t C, bool pool, int bits,
-                          float premul, int hrelu, void *codes, uint32_t *planes, hipStream_t s) {
+                          float premul, int clip, void *codes, uint32_t *planes, hipStream_t s) {
     const int Ho = (int)(pool ? H / 2 : H), Wo = (int)(pool ? W / 2 : W);
     const int64_t out_pixels = Nb * Ho * (int64_t)Wo;
     const int64_t items = out_pixels * ((C + 63) / 64);
@@ -295,7 +300,7 @@ hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int6
     const int64_t want = (items + 3) / 4;
     const int64_t cap = (int64_t)device_simd_count() * 2;
     const unsigned blocks = (unsigned)(want < cap ? want : cap);
-#define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, out_pixels, Ho, Wo, (int)C, pool, premul, hrelu, codes, planes, blocks, s)
+#define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, out_pixels, Ho, Wo, (int)C, pool, premul, clip, codes, planes, blocks, s)
     switch (bits) {
         QNN_RQ(1, int8_t); QNN_RQ(2, int8_t); QNN_RQ(3, int8_t); QNN_RQ(4, int8_t);
         QNN_RQ(5, int8_t); QNN_RQ(6, int8_t); QNN_RQ(7, int8_t); QNN_RQ(8, int16_t);

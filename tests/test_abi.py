@@ -224,7 +224,8 @@ def test_encode_real_argument_errors(L):
     from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK
     f = L.qnn_encode_real
     assert f(P, 4, 64, 0, 0, P, P, None) == QNN_EINVAL
-    assert f(P, 4, 64, 2, 2, P, P, None) == QNN_EINVAL            # hrelu is 0 or 1
+    assert f(P, 4, 64, 2, 4, P, P, None) == QNN_EINVAL            # clip is one of the four range limiters
+    assert f(P, 4, 64, 2, -1, P, P, None) == QNN_EINVAL
     assert f(P, -1, 64, 2, 0, P, P, None) == QNN_EINVAL
     assert f(None, 4, 64, 2, 0, P, P, None) == QNN_EINVAL
     assert f(P, 4, 64, 2, 0, None, None, None) == QNN_EINVAL
@@ -282,3 +283,32 @@ def test_static_scratch_entry_point_checks_on_the_host(L):
     assert f(P, 1, 2, P, 2, 1, 4, 4, 64, 64, None, None, None, None) == QNN_EINVAL       # no output
     assert f(P, 1, 2, P + 4, 2, 1, 4, 4, 64, 64, P, None, None, None) == QNN_EALIGN
     assert f(None, 1, 2, None, 2, 0, 4, 4, 64, 64, None, None, None, None) == QNN_OK     # empty: nothing launched
+
+
+def test_training_side_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK
+    f = L.qnn_encoder_backward
+    assert f(P, P, 16, 0, P, None) == QNN_EINVAL and f(P, P, 16, 9, P, None) == QNN_EINVAL
+    assert f(None, P, 16, 2, P, None) == QNN_EINVAL and f(P, None, 16, 2, P, None) == QNN_EINVAL
+    assert f(P, P, 16, 2, None, None) == QNN_EINVAL and f(P, P, -1, 2, P, None) == QNN_EINVAL
+    assert f(P + 2, P, 16, 2, P, None) == QNN_EALIGN
+    assert f(None, None, 0, 2, None, None) == QNN_OK
+    f = L.qnn_binarize
+    assert f(P, -1, 8, P, P, None) == QNN_EINVAL and f(None, 4, 8, P, P, None) == QNN_EINVAL
+    assert f(P, 4, 8, None, None, None) == QNN_EINVAL
+    assert f(P, 4, 8, None, P + 4, None) == QNN_EALIGN
+    assert f(None, 0, 8, None, None, None) == QNN_OK
+    f = L.qnn_binarize_backward
+    assert f(P, P, -1, P, None) == QNN_EINVAL and f(P, None, 4, P, None) == QNN_EINVAL
+    assert f(None, None, 0, None, None) == QNN_OK
+    f = L.qnn_quantize_k
+    c = ctypes.c_float
+    assert f(P, 16, 1, c(1.0), P, None, None) == QNN_EINVAL          # one bit has no state but 0
+    assert f(P, 16, 25, c(1.0), P, None, None) == QNN_EINVAL
+    assert f(P, 16, 3, c(0.0), P, None, None) == QNN_EINVAL and f(P, 16, 3, c(-1.0), P, None, None) == QNN_EINVAL
+    assert f(P, 16, 3, c(float("nan")), P, None, None) == QNN_EINVAL
+    assert f(P, 16, 3, c(1.0), None, None, None) == QNN_EINVAL
+    assert f(None, 0, 3, c(1.0), None, None, None) == QNN_OK
+    f = L.qnn_quantize_k_backward
+    assert f(P, P, 16, c(0.0), P, None) == QNN_EINVAL and f(P, None, 16, c(1.0), P, None) == QNN_EINVAL
+    assert f(None, None, 0, c(1.0), None, None) == QNN_OK
