@@ -918,8 +918,8 @@ hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
 
 template <int AB, int WB>
 hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
-    // plane strides with a dedicated instantiation (bit widths up to 4 only, to bound build time)
-    if constexpr (AB <= 4 && WB <= 4) {
+    // plane strides with a dedicated instantiation (a bounded list of bit widths, see conv_has_fixed_widths)
+    if constexpr (conv_has_fixed_widths(AB, WB)) {
         switch (g.Cw) {
             case 1: return launch_conv_fixed<AB, WB, 1>(g, s);
             case 2: return launch_conv_fixed<AB, WB, 2>(g, s);

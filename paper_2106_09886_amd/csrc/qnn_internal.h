@@ -117,7 +117,7 @@ struct ConvShapeV {
 constexpr int conv_pow2_floor(int x) { return x >= 16 ? 16 : x >= 8 ? 8 : x >= 4 ? 4 : x >= 2 ? 2 : 1; }
 constexpr int conv_shape_score(int ab, int wb, int cws, int cwt, int tpc) {
     const int cmax = cws < conv_pow2_floor(32 / ab) ? cws : conv_pow2_floor(32 / ab);
-    return (cwt <= cmax && tpc * wb * cwt <= 80) ? cwt * tpc : 0;
+    return (cwt <= cmax && tpc * wb * cwt <= (wb >= 5 ? 96 : 80)) ? cwt * tpc : 0;
 }
 constexpr ConvShapeV conv_shape(int ab, int wb, int cws) {
     int bc = 1, bs = 0;
@@ -142,9 +142,16 @@ static_assert(conv_shape(2, 2, 2).cwt == 2 && conv_shape(2, 2, 2).tpc == 9 && co
               conv_shape(2, 2, 2).p == 2, "ResNet-18 stage-1 shape: whole product in one pass, pixel pairs");
 static_assert(conv_shape(4, 3, 8).cwt == 8 && conv_shape(4, 3, 8).tpc == 3, "ResNet-50 stage-3 shape: one kernel row per pass");
 static_assert(conv_shape(4, 2, 16).cwt == 4 && conv_shape(4, 2, 16).tpc == 9, "512-channel W2A4: four passes of nine taps");
-// does the convolution launcher have an instantiation with this compile-time plane stride
+// Does the convolution launcher have an instantiation with this compile-time plane stride?  Bit
+// widths up to 4 x 4, plus the wider pairs of the paper's mixed-precision tables (Table 4: 4-bit
+// activations with 5- and 6-bit weights; 8-bit activations with 6- to 8-bit weights): a bounded
+// list, to bound build time.  (Weight widths from 5 bits on may use 96 instead of 80 weight
+// registers per chunk, so that a 64-channel layer with 5-bit weights keeps all nine taps.)
+constexpr bool conv_has_fixed_widths(int ab, int wb) {
+    return (ab <= 4 && wb <= 6) || (ab == 8 && wb >= 6);
+}
 constexpr bool conv_has_fixed_shape(int ab, int wb, int cw) {
-    return ab <= 4 && wb <= 4 && (cw == 1 || cw == 2 || cw == 4 || cw == 8 || cw == 16);
+    return conv_has_fixed_widths(ab, wb) && (cw == 1 || cw == 2 || cw == 4 || cw == 8 || cw == 16);
 }
 // chunk passes a wavefront makes over its pixels
 constexpr int conv_passes(int ab, int wb, int cw) {
