@@ -71,6 +71,9 @@ qnn_status qnn_device_info(int *h_compute_units, int *h_clock_khz);
                                   /* contiguous range of blocks (of pixels) per XCD            */
 #define QNN_TUNE_LDS_PARTIALS 5   /* GEMM with several K chunks per wavefront: 1 partial sums   */
                                   /* through the output buffer, 2 in LDS where possible        */
+#define QNN_TUNE_SPLIT_CHANNELS 6 /* 3x3 convolution: 1 one wavefront per (pixel run, 64 filters), 2 the   */
+                                  /* four wavefronts of a block split the channel chunks where a      */
+                                  /* kernel for that exists (automatic: layers with few pixels)       */
 int qnn_tune(int key, int value);
 
 /*

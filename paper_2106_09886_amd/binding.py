@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libqnn.so")
 QNN_OK, QNN_EINVAL, QNN_EALIGN, QNN_EUNSUPPORTED, QNN_EWORKSPACE, QNN_EHIP = range(6)
 QNN_PACK_VALIDATE = 1
 QNN_TUNE_WAVES_PER_SIMD, QNN_TUNE_ROWS_PER_WAVE, QNN_TUNE_GENERAL_ONLY, QNN_TUNE_BLOCK_ORDER, QNN_TUNE_LDS_PARTIALS = 1, 2, 3, 4, 5
+QNN_TUNE_SPLIT_CHANNELS = 6
 
 EXPORTS = (
     "qnn_status_string", "qnn_last_hip_error", "qnn_version", "qnn_device_info", "qnn_tune", "qnn_set_wave_trace",
@@ -171,7 +172,10 @@ def device_info():
     return cus.value, khz.value
 
 
-def tune(waves_per_simd=None, rows_per_wave=None, general_only=None, block_order=None, lds_partials=None):
+def tune(waves_per_simd=None, rows_per_wave=None, general_only=None, block_order=None, lds_partials=None,
+         split_channels=None):
+    if split_channels is not None:
+        _check(lib().qnn_tune(QNN_TUNE_SPLIT_CHANNELS, int(split_channels)), "qnn_tune")
     if lds_partials is not None:
         _check(lib().qnn_tune(QNN_TUNE_LDS_PARTIALS, int(lds_partials)), "qnn_tune")
     if block_order is not None:

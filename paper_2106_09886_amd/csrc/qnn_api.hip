@@ -11,7 +11,7 @@ static __device__ __align__(256) unsigned char scratch[QNN_STATIC_SCRATCH_BYTES]
 namespace qnn {
 
 Tuning &tuning() {
-    static Tuning t = {0, 0, nullptr, 0, 0, 0, 0};
+    static Tuning t = {0, 0, nullptr, 0, 0, 0, 0, 0};
     return t;
 }
 
@@ -313,6 +313,19 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     const int group = (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, conv_passes(ab, wb, g.Cw), group), Cout),
                                           Cout, e);
+    // Few pixels and many channels: fewer than four wavefronts per SIMD would each make several
+    // chunk passes.  The variant whose four wavefronts per block split the channel chunks gives four
+    // times the wavefronts (measured on 32 x 7 x 7 x 512 -> 512, W2A4: see the design notes).
+    const int64_t plain_waves = ((rows + g.rows_per_wave - 1) / g.rows_per_wave) * g.col_tiles;
+    if (conv_can_split(ab, wb, g.Cw) && tuning().rows_per_wave == 0 && tuning().split_channels != 1 &&
+        (plain_waves < 4 * (int64_t)device_simd_count() || tuning().split_channels == 2)) {
+        const int chunks = g.Cw / conv_shape(ab, wb, g.Cw).cwt;
+        int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, (chunks + 3) / 4, 1);
+        if (rpb > kConvSplitRows) rpb = kConvSplitRows;
+        g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(rpb, Cout), Cout, e);
+        g.split_k = 1;
+        g.xcd_ranges = 0;
+    }
     g.grid_blocks = wave_grid_blocks(g);
     set_divisors(g, /*output_image=*/true);
     return from_hip(k_conv[ab - 1](g, wb, (hipStream_t)stream));
@@ -427,6 +440,10 @@ int qnn_tune(int key, int value) {
         case QNN_TUNE_LDS_PARTIALS:
             if (value > 2) return QNN_EINVAL;
             tuning().lds_partials = value;
+            return QNN_OK;
+        case QNN_TUNE_SPLIT_CHANNELS:
+            if (value > 2) return QNN_EINVAL;
+            tuning().split_channels = value;
             return QNN_OK;
         case QNN_TUNE_BLOCK_ORDER:
             if (value > 2) return QNN_EINVAL;

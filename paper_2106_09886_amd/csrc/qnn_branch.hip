@@ -572,8 +572,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
         // what earlier chunk passes left for this pixel, asked for before its products are formed
         int prev = 0;
         if constexpr (!SINGLE) {
-            if (!first)
-                prev = __builtin_amdgcn_raw_buffer_load_b32(ov.d0, ov.col_bytes, (int)((uint32_t)(r - r0) * ov.row_bytes), 0);
+            if (!first) prev = partial_load(ov, r - r0);
         }
         run_stages<0, FLIP>(c);
 #pragma unroll
@@ -582,7 +581,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
             int ncols = 3;
             if (x == 0) ncols -= (int)(edge & 1u);
             if (x == P - 1) ncols -= (int)(edge >> 1);
-            if (first) val += ncols * krow;
+            if (first && adds_const(ov)) val += ncols * krow;
             finish_row<SINGLE>(ov, r - r0 + x, val, /*first=*/true, last);   // earlier part already added
         }
         c.off_cur = c.off_nxt;
@@ -632,7 +631,7 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
         }
     }
     int val = -2 * weighted_sum(c.part[0]);
-    if (first) val += valid_taps<S>(pos, g.H, g.W) * g.kconst;
+    if (first && adds_const(ov)) val += valid_taps<S>(pos, g.H, g.W) * g.kconst;
     finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
 }
 
@@ -757,9 +756,55 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 // a compile-time choice: even a wave-uniform test of it at the start of every wavefront showed
 // in the time of the ResNet-18-shaped layer).
 // S: stride (1, or 2 for the fixed-shape instantiations; the tail paths are stride 1 only).
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false, int S = 1>
+//
+// SPLIT (layers with few output pixels and many input channels, e.g. 7x7 or 14x14 images with 512
+// channels): a launch with one wavefront per (pixel run, 64 filters) would leave one or two
+// wavefronts per SIMD, each making several chunk passes with nothing to hide its loads behind, and
+// a quarter of the SIMDs one wavefront short of the others.  Instead the four wavefronts of a block
+// share pixel run and filters and split the channel chunks (wavefront v takes chunks v, v+4, ...);
+// their partial sums meet in LDS (no trip through the output buffer), and after one barrier each
+// wavefront finishes every fourth row.  Four times the wavefronts, each with a single weight load.
+constexpr int kSplitRows = kConvSplitRows;       // most rows per block in the SPLIT variant
+
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false, int S = 1,
+          bool SPLIT = false>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     static_assert(S == 1 || CWS > 0, "strided: compile-time plane strides only");
+    if constexpr (SPLIT) {
+        static_assert(TPC == 9 && CWS > 0 && CWS / CWT >= 2 && !XR, "all taps per chunk, several channel chunks");
+        typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
+        __shared__ int slab[4 * kSplitRows * 64];
+        const int v = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const int lane = (int)(threadIdx.x & 63);
+        int rb, ct;
+        fast_divmod(blockIdx.x, g.div_tiles, rb, ct);
+        const int r0 = rb * g.rows_per_wave;                      // rows per BLOCK here (<= kSplitRows)
+        const int r1 = min(g.rows, r0 + g.rows_per_wave);
+        const int n = ct * 64 + lane;
+        const int nload = (n < g.N) ? n : g.N - 1;
+        uniform_words As = as_uniform(g.A);
+        const OutViewSlab sv = {slab + v * (kSplitRows * 64) + lane, v == 0};
+        bool mine = false;
+        for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT) {
+            conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, sv, As, nload, r0, r1, c0, 0, /*first=*/!mine, /*last=*/false);
+            mine = true;
+        }
+        if (!mine)
+            for (int r = 0; r < r1 - r0; ++r) sv.slab[r * 64] = 0;
+        __syncthreads();
+        // The output view is built only now: made opaque here, its inputs cannot be computed (and kept
+        // in registers the chunk passes need) before the barrier.
+        int r0_late = r0, ct_late = ct, nload_late = nload;
+        asm volatile("" : "+s"(r0_late), "+s"(ct_late), "+v"(nload_late));
+        const float sc = (g.scale != nullptr) ? g.scale[nload_late] : 1.0f;
+        const OV ov = make_out_view<OV>(g, r0_late, r1, nload_late, sc, ct_late);
+        for (int r = v; r < r1 - r0; r += 4) {
+            const int *row = slab + r * 64 + lane;
+            const int val = row[0] + row[kSplitRows * 64] + row[2 * kSplitRows * 64] + row[3 * kSplitRows * 64];
+            finish_row<true>(ov, r, val, true, true);
+        }
+        return;
+    }
     typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
     const WavePos wp = wave_pos<XR>(g.div_tiles, 1, g.grid_blocks);
     // a wavefront past the last row block keeps an empty row range
@@ -892,6 +937,23 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
+    if constexpr (conv_can_split(AB, WB, CWS)) {
+        if (g.split_k) {           // the block's wavefronts split the channel chunks (few pixels, many channels)
+            const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
+            const dim3 grid((unsigned)(row_blocks * g.col_tiles));
+            if (g.rows_per_wave > kSplitRows) return hipErrorInvalidValue;                 // host bug
+            const bool emit = g.planes_out != nullptr;
+            if (g.geo.sh == 2) {
+                if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 2, true>), grid, dim3(256), 0, s, g);
+                else hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 2, true>), grid, dim3(256), 0, s, g);
+            } else {
+                if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 1, true>), grid, dim3(256), 0, s, g);
+                else hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 1, true>), grid, dim3(256), 0, s, g);
+            }
+            return hipGetLastError();
+        }
+    }
+    if (g.split_k) return hipErrorInvalidValue;                                            // host bug
     if (g.geo.sh == 2) {           // stride 2: pixel groups of two only where five input pixels fit a stage
         constexpr int P2 = conv_group_strided(AB, WB, CWS);
         if (g.planes_out != nullptr)
@@ -964,6 +1026,7 @@ hipError_t QNN_CAT(launch_gemm_ab, QNN_AB)(const BranchArgs &g, int wb, hipStrea
 
 hipError_t QNN_CAT(launch_conv_ab, QNN_AB)(const BranchArgs &g, int wb, hipStream_t s) {
     if (g.xcd_ranges && g.grid_blocks != grid_for(g).x) return hipErrorInvalidValue;   // host bug
+    if (g.split_k && g.xcd_ranges) return hipErrorInvalidValue;
     if (g.geo.sh != g.geo.sw || (g.geo.sh != 1 && g.geo.sh != 2)) return hipErrorInvalidValue;
     switch (wb) {
         case 1: return launch_conv_t<QNN_AB, 1>(g, s);

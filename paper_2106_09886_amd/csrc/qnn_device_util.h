@@ -116,6 +116,27 @@ struct OutViewEmit : OutView {
                                  // half h of plane out_bits-1-k), or -1 if the lane stores nothing
 };
 
+// Partial sums of one wavefront kept in LDS (rows x 64 lanes of int32, the lane's own column):
+// used where the four wavefronts of a block each form a part of the same outputs and one pass
+// over LDS combines them.  `slab` already points at the lane's slot of row 0.
+struct OutViewSlab {
+    int *slab;
+    bool with_const;             // this wavefront's first part carries the product's constant term
+};
+template <class OV> struct is_slab { static constexpr bool value = false; };
+template <> struct is_slab<OutViewSlab> { static constexpr bool value = true; };
+template <class OV>
+__device__ __forceinline__ bool adds_const(const OV &v) {
+    if constexpr (is_slab<OV>::value) return v.with_const;
+    else return true;
+}
+// what earlier chunk passes of this wavefront left for a row (multi-pass products)
+template <class OV>
+__device__ __forceinline__ int partial_load(const OV &v, int rel_row) {
+    if constexpr (is_slab<OV>::value) return v.slab[rel_row * 64];
+    else return __builtin_amdgcn_raw_buffer_load_b32(v.d0, v.col_bytes, (int)((uint32_t)rel_row * v.row_bytes), 0);
+}
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *p, uint32_t bytes) {
     // raw dword buffer: stride 0, num_records in bytes, 32-bit data format word for gfx9
     return __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, 0x00020000);
@@ -247,6 +268,12 @@ __device__ __forceinline__ OV make_out_view(const BranchArgs &g, int r0, int r1,
 
 // Finish one row of one chunk pass for this lane's column.  rel_row = row - r0.  SINGLE: the
 // product has a single chunk pass (first and last are both true at compile time).
+template <bool SINGLE>
+__device__ __forceinline__ void finish_row(const OutViewSlab &v, int rel_row, int val, bool first, bool) {
+    if (!first) val += v.slab[rel_row * 64];
+    v.slab[rel_row * 64] = val;
+}
+
 template <bool SINGLE, class OV>
 __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bool first, bool last) {
     const int soff = (int)((uint32_t)rel_row * v.row_bytes);

@@ -58,8 +58,8 @@ struct BranchArgs {
     int kconst;           // (true K of one tap) * (2^AB - 1) * (2^WB - 1)
     int rows_per_wave;    // contiguous rows handled by one wavefront
     int col_tiles;        // ceil(N / 64)
-    int split_k;          // GEMM only: K chunks split over the wavefronts of a block; then
-                          // rows_per_wave is the number of rows per BLOCK
+    int split_k;          // K (GEMM) or channel (3x3 convolution) chunks split over the four wavefronts of a
+                          // block; then rows_per_wave is the number of rows per BLOCK
     int gather_rows;      // GEMM only: row r is output pixel r of a single-tap strided convolution (geo, H, W);
                           // bit widths up to 4, not with split_k
     int lds_partials;     // GEMM only: partial sums between chunk passes stay in LDS (rows_per_wave <=
@@ -98,6 +98,7 @@ struct Tuning {
     int general_only;     // qnn_conv2d_general hands no 3x3 stride-1 pad-1 window to the 3x3 kernel
     int block_order;      // 0: automatic, 1: plain block numbers, 2: a contiguous range per XCD
     int lds_partials;     // 0: automatic, 1: GEMM partial sums through the output buffer, 2: in LDS where possible
+    int split_channels;   // 3x3 convolution: 0 automatic, 1 never split the channel chunks over a block, 2 wherever possible
 };
 Tuning &tuning();
 
@@ -168,6 +169,14 @@ constexpr int conv_passes(int ab, int wb, int cw) {
 constexpr int conv_group(int ab, int wb, int cw) {
     return conv_has_fixed_shape(ab, wb, cw) ? conv_shape(ab, wb, cw).p : 1;
 }
+
+// Shapes for which the 3x3 kernel also exists in the variant whose four wavefronts per block split
+// the channel chunks (all nine taps per chunk, at least two channel chunks); most rows per block.
+constexpr bool conv_can_split(int ab, int wb, int cw) {
+    return conv_has_fixed_shape(ab, wb, cw) && cw >= 4 && conv_shape(ab, wb, cw).tpc == 9 &&
+           cw / conv_shape(ab, wb, cw).cwt >= 2;
+}
+constexpr int kConvSplitRows = 16;
 
 // the same for the stride-2 variant of the 3x3 kernel: two output pixels share a stage of five input
 // pixels where those fit the scalar registers of a stage, else one pixel per iteration

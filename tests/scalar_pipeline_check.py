@@ -6,7 +6,8 @@ are in flight in between.  This module takes their assembly for every activation
 the files the library build keeps beside its objects (the very code that was linked), or a
 compilation of its own where those are missing or older than the sources -- and verifies,
 kernel by kernel, that
-  * no scratch memory is used, and
+  * no instruction addresses scratch memory (a kernel may reserve a few bytes that the register
+    allocator set aside and never used; that is reported by size only if something accesses it), and
   * on no path of the control-flow graph does an instruction outside an asm block (a spill
     to a VGPR lane included) name a requested SGPR between its s_load and the next
     `s_waitcnt lgkmcnt(0)`.
@@ -159,10 +160,23 @@ def check_kernel(name, lines):
     return problems, spills
 
 
+def uses_scratch(lines):
+    """Does any instruction of the kernel address scratch memory?"""
+    for _, raw in lines:
+        l = raw.strip()
+        if l.startswith("scratch_") or (l.startswith("buffer_") and "s[0:3]" in l and "offen" not in l.split(";")[0] and " off" in l):
+            return True
+        if l.startswith("buffer_") and re.search(r"s\[0:3\],\s*0(\s|$)", l.split(";")[0]):      # stack accesses: soffset 0 on the scratch descriptor
+            return True
+    return False
+
+
 def check_file(path):
     text = open(path).read().split("\n")
     problems, nk, nspill = [], 0, 0
     cur, name = None, None
+    touches_scratch = {}
+    last_kernel = None
     for i, l in enumerate(text, 1):
         m = re.match(r"^(_ZN3qnn\S*_kernel\S*):", l)
         if m:
@@ -175,10 +189,17 @@ def check_file(path):
                 problems += p
                 nspill += sp
                 nk += 1
+                touches_scratch[name] = uses_scratch(cur)
                 cur = None
+        m = re.match(r"^\s*\.amdhsa_kernel\s+(\S+)", l)
+        if m:
+            last_kernel = m.group(1)
         m = re.match(r"^\s*\.amdhsa_private_segment_fixed_size\s+(\d+)", l)
         if m and int(m.group(1)) != 0:
-            problems.append("%s: kernel uses %s bytes of scratch" % (path, m.group(1)))
+            # the descriptor may come before the function's end label: then `cur` is the kernel's text so far
+            touched = uses_scratch(cur) if (cur is not None and name == last_kernel) else touches_scratch.get(last_kernel, True)
+            if touched:
+                problems.append("%s: kernel %s uses %s bytes of scratch" % (path, last_kernel, m.group(1)))
     return nk, problems, nspill
 
 

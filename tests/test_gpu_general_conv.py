@@ -164,6 +164,17 @@ def test_conv3x3_stride2_any_rows_per_wave(q, oracle, rpw):
         q.tune(rows_per_wave=0)
 
 
+def test_conv3x3_stride2_split_channels(q, oracle):
+    """Stride 2 together with the channel-splitting variant, forced on (and an emitted result)."""
+    q.tune(split_channels=2)
+    try:
+        run_case(q, oracle, Nb=2, H=14, W=14, C=256, Cout=70, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1)
+        run_case(q, oracle, Nb=1, H=9, W=11, C=512, Cout=64, ab=4, wb=2, KH=3, KW=3, stride=2, pad=1, out_bits=4, seed=2)
+        run_case(q, oracle, Nb=2, H=7, W=7, C=512, Cout=128, ab=4, wb=2, KH=3, KW=3, stride=1, pad=1, out_bits=4, seed=4)
+    finally:
+        q.tune(split_channels=0)
+
+
 # the layers bench.py times (`--workload conv_geometries`), at their full sizes and in the launch
 # configuration the library picks for them; the oracle computes the whole layer
 FULL_SIZE_CASES = [

@@ -296,6 +296,24 @@ def test_conv_any_rows_per_wave(q, oracle, rpw):
         q.tune(rows_per_wave=0)
 
 
+@pytest.mark.parametrize("case", [(2, 7, 7, 512, 64, 4, 2), (1, 14, 14, 512, 130, 4, 2), (3, 5, 6, 256, 64, 4, 2),
+                                  (2, 9, 4, 128, 70, 2, 2), (1, 3, 20, 512, 64, 2, 1), (2, 6, 6, 256, 64, 3, 3),
+                                  (1, 1, 1, 512, 64, 4, 2), (2, 17, 3, 128, 64, 1, 1)])
+def test_conv_split_channels(q, oracle, case):
+    """The 3x3 kernel whose four wavefronts per block split the channel chunks (layers with few pixels
+    and many channels), forced on; also rows that are not a multiple of four, one-pixel images and
+    chunk counts of 2, 4 and 8."""
+    Nb, H, W, C, Cout, ab, wb = case
+    say("conv split channels", case)
+    rng = np.random.default_rng(sum(case))
+    q.tune(split_channels=2)
+    try:
+        run_conv(q, oracle, rand_codes(rng, (Nb, H, W, C), ab), rand_codes(rng, (Cout, 3, 3, C), wb), ab, wb,
+                 rng.uniform(0.01, 0.1, Cout).astype(np.float32))
+    finally:
+        q.tune(split_channels=0)
+
+
 @pytest.mark.parametrize("order", [1, 2])
 def test_conv_any_block_order(q, oracle, order):
     """The numbering of the blocks (plain, or one contiguous range per XCD) is a performance knob

@@ -53,6 +53,20 @@ def test_checker_ignores_compiler_issued_loads():
     assert kernel(["\ts_load_dwordx2 s[8:9], s[0:1], 0x0", "\ts_waitcnt lgkmcnt(0)", "\tv_mov_b32_e32 v0, s8"]) == []
 
 
+def test_checker_tells_reserved_from_used_scratch(tmp_path):
+    """A kernel that only reserves scratch (the allocator's emergency slot) passes; one whose code
+    addresses it does not."""
+    def asm_file(body):
+        text = ["_ZN3qnn6a_kernelEv:"] + body + ["\ts_endpgm", ".Lfunc_end0:", "\t.amdhsa_kernel _ZN3qnn6a_kernelEv",
+                                                  "\t\t.amdhsa_private_segment_fixed_size 20", "\t.end_amdhsa_kernel"]
+        f = tmp_path / "k.s"
+        f.write_text("\n".join(text))
+        return str(f)
+    assert chk.check_file(asm_file(["\tv_mov_b32_e32 v0, 0"]))[1] == []
+    assert len(chk.check_file(asm_file(["\tscratch_store_dword off, v0, off offset:4"]))[1]) == 1
+    assert len(chk.check_file(asm_file(["\tbuffer_store_dword v0, off, s[0:3], 0 offset:4"]))[1]) == 1
+
+
 @pytest.fixture(scope="module")
 def asm():
     tmp = tempfile.mkdtemp(prefix="qnn_asm_test_")
