@@ -60,7 +60,13 @@ qnn_status qnn_device_info(int *h_compute_units, int *h_clock_khz);
 
 /*
  * Performance knobs (process-wide; results never depend on them).  value 0 restores the
- * automatic choice.  Returns QNN_OK or QNN_EINVAL.  Not thread-safe against running calls.
+ * automatic choice.  Returns QNN_OK or QNN_EINVAL.
+ * Who reads them: qnn_gemm_packed, qnn_conv2d_packed, qnn_conv2d_general, qnn_conv2d_im2col and
+ * qnn_conv2d_im2col_static, on the host while they size their launch; no kernel and no other
+ * entry point does.  Each knob is an atomic word read once per call, so qnn_tune may be called
+ * from any thread at any time: a call that is already sizing its launch may use the old or the
+ * new value of a knob (and the old value of one with the new value of another), a call that
+ * starts after qnn_tune returns uses the new one.
  */
 #define QNN_TUNE_WAVES_PER_SIMD 1 /* resident wavefronts per SIMD the launch sizing aims for */
 #define QNN_TUNE_ROWS_PER_WAVE 2  /* rows (GEMM rows / output pixels) per wavefront        */
@@ -82,7 +88,8 @@ int qnn_tune(int key, int value);
  * {start clock, end clock, HW_ID | XCC_ID << 32, start real-time clock}: the first two are the
  * shader clock of s_memtime (local to a compute unit), the last the chip-wide 100 MHz clock.
  * NULL switches tracing off.  The buffer must be 8-byte aligned and stay valid while traced
- * kernels run; results of the kernels do not change.
+ * kernels run; results of the kernels do not change.  The address and the size are two words:
+ * do not call this while another thread is inside one of the entry points that qnn_tune lists.
  */
 int qnn_set_wave_trace(void *buffer, size_t bytes);
 

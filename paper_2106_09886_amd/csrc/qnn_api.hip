@@ -11,7 +11,7 @@ static __device__ __align__(256) unsigned char scratch[QNN_STATIC_SCRATCH_BYTES]
 namespace qnn {
 
 Tuning &tuning() {
-    static Tuning t = {0, 0, nullptr, 0, 0, 0, 0, 0};
+    static Tuning t;
     return t;
 }
 
@@ -71,10 +71,9 @@ const int64_t kInt31 = ((int64_t)1 << 31) - 1;
 // `waves_per_simd` of them, but never fewer than `min_rows` rows each (the weight chunk a
 // wavefront loads is reused for all of its rows).
 int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows, int default_waves_per_simd = 4) {
-    const Tuning &t = tuning();
-    if (t.rows_per_wave > 0) return t.rows_per_wave;
-    const int64_t target_waves =
-        (int64_t)device_simd_count() * (t.waves_per_simd > 0 ? t.waves_per_simd : default_waves_per_simd);
+    const int knob_rows = tuning().rows_per_wave, knob_waves = tuning().waves_per_simd;
+    if (knob_rows > 0) return knob_rows;
+    const int64_t target_waves = (int64_t)device_simd_count() * (knob_waves > 0 ? knob_waves : default_waves_per_simd);
     int64_t row_blocks = target_waves / col_tiles;
     if (row_blocks < 1) row_blocks = 1;
     int64_t rpw = (rows + row_blocks - 1) / row_blocks;
@@ -97,10 +96,10 @@ int pick_rows_per_wave(int64_t rows, int col_tiles, int min_rows, int default_wa
 //   fewer than four wavefronts per SIMD hide latencies badly.
 // The constants were fitted to measured times of the VGG- and ResNet-shaped layers.
 int pick_conv_rows_per_wave(int64_t rows, int64_t W, int col_tiles, int passes, int group) {
-    const Tuning &t = tuning();
-    if (t.rows_per_wave > 0) return t.rows_per_wave;
+    const int knob_rows = tuning().rows_per_wave, knob_waves = tuning().waves_per_simd;
+    if (knob_rows > 0) return knob_rows;
     const double simds = (double)device_simd_count();
-    const int resident = t.waves_per_simd > 0 ? t.waves_per_simd : 8;   // wavefronts a SIMD holds at once
+    const int resident = knob_waves > 0 ? knob_waves : 8;   // wavefronts a SIMD holds at once
     int64_t best = 0;
     double best_cost = 0.0;
     auto consider = [&](int64_t rpw) {
@@ -265,9 +264,9 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     // wavefront, and their round trip is small against the products of a chunk), hence the limit
     // of 256 vector instructions per row and chunk for the automatic choice.
     const bool lds_auto = 2 * ab * wb * gemm_chunk_words(wb) <= 256;
+    const int knob_lds = tuning().lds_partials, knob_rows = tuning().rows_per_wave;
     if (!g.split_k && !g.gather_rows && chunks >= 2 && ab <= 4 && wb <= 4 &&
-        (tuning().lds_partials == 2 || (tuning().lds_partials == 0 && lds_auto)) &&
-        (tuning().rows_per_wave == 0 || tuning().rows_per_wave <= kLdsPartialRows)) {
+        (knob_lds == 2 || (knob_lds == 0 && lds_auto)) && (knob_rows == 0 || knob_rows <= kLdsPartialRows)) {
         g.lds_partials = 1;
         if (g.rows_per_wave > kLdsPartialRows) g.rows_per_wave = kLdsPartialRows;
     }
@@ -317,8 +316,9 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     // chunk passes.  The variant whose four wavefronts per block split the channel chunks gives four
     // times the wavefronts (measured on 32 x 7 x 7 x 512 -> 512, W2A4: see the design notes).
     const int64_t plain_waves = ((rows + g.rows_per_wave - 1) / g.rows_per_wave) * g.col_tiles;
-    if (conv_can_split(ab, wb, g.Cw) && tuning().rows_per_wave == 0 && tuning().split_channels != 1 &&
-        (plain_waves < 4 * (int64_t)device_simd_count() || tuning().split_channels == 2)) {
+    const int knob_split = tuning().split_channels;
+    if (conv_can_split(ab, wb, g.Cw) && tuning().rows_per_wave == 0 && knob_split != 1 &&
+        (plain_waves < 4 * (int64_t)device_simd_count() || knob_split == 2)) {
         const int chunks = g.Cw / conv_shape(ab, wb, g.Cw).cwt;
         int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, (chunks + 3) / 4, 1);
         if (rpb > kConvSplitRows) rpb = kConvSplitRows;
@@ -380,7 +380,8 @@ qnn_status run_conv_im2col(const void *x_codes, int code_bytes, int ab, const ui
             // Short wavefronts that stream through the SIMDs: measured on the 16 x 224 x 224 x 3 -> 64
             // layer, 16 pixels each are best with int32 + fp32 outputs (95 us; 123 us at 196 pixels, where
             // four wavefronts per SIMD are all there is) and 28 with emitted planes only (99.5 us).
-            const int small_rpw = tuning().rows_per_wave > 0 ? tuning().rows_per_wave : (e.bits != 0 ? 28 : 16);
+            const int knob_rows = tuning().rows_per_wave;
+            const int small_rpw = knob_rows > 0 ? knob_rows : (e.bits != 0 ? 28 : 16);
             g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(small_rpw, Cout), Cout, e);
             g.grid_blocks = wave_grid_blocks(g);
             set_divisors(g);

@@ -877,20 +877,20 @@ template <int AB, int WB, int SEGS, int CWT>
 void launch_gemm_plain(const BranchArgs &g, bool emit, hipStream_t s) {
     if constexpr (AB <= 4 && WB <= 4) {       // strided rows: bit widths up to 4 only, to bound build time
         if (g.gather_rows) {
-            if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true, true>), grid_for(g), dim3(256), 0, s, g);
-            else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false, true>), grid_for(g), dim3(256), 0, s, g);
+            if (emit) launch_kernel((gemm_kernel<AB, WB, SEGS, CWT, true, true>), grid_for(g), dim3(256), 0, s, g);
+            else launch_kernel((gemm_kernel<AB, WB, SEGS, CWT, false, true>), grid_for(g), dim3(256), 0, s, g);
             return;
         }
     }
     if constexpr (AB <= 4 && WB <= 4) {
         if (g.lds_partials) {
-            if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true, false, true>), grid_for(g), dim3(256), 0, s, g);
-            else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false, false, true>), grid_for(g), dim3(256), 0, s, g);
+            if (emit) launch_kernel((gemm_kernel<AB, WB, SEGS, CWT, true, false, true>), grid_for(g), dim3(256), 0, s, g);
+            else launch_kernel((gemm_kernel<AB, WB, SEGS, CWT, false, false, true>), grid_for(g), dim3(256), 0, s, g);
             return;
         }
     }
-    if (emit) hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, true>), grid_for(g), dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((gemm_kernel<AB, WB, SEGS, CWT, false>), grid_for(g), dim3(256), 0, s, g);
+    if (emit) launch_kernel((gemm_kernel<AB, WB, SEGS, CWT, true>), grid_for(g), dim3(256), 0, s, g);
+    else launch_kernel((gemm_kernel<AB, WB, SEGS, CWT, false>), grid_for(g), dim3(256), 0, s, g);
 }
 
 template <int AB, int WB, int KC>
@@ -912,8 +912,8 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
     if (g.split_k) {
         const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
         const dim3 grid((unsigned)(row_blocks * g.col_tiles));
-        if (emit) hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, true>), grid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, false>), grid, dim3(256), 0, s, g);
+        if (emit) launch_kernel((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, true>), grid, dim3(256), 0, s, g);
+        else launch_kernel((gemm_splitk_kernel<AB, WB, S::SEGS, S::CWT, false>), grid, dim3(256), 0, s, g);
     } else {
         // A product shorter than the regular chunk (1x1 convolutions, narrow layers) would run
         // entirely through the guarded tail path: take the largest shorter chunk that fits instead
@@ -924,12 +924,12 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
                 else if (S::KC > 8 && g.Cw >= 8) launch_gemm_short<AB, WB, 8>(g, emit, s);
                 else if (g.Cw >= 4) launch_gemm_short<AB, WB, 4>(g, emit, s);
                 else launch_gemm_short<AB, WB, 2>(g, emit, s);
-                return hipGetLastError();
+                return launch_status();
             }
         }
         launch_gemm_plain<AB, WB, S::SEGS, S::CWT>(g, emit, s);
     }
-    return hipGetLastError();
+    return launch_status();
 }
 
 
@@ -944,38 +944,38 @@ hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
             if (g.rows_per_wave > kSplitRows) return hipErrorInvalidValue;                 // host bug
             const bool emit = g.planes_out != nullptr;
             if (g.geo.sh == 2) {
-                if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 2, true>), grid, dim3(256), 0, s, g);
-                else hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 2, true>), grid, dim3(256), 0, s, g);
+                if (emit) launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 2, true>), grid, dim3(256), 0, s, g);
+                else launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 2, true>), grid, dim3(256), 0, s, g);
             } else {
-                if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 1, true>), grid, dim3(256), 0, s, g);
-                else hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 1, true>), grid, dim3(256), 0, s, g);
+                if (emit) launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 1, true>), grid, dim3(256), 0, s, g);
+                else launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 1, true>), grid, dim3(256), 0, s, g);
             }
-            return hipGetLastError();
+            return launch_status();
         }
     }
     if (g.split_k) return hipErrorInvalidValue;                                            // host bug
     if (g.geo.sh == 2) {           // stride 2: pixel groups of two only where five input pixels fit a stage
         constexpr int P2 = conv_group_strided(AB, WB, CWS);
         if (g.planes_out != nullptr)
-            hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, P2, true, false, 2>), grid_for(g), dim3(256), 0, s, g);
+            launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, P2, true, false, 2>), grid_for(g), dim3(256), 0, s, g);
         else
-            hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, P2, false, false, 2>), grid_for(g), dim3(256), 0, s, g);
-        return hipGetLastError();
+            launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, P2, false, false, 2>), grid_for(g), dim3(256), 0, s, g);
+        return launch_status();
     }
     if constexpr (CWS >= 2) {      // 64 channels and more: the automatic choice asks for it from 256 filters on
         if (g.xcd_ranges) {
             if (g.planes_out != nullptr)
-                hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true, true>), grid_for(g), dim3(256), 0, s, g);
+                launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true, true>), grid_for(g), dim3(256), 0, s, g);
             else
-                hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, false, true>), grid_for(g), dim3(256), 0, s, g);
-            return hipGetLastError();
+                launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, false, true>), grid_for(g), dim3(256), 0, s, g);
+            return launch_status();
         }
     }
     if (g.planes_out != nullptr)
-        hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true>), grid_for(g), dim3(256), 0, s, g);
+        launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, true>), grid_for(g), dim3(256), 0, s, g);
     else
-        hipLaunchKernelGGL((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, false>), grid_for(g), dim3(256), 0, s, g);
-    return hipGetLastError();
+        launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, S::P, false>), grid_for(g), dim3(256), 0, s, g);
+    return launch_status();
 }
 
 template <int AB, int WB>
@@ -996,13 +996,13 @@ hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
     // buffers (2 * AB * CWT SGPRs) leave the allocator room, else one word
     const bool emit = g.planes_out != nullptr;
     if (g.Cw == 1 || AB > 4) {
-        if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 1, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+        if (emit) launch_kernel((conv_kernel<AB, WB, 0, 1, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+        else launch_kernel((conv_kernel<AB, WB, 0, 1, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
     } else if constexpr (AB <= 4) {
-        if (emit) hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_kernel<AB, WB, 0, 2, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+        if (emit) launch_kernel((conv_kernel<AB, WB, 0, 2, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+        else launch_kernel((conv_kernel<AB, WB, 0, 2, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
     }
-    return hipGetLastError();
+    return launch_status();
 }
 
 }  // namespace

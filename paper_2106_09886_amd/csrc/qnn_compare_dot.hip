@@ -78,10 +78,10 @@ hipError_t launch_dot4_gemm(const int8_t *A, const int8_t *Wt, int64_t M, int64_
     if (rpw > M) rpw = M;
     const int64_t row_blocks = (M + rpw - 1) / rpw;
     const int64_t waves = row_blocks * col_tiles;
-    hipLaunchKernelGGL(dot4_gemm_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s,
+    launch_kernel(dot4_gemm_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s,
                        reinterpret_cast<const uint32_t *>(A), reinterpret_cast<const uint32_t *>(Wt), (int)M, (int)N,
                        (int)(K / 4), (int)rpw, col_tiles, C);
-    return hipGetLastError();
+    return launch_status();
 }
 
 }  // namespace qnn

@@ -101,8 +101,8 @@ hipError_t launch_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, voi
     if (total == 0) return hipSuccess;
     const int64_t want = (total + 255) / 256;
     const unsigned blocks = (unsigned)(want < (int64_t)1 << 20 ? want : (int64_t)1 << 20);
-    hipLaunchKernelGGL(mfma_arrange_kernel, dim3(blocks), dim3(256), 0, s, codes, rows, K, rb, kb, (v4i *)out);
-    return hipGetLastError();
+    launch_kernel(mfma_arrange_kernel, dim3(blocks), dim3(256), 0, s, codes, rows, K, rb, kb, (v4i *)out);
+    return launch_status();
 }
 
 hipError_t launch_mfma_gemm(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int32_t *C,
@@ -112,9 +112,9 @@ hipError_t launch_mfma_gemm(const void *A, const void *B, int64_t M, int64_t N, 
     const int64_t blocks_m = (tiles_m + 1) / 2, blocks_n = (tiles_n + 1) / 2;
     const int64_t blocks = blocks_m * blocks_n;
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(mfma_gemm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const v4i *)A, (const v4i *)B, (int)M,
+    launch_kernel(mfma_gemm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const v4i *)A, (const v4i *)B, (int)M,
                        (int)N, kb, tiles_n, blocks * 4, C);
-    return hipGetLastError();
+    return launch_status();
 }
 
 }  // namespace qnn

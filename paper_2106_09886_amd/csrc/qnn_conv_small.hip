@@ -289,9 +289,9 @@ hipError_t launch_small_t(const BranchArgs &g, hipStream_t s) {
     const int64_t waves = row_blocks * g.col_tiles;
     const dim3 grid((unsigned)((waves + 3) / 4));
     if (g.xcd_ranges && g.grid_blocks != grid.x) return hipErrorInvalidValue;             // host bug
-    if (g.planes_out != nullptr) hipLaunchKernelGGL((conv_small_kernel<AB, WB, true>), grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((conv_small_kernel<AB, WB, false>), grid, dim3(256), 0, s, g);
-    return hipGetLastError();
+    if (g.planes_out != nullptr) launch_kernel((conv_small_kernel<AB, WB, true>), grid, dim3(256), 0, s, g);
+    else launch_kernel((conv_small_kernel<AB, WB, false>), grid, dim3(256), 0, s, g);
+    return launch_status();
 }
 
 }  // namespace
@@ -321,22 +321,22 @@ hipError_t QNN_CAT(launch_im2col_pack_ab, QNN_AB)(const void *codes, int code_by
         const size_t lds = (size_t)(256 + kIm2colBlock + 2 * W + 2) * 4u;
         const FastDiv dw = fast_div_for(W), dh = fast_div_for(H);
         if (code_bytes == 1)
-            hipLaunchKernelGGL((im2col_pack_kernel<int8_t, QNN_AB>), dim3(blocks), dim3(kIm2colBlock), lds, s,
+            launch_kernel((im2col_pack_kernel<int8_t, QNN_AB>), dim3(blocks), dim3(kIm2colBlock), lds, s,
                                (const int8_t *)codes, pixels, H, W, C, dw, dh, words);
         else
-            hipLaunchKernelGGL((im2col_pack_kernel<int16_t, QNN_AB>), dim3(blocks), dim3(kIm2colBlock), lds, s,
+            launch_kernel((im2col_pack_kernel<int16_t, QNN_AB>), dim3(blocks), dim3(kIm2colBlock), lds, s,
                                (const int16_t *)codes, pixels, H, W, C, dw, dh, words);
-        return hipGetLastError();
+        return launch_status();
     }
     const int64_t want = (pixels + 255) / 256;
     const unsigned blocks = (unsigned)(want < (int64_t)1 << 20 ? want : (int64_t)1 << 20);
     if (code_bytes == 1)
-        hipLaunchKernelGGL((im2col_pack_simple_kernel<int8_t, QNN_AB>), dim3(blocks), dim3(256), 0, s,
+        launch_kernel((im2col_pack_simple_kernel<int8_t, QNN_AB>), dim3(blocks), dim3(256), 0, s,
                            (const int8_t *)codes, pixels, H, W, C, words);
     else
-        hipLaunchKernelGGL((im2col_pack_simple_kernel<int16_t, QNN_AB>), dim3(blocks), dim3(256), 0, s,
+        launch_kernel((im2col_pack_simple_kernel<int16_t, QNN_AB>), dim3(blocks), dim3(256), 0, s,
                            (const int16_t *)codes, pixels, H, W, C, words);
-    return hipGetLastError();
+    return launch_status();
 }
 
 }  // namespace qnn

@@ -97,37 +97,37 @@ __global__ __launch_bounds__(kBlock) void quantize_k_backward_kernel(const float
 
 hipError_t launch_encoder_backward(const float *x, const float *g, int64_t n, int bits, float *gx, hipStream_t s) {
     const unsigned blocks = blocks_for(n);
-#define QNN_EB(M) case M: hipLaunchKernelGGL((encoder_backward_kernel<M>), dim3(blocks), dim3(kBlock), 0, s, x, g, n, gx); break
+#define QNN_EB(M) case M: launch_kernel((encoder_backward_kernel<M>), dim3(blocks), dim3(kBlock), 0, s, x, g, n, gx); break
     switch (bits) {
         QNN_EB(1); QNN_EB(2); QNN_EB(3); QNN_EB(4); QNN_EB(5); QNN_EB(6); QNN_EB(7); QNN_EB(8);
         default: return hipErrorInvalidValue;
     }
 #undef QNN_EB
-    return hipGetLastError();
+    return launch_status();
 }
 
 hipError_t launch_binarize(const float *w, int64_t rows, int64_t K, int8_t *codes, uint32_t *planes, hipStream_t s) {
     const int groups = (int)((K + 63) / 64);
-    hipLaunchKernelGGL(binarize_kernel, dim3(blocks_for(rows * groups * 64)), dim3(kBlock), 0, s, w, rows, (int)K, groups, codes,
+    launch_kernel(binarize_kernel, dim3(blocks_for(rows * groups * 64)), dim3(kBlock), 0, s, w, rows, (int)K, groups, codes,
                        planes);
-    return hipGetLastError();
+    return launch_status();
 }
 
 hipError_t launch_binarize_backward(const float *w, const float *g_wb, int64_t n, float *g_w, hipStream_t s) {
-    hipLaunchKernelGGL(binarize_backward_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, w, g_wb, n, g_w);
-    return hipGetLastError();
+    launch_kernel(binarize_backward_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, w, g_wb, n, g_w);
+    return launch_status();
 }
 
 hipError_t launch_quantize_k(const float *x, int64_t n, int bits, float t, float *q, int32_t *levels, hipStream_t s) {
     const float nlev = (float)((1 << (bits - 1)) - 1);
     const float d = t / nlev;                        // one binary32 division on the host, as in the definition
-    hipLaunchKernelGGL(quantize_k_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, x, n, t, nlev, d, q, levels);
-    return hipGetLastError();
+    launch_kernel(quantize_k_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, x, n, t, nlev, d, q, levels);
+    return launch_status();
 }
 
 hipError_t launch_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x, hipStream_t s) {
-    hipLaunchKernelGGL(quantize_k_backward_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, x, g_q, n, t, g_x);
-    return hipGetLastError();
+    launch_kernel(quantize_k_backward_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s, x, g_q, n, t, g_x);
+    return launch_status();
 }
 
 }  // namespace qnn

@@ -39,11 +39,11 @@ hipError_t launch_scale(const int32_t *acc, int64_t total, int64_t N, const floa
     const int64_t want = (work + 255) / 256;
     const unsigned blocks = (unsigned)(want < 65536 ? want : 65536);
     if (v4)
-        hipLaunchKernelGGL(scale_kernel_v4, dim3(blocks), dim3(256), 0, s, (const int4 *)acc, work,
+        launch_kernel(scale_kernel_v4, dim3(blocks), dim3(256), 0, s, (const int4 *)acc, work,
                            (int)(N / 4), (const float4 *)scale, (float4 *)out);
     else
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks), dim3(256), 0, s, acc, total, N, scale, out);
-    return hipGetLastError();
+        launch_kernel(scale_kernel, dim3(blocks), dim3(256), 0, s, acc, total, N, scale, out);
+    return launch_status();
 }
 
 }  // namespace qnn

@@ -1,10 +1,43 @@
 // Internal declarations shared by the translation units of libqnn (not installed).
 #pragma once
+#include <atomic>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <tuple>
+#include <type_traits>
+#include <utility>
 #include "qnn.h"
 
 namespace qnn {
+
+// Kernel launches.  launch_kernel starts `kernel` on `stream` and keeps the status that the launch
+// call itself returned (the first failure since the last launch_status()); launch_status() hands
+// it out and clears it.  The runtime's per-thread "last error" is not consulted: an error left
+// there by an unrelated call of the host program would otherwise be reported as this library's.
+inline thread_local hipError_t t_launch_error = hipSuccess;
+
+template <typename... KArgs, size_t... I>
+inline hipError_t launch_held(const void *kernel, dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t stream,
+                              std::tuple<KArgs...> &held, std::index_sequence<I...>) {
+    void *ptrs[sizeof...(KArgs) + 1] = {static_cast<void *>(&std::get<I>(held))..., nullptr};
+    return hipLaunchKernel(kernel, grid, block, ptrs, lds_bytes, stream);
+}
+
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t stream,
+                          const Args &...args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one value per kernel parameter");
+    std::tuple<std::remove_cv_t<KArgs>...> held(args...);   // values of exactly the parameters' types
+    const hipError_t e = launch_held(reinterpret_cast<const void *>(kernel), grid, block, lds_bytes, stream, held,
+                                     std::index_sequence_for<KArgs...>{});
+    if (e != hipSuccess && t_launch_error == hipSuccess) t_launch_error = e;
+}
+
+inline hipError_t launch_status() {
+    const hipError_t e = t_launch_error;
+    t_launch_error = hipSuccess;
+    return e;
+}
 
 // Window geometry of the general convolution kernel (all run-time values).
 struct ConvGeom {
@@ -90,15 +123,18 @@ inline unsigned wave_grid_blocks(const BranchArgs &g) {
     return (unsigned)((row_blocks * g.col_tiles + 3) / 4);
 }
 
+// Process-wide knobs behind qnn_tune and qnn_set_trace.  Each is an atomic of its own: a launch reads
+// every knob it uses once, while it sizes its grid, so a change made from another thread takes
+// effect at a call boundary of the calls that start later and never tears a value.
 struct Tuning {
-    int waves_per_simd;   // target resident wavefronts per SIMD when sizing rows_per_wave
-    int rows_per_wave;    // > 0 overrides the automatic choice
-    uint64_t *trace;      // device buffer for per-wavefront trace records, or nullptr
-    uint32_t trace_waves;
-    int general_only;     // qnn_conv2d_general hands no 3x3 stride-1 pad-1 window to the 3x3 kernel
-    int block_order;      // 0: automatic, 1: plain block numbers, 2: a contiguous range per XCD
-    int lds_partials;     // 0: automatic, 1: GEMM partial sums through the output buffer, 2: in LDS where possible
-    int split_channels;   // 3x3 convolution: 0 automatic, 1 never split the channel chunks over a block, 2 wherever possible
+    std::atomic<int> waves_per_simd{0};   // target resident wavefronts per SIMD when sizing rows_per_wave
+    std::atomic<int> rows_per_wave{0};    // > 0 overrides the automatic choice
+    std::atomic<uint64_t *> trace{nullptr};  // device buffer for per-wavefront trace records, or nullptr
+    std::atomic<uint32_t> trace_waves{0};
+    std::atomic<int> general_only{0};     // qnn_conv2d_general hands no 3x3 pad-1 window to the 3x3 kernel
+    std::atomic<int> block_order{0};      // 0: automatic, 1: plain block numbers, 2: a contiguous range per XCD
+    std::atomic<int> lds_partials{0};     // 0: automatic, 1: GEMM partial sums through the output buffer, 2: in LDS where possible
+    std::atomic<int> split_channels{0};   // 3x3 convolution: 0 automatic, 1 never split the channel chunks over a block, 2 wherever possible
 };
 Tuning &tuning();
 

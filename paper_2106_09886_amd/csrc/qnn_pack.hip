@@ -57,6 +57,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const CodeT *__restrict__ cod
         for (int p = 0; p < BITS; ++p) word[p] = 0u;
         const bool fast = (cnt == 32) && ((((uintptr_t)src) & 15u) == 0);
         if (fast) {
+            int bad_here = 0;                                          // of this group of 32 alone
             constexpr int NLD = (int)sizeof(CodeT) * 2;                // 16-byte loads per 32 codes
             const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
 #pragma unroll
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const CodeT *__restrict__ cod
                     if (sizeof(CodeT) == 1) {
                         if (VALIDATE) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) bad += count_bad((int)(int8_t)(x >> (8 * e)), VMAX);
+                            for (int e = 0; e < 4; ++e) bad_here += count_bad((int)(int8_t)(x >> (8 * e)), VMAX);
                         }
                         const uint32_t t = add_bytes(x, 0x01010101u * (uint32_t)VMAX);
 #pragma unroll
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const CodeT *__restrict__ cod
                     } else {
                         if (VALIDATE) {
 #pragma unroll
-                            for (int e = 0; e < 2; ++e) bad += count_bad((int)(int16_t)(x >> (16 * e)), VMAX);
+                            for (int e = 0; e < 2; ++e) bad_here += count_bad((int)(int16_t)(x >> (16 * e)), VMAX);
                         }
                         const uint32_t t = add_halves(x, 0x00010001u * (uint32_t)VMAX);
 #pragma unroll
@@ -87,8 +88,9 @@ __global__ __launch_bounds__(256) void pack_kernel(const CodeT *__restrict__ cod
                     }
                 }
             }
-            if (VALIDATE && bad) {
+            if (VALIDATE && bad_here) {
                 // a bad entry packs as the lowest code: redo this group element by element
+                bad += bad_here;
 #pragma unroll
                 for (int p = 0; p < BITS; ++p) word[p] = 0u;
                 for (int k = 0; k < 32; ++k) {
@@ -124,12 +126,12 @@ template <typename CodeT, int BITS>
 hipError_t launch_bits(const void *codes, int64_t rows, int K, int Kw, uint32_t *planes,
                        int32_t *bad_count, bool validate, unsigned blocks, hipStream_t s) {
     if (validate)
-        hipLaunchKernelGGL((pack_kernel<CodeT, BITS, true>), dim3(blocks), dim3(256), 0, s,
+        launch_kernel((pack_kernel<CodeT, BITS, true>), dim3(blocks), dim3(256), 0, s,
                            (const CodeT *)codes, rows, K, Kw, planes, bad_count);
     else
-        hipLaunchKernelGGL((pack_kernel<CodeT, BITS, false>), dim3(blocks), dim3(256), 0, s,
+        launch_kernel((pack_kernel<CodeT, BITS, false>), dim3(blocks), dim3(256), 0, s,
                            (const CodeT *)codes, rows, K, Kw, planes, bad_count);
-    return hipGetLastError();
+    return launch_status();
 }
 
 template <typename CodeT>
@@ -275,10 +277,10 @@ hipError_t launch_window_pack(const uint32_t *planes, int64_t out_pixels, const 
     const int64_t want = (items + 255) / 256;
     const unsigned blocks = (unsigned)(want < (int64_t)1 << 20 ? want : (int64_t)1 << 20);
     if (dense_rows)
-        hipLaunchKernelGGL(window_pack_dense_kernel, dim3(blocks), dim3(256), 0, s, planes, items, q, H, W, C, ab, kwp, out);
+        launch_kernel(window_pack_dense_kernel, dim3(blocks), dim3(256), 0, s, planes, items, q, H, W, C, ab, kwp, out);
     else
-        hipLaunchKernelGGL(window_pack_kernel, dim3(blocks), dim3(256), 0, s, planes, items, q, H, W, C, ab, kwp, out);
-    return hipGetLastError();
+        launch_kernel(window_pack_kernel, dim3(blocks), dim3(256), 0, s, planes, items, q, H, W, C, ab, kwp, out);
+    return launch_status();
 }
 
 }  // namespace qnn

@@ -198,14 +198,14 @@ template <typename CodeT, int BITS>
 hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, float premul, int clip,
                      void *codes, uint32_t *planes, unsigned blocks, hipStream_t s) {
     if (pool)
-        hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
+        launch_kernel((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, clip, (CodeT *)codes, planes);
     else if (C % 64 == 0 && out_pixels * (C / 64) < ((int64_t)1 << 30)) {
         const int items = (int)(out_pixels * (C / 64)), groups = C / 64;
         const FastDiv dg = fast_div_for(groups);
         const bool front = clip || premul != 1.0f;
         CodeT *cp = (CodeT *)codes;
-#define QNN_FLAT(F, CO, PL) hipLaunchKernelGGL((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL>), dim3(blocks), dim3(256), 0, s, \
+#define QNN_FLAT(F, CO, PL) launch_kernel((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL>), dim3(blocks), dim3(256), 0, s, \
                                                y, items, groups, dg, premul, clip, cp, planes)
         if (front) {
             if (cp && planes) QNN_FLAT(true, true, true);
@@ -219,9 +219,9 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
 #undef QNN_FLAT
     }
     else
-        hipLaunchKernelGGL((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
+        launch_kernel((requant_pack_kernel<CodeT, BITS, false, 8>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, clip, (CodeT *)codes, planes);
-    return hipGetLastError();
+    return launch_status();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -283,9 +283,9 @@ hipError_t launch_pool_planes_t(const uint32_t *in, int64_t items, int Ho, int W
                                 hipStream_t s) {
     const int64_t want = (items + 255) / 256;
     const int64_t cap = (int64_t)device_simd_count() * 8;
-    hipLaunchKernelGGL((pool_planes_kernel<BITS>), dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, s, in,
+    launch_kernel((pool_planes_kernel<BITS>), dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, s, in,
                        items, Ho, Wo, Cw, out);
-    return hipGetLastError();
+    return launch_status();
 }
 
 }  // namespace
