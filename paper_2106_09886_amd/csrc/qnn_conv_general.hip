@@ -202,7 +202,7 @@ __device__ __forceinline__ void step(TapWalk &w, AxisSplit dil, int stride) {   
 // of rows_per_wave, so a wavefront has ONE sub-kernel and every SIMD gets its share whatever the
 // stride.  Sub-row i, sub-column j of phase (pa, pb) is output pixel (a0 + i*sh, b0 + j*sw), with
 // a0 the first row of the phase, and reads input pixel (i + qa, j + qb) shifted by the tap.
-template <int AB, int WB, int CWT, int TT, class OV>
+template <int AB, int WB, int CWT, int TT, int LG, class OV>
 __device__ __forceinline__ void transposed_phases(const BranchArgs &g, uniform_words As, int nload, float sc, int ct,
                                                   int wave_x) {
     const ConvGeom &q = g.geo;
@@ -355,7 +355,7 @@ __device__ __forceinline__ void transposed_phases(const BranchArgs &g, uniform_w
                     if (xb > xa) {
                         const uint32_t off_a = (uint32_t)((n * g.H + Iq) * g.W + Jq0 + xa) * pixel_bytes + (uint32_t)c0 * 4u;
                         const int kadd = (c0 == 0) ? __builtin_popcount(c.okmask) * g.kconst : 0;
-                        gen_run_fast<AB, WB, CWT, TT, TT>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
+                        gen_run_fast<AB, WB, CWT, TT, LG>(c, ov, rel0 + xa * q.sw, xb - xa, q.sw, off_a, pixel_bytes, kadd, first, last);
                     }
                     for (int x = max(xb, xa); x < count; ++x) checked(x);
                     it = seg_end;
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(256) void conv_general_kernel(const BranchArgs g) {
     const int T = q.KH * q.KW, Cw = g.Cw;
     if constexpr (TR) {
         if (Cw != 0 && T != 0) {                        // (the empty sum takes the plain row split below)
-            transposed_phases<AB, WB, CWT, TT, OV>(g, As, nload, sc, ct, rb);
+            transposed_phases<AB, WB, CWT, TT, LG, OV>(g, As, nload, sc, ct, rb);
             return;
         }
     }
@@ -588,8 +588,8 @@ __global__ __launch_bounds__(256) void conv_window_kernel(const BranchArgs g) {
 
 template <int AB, int WB, int KWP>
 void launch_window_shape(const BranchArgs &g, dim3 grid, hipStream_t s) {
-    if (g.planes_out != nullptr) hipLaunchKernelGGL((conv_window_kernel<AB, WB, KWP, true>), grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((conv_window_kernel<AB, WB, KWP, false>), grid, dim3(256), 0, s, g);
+    if (g.planes_out != nullptr) launch_kernel((conv_window_kernel<AB, WB, KWP, true>), grid, dim3(256), 0, s, g);
+    else launch_kernel((conv_window_kernel<AB, WB, KWP, false>), grid, dim3(256), 0, s, g);
 }
 
 template <int AB, int WB>
@@ -605,20 +605,33 @@ hipError_t launch_window_t(const BranchArgs &g, hipStream_t s) {
         case 8: launch_window_shape<AB, WB, 8>(g, grid, s); break;
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
+    return launch_status();
 }
 
 constexpr int imin3(int a, int b, int c) { return a < b ? (a < c ? a : c) : (b < c ? b : c); }
+
+// Largest number of kernel elements any phase of a transposed convolution uses (see transposed_phases)
+inline int transposed_phase_taps(const ConvGeom &q) {
+    int most = 0;
+    for (int pa = 0; pa < q.sh; ++pa)
+        for (int pb = 0; pb < q.sw; ++pb) {
+            int nh = 0, nw = 0;
+            for (int kh = 0; kh < q.KH; ++kh) nh += ((kh * q.dh) % q.sh == pa);
+            for (int kw = 0; kw < q.KW; ++kw) nw += ((kw * q.dw) % q.sw == pb);
+            most = nh * nw > most ? nh * nw : most;
+        }
+    return most;
+}
 
 template <int AB, int WB, int CWT>
 void launch_general_shape(const BranchArgs &g, dim3 grid, bool emit, hipStream_t s) {
     // taps whose activation words are requested together (scalar registers), also the weight chunk
     // of the plain variant
-    constexpr int TT = imin3(6, 64 / (WB * CWT), 24 / (AB * CWT));
+    constexpr int TT = CWT > 4 ? 1 : imin3(6, 64 / (WB * CWT), 24 / (AB * CWT));
     // wide variant for kernels with more taps than that: up to three groups of (at most 3) taps per
     // weight chunk while the chunk stays below 96 vector registers; fewer passes over the output
-    // and fewer weight reloads (forward convolution, one or two activation bits: measured 15 %
-    // faster on 3x3 and 5x5 layers with 64..96 channels, 5 % slower with four activation bits)
+    // and fewer weight reloads (forward convolution, up to four activation bits: measured 15 %
+    // faster on 3x3 and 5x5 layers with 64..96 channels and one or two bits, 0..6 % with four)
     constexpr int LGW = TT < 3 ? TT : 3;
     constexpr int NGW = imin3(3, 96 / (WB * CWT * LGW), 3);
     if (g.geo.transposed) {
@@ -629,19 +642,37 @@ void launch_general_shape(const BranchArgs &g, dim3 grid, bool emit, hipStream_t
         const int64_t waves = ((nb * hp * wp + g.rows_per_wave - 1) / g.rows_per_wave) * g.col_tiles;
         const int64_t phases = (int64_t)q.sh * q.sw;
         const dim3 tgrid((unsigned)((waves + 3) / 4), (unsigned)(phases < 65535 ? phases : 65535));
-        if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, true>), tgrid, dim3(256), 0, s, g);
-        else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, true, false>), tgrid, dim3(256), 0, s, g);
+        // A phase of the usual deconvolutions (4x4 or 3x3 kernel, stride 2) has at most four taps:
+        // with one or two activation bits all four fit one chunk (4 x WB x CWT weight registers),
+        // taken as two groups of two taps (one group of one with eight channel words and two bits),
+        // instead of a chunk of TT taps and a second one for the rest.
+        if constexpr (AB <= 2 && WB * CWT <= 16 && TT < 4) {
+            if (transposed_phase_taps(q) == 4) {
+                if (emit) launch_kernel((conv_general_kernel<AB, WB, CWT, 4, (AB * CWT <= 8 ? 2 : 1), true, true>), tgrid, dim3(256), 0, s, g);
+                else launch_kernel((conv_general_kernel<AB, WB, CWT, 4, (AB * CWT <= 8 ? 2 : 1), true, false>), tgrid, dim3(256), 0, s, g);
+                return;
+            }
+        }
+        if constexpr (CWT <= 4) {
+            if (emit) launch_kernel((conv_general_kernel<AB, WB, CWT, TT, TT, true, true>), tgrid, dim3(256), 0, s, g);
+            else launch_kernel((conv_general_kernel<AB, WB, CWT, TT, TT, true, false>), tgrid, dim3(256), 0, s, g);
+        }
         return;
     }
-    if constexpr (AB <= 2 && WB <= 4 && NGW >= 2) {
-        if (g.geo.KH * g.geo.KW > TT) {
-            if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, NGW * LGW, LGW, false, true>), grid, dim3(256), 0, s, g);
-            else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, NGW * LGW, LGW, false, false>), grid, dim3(256), 0, s, g);
-            return;
+    // (eight-word chunks exist for the four-tap deconvolution alone)
+    if constexpr (CWT <= 4) {
+        // measured with four activation bits: 5x5, 64 -> 64 channels, 56x56: 135 -> 127 us; 3x3 dilation 4,
+        // 512 -> 512, 17x17: 357 -> 340 us; 3x3 dilation 2, 256 -> 256, 33x33, three weight bits: equal
+        if constexpr (AB <= 4 && WB <= 4 && NGW >= 2) {
+            if (g.geo.KH * g.geo.KW > TT) {
+                if (emit) launch_kernel((conv_general_kernel<AB, WB, CWT, NGW * LGW, LGW, false, true>), grid, dim3(256), 0, s, g);
+                else launch_kernel((conv_general_kernel<AB, WB, CWT, NGW * LGW, LGW, false, false>), grid, dim3(256), 0, s, g);
+                return;
+            }
         }
+        if (emit) launch_kernel((conv_general_kernel<AB, WB, CWT, TT, TT, false, true>), grid, dim3(256), 0, s, g);
+        else launch_kernel((conv_general_kernel<AB, WB, CWT, TT, TT, false, false>), grid, dim3(256), 0, s, g);
     }
-    if (emit) hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, false, true>), grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((conv_general_kernel<AB, WB, CWT, TT, TT, false, false>), grid, dim3(256), 0, s, g);
 }
 
 template <int AB, int WB>
@@ -658,11 +689,17 @@ hipError_t launch_general_t(const BranchArgs &g, hipStream_t s) {
     // one word); only beyond 16 words is a ragged last chunk the smaller cost.
     constexpr int CMAX = (AB <= 2) ? 4 : (AB <= 4) ? 2 : 1;
     const bool any = g.Cw > 16;
+    if constexpr (AB <= 2 && WB <= 2) {
+        if (g.geo.transposed && g.Cw % 8 == 0 && transposed_phase_taps(g.geo) == 4) {
+            launch_general_shape<AB, WB, 8>(g, grid, emit, s);
+            return launch_status();
+        }
+    }
     if (CMAX >= 4 && g.Cw >= 4 && (any || g.Cw % 4 == 0)) launch_general_shape<AB, WB, (CMAX >= 4 ? 4 : 1)>(g, grid, emit, s);
     else if (CMAX >= 4 && g.Cw % 3 == 0) launch_general_shape<AB, WB, (CMAX >= 4 ? 3 : 1)>(g, grid, emit, s);   // C = 96, 192, 288
     else if (CMAX >= 2 && g.Cw >= 2 && (any || g.Cw % 2 == 0)) launch_general_shape<AB, WB, (CMAX >= 2 ? 2 : 1)>(g, grid, emit, s);
     else launch_general_shape<AB, WB, 1>(g, grid, emit, s);
-    return hipGetLastError();
+    return launch_status();
 }
 
 }  // namespace

@@ -14,11 +14,23 @@
 // items in flight.  HBM-bound: 4 (16 with pooling) bytes in and bits/8 (+1 with codes) bytes
 // out per output element.  The same kernel serves the real-valued front end (qnn_encode_real):
 // an optional clip to [0,1] and one binary32 multiply by 2^bits - 1 before the rule.
+#include <type_traits>
+#include <utility>
 #include "qnn_internal.h"
 #include "qnn_device_util.h"
 
 namespace qnn {
 namespace {
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_items_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant
+template <int N, class F>
+__device__ __forceinline__ void static_for_items(F &&f) {
+    static_for_items_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // Stored index u = (code + 2^BITS - 1) / 2 of the rule above: with H = 2^(BITS-1) and
 // f = min(floor(|y|/2), H-1),  u = f xor (y > 0 ? H : H-1)  (and code = 2u - (2^BITS - 1)).
@@ -123,6 +135,83 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
     }
 }
 
+// Planes of one item into lanes 2*ITEM and 2*ITEM+1 of P[k] (step k carries plane BITS-1-k, as in
+// emit_planes): after the U items of a trip, lane 2u+h of P[k] holds half h of that plane of item u,
+// and one store per plane writes the trip's words of the plane, which are consecutive in memory
+// wherever the items are consecutive channel groups of one pixel.  One asm statement for the
+// doublings and one per (at most) four planes for the lane writes, as in emit_planes.
+template <int BITS, int ITEM>
+struct PlanesAt;
+
+template <int ITEM>
+struct PlanesAt<1, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[1]) {
+        uint64_t m0;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0" : "+v"(top), "=&s"(m0));
+        asm volatile("v_writelane_b32 %0, %1, %c3\n\tv_writelane_b32 %0, %2, %c4" : "+v"(P[0]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<2, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[2]) {
+        uint64_t m0, m1;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1));
+        asm volatile("v_writelane_b32 %0, %2, %c6\n\tv_writelane_b32 %0, %3, %c7\n\tv_writelane_b32 %1, %4, %c6\n\tv_writelane_b32 %1, %5, %c7" : "+v"(P[0]), "+v"(P[1]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<3, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[3]) {
+        uint64_t m0, m1, m2;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2));
+        asm volatile("v_writelane_b32 %0, %3, %c9\n\tv_writelane_b32 %0, %4, %c10\n\tv_writelane_b32 %1, %5, %c9\n\tv_writelane_b32 %1, %6, %c10\n\tv_writelane_b32 %2, %7, %c9\n\tv_writelane_b32 %2, %8, %c10" : "+v"(P[0]), "+v"(P[1]), "+v"(P[2]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<4, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[4]) {
+        uint64_t m0, m1, m2, m3;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3));
+        asm volatile("v_writelane_b32 %0, %4, %c12\n\tv_writelane_b32 %0, %5, %c13\n\tv_writelane_b32 %1, %6, %c12\n\tv_writelane_b32 %1, %7, %c13\n\tv_writelane_b32 %2, %8, %c12\n\tv_writelane_b32 %2, %9, %c13\n\tv_writelane_b32 %3, %10, %c12\n\tv_writelane_b32 %3, %11, %c13" : "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<5, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[5]) {
+        uint64_t m0, m1, m2, m3, m4;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4));
+        asm volatile("v_writelane_b32 %0, %4, %c12\n\tv_writelane_b32 %0, %5, %c13\n\tv_writelane_b32 %1, %6, %c12\n\tv_writelane_b32 %1, %7, %c13\n\tv_writelane_b32 %2, %8, %c12\n\tv_writelane_b32 %2, %9, %c13\n\tv_writelane_b32 %3, %10, %c12\n\tv_writelane_b32 %3, %11, %c13" : "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+        asm volatile("v_writelane_b32 %0, %1, %c3\n\tv_writelane_b32 %0, %2, %c4" : "+v"(P[4]) : "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<6, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[6]) {
+        uint64_t m0, m1, m2, m3, m4, m5;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0\n\tv_add_co_u32 %0, %6, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5));
+        asm volatile("v_writelane_b32 %0, %4, %c12\n\tv_writelane_b32 %0, %5, %c13\n\tv_writelane_b32 %1, %6, %c12\n\tv_writelane_b32 %1, %7, %c13\n\tv_writelane_b32 %2, %8, %c12\n\tv_writelane_b32 %2, %9, %c13\n\tv_writelane_b32 %3, %10, %c12\n\tv_writelane_b32 %3, %11, %c13" : "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+        asm volatile("v_writelane_b32 %0, %2, %c6\n\tv_writelane_b32 %0, %3, %c7\n\tv_writelane_b32 %1, %4, %c6\n\tv_writelane_b32 %1, %5, %c7" : "+v"(P[4]), "+v"(P[5]) : "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "s"((uint32_t)m5), "s"((uint32_t)(m5 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<7, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[7]) {
+        uint64_t m0, m1, m2, m3, m4, m5, m6;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0\n\tv_add_co_u32 %0, %6, %0, %0\n\tv_add_co_u32 %0, %7, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6));
+        asm volatile("v_writelane_b32 %0, %4, %c12\n\tv_writelane_b32 %0, %5, %c13\n\tv_writelane_b32 %1, %6, %c12\n\tv_writelane_b32 %1, %7, %c13\n\tv_writelane_b32 %2, %8, %c12\n\tv_writelane_b32 %2, %9, %c13\n\tv_writelane_b32 %3, %10, %c12\n\tv_writelane_b32 %3, %11, %c13" : "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+        asm volatile("v_writelane_b32 %0, %3, %c9\n\tv_writelane_b32 %0, %4, %c10\n\tv_writelane_b32 %1, %5, %c9\n\tv_writelane_b32 %1, %6, %c10\n\tv_writelane_b32 %2, %7, %c9\n\tv_writelane_b32 %2, %8, %c10" : "+v"(P[4]), "+v"(P[5]), "+v"(P[6]) : "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "s"((uint32_t)m5), "s"((uint32_t)(m5 >> 32)), "s"((uint32_t)m6), "s"((uint32_t)(m6 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+template <int ITEM>
+struct PlanesAt<8, ITEM> {
+    static __device__ __forceinline__ void put(uint32_t top, int (&P)[8]) {
+        uint64_t m0, m1, m2, m3, m4, m5, m6, m7;
+        asm volatile("v_add_co_u32 %0, %1, %0, %0\n\tv_add_co_u32 %0, %2, %0, %0\n\tv_add_co_u32 %0, %3, %0, %0\n\tv_add_co_u32 %0, %4, %0, %0\n\tv_add_co_u32 %0, %5, %0, %0\n\tv_add_co_u32 %0, %6, %0, %0\n\tv_add_co_u32 %0, %7, %0, %0\n\tv_add_co_u32 %0, %8, %0, %0" : "+v"(top), "=&s"(m0), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4), "=&s"(m5), "=&s"(m6), "=&s"(m7));
+        asm volatile("v_writelane_b32 %0, %4, %c12\n\tv_writelane_b32 %0, %5, %c13\n\tv_writelane_b32 %1, %6, %c12\n\tv_writelane_b32 %1, %7, %c13\n\tv_writelane_b32 %2, %8, %c12\n\tv_writelane_b32 %2, %9, %c13\n\tv_writelane_b32 %3, %10, %c12\n\tv_writelane_b32 %3, %11, %c13" : "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]) : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)), "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+        asm volatile("v_writelane_b32 %0, %4, %c12\n\tv_writelane_b32 %0, %5, %c13\n\tv_writelane_b32 %1, %6, %c12\n\tv_writelane_b32 %1, %7, %c13\n\tv_writelane_b32 %2, %8, %c12\n\tv_writelane_b32 %2, %9, %c13\n\tv_writelane_b32 %3, %10, %c12\n\tv_writelane_b32 %3, %11, %c13" : "+v"(P[4]), "+v"(P[5]), "+v"(P[6]), "+v"(P[7]) : "s"((uint32_t)m4), "s"((uint32_t)(m4 >> 32)), "s"((uint32_t)m5), "s"((uint32_t)(m5 >> 32)), "s"((uint32_t)m6), "s"((uint32_t)(m6 >> 32)), "s"((uint32_t)m7), "s"((uint32_t)(m7 >> 32)), "n"(2 * ITEM), "n"(2 * ITEM + 1));
+    }
+};
+
 // The same without pooling when C is a multiple of 64: item i is the 64 consecutive floats
 // y[64 i ..], i.e. (pixel i / (C/64), channel group i % (C/64)), and its plane words are
 // planes[(pixel*BITS + p)*Cw + 2*group + h].  All addressing is wave-uniform (scalar unit) plus
@@ -131,9 +220,12 @@ __global__ __launch_bounds__(256) void requant_pack_kernel(const float *__restri
 // CODES / PLANES: which outputs are written (compile-time, so a trip carries no test for them).
 // Everything but the rule itself is kept on the scalar unit: item numbers are 32-bit (the host sends
 // larger problems to the general kernel), a full trip of U items has no per-item tests, and the
-// pixel / channel-group position is divided out once per trip with the host's constants and then
-// stepped.  Per item the vector ALU sees 7 instructions for the rule and 3 per plane.
-template <typename CodeT, int BITS, int U, bool FRONT, bool CODES, bool PLANES>
+// pixel / channel-group position is divided out once per trip with the host's constants.  Per item
+// the vector ALU sees 7 instructions for the rule and 3 per plane.  GATHER: the plane words of a trip
+// are collected (PlanesAt) and stored once per plane and trip, for rows of many channels: 8-byte
+// stores per item and plane held a stream of 4096-channel rows at 4.1 TB/s where the same kernel
+// writing codes reached 5.2.
+template <typename CodeT, int BITS, int U, bool FRONT, bool CODES, bool PLANES, bool GATHER>
 __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restrict__ y, int items, int cgroups,
                                                            FastDiv div_groups, float premul, int clip,
                                                            CodeT *__restrict__ codes, uint32_t *__restrict__ planes) {
@@ -142,10 +234,11 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
     const int Cw = 2 * cgroups;
     const int wave0 = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4u + (threadIdx.x >> 6)));
     const int nwaves = (int)gridDim.x * 4;
-    // lane 2k+h stores half h of plane BITS-1-k (see emit_planes)
-    const int store_off = ((BITS - 1 - (lane >> 1)) * Cw + (lane & 1)) * 4;
+    const uint32_t plane_bytes = (uint32_t)Cw * 4u;
+    const uint32_t pixel_bytes = (uint32_t)BITS * plane_bytes;             // plane words of one pixel
+    const int lane_item = lane >> 1, lane_half = lane & 1;               // lane 2u+h: item u of a trip, half h
+    const int store_off = ((BITS - 1 - (lane >> 1)) * Cw + (lane & 1)) * 4;   // !GATHER
     const bool stores = lane < 2 * BITS;
-    const uint32_t pixel_bytes = (uint32_t)(BITS * Cw) * 4u;             // plane words of one pixel
     // trips of U items; a wavefront takes every nwaves-th trip
     for (int it0 = wave0 * U; it0 < items; it0 += nwaves * U) {
         const int n = __builtin_amdgcn_readfirstlane(min(items - it0, U));
@@ -156,15 +249,26 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
             v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, u * 256, 0));
         int pix, cg;
         fast_divmod((uint32_t)it0, div_groups, pix, cg);
-        // outputs of the trip through descriptors based at its first item; offsets are stepped
+        // outputs of the trip through descriptors based at its first item
         __amdgpu_buffer_rsrc_t dc, dp;
         if constexpr (CODES) dc = make_rsrc((void *)(codes + (int64_t)it0 * 64), (uint32_t)n * 64u * (uint32_t)sizeof(CodeT));
-        uint32_t poff = 0u;                                              // bytes from the first item's plane words
-        if constexpr (PLANES) {
+        int P[BITS];
+        int lane_off = 0;                   // bytes from the first item's plane-0 words to this lane's item and half
+        uint32_t poff = 0u;                 // !GATHER: bytes from the first item's plane words to the current item's
+        int cgi = cg;
+        if constexpr (PLANES && !GATHER) dp = make_rsrc((void *)(planes + ((int64_t)pix * BITS) * Cw + 2 * cg), 0xffffffffu);
+        if constexpr (PLANES && GATHER) {
             // the trip spans at most U/cgroups + 2 pixels
             dp = make_rsrc((void *)(planes + ((int64_t)pix * BITS) * Cw + 2 * cg), 0xffffffffu);
+#pragma unroll
+            for (int k = 0; k < BITS; ++k) P[k] = 0;
+            // item u of the trip is channel group (cg + u) mod cgroups of pixel pix + (cg + u) / cgroups
+            const int t = cg + lane_item;
+            const int dpix = (int)fast_div((uint32_t)t, div_groups);
+            lane_off = dpix * (int)pixel_bytes + (2 * (t - dpix * cgroups - cg) + lane_half) * 4;
         }
-        auto item = [&](int u) {
+        auto item = [&](auto UC) {
+            constexpr int u = decltype(UC)::value;
             float val = v[u];
             if constexpr (FRONT) val = limit_range(val, clip) * premul;
             const uint32_t uidx = round_odd_index<BITS>(val);
@@ -173,23 +277,31 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
                 if (sizeof(CodeT) == 1) __builtin_amdgcn_raw_buffer_store_b8((char)code, dc, lane, u * 64, 0);
                 else __builtin_amdgcn_raw_buffer_store_b16((short)code, dc, lane * 2, u * 128, 0);
             }
-            if constexpr (PLANES) {
+            if constexpr (PLANES && GATHER) PlanesAt<BITS, u>::put(uidx << (32 - BITS), P);
+            if constexpr (PLANES && !GATHER) {
+                // lane 2k+h stores half h of plane BITS-1-k (see emit_planes)
                 const int mine = emit_planes<BITS>(uidx << (32 - BITS));
                 if (stores) __builtin_amdgcn_raw_buffer_store_b32(mine, dp, store_off, (int)poff, 0);
                 poff += 8u;                                              // next channel group: two words on
-                if (++cg == cgroups) {                                   // next pixel
-                    cg = 0;
+                if (++cgi == cgroups) {                                  // next pixel
+                    cgi = 0;
                     poff += pixel_bytes - 8u * (uint32_t)cgroups;
                 }
             }
         };
         if (n == U) {                                                    // a full trip: no test per item
-#pragma unroll
-            for (int u = 0; u < U; ++u) item(u);
+            static_for_items<U>(item);
         } else {                                                         // the short last trip
+            static_for_items<U>([&](auto UC) {
+                if (decltype(UC)::value < n) item(UC);
+            });
+        }
+        if constexpr (PLANES && GATHER) {
+            if (lane_item < n && lane < 2 * U) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (u < n) item(u);
+                for (int k = 0; k < BITS; ++k)
+                    __builtin_amdgcn_raw_buffer_store_b32(P[k], dp, lane_off, (int)((uint32_t)(BITS - 1 - k) * plane_bytes), 0);
+            }
         }
     }
 }
@@ -205,8 +317,19 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
         const FastDiv dg = fast_div_for(groups);
         const bool front = clip || premul != 1.0f;
         CodeT *cp = (CodeT *)codes;
-#define QNN_FLAT(F, CO, PL) launch_kernel((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL>), dim3(blocks), dim3(256), 0, s, \
-                                               y, items, groups, dg, premul, clip, cp, planes)
+        // plane words gathered per trip (one store per plane) from 1024 channels on; measured, 4-bit planes
+        // out of fp32: 65536 x 4096: 289 -> 251 us, 65536 x 1024: 67 -> 49 us; up to 512 channels the
+        // per-item stores are as fast or 3 % faster (the words of a pixel's planes lie close together)
+        const bool gather = groups >= 16;
+#define QNN_FLAT(F, CO, PL)                                                                                            \
+    do {                                                                                                               \
+        if (PL && gather)                                                                                              \
+            launch_kernel((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL, PL>), dim3(blocks), dim3(256), 0, s, y, items, \
+                          groups, dg, premul, clip, cp, planes);                                                       \
+        else                                                                                                           \
+            launch_kernel((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL, false>), dim3(blocks), dim3(256), 0, s, y,  \
+                          items, groups, dg, premul, clip, cp, planes);                                                \
+    } while (0)
         if (front) {
             if (cp && planes) QNN_FLAT(true, true, true);
             else if (planes) QNN_FLAT(true, false, true);

@@ -21,7 +21,12 @@ def q():
 # ------------------------------------------------------------ re-encode kernel on its own
 @pytest.mark.parametrize("bits", [1, 2, 4, 7, 8])
 @pytest.mark.parametrize("shape,pool", [((1, 1, 1, 1), False), ((2, 3, 5, 7), False), ((1, 4, 6, 64), True),
-                                        ((2, 2, 2, 65), True), ((1, 6, 4, 130), False), ((3, 8, 8, 32), True)])
+                                        ((2, 2, 2, 65), True), ((1, 6, 4, 130), False), ((3, 8, 8, 32), True),
+                                        # multiples of 64 channels without pooling: the flat kernel; from 1024
+                                        # channels on its plane words are gathered per trip of 16 items (trips
+                                        # inside one pixel, across pixels, and a short last trip)
+                                        ((2, 3, 3, 128), False), ((1, 5, 5, 320), False), ((1, 3, 7, 1024), False),
+                                        ((1, 1, 5, 1088), False), ((2, 1, 3, 4096), False)])
 def test_requant_pack(q, oracle, bits, shape, pool):
     say("requant", bits, shape, pool)
     rng = np.random.default_rng(bits * 100 + sum(shape))
@@ -48,7 +53,7 @@ def test_requant_pack(q, oracle, bits, shape, pool):
 
 @pytest.mark.parametrize("bits", [1, 2, 3, 4, 7, 8])
 @pytest.mark.parametrize("hrelu", [False, True])
-@pytest.mark.parametrize("shape", [(1, 1), (7, 33), (64, 64), (5, 200), (300, 70)])
+@pytest.mark.parametrize("shape", [(1, 1), (7, 33), (64, 64), (5, 200), (300, 70), (37, 2048), (3, 1216)])
 def test_encode_real(q, oracle, bits, hrelu, shape):
     """Real-valued front end: clip, scale by 2^bits - 1 in binary32, Table 2 rule, planes."""
     say("encode_real", bits, hrelu, shape)

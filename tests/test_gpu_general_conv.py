@@ -102,6 +102,11 @@ CASES = [
     dict(Nb=1, H=6, W=6, C=96, Cout=64, ab=2, wb=2, KH=5, KW=5, stride=2, pad=2, transposed=True, output_padding=1),
     dict(Nb=3, H=14, W=13, C=64, Cout=130, ab=2, wb=2, KH=4, KW=4, stride=2, pad=1, transposed=True),
     dict(Nb=2, H=9, W=9, C=128, Cout=64, ab=1, wb=1, KH=3, KW=3, stride=(1, 2), pad=(1, 0), transposed=True),
+    # phases of at most four taps, one or two activation bits: the four-tap chunk (4 and 8 channel words)
+    dict(Nb=2, H=7, W=9, C=128, Cout=70, ab=2, wb=3, KH=4, KW=4, stride=2, pad=1, transposed=True),
+    dict(Nb=1, H=6, W=5, C=256, Cout=64, ab=1, wb=2, KH=3, KW=3, stride=2, pad=1, transposed=True, output_padding=1),
+    dict(Nb=1, H=5, W=7, C=512, Cout=33, ab=2, wb=1, KH=4, KW=4, stride=2, pad=1, transposed=True),
+    dict(Nb=1, H=6, W=6, C=256, Cout=64, ab=2, wb=2, KH=4, KW=4, stride=2, pad=0, transposed=True),
 ]
 
 
