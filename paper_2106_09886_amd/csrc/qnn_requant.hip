@@ -225,10 +225,20 @@ struct PlanesAt<8, ITEM> {
 // are collected (PlanesAt) and stored once per plane and trip, for rows of many channels: 8-byte
 // stores per item and plane held a stream of 4096-channel rows at 4.1 TB/s where the same kernel
 // writing codes reached 5.2.
-template <typename CodeT, int BITS, int U, bool FRONT, bool CODES, bool PLANES, bool GATHER>
+// POOL: the item's value is the maximum over the 2x2 input pixels of its output pixel (four loads per
+// item; the input is addressed through one descriptor with byte offsets below 2^32, which the host
+// checks), taken in the order (0,0), (0,1), (1,0), (1,1) with "greater than" as the plain kernel does.
+struct PoolArgs {
+    FastDiv div_wo, div_howo;       // output pixel -> (image, row, column)
+    int Wo, Ho;
+    uint32_t pix_bytes, row_bytes, img_bytes, total_bytes;      // of the input: C*4, W*C*4, H*W*C*4, Nb*H*W*C*4
+};
+
+template <typename CodeT, int BITS, int U, bool FRONT, bool CODES, bool PLANES, bool GATHER, bool POOL = false>
 __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restrict__ y, int items, int cgroups,
                                                            FastDiv div_groups, float premul, int clip,
-                                                           CodeT *__restrict__ codes, uint32_t *__restrict__ planes) {
+                                                           CodeT *__restrict__ codes, uint32_t *__restrict__ planes,
+                                                           PoolArgs pg) {
     constexpr int VMAX = (1 << BITS) - 1;
     const int lane = (int)(threadIdx.x & 63);
     const int Cw = 2 * cgroups;
@@ -242,13 +252,46 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
     // trips of U items; a wavefront takes every nwaves-th trip
     for (int it0 = wave0 * U; it0 < items; it0 += nwaves * U) {
         const int n = __builtin_amdgcn_readfirstlane(min(items - it0, U));
-        const __amdgpu_buffer_rsrc_t src = make_rsrc((void *)(y + (int64_t)it0 * 64), (uint32_t)n * 256u);
-        float v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)         // reads past the descriptor's n*256 bytes return 0
-            v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, u * 256, 0));
         int pix, cg;
         fast_divmod((uint32_t)it0, div_groups, pix, cg);
+        float v[U];
+        if constexpr (!POOL) {
+            const __amdgpu_buffer_rsrc_t src = make_rsrc((void *)(y + (int64_t)it0 * 64), (uint32_t)n * 256u);
+#pragma unroll
+            for (int u = 0; u < U; ++u)         // reads past the descriptor's n*256 bytes return 0
+                v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, u * 256, 0));
+        } else {
+            const __amdgpu_buffer_rsrc_t src = make_rsrc((void *)y, pg.total_bytes);
+            int img, rem, oh, ow;
+            fast_divmod((uint32_t)pix, pg.div_howo, img, rem);
+            fast_divmod((uint32_t)rem, pg.div_wo, oh, ow);
+            int cgl = cg;
+            float w4[U][4];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {       // (an item past the last one reads zeros or valid memory, and is not used)
+                const uint32_t base = (uint32_t)img * pg.img_bytes + (uint32_t)(2 * oh) * pg.row_bytes +
+                                      (uint32_t)(2 * ow) * pg.pix_bytes + (uint32_t)cgl * 256u;
+                w4[u][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, (int)base, 0));
+                w4[u][1] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, (int)(base + pg.pix_bytes), 0));
+                w4[u][2] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, (int)(base + pg.row_bytes), 0));
+                w4[u][3] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, lane * 4, (int)(base + pg.row_bytes + pg.pix_bytes), 0));
+                if (++cgl == cgroups) {
+                    cgl = 0;
+                    if (++ow == pg.Wo) {
+                        ow = 0;
+                        if (++oh == pg.Ho) { oh = 0; ++img; }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float m = w4[u][0];
+                if (w4[u][1] > m) m = w4[u][1];
+                if (w4[u][2] > m) m = w4[u][2];
+                if (w4[u][3] > m) m = w4[u][3];
+                v[u] = m;
+            }
+        }
         // outputs of the trip through descriptors based at its first item
         __amdgpu_buffer_rsrc_t dc, dp;
         if constexpr (CODES) dc = make_rsrc((void *)(codes + (int64_t)it0 * 64), (uint32_t)n * 64u * (uint32_t)sizeof(CodeT));
@@ -307,16 +350,45 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
 }
 
 template <typename CodeT, int BITS>
-hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, bool pool, float premul, int clip,
-                     void *codes, uint32_t *planes, unsigned blocks, hipStream_t s) {
-    if (pool)
+hipError_t launch_rq(const float *y, int64_t Nb, int64_t H, int64_t W, int64_t out_pixels, int Ho, int Wo, int C, bool pool,
+                     float premul, int clip, void *codes, uint32_t *planes, unsigned blocks, hipStream_t s) {
+    const int64_t in_bytes = (int64_t)Nb * H * W * C * 4;
+    const bool flat_ok = C % 64 == 0 && out_pixels * (C / 64) < ((int64_t)1 << 30);
+    if (pool && flat_ok && in_bytes < ((int64_t)1 << 32) && Ho > 0 && Wo > 0) {
+        const int items = (int)(out_pixels * (C / 64)), groups = C / 64;
+        const FastDiv dg = fast_div_for(groups);
+        PoolArgs pg;
+        pg.div_wo = fast_div_for(Wo);
+        pg.div_howo = fast_div_for(Ho * Wo);
+        pg.Wo = Wo; pg.Ho = Ho;
+        pg.pix_bytes = (uint32_t)C * 4u;
+        pg.row_bytes = (uint32_t)(W * C * 4);
+        pg.img_bytes = (uint32_t)(H * W * C * 4);
+        pg.total_bytes = (uint32_t)in_bytes;
+        const bool front = clip || premul != 1.0f;
+        CodeT *cp = (CodeT *)codes;
+        // four items (sixteen 256-byte rows) in flight per wavefront
+#define QNN_POOL(F, CO, PL) launch_kernel((requant_flat_kernel<CodeT, BITS, 4, F, CO, PL, false, true>), dim3(blocks), dim3(256), 0, \
+                                          s, y, items, groups, dg, premul, clip, cp, planes, pg)
+        if (front) {
+            if (cp && planes) QNN_POOL(true, true, true);
+            else if (planes) QNN_POOL(true, false, true);
+            else QNN_POOL(true, true, false);
+        } else {
+            if (cp && planes) QNN_POOL(false, true, true);
+            else if (planes) QNN_POOL(false, false, true);
+            else QNN_POOL(false, true, false);
+        }
+#undef QNN_POOL
+    } else if (pool)
         launch_kernel((requant_pack_kernel<CodeT, BITS, true, 2>), dim3(blocks), dim3(256), 0, s, y,
                            out_pixels, Ho, Wo, C, premul, clip, (CodeT *)codes, planes);
-    else if (C % 64 == 0 && out_pixels * (C / 64) < ((int64_t)1 << 30)) {
+    else if (flat_ok) {
         const int items = (int)(out_pixels * (C / 64)), groups = C / 64;
         const FastDiv dg = fast_div_for(groups);
         const bool front = clip || premul != 1.0f;
         CodeT *cp = (CodeT *)codes;
+        const PoolArgs pg = {};
         // plane words gathered per trip (one store per plane) from 1024 channels on; measured, 4-bit planes
         // out of fp32: 65536 x 4096: 289 -> 251 us, 65536 x 1024: 67 -> 49 us; up to 512 channels the
         // per-item stores are as fast or 3 % faster (the words of a pixel's planes lie close together)
@@ -325,10 +397,10 @@ hipError_t launch_rq(const float *y, int64_t out_pixels, int Ho, int Wo, int C, 
     do {                                                                                                               \
         if (PL && gather)                                                                                              \
             launch_kernel((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL, PL>), dim3(blocks), dim3(256), 0, s, y, items, \
-                          groups, dg, premul, clip, cp, planes);                                                       \
+                          groups, dg, premul, clip, cp, planes, pg);                                                   \
         else                                                                                                           \
             launch_kernel((requant_flat_kernel<CodeT, BITS, 16, F, CO, PL, false>), dim3(blocks), dim3(256), 0, s, y,  \
-                          items, groups, dg, premul, clip, cp, planes);                                                \
+                          items, groups, dg, premul, clip, cp, planes, pg);                                            \
     } while (0)
         if (front) {
             if (cp && planes) QNN_FLAT(true, true, true);
@@ -423,7 +495,7 @@ hipError_t launch_requant(const float *y, int64_t Nb, int64_t H, int64_t W, int6
     const int64_t want = (items + 3) / 4;
     const int64_t cap = (int64_t)device_simd_count() * 2;
     const unsigned blocks = (unsigned)(want < cap ? want : cap);
-#define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, out_pixels, Ho, Wo, (int)C, pool, premul, clip, codes, planes, blocks, s)
+#define QNN_RQ(B, T) case B: return launch_rq<T, B>(y, Nb, H, W, out_pixels, Ho, Wo, (int)C, pool, premul, clip, codes, planes, blocks, s)
     switch (bits) {
         QNN_RQ(1, int8_t); QNN_RQ(2, int8_t); QNN_RQ(3, int8_t); QNN_RQ(4, int8_t);
         QNN_RQ(5, int8_t); QNN_RQ(6, int8_t); QNN_RQ(7, int8_t); QNN_RQ(8, int16_t);

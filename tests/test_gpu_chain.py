@@ -26,7 +26,9 @@ def q():
                                         # channels on its plane words are gathered per trip of 16 items (trips
                                         # inside one pixel, across pixels, and a short last trip)
                                         ((2, 3, 3, 128), False), ((1, 5, 5, 320), False), ((1, 3, 7, 1024), False),
-                                        ((1, 1, 5, 1088), False), ((2, 1, 3, 4096), False)])
+                                        ((1, 1, 5, 1088), False), ((2, 1, 3, 4096), False),
+                                        # ... and with pooling
+                                        ((2, 4, 6, 128), True), ((2, 6, 6, 192), True), ((1, 8, 4, 64), True)])
 def test_requant_pack(q, oracle, bits, shape, pool):
     say("requant", bits, shape, pool)
     rng = np.random.default_rng(bits * 100 + sum(shape))
