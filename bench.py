@@ -110,7 +110,11 @@ def record_traffic(args):
         cal, ker = vals("copyBuffer"), vals(kernel)
         if not cal or not ker:
             raise SystemExit("%s: no %s rows for the copy or for '%s'" % (path, counter, kernel))
-        factor = (256 << 10) / statistics.median(cal)             # the copy moves 262144 KiB each way
+        # the calibration copy (262144 KiB each way) is the largest device copy of the run; smaller ones
+        # (torch's own) share the kernel name
+        factor = (256 << 10) / max(cal)
+        if not 0.9 <= factor <= 2.2:
+            raise SystemExit("%s: the largest copy shows %s = %.1f KiB, not a 256 MiB copy" % (path, counter, max(cal)))
         return statistics.median(ker) * 1024.0 * factor, factor, len(ker)
     fb, ff, nf = per_dispatch(fetch_csv, "FETCH_SIZE")
     wb, wf, nw = per_dispatch(write_csv, "WRITE_SIZE")
