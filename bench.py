@@ -370,6 +370,10 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
                  ("4x4 stride 2 transposed, 256->128, 28^2, W2A2", 16, 28, 28, 256, 128, 2, 2, 4, 4, 2, 1, 1, True)]
         cases.insert(1, ("ResNet stem 7x7 stride 2, 3->64, 224^2, W2A8, row-dense input", 32, 224, 224, 3, 64, 8, 2,
                          7, 7, 2, 3, 1, False))
+        if args.only:
+            cases = [c for c in cases if args.only in c[0]]
+            if not cases:
+                raise SystemExit("--only %r matches no layer of the suite" % args.only)
         for (label, Nb, H, W, C, Cout, ab, wb, KH, KW, st, pd, dl, tr) in cases:
             Cw = (C + 31) // 32
             dense = label.endswith("row-dense input")
@@ -422,6 +426,8 @@ def main():
                     help="resnet18_s1 / resnet50_s3 only: run the same layer on this many images instead of the "
                          "configuration's batch (a side measurement: how much of a launch is fixed cost)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default=None, metavar="TEXT",
+                    help="conv_geometries: time only the layers whose label contains TEXT (for counter runs on one kernel)")
     ap.add_argument("--graph", action="store_true",
                     help="additionally capture one step into a HIP graph and report the time per replay "
                          "(config.graph_ms_per_step); the headline value stays the eagerly launched step")
