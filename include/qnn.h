@@ -79,7 +79,8 @@ qnn_status qnn_device_info(int *h_compute_units, int *h_clock_khz);
                                   /* through the output buffer, 2 in LDS where possible        */
 #define QNN_TUNE_SPLIT_CHANNELS 6 /* 3x3 convolution: 1 one wavefront per (pixel run, 64 filters), 2 the   */
                                   /* four wavefronts of a block split the channel chunks where a      */
-                                  /* kernel for that exists (automatic: layers with few pixels)       */
+                                  /* kernel for that exists (automatic: layers with few pixels, and    */
+                                  /* wherever the chunks divide evenly among the four wavefronts)     */
 int qnn_tune(int key, int value);
 
 /*

@@ -314,12 +314,18 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
                                           Cout, e);
     // Few pixels and many channels: fewer than four wavefronts per SIMD would each make several
     // chunk passes.  The variant whose four wavefronts per block split the channel chunks gives four
-    // times the wavefronts (measured on 32 x 7 x 7 x 512 -> 512, W2A4: see the design notes).
+    // times the wavefronts (measured on 32 x 7 x 7 x 512 -> 512, W2A4: 70.7 -> 50.6 us).  Where the
+    // chunks divide evenly among the four wavefronts (512 channels at W2A4: four chunks) it is the
+    // faster variant at any size, since no partial sum passes through the output buffer and every
+    // wavefront loads one chunk of weights (measured, W2A4 512 -> 512: 16 x 14 x 14: 115.6 -> 103.1 us,
+    // 16 x 28 x 28: 414.3 -> 385.6 us); with two chunks half of the wavefronts would idle
+    // (32 x 14 x 14 x 256 -> 256: 59.2 -> 76.7 us), so those keep the plain variant.
     const int64_t plain_waves = ((rows + g.rows_per_wave - 1) / g.rows_per_wave) * g.col_tiles;
     const int knob_split = tuning().split_channels;
-    if (conv_can_split(ab, wb, g.Cw) && tuning().rows_per_wave == 0 && knob_split != 1 &&
-        (plain_waves < 4 * (int64_t)device_simd_count() || knob_split == 2)) {
-        const int chunks = g.Cw / conv_shape(ab, wb, g.Cw).cwt;
+    const int split_chunks = conv_can_split(ab, wb, g.Cw) ? g.Cw / conv_shape(ab, wb, g.Cw).cwt : 0;
+    if (split_chunks != 0 && tuning().rows_per_wave == 0 && knob_split != 1 &&
+        (plain_waves < 4 * (int64_t)device_simd_count() || split_chunks % 4 == 0 || knob_split == 2)) {
+        const int chunks = split_chunks;
         int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, (chunks + 3) / 4, 1);
         if (rpb > kConvSplitRows) rpb = kConvSplitRows;
         g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(rpb, Cout), Cout, e);
