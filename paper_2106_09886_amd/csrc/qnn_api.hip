@@ -314,17 +314,22 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
                                           Cout, e);
     // Few pixels and many channels: fewer than four wavefronts per SIMD would each make several
     // chunk passes.  The variant whose four wavefronts per block split the channel chunks gives four
-    // times the wavefronts (measured on 32 x 7 x 7 x 512 -> 512, W2A4: 70.7 -> 50.6 us).  Where the
-    // chunks divide evenly among the four wavefronts (512 channels at W2A4: four chunks) it is the
-    // faster variant at any size, since no partial sum passes through the output buffer and every
-    // wavefront loads one chunk of weights (measured, W2A4 512 -> 512: 16 x 14 x 14: 115.6 -> 103.1 us,
-    // 16 x 28 x 28: 414.3 -> 385.6 us); with two chunks half of the wavefronts would idle
-    // (32 x 14 x 14 x 256 -> 256: 59.2 -> 76.7 us), so those keep the plain variant.
+    // times the wavefronts (measured on 32 x 7 x 7 x 512 -> 512, W2A4: 70.7 -> 50.6 us).  Its chunks
+    // are a quarter of the plane where nine taps of that fit the weight registers, so they divide
+    // evenly among the four wavefronts, no partial sum passes through the output buffer and every
+    // wavefront loads one chunk of weights: with chunks of at least two words it is the faster
+    // variant at any size (measured, W2A4: 512 -> 512 at 16 x 14 x 14: 115.6 -> 103.1 us, at
+    // 16 x 28 x 28: 414.3 -> 382.1 us; 256 -> 256 at 16 x 56 x 56: 417.3 -> 394.5 us; W3A4
+    // 256 -> 256 at 64 x 14 x 14: 161.4 -> 155.1 us; W4A4 256 -> 256 at 32 x 14 x 14: 145.2 ->
+    // 103.9 us).  One-word chunks (128 channels, W3A4) gain at 56 x 56 (325.8 -> 299.3 us) and lose
+    // at 28 x 28 (87.5 -> 91.7 us): those keep the plain variant unless the pixels are few.
+    // (24 instead of 16 rows per block: equal for W2A4, 6-11 % slower for W3A4.)
     const int64_t plain_waves = ((rows + g.rows_per_wave - 1) / g.rows_per_wave) * g.col_tiles;
     const int knob_split = tuning().split_channels;
-    const int split_chunks = conv_can_split(ab, wb, g.Cw) ? g.Cw / conv_shape(ab, wb, g.Cw).cwt : 0;
+    const int split_words = conv_can_split(ab, wb, g.Cw) ? conv_split_shape(ab, wb, g.Cw).cwt : 0;
+    const int split_chunks = split_words ? g.Cw / split_words : 0;
     if (split_chunks != 0 && tuning().rows_per_wave == 0 && knob_split != 1 &&
-        (plain_waves < 4 * (int64_t)device_simd_count() || split_chunks % 4 == 0 || knob_split == 2)) {
+        (plain_waves < 4 * (int64_t)device_simd_count() || (split_chunks % 4 == 0 && split_words >= 2) || knob_split == 2)) {
         const int chunks = split_chunks;
         int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, (chunks + 3) / 4, 1);
         if (rpb > kConvSplitRows) rpb = kConvSplitRows;

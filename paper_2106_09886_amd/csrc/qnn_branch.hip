@@ -938,17 +938,18 @@ template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
     if constexpr (conv_can_split(AB, WB, CWS)) {
-        if (g.split_k) {           // the block's wavefronts split the channel chunks (few pixels, many channels)
+        if (g.split_k) {           // the block's wavefronts split the channel chunks
+            constexpr int SC = conv_split_shape(AB, WB, CWS).cwt;
             const int64_t row_blocks = ((int64_t)g.rows + g.rows_per_wave - 1) / g.rows_per_wave;
             const dim3 grid((unsigned)(row_blocks * g.col_tiles));
             if (g.rows_per_wave > kSplitRows) return hipErrorInvalidValue;                 // host bug
             const bool emit = g.planes_out != nullptr;
             if (g.geo.sh == 2) {
-                if (emit) launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 2, true>), grid, dim3(256), 0, s, g);
-                else launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 2, true>), grid, dim3(256), 0, s, g);
+                if (emit) launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, true, false, 2, true>), grid, dim3(256), 0, s, g);
+                else launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, false, false, 2, true>), grid, dim3(256), 0, s, g);
             } else {
-                if (emit) launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, true, false, 1, true>), grid, dim3(256), 0, s, g);
-                else launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, S::GT, 1, false, false, 1, true>), grid, dim3(256), 0, s, g);
+                if (emit) launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, true, false, 1, true>), grid, dim3(256), 0, s, g);
+                else launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, false, false, 1, true>), grid, dim3(256), 0, s, g);
             }
             return launch_status();
         }

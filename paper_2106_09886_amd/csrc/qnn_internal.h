@@ -206,12 +206,22 @@ constexpr int conv_group(int ab, int wb, int cw) {
     return conv_has_fixed_shape(ab, wb, cw) ? conv_shape(ab, wb, cw).p : 1;
 }
 
-// Shapes for which the 3x3 kernel also exists in the variant whose four wavefronts per block split
-// the channel chunks (all nine taps per chunk, at least two channel chunks); most rows per block.
-constexpr bool conv_can_split(int ab, int wb, int cw) {
-    return conv_has_fixed_shape(ab, wb, cw) && cw >= 4 && conv_shape(ab, wb, cw).tpc == 9 &&
-           cw / conv_shape(ab, wb, cw).cwt >= 2;
+// Chunk shape of the variant of the 3x3 kernel whose four wavefronts per block split the channel
+// chunks: all nine taps per chunk, and channel words per chunk such that the chunks divide evenly
+// among the four wavefronts (a quarter of the plane, or less if nine taps of that many words do not
+// fit the weight registers).  It exists for the fixed shapes with at least four channel words whose
+// plain kernel makes more than one pass.
+constexpr ConvShapeV conv_split_shape(int ab, int wb, int cws) {
+    int cwt = cws / 4;
+    while (cwt >= 1 && conv_shape_score(ab, wb, cws, cwt, 9) == 0) cwt /= 2;
+    return ConvShapeV{cwt, 9, 1, 1};
 }
+constexpr bool conv_can_split(int ab, int wb, int cw) {
+    return conv_has_fixed_shape(ab, wb, cw) && cw >= 4 && conv_split_shape(ab, wb, cw).cwt >= 1 &&
+           (cw / conv_shape(ab, wb, cw).cwt) * (9 / conv_shape(ab, wb, cw).tpc) >= 2;
+}
+static_assert(conv_split_shape(4, 2, 16).cwt == 4 && conv_split_shape(4, 2, 8).cwt == 2 && conv_split_shape(4, 3, 8).cwt == 2,
+              "512- and 256-channel W2A4 and the ResNet-50 stage-3 shape: four chunks of nine taps");
 constexpr int kConvSplitRows = 16;
 
 // the same for the stride-2 variant of the 3x3 kernel: two output pixels share a stage of five input

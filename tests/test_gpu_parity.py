@@ -296,11 +296,15 @@ def test_conv_any_rows_per_wave(q, oracle, rpw):
 
 @pytest.mark.parametrize("case", [(2, 7, 7, 512, 64, 4, 2), (1, 14, 14, 512, 130, 4, 2), (3, 5, 6, 256, 64, 4, 2),
                                   (2, 9, 4, 128, 70, 2, 2), (1, 3, 20, 512, 64, 2, 1), (2, 6, 6, 256, 64, 3, 3),
-                                  (1, 1, 1, 512, 64, 4, 2), (2, 17, 3, 128, 64, 1, 1)])
+                                  (1, 1, 1, 512, 64, 4, 2), (2, 17, 3, 128, 64, 1, 1),
+                                  # shapes whose plain kernel takes three taps per pass (the ResNet-50
+                                  # stage-3 pair) or two chunks: split into four chunks of nine taps
+                                  (2, 14, 14, 256, 70, 4, 3), (1, 9, 11, 128, 64, 4, 3), (2, 8, 8, 256, 64, 4, 4),
+                                  (1, 10, 10, 512, 64, 4, 5), (2, 7, 9, 256, 130, 8, 6)])
 def test_conv_split_channels(q, oracle, case):
-    """The 3x3 kernel whose four wavefronts per block split the channel chunks (layers with few pixels
-    and many channels), forced on; also rows that are not a multiple of four, one-pixel images and
-    chunk counts of 2, 4 and 8."""
+    """The 3x3 kernel whose four wavefronts per block split the channel chunks, forced on (it is the
+    automatic choice for most layers with 256 and more channels); also rows that are not a multiple
+    of four, one-pixel images, chunks of 1, 2 and 4 words and 4 or 8 chunks."""
     Nb, H, W, C, Cout, ab, wb = case
     say("conv split channels", case)
     rng = np.random.default_rng(sum(case))
