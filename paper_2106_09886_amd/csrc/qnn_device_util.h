@@ -279,7 +279,10 @@ __device__ __forceinline__ void finish_row(const OutViewSlab &v, int rel_row, in
 // as the kernel runs.  With the default policy the results stay dirty in the L2s and are written back
 // when the kernel ends, before the next one may start: on the ResNet-18-shaped layer (51 MB of
 // results per launch) that write-back was 2.4 us of every 30.9 us launch (28.5 us with sc1; the
-// non-temporal bit alone gives 29.2, the workgroup-scope bit nothing).
+// non-temporal bit alone gives 29.2, the workgroup-scope bit nothing).  Only for the branch kernels'
+// row stores (256 contiguous bytes per wavefront): on the re-encoder's 8-byte plane pieces the same
+// bit costs 10-45 % (the L2 no longer merges them into whole lines), and on the pack and pooling
+// kernels' word stores it changed nothing or cost 1 %.
 constexpr int kResultStore = 16;
 template <bool SINGLE, class OV>
 __device__ __forceinline__ void finish_row(const OV &v, int rel_row, int val, bool first, bool last) {

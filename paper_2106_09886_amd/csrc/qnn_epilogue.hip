@@ -12,12 +12,13 @@ __global__ __launch_bounds__(256) void scale_kernel_v4(const int4 *__restrict__ 
          i += (int64_t)gridDim.x * blockDim.x) {
         const int4 a = acc[i];
         const float4 s = scale[i % N4];
-        float4 o;
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 o;
         o.x = (float)a.x * s.x;
         o.y = (float)a.y * s.y;
         o.z = (float)a.z * s.z;
         o.w = (float)a.w * s.w;
-        out[i] = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out + i));   // streamed: nothing reads it back here
     }
 }
 
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(256) void scale_kernel(const int32_t *__restrict__ 
                                                     float *__restrict__ out) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x)
-        out[i] = (float)acc[i] * scale[i % N];
+        __builtin_nontemporal_store((float)acc[i] * scale[i % N], &out[i]);
 }
 
 }  // namespace

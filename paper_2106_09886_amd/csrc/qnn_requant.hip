@@ -317,14 +317,14 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
             const uint32_t uidx = round_odd_index<BITS>(val);
             if constexpr (CODES) {
                 const int code = 2 * (int)uidx - VMAX;
-                if (sizeof(CodeT) == 1) __builtin_amdgcn_raw_buffer_store_b8((char)code, dc, lane, u * 64, kResultStore);
-                else __builtin_amdgcn_raw_buffer_store_b16((short)code, dc, lane * 2, u * 128, kResultStore);
+                if (sizeof(CodeT) == 1) __builtin_amdgcn_raw_buffer_store_b8((char)code, dc, lane, u * 64, 0);
+                else __builtin_amdgcn_raw_buffer_store_b16((short)code, dc, lane * 2, u * 128, 0);
             }
             if constexpr (PLANES && GATHER) PlanesAt<BITS, u>::put(uidx << (32 - BITS), P);
             if constexpr (PLANES && !GATHER) {
                 // lane 2k+h stores half h of plane BITS-1-k (see emit_planes)
                 const int mine = emit_planes<BITS>(uidx << (32 - BITS));
-                if (stores) __builtin_amdgcn_raw_buffer_store_b32(mine, dp, store_off, (int)poff, kResultStore);
+                if (stores) __builtin_amdgcn_raw_buffer_store_b32(mine, dp, store_off, (int)poff, 0);
                 poff += 8u;                                              // next channel group: two words on
                 if (++cgi == cgroups) {                                  // next pixel
                     cgi = 0;
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256) void requant_flat_kernel(const float *__restri
             if (lane_item < n && lane < 2 * U) {
 #pragma unroll
                 for (int k = 0; k < BITS; ++k)
-                    __builtin_amdgcn_raw_buffer_store_b32(P[k], dp, lane_off, (int)((uint32_t)(BITS - 1 - k) * plane_bytes), kResultStore);
+                    __builtin_amdgcn_raw_buffer_store_b32(P[k], dp, lane_off, (int)((uint32_t)(BITS - 1 - k) * plane_bytes), 0);
             }
         }
     }
