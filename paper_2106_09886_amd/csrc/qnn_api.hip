@@ -284,10 +284,11 @@ qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout
     return QNN_OK;
 }
 
-// stride: 1, or 2 where the 3x3 kernel has a fixed-shape instantiation (conv_has_fixed_shape)
+// stride: 1, or 2 where the 3x3 kernel has a fixed-shape instantiation (conv_has_fixed_shape).
+// dilation (= padding): above 1 only at stride 1 and for the shapes conv_can_dilate() names.
 qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
                            int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
-                           float *out_f32, const Emit &e, void *stream, int stride = 1) {
+                           float *out_f32, const Emit &e, void *stream, int stride = 1, int dilation = 1) {
     qnn_status st = check_image(Nb, H, W, C, Cout);
     if (st != QNN_OK) return st;
     const int64_t Ho = (H > 0) ? (H - 1) / stride + 1 : 0, Wo = (W > 0) ? (W - 1) / stride + 1 : 0;
@@ -307,7 +308,8 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0;
     g.xcd_ranges = (stride == 1) ? xcd_ranges_for(g.col_tiles >= 4) : 0;        // the strided variant keeps plain numbers
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
-    g.geo.KH = 3; g.geo.KW = 3; g.geo.sh = stride; g.geo.sw = stride; g.geo.ph = 1; g.geo.pw = 1; g.geo.dh = 1; g.geo.dw = 1;
+    g.geo.KH = 3; g.geo.KW = 3; g.geo.sh = stride; g.geo.sw = stride; g.geo.ph = dilation; g.geo.pw = dilation;
+    g.geo.dh = dilation; g.geo.dw = dilation;
     g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = 0;
     const int group = (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
     g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, conv_passes(ab, wb, g.Cw), group), Cout),
@@ -776,6 +778,13 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     if (!q->transposed && q->kh == 3 && q->kw == 3 && (s1 || s2) && q->pad_h == 1 &&
         q->pad_w == 1 && q->dil_h == 1 && q->dil_w == 1 && cw > 0 && !tuning().general_only)
         return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, s1 ? 1 : 2);
+    // The atrous 3x3 convolution ("same" padding = dilation, stride 1) runs on that kernel too where
+    // its shape takes one tap per pipeline stage (128 channels and more): only tap offsets and border
+    // tests depend on the dilation there.
+    if (!q->transposed && q->kh == 3 && q->kw == 3 && s1 && q->dil_h == q->dil_w && q->dil_h > 1 &&
+        q->pad_h == q->dil_h && q->pad_w == q->dil_w && conv_can_dilate(ab, wb, (int)cw) && W > q->dil_w &&
+        !tuning().general_only)
+        return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, 1, q->dil_h);
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the
     // wavefront's weight words, which has to be spread over enough pixels (measured optimum 14-16
     // on layers of 25 k to 100 k pixels)

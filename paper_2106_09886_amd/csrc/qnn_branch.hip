@@ -436,12 +436,14 @@ struct ConvCtx {
         return (TPC == 1) ? tap_dw(t0) : (ST * GT + i) % 3 - 1;
     }
 
-    __device__ __forceinline__ void set_image_row(int oh, int H, int W) {
+    // D: dilation (taps D pixels apart in both directions; D > 1 only with one tap per stage, where
+    // nothing but these offsets and the border tests depends on it)
+    __device__ __forceinline__ void set_image_row(int oh, int H, int W, int D) {
         stage_ok = 0u;
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
-            const int dh = (TPC == 9) ? first_tap(st) / 3 - 1 : tap_dh(t0 + st * GT);
-            const int dw = (TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1;
+            const int dh = ((TPC == 9) ? first_tap(st) / 3 - 1 : tap_dh(t0 + st * GT)) * D;
+            const int dw = ((TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1) * D;
             const bool ok = (unsigned)(S * oh + dh) < (unsigned)H;
             if (ok) stage_ok |= 1u << st;
             stage_off[st] = (uint32_t)((ok ? dh * W : 0) + dw) * pixel_bytes();
@@ -523,9 +525,9 @@ __device__ __forceinline__ PixelPos pixel_pos(int r, const BranchArgs &g) {     
 
 // number of taps of the 3x3 window of an output pixel that fall inside the image
 template <int S>
-__device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
-    const int nh = 3 - (S * p.oh == 0 ? 1 : 0) - (S * p.oh + 1 >= H ? 1 : 0);
-    const int nw = 3 - (S * p.ow == 0 ? 1 : 0) - (S * p.ow + 1 >= W ? 1 : 0);
+__device__ __forceinline__ int valid_taps(PixelPos p, int H, int W, int D = 1) {
+    const int nh = 3 - (S * p.oh < D ? 1 : 0) - (S * p.oh + D >= H ? 1 : 0);
+    const int nw = 3 - (S * p.ow < D ? 1 : 0) - (S * p.ow + D >= W ? 1 : 0);
     return nh * nw;
 }
 
@@ -540,11 +542,11 @@ template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c,
                                                    const BranchArgs &g, const OV &ov, int r0, int ra,
                                                    int rb, int oh, int in_a, uint32_t left_first, uint32_t right_last,
-                                                   bool first, bool last) {
+                                                   bool first, bool last, int D = 1) {
     constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
     static_assert(P == 1 || SINGLE, "pixel groups only where a chunk pass is the whole product");
-    c.set_image_row(oh, g.H, g.W);
-    const int krow = (3 - (S * oh == 0 ? 1 : 0) - (S * oh + 1 >= g.H ? 1 : 0)) * g.kconst;   // per valid column
+    c.set_image_row(oh, g.H, g.W, D);
+    const int krow = (3 - (S * oh < D ? 1 : 0) - (S * oh + D >= g.H ? 1 : 0)) * g.kconst;   // per valid column
     const uint32_t pb = c.pixel_bytes();
     const uint32_t edge_first = left_first, edge_last = right_last;
     const uint32_t off_a = (uint32_t)in_a * pb + (uint32_t)c.c0 * 4u;
@@ -606,13 +608,13 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
 __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c, uniform_words As,
                                                  const BranchArgs &g, const OV &ov, int r0, int r,
-                                                 PixelPos pos, bool first, bool last) {
+                                                 PixelPos pos, bool first, bool last, int D = 1) {
 #pragma unroll
     for (int s = 0; s < AB + WB - 1; ++s) c.part[0][s] = 0;
 #pragma unroll
     for (int t = 0; t < TPC; ++t) {
-        const int dh = (TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t);
-        const int dw = (TPC == 1) ? tap_dw(c.t0) : t % 3 - 1;
+        const int dh = ((TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t)) * D;
+        const int dw = ((TPC == 1) ? tap_dw(c.t0) : t % 3 - 1) * D;
         const int ih = S * pos.oh + dh, iw = S * pos.ow + dw;
         const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
         if (ok) {
@@ -631,7 +633,7 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
         }
     }
     int val = -2 * weighted_sum(c.part[0]);
-    if (first && adds_const(ov)) val += valid_taps<S>(pos, g.H, g.W) * g.kconst;
+    if (first && adds_const(ov)) val += valid_taps<S>(pos, g.H, g.W, D) * g.kconst;
     finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
 }
 
@@ -680,23 +682,41 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     // the right-hand tap of the last output column is outside the image exactly in that case
     const bool right_edge = ((g.W - 1) % S == 0);
     PixelPos pos = pixel_pos(r0, g);
+    // Dilation (shapes with one tap per stage at stride 1; the host sends no other here): the taps of
+    // a kernel row are D pixels apart, so the D first and D last pixels of an image row miss a tap.
+    // Each of them is a run of its own with its edge flag, the pixels between them one run without.
+    // The untested addresses of a run stay inside the plane buffer except in the first D columns of
+    // rows 0 and D of the first image and the last D columns of rows H-1 and H-1-D of the last.
+    const int D = (GT == 1 && S == 1 && P == 1) ? g.geo.dh : 1;
+    const int last_img = (D > 1) ? __builtin_amdgcn_readfirstlane(g.rows / (Ho * Wo)) - 1 : 0;
     int r = r0;
     while (r < r1) {
         const int row_end = r - pos.ow + Wo;             // first pixel of the next output row
         int stop = min(r1, row_end);
         bool is_special = false;
+        uint32_t left = spin(pos.ow == 0 ? 1u : 0u), right;
+        if (D > 1) {
+            const bool lb = pos.ow < D, rbord = pos.ow >= g.W - D;
+            if (lb || rbord) stop = r + 1;
+            else stop = min(stop, r - pos.ow + (g.W - D));
+            is_special = (lb && pos.n == 0 && (pos.oh == 0 || pos.oh == D)) ||
+                         (rbord && pos.n == last_img && (pos.oh == g.H - 1 || pos.oh == g.H - 1 - D));
+            left = spin(lb ? 1u : 0u);
+            right = spin(rbord ? 2u : 0u);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (special[i] == r) is_special = true;
-            if (special[i] > r && special[i] < stop) stop = special[i];
+            for (int i = 0; i < 4; ++i) {
+                if (special[i] == r) is_special = true;
+                if (special[i] > r && special[i] < stop) stop = special[i];
+            }
+            right = spin((stop == row_end && right_edge) ? 2u : 0u);
         }
         if (is_special || stop - r < P) {              // end pixels, and runs shorter than a group
-            conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
+            conv_row_checked(c, As, g, ov, r0, r, pos, first, last, D);
             stop = r + 1;
         } else {
             conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, (pos.n * g.H + S * pos.oh) * g.W + S * pos.ow,
-                               spin(pos.ow == 0 ? 1u : 0u), spin((stop == row_end && right_edge) ? 2u : 0u), first,
-                               last);
+                               left, right, first, last, D);
         }
         pos.ow += stop - r;
         r = stop;

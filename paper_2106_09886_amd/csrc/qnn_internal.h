@@ -223,6 +223,11 @@ constexpr bool conv_can_split(int ab, int wb, int cw) {
 static_assert(conv_split_shape(4, 2, 16).cwt == 4 && conv_split_shape(4, 2, 8).cwt == 2 && conv_split_shape(4, 3, 8).cwt == 2,
               "512- and 256-channel W2A4 and the ResNet-50 stage-3 shape: four chunks of nine taps");
 constexpr int kConvSplitRows = 16;
+// Fixed shapes of the 3x3 kernel that also serve a dilated window: one tap per pipeline stage and
+// one pixel per iteration, in the plain variant (the split variant always has that shape).
+constexpr bool conv_can_dilate(int ab, int wb, int cw) {
+    return conv_has_fixed_shape(ab, wb, cw) && conv_shape(ab, wb, cw).gt == 1 && conv_shape(ab, wb, cw).p == 1;
+}
 
 // the same for the stride-2 variant of the 3x3 kernel: two output pixels share a stage of five input
 // pixels where those fit the scalar registers of a stage, else one pixel per iteration

@@ -41,6 +41,9 @@ def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dila
     pair = lambda v: tuple(v) if isinstance(v, (tuple, list)) else (v, v)
     handed_over = (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) in ((1, 1), (2, 2))
                    and pair(pad) == (1, 1) and pair(dilation) == (1, 1))
+    # ... and so does the atrous 3x3 window (padding = dilation, stride 1) from 128 channels on
+    handed_over = handed_over or (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) == (1, 1)
+                                  and pair(pad) == pair(dilation) and pair(dilation)[0] == pair(dilation)[1] > 1)
     for general_only in ((1, 0) if handed_over else (0,)):
         q.tune(general_only=general_only)
         try:
@@ -69,6 +72,17 @@ CASES = [
     dict(Nb=2, H=12, W=12, C=20, Cout=50, ab=4, wb=4, KH=5, KW=5),                          # LeNet conv2
     dict(Nb=1, H=13, W=13, C=96, Cout=33, ab=3, wb=3, KH=3, KW=3, pad=2, dilation=2),       # atrous conv
     dict(Nb=1, H=17, W=15, C=40, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=4, dilation=4),
+    # atrous 3x3 on the 3x3 kernel (one tap per stage: 128 channels and more): interior run and border
+    # pixels, images narrower than two dilations, images of fewer rows than the dilation, several
+    # wavefronts per image, the channel-split shapes (256 and 512 channels), emitted planes
+    dict(Nb=2, H=9, W=11, C=128, Cout=70, ab=2, wb=2, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=2, H=7, W=7, C=256, Cout=64, ab=4, wb=3, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=1, H=5, W=9, C=512, Cout=64, ab=4, wb=2, KH=3, KW=3, pad=4, dilation=4, out_bits=4),
+    dict(Nb=2, H=6, W=5, C=128, Cout=64, ab=4, wb=2, KH=3, KW=3, pad=3, dilation=3),
+    dict(Nb=3, H=2, W=6, C=256, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=2, H=19, W=17, C=128, Cout=130, ab=3, wb=3, KH=3, KW=3, pad=2, dilation=2, out_bits=3),
+    dict(Nb=1, H=3, W=3, C=128, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=1, H=12, W=12, C=192, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=2, dilation=2),
     dict(Nb=1, H=9, W=14, C=64, Cout=64, ab=2, wb=1, KH=3, KW=1, stride=(1, 2), pad=(1, 0)),
     dict(Nb=2, H=8, W=10, C=100, Cout=130, ab=1, wb=1, KH=2, KW=4, stride=(2, 1), pad=(0, 2), dilation=(1, 2)),
     dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=6, wb=2, KH=3, KW=3, pad=1),                     # wide activations
