@@ -285,15 +285,17 @@ qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout
 }
 
 // stride: 1, or 2 where the 3x3 kernel has a fixed-shape instantiation (conv_has_fixed_shape).
-// dilation (= padding): above 1 only at stride 1 and for the shapes conv_can_dilate() names.
+// Other windows than 3x3 / dilation 1 (odd kh x kw, taps `dilation` pixels apart, "same" padding
+// (k/2)*dilation): only at stride 1 and for the shapes conv_can_dilate() names.
 qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
                            int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
-                           float *out_f32, const Emit &e, void *stream, int stride = 1, int dilation = 1) {
+                           float *out_f32, const Emit &e, void *stream, int stride = 1, int dilation = 1,
+                           int kh = 3, int kw = 3) {
     qnn_status st = check_image(Nb, H, W, C, Cout);
     if (st != QNN_OK) return st;
     const int64_t Ho = (H > 0) ? (H - 1) / stride + 1 : 0, Wo = (W > 0) ? (W - 1) / stride + 1 : 0;
     const int64_t rows = Nb * Ho * Wo;
-    st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, 9, acc, scale, out_f32, e);
+    st = check_branch(x_planes, ab, Wt, wb, rows, Cout, C, kh * kw, acc, scale, out_f32, e);
     if (st != QNN_OK || rows == 0 || Cout == 0) return st;
     const int64_t cw = (C + 31) / 32;
     if (cw > 0 && Nb * H * W > ((((int64_t)1 << 30) - 1) / (ab * cw))) return QNN_EUNSUPPORTED;      // input planes
@@ -308,11 +310,13 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.split_k = 0; g.gather_rows = 0; g.lds_partials = 0;
     g.xcd_ranges = (stride == 1) ? xcd_ranges_for(g.col_tiles >= 4) : 0;        // the strided variant keeps plain numbers
     g.trace = tuning().trace; g.trace_waves = tuning().trace_waves;
-    g.geo.KH = 3; g.geo.KW = 3; g.geo.sh = stride; g.geo.sw = stride; g.geo.ph = dilation; g.geo.pw = dilation;
-    g.geo.dh = dilation; g.geo.dw = dilation;
+    g.geo.KH = kh; g.geo.KW = kw; g.geo.sh = stride; g.geo.sw = stride;
+    g.geo.ph = (kh / 2) * dilation; g.geo.pw = (kw / 2) * dilation; g.geo.dh = dilation; g.geo.dw = dilation;
     g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = 0;
     const int group = (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
-    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, conv_passes(ab, wb, g.Cw), group), Cout),
+    // chunk passes per pixel: for a window of more than nine taps, so many times more tap chunks
+    const int tap_factor = (kh * kw + 8) / 9;
+    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, conv_passes(ab, wb, g.Cw) * tap_factor, group), Cout),
                                           Cout, e);
     // Few pixels and many channels: fewer than four wavefronts per SIMD would each make several
     // chunk passes.  The variant whose four wavefronts per block split the channel chunks gives four
@@ -333,7 +337,7 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     if (split_chunks != 0 && tuning().rows_per_wave == 0 && knob_split != 1 &&
         (plain_waves < 4 * (int64_t)device_simd_count() || (split_chunks % 4 == 0 && split_words >= 2) || knob_split == 2)) {
         const int chunks = split_chunks;
-        int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, (chunks + 3) / 4, 1);
+        int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, ((chunks + 3) / 4) * tap_factor, 1);
         if (rpb > kConvSplitRows) rpb = kConvSplitRows;
         g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(rpb, Cout), Cout, e);
         g.split_k = 1;
@@ -778,13 +782,14 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     if (!q->transposed && q->kh == 3 && q->kw == 3 && (s1 || s2) && q->pad_h == 1 &&
         q->pad_w == 1 && q->dil_h == 1 && q->dil_w == 1 && cw > 0 && !tuning().general_only)
         return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, s1 ? 1 : 2);
-    // The atrous 3x3 convolution ("same" padding = dilation, stride 1) runs on that kernel too where
-    // its shape takes one tap per pipeline stage (128 channels and more): only tap offsets and border
-    // tests depend on the dilation there.
-    if (!q->transposed && q->kh == 3 && q->kw == 3 && s1 && q->dil_h == q->dil_w && q->dil_h > 1 &&
-        q->pad_h == q->dil_h && q->pad_w == q->dil_w && conv_can_dilate(ab, wb, (int)cw) && W > q->dil_w &&
-        !tuning().general_only)
-        return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, 1, q->dil_h);
+    // Other odd windows with "same" padding at stride 1 -- the atrous 3x3 convolution, 5x5, 7x7, 1x3 ...
+    // -- run on that kernel too where its shape takes one tap per pipeline stage (128 channels and
+    // more): only the tap offsets, their number and the border tests depend on the window there.
+    if (!q->transposed && s1 && (q->kh & 1) && (q->kw & 1) && q->kh * q->kw > 1 && q->kh * q->kw <= 49 &&
+        q->dil_h == q->dil_w && q->dil_h >= 1 && q->dil_h <= 64 && q->pad_h == (q->kh / 2) * q->dil_h &&
+        q->pad_w == (q->kw / 2) * q->dil_w && conv_can_dilate(ab, wb, (int)cw) && !tuning().general_only)
+        return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, 1, q->dil_h,
+                               q->kh, q->kw);
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the
     // wavefront's weight words, which has to be spread over enough pixels (measured optimum 14-16
     // on layers of 25 k to 100 k pixels)

@@ -451,6 +451,30 @@ struct ConvCtx {
         stage_ok = spin(stage_ok);
     }
 
+    // Any odd KH x KW window with "same" padding and dilation D (shapes with one tap per stage): stage
+    // st holds tap t0 + st of the KH*KW, decoded on the scalar unit.  A tap is used if it exists
+    // (t < KH*KW), its image row exists, and -- for a border pixel, which is a run of its own and
+    // passes its column ow; an interior run passes -1 -- its column exists.  A tap that is not used
+    // points at the pixel itself, so every address of the run is inside the image.
+    // Returns the number of taps used.
+    __device__ __forceinline__ int set_window_taps(int oh, int ow, int H, int W, int KH, int KW, int D) {
+        stage_ok = 0u;
+        int used = 0;
+        const int T = KH * KW;
+        const int recip = (65536 + KW - 1) / KW;            // t / KW == (t * recip) >> 16 for the few taps there are
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            const int t = t0 + st;
+            const int kh = (t * recip) >> 16, kw = t - kh * KW;
+            const int dh = (kh - (KH >> 1)) * D, dw = (kw - (KW >> 1)) * D;
+            const bool ok = t < T && (unsigned)(oh + dh) < (unsigned)H && (ow < 0 || (unsigned)(ow + dw) < (unsigned)W);
+            if (ok) { stage_ok |= 1u << st; ++used; }
+            stage_off[st] = ok ? (uint32_t)(dh * W + dw) * pixel_bytes() : 0u;
+        }
+        stage_ok = spin(stage_ok);
+        return used;
+    }
+
     template <int ST>
     __device__ __forceinline__ void request(Buf &b, bool next_row) {
         const uint32_t off = (next_row ? off_nxt : off_cur) + stage_off[ST];
@@ -542,11 +566,22 @@ template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c,
                                                    const BranchArgs &g, const OV &ov, int r0, int ra,
                                                    int rb, int oh, int in_a, uint32_t left_first, uint32_t right_last,
-                                                   bool first, bool last, int D = 1) {
+                                                   bool first, bool last, int D = 1, bool wide = false, int wide_ow = -1) {
     constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
     static_assert(P == 1 || SINGLE, "pixel groups only where a chunk pass is the whole product");
-    c.set_image_row(oh, g.H, g.W, D);
-    const int krow = (3 - (S * oh < D ? 1 : 0) - (S * oh + D >= g.H ? 1 : 0)) * g.kconst;   // per valid column
+    // a window of more than TPC taps is taken in several tap chunks even where the chunk is the whole plane
+    const bool single = SINGLE && !(wide && g.geo.KH * g.geo.KW > TPC);
+    int krow, wide_add = 0;                          // constant term: per valid column / for the whole pixel
+    if (wide) {
+        // the constant of a tap covers all its channels: counted with the first channel chunk, for the
+        // taps of this tap chunk
+        const int used = c.set_window_taps(oh, wide_ow, g.H, g.W, g.geo.KH, g.geo.KW, D);
+        wide_add = (c.c0 == 0) ? used * g.kconst : 0;
+        krow = 0;
+    } else {
+        c.set_image_row(oh, g.H, g.W, D);
+        krow = (3 - (S * oh < D ? 1 : 0) - (S * oh + D >= g.H ? 1 : 0)) * g.kconst;
+    }
     const uint32_t pb = c.pixel_bytes();
     const uint32_t edge_first = left_first, edge_last = right_last;
     const uint32_t off_a = (uint32_t)in_a * pb + (uint32_t)c.c0 * 4u;
@@ -573,7 +608,7 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
         c.edge = edge = spin(edge);
         // what earlier chunk passes left for this pixel, asked for before its products are formed
         int prev = 0;
-        if constexpr (!SINGLE) {
+        if (!single) {
             if (!first) prev = partial_load(ov, r - r0);
         }
         run_stages<0, FLIP>(c);
@@ -583,8 +618,9 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
             int ncols = 3;
             if (x == 0) ncols -= (int)(edge & 1u);
             if (x == P - 1) ncols -= (int)(edge >> 1);
-            if (first && adds_const(ov)) val += ncols * krow;
-            finish_row<SINGLE>(ov, r - r0 + x, val, /*first=*/true, last);   // earlier part already added
+            if (adds_const(ov)) val += (first ? ncols * krow : 0) + wide_add;
+            if (single) finish_row<true>(ov, r - r0 + x, val, true, true);
+            else finish_row<false>(ov, r - r0 + x, val, /*first=*/true, last);   // earlier part already added
         }
         c.off_cur = c.off_nxt;
         r = rn;
@@ -651,7 +687,16 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     {
         constexpr int NW = TPC * WB * CWT;            // word k = (t * WB + q) * CWT + j
         uint32_t wl[NW];
-        if constexpr (CWS > 0 && CWT == CWS) {        // the chunk takes every channel word: one contiguous run
+        constexpr bool CAN_WIDE = (GT == 1 && S == 1 && P == 1);
+        const int T = CAN_WIDE ? g.geo.KH * g.geo.KW : 9;          // taps of the window (9 unless the host says otherwise)
+        if (CAN_WIDE && T != 9) {
+            // a window of T taps: the last tap chunk may run past them; such a slot repeats tap T-1 and is never used
+#pragma unroll
+            for (int k = 0; k < TPC * WB; ++k) {
+                const int t = min(t0 + k / WB, T - 1);
+                load_run<CWT>(g.Wt + ((nload * T + t) * WB + k % WB) * ps + c0, wl + k * CWT);
+            }
+        } else if constexpr (CWS > 0 && CWT == CWS) {        // the chunk takes every channel word: one contiguous run
             load_run<NW>(g.Wt + (nload * 9 + t0) * WB * CWS, wl);
         } else {
 #pragma unroll
@@ -682,27 +727,31 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     // the right-hand tap of the last output column is outside the image exactly in that case
     const bool right_edge = ((g.W - 1) % S == 0);
     PixelPos pos = pixel_pos(r0, g);
-    // Dilation (shapes with one tap per stage at stride 1; the host sends no other here): the taps of
-    // a kernel row are D pixels apart, so the D first and D last pixels of an image row miss a tap.
-    // Each of them is a run of its own with its edge flag, the pixels between them one run without.
-    // The untested addresses of a run stay inside the plane buffer except in the first D columns of
-    // rows 0 and D of the first image and the last D columns of rows H-1 and H-1-D of the last.
-    const int D = (GT == 1 && S == 1 && P == 1) ? g.geo.dh : 1;
-    const int last_img = (D > 1) ? __builtin_amdgcn_readfirstlane(g.rows / (Ho * Wo)) - 1 : 0;
+    // Other windows than the plain 3x3 (shapes with one tap per stage at stride 1; the host sends no other
+    // here): any odd KH x KW with "same" padding, taps D pixels apart.  The first and last (KW/2)*D pixels
+    // of an image row miss taps: each of them is a run of its own with exactly its taps
+    // (set_window_taps), the pixels between them one run with all columns.  No address of such a run
+    // leaves the image, so there are no end pixels to test.
+    constexpr bool CAN_WIDE = (GT == 1 && S == 1 && P == 1);
+    const int D = CAN_WIDE ? g.geo.dh : 1;
+    const bool wide = CAN_WIDE && (D != 1 || g.geo.KH != 3 || g.geo.KW != 3);
+    const int halfw = wide ? (g.geo.KW >> 1) * D : 0;
     int r = r0;
     while (r < r1) {
         const int row_end = r - pos.ow + Wo;             // first pixel of the next output row
         int stop = min(r1, row_end);
         bool is_special = false;
         uint32_t left = spin(pos.ow == 0 ? 1u : 0u), right;
-        if (D > 1) {
-            const bool lb = pos.ow < D, rbord = pos.ow >= g.W - D;
-            if (lb || rbord) stop = r + 1;
-            else stop = min(stop, r - pos.ow + (g.W - D));
-            is_special = (lb && pos.n == 0 && (pos.oh == 0 || pos.oh == D)) ||
-                         (rbord && pos.n == last_img && (pos.oh == g.H - 1 || pos.oh == g.H - 1 - D));
-            left = spin(lb ? 1u : 0u);
-            right = spin(rbord ? 2u : 0u);
+        int wide_ow = -1;
+        if (wide) {
+            if (pos.ow < halfw || pos.ow >= g.W - halfw) {
+                stop = r + 1;
+                wide_ow = pos.ow;
+            } else {
+                stop = min(stop, r - pos.ow + (g.W - halfw));
+            }
+            left = spin(0u);
+            right = spin(0u);
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -712,11 +761,11 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
             right = spin((stop == row_end && right_edge) ? 2u : 0u);
         }
         if (is_special || stop - r < P) {              // end pixels, and runs shorter than a group
-            conv_row_checked(c, As, g, ov, r0, r, pos, first, last, D);
+            conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
             stop = r + 1;
         } else {
             conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, (pos.n * g.H + S * pos.oh) * g.W + S * pos.ow,
-                               left, right, first, last, D);
+                               left, right, first, last, D, wide, wide_ow);
         }
         pos.ow += stop - r;
         r = stop;
@@ -805,10 +854,13 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
         uniform_words As = as_uniform(g.A);
         const OutViewSlab sv = {slab + v * (kSplitRows * 64) + lane, v == 0};
         bool mine = false;
-        for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT) {
-            conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, sv, As, nload, r0, r1, c0, 0, /*first=*/!mine, /*last=*/false);
-            mine = true;
-        }
+        // (a window of more than nine taps, S == 1 only, takes its taps nine at a time)
+        const int tap_chunks = (S == 1) ? (g.geo.KH * g.geo.KW + 8) / 9 : 1;
+        for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT)
+            for (int tc = 0; tc < tap_chunks; ++tc) {
+                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, sv, As, nload, r0, r1, c0, tc * 9, /*first=*/!mine, /*last=*/false);
+                mine = true;
+            }
         if (!mine)
             for (int r = 0; r < r1 - r0; ++r) sv.slab[r * 64] = 0;
         __syncthreads();
@@ -844,7 +896,8 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
         trace_end(g, wp);
         return;
     }
-    constexpr int TAP_CHUNKS = 9 / TPC;
+    // tap chunks: 9 / TPC for the 3x3 window; shapes with one tap per stage also take other windows
+    const int TAP_CHUNKS = (GT == 1 && S == 1 && P == 1) ? (g.geo.KH * g.geo.KW + TPC - 1) / TPC : 9 / TPC;
     // Very wide activations leave too few SGPRs for the two hand-managed stage buffers next to
     // the runtime-stride address arithmetic; those (rare) shapes use compiler-managed loads.
     constexpr bool PIPELINED = (CWS > 0) || (AB <= 4);

@@ -41,9 +41,11 @@ def run_case(q, oracle, Nb, H, W, C, Cout, ab, wb, KH, KW, stride=1, pad=0, dila
     pair = lambda v: tuple(v) if isinstance(v, (tuple, list)) else (v, v)
     handed_over = (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) in ((1, 1), (2, 2))
                    and pair(pad) == (1, 1) and pair(dilation) == (1, 1))
-    # ... and so does the atrous 3x3 window (padding = dilation, stride 1) from 128 channels on
-    handed_over = handed_over or (not transposed and not dense_rows and (KH, KW) == (3, 3) and pair(stride) == (1, 1)
-                                  and pair(pad) == pair(dilation) and pair(dilation)[0] == pair(dilation)[1] > 1)
+    # ... and so does any odd window with "same" padding at stride 1 (atrous 3x3, 5x5, 1x3 ...) from 128 channels on
+    d2 = pair(dilation)
+    handed_over = handed_over or (not transposed and not dense_rows and KH % 2 == 1 and KW % 2 == 1 and KH * KW > 1
+                                  and pair(stride) == (1, 1) and d2[0] == d2[1]
+                                  and pair(pad) == ((KH // 2) * d2[0], (KW // 2) * d2[1]))
     for general_only in ((1, 0) if handed_over else (0,)):
         q.tune(general_only=general_only)
         try:
@@ -83,6 +85,17 @@ CASES = [
     dict(Nb=2, H=19, W=17, C=128, Cout=130, ab=3, wb=3, KH=3, KW=3, pad=2, dilation=2, out_bits=3),
     dict(Nb=1, H=3, W=3, C=128, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=2, dilation=2),
     dict(Nb=1, H=12, W=12, C=192, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=2, dilation=2),
+    # other odd windows with "same" padding on the 3x3 kernel: 5x5 (three tap chunks, the last of seven
+    # taps), 7x7, 1x3 and 3x1, 5x5 with dilation, 5x3; images smaller than the window; split shapes
+    dict(Nb=2, H=9, W=10, C=128, Cout=70, ab=2, wb=2, KH=5, KW=5, pad=2),
+    dict(Nb=1, H=8, W=8, C=256, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2, out_bits=4),
+    dict(Nb=1, H=9, W=9, C=128, Cout=64, ab=2, wb=2, KH=7, KW=7, pad=3),
+    dict(Nb=2, H=6, W=7, C=256, Cout=64, ab=4, wb=3, KH=1, KW=3, pad=(0, 1)),
+    dict(Nb=2, H=6, W=7, C=512, Cout=64, ab=4, wb=2, KH=3, KW=1, pad=(1, 0)),
+    dict(Nb=1, H=11, W=12, C=128, Cout=64, ab=3, wb=2, KH=5, KW=5, pad=4, dilation=2),
+    dict(Nb=1, H=7, W=9, C=128, Cout=130, ab=2, wb=2, KH=5, KW=3, pad=(2, 1)),
+    dict(Nb=2, H=3, W=2, C=128, Cout=64, ab=2, wb=2, KH=5, KW=5, pad=2),
+    dict(Nb=3, H=17, W=19, C=128, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=1, H=9, W=14, C=64, Cout=64, ab=2, wb=1, KH=3, KW=1, stride=(1, 2), pad=(1, 0)),
     dict(Nb=2, H=8, W=10, C=100, Cout=130, ab=1, wb=1, KH=2, KW=4, stride=(2, 1), pad=(0, 2), dilation=(1, 2)),
     dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=6, wb=2, KH=3, KW=3, pad=1),                     # wide activations
@@ -204,6 +217,7 @@ FULL_SIZE_CASES = [
     dict(Nb=32, H=56, W=56, C=256, Cout=64, ab=2, wb=2, KH=1, KW=1),
     dict(Nb=32, H=56, W=56, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),
     dict(Nb=16, H=33, W=33, C=256, Cout=256, ab=4, wb=3, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=32, H=28, W=28, C=128, Cout=128, ab=4, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=16, H=56, W=56, C=64, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=32, H=28, W=28, C=96, Cout=96, ab=2, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=16, H=28, W=28, C=256, Cout=128, ab=2, wb=2, KH=4, KW=4, stride=2, pad=1, transposed=True),
