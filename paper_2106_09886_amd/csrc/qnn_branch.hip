@@ -436,14 +436,12 @@ struct ConvCtx {
         return (TPC == 1) ? tap_dw(t0) : (ST * GT + i) % 3 - 1;
     }
 
-    // D: dilation (taps D pixels apart in both directions; D > 1 only with one tap per stage, where
-    // nothing but these offsets and the border tests depends on it)
-    __device__ __forceinline__ void set_image_row(int oh, int H, int W, int D) {
+    __device__ __forceinline__ void set_image_row(int oh, int H, int W) {
         stage_ok = 0u;
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
-            const int dh = ((TPC == 9) ? first_tap(st) / 3 - 1 : tap_dh(t0 + st * GT)) * D;
-            const int dw = ((TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1) * D;
+            const int dh = (TPC == 9) ? first_tap(st) / 3 - 1 : tap_dh(t0 + st * GT);
+            const int dw = (TPC == 1) ? tap_dw(t0) : (st * GT) % 3 - 1;
             const bool ok = (unsigned)(S * oh + dh) < (unsigned)H;
             if (ok) stage_ok |= 1u << st;
             stage_off[st] = (uint32_t)((ok ? dh * W : 0) + dw) * pixel_bytes();
@@ -549,9 +547,9 @@ __device__ __forceinline__ PixelPos pixel_pos(int r, const BranchArgs &g) {     
 
 // number of taps of the 3x3 window of an output pixel that fall inside the image
 template <int S>
-__device__ __forceinline__ int valid_taps(PixelPos p, int H, int W, int D = 1) {
-    const int nh = 3 - (S * p.oh < D ? 1 : 0) - (S * p.oh + D >= H ? 1 : 0);
-    const int nw = 3 - (S * p.ow < D ? 1 : 0) - (S * p.ow + D >= W ? 1 : 0);
+__device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
+    const int nh = 3 - (S * p.oh == 0 ? 1 : 0) - (S * p.oh + 1 >= H ? 1 : 0);
+    const int nw = 3 - (S * p.ow == 0 ? 1 : 0) - (S * p.ow + 1 >= W ? 1 : 0);
     return nh * nw;
 }
 
@@ -562,25 +560,26 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W, int D = 1) {
 // pixels of the group before it (P > 1 is used for single-chunk shapes only, where a
 // recomputed pixel is simply stored again with the same value).
 // in_a: number of the input pixel under output pixel ra, (n*H + S*oh)*W + S*ow.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
+// WIDE: another window than the plain 3x3 (see set_window_taps); wide_ow: the pixel's column if the
+// run is a border pixel, else -1.
+template <bool WIDE = false, int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c,
                                                    const BranchArgs &g, const OV &ov, int r0, int ra,
                                                    int rb, int oh, int in_a, uint32_t left_first, uint32_t right_last,
-                                                   bool first, bool last, int D = 1, bool wide = false, int wide_ow = -1) {
-    constexpr bool SINGLE = (TPC == 9 && CWS > 0 && CWT == CWS);
-    static_assert(P == 1 || SINGLE, "pixel groups only where a chunk pass is the whole product");
+                                                   bool first, bool last, int wide_ow = -1) {
+    constexpr bool SINGLE_SHAPE = (TPC == 9 && CWS > 0 && CWT == CWS);
+    static_assert(P == 1 || SINGLE_SHAPE, "pixel groups only where a chunk pass is the whole product");
     // a window of more than TPC taps is taken in several tap chunks even where the chunk is the whole plane
-    const bool single = SINGLE && !(wide && g.geo.KH * g.geo.KW > TPC);
-    int krow, wide_add = 0;                          // constant term: per valid column / for the whole pixel
-    if (wide) {
+    const bool single = SINGLE_SHAPE && !(WIDE && g.geo.KH * g.geo.KW > TPC);
+    int krow = 0, wide_add = 0;                      // constant term: per valid column / for the whole pixel
+    if constexpr (WIDE) {
         // the constant of a tap covers all its channels: counted with the first channel chunk, for the
         // taps of this tap chunk
-        const int used = c.set_window_taps(oh, wide_ow, g.H, g.W, g.geo.KH, g.geo.KW, D);
+        const int used = c.set_window_taps(oh, wide_ow, g.H, g.W, g.geo.KH, g.geo.KW, g.geo.dh);
         wide_add = (c.c0 == 0) ? used * g.kconst : 0;
-        krow = 0;
     } else {
-        c.set_image_row(oh, g.H, g.W, D);
-        krow = (3 - (S * oh < D ? 1 : 0) - (S * oh + D >= g.H ? 1 : 0)) * g.kconst;
+        c.set_image_row(oh, g.H, g.W);
+        krow = (3 - (S * oh == 0 ? 1 : 0) - (S * oh + 1 >= g.H ? 1 : 0)) * g.kconst;   // per valid column
     }
     const uint32_t pb = c.pixel_bytes();
     const uint32_t edge_first = left_first, edge_last = right_last;
@@ -618,9 +617,14 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
             int ncols = 3;
             if (x == 0) ncols -= (int)(edge & 1u);
             if (x == P - 1) ncols -= (int)(edge >> 1);
-            if (adds_const(ov)) val += (first ? ncols * krow : 0) + wide_add;
-            if (single) finish_row<true>(ov, r - r0 + x, val, true, true);
-            else finish_row<false>(ov, r - r0 + x, val, /*first=*/true, last);   // earlier part already added
+            if constexpr (WIDE) {
+                if (adds_const(ov)) val += wide_add;
+                if (single) finish_row<true>(ov, r - r0 + x, val, true, true);
+                else finish_row<false>(ov, r - r0 + x, val, /*first=*/true, last);
+            } else {
+                if (first && adds_const(ov)) val += ncols * krow;
+                finish_row<SINGLE_SHAPE>(ov, r - r0 + x, val, /*first=*/true, last);   // earlier part already added
+            }
         }
         c.off_cur = c.off_nxt;
         r = rn;
@@ -644,13 +648,13 @@ __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
 __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c, uniform_words As,
                                                  const BranchArgs &g, const OV &ov, int r0, int r,
-                                                 PixelPos pos, bool first, bool last, int D = 1) {
+                                                 PixelPos pos, bool first, bool last) {
 #pragma unroll
     for (int s = 0; s < AB + WB - 1; ++s) c.part[0][s] = 0;
 #pragma unroll
     for (int t = 0; t < TPC; ++t) {
-        const int dh = ((TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t)) * D;
-        const int dw = ((TPC == 1) ? tap_dw(c.t0) : t % 3 - 1) * D;
+        const int dh = (TPC == 9) ? t / 3 - 1 : tap_dh(c.t0 + t);
+        const int dw = (TPC == 1) ? tap_dw(c.t0) : t % 3 - 1;
         const int ih = S * pos.oh + dh, iw = S * pos.ow + dw;
         const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
         if (ok) {
@@ -669,17 +673,18 @@ __device__ __forceinline__ void conv_row_checked(ConvCtx<AB, WB, CWS, CWT, TPC, 
         }
     }
     int val = -2 * weighted_sum(c.part[0]);
-    if (first && adds_const(ov)) val += valid_taps<S>(pos, g.H, g.W, D) * g.kconst;
+    if (first && adds_const(ov)) val += valid_taps<S>(pos, g.H, g.W) * g.kconst;
     finish_row<(TPC == 9 && CWS > 0 && CWT == CWS)>(ov, r - r0, val, first, last);
 }
 
 // full chunk: every word c0 .. c0+CWT-1 exists.  The wavefront's pixel range is cut into
 // runs inside one image row; the four pixels whose untested neighbour addresses could leave
 // the buffer (0, W, rows-1-W, rows-1) go through the tested path.
-template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
+template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, bool WIDE = false, class OV>
 __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &ov, uniform_words As,
                                                 int nload, int r0, int r1, int c0, int t0, bool first,
                                                 bool last) {
+    static_assert(!WIDE || (GT == 1 && S == 1 && P == 1), "other windows: one tap per stage, stride 1");
     static_assert(TPC % GT == 0 && ((TPC / GT) & 1) == 1, "odd number of stages per pixel");
     ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> c;
     c.base = (uint64_t)g.A; c.Cw = g.Cw; c.c0 = c0; c.t0 = t0;
@@ -687,10 +692,9 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     {
         constexpr int NW = TPC * WB * CWT;            // word k = (t * WB + q) * CWT + j
         uint32_t wl[NW];
-        constexpr bool CAN_WIDE = (GT == 1 && S == 1 && P == 1);
-        const int T = CAN_WIDE ? g.geo.KH * g.geo.KW : 9;          // taps of the window (9 unless the host says otherwise)
-        if (CAN_WIDE && T != 9) {
+        if constexpr (WIDE) {
             // a window of T taps: the last tap chunk may run past them; such a slot repeats tap T-1 and is never used
+            const int T = g.geo.KH * g.geo.KW;
 #pragma unroll
             for (int k = 0; k < TPC * WB; ++k) {
                 const int t = min(t0 + k / WB, T - 1);
@@ -716,6 +720,34 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     // output column when (W - 1) is a multiple of the stride, in the output rows with
     // |S*oh - (H - 1)| <= 1 (the last one or two).
     const int Ho = g.geo.Ho, Wo = g.geo.Wo;
+    if constexpr (WIDE) {
+        // The first and last (KW/2)*D pixels of an image row miss taps: each of them is a run of its own
+        // with exactly its taps, the pixels between them one run with all columns.  No address of such a
+        // run leaves the image, so there are no end pixels to test.
+        const int halfw = (g.geo.KW >> 1) * g.geo.dh;
+        PixelPos pos = pixel_pos(r0, g);
+        int r = r0;
+        while (r < r1) {
+            const int row_end = r - pos.ow + Wo;
+            int stop = min(r1, row_end);
+            int wide_ow = -1;
+            if (pos.ow < halfw || pos.ow >= g.W - halfw) {
+                stop = r + 1;
+                wide_ow = pos.ow;
+            } else {
+                stop = min(stop, r - pos.ow + (g.W - halfw));
+            }
+            conv_run_pipelined<true>(c, g, ov, r0, r, stop, pos.oh, (pos.n * g.H + pos.oh) * g.W + pos.ow, spin(0u), spin(0u),
+                                     first, last, wide_ow);
+            pos.ow += stop - r;
+            r = stop;
+            if (pos.ow == Wo) {
+                pos.ow = 0;
+                if (++pos.oh == Ho) { pos.oh = 0; ++pos.n; }
+            }
+        }
+        return;
+    }
     int special[4] = {0, (S == 1) ? Wo : -1, -1, -1};
     if ((g.W - 1) % S == 0) {
 #pragma unroll
@@ -727,45 +759,23 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     // the right-hand tap of the last output column is outside the image exactly in that case
     const bool right_edge = ((g.W - 1) % S == 0);
     PixelPos pos = pixel_pos(r0, g);
-    // Other windows than the plain 3x3 (shapes with one tap per stage at stride 1; the host sends no other
-    // here): any odd KH x KW with "same" padding, taps D pixels apart.  The first and last (KW/2)*D pixels
-    // of an image row miss taps: each of them is a run of its own with exactly its taps
-    // (set_window_taps), the pixels between them one run with all columns.  No address of such a run
-    // leaves the image, so there are no end pixels to test.
-    constexpr bool CAN_WIDE = (GT == 1 && S == 1 && P == 1);
-    const int D = CAN_WIDE ? g.geo.dh : 1;
-    const bool wide = CAN_WIDE && (D != 1 || g.geo.KH != 3 || g.geo.KW != 3);
-    const int halfw = wide ? (g.geo.KW >> 1) * D : 0;
     int r = r0;
     while (r < r1) {
         const int row_end = r - pos.ow + Wo;             // first pixel of the next output row
         int stop = min(r1, row_end);
         bool is_special = false;
-        uint32_t left = spin(pos.ow == 0 ? 1u : 0u), right;
-        int wide_ow = -1;
-        if (wide) {
-            if (pos.ow < halfw || pos.ow >= g.W - halfw) {
-                stop = r + 1;
-                wide_ow = pos.ow;
-            } else {
-                stop = min(stop, r - pos.ow + (g.W - halfw));
-            }
-            left = spin(0u);
-            right = spin(0u);
-        } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (special[i] == r) is_special = true;
-                if (special[i] > r && special[i] < stop) stop = special[i];
-            }
-            right = spin((stop == row_end && right_edge) ? 2u : 0u);
+        for (int i = 0; i < 4; ++i) {
+            if (special[i] == r) is_special = true;
+            if (special[i] > r && special[i] < stop) stop = special[i];
         }
         if (is_special || stop - r < P) {              // end pixels, and runs shorter than a group
             conv_row_checked(c, As, g, ov, r0, r, pos, first, last);
             stop = r + 1;
         } else {
             conv_run_pipelined(c, g, ov, r0, r, stop, pos.oh, (pos.n * g.H + S * pos.oh) * g.W + S * pos.ow,
-                               left, right, first, last, D, wide, wide_ow);
+                               spin(pos.ow == 0 ? 1u : 0u), spin((stop == row_end && right_edge) ? 2u : 0u), first,
+                               last);
         }
         pos.ow += stop - r;
         r = stop;
@@ -854,13 +864,23 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
         uniform_words As = as_uniform(g.A);
         const OutViewSlab sv = {slab + v * (kSplitRows * 64) + lane, v == 0};
         bool mine = false;
-        // (a window of more than nine taps, S == 1 only, takes its taps nine at a time)
-        const int tap_chunks = (S == 1) ? (g.geo.KH * g.geo.KW + 8) / 9 : 1;
-        for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT)
-            for (int tc = 0; tc < tap_chunks; ++tc) {
-                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, sv, As, nload, r0, r1, c0, tc * 9, /*first=*/!mine, /*last=*/false);
+        bool wide = false;
+        if constexpr (S == 1) wide = (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1);
+        if (wide) {                // another window (S == 1 only): its taps nine at a time
+            if constexpr (S == 1) {
+                const int tap_chunks = (g.geo.KH * g.geo.KW + 8) / 9;
+                for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT)
+                    for (int tc = 0; tc < tap_chunks; ++tc) {
+                        conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S, true>(g, sv, As, nload, r0, r1, c0, tc * 9, /*first=*/!mine, /*last=*/false);
+                        mine = true;
+                    }
+            }
+        } else {
+            for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT) {
+                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, sv, As, nload, r0, r1, c0, 0, /*first=*/!mine, /*last=*/false);
                 mine = true;
             }
+        }
         if (!mine)
             for (int r = 0; r < r1 - r0; ++r) sv.slab[r * 64] = 0;
         __syncthreads();
@@ -896,11 +916,24 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
         trace_end(g, wp);
         return;
     }
-    // tap chunks: 9 / TPC for the 3x3 window; shapes with one tap per stage also take other windows
-    const int TAP_CHUNKS = (GT == 1 && S == 1 && P == 1) ? (g.geo.KH * g.geo.KW + TPC - 1) / TPC : 9 / TPC;
+    constexpr int TAP_CHUNKS = 9 / TPC;
     // Very wide activations leave too few SGPRs for the two hand-managed stage buffers next to
     // the runtime-stride address arithmetic; those (rare) shapes use compiler-managed loads.
     constexpr bool PIPELINED = (CWS > 0) || (AB <= 4);
+    // Another window than the plain 3x3 (the host sends it only to fixed shapes with one tap per stage):
+    // a copy of the chunk loop of its own, so that the 3x3 loop below carries none of its bookkeeping.
+    if constexpr (CWS > 0 && GT == 1 && S == 1 && P == 1) {
+        if (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1) {
+            const int tap_chunks = (g.geo.KH * g.geo.KW + TPC - 1) / TPC;
+            for (int c0 = 0; c0 < Cw; c0 += CWT)
+                for (int tc = 0; tc < tap_chunks; ++tc)
+                    conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S, true>(g, ov, As, nload, r0, r1, c0, tc * TPC,
+                                                                            c0 == 0 && tc == 0,
+                                                                            c0 + CWT >= Cw && tc == tap_chunks - 1);
+            trace_end(g, wp);
+            return;
+        }
+    }
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
         const bool full = (c0 + CWT <= Cw);
         if constexpr (!PIPELINED) {
