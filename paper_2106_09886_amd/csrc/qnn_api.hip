@@ -286,7 +286,7 @@ qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout
 
 // stride: 1, or 2 where the 3x3 kernel has a fixed-shape instantiation (conv_has_fixed_shape).
 // Other windows than 3x3 / dilation 1 (odd kh x kw, taps `dilation` pixels apart, "same" padding
-// (k/2)*dilation): only at stride 1 and for the shapes conv_can_dilate() names.
+// (k/2)*dilation): only at stride 1 and for the shapes conv_wide_plain_ok() / conv_wide_split_ok() name.
 qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
                            int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
                            float *out_f32, const Emit &e, void *stream, int stride = 1, int dilation = 1,
@@ -334,8 +334,12 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     const int knob_split = tuning().split_channels;
     const int split_words = conv_can_split(ab, wb, g.Cw) ? conv_split_shape(ab, wb, g.Cw).cwt : 0;
     const int split_chunks = split_words ? g.Cw / split_words : 0;
-    if (split_chunks != 0 && tuning().rows_per_wave == 0 && knob_split != 1 &&
-        (plain_waves < 4 * (int64_t)device_simd_count() || (split_chunks % 4 == 0 && split_words >= 2) || knob_split == 2)) {
+    // another window than the plain 3x3 on a shape whose plain variant does not take it: the split variant does
+    const bool wide_needs_split = (kh != 3 || kw != 3 || dilation != 1) && !conv_wide_plain_ok(ab, wb, g.Cw);
+    const bool wide_needs_plain = (kh != 3 || kw != 3 || dilation != 1) && !conv_wide_split_ok(ab, wb, g.Cw);
+    if (split_chunks != 0 && !wide_needs_plain && ((tuning().rows_per_wave == 0 && knob_split != 1 &&
+        (plain_waves < 4 * (int64_t)device_simd_count() || (split_chunks % 4 == 0 && split_words >= 2) || knob_split == 2)) ||
+        wide_needs_split)) {
         const int chunks = split_chunks;
         int rpb = pick_conv_rows_per_wave(rows, Wo, g.col_tiles * 4, ((chunks + 3) / 4) * tap_factor, 1);
         if (rpb > kConvSplitRows) rpb = kConvSplitRows;
@@ -787,7 +791,8 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     // more): only the tap offsets, their number and the border tests depend on the window there.
     if (!q->transposed && s1 && (q->kh & 1) && (q->kw & 1) && q->kh * q->kw > 1 && q->kh * q->kw <= 49 &&
         q->dil_h == q->dil_w && q->dil_h >= 1 && q->dil_h <= 64 && q->pad_h == (q->kh / 2) * q->dil_h &&
-        q->pad_w == (q->kw / 2) * q->dil_w && conv_can_dilate(ab, wb, (int)cw) && !tuning().general_only)
+        q->pad_w == (q->kw / 2) * q->dil_w && !tuning().general_only &&
+        (conv_wide_plain_ok(ab, wb, (int)cw) || (conv_wide_split_ok(ab, wb, (int)cw) && tuning().split_channels != 1)))
         return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, 1, q->dil_h,
                                q->kh, q->kw);
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the

@@ -864,10 +864,11 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
         uniform_words As = as_uniform(g.A);
         const OutViewSlab sv = {slab + v * (kSplitRows * 64) + lane, v == 0};
         bool mine = false;
+        constexpr bool CAN_WIDE = (S == 1) && conv_wide_stage_ok(AB, CWT);
         bool wide = false;
-        if constexpr (S == 1) wide = (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1);
-        if (wide) {                // another window (S == 1 only): its taps nine at a time
-            if constexpr (S == 1) {
+        if constexpr (CAN_WIDE) wide = (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1);
+        if (wide) {                // another window: its taps nine at a time
+            if constexpr (CAN_WIDE) {
                 const int tap_chunks = (g.geo.KH * g.geo.KW + 8) / 9;
                 for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT)
                     for (int tc = 0; tc < tap_chunks; ++tc) {
@@ -922,7 +923,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     constexpr bool PIPELINED = (CWS > 0) || (AB <= 4);
     // Another window than the plain 3x3 (the host sends it only to fixed shapes with one tap per stage):
     // a copy of the chunk loop of its own, so that the 3x3 loop below carries none of its bookkeeping.
-    if constexpr (CWS > 0 && GT == 1 && S == 1 && P == 1) {
+    if constexpr (CWS > 0 && GT == 1 && S == 1 && P == 1 && conv_wide_stage_ok(AB, CWT)) {
         if (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1) {
             const int tap_chunks = (g.geo.KH * g.geo.KW + TPC - 1) / TPC;
             for (int c0 = 0; c0 < Cw; c0 += CWT)

@@ -223,10 +223,19 @@ constexpr bool conv_can_split(int ab, int wb, int cw) {
 static_assert(conv_split_shape(4, 2, 16).cwt == 4 && conv_split_shape(4, 2, 8).cwt == 2 && conv_split_shape(4, 3, 8).cwt == 2,
               "512- and 256-channel W2A4 and the ResNet-50 stage-3 shape: four chunks of nine taps");
 constexpr int kConvSplitRows = 16;
-// Fixed shapes of the 3x3 kernel that also serve a dilated window: one tap per pipeline stage and
-// one pixel per iteration, in the plain variant (the split variant always has that shape).
-constexpr bool conv_can_dilate(int ab, int wb, int cw) {
-    return conv_has_fixed_shape(ab, wb, cw) && conv_shape(ab, wb, cw).gt == 1 && conv_shape(ab, wb, cw).p == 1;
+// Fixed shapes of the 3x3 kernel that also serve other odd windows with "same" padding at stride 1
+// (atrous 3x3, 5x5, 7x7, 1x3 ...): one tap per pipeline stage, one pixel per iteration, and a stage
+// of at most 16 scalar registers -- with 32 the second copy of the chunk loop leaves the compiler
+// too few scalar registers and it spills stage registers whose load is in flight (the static check
+// of the generated code finds exactly those).  Separately for the plain variant and for the one
+// whose four wavefronts per block split the channel chunks; the host takes whichever exists.
+constexpr bool conv_wide_stage_ok(int ab, int cwt) { return ab * cwt <= 16; }
+constexpr bool conv_wide_plain_ok(int ab, int wb, int cw) {
+    return conv_has_fixed_shape(ab, wb, cw) && conv_shape(ab, wb, cw).gt == 1 && conv_shape(ab, wb, cw).p == 1 &&
+           conv_wide_stage_ok(ab, conv_shape(ab, wb, cw).cwt);
+}
+constexpr bool conv_wide_split_ok(int ab, int wb, int cw) {
+    return conv_can_split(ab, wb, cw) && conv_wide_stage_ok(ab, conv_split_shape(ab, wb, cw).cwt);
 }
 
 // the same for the stride-2 variant of the 3x3 kernel: two output pixels share a stage of five input
