@@ -286,7 +286,8 @@ qnn_status check_image(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout
 
 // stride: 1, or 2 where the 3x3 kernel has a fixed-shape instantiation (conv_has_fixed_shape).
 // Other windows than 3x3 / dilation 1 (odd kh x kw, taps `dilation` pixels apart, "same" padding
-// (k/2)*dilation): only at stride 1 and for the shapes conv_wide_plain_ok() / conv_wide_split_ok() name.
+// (k/2)*dilation): only at stride 1 and for the shapes conv_wide_plain_ok() / conv_wide_split_ok() /
+// conv_wide_extra_ok() name.
 qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt, int wb, int64_t Nb, int64_t H,
                            int64_t W, int64_t C, int64_t Cout, int32_t *acc, const float *scale,
                            float *out_f32, const Emit &e, void *stream, int stride = 1, int dilation = 1,
@@ -313,10 +314,15 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.geo.KH = kh; g.geo.KW = kw; g.geo.sh = stride; g.geo.sw = stride;
     g.geo.ph = (kh / 2) * dilation; g.geo.pw = (kw / 2) * dilation; g.geo.dh = dilation; g.geo.dw = dilation;
     g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = 0;
-    const int group = (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
+    const bool other_window = kh != 3 || kw != 3 || dilation != 1;
+    // 64 channels: another window than the plain 3x3 has an instantiation of its own there
+    const bool wide_extra = other_window && conv_wide_extra_ok(ab, wb, g.Cw);
+    if (wide_extra) g.xcd_ranges = 0;
+    const int group = wide_extra ? 1 : (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
     // chunk passes per pixel: for a window of more than nine taps, so many times more tap chunks
     const int tap_factor = (kh * kw + 8) / 9;
-    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, conv_passes(ab, wb, g.Cw) * tap_factor, group), Cout),
+    const int passes = wide_extra ? conv_wide_extra_passes(ab, wb, g.Cw) : conv_passes(ab, wb, g.Cw);
+    g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(pick_conv_rows_per_wave(rows, Wo, g.col_tiles, passes * tap_factor, group), Cout),
                                           Cout, e);
     // Few pixels and many channels: fewer than four wavefronts per SIMD would each make several
     // chunk passes.  The variant whose four wavefronts per block split the channel chunks gives four
@@ -335,8 +341,8 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     const int split_words = conv_can_split(ab, wb, g.Cw) ? conv_split_shape(ab, wb, g.Cw).cwt : 0;
     const int split_chunks = split_words ? g.Cw / split_words : 0;
     // another window than the plain 3x3 on a shape whose plain variant does not take it: the split variant does
-    const bool wide_needs_split = (kh != 3 || kw != 3 || dilation != 1) && !conv_wide_plain_ok(ab, wb, g.Cw);
-    const bool wide_needs_plain = (kh != 3 || kw != 3 || dilation != 1) && !conv_wide_split_ok(ab, wb, g.Cw);
+    const bool wide_needs_split = other_window && !conv_wide_plain_ok(ab, wb, g.Cw) && !wide_extra;
+    const bool wide_needs_plain = other_window && !conv_wide_split_ok(ab, wb, g.Cw);
     if (split_chunks != 0 && !wide_needs_plain && ((tuning().rows_per_wave == 0 && knob_split != 1 &&
         (plain_waves < 4 * (int64_t)device_simd_count() || (split_chunks % 4 == 0 && split_words >= 2) || knob_split == 2)) ||
         wide_needs_split)) {
@@ -792,7 +798,8 @@ qnn_status qnn_conv2d_general(const uint32_t *x_planes, int ab, const uint32_t *
     if (!q->transposed && s1 && (q->kh & 1) && (q->kw & 1) && q->kh * q->kw > 1 && q->kh * q->kw <= 49 &&
         q->dil_h == q->dil_w && q->dil_h >= 1 && q->dil_h <= 64 && q->pad_h == (q->kh / 2) * q->dil_h &&
         q->pad_w == (q->kw / 2) * q->dil_w && !tuning().general_only &&
-        (conv_wide_plain_ok(ab, wb, (int)cw) || (conv_wide_split_ok(ab, wb, (int)cw) && tuning().split_channels != 1)))
+        (conv_wide_plain_ok(ab, wb, (int)cw) || conv_wide_extra_ok(ab, wb, (int)cw) ||
+         (conv_wide_split_ok(ab, wb, (int)cw) && tuning().split_channels != 1)))
         return run_conv_packed(x_planes, ab, Wt, wb, Nb, H, W, C, Cout, acc, scale, out_f32, e, stream, 1, q->dil_h,
                                q->kh, q->kw);
     // about six wavefronts per SIMD, but at least 14 pixels each: every chunk pass reloads the

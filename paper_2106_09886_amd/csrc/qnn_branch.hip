@@ -1062,6 +1062,17 @@ hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
         }
     }
     if (g.split_k) return hipErrorInvalidValue;                                            // host bug
+    if constexpr (conv_wide_extra_ok(AB, WB, CWS)) {
+        if (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1) {   // another window: one tap per stage
+            constexpr int EC = conv_wide_extra_shape(AB, WB, CWS).cwt;
+            if (g.geo.sh != 1 || g.xcd_ranges) return hipErrorInvalidValue;                // host bug
+            if (g.planes_out != nullptr)
+                launch_kernel((conv_kernel<AB, WB, CWS, EC, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+            else
+                launch_kernel((conv_kernel<AB, WB, CWS, EC, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+            return launch_status();
+        }
+    }
     if (g.geo.sh == 2) {           // stride 2: pixel groups of two only where five input pixels fit a stage
         constexpr int P2 = conv_group_strided(AB, WB, CWS);
         if (g.planes_out != nullptr)

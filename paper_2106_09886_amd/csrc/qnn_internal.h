@@ -237,6 +237,19 @@ constexpr bool conv_wide_plain_ok(int ab, int wb, int cw) {
 constexpr bool conv_wide_split_ok(int ab, int wb, int cw) {
     return conv_can_split(ab, wb, cw) && conv_wide_stage_ok(ab, conv_split_shape(ab, wb, cw).cwt);
 }
+// 64 channels: the 3x3 shape there holds several taps or pixels per stage, so other windows get an
+// instantiation of their own with one tap of both channel words per stage (bit widths up to 4 x 4,
+// to bound build time)
+constexpr ConvShapeV conv_wide_extra_shape(int ab, int wb, int cws) {
+    int cwt = cws;
+    while (cwt >= 1 && (!conv_wide_stage_ok(ab, cwt) || conv_shape_score(ab, wb, cws, cwt, 9) == 0)) cwt /= 2;
+    return ConvShapeV{cwt, 9, 1, 1};
+}
+constexpr bool conv_wide_extra_ok(int ab, int wb, int cw) {
+    return cw == 2 && ab <= 4 && wb <= 4 && conv_has_fixed_shape(ab, wb, cw) && !conv_wide_plain_ok(ab, wb, cw) &&
+           conv_wide_extra_shape(ab, wb, cw).cwt >= 1;
+}
+constexpr int conv_wide_extra_passes(int ab, int wb, int cw) { return cw / conv_wide_extra_shape(ab, wb, cw).cwt; }
 
 // the same for the stride-2 variant of the 3x3 kernel: two output pixels share a stage of five input
 // pixels where those fit the scalar registers of a stage, else one pixel per iteration

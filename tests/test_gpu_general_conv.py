@@ -96,6 +96,12 @@ CASES = [
     dict(Nb=1, H=7, W=9, C=128, Cout=130, ab=2, wb=2, KH=5, KW=3, pad=(2, 1)),
     dict(Nb=2, H=3, W=2, C=128, Cout=64, ab=2, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=3, H=17, W=19, C=128, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2),
+    # ... and on 64 channels (an instantiation of its own for other windows): every activation width up to 4
+    dict(Nb=2, H=9, W=10, C=64, Cout=70, ab=2, wb=2, KH=5, KW=5, pad=2),
+    dict(Nb=1, H=11, W=9, C=64, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2, out_bits=2),
+    dict(Nb=1, H=8, W=9, C=64, Cout=64, ab=1, wb=1, KH=7, KW=7, pad=3),
+    dict(Nb=2, H=7, W=8, C=64, Cout=130, ab=3, wb=4, KH=3, KW=3, pad=3, dilation=3),
+    dict(Nb=1, H=6, W=12, C=64, Cout=64, ab=4, wb=4, KH=1, KW=5, pad=(0, 2)),
     dict(Nb=1, H=9, W=14, C=64, Cout=64, ab=2, wb=1, KH=3, KW=1, stride=(1, 2), pad=(1, 0)),
     dict(Nb=2, H=8, W=10, C=100, Cout=130, ab=1, wb=1, KH=2, KW=4, stride=(2, 1), pad=(0, 2), dilation=(1, 2)),
     dict(Nb=1, H=6, W=6, C=64, Cout=64, ab=6, wb=2, KH=3, KW=3, pad=1),                     # wide activations
