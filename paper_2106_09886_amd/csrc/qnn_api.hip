@@ -233,13 +233,17 @@ qnn_status run_gemm(const uint32_t *A, int ab, const uint32_t *Wt, int wb, int64
     // the floor keeps a wavefront's products per weight chunk at about 1500 vector instructions or
     // more, below which reloading the weights costs more than the balance gains.  Measured on
     // products from 100352 x 64 x 256 to 8192^3 at one to four bits: 0.90-0.96 of the lane-op peak
-    // at 16-32 wavefronts per SIMD against 0.82-0.87 at four.
+    // at 16-32 wavefronts per SIMD against 0.82-0.87 at four.  The floor never leaves fewer than ten
+    // wavefronts per SIMD: with four, one SIMD in ten gets a fifth and the launch waits for it
+    // (measured with the floor at four per SIMD -> ten: 100352 x 64 x 256 at W2A2 20.2 -> 16.0 us,
+    // 25088 x 512 x 256 31.0 -> 28.6 us, 100352 x 256 x 64 42.6 -> 33 us).
     {
         const int kc = gemm_chunk_words(wb);
         const int64_t per_row = 2 * (int64_t)ab * wb * (g.Cw < kc ? (g.Cw > 0 ? g.Cw : 1) : kc);
         int min_rows = (int)((1536 + per_row - 1) / per_row);
-        const int at_four = pick_rows_per_wave(M, g.col_tiles, 4, 4);      // the floor never leaves fewer than
-        if (min_rows > at_four) min_rows = at_four;                         // four wavefronts per SIMD
+        const int at_ten = pick_rows_per_wave(M, g.col_tiles, 4, 10);
+        if (min_rows > at_ten) min_rows = at_ten;
+        if (min_rows > 20) min_rows = 20;      // very short rows (100352 x 256 x 64: 38.2 us at 39 rows, 32.5 at 20)
         const int rpw = pick_rows_per_wave(M, g.col_tiles, min_rows < 4 ? 4 : min_rows, 32);
         g.rows_per_wave = clamp_rows_for_emit(clamp_rows_per_wave(rpw, N), N, e);
     }
