@@ -364,7 +364,9 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
                  ("1x1 stride 1, 256->64, 56^2, W2A2", 32, 56, 56, 256, 64, 2, 2, 1, 1, 1, 0, 1, False),
                  ("3x3 stride 1, 64->64, 56^2, W2A2 (general kernel kept on the headline shape)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
                  ("3x3 stride 1, 64->64, 56^2, W2A2 (as called: handed to the 3x3 kernel)", 32, 56, 56, 64, 64, 2, 2, 3, 3, 1, 1, 1, False),
+                 ("3x3 dilation 2, 256->256, 33^2, W3A4 (general kernel kept)", 16, 33, 33, 256, 256, 4, 3, 3, 3, 1, 2, 2, False),
                  ("3x3 dilation 2, 256->256, 33^2, W3A4", 16, 33, 33, 256, 256, 4, 3, 3, 3, 1, 2, 2, False),
+                 ("3x3 dilation 4, 512->512, 17^2, W2A4", 16, 17, 17, 512, 512, 4, 2, 3, 3, 1, 4, 4, False),
                  ("5x5 stride 1, 128->128, 28^2, W2A4", 32, 28, 28, 128, 128, 4, 2, 5, 5, 1, 2, 1, False),
                  ("5x5 stride 1, 64->64, 56^2, W2A4", 16, 56, 56, 64, 64, 4, 2, 5, 5, 1, 2, 1, False),
                  ("5x5 stride 1, 96->96, 28^2, W2A2 (half of the second 64-filter tile is idle)", 32, 28, 28, 96, 96, 2, 2, 5, 5, 1, 2, 1, False),

@@ -327,9 +327,9 @@ qnn_status qnn_conv2d_im2col_requant(const void *x_codes, int code_bytes, int ab
  * the window workspace, runs on the kernel of qnn_conv2d_packed (same operands, same outputs;
  * QNN_TUNE_GENERAL_ONLY keeps it here); so do the 3x3 / stride 2 / pad 1 convolution and, at
  * stride 1, any odd window of at most 49 taps with "same" padding ((k/2) * dilation; equal
- * dilation in both directions) -- atrous 3x3, 5x5, 7x7, 1x3 ... -- for 256 or 512 input
- * channels (128 too with three or more activation bits) and the bit widths that kernel has fixed
- * shapes for.  A 1x1 convolution
+ * dilation in both directions) -- atrous 3x3, 5x5, 7x7, 1x3 ... -- for 64, 128, 256 or 512 input
+ * channels at the bit widths that kernel has fixed shapes for (up to 4 x 4 bits all of these;
+ * wider pairs where the shape takes one tap per pipeline stage).  A 1x1 convolution
  * without padding runs on the kernels of qnn_branch_gemm (rows = output pixels; with a stride and
  * bit widths up to 4 the rows are the strided selection of the input pixels).
  */

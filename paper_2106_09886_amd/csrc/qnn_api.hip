@@ -319,9 +319,9 @@ qnn_status run_conv_packed(const uint32_t *x_planes, int ab, const uint32_t *Wt,
     g.geo.ph = (kh / 2) * dilation; g.geo.pw = (kw / 2) * dilation; g.geo.dh = dilation; g.geo.dw = dilation;
     g.geo.Ho = (int)Ho; g.geo.Wo = (int)Wo; g.geo.transposed = 0;
     const bool other_window = kh != 3 || kw != 3 || dilation != 1;
-    // 64 channels: another window than the plain 3x3 has an instantiation of its own there
+    // shapes without a one-tap-per-stage 3x3 kernel: another window has an instantiation of its own there
     const bool wide_extra = other_window && conv_wide_extra_ok(ab, wb, g.Cw);
-    if (wide_extra) g.xcd_ranges = 0;
+    if (other_window) g.xcd_ranges = 0;          // those kernels exist with plain block numbers only
     const int group = wide_extra ? 1 : (stride == 1) ? conv_group(ab, wb, g.Cw) : conv_group_strided(ab, wb, g.Cw);
     // chunk passes per pixel: for a window of more than nine taps, so many times more tap chunks
     const int tap_factor = (kh * kw + 8) / 9;

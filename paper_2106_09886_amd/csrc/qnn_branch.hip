@@ -845,10 +845,15 @@ __device__ __forceinline__ void conv_chunk_tail(const BranchArgs &g, const OV &o
 // wavefront finishes every fourth row.  Four times the wavefronts, each with a single weight load.
 constexpr int kSplitRows = kConvSplitRows;       // most rows per block in the SPLIT variant
 
+// WIDE: another window than the plain 3x3 (any odd KH x KW with "same" padding at equal dilation,
+// stride 1), a kernel of its own so that the 3x3 kernels carry none of its code; only for shapes
+// with one tap per pipeline stage and a stage of at most 16 scalar registers.
 template <int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, bool EMIT, bool XR = false, int S = 1,
-          bool SPLIT = false>
+          bool SPLIT = false, bool WIDE = false>
 __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     static_assert(S == 1 || CWS > 0, "strided: compile-time plane strides only");
+    static_assert(!WIDE || (CWS > 0 && GT == 1 && S == 1 && P == 1 && !XR && conv_wide_stage_ok(AB, CWT)),
+                  "other windows: one tap per stage, at most 16 scalar registers per stage");
     if constexpr (SPLIT) {
         static_assert(TPC == 9 && CWS > 0 && CWS / CWT >= 2 && !XR, "all taps per chunk, several channel chunks");
         typedef typename std::conditional<EMIT, OutViewEmit, OutView>::type OV;
@@ -864,18 +869,13 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
         uniform_words As = as_uniform(g.A);
         const OutViewSlab sv = {slab + v * (kSplitRows * 64) + lane, v == 0};
         bool mine = false;
-        constexpr bool CAN_WIDE = (S == 1) && conv_wide_stage_ok(AB, CWT);
-        bool wide = false;
-        if constexpr (CAN_WIDE) wide = (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1);
-        if (wide) {                // another window: its taps nine at a time
-            if constexpr (CAN_WIDE) {
-                const int tap_chunks = (g.geo.KH * g.geo.KW + 8) / 9;
-                for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT)
-                    for (int tc = 0; tc < tap_chunks; ++tc) {
-                        conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S, true>(g, sv, As, nload, r0, r1, c0, tc * 9, /*first=*/!mine, /*last=*/false);
-                        mine = true;
-                    }
-            }
+        if constexpr (WIDE) {      // another window: its taps nine at a time
+            const int tap_chunks = (g.geo.KH * g.geo.KW + 8) / 9;
+            for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT)
+                for (int tc = 0; tc < tap_chunks; ++tc) {
+                    conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S, true>(g, sv, As, nload, r0, r1, c0, tc * 9, /*first=*/!mine, /*last=*/false);
+                    mine = true;
+                }
         } else {
             for (int c0 = v * CWT; c0 < CWS; c0 += 4 * CWT) {
                 conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S>(g, sv, As, nload, r0, r1, c0, 0, /*first=*/!mine, /*last=*/false);
@@ -921,19 +921,15 @@ __global__ __launch_bounds__(256) void conv_kernel(const BranchArgs g) {
     // Very wide activations leave too few SGPRs for the two hand-managed stage buffers next to
     // the runtime-stride address arithmetic; those (rare) shapes use compiler-managed loads.
     constexpr bool PIPELINED = (CWS > 0) || (AB <= 4);
-    // Another window than the plain 3x3 (the host sends it only to fixed shapes with one tap per stage):
-    // a copy of the chunk loop of its own, so that the 3x3 loop below carries none of its bookkeeping.
-    if constexpr (CWS > 0 && GT == 1 && S == 1 && P == 1 && conv_wide_stage_ok(AB, CWT)) {
-        if (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1) {
-            const int tap_chunks = (g.geo.KH * g.geo.KW + TPC - 1) / TPC;
-            for (int c0 = 0; c0 < Cw; c0 += CWT)
-                for (int tc = 0; tc < tap_chunks; ++tc)
-                    conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S, true>(g, ov, As, nload, r0, r1, c0, tc * TPC,
-                                                                            c0 == 0 && tc == 0,
-                                                                            c0 + CWT >= Cw && tc == tap_chunks - 1);
-            trace_end(g, wp);
-            return;
-        }
+    if constexpr (WIDE) {          // another window than the plain 3x3: its taps TPC at a time
+        const int tap_chunks = (g.geo.KH * g.geo.KW + TPC - 1) / TPC;
+        for (int c0 = 0; c0 < Cw; c0 += CWT)
+            for (int tc = 0; tc < tap_chunks; ++tc)
+                conv_chunk_full<AB, WB, CWS, CWT, TPC, GT, P, S, true>(g, ov, As, nload, r0, r1, c0, tc * TPC,
+                                                                        c0 == 0 && tc == 0,
+                                                                        c0 + CWT >= Cw && tc == tap_chunks - 1);
+        trace_end(g, wp);
+        return;
     }
     for (int c0 = 0; c0 < Cw; c0 += CWT) {
         const bool full = (c0 + CWT <= Cw);
@@ -1044,6 +1040,7 @@ hipError_t launch_gemm_t(const BranchArgs &g, hipStream_t s) {
 template <int AB, int WB, int CWS>
 hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
     using S = ConvShape<AB, WB, CWS>;
+    const bool other_window = g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1;
     if constexpr (conv_can_split(AB, WB, CWS)) {
         if (g.split_k) {           // the block's wavefronts split the channel chunks
             constexpr int SC = conv_split_shape(AB, WB, CWS).cwt;
@@ -1051,6 +1048,15 @@ hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
             const dim3 grid((unsigned)(row_blocks * g.col_tiles));
             if (g.rows_per_wave > kSplitRows) return hipErrorInvalidValue;                 // host bug
             const bool emit = g.planes_out != nullptr;
+            if (other_window) {
+                if constexpr (conv_wide_split_ok(AB, WB, CWS)) {
+                    if (g.geo.sh != 1) return hipErrorInvalidValue;                        // host bug
+                    if (emit) launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, true, false, 1, true, true>), grid, dim3(256), 0, s, g);
+                    else launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, false, false, 1, true, true>), grid, dim3(256), 0, s, g);
+                    return launch_status();
+                }
+                return hipErrorInvalidValue;                                               // host bug
+            }
             if (g.geo.sh == 2) {
                 if (emit) launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, true, false, 2, true>), grid, dim3(256), 0, s, g);
                 else launch_kernel((conv_kernel<AB, WB, CWS, SC, 9, 1, 1, false, false, 2, true>), grid, dim3(256), 0, s, g);
@@ -1062,16 +1068,23 @@ hipError_t launch_conv_fixed(const BranchArgs &g, hipStream_t s) {
         }
     }
     if (g.split_k) return hipErrorInvalidValue;                                            // host bug
-    if constexpr (conv_wide_extra_ok(AB, WB, CWS)) {
-        if (g.geo.KH != 3 || g.geo.KW != 3 || g.geo.dh != 1) {   // another window: one tap per stage
-            constexpr int EC = conv_wide_extra_shape(AB, WB, CWS).cwt;
-            if (g.geo.sh != 1 || g.xcd_ranges) return hipErrorInvalidValue;                // host bug
+    if (other_window) {            // the kernels of their own for other windows
+        if (g.geo.sh != 1 || g.xcd_ranges) return hipErrorInvalidValue;                    // host bug
+        if constexpr (conv_wide_plain_ok(AB, WB, CWS)) {
             if (g.planes_out != nullptr)
-                launch_kernel((conv_kernel<AB, WB, CWS, EC, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+                launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, 1, 1, true, false, 1, false, true>), grid_for(g), dim3(256), 0, s, g);
             else
-                launch_kernel((conv_kernel<AB, WB, CWS, EC, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+                launch_kernel((conv_kernel<AB, WB, CWS, S::CWT, S::TPC, 1, 1, false, false, 1, false, true>), grid_for(g), dim3(256), 0, s, g);
+            return launch_status();
+        } else if constexpr (conv_wide_extra_ok(AB, WB, CWS)) {   // an instantiation with one tap per stage
+            constexpr int EC = conv_wide_extra_shape(AB, WB, CWS).cwt;
+            if (g.planes_out != nullptr)
+                launch_kernel((conv_kernel<AB, WB, CWS, EC, 9, 1, 1, true, false, 1, false, true>), grid_for(g), dim3(256), 0, s, g);
+            else
+                launch_kernel((conv_kernel<AB, WB, CWS, EC, 9, 1, 1, false, false, 1, false, true>), grid_for(g), dim3(256), 0, s, g);
             return launch_status();
         }
+        return hipErrorInvalidValue;                                                       // host bug
     }
     if (g.geo.sh == 2) {           // stride 2: pixel groups of two only where five input pixels fit a stage
         constexpr int P2 = conv_group_strided(AB, WB, CWS);

@@ -237,17 +237,17 @@ constexpr bool conv_wide_plain_ok(int ab, int wb, int cw) {
 constexpr bool conv_wide_split_ok(int ab, int wb, int cw) {
     return conv_can_split(ab, wb, cw) && conv_wide_stage_ok(ab, conv_split_shape(ab, wb, cw).cwt);
 }
-// 64 channels: the 3x3 shape there holds several taps or pixels per stage, so other windows get an
-// instantiation of their own with one tap of both channel words per stage (bit widths up to 4 x 4,
-// to bound build time)
+// Shapes (64 to 256 channels) whose 3x3 kernel holds several taps or pixels per stage, and no split
+// variant either: other windows get an instantiation of their own there, with one tap of as many
+// channel words per stage as fit it (bit widths up to 4 x 4, to bound build time)
 constexpr ConvShapeV conv_wide_extra_shape(int ab, int wb, int cws) {
     int cwt = cws;
     while (cwt >= 1 && (!conv_wide_stage_ok(ab, cwt) || conv_shape_score(ab, wb, cws, cwt, 9) == 0)) cwt /= 2;
     return ConvShapeV{cwt, 9, 1, 1};
 }
 constexpr bool conv_wide_extra_ok(int ab, int wb, int cw) {
-    return cw == 2 && ab <= 4 && wb <= 4 && conv_has_fixed_shape(ab, wb, cw) && !conv_wide_plain_ok(ab, wb, cw) &&
-           conv_wide_extra_shape(ab, wb, cw).cwt >= 1;
+    return (cw == 2 || cw == 4 || cw == 8) && ab <= 4 && wb <= 4 && conv_has_fixed_shape(ab, wb, cw) &&
+           !conv_wide_plain_ok(ab, wb, cw) && !conv_wide_split_ok(ab, wb, cw) && conv_wide_extra_shape(ab, wb, cw).cwt >= 1;
 }
 constexpr int conv_wide_extra_passes(int ab, int wb, int cw) { return cw / conv_wide_extra_shape(ab, wb, cw).cwt; }
 

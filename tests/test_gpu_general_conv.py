@@ -96,7 +96,12 @@ CASES = [
     dict(Nb=1, H=7, W=9, C=128, Cout=130, ab=2, wb=2, KH=5, KW=3, pad=(2, 1)),
     dict(Nb=2, H=3, W=2, C=128, Cout=64, ab=2, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=3, H=17, W=19, C=128, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2),
-    # ... and on 64 channels (an instantiation of its own for other windows): every activation width up to 4
+    # ... and on the shapes whose 3x3 kernel holds several taps or pixels per stage (an instantiation of its
+    # own for other windows): 128 channels at one and two bits, 256 channels with one-bit weights, 64 channels
+    dict(Nb=1, H=10, W=9, C=128, Cout=64, ab=1, wb=1, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=2, H=8, W=9, C=128, Cout=70, ab=2, wb=1, KH=5, KW=5, pad=2, out_bits=2),
+    dict(Nb=1, H=9, W=8, C=256, Cout=64, ab=4, wb=1, KH=5, KW=5, pad=2),
+    dict(Nb=1, H=7, W=10, C=256, Cout=64, ab=3, wb=1, KH=7, KW=3, pad=(3, 1)),
     dict(Nb=2, H=9, W=10, C=64, Cout=70, ab=2, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=1, H=11, W=9, C=64, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2, out_bits=2),
     dict(Nb=1, H=8, W=9, C=64, Cout=64, ab=1, wb=1, KH=7, KW=7, pad=3),
