@@ -451,8 +451,8 @@ struct ConvCtx {
 
     // Any odd KH x KW window with "same" padding and dilation D (shapes with one tap per stage): stage
     // st holds tap t0 + st of the KH*KW, decoded on the scalar unit.  A tap is used if it exists
-    // (t < KH*KW), its image row exists, and -- for a border pixel, which is a run of its own and
-    // passes its column ow; an interior run passes -1 -- its column exists.  A tap that is not used
+    // (t < KH*KW), its image row exists, and its column exists for the run's first column ow (the caller
+    // cuts the runs so that this holds for all of a run's pixels or for none).  A tap that is not used
     // points at the pixel itself, so every address of the run is inside the image.
     // Returns the number of taps used.
     __device__ __forceinline__ int set_window_taps(int oh, int ow, int H, int W, int KH, int KW, int D) {
@@ -465,7 +465,7 @@ struct ConvCtx {
             const int t = t0 + st;
             const int kh = (t * recip) >> 16, kw = t - kh * KW;
             const int dh = (kh - (KH >> 1)) * D, dw = (kw - (KW >> 1)) * D;
-            const bool ok = t < T && (unsigned)(oh + dh) < (unsigned)H && (ow < 0 || (unsigned)(ow + dw) < (unsigned)W);
+            const bool ok = t < T && (unsigned)(oh + dh) < (unsigned)H && (unsigned)(ow + dw) < (unsigned)W;
             if (ok) { stage_ok |= 1u << st; ++used; }
             stage_off[st] = ok ? (uint32_t)(dh * W + dw) * pixel_bytes() : 0u;
         }
@@ -560,8 +560,8 @@ __device__ __forceinline__ int valid_taps(PixelPos p, int H, int W) {
 // pixels of the group before it (P > 1 is used for single-chunk shapes only, where a
 // recomputed pixel is simply stored again with the same value).
 // in_a: number of the input pixel under output pixel ra, (n*H + S*oh)*W + S*ow.
-// WIDE: another window than the plain 3x3 (see set_window_taps); wide_ow: the pixel's column if the
-// run is a border pixel, else -1.
+// WIDE: another window than the plain 3x3 (see set_window_taps); wide_ow: the first column of the run,
+// whose pixels all have the same taps.
 template <bool WIDE = false, int AB, int WB, int CWS, int CWT, int TPC, int GT, int P, int S, class OV>
 __device__ __forceinline__ void conv_run_pipelined(ConvCtx<AB, WB, CWS, CWT, TPC, GT, P, S> &c,
                                                    const BranchArgs &g, const OV &ov, int r0, int ra,
@@ -721,22 +721,23 @@ __device__ __forceinline__ void conv_chunk_full(const BranchArgs &g, const OV &o
     // |S*oh - (H - 1)| <= 1 (the last one or two).
     const int Ho = g.geo.Ho, Wo = g.geo.Wo;
     if constexpr (WIDE) {
-        // The first and last (KW/2)*D pixels of an image row miss taps: each of them is a run of its own
-        // with exactly its taps, the pixels between them one run with all columns.  No address of such a
-        // run leaves the image, so there are no end pixels to test.
-        const int halfw = (g.geo.KW >> 1) * g.geo.dh;
+        // The first and last (KW/2)*D pixels of an image row miss taps.  Which ones depends on the column
+        // only through floor(ow / D) on the left and floor((W-1-ow) / D) on the right (both saturating at
+        // KW/2), so a row is cut where one of the two changes -- at the multiples of D up to (KW/2)*D and at
+        // W - k*D, k = KW/2 .. 1 -- and every piece is a run with one set of taps, given by its first column.
+        // No address of such a run leaves the image, so there are no end pixels to test.
+        const int D = g.geo.dh, half_taps = g.geo.KW >> 1;
         PixelPos pos = pixel_pos(r0, g);
         int r = r0;
         while (r < r1) {
             const int row_end = r - pos.ow + Wo;
-            int stop = min(r1, row_end);
-            int wide_ow = -1;
-            if (pos.ow < halfw || pos.ow >= g.W - halfw) {
-                stop = r + 1;
-                wide_ow = pos.ow;
-            } else {
-                stop = min(stop, r - pos.ow + (g.W - halfw));
-            }
+            int cut = Wo;
+            for (int k = 1; k <= half_taps; ++k)
+                if (pos.ow < k * D) { cut = k * D; break; }
+            for (int k = half_taps; k >= 1; --k)
+                if (g.W - k * D > pos.ow) { cut = min(cut, g.W - k * D); break; }
+            const int stop = min(min(r1, row_end), r - pos.ow + cut);
+            const int wide_ow = pos.ow;
             conv_run_pipelined<true>(c, g, ov, r0, r, stop, pos.oh, (pos.n * g.H + pos.oh) * g.W + pos.ow, spin(0u), spin(0u),
                                      first, last, wide_ow);
             pos.ow += stop - r;
