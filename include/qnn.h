@@ -70,9 +70,10 @@ qnn_status qnn_device_info(int *h_compute_units, int *h_clock_khz);
  */
 #define QNN_TUNE_WAVES_PER_SIMD 1 /* resident wavefronts per SIMD the launch sizing aims for */
 #define QNN_TUNE_ROWS_PER_WAVE 2  /* rows (GEMM rows / output pixels) per wavefront        */
-#define QNN_TUNE_GENERAL_ONLY 3   /* nonzero: qnn_conv2d_general keeps a 3x3 stride-1 pad-1  */
-                                  /* window in its own kernel instead of handing it to the   */
-                                  /* kernel behind qnn_conv2d_packed (for comparisons)       */
+#define QNN_TUNE_GENERAL_ONLY 3   /* nonzero: qnn_conv2d_general keeps the windows it would  */
+                                  /* hand to the kernel behind qnn_conv2d_packed (3x3, odd   */
+                                  /* windows with "same" padding) in its own kernel (for     */
+                                  /* comparisons)                                            */
 #define QNN_TUNE_BLOCK_ORDER 4    /* convolution kernels: 1 plain block numbers, 2 one         */
                                   /* contiguous range of blocks (of pixels) per XCD            */
 #define QNN_TUNE_LDS_PARTIALS 5   /* GEMM with several K chunks per wavefront: 1 partial sums   */
