@@ -228,6 +228,7 @@ FULL_SIZE_CASES = [
     dict(Nb=32, H=56, W=56, C=256, Cout=64, ab=2, wb=2, KH=1, KW=1),
     dict(Nb=32, H=56, W=56, C=64, Cout=64, ab=2, wb=2, KH=3, KW=3, pad=1),
     dict(Nb=16, H=33, W=33, C=256, Cout=256, ab=4, wb=3, KH=3, KW=3, pad=2, dilation=2),
+    dict(Nb=16, H=17, W=17, C=512, Cout=512, ab=4, wb=2, KH=3, KW=3, pad=4, dilation=4),
     dict(Nb=32, H=28, W=28, C=128, Cout=128, ab=4, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=16, H=56, W=56, C=64, Cout=64, ab=4, wb=2, KH=5, KW=5, pad=2),
     dict(Nb=32, H=28, W=28, C=96, Cout=96, ab=2, wb=2, KH=5, KW=5, pad=2),
