@@ -20,6 +20,7 @@ __all__ = [
     "conv2d", "conv2d_transposed", "conv_out_size", "encode_real",
     "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
     "encode_smooth", "encoder_backward", "binarize", "binarize_backward", "quantize_k", "quantize_k_backward",
+    "branch_backward_input", "branch_backward_weight", "update_sgd",
 ]
 
 
@@ -82,6 +83,12 @@ def _L():
         lib.qnn_oracle_quantize_k.restype = None
         lib.qnn_oracle_quantize_k_backward.argtypes = [vp, vp, i64, ctypes.c_float, vp]
         lib.qnn_oracle_quantize_k_backward.restype = None
+        lib.qnn_oracle_branch_backward_input.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        lib.qnn_oracle_branch_backward_input.restype = None
+        lib.qnn_oracle_branch_backward_weight.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        lib.qnn_oracle_branch_backward_weight.restype = None
+        lib.qnn_oracle_update_sgd.argtypes = [vp, vp, i64, ctypes.c_float]
+        lib.qnn_oracle_update_sgd.restype = None
         lib.qnn_oracle_maxpool2x2.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.qnn_oracle_maxpool2x2.restype = None
         lib.qnn_oracle_round_odd.argtypes = [ctypes.c_float, i32]
@@ -321,3 +328,38 @@ def quantize_k_backward(x, g_q, t):
     out = np.zeros(x.shape, dtype=np.float32)
     _L().qnn_oracle_quantize_k_backward(_p(x), _p(g_q), x.size, ctypes.c_float(t), _p(out))
     return out
+
+
+def branch_backward_input(g_a, s, W, xb, wb):
+    """Alg. 1 backward through the product, towards the activations.  g_a fp32 [M][N], s fp32 [N] or
+    None, W codes [N][K] of wb bits -> float64 [xb][M][K] (gradient of every encoded element, low first)."""
+    g_a = np.ascontiguousarray(g_a, dtype=np.float32)
+    W = _codes(W)
+    M, N = g_a.shape
+    K = W.shape[1]
+    assert W.shape[0] == N
+    sp = None if s is None else np.ascontiguousarray(s, dtype=np.float32)
+    out = np.zeros((xb, M, K), dtype=np.float64)
+    _L().qnn_oracle_branch_backward_input(_p(g_a), None if sp is None else _p(sp), _p(W), M, N, K, int(xb), int(wb), _p(out))
+    return out
+
+
+def branch_backward_weight(g_a, s, A, xb, wb):
+    """Alg. 1 backward through the product, towards the binary weights.  g_a fp32 [M][N], s fp32 [N] or
+    None, A codes [M][K] of xb bits -> float64 [wb][N][K]."""
+    g_a = np.ascontiguousarray(g_a, dtype=np.float32)
+    A = _codes(A)
+    M, N = g_a.shape
+    K = A.shape[1]
+    assert A.shape[0] == M
+    sp = None if s is None else np.ascontiguousarray(s, dtype=np.float32)
+    out = np.zeros((wb, N, K), dtype=np.float64)
+    _L().qnn_oracle_branch_backward_weight(_p(g_a), None if sp is None else _p(sp), _p(A), M, N, K, int(xb), int(wb), _p(out))
+    return out
+
+
+def update_sgd(w, g, eta):
+    w = np.array(w, dtype=np.float32, order="C", copy=True)
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    _L().qnn_oracle_update_sgd(_p(w), _p(g), w.size, ctypes.c_float(eta))
+    return w

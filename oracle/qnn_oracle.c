@@ -398,3 +398,75 @@ void qnn_oracle_quantize_k_backward(const float *x, const float *g_q, int64_t n,
         g_x[i] = (r >= -1.0f && r <= 1.0f) ? g_q[i] : 0.0f;
     }
 }
+
+/* ---- Alg. 1, lines of the backward propagation through the multi-branch product ----------------
+ * Fully connected layer, forward lines of Alg. 1 with a per-channel scale s[n] in the place of
+ * r / ((2^M - 1)(2^K - 1)):
+ *     a_hat[i][n] = sum_{m=1..M} sum_{k=1..K} 2^(m+k-2) sum_c a^{mb}[i][c] W^{kb}[n][c],   a[i][n] = s[n] a_hat[i][n].
+ * Backward lines, given g_a = dC/da:
+ *     g_ahat[i][n]     = s[n] g_a[i][n]
+ *     g_{a^{mb}}[i][c] = sum_{k=1..K} 2^(m+k-2) backward(...),   backward(...)[i][c] = sum_n g_ahat[i][n] W^{kb}[n][c]
+ *     g_{W^{kb}}[n][c] = sum_{m=1..M} 2^(m+k-2) backward(...),   backward(...)[n][c] = sum_i g_ahat[i][n] a^{mb}[i][c]
+ * where backward() of a matrix product is the incoming gradient times the other operand (the
+ * listing prints g_{a^{mb}} as the last argument of the second backward(); the gradient that
+ * reaches the product is g_ahat, which is what is used here).  Everything in double precision;
+ * the elements a^{mb}, W^{kb} in {-1,+1} come from the encoding of the codes (Eq. (7)).
+ * A[M_rows][Kc] and W[N][Kc] hold odd-integer codes of xb and wb bits.
+ * g_bits is [xb][M_rows][Kc] (low element first), g_wb is [wb][N][Kc].  s may be NULL (all ones). */
+void qnn_oracle_branch_backward_input(const float *g_a, const float *s, const int16_t *W, int64_t M_rows,
+                                      int64_t N, int64_t Kc, int xb, int wb, double *g_bits)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M_rows; ++i) {
+        for (int64_t c = 0; c < Kc; ++c) {
+            for (int m = 1; m <= xb; ++m) {
+                double acc = 0.0;
+                for (int k = 1; k <= wb; ++k) {
+                    double back = 0.0;                     /* backward(a^{mb}, W^{kb}, g_ahat)[i][c] */
+                    for (int64_t n = 0; n < N; ++n) {
+                        int8_t e[8];
+                        qnn_oracle_encode(W[n * Kc + c], wb, e);
+                        const double g_ahat = (double)g_a[i * N + n] * (s ? (double)s[n] : 1.0);
+                        back += g_ahat * (double)e[k - 1];
+                    }
+                    acc += (double)((int64_t)1 << (m + k - 2)) * back;
+                }
+                g_bits[((int64_t)(m - 1) * M_rows + i) * Kc + c] = acc;
+            }
+        }
+    }
+}
+
+void qnn_oracle_branch_backward_weight(const float *g_a, const float *s, const int16_t *A, int64_t M_rows,
+                                       int64_t N, int64_t Kc, int xb, int wb, double *g_wb)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t c = 0; c < Kc; ++c) {
+            for (int k = 1; k <= wb; ++k) {
+                double acc = 0.0;
+                for (int m = 1; m <= xb; ++m) {
+                    double back = 0.0;                     /* backward(a^{mb}, W^{kb}, g_ahat)[n][c] */
+                    for (int64_t i = 0; i < M_rows; ++i) {
+                        int8_t e[8];
+                        qnn_oracle_encode(A[i * Kc + c], xb, e);
+                        const double g_ahat = (double)g_a[i * N + n] * (s ? (double)s[n] : 1.0);
+                        back += g_ahat * (double)e[m - 1];
+                    }
+                    acc += (double)((int64_t)1 << (m + k - 2)) * back;
+                }
+                g_wb[((int64_t)(k - 1) * N + n) * Kc + c] = acc;
+            }
+        }
+    }
+}
+
+/* Update(W, g, eta) of Alg. 1 / Alg. 2 with plain stochastic gradient descent (the text names SGD
+ * and Adam as the usual choices): w <- w - eta * g, one binary32 multiply and one subtraction.   */
+void qnn_oracle_update_sgd(float *w, const float *g, int64_t n, float eta)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float step = eta * g[i];
+        w[i] = w[i] - step;
+    }
+}

@@ -628,6 +628,84 @@ def test_quantize_k_properties(oracle, K):
     assert (oracle.quantize_k_backward(x, g, t) == (np.abs(x / t) <= 1).astype(np.float32)).all()
 
 
+def _elements(codes, bits):
+    """{-1,+1} elements of odd codes, low element first, by the binary expansion of (v + 2^bits - 1) / 2
+    (Eq. (7) written with Python integers; independent of the oracle's greedy encoder)."""
+    u = (codes.astype(np.int64) + (1 << bits) - 1) // 2
+    return [(2 * ((u >> p) & 1) - 1).astype(np.float64) for p in range(bits)]
+
+
+def _forward_from_elements(a_el, w_el, s):
+    """Forward lines of Alg. 1 on real-valued element matrices: sum_m sum_k 2^(m+k-2) a_m W_k^T, then the scale."""
+    a_hat = sum(2.0 ** (m + k) * (a_el[m] @ w_el[k].T) for m in range(len(a_el)) for k in range(len(w_el)))
+    return a_hat * s[None, :]
+
+
+@pytest.mark.parametrize("xb,wb", [(1, 1), (2, 2), (3, 2), (2, 4)])
+def test_branch_backward_is_the_slope_of_the_forward_lines(oracle, xb, wb):
+    """Alg. 1: the forward lines are linear in every element a^{mb}[i][c] and W^{kb}[n][c], so with the cost
+    C = sum g_a * a the gradient of an element is exactly C(element + 1) - C(element).  Every element of a
+    small layer, one at a time (brute force): catches a wrong factor 2^(m+k-2), a dropped scale, a
+    transposed operand, a wrong index order of the outputs."""
+    r = rng(900 + 10 * xb + wb)
+    M, N, K = 3, 4, 5
+    A, W = rand_codes(r, (M, K), xb), rand_codes(r, (N, K), wb)
+    g = r.normal(size=(M, N)).astype(np.float32)
+    s = r.uniform(0.5, 2.0, N).astype(np.float32)
+    a_el, w_el = _elements(A, xb), _elements(W, wb)
+    cost = lambda ae, we: float((g.astype(np.float64) * _forward_from_elements(ae, we, s.astype(np.float64))).sum())
+    base = cost(a_el, w_el)
+    gi = oracle.branch_backward_input(g, s, W, xb, wb)
+    gw = oracle.branch_backward_weight(g, s, A, xb, wb)
+    assert gi.shape == (xb, M, K) and gw.shape == (wb, N, K)
+    for m in range(xb):
+        for i in range(M):
+            for c in range(K):
+                bumped = [e.copy() for e in a_el]
+                bumped[m][i, c] += 1.0
+                assert abs((cost(bumped, w_el) - base) - gi[m, i, c]) <= 1e-9 * (1 + abs(gi[m, i, c]))
+    for k in range(wb):
+        for n in range(N):
+            for c in range(K):
+                bumped = [e.copy() for e in w_el]
+                bumped[k][n, c] += 1.0
+                assert abs((cost(a_el, bumped) - base) - gw[k, n, c]) <= 1e-9 * (1 + abs(gw[k, n, c]))
+
+
+@pytest.mark.parametrize("xb,wb", [(1, 1), (2, 2), (4, 3), (8, 8)])
+def test_branch_backward_closed_form_on_codes(oracle, xb, wb):
+    """Summing the branches of Alg. 1's backward lines (Eq. (7) read backwards): element m of the activation
+    gradient is 2^(m-1) * (s g_a) @ W_codes, element k of the weight gradient 2^(k-1) * (s g_a)^T @ A_codes
+    -- numpy float64 products of the decoded codes; with one bit each it is the textbook gradient of a
+    matrix product.  Without a scale the scale is one."""
+    r = rng(950 + xb + wb)
+    M, N, K = 9, 11, 37
+    A, W = rand_codes(r, (M, K), xb), rand_codes(r, (N, K), wb)
+    g = r.normal(size=(M, N)).astype(np.float32)
+    for s in (None, r.uniform(0.25, 4.0, N).astype(np.float32)):
+        gs = g.astype(np.float64) * (1.0 if s is None else s.astype(np.float64)[None, :])
+        gi = oracle.branch_backward_input(g, s, W, xb, wb)
+        gw = oracle.branch_backward_weight(g, s, A, xb, wb)
+        base_i, base_w = gs @ W.astype(np.float64), gs.T @ A.astype(np.float64)
+        for m in range(xb):
+            assert np.abs(gi[m] - 2.0 ** m * base_i).max() <= 1e-9 * (1 + np.abs(base_i).max() * 2.0 ** m)
+        for k in range(wb):
+            assert np.abs(gw[k] - 2.0 ** k * base_w).max() <= 1e-9 * (1 + np.abs(base_w).max() * 2.0 ** k)
+
+
+def test_update_sgd_is_one_multiply_and_one_subtraction(oracle):
+    """Update() of Alg. 1 / Alg. 2 as plain gradient descent: w - eta * g with both steps rounded to binary32
+    (numpy float32 arithmetic does exactly that), not a fused multiply-add."""
+    r = rng(990)
+    w, g = r.normal(size=4000).astype(np.float32), r.normal(size=4000).astype(np.float32)
+    eta = np.float32(0.0371)
+    want = w - (eta * g).astype(np.float32)
+    got = oracle.update_sgd(w, g, float(eta))
+    assert got.dtype == np.float32 and (got == want).all()
+    fused = (w.astype(np.float64) - float(eta) * g.astype(np.float64)).astype(np.float32)
+    assert (fused != want).any()            # the two readings differ on this input, so the pin separates them
+
+
 def test_speedup_model_reading(oracle):
     """Eq. (16) with the constants of Sec. 5.4 (gamma = 1.91, L = 64, beta = gamma / 2) at N = 8192
     reproduces the printed 2-bit figure; this is the reading quoted as context beside the measured
