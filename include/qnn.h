@@ -255,6 +255,38 @@ qnn_status qnn_quantize_k(const float *x, int64_t n, int bits, float t, float *q
 qnn_status qnn_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x, void *stream);
 
 /*
+ * Backward propagation through the multi-branch product of a fully connected layer (Alg. 1, the
+ * backward lines; not on the inference path).  The forward call is qnn_branch_gemm: a[i][n] =
+ * scale[n] * sum_{m,k} 2^(m+k-2) sum_c a^{mb}[i][c] W^{kb}[n][c].  Given g_out = dC/da, fp32 [M][N]
+ * row-major, Alg. 1 first forms g_ahat[i][n] = scale[n] * g_out[i][n] (one binary32 multiply; scale
+ * NULL = all ones) and then
+ *   qnn_branch_gemm_backward_input    g_bits[m-1][i][c] = sum_k 2^(m+k-2) sum_n g_ahat[i][n] W^{kb}[n][c]
+ *       the gradient of every encoded activation element, fp32 [ab][M][K] (low element first): what
+ *       qnn_encoder_backward takes.  Wt = the packed weights of the forward call, uint32 [N][wb][ceil(K/32)].
+ *   qnn_branch_gemm_backward_weight   g_wb[k-1][n][c] = sum_m 2^(m+k-2) sum_i g_ahat[i][n] a^{mb}[i][c]
+ *       the gradient of every binary weight element, fp32 [wb][N][K]: what qnn_binarize_backward takes,
+ *       element by element.  A = the packed activations of the forward call, uint32 [M][ab][ceil(K/32)].
+ * (The listing prints g_{a^{mb}} as the last argument of the second backward(); the gradient that
+ * reaches the product is g_ahat, which is used.)  Summed over the other operand's elements these
+ * are 2^(m-1) * g_ahat . w and 2^(k-1) * g_ahat^T . a with the odd-integer codes w, a (Eq. (7)):
+ * real-valued contractions, evaluated in binary32 on the matrix cores with the codes decoded from
+ * the planes; the result differs from the exact sum by at most (J + 2) * 2^-24 * sum_j |term_j| per
+ * output, J = N or M the length of the sum.
+ * All buffers device memory, outputs written in full; g_out, scale, outputs 4-byte aligned, planes
+ * 16-byte aligned.  M, N, K >= 0: an empty output launches nothing, an empty sum writes zeros.
+ * Limits: M, N, K < 2^31; ab, wb in 1..8.  QNN_EINVAL / QNN_EALIGN / QNN_EUNSUPPORTED / QNN_EHIP as elsewhere.
+ *
+ * qnn_update_sgd   Update(W, g, eta) of Alg. 1 / Alg. 2 as plain gradient descent (the text names SGD
+ *   and Adam as the usual choices): w[i] <- w[i] - lr * g[i], one binary32 multiply and one
+ *   subtraction, in place; w, g fp32 [n].
+ */
+qnn_status qnn_branch_gemm_backward_input(const float *g_out, const float *scale, const uint32_t *Wt, int wb,
+                                          int64_t M, int64_t N, int64_t K, int ab, float *g_bits, void *stream);
+qnn_status qnn_branch_gemm_backward_weight(const float *g_out, const float *scale, const uint32_t *A, int ab,
+                                           int64_t M, int64_t N, int64_t K, int wb, float *g_wb, void *stream);
+qnn_status qnn_update_sgd(float *w, const float *g, int64_t n, float lr, void *stream);
+
+/*
  * Chained layers (Alg. 1 forward as one kernel: branch sum, scale, re-encode).  The *_requant
  * variants of the three product entry points compute the same int32 product, multiply by
  * scale[n] (scale == NULL: y = (float)acc), map y to the odd code grid of out_bits bits with the

@@ -26,7 +26,8 @@ EXPORTS = (
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
     "qnn_encode_real", "qnn_encoder_backward", "qnn_binarize", "qnn_binarize_backward", "qnn_quantize_k",
-    "qnn_quantize_k_backward", "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
+    "qnn_quantize_k_backward", "qnn_branch_gemm_backward_input", "qnn_branch_gemm_backward_weight", "qnn_update_sgd",
+    "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
     "qnn_compare_dot4_gemm",
     "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
 )
@@ -131,6 +132,12 @@ def lib():
     L.qnn_quantize_k.restype = i32
     L.qnn_quantize_k_backward.argtypes = [vp, vp, i64, ctypes.c_float, vp, vp]
     L.qnn_quantize_k_backward.restype = i32
+    L.qnn_branch_gemm_backward_input.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
+    L.qnn_branch_gemm_backward_input.restype = i32
+    L.qnn_branch_gemm_backward_weight.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
+    L.qnn_branch_gemm_backward_weight.restype = i32
+    L.qnn_update_sgd.argtypes = [vp, vp, i64, ctypes.c_float, vp]
+    L.qnn_update_sgd.restype = i32
     gp = ctypes.POINTER(ConvGeometry)
     L.qnn_conv2d_general_output_size.argtypes = [i64, i64, gp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.qnn_conv2d_general_output_size.restype = i32
@@ -487,6 +494,40 @@ def quantize_k_backward(x, g_q, t):
     _check(lib().qnn_quantize_k_backward(_ptr(x), _ptr(g_q), x.numel(), ctypes.c_float(t), _ptr(out), _stream()),
            "qnn_quantize_k_backward")
     return out
+
+
+def branch_gemm_backward_input(g_out, Wt, wb, K, ab, scale=None):
+    """Alg. 1 backward towards the activations: g_out fp32 [M][N], Wt planes [N][wb][Kw] -> fp32 [ab][M][K]."""
+    _dev(g_out, torch.float32, "g_out")
+    _dev(Wt, torch.int32, "Wt")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    M, N = g_out.shape
+    out = torch.empty((ab, M, K), dtype=torch.float32, device=g_out.device)
+    _check(lib().qnn_branch_gemm_backward_input(_ptr(g_out), _ptr(scale), _ptr(Wt), wb, M, N, K, ab, _ptr(out), _stream()),
+           "qnn_branch_gemm_backward_input")
+    return out
+
+
+def branch_gemm_backward_weight(g_out, A, ab, K, wb, scale=None):
+    """Alg. 1 backward towards the binary weights: g_out fp32 [M][N], A planes [M][ab][Kw] -> fp32 [wb][N][K]."""
+    _dev(g_out, torch.float32, "g_out")
+    _dev(A, torch.int32, "A")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    M, N = g_out.shape
+    out = torch.empty((wb, N, K), dtype=torch.float32, device=g_out.device)
+    _check(lib().qnn_branch_gemm_backward_weight(_ptr(g_out), _ptr(scale), _ptr(A), ab, M, N, K, wb, _ptr(out), _stream()),
+           "qnn_branch_gemm_backward_weight")
+    return out
+
+
+def update_sgd(w, g, lr):
+    """In place: w <- w - lr * g."""
+    _dev(w, torch.float32, "w")
+    _dev(g, torch.float32, "g")
+    _check(lib().qnn_update_sgd(_ptr(w), _ptr(g), w.numel(), ctypes.c_float(lr), _stream()), "qnn_update_sgd")
+    return w
 
 
 def compare_mfma_arrange(codes):

@@ -62,6 +62,7 @@ def build(jobs=None, verbose=False, incremental=False):
             ("qnn_epilogue.hip", os.path.join(OBJ, "qnn_epilogue.o"), []),
             ("qnn_requant.hip", os.path.join(OBJ, "qnn_requant.o"), []),
             ("qnn_elementwise.hip", os.path.join(OBJ, "qnn_elementwise.o"), []),
+            ("qnn_backward.hip", os.path.join(OBJ, "qnn_backward.o"), []),
             ("qnn_compare_mfma.hip", os.path.join(OBJ, "qnn_compare_mfma.o"), []),
             ("qnn_compare_dot.hip", os.path.join(OBJ, "qnn_compare_dot.o"), [])]
     for ab in range(1, 9):

@@ -669,6 +669,36 @@ qnn_status qnn_quantize_k_backward(const float *x, const float *g_q, int64_t n, 
     return from_hip(launch_quantize_k_backward(x, g_q, n, t, g_x, (hipStream_t)stream));
 }
 
+qnn_status qnn_branch_gemm_backward_input(const float *g_out, const float *scale, const uint32_t *Wt, int wb,
+                                          int64_t M, int64_t N, int64_t K, int ab, float *g_bits, void *stream) {
+    if (!bits_ok(ab) || !bits_ok(wb) || M < 0 || N < 0 || K < 0) return QNN_EINVAL;
+    if (M > kInt31 || N > kInt31 || K > kInt31) return QNN_EUNSUPPORTED;
+    if (M == 0 || K == 0) return QNN_OK;
+    if (g_bits == nullptr || (N > 0 && (g_out == nullptr || Wt == nullptr))) return QNN_EINVAL;
+    if (!aligned4(g_out) || !aligned4(scale) || !aligned4(g_bits) || !aligned16(Wt)) return QNN_EALIGN;
+    return from_hip(launch_backward_gemm(g_out, N, scale, Wt, wb, (int)M, (int)N, (int)K, ab, /*towards_weights=*/false,
+                                         g_bits, (hipStream_t)stream));
+}
+
+qnn_status qnn_branch_gemm_backward_weight(const float *g_out, const float *scale, const uint32_t *A, int ab,
+                                           int64_t M, int64_t N, int64_t K, int wb, float *g_wb, void *stream) {
+    if (!bits_ok(ab) || !bits_ok(wb) || M < 0 || N < 0 || K < 0) return QNN_EINVAL;
+    if (M > kInt31 || N > kInt31 || K > kInt31) return QNN_EUNSUPPORTED;
+    if (N == 0 || K == 0) return QNN_OK;
+    if (g_wb == nullptr || (M > 0 && (g_out == nullptr || A == nullptr))) return QNN_EINVAL;
+    if (!aligned4(g_out) || !aligned4(scale) || !aligned4(g_wb) || !aligned16(A)) return QNN_EALIGN;
+    return from_hip(launch_backward_gemm(g_out, N, scale, A, ab, (int)N, (int)M, (int)K, wb, /*towards_weights=*/true,
+                                         g_wb, (hipStream_t)stream));
+}
+
+qnn_status qnn_update_sgd(float *w, const float *g, int64_t n, float lr, void *stream) {
+    if (n < 0) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (w == nullptr || g == nullptr) return QNN_EINVAL;
+    if (!aligned4(w) || !aligned4(g)) return QNN_EALIGN;
+    return from_hip(launch_update_sgd(w, g, n, lr, (hipStream_t)stream));
+}
+
 qnn_status qnn_conv2d_general_output_size(int64_t H, int64_t W, const qnn_conv_geometry *q, int64_t *h_Ho,
                                           int64_t *h_Wo) {
     if (q == nullptr || h_Ho == nullptr || h_Wo == nullptr || H < 0 || W < 0) return QNN_EINVAL;

@@ -327,6 +327,10 @@ hipError_t launch_binarize(const float *w, int64_t rows, int64_t K, int8_t *code
 hipError_t launch_binarize_backward(const float *w, const float *g_wb, int64_t n, float *g_w, hipStream_t);
 hipError_t launch_quantize_k(const float *x, int64_t n, int bits, float t, float *q, int32_t *levels, hipStream_t);
 hipError_t launch_quantize_k_backward(const float *x, const float *g_q, int64_t n, float t, float *g_x, hipStream_t);
+// backward lines of Alg. 1 through the product: out[p][r][c] = 2^p sum_j G(r, j) code[j][c] (qnn_backward.hip)
+hipError_t launch_backward_gemm(const float *g, int64_t ldg, const float *scale, const uint32_t *planes, int code_bits,
+                                int R, int J, int C, int P, bool towards_weights, float *out, hipStream_t);
+hipError_t launch_update_sgd(float *w, const float *g, int64_t n, float lr, hipStream_t);
 hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, int64_t Wo, int64_t Cw, int bits,
                               uint32_t *out, hipStream_t);
 hipError_t launch_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, void *out, hipStream_t);

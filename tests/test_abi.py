@@ -312,3 +312,21 @@ def test_training_side_argument_errors(L):
     f = L.qnn_quantize_k_backward
     assert f(P, P, 16, c(0.0), P, None) == QNN_EINVAL and f(P, None, 16, c(1.0), P, None) == QNN_EINVAL
     assert f(None, None, 0, c(1.0), None, None) == QNN_OK
+
+
+def test_backward_product_argument_errors(L):
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED
+    for f in (L.qnn_branch_gemm_backward_input, L.qnn_branch_gemm_backward_weight):
+        assert f(P, None, P, 0, 4, 4, 32, 2, P, None) == QNN_EINVAL and f(P, None, P, 2, 4, 4, 32, 9, P, None) == QNN_EINVAL
+        assert f(P, None, P, 2, -1, 4, 32, 2, P, None) == QNN_EINVAL
+        assert f(None, None, P, 2, 4, 4, 32, 2, P, None) == QNN_EINVAL and f(P, None, None, 2, 4, 4, 32, 2, P, None) == QNN_EINVAL
+        assert f(P, None, P, 2, 4, 4, 32, 2, None, None) == QNN_EINVAL
+        assert f(P + 2, None, P, 2, 4, 4, 32, 2, P, None) == QNN_EALIGN and f(P, None, P + 4, 2, 4, 4, 32, 2, P, None) == QNN_EALIGN
+        assert f(P, P + 1, P, 2, 4, 4, 32, 2, P, None) == QNN_EALIGN
+        assert f(P, None, P, 2, 1 << 31, 4, 32, 2, P, None) == QNN_EUNSUPPORTED
+        assert f(None, None, None, 2, 4, 4, 0, 2, None, None) == QNN_OK          # no columns: empty output
+    assert L.qnn_branch_gemm_backward_input(None, None, None, 2, 0, 4, 32, 2, None, None) == QNN_OK
+    assert L.qnn_branch_gemm_backward_weight(None, None, None, 2, 4, 0, 32, 2, None, None) == QNN_OK
+    f = L.qnn_update_sgd
+    assert f(P, P, -1, 0.1, None) == QNN_EINVAL and f(None, P, 4, 0.1, None) == QNN_EINVAL and f(P, None, 4, 0.1, None) == QNN_EINVAL
+    assert f(P + 2, P, 4, 0.1, None) == QNN_EALIGN and f(None, None, 0, 0.1, None) == QNN_OK

@@ -104,3 +104,124 @@ def test_quantize_k(q, oracle, bits, t):
     assert (host(gq).view(np.uint32) == want_q.view(np.uint32)).all()
     g = rng.normal(size=x.shape).astype(np.float32)
     assert (host(q.quantize_k_backward(dev(x), dev(g), t)) == oracle.quantize_k_backward(x, g, t)).all()
+
+
+# ------------------------------------------------------------------ Alg. 1, backward through the product
+def _backward_case(q, oracle, M, N, K, ab, wb, with_scale, seed):
+    from gpu_util import rand_codes
+    rng = np.random.default_rng(seed)
+    A, W = rand_codes(rng, (M, K), ab), rand_codes(rng, (N, K), wb)
+    g = rng.normal(size=(M, N)).astype(np.float32)
+    s = rng.uniform(0.25, 4.0, N).astype(np.float32) if with_scale else None
+    Ap = q.encode_pack(dev(A), ab) if M and K else None
+    Wp = q.encode_pack(dev(W), wb) if N and K else None
+    return A, W, g, s, Ap, Wp
+
+
+def _bound(g, s, codes_abs_sum_matrix, J):
+    """(J + 2) * 2^-24 * sum_j |g_ahat| |code|: binary32 accumulation of J terms in any order, one rounding
+    of the scale product, exact codes and exact powers of two (the tolerance the header states)."""
+    return (J + 2) * 2.0 ** -24 * codes_abs_sum_matrix
+
+
+BACKWARD_CASES = [
+    # (M, N, K, ab, wb, with_scale): several 32-row / 128-column tiles with ragged tails in every
+    # direction, reduction lengths that are and are not multiples of 8 (vector and scalar load paths),
+    # every code width, single rows and columns
+    (70, 100, 130, 2, 2, True), (33, 64, 257, 4, 3, False), (128, 256, 128, 2, 2, True), (1, 1, 1, 1, 1, False),
+    (5, 8, 32, 8, 8, True), (200, 24, 40, 3, 5, True), (257, 40, 129, 1, 4, False), (64, 7, 64, 6, 1, True),
+    (96, 136, 300, 7, 2, False), (40, 264, 96, 2, 6, True), (300, 16, 33, 5, 7, False),
+]
+
+
+@pytest.mark.parametrize("case", BACKWARD_CASES, ids=lambda c: "M%d-N%d-K%d-A%dW%d%s" % (c[0], c[1], c[2], c[3], c[4], "-s" if c[5] else ""))
+def test_branch_gemm_backward(q, oracle, case):
+    """Both gradients of Alg. 1's backward lines against the float64 oracle, element by element, within the
+    binary32 accumulation bound; the 2^(m-1) / 2^(k-1) copies are exact multiples of the first."""
+    M, N, K, ab, wb, with_scale = case
+    say("branch_gemm_backward", case)
+    A, W, g, s, Ap, Wp = _backward_case(q, oracle, M, N, K, ab, wb, with_scale, 7 * M + 3 * N + K + ab + wb)
+    gs = np.abs(g.astype(np.float64)) * (1.0 if s is None else s.astype(np.float64)[None, :])
+    want_i = oracle.branch_backward_input(g, s, W, ab, wb)
+    got_i = host(q.branch_gemm_backward_input(dev(g), Wp, wb, K, ab, scale=None if s is None else dev(s))).astype(np.float64)
+    assert got_i.shape == want_i.shape == (ab, M, K)
+    bound_i = _bound(g, s, gs @ np.abs(W.astype(np.float64)), N)
+    for m in range(ab):
+        assert (np.abs(got_i[m] - want_i[m]) <= 2.0 ** m * bound_i).all()
+        assert (got_i[m] == 2.0 ** m * got_i[0]).all()
+    want_w = oracle.branch_backward_weight(g, s, A, ab, wb)
+    got_w = host(q.branch_gemm_backward_weight(dev(g), Ap, ab, K, wb, scale=None if s is None else dev(s))).astype(np.float64)
+    assert got_w.shape == want_w.shape == (wb, N, K)
+    bound_w = _bound(g, s, gs.T @ np.abs(A.astype(np.float64)), M)
+    for k in range(wb):
+        assert (np.abs(got_w[k] - want_w[k]) <= 2.0 ** k * bound_w).all()
+        assert (got_w[k] == 2.0 ** k * got_w[0]).all()
+    # not vacuous: the results are far from zero compared with the bound
+    assert np.abs(want_i[0]).mean() > 100 * bound_i.mean() and np.abs(want_w[0]).mean() > 100 * bound_w.mean()
+
+
+def test_branch_gemm_backward_exact_on_small_integers(q, oracle):
+    """Integer-valued gradients of small magnitude: every product and partial sum is an integer below 2^24,
+    so binary32 accumulation is exact in any order and the result must equal the oracle's bit for bit."""
+    from gpu_util import rand_codes
+    rng = np.random.default_rng(5)
+    M, N, K, ab, wb = 100, 72, 200, 3, 4
+    A, W = rand_codes(rng, (M, K), ab), rand_codes(rng, (N, K), wb)
+    g = rng.integers(-8, 9, size=(M, N)).astype(np.float32)
+    s = (2.0 ** rng.integers(-1, 3, size=N)).astype(np.float32)
+    Ap, Wp = q.encode_pack(dev(A), ab), q.encode_pack(dev(W), wb)
+    assert (host(q.branch_gemm_backward_input(dev(g), Wp, wb, K, ab, scale=dev(s))).astype(np.float64)
+            == oracle.branch_backward_input(g, s, W, ab, wb)).all()
+    assert (host(q.branch_gemm_backward_weight(dev(g), Ap, ab, K, wb, scale=dev(s))).astype(np.float64)
+            == oracle.branch_backward_weight(g, s, A, ab, wb)).all()
+
+
+def test_branch_gemm_backward_degenerate_sizes(q, oracle):
+    """An empty sum writes zeros; an empty output launches nothing."""
+    import torch
+    from gpu_util import rand_codes
+    rng = np.random.default_rng(6)
+    g0 = torch.empty((5, 0), dtype=torch.float32, device="cuda")
+    Wp0 = torch.empty((0, 2, 2), dtype=torch.int32, device="cuda")
+    out = q.branch_gemm_backward_input(g0, Wp0, 2, 40, 3)
+    assert tuple(out.shape) == (3, 5, 40) and (host(out) == 0).all()
+    gM0 = torch.empty((0, 7), dtype=torch.float32, device="cuda")
+    Ap0 = torch.empty((0, 2, 2), dtype=torch.int32, device="cuda")
+    out = q.branch_gemm_backward_weight(gM0, Ap0, 2, 40, 3)
+    assert tuple(out.shape) == (3, 7, 40) and (host(out) == 0).all()
+    assert tuple(q.branch_gemm_backward_input(gM0, q.encode_pack(dev(rand_codes(rng, (7, 40), 2)), 2), 2, 40, 3).shape) == (3, 0, 40)
+
+
+def test_branch_gemm_backward_at_the_fc_layer_size(q, oracle):
+    """The fully connected configuration of the benchmark (256 x 4096 x 4096, W2A2) in the launch shape the
+    library picks; sampled rows against the oracle (the oracle computes only those rows / filters)."""
+    from gpu_util import rand_codes
+    rng = np.random.default_rng(11)
+    M, N, K, ab, wb = 256, 4096, 4096, 2, 2
+    A, W = rand_codes(rng, (M, K), ab), rand_codes(rng, (N, K), wb)
+    g = rng.normal(size=(M, N)).astype(np.float32)
+    s = rng.uniform(0.5, 2.0, N).astype(np.float32)
+    Ap, Wp = q.encode_pack(dev(A), ab), q.encode_pack(dev(W), wb)
+    got_i = host(q.branch_gemm_backward_input(dev(g), Wp, wb, K, ab, scale=dev(s))).astype(np.float64)
+    got_w = host(q.branch_gemm_backward_weight(dev(g), Ap, ab, K, wb, scale=dev(s))).astype(np.float64)
+    gs = np.abs(g.astype(np.float64)) * s.astype(np.float64)[None, :]
+    rows = np.array([0, 31, 32, 127, 128, 255])
+    want = oracle.branch_backward_input(g[rows], s, W, ab, wb)
+    bound = _bound(g, s, gs[rows] @ np.abs(W.astype(np.float64)), N)
+    for m in range(ab):
+        assert (np.abs(got_i[m][rows] - want[m]) <= 2.0 ** m * bound).all()
+    filt = np.array([0, 63, 64, 2047, 4095])
+    want = oracle.branch_backward_weight(g[:, filt], s[filt], A, ab, wb)
+    bound = _bound(g, s, gs[:, filt].T @ np.abs(A.astype(np.float64)), M)
+    for k in range(wb):
+        assert (np.abs(got_w[k][filt] - want[k]) <= 2.0 ** k * bound).all()
+
+
+@pytest.mark.parametrize("n", [1, 255, 4096, 100003])
+def test_update_sgd(q, oracle, n):
+    rng = np.random.default_rng(n)
+    w, g = rng.normal(size=n).astype(np.float32), rng.normal(size=n).astype(np.float32)
+    want = oracle.update_sgd(w, g, 0.0371)
+    wd = dev(w)
+    q.update_sgd(wd, dev(g), 0.0371)
+    assert (host(wd) == want).all()
