@@ -10,8 +10,9 @@ Default workload: `resnet18_s1`, the ResNet-18-stage-1-shaped W2A2 3x3 convoluti
 is quoted on.  Other workloads (`--workload`): `resnet50_s3`, `fc4096`, `gemm64`, `gemm8192`
 (`--bits b`, with the two comparison lines: int8 matrix cores and packed int8 dot product), `vgg16_stack` (13 chained layers: conv +
 scale, then max-pool / re-encode / pack per layer), `vgg16_stack_fused` (the same through the
-fused kernels), and two side suites that print their own tables: `hbm_kernels` (the
-memory-bound kernels at chip-filling sizes) and `conv_geometries` (`qnn_conv2d_general`).
+fused kernels), and side suites that print their own tables: `hbm_kernels` (the
+memory-bound kernels at chip-filling sizes), `conv_geometries` (`qnn_conv2d_general`),
+`resnet18_mixed` and `backward_products` (the training-side products of Alg. 1).
 
 Prints ONE JSON line.  `value` is the effective quantized throughput 2*M*N*K / t_step in
 GOPS.  `roofline` prices the dominant kernel (the branch kernel) against the chip's integer
@@ -294,6 +295,32 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
         res = {"metric": "GB/s of qnn_encode_pack (algorithmic bytes: codes in + planes out)", "value": head["GBps"],
                "unit": "GB/s", "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": head["GBps"], "peak": 8000.0,
                                             "unit": "GB/s", "frac": round(head["GBps"] / 8000.0, 4), "traffic": None}}
+    elif name == "backward_products":
+        # Alg. 1's backward lines through the product of a fully connected layer: real gradient times the
+        # codes held as bit planes, on the fp32 matrix cores (dense peak 157.3 TFLOP/s).  flops = 2 * M * N * K
+        # per call (the 2^(m-1) / 2^(k-1) copies are exact multiples, written, not recomputed).
+        PEAK_F32_MFMA = 157.3e12
+        for (label, M, N, K, ab, wb) in (("FC 256 x 4096 x 4096, W2A2", 256, 4096, 4096, 2, 2),
+                                         ("FC 4096 x 4096 x 4096, W2A2", 4096, 4096, 4096, 2, 2),
+                                         ("FC 4096 x 4096 x 4096, W4A4", 4096, 4096, 4096, 4, 4),
+                                         ("FC 1024 x 1000 x 512, W6A4", 1024, 1000, 512, 4, 6)):
+            Kw = (K + 31) // 32
+            Ap = torch.randint(-2 ** 31, 2 ** 31 - 1, (M, ab, Kw), dtype=torch.int32, device=dev)
+            Wp = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, wb, Kw), dtype=torch.int32, device=dev)
+            g = torch.randn((M, N), device=dev)
+            sd = torch.rand(N, device=dev) + 0.5
+            flops = 2.0 * M * N * K
+            for which, fn, out_bytes in (("towards the activations", lambda: q.branch_gemm_backward_input(g, Wp, wb, K, ab, scale=sd), ab * M * K * 4),
+                                         ("towards the weights", lambda: q.branch_gemm_backward_weight(g, Ap, ab, K, wb, scale=sd), wb * N * K * 4)):
+                t = avg_us(fn)
+                rows.append({"layer": label, "gradient": which, "us": round(t, 1), "TFLOPs": round(flops / t / 1e6, 2),
+                             "frac_of_f32_matrix_peak": round(flops / (t * 1e-6) / PEAK_F32_MFMA, 3),
+                             "output_MB": round(out_bytes / 1e6, 1)})
+            del Ap, Wp, g, sd
+        head = rows[3]
+        res = {"metric": "TFLOP/s of qnn_branch_gemm_backward_weight, 4096^3 W2A2", "value": head["TFLOPs"], "unit": "TFLOP/s",
+               "roofline": {"bound": "mfma", "kernel": "backward_gemm_kernel", "achieved": head["TFLOPs"], "peak": 157.3,
+                            "unit": "TFLOP/s", "frac": head["frac_of_f32_matrix_peak"], "traffic": None}}
     elif name == "resnet18_mixed":
         # The paper's mixed-precision example (Sec. 5.1, Table 4, second precision column): ResNet-18 with
         # 4-bit activations and 5 / 3 / 2 / 2-bit weights in the four residual stages, a 6-bit fully
@@ -422,7 +449,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="resnet18_s1",
                     choices=["resnet18_s1", "resnet50_s3", "fc4096", "gemm64", "gemm8192", "vgg16_stack",
-                             "vgg16_stack_fused", "hbm_kernels", "conv_geometries", "resnet18_mixed"])
+                             "vgg16_stack_fused", "hbm_kernels", "conv_geometries", "resnet18_mixed", "backward_products"])
     ap.add_argument("--bits", type=int, default=None,
                     help="gemm8192 only: activation = weight bit width (1..6 in the paper's sweep; default 2)")
     ap.add_argument("--batch", type=int, default=None,
@@ -484,7 +511,7 @@ def main():
     def check(st):
         assert st == 0, L.qnn_status_string(st)
 
-    if name in ("hbm_kernels", "conv_geometries", "resnet18_mixed"):
+    if name in ("hbm_kernels", "conv_geometries", "resnet18_mixed", "backward_products"):
         return side_suites(name, args, steps, warmup, torch, np, q, dev)
 
     cpu = cpu1 = None

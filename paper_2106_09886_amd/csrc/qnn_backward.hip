@@ -30,124 +30,213 @@ struct BackArgs {
     int64_t ldg;
 };
 
-// A block of four wavefronts takes 32*RT rows x 128 columns of the output; wavefront v the 32
-// columns of plane word 4*cb + v.  One iteration takes eight reduction indices: lanes 0..31 hold
-// j0..j0+3, lanes 32..63 j0+4..j0+7, and the u-th of four matrix instructions pairs j0+u with
-// j0+4+u (any pairing is right as long as both operands use it).
+// A block of four wavefronts takes 32*RT rows x 128 columns of the output; wavefront v all rows
+// and the 32 columns of plane word 4*cb + v, so a decoded code feeds RT matrix instructions.
+// (A 2 x 2 arrangement of the wavefronts with two row tiles and two plane words each, which halves
+// what a block fetches, measured 5-20 % slower at 4096^3.)
+// One iteration takes eight reduction indices: lanes 0..31 hold j0..j0+3, lanes 32..63
+// j0+4..j0+7, and the u-th of four matrix instructions pairs j0+u with j0+4+u (any pairing is
+// right as long as both operands use it).
 //   A operand (32 x 2): lane l supplies row l % 32, reduction index l / 32.
 //   B operand (2 x 32): lane l supplies column l % 32, reduction index l / 32.
 //   D (32 x 32, 16 registers): register v of lane l is row 8 * (v / 4) + 4 * (l / 32) + v % 4, column l % 32.
+// The loads of the next eight indices are issued before the matrix instructions of the current ones
+// (two stage buffers, the loop unrolled by two).
 // GT: g is indexed [j][r] (gradient of the weights) instead of [r][j].
 // VEC (only without GT): J is a multiple of 8, ldg of 4 and g, scale are 16-byte aligned: the four
 // values of a lane are one 16-byte load.
-template <int CB, int RT, bool GT, bool VEC>
-__global__ __launch_bounds__(256) void backward_gemm_kernel(const BackArgs a) {
+// SPLITJ (outputs of few tiles, long sums; RT = 1, 2): the block takes 32*RT rows x 32 columns and
+// its four wavefronts a quarter of the sum each; the quarters meet in LDS and are added in a fixed order.
+// (Left to itself the compiler sizes the kernel for one wavefront per SIMD; for the smaller tiles
+// two to four resident wavefronts are asked for instead.)
+template <int CB, int RT, bool GT, bool VEC, bool SPLITJ>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RT == 4 ? 1 : RT == 2 ? (CB >= 7 ? 2 : 3) : (CB >= 7 ? 3 : 4))))
+void backward_gemm_kernel(const BackArgs a) {
+    constexpr int NT = RT;                               // row tiles per wavefront
+    constexpr int CT = 1;                                // plane words (32 columns each) per wavefront
+    static_assert(!SPLITJ || RT <= 2, "the split form has one plane word per block");
     const int wave = (int)(threadIdx.x >> 6), lane = (int)(threadIdx.x & 63);
     const int half = lane >> 5, l5 = lane & 31;
     const int rb = (int)(blockIdx.x / (unsigned)a.col_blocks);
     const int cb = (int)(blockIdx.x - (unsigned)rb * (unsigned)a.col_blocks);
     const int r0 = rb * (32 * RT);
-    const int cw = cb * 4 + wave;
-    if (cw >= a.Cw) return;                              // no barrier in this kernel
-    f32x16 acc[RT];
+    const int cw0 = SPLITJ ? cb : cb * 4 + wave;
+    if (!SPLITJ && (cw0 >= a.Cw || r0 >= a.R)) return;   // (no barrier without SPLITJ; with it both hold always)
+    // the wavefront's part of the sum
+    int jbeg = 0, jend = a.J;
+    if constexpr (SPLITJ) {
+        const int quarter = ((a.J + 31) / 32) * 8;       // a multiple of 8
+        jbeg = min(a.J, wave * quarter);
+        jend = min(a.J, jbeg + quarter);
+    }
+    f32x16 acc[NT][CT];
 #pragma unroll
-    for (int t = 0; t < RT; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
-    int rowc[RT];                                        // the lane's A row, clamped for the loads
-    float srow[RT];
+        for (int c = 0; c < CT; ++c)
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
+            for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
+    int rowc[NT];                                        // the lane's A row, clamped for the loads
+    float srow[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
         const int row = r0 + t * 32 + l5;
         rowc[t] = row < a.R ? row : a.R - 1;
         srow[t] = (GT && a.scale != nullptr) ? a.scale[rowc[t]] : 1.0f;
     }
+    int cwc[CT];                                         // plane words, clamped for the loads
+#pragma unroll
+    for (int c = 0; c < CT; ++c) cwc[c] = min(cw0 + c, a.Cw - 1);
     constexpr int kOffset = (1 << CB) - 1;
-    for (int j0 = 0; j0 < a.J; j0 += 8) {
+    // A stage holds what was loaded, untouched (any arithmetic on it would wait for the loads at
+    // once), and loading is free of branches: indices past the end are clamped to valid addresses
+    // and their products masked in compute(), a missing scale reads the gradient's address instead
+    // and is replaced by one.  With a branch around the loads the compiler can no longer count how
+    // many are in flight and waits for all of them before the matrix instructions.
+    struct Stage {
+        float gv[NT][4];
+        float sv[4];
+        uint32_t pw[4][CT][CB];
+    };
+    const bool has_scale = a.scale != nullptr;
+    auto load = [&](int j0, Stage &st) {
         const int jb = j0 + 4 * half;
-        float av[RT][4], bv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int j = jb + u;
-            const int jc = j < a.J ? j : a.J - 1;
-            uint32_t bits = 0;
+            const int jc = min(jb + u, jend - 1);
 #pragma unroll
-            for (int q = 0; q < CB; ++q) {
-                const uint32_t w = a.planes[((int64_t)jc * CB + q) * a.Cw + cw];
-                bits |= ((w >> l5) & 1u) << q;
-            }
-            bv[u] = (float)(2 * (int)bits - kOffset);
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int q = 0; q < CB; ++q) st.pw[u][c][q] = a.planes[((int64_t)jc * CB + q) * a.Cw + cwc[c]];
         }
         if constexpr (VEC) {
-            f32x4 sv = {1.0f, 1.0f, 1.0f, 1.0f};
-            if (a.scale != nullptr) sv = *reinterpret_cast<const f32x4 *>(a.scale + jb);
+            const int jbc = min(jb, jend - 4);           // jb, jend multiples of 4, jend >= 8
+            const float *sp = has_scale ? a.scale + jbc : a.g + (int64_t)rowc[0] * a.ldg + jbc;
+            const f32x4 sv = *reinterpret_cast<const f32x4 *>(sp);
 #pragma unroll
-            for (int t = 0; t < RT; ++t) {
-                const f32x4 gv = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)rowc[t] * a.ldg + jb);
+            for (int u = 0; u < 4; ++u) st.sv[u] = sv[u];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) av[t][u] = gv[u] * sv[u];
+            for (int t = 0; t < NT; ++t) {
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)rowc[t] * a.ldg + jbc);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) st.gv[t][u] = gv[u];
             }
         } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int j = jb + u;
-                const bool jok = j < a.J;
-                const int jc = jok ? j : a.J - 1;
-                const float sj = (!GT && a.scale != nullptr) ? a.scale[jc] : 1.0f;
+                const int jc = min(jb + u, jend - 1);
 #pragma unroll
-                for (int t = 0; t < RT; ++t) {
-                    const float gv = GT ? a.g[(int64_t)jc * a.ldg + rowc[t]] : a.g[(int64_t)rowc[t] * a.ldg + jc];
-                    const float val = GT ? gv * srow[t] : gv * sj;
-                    av[t][u] = jok ? val : 0.0f;
+                for (int t = 0; t < NT; ++t)
+                    st.gv[t][u] = GT ? a.g[(int64_t)jc * a.ldg + rowc[t]] : a.g[(int64_t)rowc[t] * a.ldg + jc];
+                if constexpr (!GT) {
+                    const float *sp = has_scale ? a.scale + jc : a.g + (int64_t)rowc[0] * a.ldg + jc;
+                    st.sv[u] = *sp;
+                } else {
+                    st.sv[u] = 1.0f;
                 }
             }
         }
+    };
+    auto compute = [&](int j0, const Stage &st) {
+        const int jb = j0 + 4 * half;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u) {
+            const bool jok = jb + u < jend;
+            const float sj = (GT || !has_scale) ? 1.0f : st.sv[u];
+            float av[NT];
 #pragma unroll
-            for (int t = 0; t < RT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t][u], bv[u], acc[t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t) {
+                const float val = GT ? st.gv[t][u] * srow[t] : st.gv[t][u] * sj;
+                av[t] = jok ? val : 0.0f;
+            }
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                uint32_t bits = 0;
+#pragma unroll
+                for (int q = 0; q < CB; ++q) bits |= ((st.pw[u][c][q] >> l5) & 1u) << q;
+                const float bv = (float)(2 * (int)bits - kOffset);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t], bv, acc[t][c], 0, 0, 0);
+            }
+        }
+    };
+    if (jbeg < jend) {
+        Stage s0, s1;
+        load(jbeg, s0);
+        for (int j0 = jbeg; j0 < jend; j0 += 16) {       // the second half of the last pass may be all masked
+            load(j0 + 8, s1);
+            compute(j0, s0);
+            load(j0 + 16, s0);
+            compute(j0 + 8, s1);
+        }
     }
-    const int col = cw * 32 + l5;
-    if (col >= a.C) return;
-#pragma unroll
-    for (int t = 0; t < RT; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = r0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-            if (row < a.R) {
-                float val = acc[t][v];
-                for (int p = 0; p < a.P; ++p) {
-                    a.out[((int64_t)p * a.R + row) * a.C + col] = val;
-                    val *= 2.0f;                          // exact
-                }
+    auto store = [&](int t, int c, int v, float val) {
+        const int row = r0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+        const int col = (cw0 + c) * 32 + l5;
+        if (row < a.R && col < a.C) {
+            for (int p = 0; p < a.P; ++p) {
+                a.out[((int64_t)p * a.R + row) * a.C + col] = val;
+                val *= 2.0f;                              // exact
             }
         }
+    };
+    if constexpr (SPLITJ) {
+        __shared__ float part[4][NT][16][64];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) part[wave][t][v][lane] = acc[t][0][v];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int v = wave * 4 + k;              // a quarter of the tile's registers per wavefront
+                store(t, 0, v, ((part[0][t][v][lane] + part[1][t][v][lane]) + part[2][t][v][lane]) + part[3][t][v][lane]);
+            }
+    } else {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) store(t, c, v, acc[t][c][v]);
+    }
 }
 
-template <int CB, int RT, bool GT>
+template <int CB, int RT, bool GT, bool SPLITJ>
 void launch_one(const BackArgs &a, bool vec, dim3 grid, hipStream_t s) {
     if constexpr (!GT) {
         if (vec) {
-            launch_kernel((backward_gemm_kernel<CB, RT, false, true>), grid, dim3(256), 0, s, a);
+            launch_kernel((backward_gemm_kernel<CB, RT, false, true, SPLITJ>), grid, dim3(256), 0, s, a);
             return;
         }
     }
-    launch_kernel((backward_gemm_kernel<CB, RT, GT, false>), grid, dim3(256), 0, s, a);
+    launch_kernel((backward_gemm_kernel<CB, RT, GT, false, SPLITJ>), grid, dim3(256), 0, s, a);
 }
 
 template <int CB, bool GT>
 hipError_t launch_cb(BackArgs a, bool vec, hipStream_t s) {
-    // rows per block: 128 where that still gives two blocks per compute unit, else 64 or 32
-    a.col_blocks = (a.Cw + 3) / 4;
+    // rows per block: 128 where that still gives two blocks per compute unit, else 64 or 32; if even
+    // that leaves fewer and the sum is long, blocks of 32 columns whose wavefronts split the sum
     const int64_t want = 2 * (int64_t)device_simd_count() / 4;
-    auto blocks = [&](int rt) { return ((int64_t)a.R + 32 * rt - 1) / (32 * rt) * a.col_blocks; };
-    const int rt = blocks(4) >= want ? 4 : blocks(2) >= want ? 2 : 1;
-    const int64_t nb = blocks(rt);
+    auto blocks = [&](int rt, int words) { return ((int64_t)a.R + 32 * rt - 1) / (32 * rt) * ((a.Cw + words - 1) / words); };
+    const bool split = blocks(1, 4) < want && a.J >= 256;
+    int rt;
+    if (split) rt = blocks(2, 1) >= want ? 2 : 1;
+    else rt = blocks(4, 4) >= want ? 4 : blocks(2, 4) >= want ? 2 : 1;
+    a.col_blocks = split ? a.Cw : (a.Cw + 3) / 4;
+    const int64_t nb = blocks(rt, split ? 1 : 4);
     if (nb > 0x7fffffff) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nb);
-    if (rt == 4) launch_one<CB, 4, GT>(a, vec, grid, s);
-    else if (rt == 2) launch_one<CB, 2, GT>(a, vec, grid, s);
-    else launch_one<CB, 1, GT>(a, vec, grid, s);
+    if (split) {
+        if (rt == 2) launch_one<CB, 2, GT, true>(a, vec, grid, s);
+        else launch_one<CB, 1, GT, true>(a, vec, grid, s);
+    } else {
+        if (rt == 4) launch_one<CB, 4, GT, false>(a, vec, grid, s);
+        else if (rt == 2) launch_one<CB, 2, GT, false>(a, vec, grid, s);
+        else launch_one<CB, 1, GT, false>(a, vec, grid, s);
+    }
     return launch_status();
 }
 
