@@ -27,6 +27,7 @@ struct BackArgs {
     const uint32_t *planes;  // [J][CB][Cw]
     float *out;              // [P][R][C]
     int R, J, C, Cw, P, col_blocks;
+    int lds_vec;             // 16-byte loads are possible in the LDS-staged kernel
     int64_t ldg;
 };
 
@@ -204,6 +205,173 @@ void backward_gemm_kernel(const BackArgs a) {
     }
 }
 
+// Outputs of many tiles: the same block tile (128 rows x 128 columns, wavefront v the columns of
+// plane word 4*cb + v), with the real operand staged through LDS in tiles of 32 reduction indices.
+// Read straight from memory, a lane's values of one row lie 16 bytes apart from one iteration to the
+// next and the rows of a tile a whole row of g apart: every cache line is fetched again for each
+// 32 bytes used (measured: matrix pipes busy in 62 % of the cycles).  Here the 256 threads load a
+// tile [128 rows][32 indices] with whole lines, scale it and keep it as [index][row] (row stride
+// 132 words) in one of two LDS buffers; the next tile is loaded into registers before the matrix
+// instructions of the current one and written to the other buffer after them, one barrier per tile.
+// The plane words of a tile's 32 indices are loaded by lanes 0..31 (one index each) and handed out
+// per step with v_readlane.  A wavefront whose plane word lies past the last one still loads, stores
+// and waits with the others and only skips the products.
+// VEC: 16-byte loads (ldg, and J or R, multiples of 4; g and scale 16-byte aligned), else scalar loads.
+template <int CB, bool GT, bool VEC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void backward_gemm_lds_kernel(const BackArgs a) {
+    constexpr int KT = 32, LD = 132;
+    __shared__ __attribute__((aligned(16))) float tile[2][KT][LD];
+    const int tid = (int)threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int half = lane >> 5, l5 = lane & 31;
+    const int rb = (int)(blockIdx.x / (unsigned)a.col_blocks);
+    const int cb = (int)(blockIdx.x - (unsigned)rb * (unsigned)a.col_blocks);
+    const int r0 = rb * 128;
+    const int cw = cb * 4 + wave;
+    const bool active = cw < a.Cw;
+    const int cwc = active ? cw : a.Cw - 1;
+    const bool has_scale = a.scale != nullptr;
+    constexpr int kOffset = (1 << CB) - 1;
+    f32x16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+    // this thread's part of a tile: four pieces of four values
+    //   !GT: piece i = row r0 + tid / 8 + 32 i, indices j0 + 4 (tid % 8) .. + 3   (a quarter line of g)
+    //    GT: piece i = index j0 + tid / 32 + 8 i, rows r0 + 4 (tid % 32) .. + 3
+    struct Regs {
+        f32x4 v[4];
+        f32x4 sc;                                       // !GT: the scale of the piece's four indices
+        uint32_t pw[CB];                                // lanes 0..31: plane words of index j0 + lane
+    };
+    f32x4 srow = {1.0f, 1.0f, 1.0f, 1.0f};              // GT: the scale of the piece's four rows
+    if constexpr (GT) {
+        if (has_scale) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) srow[e] = a.scale[min(r0 + 4 * (tid & 31) + e, a.R - 1)];
+        }
+    }
+    auto load = [&](int j0, Regs &rg) {
+        {
+            const int jc = min(j0 + l5, a.J - 1);
+#pragma unroll
+            for (int q = 0; q < CB; ++q) rg.pw[q] = a.planes[((int64_t)jc * CB + q) * a.Cw + cwc];
+        }
+        if constexpr (!GT) {
+            const int jp = j0 + 4 * (tid & 7);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = min(r0 + (tid >> 3) + 32 * i, a.R - 1);
+                if constexpr (VEC) {
+                    rg.v[i] = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)row * a.ldg + min(jp, a.J - 4));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rg.v[i][e] = a.g[(int64_t)row * a.ldg + min(jp + e, a.J - 1)];
+                }
+            }
+            if constexpr (VEC) {
+                const float *sp = has_scale ? a.scale + min(jp, a.J - 4) : a.g;
+                rg.sc = *reinterpret_cast<const f32x4 *>(sp);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rg.sc[e] = has_scale ? a.scale[min(jp + e, a.J - 1)] : 1.0f;
+            }
+        } else {
+            const int rp = r0 + 4 * (tid & 31);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = min(j0 + (tid >> 5) + 8 * i, a.J - 1);
+                if constexpr (VEC) {
+                    rg.v[i] = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)j * a.ldg + min(rp, a.R - 4));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rg.v[i][e] = a.g[(int64_t)j * a.ldg + min(rp + e, a.R - 1)];
+                }
+            }
+        }
+    };
+    // registers -> LDS [index][row], scaled; indices past J become zero
+    auto stage = [&](int j0, const Regs &rg, int buf) {
+        if constexpr (!GT) {
+            const int jl = 4 * (tid & 7);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int rl = (tid >> 3) + 32 * i;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float s = has_scale ? rg.sc[e] : 1.0f;
+                    tile[buf][jl + e][rl] = (j0 + jl + e < a.J) ? rg.v[i][e] * s : 0.0f;
+                }
+            }
+        } else {
+            const int rl = 4 * (tid & 31);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int jl = (tid >> 5) + 8 * i;
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (j0 + jl < a.J) ? rg.v[i][e] * srow[e] : 0.0f;
+                *reinterpret_cast<f32x4 *>(&tile[buf][jl][rl]) = o;
+            }
+        }
+    };
+    auto compute = [&](const uint32_t (&pw)[CB], int buf) {
+#pragma unroll
+        for (int s = 0; s < KT / 2; ++s) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int q = 0; q < CB; ++q) {
+                const uint32_t w0 = (uint32_t)__builtin_amdgcn_readlane((int)pw[q], 2 * s);
+                const uint32_t w1 = (uint32_t)__builtin_amdgcn_readlane((int)pw[q], 2 * s + 1);
+                bits |= (((half ? w1 : w0) >> l5) & 1u) << q;
+            }
+            const float bv = (float)(2 * (int)bits - kOffset);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(tile[buf][2 * s + half][t * 32 + l5], bv, acc[t], 0, 0, 0);
+        }
+    };
+    if (a.J > 0) {
+        Regs rg;
+        uint32_t pw_cur[CB];
+        load(0, rg);
+        stage(0, rg, 0);
+#pragma unroll
+        for (int q = 0; q < CB; ++q) pw_cur[q] = rg.pw[q];
+        __syncthreads();
+        int buf = 0;
+        for (int j0 = 0; j0 < a.J; j0 += KT) {
+            const bool more = j0 + KT < a.J;             // uniform over the block
+            if (more) load(j0 + KT, rg);
+            if (active) compute(pw_cur, buf);
+            if (more) {
+                stage(j0 + KT, rg, buf ^ 1);
+#pragma unroll
+                for (int q = 0; q < CB; ++q) pw_cur[q] = rg.pw[q];
+            }
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    if (!active) return;
+    const int col = cw * 32 + l5;
+    if (col >= a.C) return;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+            if (row < a.R) {
+                float val = acc[t][v];
+                for (int p = 0; p < a.P; ++p) {
+                    a.out[((int64_t)p * a.R + row) * a.C + col] = val;
+                    val *= 2.0f;                          // exact
+                }
+            }
+        }
+}
+
 template <int CB, int RT, bool GT, bool SPLITJ>
 void launch_one(const BackArgs &a, bool vec, dim3 grid, hipStream_t s) {
     if constexpr (!GT) {
@@ -233,8 +401,10 @@ hipError_t launch_cb(BackArgs a, bool vec, hipStream_t s) {
         if (rt == 2) launch_one<CB, 2, GT, true>(a, vec, grid, s);
         else launch_one<CB, 1, GT, true>(a, vec, grid, s);
     } else {
-        if (rt == 4) launch_one<CB, 4, GT, false>(a, vec, grid, s);
-        else if (rt == 2) launch_one<CB, 2, GT, false>(a, vec, grid, s);
+        if (rt == 4) {
+            if (a.lds_vec) launch_kernel((backward_gemm_lds_kernel<CB, GT, true>), grid, dim3(256), 0, s, a);
+            else launch_kernel((backward_gemm_lds_kernel<CB, GT, false>), grid, dim3(256), 0, s, a);
+        } else if (rt == 2) launch_one<CB, 2, GT, false>(a, vec, grid, s);
         else launch_one<CB, 1, GT, false>(a, vec, grid, s);
     }
     return launch_status();
@@ -270,6 +440,8 @@ hipError_t launch_backward_gemm(const float *g, int64_t ldg, const float *scale,
     BackArgs a;
     a.g = g; a.scale = scale; a.planes = planes; a.out = out;
     a.R = R; a.J = J; a.C = C; a.Cw = (C + 31) / 32; a.P = P; a.col_blocks = 0; a.ldg = ldg;
+    const bool aligned = ldg % 4 == 0 && ((((uintptr_t)g) & 15u) == 0) && (scale == nullptr || (((uintptr_t)scale) & 15u) == 0);
+    a.lds_vec = (aligned && (towards_weights ? R % 4 == 0 && R >= 4 : J % 4 == 0 && J >= 4)) ? 1 : 0;
     const bool vec = !towards_weights && J % 8 == 0 && ldg % 4 == 0 && ((((uintptr_t)g) & 15u) == 0) &&
                      (scale == nullptr || (((uintptr_t)scale) & 15u) == 0);
     return towards_weights ? launch_form<true>(code_bits, a, vec, s) : launch_form<false>(code_bits, a, vec, s);

@@ -225,3 +225,37 @@ def test_update_sgd(q, oracle, n):
     wd = dev(w)
     q.update_sgd(wd, dev(g), 0.0371)
     assert (host(wd) == want).all()
+
+
+@pytest.mark.parametrize("M,N,K,ab,wb", [(2053, 204, 4001, 2, 3), (2050, 203, 4033, 3, 2), (2176, 40, 4096, 8, 8), (2048, 36, 4000, 1, 1)])
+def test_branch_gemm_backward_input_many_tiles(q, oracle, M, N, K, ab, wb):
+    """Outputs of more than 512 block tiles take the kernel that stages the gradient through LDS: sum
+    lengths that are and are not multiples of 4 (16-byte and scalar loads) and of 32 (last tile partly
+    empty), ragged last row and column tiles, one to eight code bits.  Sampled rows against the oracle."""
+    say("backward_input_many_tiles", M, N, K, ab, wb)
+    A, W, g, s, Ap, Wp = _backward_case(q, oracle, M, N, K, ab, wb, True, M + N + K)
+    got = host(q.branch_gemm_backward_input(dev(g), Wp, wb, K, ab, scale=dev(s))).astype(np.float64)
+    rows = np.array([0, 1, 31, 32, 127, 128, 1000, M - 130, M - 2, M - 1])
+    want = oracle.branch_backward_input(g[rows], s, W, ab, wb)
+    gs = np.abs(g[rows].astype(np.float64)) * s.astype(np.float64)[None, :]
+    bound = _bound(g, s, gs @ np.abs(W.astype(np.float64)), N)
+    for m in range(ab):
+        assert (np.abs(got[m][rows] - want[m]) <= 2.0 ** m * bound).all()
+        assert (got[m] == 2.0 ** m * got[0]).all()
+    assert np.abs(want[0]).mean() > 100 * bound.mean()
+
+
+@pytest.mark.parametrize("M,N,K,ab,wb", [(150, 2052, 4001, 3, 2), (97, 2053, 4033, 2, 3), (64, 2176, 4096, 8, 8), (33, 2048, 4000, 1, 1)])
+def test_branch_gemm_backward_weight_many_tiles(q, oracle, M, N, K, ab, wb):
+    """The same for the gradient of the weights (the gradient matrix is read along its rows)."""
+    say("backward_weight_many_tiles", M, N, K, ab, wb)
+    A, W, g, s, Ap, Wp = _backward_case(q, oracle, M, N, K, ab, wb, True, M + N + K + 1)
+    got = host(q.branch_gemm_backward_weight(dev(g), Ap, ab, K, wb, scale=dev(s))).astype(np.float64)
+    filt = np.array([0, 1, 31, 32, 127, 128, 1000, N - 130, N - 2, N - 1])
+    want = oracle.branch_backward_weight(g[:, filt], s[filt], A, ab, wb)
+    gs = np.abs(g[:, filt].astype(np.float64)) * s[filt].astype(np.float64)[None, :]
+    bound = _bound(g, s, gs.T @ np.abs(A.astype(np.float64)), M)
+    for k in range(wb):
+        assert (np.abs(got[k][filt] - want[k]) <= 2.0 ** k * bound).all()
+        assert (got[k] == 2.0 ** k * got[0]).all()
+    assert np.abs(want[0]).mean() > 100 * bound.mean()
