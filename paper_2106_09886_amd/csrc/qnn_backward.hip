@@ -214,7 +214,7 @@ void backward_gemm_kernel(const BackArgs a) {
 // 132 words) in one of two LDS buffers; the next tile is loaded into registers before the matrix
 // instructions of the current one and written to the other buffer after them, one barrier per tile.
 // The plane words of a tile's 32 indices are loaded by lanes 0..31 (one index each) and handed out
-// per step with v_readlane.  A wavefront whose plane word lies past the last one still loads, stores
+// per step with ds_bpermute (one instruction per plane; two v_readlane and a select measured slower).  A wavefront whose plane word lies past the last one still loads, stores
 // and waits with the others and only skips the products.
 // VEC: 16-byte loads (ldg, and J or R, multiples of 4; g and scale 16-byte aligned), else scalar loads.
 template <int CB, bool GT, bool VEC>
@@ -317,19 +317,28 @@ void backward_gemm_lds_kernel(const BackArgs a) {
         }
     };
     auto compute = [&](const uint32_t (&pw)[CB], int buf) {
+        float an[4];                                     // the real operand of the next step, read a step ahead
+#pragma unroll
+        for (int t = 0; t < 4; ++t) an[t] = tile[buf][half][t * 32 + l5];
 #pragma unroll
         for (int s = 0; s < KT / 2; ++s) {
+            float ac[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ac[t] = an[t];
+            if (s + 1 < KT / 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) an[t] = tile[buf][2 * (s + 1) + half][t * 32 + l5];
+            }
             uint32_t bits = 0;
 #pragma unroll
             for (int q = 0; q < CB; ++q) {
-                const uint32_t w0 = (uint32_t)__builtin_amdgcn_readlane((int)pw[q], 2 * s);
-                const uint32_t w1 = (uint32_t)__builtin_amdgcn_readlane((int)pw[q], 2 * s + 1);
-                bits |= (((half ? w1 : w0) >> l5) & 1u) << q;
+                // the word of index 2s (lanes 0..31) or 2s+1 (lanes 32..63), held by the lane of that number
+                const uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((2 * s + half) << 2, (int)pw[q]);
+                bits |= ((w >> l5) & 1u) << q;
             }
             const float bv = (float)(2 * (int)bits - kOffset);
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(tile[buf][2 * s + half][t * 32 + l5], bv, acc[t], 0, 0, 0);
+            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bv, acc[t], 0, 0, 0);
         }
     };
     if (a.J > 0) {
