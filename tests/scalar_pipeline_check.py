@@ -42,11 +42,12 @@ def compile_asm(job):
 
 def built_asm(src, ab):
     """The assembly the library build kept for (source, activation width), or None if it is missing
-    or older than any kernel source."""
+    or older than what it is compiled from (its source, every header)."""
     path = os.path.join(BUILD, "ab%d" % ab, src.split(".")[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
     if not os.path.exists(path):
         return None
-    deps = [os.path.join(HERE, f) for f in os.listdir(HERE) if f.endswith((".hip", ".h"))]
+    deps = [os.path.join(HERE, f) for f in os.listdir(HERE) if f.endswith(".h")]
+    deps.append(os.path.join(HERE, src))
     deps.append(os.path.join(ROOT, "include", "qnn.h"))
     return path if os.path.getmtime(path) >= max(os.path.getmtime(d) for d in deps) else None
 
