@@ -1128,6 +1128,14 @@ hipError_t launch_conv_t(const BranchArgs &g, hipStream_t s) {
     // any other channel count: runtime stride, chunks of two channel words while the two stage
     // buffers (2 * AB * CWT SGPRs) leave the allocator room, else one word
     const bool emit = g.planes_out != nullptr;
+    if constexpr (AB <= 4 && WB <= 2) {
+        // plane strides that are multiples of four words (384, 640 ... channels): chunks of four words
+        if (g.Cw % 4 == 0) {
+            if (emit) launch_kernel((conv_kernel<AB, WB, 0, 4, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
+            else launch_kernel((conv_kernel<AB, WB, 0, 4, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);
+            return launch_status();
+        }
+    }
     if (g.Cw == 1 || AB > 4) {
         if (emit) launch_kernel((conv_kernel<AB, WB, 0, 1, 9, 1, 1, true>), grid_for(g), dim3(256), 0, s, g);
         else launch_kernel((conv_kernel<AB, WB, 0, 1, 9, 1, 1, false>), grid_for(g), dim3(256), 0, s, g);

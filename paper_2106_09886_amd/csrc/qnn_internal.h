@@ -197,7 +197,8 @@ constexpr int conv_passes(int ab, int wb, int cw) {
         const ConvShapeV v = conv_shape(ab, wb, cw);
         return (cw / v.cwt) * (9 / v.tpc);
     }
-    const int cwt = (cw == 1 || ab > 4) ? 1 : 2;       // the runtime-stride kernels
+    // the runtime-stride kernels: chunks of four words where they divide the plane (up to W2A4), else two, else one
+    const int cwt = (ab <= 4 && wb <= 2 && cw % 4 == 0) ? 4 : (cw == 1 || ab > 4) ? 1 : 2;
     return (cw + cwt - 1) / cwt;
 }
 

@@ -44,6 +44,7 @@ CONV_CASES = [
     (1, 7, 5, 256, 40, 4, 2, 3),         # two chunk passes, partial sums in the workspace
     (1, 6, 6, 512, 130, 4, 2, 4),        # four chunk passes, three column tiles
     (1, 5, 6, 96, 64, 3, 3, 5),          # runtime plane stride
+    (1, 5, 6, 384, 70, 4, 2, 4),         # runtime plane stride of twelve words: chunks of four
     (1, 4, 4, 40, 20, 6, 2, 8),          # wide activations (unpipelined path), 8-bit result
     (1, 3, 10, 256, 64, 4, 3, 7),        # taps in separate chunks
     (3, 14, 14, 64, 64, 2, 2, 2),        # several wavefronts per image

@@ -250,7 +250,9 @@ def run_conv(q, oracle, X, Wt, ab, wb, s=None, packed_too=True):
 
 @pytest.mark.parametrize("shape", [(1, 1, 1, 3, 1), (2, 1, 5, 32, 3), (1, 4, 1, 33, 5), (2, 2, 2, 64, 64),
                                    (1, 3, 3, 7, 65), (3, 5, 6, 96, 70), (1, 7, 9, 128, 130),
-                                   (2, 6, 5, 256, 64), (1, 4, 4, 320, 10)])
+                                   (2, 6, 5, 256, 64), (1, 4, 4, 320, 10),
+                                   # plane strides of 12 and 20 words: runtime-stride kernel with four-word chunks
+                                   (2, 5, 7, 384, 70), (1, 6, 4, 640, 64)])
 @pytest.mark.parametrize("ab,wb", [(2, 2), (4, 3), (4, 2), (8, 2), (1, 1), (3, 5)])
 def test_conv_shapes(q, oracle, shape, ab, wb):
     Nb, H, W, C, Cout = shape
