@@ -31,10 +31,9 @@ struct BackArgs {
     int64_t ldg;
 };
 
-// A block of four wavefronts takes 32*RT rows x 128 columns of the output; wavefront v all rows
-// and the 32 columns of plane word 4*cb + v, so a decoded code feeds RT matrix instructions.
-// (A 2 x 2 arrangement of the wavefronts with two row tiles and two plane words each, which halves
-// what a block fetches, measured 5-20 % slower at 4096^3.)
+// Outputs of fewer than 512 tiles of 128 x 128 (larger ones take backward_gemm_lds_kernel below).
+// A block of four wavefronts takes 32*RT rows (RT = 1, 2) x 128 columns of the output; wavefront v
+// all rows and the 32 columns of plane word 4*cb + v, so a decoded code feeds RT matrix instructions.
 // One iteration takes eight reduction indices: lanes 0..31 hold j0..j0+3, lanes 32..63
 // j0+4..j0+7, and the u-th of four matrix instructions pairs j0+u with j0+4+u (any pairing is
 // right as long as both operands use it).
@@ -46,16 +45,16 @@ struct BackArgs {
 // GT: g is indexed [j][r] (gradient of the weights) instead of [r][j].
 // VEC (only without GT): J is a multiple of 8, ldg of 4 and g, scale are 16-byte aligned: the four
 // values of a lane are one 16-byte load.
-// SPLITJ (outputs of few tiles, long sums; RT = 1, 2): the block takes 32*RT rows x 32 columns and
+// SPLITJ (outputs of few tiles, long sums): the block takes 32*RT rows x 32 columns and
 // its four wavefronts a quarter of the sum each; the quarters meet in LDS and are added in a fixed order.
-// (Left to itself the compiler sizes the kernel for one wavefront per SIMD; for the smaller tiles
-// two to four resident wavefronts are asked for instead.)
+// (Left to itself the compiler sizes the kernel for one wavefront per SIMD; two to four resident
+// wavefronts are asked for instead.)
 template <int CB, int RT, bool GT, bool VEC, bool SPLITJ>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RT == 4 ? 1 : RT == 2 ? (CB >= 7 ? 2 : 3) : (CB >= 7 ? 3 : 4))))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RT == 2 ? (CB >= 7 ? 2 : 3) : (CB >= 7 ? 3 : 4))))
 void backward_gemm_kernel(const BackArgs a) {
     constexpr int NT = RT;                               // row tiles per wavefront
     constexpr int CT = 1;                                // plane words (32 columns each) per wavefront
-    static_assert(!SPLITJ || RT <= 2, "the split form has one plane word per block");
+    static_assert(RT == 1 || RT == 2, "larger tiles belong to the LDS-staged kernel");
     const int wave = (int)(threadIdx.x >> 6), lane = (int)(threadIdx.x & 63);
     const int half = lane >> 5, l5 = lane & 31;
     const int rb = (int)(blockIdx.x / (unsigned)a.col_blocks);
@@ -214,8 +213,10 @@ void backward_gemm_kernel(const BackArgs a) {
 // 132 words) in one of two LDS buffers; the next tile is loaded into registers before the matrix
 // instructions of the current one and written to the other buffer after them, one barrier per tile.
 // The plane words of a tile's 32 indices are loaded by lanes 0..31 (one index each) and handed out
-// per step with ds_bpermute (one instruction per plane; two v_readlane and a select measured slower).  A wavefront whose plane word lies past the last one still loads, stores
-// and waits with the others and only skips the products.
+// per step with ds_bpermute (one instruction per plane; two v_readlane and a select measured
+// slower).  A wavefront whose plane word lies past the last one still loads, stores and waits with
+// the others and only skips the products.  (Tried against this tile: a 2 x 2 arrangement of the
+// wavefronts with two row tiles and two plane words each, 5-20 % slower without the LDS stage.)
 // VEC: 16-byte loads (ldg, and J or R, multiples of 4; g and scale 16-byte aligned), else scalar loads.
 template <int CB, bool GT, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
