@@ -46,7 +46,9 @@ NOMINAL_CUS, NOMINAL_GHZ = 256, 2.4
 PEAK_LANE_OPS = NOMINAL_CUS * 64 * NOMINAL_GHZ * 1e9
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
-KERNEL_SOURCES = ("include/qnn.h", "paper_2106_09886_amd/csrc")
+# what the kernels with a stored traffic figure (branch GEMM / convolution) and their launch sizing are built from
+KERNEL_SOURCES = ("include/qnn.h", "paper_2106_09886_amd/csrc/qnn_branch.hip", "paper_2106_09886_amd/csrc/qnn_device_util.h",
+                  "paper_2106_09886_amd/csrc/qnn_internal.h", "paper_2106_09886_amd/csrc/qnn_api.hip")
 
 
 def device_peak(q):
@@ -67,7 +69,7 @@ def device_peak(q):
 
 
 def kernel_source_hash():
-    """sha256 over the kernel sources: ties a stored traffic figure to the code it was measured on."""
+    """sha256 over the sources of the measured kernels: ties a stored traffic figure to the code it was measured on."""
     h = hashlib.sha256()
     files = []
     for rel in KERNEL_SOURCES:
