@@ -259,3 +259,33 @@ def test_branch_gemm_backward_weight_many_tiles(q, oracle, M, N, K, ab, wb):
         assert (np.abs(got[k][filt] - want[k]) <= 2.0 ** k * bound).all()
         assert (got[k] == 2.0 ** k * got[0]).all()
     assert np.abs(want[0]).mean() > 100 * bound.mean()
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 64, 4096), (40, 2048, 4096), (70, 96, 130)])
+def test_branch_gemm_backward_unaligned_gradient(q, oracle, M, N, K):
+    """A gradient and a scale that are only 4-byte aligned (views one element into a buffer): the kernels
+    must fall back to scalar loads; sampled rows / filters against the oracle."""
+    import torch
+    say("backward unaligned", M, N, K)
+    ab = wb = 2
+    A, W, g, s, Ap, Wp = _backward_case(q, oracle, M, N, K, ab, wb, True, M * 3 + N)
+    gbuf = torch.empty(M * N + 1, dtype=torch.float32, device="cuda")
+    gd = gbuf[1:].view(M, N)
+    gd.copy_(dev(g))
+    sbuf = torch.empty(N + 1, dtype=torch.float32, device="cuda")
+    sd = sbuf[1:]
+    sd.copy_(dev(s))
+    assert gd.data_ptr() % 16 == 4 and sd.data_ptr() % 16 == 4
+    gs = np.abs(g.astype(np.float64)) * s.astype(np.float64)[None, :]
+    rows = np.unique(np.array([0, 33, M // 2, M - 1]))
+    got = host(q.branch_gemm_backward_input(gd, Wp, wb, K, ab, scale=sd)).astype(np.float64)
+    want = oracle.branch_backward_input(g[rows], s, W, ab, wb)
+    bound = _bound(g, s, gs[rows] @ np.abs(W.astype(np.float64)), N)
+    for m in range(ab):
+        assert (np.abs(got[m][rows] - want[m]) <= 2.0 ** m * bound).all()
+    filt = np.unique(np.array([0, 31, N // 2, N - 1]))
+    got = host(q.branch_gemm_backward_weight(gd, Ap, ab, K, wb, scale=sd)).astype(np.float64)
+    want = oracle.branch_backward_weight(g[:, filt], s[filt], A, ab, wb)
+    bound = _bound(g, s, gs[:, filt].T @ np.abs(A.astype(np.float64)), M)
+    for k in range(wb):
+        assert (np.abs(got[k][filt] - want[k]) <= 2.0 ** k * bound).all()
