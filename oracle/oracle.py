@@ -20,7 +20,7 @@ __all__ = [
     "conv2d", "conv2d_transposed", "conv_out_size", "encode_real",
     "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
     "encode_smooth", "encoder_backward", "binarize", "binarize_backward", "quantize_k", "quantize_k_backward",
-    "branch_backward_input", "branch_backward_weight", "update_sgd",
+    "branch_backward_input", "branch_backward_weight", "update_sgd", "update_adam",
 ]
 
 
@@ -89,6 +89,9 @@ def _L():
         lib.qnn_oracle_branch_backward_weight.restype = None
         lib.qnn_oracle_update_sgd.argtypes = [vp, vp, i64, ctypes.c_float]
         lib.qnn_oracle_update_sgd.restype = None
+        f32 = ctypes.c_float
+        lib.qnn_oracle_update_adam.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, i32]
+        lib.qnn_oracle_update_adam.restype = None
         lib.qnn_oracle_maxpool2x2.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.qnn_oracle_maxpool2x2.restype = None
         lib.qnn_oracle_round_odd.argtypes = [ctypes.c_float, i32]
@@ -363,3 +366,12 @@ def update_sgd(w, g, eta):
     g = np.ascontiguousarray(g, dtype=np.float32)
     _L().qnn_oracle_update_sgd(_p(w), _p(g), w.size, ctypes.c_float(eta))
     return w
+
+
+def update_adam(w, g, m, v, eta, b1, b2, eps, t):
+    """-> (w, m, v) after one Adam step (copies; binary32 throughout)."""
+    w, m, v = (np.array(a, dtype=np.float32, order="C", copy=True) for a in (w, m, v))
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    _L().qnn_oracle_update_adam(_p(w), _p(g), _p(m), _p(v), w.size, ctypes.c_float(eta), ctypes.c_float(b1),
+                                ctypes.c_float(b2), ctypes.c_float(eps), int(t))
+    return w, m, v

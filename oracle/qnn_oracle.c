@@ -470,3 +470,35 @@ void qnn_oracle_update_sgd(float *w, const float *g, int64_t n, float eta)
         w[i] = w[i] - step;
     }
 }
+
+/* Update(W, g, eta) with Adam, the other optimiser the text names (Kingma & Ba's update rule):
+ *     m <- b1 m + (1 - b1) g,   v <- b2 v + (1 - b2) g^2,
+ *     w <- w - eta * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).
+ * Every operation is one binary32 operation in the order written (IEEE multiply, add, divide and
+ * square root are correctly rounded, so a device that does the same steps gives the same bits);
+ * 1 - b1, 1 - b2 and the two bias corrections 1 - b^t are formed in double precision and rounded
+ * to binary32 once.  m, v, w are updated in place; t >= 1 is the step number.                   */
+void qnn_oracle_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float eta,
+                            float b1, float b2, float eps, int t)
+{
+    const float omb1 = (float)(1.0 - (double)b1), omb2 = (float)(1.0 - (double)b2);
+    const float bc1 = (float)(1.0 - pow((double)b1, (double)t)), bc2 = (float)(1.0 - pow((double)b2, (double)t));
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float a = b1 * m[i];
+        volatile float b = omb1 * g[i];
+        volatile float mn = a + b;
+        volatile float g2 = g[i] * g[i];
+        volatile float c = b2 * v[i];
+        volatile float d = omb2 * g2;
+        volatile float vn = c + d;
+        volatile float mh = mn / bc1;
+        volatile float vh = vn / bc2;
+        volatile float rt = sqrtf(vh);
+        volatile float den = rt + eps;
+        volatile float num = eta * mh;
+        volatile float step = num / den;
+        m[i] = mn;
+        v[i] = vn;
+        w[i] = w[i] - step;
+    }
+}

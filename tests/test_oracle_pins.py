@@ -706,6 +706,34 @@ def test_update_sgd_is_one_multiply_and_one_subtraction(oracle):
     assert (fused != want).any()            # the two readings differ on this input, so the pin separates them
 
 
+def test_update_adam_against_the_textbook_rule(oracle):
+    """Adam as the text's other choice for Update(): the float64 evaluation of the published rule (numpy)
+    within a few binary32 roundings, for several steps run one after the other; the first step from zero
+    moments moves every weight by eta against the sign of its gradient (|g| >> eps); a zero gradient with zero
+    moments moves nothing."""
+    r = rng(991)
+    n = 3000
+    w0 = r.normal(size=n).astype(np.float32)
+    eta, b1, b2, eps = 1e-3, 0.9, 0.999, 1e-8
+    w, m, v = w0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    wd, md, vd = w0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t in range(1, 6):
+        g = r.normal(size=n).astype(np.float32)
+        w, m, v = oracle.update_adam(w, g, m, v, eta, b1, b2, eps, t)
+        gd = g.astype(np.float64)
+        md = np.float32(b1) * md + (1 - np.float64(np.float32(b1))) * gd
+        vd = np.float32(b2) * vd + (1 - np.float64(np.float32(b2))) * gd * gd
+        wd = wd - np.float32(eta) * (md / (1 - np.float64(np.float32(b1)) ** t)) / (np.sqrt(vd / (1 - np.float64(np.float32(b2)) ** t)) + np.float32(eps))
+        assert np.abs(w - wd).max() <= 1e-5 * eta * t + 4e-7 * np.abs(wd).max()
+        assert np.abs(m - md).max() <= 1e-6 * (1 + np.abs(md).max()) and np.abs(v - vd).max() <= 1e-6 * (1 + np.abs(vd).max())
+    g = r.normal(size=n).astype(np.float32)
+    g[np.abs(g) < 1e-3] = 1.0
+    w1, _, _ = oracle.update_adam(w0, g, np.zeros(n, np.float32), np.zeros(n, np.float32), eta, b1, b2, eps, 1)
+    assert np.abs((w1.astype(np.float64) - w0) + eta * np.sign(g)).max() <= 1e-6
+    w2, m2, v2 = oracle.update_adam(w0, np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32), eta, b1, b2, eps, 3)
+    assert (w2 == w0).all() and (m2 == 0).all() and (v2 == 0).all()
+
+
 def test_speedup_model_reading(oracle):
     """Eq. (16) with the constants of Sec. 5.4 (gamma = 1.91, L = 64, beta = gamma / 2) at N = 8192
     reproduces the printed 2-bit figure; this is the reading quoted as context beside the measured
