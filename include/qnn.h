@@ -285,6 +285,16 @@ qnn_status qnn_branch_gemm_backward_input(const float *g_out, const float *scale
 qnn_status qnn_branch_gemm_backward_weight(const float *g_out, const float *scale, const uint32_t *A, int ab,
                                            int64_t M, int64_t N, int64_t K, int wb, float *g_wb, void *stream);
 qnn_status qnn_update_sgd(float *w, const float *g, int64_t n, float lr, void *stream);
+/*
+ * qnn_update_adam   the same Update() with Adam (the text's other choice; Kingma & Ba's rule), in place:
+ *   m <- beta1 m + (1 - beta1) g,  v <- beta2 v + (1 - beta2) g^2,
+ *   w <- w - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps),
+ *   every operation one correctly rounded binary32 operation in the order written; 1 - beta and the two
+ *   bias corrections are formed in double precision on the host and rounded once.  w, g, m, v fp32 [n];
+ *   step >= 1, 0 <= beta1, beta2 < 1, eps >= 0 (else QNN_EINVAL).
+ */
+qnn_status qnn_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float lr, float beta1, float beta2,
+                           float eps, int step, void *stream);
 
 /*
  * Chained layers (Alg. 1 forward as one kernel: branch sum, scale, re-encode).  The *_requant

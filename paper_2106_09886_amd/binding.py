@@ -26,7 +26,7 @@ EXPORTS = (
     "qnn_requant_workspace_bytes", "qnn_branch_gemm_requant", "qnn_conv2d_packed_requant",
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
     "qnn_encode_real", "qnn_encoder_backward", "qnn_binarize", "qnn_binarize_backward", "qnn_quantize_k",
-    "qnn_quantize_k_backward", "qnn_branch_gemm_backward_input", "qnn_branch_gemm_backward_weight", "qnn_update_sgd",
+    "qnn_quantize_k_backward", "qnn_branch_gemm_backward_input", "qnn_branch_gemm_backward_weight", "qnn_update_sgd", "qnn_update_adam",
     "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
     "qnn_compare_dot4_gemm",
     "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
@@ -138,6 +138,9 @@ def lib():
     L.qnn_branch_gemm_backward_weight.restype = i32
     L.qnn_update_sgd.argtypes = [vp, vp, i64, ctypes.c_float, vp]
     L.qnn_update_sgd.restype = i32
+    f32 = ctypes.c_float
+    L.qnn_update_adam.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, i32, vp]
+    L.qnn_update_adam.restype = i32
     gp = ctypes.POINTER(ConvGeometry)
     L.qnn_conv2d_general_output_size.argtypes = [i64, i64, gp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.qnn_conv2d_general_output_size.restype = i32
@@ -527,6 +530,15 @@ def update_sgd(w, g, lr):
     _dev(w, torch.float32, "w")
     _dev(g, torch.float32, "g")
     _check(lib().qnn_update_sgd(_ptr(w), _ptr(g), w.numel(), ctypes.c_float(lr), _stream()), "qnn_update_sgd")
+    return w
+
+
+def update_adam(w, g, m, v, lr, beta1, beta2, eps, step):
+    """In place: one Adam step on (w, m, v)."""
+    for t, name in ((w, "w"), (g, "g"), (m, "m"), (v, "v")):
+        _dev(t, torch.float32, name)
+    _check(lib().qnn_update_adam(_ptr(w), _ptr(g), _ptr(m), _ptr(v), w.numel(), ctypes.c_float(lr), ctypes.c_float(beta1),
+                                 ctypes.c_float(beta2), ctypes.c_float(eps), int(step), _stream()), "qnn_update_adam")
     return w
 
 

@@ -691,6 +691,19 @@ qnn_status qnn_branch_gemm_backward_weight(const float *g_out, const float *scal
                                          g_wb, (hipStream_t)stream));
 }
 
+qnn_status qnn_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float lr, float beta1, float beta2,
+                           float eps, int step, void *stream) {
+    if (n < 0 || step < 1 || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps >= 0.0f))
+        return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (w == nullptr || g == nullptr || m == nullptr || v == nullptr) return QNN_EINVAL;
+    if (!aligned4(w) || !aligned4(g) || !aligned4(m) || !aligned4(v)) return QNN_EALIGN;
+    const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
+    const float bc1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    const float bc2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    return from_hip(launch_update_adam(w, g, m, v, n, lr, beta1, beta2, omb1, omb2, bc1, bc2, eps, (hipStream_t)stream));
+}
+
 qnn_status qnn_update_sgd(float *w, const float *g, int64_t n, float lr, void *stream) {
     if (n < 0) return QNN_EINVAL;
     if (n == 0) return QNN_OK;

@@ -441,6 +441,25 @@ __global__ __launch_bounds__(256) void update_sgd_kernel(float *__restrict__ w, 
         w[i] = __fsub_rn(w[i], __fmul_rn(lr, g[i]));
 }
 
+// Adam: every step one correctly rounded binary32 operation, in this order (the CPU reference does the same)
+__global__ __launch_bounds__(256) void update_adam_kernel(float *__restrict__ w, const float *__restrict__ g, float *__restrict__ m,
+                                                           float *__restrict__ v, int64_t n, float lr, float b1, float b2,
+                                                           float omb1, float omb2, float bc1, float bc2, float eps) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const float gi = g[i];
+        const float mn = __fadd_rn(__fmul_rn(b1, m[i]), __fmul_rn(omb1, gi));
+        const float vn = __fadd_rn(__fmul_rn(b2, v[i]), __fmul_rn(omb2, __fmul_rn(gi, gi)));
+        // plain division and sqrtf: correctly rounded in this compiler's default mode for device code (the
+        // __fdiv_rn / __fsqrt_rn intrinsics map to the approximate hardware operations unless the math
+        // library is built with rounded operations)
+        const float mh = mn / bc1, vh = vn / bc2;
+        const float step = __fmul_rn(lr, mh) / __fadd_rn(sqrtf(vh), eps);
+        m[i] = mn;
+        v[i] = vn;
+        w[i] = __fsub_rn(w[i], step);
+    }
+}
+
 }  // namespace
 
 // out[p][r][c] = 2^p sum_j G(r, j) code[j][c]; towards_weights selects G(r, j) = g[j][r] scale[r],
@@ -461,6 +480,15 @@ hipError_t launch_update_sgd(float *w, const float *g, int64_t n, float lr, hipS
     const int64_t want = (n + 255) / 256;
     const int64_t cap = (int64_t)device_simd_count() * 16;
     launch_kernel(update_sgd_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, s, w, g, n, lr);
+    return launch_status();
+}
+
+hipError_t launch_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float lr, float b1, float b2,
+                              float omb1, float omb2, float bc1, float bc2, float eps, hipStream_t s) {
+    const int64_t want = (n + 255) / 256;
+    const int64_t cap = (int64_t)device_simd_count() * 16;
+    launch_kernel(update_adam_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, s, w, g, m, v, n, lr, b1, b2,
+                  omb1, omb2, bc1, bc2, eps);
     return launch_status();
 }
 

@@ -332,6 +332,8 @@ hipError_t launch_quantize_k_backward(const float *x, const float *g_q, int64_t 
 hipError_t launch_backward_gemm(const float *g, int64_t ldg, const float *scale, const uint32_t *planes, int code_bits,
                                 int R, int J, int C, int P, bool towards_weights, float *out, hipStream_t);
 hipError_t launch_update_sgd(float *w, const float *g, int64_t n, float lr, hipStream_t);
+hipError_t launch_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float lr, float b1, float b2,
+                              float omb1, float omb2, float bc1, float bc2, float eps, hipStream_t);
 hipError_t launch_pool_planes(const uint32_t *planes, int64_t Nb, int64_t Ho, int64_t Wo, int64_t Cw, int bits,
                               uint32_t *out, hipStream_t);
 hipError_t launch_mfma_arrange(const int8_t *codes, int64_t rows, int64_t K, void *out, hipStream_t);

@@ -330,3 +330,10 @@ def test_backward_product_argument_errors(L):
     f = L.qnn_update_sgd
     assert f(P, P, -1, 0.1, None) == QNN_EINVAL and f(None, P, 4, 0.1, None) == QNN_EINVAL and f(P, None, 4, 0.1, None) == QNN_EINVAL
     assert f(P + 2, P, 4, 0.1, None) == QNN_EALIGN and f(None, None, 0, 0.1, None) == QNN_OK
+    f = L.qnn_update_adam
+    ok = (0.001, 0.9, 0.999, 1e-8, 1, None)
+    assert f(P, P, P, P, -1, *ok) == QNN_EINVAL and f(None, P, P, P, 4, *ok) == QNN_EINVAL and f(P, P, None, P, 4, *ok) == QNN_EINVAL
+    assert f(P, P, P, P, 4, 0.001, 0.9, 0.999, 1e-8, 0, None) == QNN_EINVAL           # steps count from one
+    assert f(P, P, P, P, 4, 0.001, 1.0, 0.999, 1e-8, 1, None) == QNN_EINVAL and f(P, P, P, P, 4, 0.001, 0.9, -0.1, 1e-8, 1, None) == QNN_EINVAL
+    assert f(P, P, P, P, 4, 0.001, 0.9, 0.999, -1.0, 1, None) == QNN_EINVAL
+    assert f(P, P, P + 2, P, 4, *ok) == QNN_EALIGN and f(None, None, None, None, 0, *ok) == QNN_OK

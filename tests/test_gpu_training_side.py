@@ -289,3 +289,19 @@ def test_branch_gemm_backward_unaligned_gradient(q, oracle, M, N, K):
     bound = _bound(g, s, gs[:, filt].T @ np.abs(A.astype(np.float64)), M)
     for k in range(wb):
         assert (np.abs(got[k][filt] - want[k]) <= 2.0 ** k * bound).all()
+
+
+@pytest.mark.parametrize("n", [1, 257, 100003])
+def test_update_adam(q, oracle, n):
+    """Five Adam steps in a row, bit for bit: both sides take the same sequence of correctly rounded binary32
+    operations (including a gradient of zero and tiny second moments)."""
+    rng = np.random.default_rng(n + 17)
+    w = rng.normal(size=n).astype(np.float32)
+    m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    wd, md, vd = dev(w), dev(m), dev(v)
+    for t in range(1, 6):
+        g = (rng.normal(size=n) * 10.0 ** rng.integers(-6, 2)).astype(np.float32)
+        g[:: 7] = 0.0
+        w, m, v = oracle.update_adam(w, g, m, v, 1e-3, 0.9, 0.999, 1e-8, t)
+        q.update_adam(wd, dev(g), md, vd, 1e-3, 0.9, 0.999, 1e-8, t)
+        assert (host(md) == m).all() and (host(vd) == v).all() and (host(wd) == w).all()
