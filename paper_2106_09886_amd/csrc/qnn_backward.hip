@@ -31,7 +31,8 @@ struct BackArgs {
     int64_t ldg;
 };
 
-// Outputs of fewer than 512 tiles of 128 x 128 (larger ones take backward_gemm_lds_kernel below).
+// Small outputs with short sums (fewer than 512 tiles of 128 x 128 and sums under 256 terms; the
+// others take the two LDS-staged kernels below).
 // A block of four wavefronts takes 32*RT rows (RT = 1, 2) x 128 columns of the output; wavefront v
 // all rows and the 32 columns of plane word 4*cb + v, so a decoded code feeds RT matrix instructions.
 // One iteration takes eight reduction indices: lanes 0..31 hold j0..j0+3, lanes 32..63
@@ -45,11 +46,9 @@ struct BackArgs {
 // GT: g is indexed [j][r] (gradient of the weights) instead of [r][j].
 // VEC (only without GT): J is a multiple of 8, ldg of 4 and g, scale are 16-byte aligned: the four
 // values of a lane are one 16-byte load.
-// SPLITJ (outputs of few tiles, long sums): the block takes 32*RT rows x 32 columns and
-// its four wavefronts a quarter of the sum each; the quarters meet in LDS and are added in a fixed order.
 // (Left to itself the compiler sizes the kernel for one wavefront per SIMD; two to four resident
 // wavefronts are asked for instead.)
-template <int CB, int RT, bool GT, bool VEC, bool SPLITJ>
+template <int CB, int RT, bool GT, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RT == 2 ? (CB >= 7 ? 2 : 3) : (CB >= 7 ? 3 : 4))))
 void backward_gemm_kernel(const BackArgs a) {
     constexpr int NT = RT;                               // row tiles per wavefront
@@ -60,15 +59,9 @@ void backward_gemm_kernel(const BackArgs a) {
     const int rb = (int)(blockIdx.x / (unsigned)a.col_blocks);
     const int cb = (int)(blockIdx.x - (unsigned)rb * (unsigned)a.col_blocks);
     const int r0 = rb * (32 * RT);
-    const int cw0 = SPLITJ ? cb : cb * 4 + wave;
-    if (!SPLITJ && (cw0 >= a.Cw || r0 >= a.R)) return;   // (no barrier without SPLITJ; with it both hold always)
-    // the wavefront's part of the sum
-    int jbeg = 0, jend = a.J;
-    if constexpr (SPLITJ) {
-        const int quarter = ((a.J + 31) / 32) * 8;       // a multiple of 8
-        jbeg = min(a.J, wave * quarter);
-        jend = min(a.J, jbeg + quarter);
-    }
+    const int cw0 = cb * 4 + wave;
+    if (cw0 >= a.Cw || r0 >= a.R) return;                // (no barrier in this kernel)
+    const int jbeg = 0, jend = a.J;
     f32x16 acc[NT][CT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -180,28 +173,12 @@ void backward_gemm_kernel(const BackArgs a) {
             }
         }
     };
-    if constexpr (SPLITJ) {
-        __shared__ float part[4][NT][16][64];
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) part[wave][t][v][lane] = acc[t][0][v];
-        __syncthreads();
+        for (int c = 0; c < CT; ++c)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int v = wave * 4 + k;              // a quarter of the tile's registers per wavefront
-                store(t, 0, v, ((part[0][t][v][lane] + part[1][t][v][lane]) + part[2][t][v][lane]) + part[3][t][v][lane]);
-            }
-    } else {
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int c = 0; c < CT; ++c)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) store(t, c, v, acc[t][c][v]);
-    }
+            for (int v = 0; v < 16; ++v) store(t, c, v, acc[t][c][v]);
 }
 
 // Outputs of many tiles: the same block tile (128 rows x 128 columns, wavefront v the columns of
@@ -318,18 +295,8 @@ void backward_gemm_lds_kernel(const BackArgs a) {
         }
     };
     auto compute = [&](const uint32_t (&pw)[CB], int buf) {
-        float an[4];                                     // the real operand of the next step, read a step ahead
-#pragma unroll
-        for (int t = 0; t < 4; ++t) an[t] = tile[buf][half][t * 32 + l5];
-#pragma unroll
-        for (int s = 0; s < KT / 2; ++s) {
-            float ac[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) ac[t] = an[t];
-            if (s + 1 < KT / 2) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) an[t] = tile[buf][2 * (s + 1) + half][t * 32 + l5];
-            }
+        // both operands of a step are fetched a step ahead: the real one from LDS, the code through ds_bpermute
+        auto code = [&](int s) {
             uint32_t bits = 0;
 #pragma unroll
             for (int q = 0; q < CB; ++q) {
@@ -337,9 +304,24 @@ void backward_gemm_lds_kernel(const BackArgs a) {
                 const uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((2 * s + half) << 2, (int)pw[q]);
                 bits |= ((w >> l5) & 1u) << q;
             }
-            const float bv = (float)(2 * (int)bits - kOffset);
+            return (float)(2 * (int)bits - kOffset);
+        };
+        float an[4], bn = code(0);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bv, acc[t], 0, 0, 0);
+        for (int t = 0; t < 4; ++t) an[t] = tile[buf][half][t * 32 + l5];
+#pragma unroll
+        for (int s = 0; s < KT / 2; ++s) {
+            float ac[4];
+            const float bc = bn;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ac[t] = an[t];
+            if (s + 1 < KT / 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) an[t] = tile[buf][2 * (s + 1) + half][t * 32 + l5];
+                bn = code(s + 1);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bc, acc[t], 0, 0, 0);
         }
     };
     if (a.J > 0) {
@@ -382,15 +364,198 @@ void backward_gemm_lds_kernel(const BackArgs a) {
         }
 }
 
-template <int CB, int RT, bool GT, bool SPLITJ>
+// Outputs of few tiles with long sums, staged through LDS: the block takes 32*RT rows x 32 columns
+// (one plane word) and its four wavefronts a quarter of the sum each (four times the wavefronts of a
+// tile per block, deterministic: no atomics); every wavefront brings its part of the real operand
+// in through LDS in tiles of 32 indices
+// (whole cache lines per load, [index][row] with a row stride of 32*RT + 4 words, two buffers, one
+// barrier per tile: all wavefronts make the same number of passes, those past the end of the sum
+// stage zeros).  The four partial tiles are then added in LDS in a fixed order.
+template <int CB, int RT, bool GT, bool VEC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void backward_gemm_split_lds_kernel(const BackArgs a) {
+    constexpr int KT = 32, ROWS = 32 * RT, LD = ROWS + 4, PIECES = 4 * RT;
+    constexpr int TILE_WORDS = 2 * 4 * KT * LD, PART_WORDS = 4 * RT * 16 * 64;
+    __shared__ __attribute__((aligned(16))) float lds[TILE_WORDS > PART_WORDS ? TILE_WORDS : PART_WORDS];
+    const int wave = (int)(threadIdx.x >> 6), lane = (int)(threadIdx.x & 63);
+    const int half = lane >> 5, l5 = lane & 31;
+    const int rb = (int)(blockIdx.x / (unsigned)a.col_blocks);
+    const int cw = (int)(blockIdx.x - (unsigned)rb * (unsigned)a.col_blocks);      // < Cw always
+    const int r0 = rb * ROWS;
+    const bool has_scale = a.scale != nullptr;
+    constexpr int kOffset = (1 << CB) - 1;
+    const int quarter = ((a.J + 4 * KT - 1) / (4 * KT)) * KT;                       // a multiple of 32
+    const int jbeg = min(a.J, wave * quarter), jend = min(a.J, jbeg + quarter);
+    auto tile = [&](int buf, int j, int r) -> float & { return lds[((buf * 4 + wave) * KT + j) * LD + r]; };
+    f32x16 acc[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+    // this lane's part of a tile: PIECES pieces of four values
+    //   !GT: piece i = row r0 + lane / 8 + 8 i, indices j0 + 4 (lane % 8) .. + 3
+    //    GT: piece i = index j0 + lane / (8 RT) + (8 / RT) i, rows r0 + 4 (lane % (8 RT)) .. + 3
+    struct Regs {
+        f32x4 v[PIECES];
+        f32x4 sc;
+        uint32_t pw[CB];
+    };
+    f32x4 srow = {1.0f, 1.0f, 1.0f, 1.0f};
+    if constexpr (GT) {
+        if (has_scale) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) srow[e] = a.scale[min(r0 + 4 * (lane % (8 * RT)) + e, a.R - 1)];
+        }
+    }
+    const int jlast = max(jend - 1, 0);                                              // a valid index for clamped loads
+    auto load = [&](int j0, Regs &rg) {
+        {
+            const int jc = min(j0 + l5, jlast);
+#pragma unroll
+            for (int q = 0; q < CB; ++q) rg.pw[q] = a.planes[((int64_t)jc * CB + q) * a.Cw + cw];
+        }
+        if constexpr (!GT) {
+            const int jp = j0 + 4 * (lane & 7);
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                const int row = min(r0 + (lane >> 3) + 8 * i, a.R - 1);
+                if constexpr (VEC) {
+                    rg.v[i] = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)row * a.ldg + min(jp, a.J - 4));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rg.v[i][e] = a.g[(int64_t)row * a.ldg + min(jp + e, a.J - 1)];
+                }
+            }
+            if constexpr (VEC) {
+                const float *sp = has_scale ? a.scale + min(jp, a.J - 4) : a.g;
+                rg.sc = *reinterpret_cast<const f32x4 *>(sp);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rg.sc[e] = has_scale ? a.scale[min(jp + e, a.J - 1)] : 1.0f;
+            }
+        } else {
+            const int rp = r0 + 4 * (lane % (8 * RT));
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                const int j = min(j0 + lane / (8 * RT) + (8 / RT) * i, a.J - 1);
+                if constexpr (VEC) {
+                    rg.v[i] = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)j * a.ldg + min(rp, a.R - 4));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rg.v[i][e] = a.g[(int64_t)j * a.ldg + min(rp + e, a.R - 1)];
+                }
+            }
+        }
+    };
+    // registers -> LDS [index][row], scaled; indices past the wavefront's part of the sum become zero
+    auto stage = [&](int j0, const Regs &rg, int buf) {
+        if constexpr (!GT) {
+            const int jl = 4 * (lane & 7);
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                const int rl = (lane >> 3) + 8 * i;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float s = has_scale ? rg.sc[e] : 1.0f;
+                    tile(buf, jl + e, rl) = (j0 + jl + e < jend) ? rg.v[i][e] * s : 0.0f;
+                }
+            }
+        } else {
+            const int rl = 4 * (lane % (8 * RT));
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                const int jl = lane / (8 * RT) + (8 / RT) * i;
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (j0 + jl < jend) ? rg.v[i][e] * srow[e] : 0.0f;
+                *reinterpret_cast<f32x4 *>(&tile(buf, jl, rl)) = o;
+            }
+        }
+    };
+    auto compute = [&](const uint32_t (&pw)[CB], int buf) {
+        auto code = [&](int s) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int q = 0; q < CB; ++q) {
+                const uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((2 * s + half) << 2, (int)pw[q]);
+                bits |= ((w >> l5) & 1u) << q;
+            }
+            return (float)(2 * (int)bits - kOffset);
+        };
+        float an[RT], bn = code(0);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) an[t] = tile(buf, half, t * 32 + l5);
+#pragma unroll
+        for (int s = 0; s < KT / 2; ++s) {
+            float ac[RT];
+            const float bc = bn;
+#pragma unroll
+            for (int t = 0; t < RT; ++t) ac[t] = an[t];
+            if (s + 1 < KT / 2) {
+#pragma unroll
+                for (int t = 0; t < RT; ++t) an[t] = tile(buf, 2 * (s + 1) + half, t * 32 + l5);
+                bn = code(s + 1);
+            }
+#pragma unroll
+            for (int t = 0; t < RT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bc, acc[t], 0, 0, 0);
+        }
+    };
+    if (quarter > 0) {
+        Regs rg;
+        uint32_t pw_cur[CB];
+        load(jbeg, rg);
+        stage(jbeg, rg, 0);
+#pragma unroll
+        for (int q = 0; q < CB; ++q) pw_cur[q] = rg.pw[q];
+        __syncthreads();
+        int buf = 0;
+        for (int k = 0; k < quarter; k += KT) {                                      // the same count in every wavefront
+            const bool more = k + KT < quarter;
+            if (more) load(jbeg + k + KT, rg);
+            compute(pw_cur, buf);
+            if (more) {
+                stage(jbeg + k + KT, rg, buf ^ 1);
+#pragma unroll
+                for (int q = 0; q < CB; ++q) pw_cur[q] = rg.pw[q];
+            }
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    // the four partial tiles meet in LDS (the tile buffers are free after the last barrier)
+    float *part = lds;
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) part[((wave * RT + t) * 16 + v) * 64 + lane] = acc[t][v];
+    __syncthreads();
+    const int col = cw * 32 + l5;
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int v = wave * 4 + k;                  // a quarter of the tile's registers per wavefront
+            auto at = [&](int w) { return part[((w * RT + t) * 16 + v) * 64 + lane]; };
+            float val = ((at(0) + at(1)) + at(2)) + at(3);
+            const int row = r0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+            if (row < a.R && col < a.C) {
+                for (int p = 0; p < a.P; ++p) {
+                    a.out[((int64_t)p * a.R + row) * a.C + col] = val;
+                    val *= 2.0f;                          // exact
+                }
+            }
+        }
+}
+
+template <int CB, int RT, bool GT>
 void launch_one(const BackArgs &a, bool vec, dim3 grid, hipStream_t s) {
     if constexpr (!GT) {
         if (vec) {
-            launch_kernel((backward_gemm_kernel<CB, RT, false, true, SPLITJ>), grid, dim3(256), 0, s, a);
+            launch_kernel((backward_gemm_kernel<CB, RT, false, true>), grid, dim3(256), 0, s, a);
             return;
         }
     }
-    launch_kernel((backward_gemm_kernel<CB, RT, GT, false, SPLITJ>), grid, dim3(256), 0, s, a);
+    launch_kernel((backward_gemm_kernel<CB, RT, GT, false>), grid, dim3(256), 0, s, a);
 }
 
 template <int CB, bool GT>
@@ -401,21 +566,26 @@ hipError_t launch_cb(BackArgs a, bool vec, hipStream_t s) {
     auto blocks = [&](int rt, int words) { return ((int64_t)a.R + 32 * rt - 1) / (32 * rt) * ((a.Cw + words - 1) / words); };
     const bool split = blocks(1, 4) < want && a.J >= 256;
     int rt;
-    if (split) rt = blocks(2, 1) >= want ? 2 : 1;
+    if (split) rt = blocks(2, 1) >= want ? 2 : 1;           // (32-row tiles throughout measured 13 % slower on 256 x 4096 x 4096)
     else rt = blocks(4, 4) >= want ? 4 : blocks(2, 4) >= want ? 2 : 1;
     a.col_blocks = split ? a.Cw : (a.Cw + 3) / 4;
     const int64_t nb = blocks(rt, split ? 1 : 4);
     if (nb > 0x7fffffff) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nb);
     if (split) {
-        if (rt == 2) launch_one<CB, 2, GT, true>(a, vec, grid, s);
-        else launch_one<CB, 1, GT, true>(a, vec, grid, s);
+        if (rt == 2) {
+            if (a.lds_vec) launch_kernel((backward_gemm_split_lds_kernel<CB, 2, GT, true>), grid, dim3(256), 0, s, a);
+            else launch_kernel((backward_gemm_split_lds_kernel<CB, 2, GT, false>), grid, dim3(256), 0, s, a);
+        } else {
+            if (a.lds_vec) launch_kernel((backward_gemm_split_lds_kernel<CB, 1, GT, true>), grid, dim3(256), 0, s, a);
+            else launch_kernel((backward_gemm_split_lds_kernel<CB, 1, GT, false>), grid, dim3(256), 0, s, a);
+        }
     } else {
         if (rt == 4) {
             if (a.lds_vec) launch_kernel((backward_gemm_lds_kernel<CB, GT, true>), grid, dim3(256), 0, s, a);
             else launch_kernel((backward_gemm_lds_kernel<CB, GT, false>), grid, dim3(256), 0, s, a);
-        } else if (rt == 2) launch_one<CB, 2, GT, false>(a, vec, grid, s);
-        else launch_one<CB, 1, GT, false>(a, vec, grid, s);
+        } else if (rt == 2) launch_one<CB, 2, GT>(a, vec, grid, s);
+        else launch_one<CB, 1, GT>(a, vec, grid, s);
     }
     return launch_status();
 }
