@@ -21,6 +21,7 @@ __all__ = [
     "branch_dot", "scale_f64", "scale_f32", "maxpool2x2", "round_odd", "requant",
     "encode_smooth", "encoder_backward", "binarize", "binarize_backward", "quantize_k", "quantize_k_backward",
     "branch_backward_input", "branch_backward_weight", "update_sgd", "update_adam",
+    "conv3x3_backward_input", "conv3x3_backward_weight",
 ]
 
 
@@ -89,6 +90,11 @@ def _L():
         lib.qnn_oracle_branch_backward_weight.restype = None
         lib.qnn_oracle_update_sgd.argtypes = [vp, vp, i64, ctypes.c_float]
         lib.qnn_oracle_update_sgd.restype = None
+        cb_args = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, vp]
+        lib.qnn_oracle_conv3x3_backward_input.argtypes = cb_args
+        lib.qnn_oracle_conv3x3_backward_input.restype = None
+        lib.qnn_oracle_conv3x3_backward_weight.argtypes = cb_args
+        lib.qnn_oracle_conv3x3_backward_weight.restype = None
         f32 = ctypes.c_float
         lib.qnn_oracle_update_adam.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, i32]
         lib.qnn_oracle_update_adam.restype = None
@@ -375,3 +381,30 @@ def update_adam(w, g, m, v, eta, b1, b2, eps, t):
     _L().qnn_oracle_update_adam(_p(w), _p(g), _p(m), _p(v), w.size, ctypes.c_float(eta), ctypes.c_float(b1),
                                 ctypes.c_float(b2), ctypes.c_float(eps), int(t))
     return w, m, v
+
+
+def conv3x3_backward_input(g_a, s, Wt, xb, wb):
+    """Alg. 1 backward through a 3x3 / stride 1 / pad 1 convolution, towards the activations.
+    g_a fp32 [Nb][H][W][O], s fp32 [O] or None, Wt codes [O][3][3][C] -> float64 [xb][Nb][H][W][C]."""
+    g_a = np.ascontiguousarray(g_a, dtype=np.float32)
+    Wt = _codes(Wt)
+    Nb, H, W, O = g_a.shape
+    C = Wt.shape[3]
+    assert Wt.shape[:3] == (O, 3, 3)
+    sp = None if s is None else np.ascontiguousarray(s, dtype=np.float32)
+    out = np.zeros((xb, Nb, H, W, C), dtype=np.float64)
+    _L().qnn_oracle_conv3x3_backward_input(_p(g_a), None if sp is None else _p(sp), _p(Wt), Nb, H, W, C, O, int(xb), int(wb), _p(out))
+    return out
+
+
+def conv3x3_backward_weight(g_a, s, X, xb, wb):
+    """... towards the binary weights.  X codes [Nb][H][W][C] -> float64 [wb][O][3][3][C]."""
+    g_a = np.ascontiguousarray(g_a, dtype=np.float32)
+    X = _codes(X)
+    Nb, H, W, O = g_a.shape
+    C = X.shape[3]
+    assert X.shape[:3] == (Nb, H, W)
+    sp = None if s is None else np.ascontiguousarray(s, dtype=np.float32)
+    out = np.zeros((wb, O, 3, 3, C), dtype=np.float64)
+    _L().qnn_oracle_conv3x3_backward_weight(_p(g_a), None if sp is None else _p(sp), _p(X), Nb, H, W, C, O, int(xb), int(wb), _p(out))
+    return out

@@ -502,3 +502,70 @@ void qnn_oracle_update_adam(float *w, const float *g, float *m, float *v, int64_
         w[i] = w[i] - step;
     }
 }
+
+/* ---- Alg. 1, backward lines through the multi-branch product of a 3x3 convolution -------------
+ * Forward (stride 1, zero padding 1, NHWC): a[n,h,w,o] = s[o] * sum_{m,k} 2^(m+k-2) sum_{kh,kw,c}
+ * x^{mb}[n,h+kh-1,w+kw-1,c] W^{kb}[o,kh,kw,c], positions outside the image contributing nothing.
+ * Backward, with g_ahat = s * g_a and backward() of a product = incoming gradient times the other
+ * operand, summed over every output position the element took part in:
+ *   g_{x^{mb}}[n,h,w,c]   = sum_k 2^(m+k-2) sum_{kh,kw,o} g_ahat[n,h-(kh-1),w-(kw-1),o] W^{kb}[o,kh,kw,c]
+ *   g_{W^{kb}}[o,kh,kw,c] = sum_m 2^(m+k-2) sum_{n,h,w}   g_ahat[n,h,w,o] x^{mb}[n,h+kh-1,w+kw-1,c]
+ * (terms whose image position does not exist are absent).  X codes [Nb][H][W][C] of xb bits, Wt
+ * codes [O][3][3][C] of wb bits, g_a fp32 [Nb][H][W][O]; outputs double [xb][Nb][H][W][C] and
+ * [wb][O][3][3][C].                                                                             */
+void qnn_oracle_conv3x3_backward_input(const float *g_a, const float *s, const int16_t *Wt, int64_t Nb, int64_t H,
+                                       int64_t W, int64_t C, int64_t O, int xb, int wb, double *g_bits)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t pix = 0; pix < Nb * H * W; ++pix) {
+        const int64_t n = pix / (H * W), h = (pix / W) % H, w = pix % W;
+        for (int64_t c = 0; c < C; ++c)
+            for (int m = 1; m <= xb; ++m) {
+                double acc = 0.0;
+                for (int k = 1; k <= wb; ++k) {
+                    double back = 0.0;
+                    for (int kh = 0; kh < 3; ++kh)
+                        for (int kw = 0; kw < 3; ++kw) {
+                            const int64_t oh = h - (kh - 1), ow = w - (kw - 1);     /* the output that read this pixel through (kh,kw) */
+                            if (oh < 0 || oh >= H || ow < 0 || ow >= W) continue;
+                            for (int64_t o = 0; o < O; ++o) {
+                                int8_t e[8];
+                                qnn_oracle_encode(Wt[((o * 3 + kh) * 3 + kw) * C + c], wb, e);
+                                const double g_ahat = (double)g_a[((n * H + oh) * W + ow) * O + o] * (s ? (double)s[o] : 1.0);
+                                back += g_ahat * (double)e[k - 1];
+                            }
+                        }
+                    acc += (double)((int64_t)1 << (m + k - 2)) * back;
+                }
+                g_bits[((int64_t)(m - 1) * Nb * H * W + pix) * C + c] = acc;
+            }
+    }
+}
+
+void qnn_oracle_conv3x3_backward_weight(const float *g_a, const float *s, const int16_t *X, int64_t Nb, int64_t H,
+                                        int64_t W, int64_t C, int64_t O, int xb, int wb, double *g_wb)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < O; ++o)
+        for (int kh = 0; kh < 3; ++kh)
+            for (int kw = 0; kw < 3; ++kw)
+                for (int64_t c = 0; c < C; ++c)
+                    for (int k = 1; k <= wb; ++k) {
+                        double acc = 0.0;
+                        for (int m = 1; m <= xb; ++m) {
+                            double back = 0.0;
+                            for (int64_t n = 0; n < Nb; ++n)
+                                for (int64_t h = 0; h < H; ++h)
+                                    for (int64_t w = 0; w < W; ++w) {
+                                        const int64_t ih = h + kh - 1, iw = w + kw - 1;
+                                        if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                                        int8_t e[8];
+                                        qnn_oracle_encode(X[((n * H + ih) * W + iw) * C + c], xb, e);
+                                        const double g_ahat = (double)g_a[((n * H + h) * W + w) * O + o] * (s ? (double)s[o] : 1.0);
+                                        back += g_ahat * (double)e[m - 1];
+                                    }
+                            acc += (double)((int64_t)1 << (m + k - 2)) * back;
+                        }
+                        g_wb[((int64_t)(k - 1) * O + o) * 9 * C + (kh * 3 + kw) * C + c] = acc;
+                    }
+}

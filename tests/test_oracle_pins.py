@@ -693,6 +693,44 @@ def test_branch_backward_closed_form_on_codes(oracle, xb, wb):
             assert np.abs(gw[k] - 2.0 ** k * base_w).max() <= 1e-9 * (1 + np.abs(base_w).max() * 2.0 ** k)
 
 
+@pytest.mark.parametrize("xb,wb", [(1, 1), (2, 2), (4, 3)])
+def test_conv_backward_against_torch_autograd_and_transposed_convolution(oracle, xb, wb):
+    """Alg. 1's backward lines through a 3x3 convolution.  Summed over the other operand's elements they are
+    2^(m-1) * d/dx and 2^(k-1) * d/dW of sum(g_a * s * conv(x, W)) on the decoded codes: torch's float64
+    autograd through its own conv2d gives both (a library routine, independent of the oracle's loops), and
+    the first is also the transposed convolution of s * g_a with the weights (conv_transpose2d)."""
+    import torch
+    import torch.nn.functional as F
+    r = rng(970 + xb * 8 + wb)
+    Nb, H, W, C, O = 2, 5, 4, 6, 7
+    X, Wt = rand_codes(r, (Nb, H, W, C), xb), rand_codes(r, (O, 3, 3, C), wb)
+    g = r.normal(size=(Nb, H, W, O)).astype(np.float32)
+    s = r.uniform(0.5, 2.0, O).astype(np.float32)
+    x = torch.tensor(X.astype(np.float64)).permute(0, 3, 1, 2).requires_grad_(True)          # NCHW
+    wt = torch.tensor(Wt.astype(np.float64)).permute(0, 3, 1, 2).requires_grad_(True)        # [O][C][3][3]
+    gs = torch.tensor(g.astype(np.float64) * s.astype(np.float64)).permute(0, 3, 1, 2)
+    (F.conv2d(x, wt, padding=1) * gs).sum().backward()
+    dx = x.grad.permute(0, 2, 3, 1).numpy()
+    dw = wt.grad.permute(0, 2, 3, 1).numpy()
+    gi = oracle.conv3x3_backward_input(g, s, Wt, xb, wb)
+    gw = oracle.conv3x3_backward_weight(g, s, X, xb, wb)
+    assert gi.shape == (xb, Nb, H, W, C) and gw.shape == (wb, O, 3, 3, C)
+    for m in range(xb):
+        assert np.abs(gi[m] - 2.0 ** m * dx).max() <= 1e-9 * (1 + 2.0 ** m * np.abs(dx).max())
+    for k in range(wb):
+        assert np.abs(gw[k] - 2.0 ** k * dw).max() <= 1e-9 * (1 + 2.0 ** k * np.abs(dw).max())
+    tr = F.conv_transpose2d(gs, wt.detach(), padding=1).permute(0, 2, 3, 1).numpy()
+    assert np.abs(gi[0] - tr).max() <= 1e-9 * (1 + np.abs(tr).max())
+    # without a scale the scale is one; a single pixel in the corner touches four taps only
+    g1 = np.zeros((1, 3, 3, 2), np.float32)
+    g1[0, 0, 0, 1] = 1.0
+    W1 = rand_codes(r, (2, 3, 3, 1), 1)
+    one = oracle.conv3x3_backward_input(g1, None, W1, 1, 1)[0, 0, :, :, 0]
+    want = np.zeros((3, 3))
+    want[0:2, 0:2] = W1[1, 1:3, 1:3, 0]                  # input (h, w) feeds output (0, 0) through tap (h + 1, w + 1)
+    assert (one == want).all()
+
+
 def test_update_sgd_is_one_multiply_and_one_subtraction(oracle):
     """Update() of Alg. 1 / Alg. 2 as plain gradient descent: w - eta * g with both steps rounded to binary32
     (numpy float32 arithmetic does exactly that), not a fused multiply-add."""
