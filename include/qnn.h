@@ -284,6 +284,28 @@ qnn_status qnn_branch_gemm_backward_input(const float *g_out, const float *scale
                                           int64_t M, int64_t N, int64_t K, int ab, float *g_bits, void *stream);
 qnn_status qnn_branch_gemm_backward_weight(const float *g_out, const float *scale, const uint32_t *A, int ab,
                                            int64_t M, int64_t N, int64_t K, int wb, float *g_wb, void *stream);
+/*
+ * The same backward lines through the 3x3 / stride 1 / zero padding 1 convolution of qnn_conv2d_packed
+ * (NHWC).  g_out = dC/da fp32 [Nb][H][W][Cout], g_ahat = scale[o] * g_out (scale NULL = ones);
+ *   qnn_conv2d_backward_input    g_bits[m-1][n][h][w][c] = sum_k 2^(m+k-2) sum_{kh,kw,o}
+ *       g_ahat[n][h-(kh-1)][w-(kw-1)][o] W^{kb}[o][kh][kw][c]      fp32 [ab][Nb][H][W][C]
+ *       Wt = the packed weights of the forward call, uint32 [Cout][9][wb][ceil(C/32)].
+ *   qnn_conv2d_backward_weight   g_wb[k-1][o][kh][kw][c] = sum_m 2^(m+k-2) sum_{n,h,w}
+ *       g_ahat[n][h][w][o] x^{mb}[n][h+kh-1][w+kw-1][c]            fp32 [wb][Cout][3][3][C]
+ *       x_planes = the packed activations of the forward call, uint32 [Nb*H*W][ab][ceil(C/32)];
+ *       the pixels are summed in several ranges whose partial results pass through `workspace`
+ *       (device memory, 16-byte aligned, at least qnn_conv2d_backward_weight_workspace_bytes(...) bytes)
+ *       and are added in a fixed order: the result does not depend on the launch.
+ * Positions outside the image contribute nothing.  Accuracy, alignment, empty sizes and status
+ * codes as for the fully connected pair; QNN_EWORKSPACE for a workspace that is too small.
+ * Limits: Nb*H*W < 2^30, C, Cout < 2^20.
+ */
+qnn_status qnn_conv2d_backward_input(const float *g_out, const float *scale, const uint32_t *Wt, int wb, int64_t Nb,
+                                     int64_t H, int64_t W, int64_t C, int64_t Cout, int ab, float *g_bits, void *stream);
+size_t qnn_conv2d_backward_weight_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout);
+qnn_status qnn_conv2d_backward_weight(const float *g_out, const float *scale, const uint32_t *x_planes, int ab, int64_t Nb,
+                                      int64_t H, int64_t W, int64_t C, int64_t Cout, int wb, float *g_wb, void *workspace,
+                                      size_t workspace_bytes, void *stream);
 qnn_status qnn_update_sgd(float *w, const float *g, int64_t n, float lr, void *stream);
 /*
  * qnn_update_adam   the same Update() with Adam (the text's other choice; Kingma & Ba's rule), in place:

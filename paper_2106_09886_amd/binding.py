@@ -27,6 +27,7 @@ EXPORTS = (
     "qnn_conv2d_im2col_requant_workspace_bytes", "qnn_conv2d_im2col_requant", "qnn_maxpool2x2_planes",
     "qnn_encode_real", "qnn_encoder_backward", "qnn_binarize", "qnn_binarize_backward", "qnn_quantize_k",
     "qnn_quantize_k_backward", "qnn_branch_gemm_backward_input", "qnn_branch_gemm_backward_weight", "qnn_update_sgd", "qnn_update_adam",
+    "qnn_conv2d_backward_input", "qnn_conv2d_backward_weight_workspace_bytes", "qnn_conv2d_backward_weight",
     "qnn_compare_mfma_arranged_bytes", "qnn_compare_mfma_arrange", "qnn_compare_mfma_gemm",
     "qnn_compare_dot4_gemm",
     "qnn_conv2d_general_output_size", "qnn_conv2d_general_workspace_bytes", "qnn_conv2d_general",
@@ -138,6 +139,12 @@ def lib():
     L.qnn_branch_gemm_backward_weight.restype = i32
     L.qnn_update_sgd.argtypes = [vp, vp, i64, ctypes.c_float, vp]
     L.qnn_update_sgd.restype = i32
+    L.qnn_conv2d_backward_input.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i64, i32, vp, vp]
+    L.qnn_conv2d_backward_input.restype = i32
+    L.qnn_conv2d_backward_weight_workspace_bytes.argtypes = [i64, i64, i64, i64, i64]
+    L.qnn_conv2d_backward_weight_workspace_bytes.restype = sz
+    L.qnn_conv2d_backward_weight.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i64, i32, vp, vp, sz, vp]
+    L.qnn_conv2d_backward_weight.restype = i32
     f32 = ctypes.c_float
     L.qnn_update_adam.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, i32, vp]
     L.qnn_update_adam.restype = i32
@@ -531,6 +538,36 @@ def update_sgd(w, g, lr):
     _dev(g, torch.float32, "g")
     _check(lib().qnn_update_sgd(_ptr(w), _ptr(g), w.numel(), ctypes.c_float(lr), _stream()), "qnn_update_sgd")
     return w
+
+
+def conv2d_backward_input(g_out, Wt, wb, C, ab, scale=None):
+    """Alg. 1 backward through the 3x3 convolution, towards the activations: g_out fp32 [Nb][H][W][Cout],
+    Wt planes [Cout][9][wb][Cw] -> fp32 [ab][Nb][H][W][C]."""
+    _dev(g_out, torch.float32, "g_out")
+    _dev(Wt, torch.int32, "Wt")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    Nb, H, W, Cout = g_out.shape
+    out = torch.empty((ab, Nb, H, W, C), dtype=torch.float32, device=g_out.device)
+    _check(lib().qnn_conv2d_backward_input(_ptr(g_out), _ptr(scale), _ptr(Wt), wb, Nb, H, W, C, Cout, ab, _ptr(out), _stream()),
+           "qnn_conv2d_backward_input")
+    return out
+
+
+def conv2d_backward_weight(g_out, x_planes, ab, C, wb, scale=None, workspace=None):
+    """... towards the binary weights: x_planes [Nb*H*W][ab][Cw] -> fp32 [wb][Cout][3][3][C]."""
+    _dev(g_out, torch.float32, "g_out")
+    _dev(x_planes, torch.int32, "x_planes")
+    if scale is not None:
+        _dev(scale, torch.float32, "scale")
+    Nb, H, W, Cout = g_out.shape
+    out = torch.empty((wb, Cout, 3, 3, C), dtype=torch.float32, device=g_out.device)
+    need = int(lib().qnn_conv2d_backward_weight_workspace_bytes(Nb, H, W, C, Cout))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=g_out.device)
+    _check(lib().qnn_conv2d_backward_weight(_ptr(g_out), _ptr(scale), _ptr(x_planes), ab, Nb, H, W, C, Cout, wb, _ptr(out),
+                                            _ptr(workspace), workspace.numel(), _stream()), "qnn_conv2d_backward_weight")
+    return out
 
 
 def update_adam(w, g, m, v, lr, beta1, beta2, eps, step):

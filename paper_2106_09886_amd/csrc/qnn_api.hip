@@ -691,6 +691,45 @@ qnn_status qnn_branch_gemm_backward_weight(const float *g_out, const float *scal
                                          g_wb, (hipStream_t)stream));
 }
 
+namespace {
+qnn_status check_conv_backward(int ab, int wb, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout) {
+    if (!bits_ok(ab) || !bits_ok(wb) || Nb < 0 || H < 0 || W < 0 || C < 0 || Cout < 0) return QNN_EINVAL;
+    if (H > kInt31 || W > kInt31 || Nb > kInt31 || C >= ((int64_t)1 << 20) || Cout >= ((int64_t)1 << 20)) return QNN_EUNSUPPORTED;
+    if (H > 0 && W > 0 && Nb > ((((int64_t)1 << 30) - 1) / H) / W) return QNN_EUNSUPPORTED;
+    return QNN_OK;
+}
+}  // namespace
+
+qnn_status qnn_conv2d_backward_input(const float *g_out, const float *scale, const uint32_t *Wt, int wb, int64_t Nb,
+                                     int64_t H, int64_t W, int64_t C, int64_t Cout, int ab, float *g_bits, void *stream) {
+    const qnn_status st = check_conv_backward(ab, wb, Nb, H, W, C, Cout);
+    if (st != QNN_OK) return st;
+    if (Nb * H * W == 0 || C == 0) return QNN_OK;
+    if (g_bits == nullptr || (Cout > 0 && (g_out == nullptr || Wt == nullptr))) return QNN_EINVAL;
+    if (!aligned4(g_out) || !aligned4(scale) || !aligned4(g_bits) || !aligned16(Wt)) return QNN_EALIGN;
+    return from_hip(launch_conv_backward_input(g_out, scale, Wt, wb, Nb, (int)H, (int)W, (int)C, (int)Cout, ab, g_bits,
+                                               (hipStream_t)stream));
+}
+
+size_t qnn_conv2d_backward_weight_workspace_bytes(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Cout) {
+    if (check_conv_backward(1, 1, Nb, H, W, C, Cout) != QNN_OK || C == 0 || Cout == 0) return 0;
+    return (size_t)conv_backward_splits(Nb * H * W, Cout, C) * (size_t)Cout * 9u * (size_t)C * 4u;
+}
+
+qnn_status qnn_conv2d_backward_weight(const float *g_out, const float *scale, const uint32_t *x_planes, int ab, int64_t Nb,
+                                      int64_t H, int64_t W, int64_t C, int64_t Cout, int wb, float *g_wb, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    const qnn_status st = check_conv_backward(ab, wb, Nb, H, W, C, Cout);
+    if (st != QNN_OK) return st;
+    if (Cout == 0 || C == 0) return QNN_OK;
+    const int64_t pixels = Nb * H * W;
+    if (g_wb == nullptr || workspace == nullptr || (pixels > 0 && (g_out == nullptr || x_planes == nullptr))) return QNN_EINVAL;
+    if (!aligned4(g_out) || !aligned4(scale) || !aligned4(g_wb) || !aligned16(x_planes) || !aligned16(workspace)) return QNN_EALIGN;
+    if (workspace_bytes < qnn_conv2d_backward_weight_workspace_bytes(Nb, H, W, C, Cout)) return QNN_EWORKSPACE;
+    return from_hip(launch_conv_backward_weight(g_out, scale, x_planes, ab, Nb, (int)H, (int)W, (int)C, (int)Cout, wb, g_wb,
+                                                static_cast<float *>(workspace), (hipStream_t)stream));
+}
+
 qnn_status qnn_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float lr, float beta1, float beta2,
                            float eps, int step, void *stream) {
     if (n < 0 || step < 1 || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps >= 0.0f))

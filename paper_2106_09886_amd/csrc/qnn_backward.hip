@@ -611,6 +611,262 @@ __global__ __launch_bounds__(256) void update_sgd_kernel(float *__restrict__ w, 
         w[i] = __fsub_rn(w[i], __fmul_rn(lr, g[i]));
 }
 
+// ---------------------------------------------------------------------------------------
+// The same backward lines through a 3x3 / stride 1 / zero padding 1 convolution (NHWC).
+//   towards the activations:  g_x[p][pixel q][c] = 2^p sum_{o, tap} s[o] g[q - off(tap)][o] w[o][tap][c]
+//     rows = pixels, sum index j = 9 o + tap (the row of the packed weights [O][9][wb][Cw]), the real
+//     operand gathered from the gradient image: G(q, j) = s[o] g[q - off(tap)][o] where that
+//     output position exists, else 0;
+//   towards the weights:      g_w[p][o][tap][c] = 2^p s[o] sum_{pixel q} g[q][o] x[q + off(tap)][c]
+//     rows = filters, columns = channels, one pass per tap, sum index = pixel; the codes are the
+//     activation planes of the neighbouring pixel, G is zero where that neighbour does not exist.
+//     The output is small and the sum long, so the pixels are cut into `splits` ranges, every
+//     range writes its partial result to a workspace [splits][O][9][C], and a second kernel adds
+//     the ranges in a fixed order and writes the 2^p copies (deterministic, no atomics).
+// Both on the LDS-staged tile scheme of backward_gemm_lds_kernel (128 x 128 per block, tiles of
+// 32 sum indices, two buffers, one barrier per tile, plane words through ds_bpermute).
+// ---------------------------------------------------------------------------------------
+struct ConvBackArgs {
+    const float *g;          // [pixels][O]
+    const float *scale;      // [O] or nullptr
+    const uint32_t *planes;  // weights [O][9][CB][Cw] (towards the activations) / activations [pixels][CB][Cw]
+    float *out;              // towards the activations: [P][pixels][C]; towards the weights: workspace [splits][O][9][C]
+    int pixels, H, W, O, C, Cw, P;
+    int row_blocks, col_blocks, splits, per_split;     // per_split: pixels per range, a multiple of 32
+    FastDiv div_w, div_h;
+};
+
+template <int CB, bool TW, bool VEC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void backward_conv_kernel(const ConvBackArgs a) {
+    constexpr int KT = 32, LD = 132;
+    __shared__ __attribute__((aligned(16))) float tile[2][KT][LD];
+    const int tid = (int)threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int half = lane >> 5, l5 = lane & 31;
+    // block -> (range of pixels, tap, row block, column block); the first two only towards the weights
+    uint32_t bid = blockIdx.x;
+    const int cb = (int)(bid % (uint32_t)a.col_blocks);
+    bid /= (uint32_t)a.col_blocks;
+    const int rb = (int)(bid % (uint32_t)a.row_blocks);
+    bid /= (uint32_t)a.row_blocks;
+    const int tap = TW ? (int)(bid % 9u) : 0, split = TW ? (int)(bid / 9u) : 0;
+    const int R = TW ? a.O : a.pixels;
+    const int jbeg = TW ? min(a.pixels, split * a.per_split) : 0;
+    const int jend = TW ? min(a.pixels, jbeg + a.per_split) : 9 * a.O;
+    const int r0 = rb * 128;
+    const int cw = cb * 4 + wave;
+    const bool active = cw < a.Cw;
+    const int cwc = active ? cw : a.Cw - 1;
+    const bool has_scale = a.scale != nullptr;
+    const int tdh = tap / 3 - 1, tdw = tap % 3 - 1;    // towards the weights: this pass's tap
+    constexpr int kOffset = (1 << CB) - 1;
+    f32x16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+    struct Regs {
+        f32x4 v[4];
+        f32x4 sc;
+        uint32_t ok;                                    // which of the values take part (their image position exists)
+        uint32_t pw[CB];
+    };
+    // towards the activations: the four pixels of this thread's pieces (row r0 + tid / 8 + 32 i)
+    int pq[4], ph[4], pwd[4];
+    f32x4 srow = {1.0f, 1.0f, 1.0f, 1.0f};
+    if constexpr (!TW) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pq[i] = min(r0 + (tid >> 3) + 32 * i, a.pixels - 1);
+            int line, n;
+            fast_divmod((uint32_t)pq[i], a.div_w, line, pwd[i]);
+            fast_divmod((uint32_t)line, a.div_h, n, ph[i]);
+        }
+    } else {
+        if (has_scale) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) srow[e] = a.scale[min(r0 + 4 * (tid & 31) + e, a.O - 1)];
+        }
+    }
+    const int jlast = max(jend - 1, 0);
+    auto load = [&](int j0, Regs &rg) {
+        rg.ok = 0u;
+        if constexpr (!TW) {
+            {
+                const int jc = min(j0 + l5, jlast);
+#pragma unroll
+                for (int q = 0; q < CB; ++q) rg.pw[q] = a.planes[((int64_t)jc * CB + q) * a.Cw + cwc];
+            }
+            const int jp = j0 + 4 * (tid & 7);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = min(jp + e, jlast);
+                const int o = j / 9, t = j - 9 * o;
+                const int dh = t / 3 - 1, dw = t - 3 * (t / 3) - 1;
+                rg.sc[e] = has_scale ? a.scale[o] : 1.0f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool ok = (unsigned)(ph[i] - dh) < (unsigned)a.H && (unsigned)(pwd[i] - dw) < (unsigned)a.W;
+                    const int src = ok ? pq[i] - dh * a.W - dw : pq[i];
+                    rg.v[i][e] = a.g[(int64_t)src * a.O + o];
+                    rg.ok |= (ok ? 1u : 0u) << (4 * i + e);
+                }
+            }
+        } else {
+            {
+                // the neighbour of pixel j0 + lane under this tap (any valid pixel if it does not exist)
+                const int pj = min(j0 + l5, jlast) + tdh * a.W + tdw;
+                const int pc = min(max(pj, 0), a.pixels - 1);
+#pragma unroll
+                for (int q = 0; q < CB; ++q) rg.pw[q] = a.planes[((int64_t)pc * CB + q) * a.Cw + cwc];
+            }
+            const int rp = r0 + 4 * (tid & 31);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = min(j0 + (tid >> 5) + 8 * i, jlast);
+                int line, n, h, w;
+                fast_divmod((uint32_t)j, a.div_w, line, w);
+                fast_divmod((uint32_t)line, a.div_h, n, h);
+                const bool ok = (unsigned)(h + tdh) < (unsigned)a.H && (unsigned)(w + tdw) < (unsigned)a.W;
+                rg.ok |= (ok ? 1u : 0u) << i;
+                if constexpr (VEC) {
+                    rg.v[i] = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)j * a.O + min(rp, a.O - 4));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rg.v[i][e] = a.g[(int64_t)j * a.O + min(rp + e, a.O - 1)];
+                }
+            }
+        }
+    };
+    auto stage = [&](int j0, const Regs &rg, int buf) {
+        if constexpr (!TW) {
+            const int jl = 4 * (tid & 7);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int rl = (tid >> 3) + 32 * i;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool use = (j0 + jl + e < jend) && ((rg.ok >> (4 * i + e)) & 1u);
+                    tile[buf][jl + e][rl] = use ? rg.v[i][e] * rg.sc[e] : 0.0f;
+                }
+            }
+        } else {
+            const int rl = 4 * (tid & 31);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int jl = (tid >> 5) + 8 * i;
+                const bool use = (j0 + jl < jend) && ((rg.ok >> i) & 1u);
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = use ? rg.v[i][e] * srow[e] : 0.0f;
+                *reinterpret_cast<f32x4 *>(&tile[buf][jl][rl]) = o;
+            }
+        }
+    };
+    auto compute = [&](const uint32_t (&pw)[CB], int buf) {
+        auto code = [&](int s) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int q = 0; q < CB; ++q) {
+                const uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute((2 * s + half) << 2, (int)pw[q]);
+                bits |= ((w >> l5) & 1u) << q;
+            }
+            return (float)(2 * (int)bits - kOffset);
+        };
+        float an[4], bn = code(0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) an[t] = tile[buf][half][t * 32 + l5];
+#pragma unroll
+        for (int s = 0; s < KT / 2; ++s) {
+            float ac[4];
+            const float bc = bn;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ac[t] = an[t];
+            if (s + 1 < KT / 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) an[t] = tile[buf][2 * (s + 1) + half][t * 32 + l5];
+                bn = code(s + 1);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bc, acc[t], 0, 0, 0);
+        }
+    };
+    if (jbeg < jend) {                                  // uniform over the block
+        Regs rg;
+        uint32_t pw_cur[CB];
+        load(jbeg, rg);
+        stage(jbeg, rg, 0);
+#pragma unroll
+        for (int q = 0; q < CB; ++q) pw_cur[q] = rg.pw[q];
+        __syncthreads();
+        int buf = 0;
+        for (int j0 = jbeg; j0 < jend; j0 += KT) {
+            const bool more = j0 + KT < jend;
+            if (more) load(j0 + KT, rg);
+            if (active) compute(pw_cur, buf);
+            if (more) {
+                stage(j0 + KT, rg, buf ^ 1);
+#pragma unroll
+                for (int q = 0; q < CB; ++q) pw_cur[q] = rg.pw[q];
+            }
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    if (!active) return;
+    const int col = cw * 32 + l5;
+    if (col >= a.C) return;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+            if (row < R) {
+                float val = acc[t][v];
+                if constexpr (TW) {
+                    a.out[(((int64_t)split * a.O + row) * 9 + tap) * a.C + col] = val;
+                } else {
+                    for (int p = 0; p < a.P; ++p) {
+                        a.out[((int64_t)p * a.pixels + row) * a.C + col] = val;
+                        val *= 2.0f;                      // exact
+                    }
+                }
+            }
+        }
+}
+
+// out[p][i] = 2^p * (ws[0][i] + ws[1][i] + ...), the ranges added in their order
+__global__ __launch_bounds__(256) void backward_conv_reduce_kernel(const float *__restrict__ ws, int splits, int64_t n, int P,
+                                                                    float *__restrict__ out) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        float val = ws[i];
+        for (int s = 1; s < splits; ++s) val += ws[(int64_t)s * n + i];
+        for (int p = 0; p < P; ++p) {
+            out[(int64_t)p * n + i] = val;
+            val *= 2.0f;
+        }
+    }
+}
+
+template <bool TW>
+hipError_t launch_conv_back(int cb, const ConvBackArgs &a, bool vec, dim3 grid, hipStream_t s) {
+#define QNN_CB(N)                                                                                          \
+    case N:                                                                                                \
+        if constexpr (TW) {                                                                                \
+            if (vec) launch_kernel((backward_conv_kernel<N, true, true>), grid, dim3(256), 0, s, a);       \
+            else launch_kernel((backward_conv_kernel<N, true, false>), grid, dim3(256), 0, s, a);          \
+        } else {                                                                                           \
+            launch_kernel((backward_conv_kernel<N, false, false>), grid, dim3(256), 0, s, a);              \
+        }                                                                                                  \
+        break;
+    switch (cb) {
+        QNN_CB(1) QNN_CB(2) QNN_CB(3) QNN_CB(4) QNN_CB(5) QNN_CB(6) QNN_CB(7) QNN_CB(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef QNN_CB
+    return launch_status();
+}
+
 // Adam: every step one correctly rounded binary32 operation, in this order (the CPU reference does the same)
 __global__ __launch_bounds__(256) void update_adam_kernel(float *__restrict__ w, const float *__restrict__ g, float *__restrict__ m,
                                                            float *__restrict__ v, int64_t n, float lr, float b1, float b2,
@@ -644,6 +900,50 @@ hipError_t launch_backward_gemm(const float *g, int64_t ldg, const float *scale,
     const bool vec = !towards_weights && J % 8 == 0 && ldg % 4 == 0 && ((((uintptr_t)g) & 15u) == 0) &&
                      (scale == nullptr || (((uintptr_t)scale) & 15u) == 0);
     return towards_weights ? launch_form<true>(code_bits, a, vec, s) : launch_form<false>(code_bits, a, vec, s);
+}
+
+// pixel ranges of the weight gradient: enough blocks for two per compute unit of a 256-unit chip, at
+// least 512 pixels per range, at most 64 ranges (a function of the sizes only: the workspace depends on it)
+int conv_backward_splits(int64_t pixels, int64_t O, int64_t C) {
+    const int64_t tiles = ((O + 127) / 128) * ((((C + 31) / 32) + 3) / 4) * 9;
+    int64_t s = (512 + tiles - 1) / tiles;
+    const int64_t most = pixels / 512 > 1 ? pixels / 512 : 1;
+    if (s > most) s = most;
+    if (s > 64) s = 64;
+    return (int)(s < 1 ? 1 : s);
+}
+
+hipError_t launch_conv_backward_input(const float *g, const float *scale, const uint32_t *Wt, int wb, int64_t Nb, int H, int W,
+                                      int C, int O, int P, float *out, hipStream_t s) {
+    ConvBackArgs a;
+    a.g = g; a.scale = scale; a.planes = Wt; a.out = out;
+    a.pixels = (int)(Nb * H * W); a.H = H; a.W = W; a.O = O; a.C = C; a.Cw = (C + 31) / 32; a.P = P;
+    a.row_blocks = (a.pixels + 127) / 128; a.col_blocks = (a.Cw + 3) / 4; a.splits = 1; a.per_split = 0;
+    a.div_w = fast_div_for(W); a.div_h = fast_div_for(H);
+    const int64_t nb = (int64_t)a.row_blocks * a.col_blocks;
+    if (nb > 0x7fffffff) return hipErrorInvalidValue;
+    return launch_conv_back<false>(wb, a, false, dim3((unsigned)nb), s);
+}
+
+hipError_t launch_conv_backward_weight(const float *g, const float *scale, const uint32_t *x_planes, int ab, int64_t Nb, int H,
+                                       int W, int C, int O, int P, float *out, float *workspace, hipStream_t s) {
+    ConvBackArgs a;
+    a.g = g; a.scale = scale; a.planes = x_planes; a.out = workspace;
+    a.pixels = (int)(Nb * H * W); a.H = H; a.W = W; a.O = O; a.C = C; a.Cw = (C + 31) / 32; a.P = P;
+    a.row_blocks = (O + 127) / 128; a.col_blocks = (a.Cw + 3) / 4;
+    a.splits = conv_backward_splits(a.pixels, O, C);
+    a.per_split = (int)(((((int64_t)a.pixels + a.splits - 1) / a.splits) + 31) / 32 * 32);
+    a.div_w = fast_div_for(W); a.div_h = fast_div_for(H);
+    const int64_t nb = (int64_t)a.row_blocks * a.col_blocks * 9 * a.splits;
+    if (nb > 0x7fffffff) return hipErrorInvalidValue;
+    const bool vec = O % 4 == 0 && O >= 4 && ((((uintptr_t)g) & 15u) == 0);
+    hipError_t e = launch_conv_back<true>(ab, a, vec, dim3((unsigned)nb), s);
+    if (e != hipSuccess) return e;
+    const int64_t n = (int64_t)O * 9 * C;
+    const int64_t want = (n + 255) / 256, cap = (int64_t)device_simd_count() * 16;
+    launch_kernel(backward_conv_reduce_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, s,
+                  (const float *)workspace, a.splits, n, P, out);
+    return launch_status();
 }
 
 hipError_t launch_update_sgd(float *w, const float *g, int64_t n, float lr, hipStream_t s) {

@@ -331,6 +331,13 @@ hipError_t launch_quantize_k_backward(const float *x, const float *g_q, int64_t 
 // backward lines of Alg. 1 through the product: out[p][r][c] = 2^p sum_j G(r, j) code[j][c] (qnn_backward.hip)
 hipError_t launch_backward_gemm(const float *g, int64_t ldg, const float *scale, const uint32_t *planes, int code_bits,
                                 int R, int J, int C, int P, bool towards_weights, float *out, hipStream_t);
+// the same through a 3x3 / stride 1 / pad 1 convolution; the weight gradient goes through a workspace of
+// conv_backward_splits() partial results
+int conv_backward_splits(int64_t pixels, int64_t O, int64_t C);
+hipError_t launch_conv_backward_input(const float *g, const float *scale, const uint32_t *Wt, int wb, int64_t Nb, int H, int W,
+                                      int C, int O, int P, float *out, hipStream_t);
+hipError_t launch_conv_backward_weight(const float *g, const float *scale, const uint32_t *x_planes, int ab, int64_t Nb, int H,
+                                       int W, int C, int O, int P, float *out, float *workspace, hipStream_t);
 hipError_t launch_update_sgd(float *w, const float *g, int64_t n, float lr, hipStream_t);
 hipError_t launch_update_adam(float *w, const float *g, float *m, float *v, int64_t n, float lr, float b1, float b2,
                               float omb1, float omb2, float bc1, float bc2, float eps, hipStream_t);

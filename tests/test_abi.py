@@ -315,7 +315,7 @@ def test_training_side_argument_errors(L):
 
 
 def test_backward_product_argument_errors(L):
-    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED
+    from paper_2106_09886_amd.binding import QNN_EINVAL, QNN_EALIGN, QNN_OK, QNN_EUNSUPPORTED, QNN_EWORKSPACE
     for f in (L.qnn_branch_gemm_backward_input, L.qnn_branch_gemm_backward_weight):
         assert f(P, None, P, 0, 4, 4, 32, 2, P, None) == QNN_EINVAL and f(P, None, P, 2, 4, 4, 32, 9, P, None) == QNN_EINVAL
         assert f(P, None, P, 2, -1, 4, 32, 2, P, None) == QNN_EINVAL
@@ -337,3 +337,17 @@ def test_backward_product_argument_errors(L):
     assert f(P, P, P, P, 4, 0.001, 1.0, 0.999, 1e-8, 1, None) == QNN_EINVAL and f(P, P, P, P, 4, 0.001, 0.9, -0.1, 1e-8, 1, None) == QNN_EINVAL
     assert f(P, P, P, P, 4, 0.001, 0.9, 0.999, -1.0, 1, None) == QNN_EINVAL
     assert f(P, P, P + 2, P, 4, *ok) == QNN_EALIGN and f(None, None, None, None, 0, *ok) == QNN_OK
+    f = L.qnn_conv2d_backward_input
+    assert f(P, None, P, 0, 1, 4, 4, 32, 8, 2, P, None) == QNN_EINVAL and f(P, None, P, 2, -1, 4, 4, 32, 8, 2, P, None) == QNN_EINVAL
+    assert f(None, None, P, 2, 1, 4, 4, 32, 8, 2, P, None) == QNN_EINVAL and f(P, None, P, 2, 1, 4, 4, 32, 8, 2, None, None) == QNN_EINVAL
+    assert f(P, None, P + 4, 2, 1, 4, 4, 32, 8, 2, P, None) == QNN_EALIGN and f(P + 2, None, P, 2, 1, 4, 4, 32, 8, 2, P, None) == QNN_EALIGN
+    assert f(P, None, P, 2, 1 << 20, 1 << 10, 1 << 10, 32, 8, 2, P, None) == QNN_EUNSUPPORTED
+    assert f(None, None, None, 2, 0, 4, 4, 32, 8, 2, None, None) == QNN_OK
+    need = L.qnn_conv2d_backward_weight_workspace_bytes(2, 8, 8, 64, 64)
+    assert need >= 64 * 9 * 64 * 4 and need % (64 * 9 * 64 * 4) == 0
+    assert L.qnn_conv2d_backward_weight_workspace_bytes(2, 8, 8, 0, 64) == 0
+    f = L.qnn_conv2d_backward_weight
+    assert f(P, None, P, 2, 2, 8, 8, 64, 64, 2, P, P, need - 1, None) == QNN_EWORKSPACE
+    assert f(P, None, P, 2, 2, 8, 8, 64, 64, 2, P, None, need, None) == QNN_EINVAL and f(P, None, P, 2, 2, 8, 8, 64, 64, 9, P, P, need, None) == QNN_EINVAL
+    assert f(P, None, P, 2, 2, 8, 8, 64, 64, 2, P, P + 4, need, None) == QNN_EALIGN
+    assert f(None, None, None, 2, 2, 8, 8, 64, 0, 2, None, None, 0, None) == QNN_OK

@@ -305,3 +305,108 @@ def test_update_adam(q, oracle, n):
         w, m, v = oracle.update_adam(w, g, m, v, 1e-3, 0.9, 0.999, 1e-8, t)
         q.update_adam(wd, dev(g), md, vd, 1e-3, 0.9, 0.999, 1e-8, t)
         assert (host(md) == m).all() and (host(vd) == v).all() and (host(wd) == w).all()
+
+
+# ------------------------------------------------------------------ Alg. 1, backward through the 3x3 convolution
+CONV_BACKWARD_CASES = [
+    # (Nb, H, W, C, Cout, ab, wb, with_scale): images smaller than the window, ragged channel and filter
+    # counts, several 128-pixel row blocks, filter counts that are and are not multiples of 4 (16-byte and
+    # scalar loads of the weight gradient), several pixel ranges (> 1024 pixels), one to eight bits
+    (1, 1, 1, 3, 2, 1, 1, False), (2, 5, 4, 6, 7, 2, 2, True), (1, 9, 11, 70, 33, 4, 3, True), (3, 8, 8, 64, 64, 2, 2, True),
+    (2, 14, 14, 130, 40, 3, 2, False), (1, 2, 7, 32, 128, 8, 8, True), (2, 32, 32, 32, 36, 2, 4, True),
+    (1, 40, 40, 40, 130, 4, 2, True),
+]
+
+
+@pytest.mark.parametrize("case", CONV_BACKWARD_CASES, ids=lambda c: "%dx%dx%dx%d-O%d-A%dW%d%s" % (c[:7] + ("-s" if c[7] else "",)))
+def test_conv2d_backward(q, oracle, case):
+    """Both gradients of the backward lines through the 3x3 convolution against the float64 oracle, element by
+    element within the binary32 accumulation bound (J = 9*Cout terms towards the activations, Nb*H*W towards
+    the weights); the copies per encoded element are exact multiples of the first."""
+    from gpu_util import rand_codes
+    Nb, H, W, C, Cout, ab, wb, with_scale = case
+    say("conv2d_backward", case)
+    rng = np.random.default_rng(sum(case[:7]) * 3 + 1)
+    X, Wt = rand_codes(rng, (Nb, H, W, C), ab), rand_codes(rng, (Cout, 3, 3, C), wb)
+    g = rng.normal(size=(Nb, H, W, Cout)).astype(np.float32)
+    s = rng.uniform(0.25, 4.0, Cout).astype(np.float32) if with_scale else None
+    sd = None if s is None else dev(s)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    gabs = np.abs(g.astype(np.float32)) * (1.0 if s is None else s[None, None, None, :])
+    ones_w = np.abs(Wt.astype(np.int64)).astype(np.int16)
+    ones_x = np.abs(X.astype(np.int64)).astype(np.int16)
+    # sum of |terms|: the same backward lines on absolute values (one encoded element of weight 1 suffices: use the
+    # closed form sum |g_ahat| |code| through the oracle's own routine on 8-bit "codes" is not possible for even
+    # values, so take numpy)
+    import torch
+    import torch.nn.functional as F
+    ga = torch.tensor(gabs.astype(np.float64)).permute(0, 3, 1, 2)
+    wa = torch.tensor(ones_w.astype(np.float64)).permute(0, 3, 1, 2)
+    xa = torch.tensor(ones_x.astype(np.float64)).permute(0, 3, 1, 2)
+    abs_i = F.conv_transpose2d(ga, wa, padding=1).permute(0, 2, 3, 1).numpy()
+    xa.requires_grad_(False)
+    wz = torch.zeros_like(wa, requires_grad=True)
+    (F.conv2d(xa, wz, padding=1) * ga).sum().backward()
+    abs_w = wz.grad.permute(0, 2, 3, 1).numpy()
+    want_i = oracle.conv3x3_backward_input(g, s, Wt, ab, wb)
+    got_i = host(q.conv2d_backward_input(dev(g), Wp, wb, C, ab, scale=sd)).astype(np.float64)
+    assert got_i.shape == want_i.shape
+    bound_i = (9 * Cout + 2) * 2.0 ** -24 * abs_i
+    for m in range(ab):
+        assert (np.abs(got_i[m] - want_i[m]) <= 2.0 ** m * bound_i + 1e-30).all()
+        assert (got_i[m] == 2.0 ** m * got_i[0]).all()
+    want_w = oracle.conv3x3_backward_weight(g, s, X, ab, wb)
+    got_w = host(q.conv2d_backward_weight(dev(g), Xp, ab, C, wb, scale=sd)).astype(np.float64)
+    assert got_w.shape == want_w.shape
+    bound_w = (Nb * H * W + 2) * 2.0 ** -24 * abs_w
+    for k in range(wb):
+        assert (np.abs(got_w[k] - want_w[k]) <= 2.0 ** k * bound_w + 1e-30).all()
+        assert (got_w[k] == 2.0 ** k * got_w[0]).all()
+    if Nb * H * W >= 64:
+        assert np.abs(want_i[0]).mean() > 50 * bound_i.mean() and np.abs(want_w[0]).mean() > 50 * bound_w.mean()
+
+
+def test_conv2d_backward_exact_on_small_integers(q, oracle):
+    """Integer gradients: every partial sum stays below 2^24, so any summation order is exact and both
+    gradients must equal the oracle bit for bit (this also pins the fixed-order addition of the pixel ranges)."""
+    from gpu_util import rand_codes
+    rng = np.random.default_rng(77)
+    Nb, H, W, C, Cout, ab, wb = 2, 24, 24, 40, 24, 2, 2
+    X, Wt = rand_codes(rng, (Nb, H, W, C), ab), rand_codes(rng, (Cout, 3, 3, C), wb)
+    g = rng.integers(-4, 5, size=(Nb, H, W, Cout)).astype(np.float32)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    assert (host(q.conv2d_backward_input(dev(g), Wp, wb, C, ab)).astype(np.float64) == oracle.conv3x3_backward_input(g, None, Wt, ab, wb)).all()
+    assert (host(q.conv2d_backward_weight(dev(g), Xp, ab, C, wb)).astype(np.float64) == oracle.conv3x3_backward_weight(g, None, X, ab, wb)).all()
+
+
+def test_conv2d_backward_at_the_resnet18_layer_size(q, oracle):
+    """The headline layer (32 x 56 x 56 x 64 -> 64, W2A2) in the launch shape the library picks; towards the
+    activations on the first image against the oracle (its pixels see only that image), towards the weights
+    through torch's float64 autograd on the decoded codes (the routine that pins the oracle)."""
+    import torch
+    import torch.nn.functional as F
+    from gpu_util import rand_codes
+    rng = np.random.default_rng(18)
+    Nb, H, W, C, Cout, ab, wb = 32, 56, 56, 64, 64, 2, 2
+    X, Wt = rand_codes(rng, (Nb, H, W, C), ab), rand_codes(rng, (Cout, 3, 3, C), wb)
+    g = rng.normal(size=(Nb, H, W, Cout)).astype(np.float32)
+    s = rng.uniform(0.5, 2.0, Cout).astype(np.float32)
+    Xp = q.encode_pack(dev(X.reshape(Nb * H * W, C)), ab)
+    Wp = q.encode_pack(dev(Wt.reshape(Cout * 9, C)), wb)
+    got_i = host(q.conv2d_backward_input(dev(g), Wp, wb, C, ab, scale=dev(s))).astype(np.float64)
+    want_i = oracle.conv3x3_backward_input(g[:1], s, Wt, ab, wb)
+    tol_i = (9 * Cout + 2) * 2.0 ** -24 * 9 * Cout * 3 * np.abs(g).max() * 2.0
+    for m in range(ab):
+        assert np.abs(got_i[m][:1] - want_i[m]).max() <= 2.0 ** m * tol_i
+    got_w = host(q.conv2d_backward_weight(dev(g), Xp, ab, C, wb, scale=dev(s))).astype(np.float64)
+    x = torch.tensor(X.astype(np.float64)).permute(0, 3, 1, 2)
+    wz = torch.zeros((Cout, C, 3, 3), dtype=torch.float64, requires_grad=True)
+    gs = torch.tensor(g.astype(np.float64) * s.astype(np.float64)).permute(0, 3, 1, 2)
+    (F.conv2d(x, wz, padding=1) * gs).sum().backward()
+    dw = wz.grad.permute(0, 2, 3, 1).numpy()
+    tol_w = (Nb * H * W + 2) * 2.0 ** -24 * 3 * np.abs(g).sum(axis=(0, 1, 2)).max() * 2.0
+    for k in range(wb):
+        assert np.abs(got_w[k] - 2.0 ** k * dw).max() <= 2.0 ** k * tol_w
+    assert np.abs(dw).mean() > 100 * tol_w / 1000           # the tolerance is small against the gradient's size
