@@ -319,6 +319,25 @@ def side_suites(name, args, steps, warmup, torch, np, q, dev):
                              "frac_of_f32_matrix_peak": round(flops / (t * 1e-6) / PEAK_F32_MFMA, 3),
                              "output_MB": round(out_bytes / 1e6, 1)})
             del Ap, Wp, g, sd
+        # the same lines through 3x3 convolutions: flops = 2 * pixels * 9 * Cout * C per gradient
+        for (label, Nb, H, W, C, Cout, ab, wb) in (("conv 32 x 56 x 56 x 64 -> 64, W2A2 (the headline layer)", 32, 56, 56, 64, 64, 2, 2),
+                                                  ("conv 64 x 14 x 14 x 256 -> 256, W3A4", 64, 14, 14, 256, 256, 4, 3),
+                                                  ("conv 16 x 112 x 112 x 128 -> 128, W2A4", 16, 112, 112, 128, 128, 4, 2)):
+            Cw = (C + 31) // 32
+            pixels = Nb * H * W
+            Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (pixels, ab, Cw), dtype=torch.int32, device=dev)
+            Wp = torch.randint(-2 ** 31, 2 ** 31 - 1, (Cout * 9, wb, Cw), dtype=torch.int32, device=dev)
+            g = torch.randn((Nb, H, W, Cout), device=dev)
+            sd = torch.rand(Cout, device=dev) + 0.5
+            ws = torch.empty(max(16, int(q.lib().qnn_conv2d_backward_weight_workspace_bytes(Nb, H, W, C, Cout))), dtype=torch.uint8, device=dev)
+            flops = 2.0 * pixels * 9 * Cout * C
+            for which, fn, out_bytes in (("towards the activations", lambda: q.conv2d_backward_input(g, Wp, wb, C, ab, scale=sd), ab * pixels * C * 4),
+                                         ("towards the weights", lambda: q.conv2d_backward_weight(g, Xp, ab, C, wb, scale=sd, workspace=ws), wb * Cout * 9 * C * 4)):
+                t = avg_us(fn)
+                rows.append({"layer": label, "gradient": which, "us": round(t, 1), "TFLOPs": round(flops / t / 1e6, 2),
+                             "frac_of_f32_matrix_peak": round(flops / (t * 1e-6) / PEAK_F32_MFMA, 3),
+                             "output_MB": round(out_bytes / 1e6, 1)})
+            del Xp, Wp, g, sd, ws
         head = rows[3]
         res = {"metric": "TFLOP/s of qnn_branch_gemm_backward_weight, 4096^3 W2A2", "value": head["TFLOPs"], "unit": "TFLOP/s",
                "roofline": {"bound": "mfma", "kernel": "backward_gemm_kernel", "achieved": head["TFLOPs"], "peak": 157.3,

@@ -614,8 +614,9 @@ __global__ __launch_bounds__(256) void update_sgd_kernel(float *__restrict__ w, 
 // ---------------------------------------------------------------------------------------
 // The same backward lines through a 3x3 / stride 1 / zero padding 1 convolution (NHWC).
 //   towards the activations:  g_x[p][pixel q][c] = 2^p sum_{o, tap} s[o] g[q - off(tap)][o] w[o][tap][c]
-//     rows = pixels, sum index j = 9 o + tap (the row of the packed weights [O][9][wb][Cw]), the real
-//     operand gathered from the gradient image: G(q, j) = s[o] g[q - off(tap)][o] where that
+//     rows = pixels, sum index j = tap * O + o (tap-major, so that consecutive indices are consecutive
+//     filters of one gradient pixel: 16-byte loads; the packed weights' row of j is 9 o + tap), the
+//     real operand gathered from the gradient image: G(q, j) = s[o] g[q - off(tap)][o] where that
 //     output position exists, else 0;
 //   towards the weights:      g_w[p][o][tap][c] = 2^p s[o] sum_{pixel q} g[q][o] x[q + off(tap)][c]
 //     rows = filters, columns = channels, one pass per tap, sum index = pixel; the codes are the
@@ -633,13 +634,16 @@ struct ConvBackArgs {
     float *out;              // towards the activations: [P][pixels][C]; towards the weights: workspace [splits][O][9][C]
     int pixels, H, W, O, C, Cw, P;
     int row_blocks, col_blocks, splits, per_split;     // per_split: pixels per range, a multiple of 32
-    FastDiv div_w, div_h;
+    FastDiv div_w, div_h, div_o;
+    int vec_in;              // towards the activations: 16-byte loads of the gradient and the scale are possible
 };
 
-template <int CB, bool TW, bool VEC>
+// WC: plane words (32 columns each) per block, 4, 2 or 1 for layers of at least 97, 33 or fewer channels: the
+// four wavefronts then form 4 / WC row groups of WC row tiles each, so that none of them idles on a narrow layer.
+template <int CB, bool TW, bool VEC, int WC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void backward_conv_kernel(const ConvBackArgs a) {
-    constexpr int KT = 32, LD = 132;
+    constexpr int KT = 32, LD = 132, NT = WC;
     __shared__ __attribute__((aligned(16))) float tile[2][KT][LD];
     const int tid = (int)threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int half = lane >> 5, l5 = lane & 31;
@@ -654,15 +658,16 @@ void backward_conv_kernel(const ConvBackArgs a) {
     const int jbeg = TW ? min(a.pixels, split * a.per_split) : 0;
     const int jend = TW ? min(a.pixels, jbeg + a.per_split) : 9 * a.O;
     const int r0 = rb * 128;
-    const int cw = cb * 4 + wave;
+    const int cw = cb * WC + wave % WC;
+    const int rw = (wave / WC) * (32 * NT);             // this wavefront's rows inside the block's 128
     const bool active = cw < a.Cw;
     const int cwc = active ? cw : a.Cw - 1;
     const bool has_scale = a.scale != nullptr;
     const int tdh = tap / 3 - 1, tdw = tap % 3 - 1;    // towards the weights: this pass's tap
     constexpr int kOffset = (1 << CB) - 1;
-    f32x16 acc[4];
+    f32x16 acc[NT];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
     struct Regs {
@@ -694,22 +699,41 @@ void backward_conv_kernel(const ConvBackArgs a) {
         if constexpr (!TW) {
             {
                 const int jc = min(j0 + l5, jlast);
+                int t, o;
+                fast_divmod((uint32_t)jc, a.div_o, t, o);
+                const int wrow = 9 * o + t;                      // the packed weights are [O][9]
 #pragma unroll
-                for (int q = 0; q < CB; ++q) rg.pw[q] = a.planes[((int64_t)jc * CB + q) * a.Cw + cwc];
+                for (int q = 0; q < CB; ++q) rg.pw[q] = a.planes[((int64_t)wrow * CB + q) * a.Cw + cwc];
             }
             const int jp = j0 + 4 * (tid & 7);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = min(jp + e, jlast);
-                const int o = j / 9, t = j - 9 * o;
+            if constexpr (VEC) {
+                // O is a multiple of 4: the four indices of a piece are four filters of one tap
+                int t, o;
+                fast_divmod((uint32_t)min(jp, jlast - 3), a.div_o, t, o);
                 const int dh = t / 3 - 1, dw = t - 3 * (t / 3) - 1;
-                rg.sc[e] = has_scale ? a.scale[o] : 1.0f;
+                const float *sp = has_scale ? a.scale + o : a.g;
+                rg.sc = *reinterpret_cast<const f32x4 *>(sp);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const bool ok = (unsigned)(ph[i] - dh) < (unsigned)a.H && (unsigned)(pwd[i] - dw) < (unsigned)a.W;
                     const int src = ok ? pq[i] - dh * a.W - dw : pq[i];
-                    rg.v[i][e] = a.g[(int64_t)src * a.O + o];
-                    rg.ok |= (ok ? 1u : 0u) << (4 * i + e);
+                    rg.v[i] = *reinterpret_cast<const f32x4 *>(a.g + (int64_t)src * a.O + o);
+                    rg.ok |= (ok ? 15u : 0u) << (4 * i);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int t, o;
+                    fast_divmod((uint32_t)min(jp + e, jlast), a.div_o, t, o);
+                    const int dh = t / 3 - 1, dw = t - 3 * (t / 3) - 1;
+                    rg.sc[e] = has_scale ? a.scale[o] : 1.0f;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const bool ok = (unsigned)(ph[i] - dh) < (unsigned)a.H && (unsigned)(pwd[i] - dw) < (unsigned)a.W;
+                        const int src = ok ? pq[i] - dh * a.W - dw : pq[i];
+                        rg.v[i][e] = a.g[(int64_t)src * a.O + o];
+                        rg.ok |= (ok ? 1u : 0u) << (4 * i + e);
+                    }
                 }
             }
         } else {
@@ -747,7 +771,7 @@ void backward_conv_kernel(const ConvBackArgs a) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const bool use = (j0 + jl + e < jend) && ((rg.ok >> (4 * i + e)) & 1u);
-                    tile[buf][jl + e][rl] = use ? rg.v[i][e] * rg.sc[e] : 0.0f;
+                    tile[buf][jl + e][rl] = use ? rg.v[i][e] * (has_scale ? rg.sc[e] : 1.0f) : 0.0f;
                 }
             }
         } else {
@@ -773,22 +797,22 @@ void backward_conv_kernel(const ConvBackArgs a) {
             }
             return (float)(2 * (int)bits - kOffset);
         };
-        float an[4], bn = code(0);
+        float an[NT], bn = code(0);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) an[t] = tile[buf][half][t * 32 + l5];
+        for (int t = 0; t < NT; ++t) an[t] = tile[buf][half][rw + t * 32 + l5];
 #pragma unroll
         for (int s = 0; s < KT / 2; ++s) {
-            float ac[4];
+            float ac[NT];
             const float bc = bn;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) ac[t] = an[t];
+            for (int t = 0; t < NT; ++t) ac[t] = an[t];
             if (s + 1 < KT / 2) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t) an[t] = tile[buf][2 * (s + 1) + half][t * 32 + l5];
+                for (int t = 0; t < NT; ++t) an[t] = tile[buf][2 * (s + 1) + half][rw + t * 32 + l5];
                 bn = code(s + 1);
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bc, acc[t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bc, acc[t], 0, 0, 0);
         }
     };
     if (jbeg < jend) {                                  // uniform over the block
@@ -817,10 +841,10 @@ void backward_conv_kernel(const ConvBackArgs a) {
     const int col = cw * 32 + l5;
     if (col >= a.C) return;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = r0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+            const int row = r0 + rw + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
             if (row < R) {
                 float val = acc[t][v];
                 if constexpr (TW) {
@@ -848,15 +872,16 @@ __global__ __launch_bounds__(256) void backward_conv_reduce_kernel(const float *
     }
 }
 
-template <bool TW>
-hipError_t launch_conv_back(int cb, const ConvBackArgs &a, bool vec, dim3 grid, hipStream_t s) {
+template <bool TW, int WC>
+hipError_t launch_conv_back_wc(int cb, const ConvBackArgs &a, bool vec, dim3 grid, hipStream_t s) {
 #define QNN_CB(N)                                                                                          \
     case N:                                                                                                \
         if constexpr (TW) {                                                                                \
-            if (vec) launch_kernel((backward_conv_kernel<N, true, true>), grid, dim3(256), 0, s, a);       \
-            else launch_kernel((backward_conv_kernel<N, true, false>), grid, dim3(256), 0, s, a);          \
+            if (vec) launch_kernel((backward_conv_kernel<N, true, true, WC>), grid, dim3(256), 0, s, a);   \
+            else launch_kernel((backward_conv_kernel<N, true, false, WC>), grid, dim3(256), 0, s, a);      \
         } else {                                                                                           \
-            launch_kernel((backward_conv_kernel<N, false, false>), grid, dim3(256), 0, s, a);              \
+            if (vec) launch_kernel((backward_conv_kernel<N, false, true, WC>), grid, dim3(256), 0, s, a);  \
+            else launch_kernel((backward_conv_kernel<N, false, false, WC>), grid, dim3(256), 0, s, a);     \
         }                                                                                                  \
         break;
     switch (cb) {
@@ -865,6 +890,18 @@ hipError_t launch_conv_back(int cb, const ConvBackArgs &a, bool vec, dim3 grid, 
     }
 #undef QNN_CB
     return launch_status();
+}
+
+// plane words per block: four from 97 channels on, two from 33, else one
+inline int conv_back_words(int Cw) { return Cw >= 3 ? 4 : Cw; }
+
+template <bool TW>
+hipError_t launch_conv_back(int cb, const ConvBackArgs &a, bool vec, dim3 grid, hipStream_t s) {
+    switch (conv_back_words(a.Cw)) {
+        case 4: return launch_conv_back_wc<TW, 4>(cb, a, vec, grid, s);
+        case 2: return launch_conv_back_wc<TW, 2>(cb, a, vec, grid, s);
+        default: return launch_conv_back_wc<TW, 1>(cb, a, vec, grid, s);
+    }
 }
 
 // Adam: every step one correctly rounded binary32 operation, in this order (the CPU reference does the same)
@@ -918,11 +955,14 @@ hipError_t launch_conv_backward_input(const float *g, const float *scale, const 
     ConvBackArgs a;
     a.g = g; a.scale = scale; a.planes = Wt; a.out = out;
     a.pixels = (int)(Nb * H * W); a.H = H; a.W = W; a.O = O; a.C = C; a.Cw = (C + 31) / 32; a.P = P;
-    a.row_blocks = (a.pixels + 127) / 128; a.col_blocks = (a.Cw + 3) / 4; a.splits = 1; a.per_split = 0;
-    a.div_w = fast_div_for(W); a.div_h = fast_div_for(H);
+    a.row_blocks = (a.pixels + 127) / 128; a.col_blocks = (a.Cw + conv_back_words(a.Cw) - 1) / conv_back_words(a.Cw);
+    a.splits = 1; a.per_split = 0;
+    a.div_w = fast_div_for(W); a.div_h = fast_div_for(H); a.div_o = fast_div_for(O);
+    const bool vec = O % 4 == 0 && O >= 4 && ((((uintptr_t)g) & 15u) == 0) && (scale == nullptr || (((uintptr_t)scale) & 15u) == 0);
+    a.vec_in = vec ? 1 : 0;
     const int64_t nb = (int64_t)a.row_blocks * a.col_blocks;
     if (nb > 0x7fffffff) return hipErrorInvalidValue;
-    return launch_conv_back<false>(wb, a, false, dim3((unsigned)nb), s);
+    return launch_conv_back<false>(wb, a, vec, dim3((unsigned)nb), s);
 }
 
 hipError_t launch_conv_backward_weight(const float *g, const float *scale, const uint32_t *x_planes, int ab, int64_t Nb, int H,
@@ -930,10 +970,10 @@ hipError_t launch_conv_backward_weight(const float *g, const float *scale, const
     ConvBackArgs a;
     a.g = g; a.scale = scale; a.planes = x_planes; a.out = workspace;
     a.pixels = (int)(Nb * H * W); a.H = H; a.W = W; a.O = O; a.C = C; a.Cw = (C + 31) / 32; a.P = P;
-    a.row_blocks = (O + 127) / 128; a.col_blocks = (a.Cw + 3) / 4;
+    a.row_blocks = (O + 127) / 128; a.col_blocks = (a.Cw + conv_back_words(a.Cw) - 1) / conv_back_words(a.Cw);
     a.splits = conv_backward_splits(a.pixels, O, C);
     a.per_split = (int)(((((int64_t)a.pixels + a.splits - 1) / a.splits) + 31) / 32 * 32);
-    a.div_w = fast_div_for(W); a.div_h = fast_div_for(H);
+    a.div_w = fast_div_for(W); a.div_h = fast_div_for(H); a.div_o = fast_div_for(O); a.vec_in = 0;
     const int64_t nb = (int64_t)a.row_blocks * a.col_blocks * 9 * a.splits;
     if (nb > 0x7fffffff) return hipErrorInvalidValue;
     const bool vec = O % 4 == 0 && O >= 4 && ((((uintptr_t)g) & 15u) == 0);
