@@ -640,10 +640,13 @@ struct ConvBackArgs {
 
 // WC: plane words (32 columns each) per block, 4, 2 or 1 for layers of at least 97, 33 or fewer channels: the
 // four wavefronts then form 4 / WC row groups of WC row tiles each, so that none of them idles on a narrow layer.
-template <int CB, bool TW, bool VEC, int WC>
+// HALF (towards the weights, at most 64 filters): only the first 64 rows of the tile exist, so every
+// wavefront takes half as many row tiles (WC / 2) and no matrix instruction works on empty rows.
+template <int CB, bool TW, bool VEC, int WC, bool HALF = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void backward_conv_kernel(const ConvBackArgs a) {
-    constexpr int KT = 32, LD = 132, NT = WC;
+    static_assert(!HALF || (TW && WC >= 2), "half tiles: weight gradient, at least two plane words per block");
+    constexpr int KT = 32, LD = 132, NT = HALF ? WC / 2 : WC;
     __shared__ __attribute__((aligned(16))) float tile[2][KT][LD];
     const int tid = (int)threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int half = lane >> 5, l5 = lane & 31;
@@ -877,6 +880,13 @@ hipError_t launch_conv_back_wc(int cb, const ConvBackArgs &a, bool vec, dim3 gri
 #define QNN_CB(N)                                                                                          \
     case N:                                                                                                \
         if constexpr (TW) {                                                                                \
+            if constexpr (WC >= 2) {                                                                       \
+                if (a.O <= 64) {                                                                           \
+                    if (vec) launch_kernel((backward_conv_kernel<N, true, true, WC, true>), grid, dim3(256), 0, s, a);   \
+                    else launch_kernel((backward_conv_kernel<N, true, false, WC, true>), grid, dim3(256), 0, s, a);      \
+                    break;                                                                                 \
+                }                                                                                          \
+            }                                                                                              \
             if (vec) launch_kernel((backward_conv_kernel<N, true, true, WC>), grid, dim3(256), 0, s, a);   \
             else launch_kernel((backward_conv_kernel<N, true, false, WC>), grid, dim3(256), 0, s, a);      \
         } else {                                                                                           \
